@@ -1,0 +1,179 @@
+"""ctypes front-end of the fp64 CPU oracle (``moa_ref.c``).
+
+TEST INFRASTRUCTURE ONLY.  Importable from ``tests/``, from the smoke check and
+from the benchmark's ``cpu_baseline`` leg -- never from the product package.
+Nothing here imports the GPU package; the two share no code.
+
+Every wrapper converts its numpy inputs to C-contiguous float64 / int32 / uint64
+(an exact conversion for fp32 and bf16-representable values) and returns fp64.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "moa_ref.c"
+_LIB = _HERE / "libmoa_ref.so"
+
+OK, BAD_ARG, BAD_TREE, EMPTY = 0, 1, 2, 3
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where}: oracle status {code}")
+        self.code = code
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (-O2, OpenMP).  Building the checker is not using it."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < max(
+            _SRC.stat().st_mtime, (_HERE / "moa_ref.h").stat().st_mtime):
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-Wall", "-Wextra", "-shared", "-fPIC",
+                               "-o", str(tmp), str(_SRC), "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(str(_LIB))
+    return _lib
+
+
+def _f64(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a, ct=C.c_double):
+    return None if a is None else a.ctypes.data_as(C.POINTER(ct))
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise OracleError(rc, where)
+
+
+def tree_build(parent):
+    parent = _i32(parent)
+    B, M = parent.shape
+    W = (M + 63) // 64
+    mask = np.zeros((B, M, W), dtype=np.uint64)
+    depth = np.zeros((B, M), dtype=np.int32)
+    rc = lib().moa_ref_tree_build(_p(parent, C.c_int32), B, M, _p(mask, C.c_uint64), _p(depth, C.c_int32))
+    _check(rc, "tree_build")
+    return mask, depth
+
+
+def linear(x, w):
+    x = _f64(x)
+    w = _f64(w)
+    R, K = x.shape
+    N = K if w is None else w.shape[0]
+    y = np.empty((R, N), dtype=np.float64)
+    _check(lib().moa_ref_linear(_p(x), C.c_int64(R), K, _p(w), N, _p(y)), "linear")
+    return y
+
+
+def lsa(hs, wq, wk, wv, wo, Hq, Hkv, dh):
+    hs = _f64(hs)
+    T, L, d_in = hs.shape
+    wq, wk, wv, wo = _f64(wq), _f64(wk), _f64(wv), _f64(wo)
+    d_out = Hq * dh if wo is None else wo.shape[0]
+    out = np.empty((T, d_out), dtype=np.float64)
+    rc = lib().moa_ref_lsa(_p(hs), C.c_int64(T), L, d_in, Hq, Hkv, dh, _p(wq), _p(wk), _p(wv), _p(wo),
+                           d_out, _p(out))
+    _check(rc, "lsa")
+    return out
+
+
+def ca_kv_append(mem_new, tok_off, wk, wv, kc, vc, ca_len, Hkv, dh):
+    """Appends in place into kc / vc (float64 [B,Hkv,P_cap,dh]) and ca_len (int32 [B])."""
+    mem_new = _f64(mem_new)
+    tok_off = _i32(tok_off)
+    wk, wv = _f64(wk), _f64(wv)
+    assert kc.dtype == np.float64 and vc.dtype == np.float64 and ca_len.dtype == np.int32
+    assert kc.flags.c_contiguous and vc.flags.c_contiguous and ca_len.flags.c_contiguous
+    B, hk, P_cap, dd = kc.shape
+    assert hk == Hkv and dd == dh and tok_off.shape == (B + 1,)
+    rc = lib().moa_ref_ca_kv_append(_p(mem_new), mem_new.shape[1], _p(tok_off, C.c_int32), B, Hkv, dh,
+                                    _p(wk), _p(wv), _p(kc), _p(vc), _p(ca_len, C.c_int32), P_cap)
+    _check(rc, "ca_kv_append")
+
+
+def cross_attn(xq, wq, wo, kc, vc, ca_len, H, Hkv, dh):
+    xq = _f64(xq)
+    B, Mq, d = xq.shape
+    wq, wo, kc, vc = _f64(wq), _f64(wo), _f64(kc), _f64(vc)
+    ca_len = _i32(ca_len)
+    P_cap = kc.shape[2]
+    d_out = H * dh if wo is None else wo.shape[0]
+    out = np.empty((B, Mq, d_out), dtype=np.float64)
+    rc = lib().moa_ref_cross_attn(_p(xq), B, Mq, d, H, Hkv, dh, _p(wq), _p(wo), d_out, _p(kc), _p(vc),
+                                  _p(ca_len, C.c_int32), P_cap, _p(out))
+    _check(rc, "cross_attn")
+    return out
+
+
+def tree_verify_attn(x, wq, wk, wv, wo, kcache, vcache, prefix_len, mask, H, Hkv, dh):
+    x = _f64(x)
+    B, M, d = x.shape
+    wq, wk, wv, wo = _f64(wq), _f64(wk), _f64(wv), _f64(wo)
+    kcache, vcache = _f64(kcache), _f64(vcache)
+    prefix_len = _i32(prefix_len)
+    mask = np.ascontiguousarray(mask, dtype=np.uint64)
+    P_cap = 0 if kcache is None else kcache.shape[2]
+    d_out = H * dh if wo is None else wo.shape[0]
+    out = np.empty((B, M, d_out), dtype=np.float64)
+    kt = np.empty((B, Hkv, M, dh), dtype=np.float64)
+    vt = np.empty((B, Hkv, M, dh), dtype=np.float64)
+    rc = lib().moa_ref_tree_verify_attn(_p(x), B, M, d, H, Hkv, dh, _p(wq), _p(wk), _p(wv), _p(wo), d_out,
+                                        _p(kcache), _p(vcache), _p(prefix_len, C.c_int32), P_cap,
+                                        _p(mask, C.c_uint64), _p(out), _p(kt), _p(vt))
+    _check(rc, "tree_verify_attn")
+    return out, kt, vt
+
+
+def tree_accept(parent, tok, tgt):
+    parent, tok, tgt = _i32(parent), _i32(tok), _i32(tgt)
+    B, M = parent.shape
+    path = np.empty((B, M), dtype=np.int32)
+    n_path = np.empty((B,), dtype=np.int32)
+    bonus = np.empty((B,), dtype=np.int32)
+    rc = lib().moa_ref_tree_accept(_p(parent, C.c_int32), _p(tok, C.c_int32), _p(tgt, C.c_int32), B, M,
+                                   _p(path, C.c_int32), _p(n_path, C.c_int32), _p(bonus, C.c_int32))
+    _check(rc, "tree_accept")
+    return path, n_path, bonus
+
+
+def softmax_weighted_sum(scores, values):
+    scores, values = _f64(scores), _f64(values)
+    n, dh = values.shape
+    o = np.empty((dh,), dtype=np.float64)
+    ps = C.c_double(0.0)
+    _check(lib().moa_ref_softmax_weighted_sum(_p(scores), _p(values), n, dh, _p(o), C.byref(ps)),
+           "softmax_weighted_sum")
+    return o, ps.value
+
+
+def softmax_weighted_sum_chunked(scores, values, chunk):
+    scores, values = _f64(scores), _f64(values)
+    n, dh = values.shape
+    o = np.empty((dh,), dtype=np.float64)
+    _check(lib().moa_ref_softmax_weighted_sum_chunked(_p(scores), _p(values), n, dh, chunk, _p(o)),
+           "softmax_weighted_sum_chunked")
+    return o

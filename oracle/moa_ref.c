@@ -1,0 +1,391 @@
+/*
+ * moa_ref.c -- CPU oracle (fp64) for the Mixture-of-Attentions draft step.
+ *
+ * TEST INFRASTRUCTURE ONLY: see moa_ref.h.  Every function is the plain
+ * definition from the paper written out: dense score rows, two-pass softmax
+ * (row max, exp, divide), no tiling, no fusion, no algebraic reordering.
+ * OpenMP is used only across units the paper states to be independent
+ * (tokens in LSA; (sequence, query, head) triples in CA / verification).
+ *
+ * Parity with the authors' own implementation is UNPINNED (the paper prints no
+ * numeric example); the pins are the closed forms / invariants / brute force in
+ * tests/test_oracle_*.py.
+ */
+#include "moa_ref.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ tree */
+
+int moa_ref_tree_build(const int32_t *parent, int B, int M, uint64_t *mask, int32_t *depth)
+{
+    if (!parent || !mask || !depth || B < 1 || M < 1) return MOA_REF_BAD_ARG;
+    const int W = (M + 63) / 64;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *par = parent + (int64_t)b * M;
+        if (par[0] != -1) return MOA_REF_BAD_TREE;
+        for (int i = 1; i < M; ++i)
+            if (par[i] < 0 || par[i] >= i) return MOA_REF_BAD_TREE;
+    }
+    for (int b = 0; b < B; ++b) {
+        const int32_t *par = parent + (int64_t)b * M;
+        uint64_t *mk = mask + (int64_t)b * M * W;
+        int32_t *dp = depth + (int64_t)b * M;
+        for (int i = 0; i < M; ++i) {
+            uint64_t *row = mk + (int64_t)i * W;
+            if (i == 0) {
+                for (int w = 0; w < W; ++w) row[w] = 0;
+                dp[0] = 0;
+            } else {
+                const uint64_t *prow = mk + (int64_t)par[i] * W;
+                for (int w = 0; w < W; ++w) row[w] = prow[w];
+                dp[i] = dp[par[i]] + 1;
+            }
+            row[i >> 6] |= (uint64_t)1 << (i & 63);
+        }
+    }
+    return MOA_REF_OK;
+}
+
+/* ---------------------------------------------------------------- linear */
+
+int moa_ref_linear(const double *x, int64_t R, int K, const double *w, int N, double *y)
+{
+    if (!x || !y || R < 0 || K < 1 || N < 1) return MOA_REF_BAD_ARG;
+    if (!w) {
+        if (N != K) return MOA_REF_BAD_ARG;
+        memcpy(y, x, sizeof(double) * (size_t)R * (size_t)K);
+        return MOA_REF_OK;
+    }
+    /* rows are independent; threads split them (no effect inside an outer parallel loop) */
+#pragma omp parallel for schedule(static) if (R > 1)
+    for (int64_t r = 0; r < R; ++r)
+        for (int n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) acc += x[r * K + k] * w[(int64_t)n * K + k];
+            y[r * N + n] = acc;
+        }
+    return MOA_REF_OK;
+}
+
+/* --------------------------------------------------------------- softmax */
+
+/* o[dh] = sum_n softmax(scores)[n] * values[n, :]   (two-pass, dense). */
+int moa_ref_softmax_weighted_sum(const double *scores, const double *values,
+                                 int n, int dh, double *o, double *prob_sum)
+{
+    if (!scores || !values || !o || dh < 1) return MOA_REF_BAD_ARG;
+    if (n < 1) return MOA_REF_EMPTY;
+    double mx = scores[0];
+    for (int i = 1; i < n; ++i) if (scores[i] > mx) mx = scores[i];
+    double *p = (double *)malloc(sizeof(double) * (size_t)n);
+    if (!p) return MOA_REF_BAD_ARG;
+    double den = 0.0;
+    for (int i = 0; i < n; ++i) { p[i] = exp(scores[i] - mx); den += p[i]; }
+    double ps = 0.0;
+    for (int i = 0; i < n; ++i) { p[i] /= den; ps += p[i]; }
+    for (int c = 0; c < dh; ++c) {
+        double acc = 0.0;
+        for (int i = 0; i < n; ++i) acc += p[i] * values[(int64_t)i * dh + c];
+        o[c] = acc;
+    }
+    if (prob_sum) *prob_sum = ps;
+    free(p);
+    return MOA_REF_OK;
+}
+
+/* Same quantity, accumulated chunk by chunk with a running max m, running
+ * denominator l and un-normalised accumulator acc, rescaled whenever m grows. */
+int moa_ref_softmax_weighted_sum_chunked(const double *scores, const double *values,
+                                         int n, int dh, int chunk, double *o)
+{
+    if (!scores || !values || !o || dh < 1 || chunk < 1) return MOA_REF_BAD_ARG;
+    if (n < 1) return MOA_REF_EMPTY;
+    double m = -INFINITY, l = 0.0;
+    for (int c = 0; c < dh; ++c) o[c] = 0.0;
+    for (int s = 0; s < n; s += chunk) {
+        int e = s + chunk < n ? s + chunk : n;
+        double cm = scores[s];
+        for (int i = s + 1; i < e; ++i) if (scores[i] > cm) cm = scores[i];
+        double nm = cm > m ? cm : m;
+        double scale = exp(m - nm);          /* exp(-inf) = 0 on the first chunk */
+        l *= scale;
+        for (int c = 0; c < dh; ++c) o[c] *= scale;
+        for (int i = s; i < e; ++i) {
+            double pi = exp(scores[i] - nm);
+            l += pi;
+            for (int c = 0; c < dh; ++c) o[c] += pi * values[(int64_t)i * dh + c];
+        }
+        m = nm;
+    }
+    for (int c = 0; c < dh; ++c) o[c] /= l;
+    return MOA_REF_OK;
+}
+
+/* ------------------------------------------------------------------- LSA */
+
+int moa_ref_lsa(const double *hs, int64_t T, int L, int d_in, int Hq, int Hkv, int dh,
+                const double *wq, const double *wk, const double *wv, const double *wo,
+                int d_out, double *out)
+{
+    if (!hs || !out || T < 0 || L < 1 || d_in < 1 || Hq < 1 || Hkv < 1 || dh < 1 || d_out < 1)
+        return MOA_REF_BAD_ARG;
+    if (Hq % Hkv) return MOA_REF_BAD_ARG;
+    const int Eq = Hq * dh, Ekv = Hkv * dh, G = Hq / Hkv;
+    if ((!wq && Eq != d_in) || (!wk && Ekv != d_in) || (!wv && Ekv != d_in) || (!wo && d_out != Eq))
+        return MOA_REF_BAD_ARG;
+    const double inv_sqrt = 1.0 / sqrt((double)dh);
+    int bad = 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t t = 0; t < T; ++t) {
+        const double *X = hs + t * (int64_t)L * d_in;
+        double *Q = (double *)malloc(sizeof(double) * (size_t)L * Eq);
+        double *K = (double *)malloc(sizeof(double) * (size_t)L * Ekv);
+        double *V = (double *)malloc(sizeof(double) * (size_t)L * Ekv);
+        double *A = (double *)malloc(sizeof(double) * (size_t)L * Eq);   /* concat of heads */
+        double *Y = (double *)malloc(sizeof(double) * (size_t)L * d_out);
+        double *s = (double *)malloc(sizeof(double) * (size_t)L);
+        double *vg = (double *)malloc(sizeof(double) * (size_t)L * dh);
+        double *oh = (double *)malloc(sizeof(double) * (size_t)dh);
+        if (!Q || !K || !V || !A || !Y || !s || !vg || !oh) {
+            bad = 1;
+        } else {
+            moa_ref_linear(X, L, d_in, wq, Eq, Q);
+            moa_ref_linear(X, L, d_in, wk, Ekv, K);
+            moa_ref_linear(X, L, d_in, wv, Ekv, V);
+            for (int h = 0; h < Hq; ++h) {
+                const int g = h / G;
+                for (int j = 0; j < L; ++j)
+                    for (int c = 0; c < dh; ++c) vg[j * dh + c] = V[j * Ekv + g * dh + c];
+                for (int i = 0; i < L; ++i) {           /* query = layer i */
+                    for (int j = 0; j < L; ++j) {       /* key   = layer j, full mask */
+                        double acc = 0.0;
+                        for (int c = 0; c < dh; ++c)
+                            acc += Q[i * Eq + h * dh + c] * K[j * Ekv + g * dh + c];
+                        s[j] = acc * inv_sqrt;
+                    }
+                    moa_ref_softmax_weighted_sum(s, vg, L, dh, oh, NULL);
+                    for (int c = 0; c < dh; ++c) A[i * Eq + h * dh + c] = oh[c];
+                }
+            }
+            moa_ref_linear(A, L, Eq, wo, d_out, Y);
+            for (int n = 0; n < d_out; ++n) {           /* mean aggregation over layers */
+                double acc = 0.0;
+                for (int i = 0; i < L; ++i) acc += Y[i * d_out + n];
+                out[t * d_out + n] = acc / (double)L;
+            }
+        }
+        free(Q); free(K); free(V); free(A); free(Y); free(s); free(vg); free(oh);
+    }
+    return bad ? MOA_REF_BAD_ARG : MOA_REF_OK;
+}
+
+/* ---------------------------------------------------------- CA kv append */
+
+int moa_ref_ca_kv_append(const double *mem_new, int d_mem, const int32_t *tok_off, int B,
+                         int Hkv, int dh, const double *wk, const double *wv,
+                         double *kc, double *vc, int32_t *ca_len, int P_cap)
+{
+    if (!mem_new || !tok_off || !kc || !vc || !ca_len || B < 1 || Hkv < 1 || dh < 1 ||
+        d_mem < 1 || P_cap < 1)
+        return MOA_REF_BAD_ARG;
+    const int Ekv = Hkv * dh;
+    if ((!wk || !wv) && Ekv != d_mem) return MOA_REF_BAD_ARG;
+    if (tok_off[0] != 0) return MOA_REF_BAD_ARG;
+    for (int b = 0; b < B; ++b) {
+        int nb = tok_off[b + 1] - tok_off[b];
+        if (nb < 0 || ca_len[b] < 0) return MOA_REF_BAD_ARG;
+        if (ca_len[b] + nb > P_cap) return MOA_REF_EMPTY;
+    }
+    double *kr = (double *)malloc(sizeof(double) * (size_t)Ekv);
+    double *vr = (double *)malloc(sizeof(double) * (size_t)Ekv);
+    if (!kr || !vr) { free(kr); free(vr); return MOA_REF_BAD_ARG; }
+    for (int b = 0; b < B; ++b) {
+        for (int r = tok_off[b]; r < tok_off[b + 1]; ++r) {
+            const double *m = mem_new + (int64_t)r * d_mem;
+            moa_ref_linear(m, 1, d_mem, wk, Ekv, kr);
+            moa_ref_linear(m, 1, d_mem, wv, Ekv, vr);
+            const int p = ca_len[b] + (r - tok_off[b]);
+            for (int g = 0; g < Hkv; ++g)
+                for (int c = 0; c < dh; ++c) {
+                    int64_t o = (((int64_t)b * Hkv + g) * P_cap + p) * dh + c;
+                    kc[o] = kr[g * dh + c];
+                    vc[o] = vr[g * dh + c];
+                }
+        }
+        ca_len[b] += tok_off[b + 1] - tok_off[b];
+    }
+    free(kr); free(vr);
+    return MOA_REF_OK;
+}
+
+/* -------------------------------------------------------- cross-attention */
+
+int moa_ref_cross_attn(const double *xq, int B, int Mq, int d, int H, int Hkv, int dh,
+                       const double *wq, const double *wo, int d_out,
+                       const double *kc, const double *vc, const int32_t *ca_len, int P_cap,
+                       double *out)
+{
+    if (!xq || !kc || !vc || !ca_len || !out || B < 1 || Mq < 1 || d < 1 || H < 1 || Hkv < 1 ||
+        dh < 1 || d_out < 1 || P_cap < 1)
+        return MOA_REF_BAD_ARG;
+    if (H % Hkv) return MOA_REF_BAD_ARG;
+    const int E = H * dh, G = H / Hkv;
+    if ((!wq && E != d) || (!wo && d_out != E)) return MOA_REF_BAD_ARG;
+    for (int b = 0; b < B; ++b) {
+        if (ca_len[b] < 0 || ca_len[b] > P_cap) return MOA_REF_BAD_ARG;
+        if (ca_len[b] == 0) return MOA_REF_EMPTY;
+    }
+    const double inv_sqrt = 1.0 / sqrt((double)dh);
+    const int64_t R = (int64_t)B * Mq;
+    double *Q = (double *)malloc(sizeof(double) * (size_t)R * E);
+    double *A = (double *)malloc(sizeof(double) * (size_t)R * E);
+    if (!Q || !A) { free(Q); free(A); return MOA_REF_BAD_ARG; }
+    moa_ref_linear(xq, R, d, wq, E, Q);
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t rh = 0; rh < R * H; ++rh) {
+        const int64_t r = rh / H;
+        const int h = (int)(rh % H), g = h / G, b = (int)(r / Mq);
+        const int n = ca_len[b];
+        const double *Kg = kc + ((int64_t)b * Hkv + g) * P_cap * dh;
+        const double *Vg = vc + ((int64_t)b * Hkv + g) * P_cap * dh;
+        const double *q = Q + r * E + h * dh;
+        double *s = (double *)malloc(sizeof(double) * (size_t)n);
+        for (int p = 0; p < n; ++p) {                 /* every cached row, no mask */
+            double acc = 0.0;
+            for (int c = 0; c < dh; ++c) acc += q[c] * Kg[(int64_t)p * dh + c];
+            s[p] = acc * inv_sqrt;
+        }
+        moa_ref_softmax_weighted_sum(s, Vg, n, dh, A + r * E + h * dh, NULL);
+        free(s);
+    }
+    moa_ref_linear(A, R, E, wo, d_out, out);
+    free(Q); free(A);
+    return MOA_REF_OK;
+}
+
+/* ------------------------------------------------------------ tree verify */
+
+int moa_ref_tree_verify_attn(const double *x, int B, int M, int d, int H, int Hkv, int dh,
+                             const double *wq, const double *wk, const double *wv,
+                             const double *wo, int d_out,
+                             const double *kcache, const double *vcache,
+                             const int32_t *prefix_len, int P_cap, const uint64_t *mask,
+                             double *out, double *k_tree, double *v_tree)
+{
+    if (!x || !prefix_len || !mask || !out || !k_tree || !v_tree || B < 1 || M < 1 || d < 1 ||
+        H < 1 || Hkv < 1 || dh < 1 || d_out < 1 || P_cap < 0)
+        return MOA_REF_BAD_ARG;
+    if (H % Hkv) return MOA_REF_BAD_ARG;
+    const int E = H * dh, Ekv = Hkv * dh, G = H / Hkv, W = (M + 63) / 64;
+    if ((!wq && E != d) || (!wk && Ekv != d) || (!wv && Ekv != d) || (!wo && d_out != E))
+        return MOA_REF_BAD_ARG;
+    for (int b = 0; b < B; ++b) {
+        if (prefix_len[b] < 0 || prefix_len[b] > P_cap) return MOA_REF_BAD_ARG;
+        if (prefix_len[b] > 0 && (!kcache || !vcache)) return MOA_REF_BAD_ARG;
+    }
+    const double inv_sqrt = 1.0 / sqrt((double)dh);
+    const int64_t R = (int64_t)B * M;
+    double *Q = (double *)malloc(sizeof(double) * (size_t)R * E);
+    double *Kt = (double *)malloc(sizeof(double) * (size_t)R * Ekv);
+    double *Vt = (double *)malloc(sizeof(double) * (size_t)R * Ekv);
+    double *A = (double *)malloc(sizeof(double) * (size_t)R * E);
+    if (!Q || !Kt || !Vt || !A) { free(Q); free(Kt); free(Vt); free(A); return MOA_REF_BAD_ARG; }
+    moa_ref_linear(x, R, d, wq, E, Q);
+    moa_ref_linear(x, R, d, wk, Ekv, Kt);
+    moa_ref_linear(x, R, d, wv, Ekv, Vt);
+
+    /* tree rows' own keys / values, laid out like one more slab of the cache */
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hkv; ++g)
+            for (int j = 0; j < M; ++j)
+                for (int c = 0; c < dh; ++c) {
+                    int64_t o = (((int64_t)b * Hkv + g) * M + j) * dh + c;
+                    k_tree[o] = Kt[((int64_t)b * M + j) * Ekv + g * dh + c];
+                    v_tree[o] = Vt[((int64_t)b * M + j) * Ekv + g * dh + c];
+                }
+
+    int empty = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t rh = 0; rh < R * H; ++rh) {
+        const int64_t r = rh / H;
+        const int h = (int)(rh % H), g = h / G, b = (int)(r / M), i = (int)(r % M);
+        const int P = prefix_len[b];
+        const uint64_t *mrow = mask + ((int64_t)b * M + i) * W;
+        const double *q = Q + r * E + h * dh;
+        /* gather the visible key set: prefix rows, then visible tree rows */
+        double *s = (double *)malloc(sizeof(double) * (size_t)(P + M));
+        double *vv = (double *)malloc(sizeof(double) * (size_t)(P + M) * dh);
+        int n = 0;
+        for (int p = 0; p < P; ++p) {
+            const double *kr = kcache + (((int64_t)b * Hkv + g) * P_cap + p) * dh;
+            const double *vr = vcache + (((int64_t)b * Hkv + g) * P_cap + p) * dh;
+            double acc = 0.0;
+            for (int c = 0; c < dh; ++c) acc += q[c] * kr[c];
+            s[n] = acc * inv_sqrt;
+            for (int c = 0; c < dh; ++c) vv[(int64_t)n * dh + c] = vr[c];
+            ++n;
+        }
+        for (int j = 0; j < M; ++j) {
+            if (!((mrow[j >> 6] >> (j & 63)) & 1)) continue;
+            const double *kr = k_tree + (((int64_t)b * Hkv + g) * M + j) * dh;
+            const double *vr = v_tree + (((int64_t)b * Hkv + g) * M + j) * dh;
+            double acc = 0.0;
+            for (int c = 0; c < dh; ++c) acc += q[c] * kr[c];
+            s[n] = acc * inv_sqrt;
+            for (int c = 0; c < dh; ++c) vv[(int64_t)n * dh + c] = vr[c];
+            ++n;
+        }
+        if (n == 0) {
+#pragma omp atomic write
+            empty = 1;
+        } else {
+            moa_ref_softmax_weighted_sum(s, vv, n, dh, A + r * E + h * dh, NULL);
+        }
+        free(s); free(vv);
+    }
+    int rc = MOA_REF_OK;
+    if (empty) rc = MOA_REF_EMPTY;
+    else moa_ref_linear(A, R, E, wo, d_out, out);
+    free(Q); free(Kt); free(Vt); free(A);
+    return rc;
+}
+
+/* ----------------------------------------------------------------- accept */
+
+int moa_ref_tree_accept(const int32_t *parent, const int32_t *tok, const int32_t *tgt,
+                        int B, int M, int32_t *path, int32_t *n_path, int32_t *bonus)
+{
+    if (!parent || !tok || !tgt || !path || !n_path || !bonus || B < 1 || M < 1)
+        return MOA_REF_BAD_ARG;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *par = parent + (int64_t)b * M;
+        if (par[0] != -1) return MOA_REF_BAD_TREE;
+        for (int i = 1; i < M; ++i)
+            if (par[i] < 0 || par[i] >= i) return MOA_REF_BAD_TREE;
+    }
+    for (int b = 0; b < B; ++b) {
+        const int32_t *par = parent + (int64_t)b * M;
+        const int32_t *tk = tok + (int64_t)b * M;
+        const int32_t *tg = tgt + (int64_t)b * M;
+        int32_t *pt = path + (int64_t)b * M;
+        for (int i = 0; i < M; ++i) pt[i] = -1;
+        int cur = 0, n = 0;
+        pt[n++] = 0;
+        for (;;) {
+            int next = -1;
+            for (int c = cur + 1; c < M; ++c)
+                if (par[c] == cur && tk[c] == tg[cur]) { next = c; break; }
+            if (next < 0) break;
+            cur = next;
+            pt[n++] = cur;
+        }
+        n_path[b] = n;
+        bonus[b] = tg[cur];
+    }
+    return MOA_REF_OK;
+}

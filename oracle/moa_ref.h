@@ -1,0 +1,114 @@
+/*
+ * moa_ref.h -- CPU oracle for the Mixture-of-Attentions draft step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, fp64, written from the paper's
+ * definitions.  Nothing in the product path may include, link or call this;
+ * only the test-suite, the smoke check and the benchmark's cpu_baseline leg do.
+ * It shares no code with the GPU library (own header, own status codes).
+ *
+ * All pointers are HOST pointers.  All floating-point tensors are fp64,
+ * row-major, dense.  Weights are [out_features, in_features].
+ * A NULL weight means "this projection is the identity" (the input is taken
+ * as already projected; widths must then agree).
+ *
+ * Value-level parity with the paper authors' implementation is UNPINNED for
+ * every floating-point function here: the paper prints no numeric example of
+ * LSA, CA or tree attention.  The functions are pinned by closed forms,
+ * invariants, library cross-checks and brute force (tests/test_oracle_*.py).
+ */
+#ifndef MOA_REF_H
+#define MOA_REF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MOA_REF_OK = 0,
+    MOA_REF_BAD_ARG = 1,   /* null pointer, non-positive size, widths that do not agree */
+    MOA_REF_BAD_TREE = 2,  /* parent[0] != -1 or parent[i] outside [0, i)               */
+    MOA_REF_EMPTY = 3,     /* softmax over an empty key set, or cache overflow          */
+};
+
+/* Draft tree (Sec. 2.2 "tree drafting", Tree Attention): node 0 is the root,
+ * parent[i] < i.  depth[0] = 0, depth[i] = depth[parent[i]] + 1.
+ * mask[b][i] is the set {i} U ancestors(i) as a bitset of W = ceil(M/64)
+ * 64-bit words: node j lives in word j>>6, bit j&63. */
+int moa_ref_tree_build(const int32_t *parent /*[B,M]*/, int B, int M,
+                       uint64_t *mask /*[B,M,W]*/, int32_t *depth /*[B,M]*/);
+
+/* y[R,N] = x[R,K] * w[N,K]^T  (w == NULL: N must equal K, y = x). */
+int moa_ref_linear(const double *x, int64_t R, int K, const double *w, int N, double *y);
+
+/* Layer Self-Attention followed by mean aggregation (Sec. 3.1.1 "Layer
+ * Self-Attention"; Alg. 1 "LSA_layer_with_mean").  Every token is independent;
+ * attention runs over the L layer rows of that token with a full mask.
+ *   Q = X wq^T [L, Hq*dh],  K = X wk^T, V = X wv^T [L, Hkv*dh]
+ *   head h reads KV head h / (Hq/Hkv);  S = Q_h K_g^T / sqrt(dh);  P = softmax rows
+ *   Y = concat_h(P V_g) wo^T  [L, d_out];   out[t] = mean over the L rows of Y. */
+int moa_ref_lsa(const double *hs /*[T,L,d_in]*/, int64_t T, int L, int d_in,
+                int Hq, int Hkv, int dh,
+                const double *wq /*[Hq*dh,d_in]*/, const double *wk /*[Hkv*dh,d_in]*/,
+                const double *wv /*[Hkv*dh,d_in]*/, const double *wo /*[d_out,Hq*dh]*/,
+                int d_out, double *out /*[T,d_out]*/);
+
+/* Cross-Attention memory: project newly verified LSA rows to keys and values and
+ * append them to each sequence's cache (Sec. 3.1.2 "Cross-Attention": keys and
+ * values come from the output of LSA; Alg. 1 "kv <- (kv, kv')").
+ * Rows tok_off[b] .. tok_off[b+1]-1 of mem_new belong to sequence b and land at
+ * cache rows ca_len[b] ..; ca_len[b] is advanced. */
+int moa_ref_ca_kv_append(const double *mem_new /*[T,d_mem]*/, int d_mem,
+                         const int32_t *tok_off /*[B+1]*/, int B, int Hkv, int dh,
+                         const double *wk /*[Hkv*dh,d_mem]*/, const double *wv,
+                         double *kc, double *vc /*[B,Hkv,P_cap,dh]*/,
+                         int32_t *ca_len /*[B] in/out*/, int P_cap);
+
+/* Cross-Attention of the draft model at generation time (Sec. 3.1.2; Alg. 1
+ * "CA_layer(q, kv)"): every query attends ALL ca_len[b] cached rows, no mask.
+ * ca_len[b] == 0 -> MOA_REF_EMPTY. */
+int moa_ref_cross_attn(const double *xq /*[B,Mq,d]*/, int B, int Mq, int d,
+                       int H, int Hkv, int dh,
+                       const double *wq /*[H*dh,d]*/, const double *wo /*[d_out,H*dh]*/, int d_out,
+                       const double *kc, const double *vc /*[B,Hkv,P_cap,dh]*/,
+                       const int32_t *ca_len /*[B]*/, int P_cap,
+                       double *out /*[B,Mq,d_out]*/);
+
+/* Tree-masked verification attention of one LLM layer (Sec. 2.2 Tree Attention;
+ * Alg. 1 verification forward pass; the attention inside every reused layer of
+ * Target Layer Inference, Sec. 3.2).  Node i, head h attends cache rows
+ * 0..prefix_len[b]-1 and tree rows j with bit j of mask[b][i] set.
+ * Also returns the tree rows' own projected keys/values. */
+int moa_ref_tree_verify_attn(const double *x /*[B,M,d]*/, int B, int M, int d,
+                             int H, int Hkv, int dh,
+                             const double *wq /*[H*dh,d]*/, const double *wk /*[Hkv*dh,d]*/,
+                             const double *wv, const double *wo /*[d_out,H*dh]*/, int d_out,
+                             const double *kcache, const double *vcache /*[B,Hkv,P_cap,dh]*/,
+                             const int32_t *prefix_len /*[B]*/, int P_cap,
+                             const uint64_t *mask /*[B,M,W]*/,
+                             double *out /*[B,M,d_out]*/,
+                             double *k_tree, double *v_tree /*[B,Hkv,M,dh]*/);
+
+/* Greedy acceptance (Sec. 2.2: everything after the first mismatch is dropped).
+ * tok[i] is the token drafted at node i; tgt[i] is the LLM's greedy token after
+ * node i.  Walk from the root to the lowest-index child whose token equals the
+ * current node's tgt; stop when none does.  path = visited nodes (unused = -1),
+ * n_path >= 1, bonus = tgt of the last visited node. */
+int moa_ref_tree_accept(const int32_t *parent, const int32_t *tok, const int32_t *tgt /*[B,M]*/,
+                        int B, int M, int32_t *path /*[B,M]*/, int32_t *n_path /*[B]*/,
+                        int32_t *bonus /*[B]*/);
+
+/* Self-check variant of the attention reduction: same result as the two-pass
+ * softmax used above, computed chunk by chunk with a running max / sum and a
+ * final merge.  scores[n], values[n,dh] -> o[dh].  Used only by a test that
+ * shows the chunked merge formula is exact. */
+int moa_ref_softmax_weighted_sum_chunked(const double *scores, const double *values,
+                                         int n, int dh, int chunk, double *o);
+int moa_ref_softmax_weighted_sum(const double *scores, const double *values,
+                                 int n, int dh, double *o, double *prob_sum);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
