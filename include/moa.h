@@ -1,0 +1,182 @@
+/*
+ * moa.h -- C ABI of libmoa: the single-device hot path of one draft step of the
+ * Mixture-of-Attentions speculative-decoding method, hand-written for gfx950.
+ *
+ * Conventions
+ *  - Every function returns an int32 status: MOA_OK (0) or a negative MOA_ERR_*.
+ *    moa_last_error() gives a thread-local detail string for the last failure.
+ *  - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns
+ *    every buffer (inputs, outputs, caches, workspace); the library allocates no
+ *    device memory, keeps no device state and never frees.
+ *  - All work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
+ *    default stream).  No host synchronisation happens inside.  Argument checks
+ *    that need only host values run before anything is launched; a failed check
+ *    launches nothing.
+ *  - Values that live in device memory (parent[], prefix_len[], ca_len[]) are
+ *    checked on the device: kernels clamp what they read so that no access leaves
+ *    the caller's buffers, and OR a MOA_DEV_* bit into *dev_status (may be NULL;
+ *    the caller zeroes it and reads it back when it wants to know).
+ *  - dtype: MOA_F32 or MOA_BF16 is the storage type of every floating-point
+ *    tensor of the call (activations, weights, caches, outputs).  Accumulation,
+ *    scores, softmax max/sum and probabilities are fp32 in both cases.
+ *  - Weights are row-major [out_features, in_features].  A NULL weight means the
+ *    projection is the identity: the input is taken as already projected (the
+ *    widths must then agree).
+ *  - Attention scale is 1/sqrt(head_dim).  Query head h reads KV head
+ *    h / (n_q_heads / n_kv_heads).  No positional encoding is applied inside.
+ *  - Workspace: moa_workspace_bytes() gives a size that suffices for every call
+ *    with sizes up to the ones queried; ws must be 256-byte aligned.
+ */
+#ifndef MOA_H
+#define MOA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MOA_OK = 0,
+    MOA_ERR_NULL = -1,      /* a required pointer is NULL                                  */
+    MOA_ERR_SHAPE = -2,     /* unsupported or inconsistent dimensions                      */
+    MOA_ERR_TREE = -3,      /* (host-visible) tree argument invalid                        */
+    MOA_ERR_RANGE = -4,     /* a length exceeds its capacity                               */
+    MOA_ERR_DTYPE = -5,     /* dtype is neither MOA_F32 nor MOA_BF16                       */
+    MOA_ERR_WORKSPACE = -6, /* workspace NULL, misaligned or too small                     */
+    MOA_ERR_HIP = -7,       /* a HIP call (launch) failed                                  */
+};
+
+enum { MOA_F32 = 0, MOA_BF16 = 1 };
+
+/* bits OR-ed into *dev_status by kernels */
+enum {
+    MOA_DEV_BAD_PARENT = 1,   /* parent[0] != -1 or parent[i] outside [0, i)                */
+    MOA_DEV_BAD_LENGTH = 2,   /* prefix_len / ca_len outside [0, P_cap] (clamped)           */
+    MOA_DEV_EMPTY_KEYS = 4,   /* cross-attention over an empty memory (output row = 0)      */
+    MOA_DEV_CACHE_FULL = 8,   /* kv append would pass P_cap (rows beyond it are dropped)    */
+};
+
+#define MOA_MAX_TREE 256      /* a tree position fits one byte (client message format, Sec. 4.2) */
+
+typedef struct {
+    int32_t n_layers;      /* L   : LLM layers stacked on LSA's layer axis                  */
+    int32_t d_model;       /* d   : LLM hidden size E                                       */
+    int32_t n_q_heads;     /* H   : query heads of CA and of the LLM's attention            */
+    int32_t n_kv_heads;    /* Hkv : key/value heads                                         */
+    int32_t head_dim;      /* dh                                                            */
+    int32_t d_lsa_in;      /* d_in: width of one layer row given to LSA (2*E_kv in the paper) */
+    int32_t lsa_q_heads;   /* H_l : LSA query heads; LSA output width d_lsa = H_l * dh      */
+    int32_t lsa_kv_heads;  /* Hkv_l                                                         */
+    int32_t dtype;         /* MOA_F32 | MOA_BF16                                            */
+} moa_shape_t;
+
+const char *moa_status_str(int32_t status);
+const char *moa_last_error(void);
+
+/* Workspace bytes sufficient for any call below with batch <= B, cache capacity <= P_cap,
+ * tree size / query count <= M and LSA token count <= T_lsa.  Host-only, launches nothing. */
+int32_t moa_workspace_bytes(const moa_shape_t *shape, int32_t B, int32_t P_cap, int32_t M,
+                            int64_t T_lsa, size_t *bytes_host);
+
+/* Draft tree structure (Sec. 2.2, tree drafting / Tree Attention).
+ * parent[b][0] = -1 (root = the last token sampled by the LLM), 0 <= parent[b][i] < i.
+ * mask[b][i] = bitset of {i} U ancestors(i), W = ceil(M/64) words per row, node j in word
+ * j>>6 bit j&63; depth[b][0] = 0.  Integer results, exact.  An invalid parent entry sets
+ * MOA_DEV_BAD_PARENT and the row keeps only the ancestors reached before it. */
+int32_t moa_tree_build(const int32_t *parent /*[B,M]*/, int32_t B, int32_t M,
+                       uint64_t *mask /*[B,M,W]*/, int32_t *depth /*[B,M]*/,
+                       int32_t *dev_status, void *stream);
+
+/* Greedy acceptance (Sec. 2.2: all tokens after the first mismatch are discarded; Alg. 1,
+ * verification step).  tok[i] = token drafted at node i, tgt[i] = the LLM's greedy token
+ * after node i.  From the root, step to the lowest-index child c with tok[c] == tgt[cur];
+ * stop when there is none.  path[b] = visited nodes then -1, n_path[b] >= 1,
+ * bonus[b] = tgt of the last visited node.  Integer results, exact. */
+int32_t moa_tree_accept(const int32_t *parent, const int32_t *tok, const int32_t *tgt /*[B,M]*/,
+                        int32_t B, int32_t M, int32_t *path /*[B,M]*/, int32_t *n_path /*[B]*/,
+                        int32_t *bonus /*[B]*/, void *stream);
+
+/* Layer Self-Attention with mean aggregation (Sec. 3.1.1 "Layer Self-Attention"; Alg. 1,
+ * LSA_layer_with_mean).  For every token independently: full (unmasked) self-attention over
+ * its L layer rows, output projection, then the mean over the L rows.
+ *   hs [T, L, d_in]  ->  out [T, H_l*dh]
+ *   wq [H_l*dh, d_in], wk, wv [Hkv_l*dh, d_in], wo [H_l*dh, H_l*dh]
+ * The kernels use mean_l(P V) Wo^T = ((1^T P / L) V) Wo^T, exact in real arithmetic. */
+int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T,
+                const void *wq, const void *wk, const void *wv, const void *wo,
+                void *out, void *ws, size_t ws_bytes, void *stream);
+
+/* Cross-attention memory append (Sec. 3.1.2: CA keys and values come from the output of
+ * LSA; Alg. 1, kv <- (kv, kv')).  Rows tok_off[b] .. tok_off[b+1]-1 of mem_new belong to
+ * sequence b (tok_off is a device array, tok_off[0] = 0, non-decreasing, tok_off[B] <= T;
+ * rows owned by no sequence are ignored); their projections are written to cache rows
+ * ca_len[b] .. and ca_len[b] is advanced.  Rows that would pass P_cap are dropped and
+ * MOA_DEV_CACHE_FULL is set.
+ *   mem_new [T, d_mem], wk, wv [Hkv*dh, d_mem], kc, vc [B, Hkv, P_cap, dh] */
+int32_t moa_ca_kv_append(const moa_shape_t *shape, const void *mem_new, int64_t T, int32_t d_mem,
+                         const int32_t *tok_off /*[B+1]*/, int32_t B,
+                         const void *wk, const void *wv, void *kc, void *vc,
+                         int32_t *ca_len /*[B] in/out*/, int32_t P_cap,
+                         int32_t *dev_status, void *stream);
+
+/* The draft model's Cross-Attention at generation time (Sec. 3.1.2; Alg. 1, CA_layer(q, kv)):
+ * every query row attends all ca_len[b] cached rows, no mask; queries do not see each other
+ * (input-independence, Property 3).
+ *   xq [B, Mq, d], wq [H*dh, d], wo [d, H*dh], kc, vc [B, Hkv, P_cap, dh] -> out [B, Mq, d] */
+int32_t moa_cross_attn_draft(const moa_shape_t *shape, const void *xq, int32_t B, int32_t Mq,
+                             const void *wq, const void *wo, const void *kc, const void *vc,
+                             const int32_t *ca_len /*[B]*/, int32_t P_cap, void *out,
+                             int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
+
+/* Tree-masked verification attention of one LLM layer (Sec. 2.2 Tree Attention; Alg. 1,
+ * verification forward pass; also the attention inside each reused layer under Target Layer
+ * Inference, Sec. 3.2).  Node i, head h attends cache rows 0..prefix_len[b]-1 and the tree
+ * rows j with bit j of mask[b][i] set; one softmax over the union.
+ *   x [B, M, d]; wq [H*dh, d], wk, wv [Hkv*dh, d], wo [d, H*dh]
+ *   kcache, vcache [B, Hkv, P_cap, dh]; mask [B, M, W] as written by moa_tree_build
+ *   -> out [B, M, d]; k_tree, v_tree [B, Hkv, M, dh] (the tree rows' own keys / values; the
+ *      caller commits the accepted ones to its cache). */
+int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B, int32_t M,
+                             const void *wq, const void *wk, const void *wv, const void *wo,
+                             const void *kcache, const void *vcache,
+                             const int32_t *prefix_len /*[B]*/, int32_t P_cap,
+                             const uint64_t *mask, void *out, void *k_tree, void *v_tree,
+                             int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
+
+/* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
+ * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
+ * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk.
+ * The *_host members are HOST arrays of n_verify_layers device pointers. */
+typedef struct {
+    const moa_shape_t *shape;
+    int32_t B, M, Mq;
+    /* tree */
+    const int32_t *parent;  uint64_t *mask;  int32_t *depth;
+    /* LSA */
+    const void *lsa_hs;  int64_t T_lsa;
+    const void *lsa_wq, *lsa_wk, *lsa_wv, *lsa_wo;
+    void *lsa_out;                                /* [T_lsa, H_l*dh]; also the CA memory rows */
+    /* CA memory append */
+    const int32_t *tok_off;                       /* device [B+1], tok_off[B] <= T_lsa        */
+    const void *ca_wk, *ca_wv;  void *ca_k, *ca_v;  int32_t *ca_len;  int32_t ca_P_cap;
+    /* CA */
+    const void *ca_xq, *ca_wq, *ca_wo;  void *ca_out;
+    /* verification */
+    int32_t n_verify_layers;
+    const void *const *v_x_host, *const *v_wq_host, *const *v_wk_host, *const *v_wv_host, *const *v_wo_host;
+    const void *const *v_kcache_host, *const *v_vcache_host;
+    void *const *v_out_host, *const *v_ktree_host, *const *v_vtree_host;
+    const int32_t *prefix_len;  int32_t P_cap;
+    /* accept */
+    const int32_t *tok, *tgt;  int32_t *path, *n_path, *bonus;
+    int32_t *dev_status;  void *ws;  size_t ws_bytes;  void *stream;
+} moa_step_args_t;
+
+int32_t moa_draft_step(const moa_step_args_t *args);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

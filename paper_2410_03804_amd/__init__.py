@@ -1,0 +1,11 @@
+"""MI355X-native hot path of the Mixture-of-Attentions draft step (LSA, CA, tree verification).
+
+The package is a thin ctypes binding over ``libmoa.so`` (hand-written HIP for gfx950, C ABI in
+``include/moa.h``).  Importing it loads the library; there is no fallback of any kind -- if the
+library is missing the import fails.  Build it with ``python -m paper_2410_03804_amd.build``.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, DEV_BAD_LENGTH, DEV_BAD_PARENT, DEV_CACHE_FULL, DEV_EMPTY_KEYS, MAX_TREE, MoaError, Shape,
+    ca_kv_append, cross_attn_draft, draft_step, exported_symbols, last_error, library_path, lsa, status_str,
+    tree_accept, tree_build, tree_verify_attn, workspace_bytes,
+)

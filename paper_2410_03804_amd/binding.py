@@ -1,0 +1,283 @@
+"""ctypes binding of libmoa.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA tensors (PyTorch is used for device memory and streams, nothing else);
+every computation happens inside the library's kernels.  Each wrapper checks that the tensors it
+hands over are contiguous, on the GPU, of the call's dtype and at least as large as the C
+function will touch -- the kernels trust their sizes.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "libmoa.so"
+if not _LIB_PATH.exists():
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2410_03804_amd.build` "
+                      "(there is no fallback path)")
+_lib = C.CDLL(str(_LIB_PATH))
+
+F32, BF16 = 0, 1
+MAX_TREE = 256
+DEV_BAD_PARENT, DEV_BAD_LENGTH, DEV_EMPTY_KEYS, DEV_CACHE_FULL = 1, 2, 4, 8
+_TORCH_DTYPE = {F32: torch.float32, BF16: torch.bfloat16}
+
+
+class MoaError(RuntimeError):
+    def __init__(self, status: int, detail: str):
+        super().__init__(f"{status_str(status)}: {detail}")
+        self.status = status
+
+
+class Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim",
+                                         "d_lsa_in", "lsa_q_heads", "lsa_kv_heads", "dtype")]
+
+
+class _StepArgs(C.Structure):
+    _fields_ = [
+        ("shape", C.POINTER(Shape)), ("B", C.c_int32), ("M", C.c_int32), ("Mq", C.c_int32),
+        ("parent", C.c_void_p), ("mask", C.c_void_p), ("depth", C.c_void_p),
+        ("lsa_hs", C.c_void_p), ("T_lsa", C.c_int64),
+        ("lsa_wq", C.c_void_p), ("lsa_wk", C.c_void_p), ("lsa_wv", C.c_void_p), ("lsa_wo", C.c_void_p),
+        ("lsa_out", C.c_void_p),
+        ("tok_off", C.c_void_p),
+        ("ca_wk", C.c_void_p), ("ca_wv", C.c_void_p), ("ca_k", C.c_void_p), ("ca_v", C.c_void_p),
+        ("ca_len", C.c_void_p), ("ca_P_cap", C.c_int32),
+        ("ca_xq", C.c_void_p), ("ca_wq", C.c_void_p), ("ca_wo", C.c_void_p), ("ca_out", C.c_void_p),
+        ("n_verify_layers", C.c_int32),
+        ("v_x_host", C.POINTER(C.c_void_p)), ("v_wq_host", C.POINTER(C.c_void_p)),
+        ("v_wk_host", C.POINTER(C.c_void_p)), ("v_wv_host", C.POINTER(C.c_void_p)),
+        ("v_wo_host", C.POINTER(C.c_void_p)), ("v_kcache_host", C.POINTER(C.c_void_p)),
+        ("v_vcache_host", C.POINTER(C.c_void_p)), ("v_out_host", C.POINTER(C.c_void_p)),
+        ("v_ktree_host", C.POINTER(C.c_void_p)), ("v_vtree_host", C.POINTER(C.c_void_p)),
+        ("prefix_len", C.c_void_p), ("P_cap", C.c_int32),
+        ("tok", C.c_void_p), ("tgt", C.c_void_p), ("path", C.c_void_p), ("n_path", C.c_void_p),
+        ("bonus", C.c_void_p),
+        ("dev_status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t), ("stream", C.c_void_p),
+    ]
+
+
+_SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
+            "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step"]
+
+_lib.moa_status_str.restype = C.c_char_p
+_lib.moa_status_str.argtypes = [C.c_int32]
+_lib.moa_last_error.restype = C.c_char_p
+_lib.moa_last_error.argtypes = []
+_vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+_lib.moa_workspace_bytes.argtypes = [C.POINTER(Shape), _i32, _i32, _i32, _i64, C.POINTER(_sz)]
+_lib.moa_tree_build.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.moa_tree_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.moa_lsa.argtypes = [C.POINTER(Shape), _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moa_ca_kv_append.argtypes = [C.POINTER(Shape), _vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
+_lib.moa_cross_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
+_lib.moa_tree_verify_attn.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
+                                      _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moa_draft_step.argtypes = [C.POINTER(_StepArgs)]
+for _n in _SYMBOLS[2:]:
+    getattr(_lib, _n).restype = C.c_int32
+
+
+def library_path() -> str:
+    return str(_LIB_PATH)
+
+
+def exported_symbols():
+    return list(_SYMBOLS)
+
+
+def status_str(status: int) -> str:
+    return _lib.moa_status_str(status).decode()
+
+
+def last_error() -> str:
+    return _lib.moa_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise MoaError(rc, last_error())
+
+
+def _dev(t, dtype, numel, name):
+    """Device pointer of tensor t after checking it can hold what the call touches."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name}: expected a torch tensor")
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name}: must be a contiguous CUDA tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if t.numel() < numel:
+        raise ValueError(f"{name}: {t.numel()} elements, the call touches {numel}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    if not ws.is_cuda or not ws.is_contiguous():
+        raise ValueError("ws: must be a contiguous CUDA tensor")
+    return C.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def workspace_bytes(shape: Shape, B: int, P_cap: int, M: int, T_lsa: int) -> int:
+    out = _sz(0)
+    _check(_lib.moa_workspace_bytes(C.byref(shape), B, P_cap, M, T_lsa, C.byref(out)))
+    return out.value
+
+
+def tree_build(parent, mask, depth, dev_status=None, stream=None):
+    B, M = parent.shape
+    W = (M + 63) // 64
+    _check(_lib.moa_tree_build(_dev(parent, torch.int32, B * M, "parent"), B, M,
+                               _dev(mask, torch.int64, B * M * W, "mask"), _dev(depth, torch.int32, B * M, "depth"),
+                               _dev(dev_status, torch.int32, 1, "dev_status"), _stream(stream)))
+
+
+def tree_accept(parent, tok, tgt, path, n_path, bonus, stream=None):
+    B, M = parent.shape
+    i32 = torch.int32
+    _check(_lib.moa_tree_accept(_dev(parent, i32, B * M, "parent"), _dev(tok, i32, B * M, "tok"),
+                                _dev(tgt, i32, B * M, "tgt"), B, M, _dev(path, i32, B * M, "path"),
+                                _dev(n_path, i32, B, "n_path"), _dev(bonus, i32, B, "bonus"), _stream(stream)))
+
+
+def lsa(shape: Shape, hs, wq, wk, wv, wo, out, ws, stream=None):
+    dt = _TORCH_DTYPE[shape.dtype]
+    T = hs.shape[0]
+    L, d_in, dh = shape.n_layers, shape.d_lsa_in, shape.head_dim
+    eq, ekv = shape.lsa_q_heads * dh, shape.lsa_kv_heads * dh
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_lsa(C.byref(shape), _dev(hs, dt, T * L * d_in, "hs"), T,
+                        _dev(wq, dt, eq * d_in, "wq"), _dev(wk, dt, ekv * d_in, "wk"), _dev(wv, dt, ekv * d_in, "wv"),
+                        _dev(wo, dt, eq * eq, "wo"), _dev(out, dt, T * eq, "out"), wsp, wsb, _stream(stream)))
+
+
+def ca_kv_append(shape: Shape, mem_new, tok_off, wk, wv, kc, vc, ca_len, P_cap, dev_status=None, stream=None):
+    dt = _TORCH_DTYPE[shape.dtype]
+    T, d_mem = mem_new.shape
+    B = ca_len.shape[0]
+    ekv = shape.n_kv_heads * shape.head_dim
+    cache = B * ekv * P_cap
+    _check(_lib.moa_ca_kv_append(C.byref(shape), _dev(mem_new, dt, T * d_mem, "mem_new"), T, d_mem,
+                                 _dev(tok_off, torch.int32, B + 1, "tok_off"), B,
+                                 _dev(wk, dt, ekv * d_mem, "wk"), _dev(wv, dt, ekv * d_mem, "wv"),
+                                 _dev(kc, dt, cache, "kc"), _dev(vc, dt, cache, "vc"),
+                                 _dev(ca_len, torch.int32, B, "ca_len"), P_cap,
+                                 _dev(dev_status, torch.int32, 1, "dev_status"), _stream(stream)))
+
+
+def cross_attn_draft(shape: Shape, xq, wq, wo, kc, vc, ca_len, P_cap, out, ws, dev_status=None, stream=None):
+    dt = _TORCH_DTYPE[shape.dtype]
+    B, Mq, d = xq.shape
+    if d != shape.d_model:
+        raise ValueError("xq: last dimension must be d_model")
+    e, ekv = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    cache = B * ekv * P_cap
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_cross_attn_draft(C.byref(shape), _dev(xq, dt, B * Mq * d, "xq"), B, Mq,
+                                     _dev(wq, dt, e * d, "wq"), _dev(wo, dt, d * e, "wo"),
+                                     _dev(kc, dt, cache, "kc"), _dev(vc, dt, cache, "vc"),
+                                     _dev(ca_len, torch.int32, B, "ca_len"), P_cap, _dev(out, dt, B * Mq * d, "out"),
+                                     _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
+
+
+def tree_verify_attn(shape: Shape, x, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask, out, k_tree, v_tree,
+                     ws, dev_status=None, stream=None):
+    dt = _TORCH_DTYPE[shape.dtype]
+    B, M, d = x.shape
+    if d != shape.d_model:
+        raise ValueError("x: last dimension must be d_model")
+    e, ekv = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    cache = B * ekv * P_cap
+    W = (M + 63) // 64
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_tree_verify_attn(C.byref(shape), _dev(x, dt, B * M * d, "x"), B, M,
+                                     _dev(wq, dt, e * d, "wq"), _dev(wk, dt, ekv * d, "wk"), _dev(wv, dt, ekv * d, "wv"),
+                                     _dev(wo, dt, d * e, "wo"),
+                                     _dev(kcache, dt, cache, "kcache"), _dev(vcache, dt, cache, "vcache"),
+                                     _dev(prefix_len, torch.int32, B, "prefix_len"), P_cap,
+                                     _dev(mask, torch.int64, B * M * W, "mask"), _dev(out, dt, B * M * d, "out"),
+                                     _dev(k_tree, dt, B * ekv * M, "k_tree"), _dev(v_tree, dt, B * ekv * M, "v_tree"),
+                                     _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
+
+
+def _ptr_array(tensors, dtype, numel, name):
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        p = _dev(t, dtype, numel, f"{name}[{i}]")
+        arr[i] = None if p is None else p.value
+    return arr
+
+
+def draft_step(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len,
+               ca_P_cap, ca_xq, ca_out, v_x, v_w, v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, P_cap,
+               tok, tgt, path, n_path, bonus, ws, dev_status=None, stream=None):
+    """One pass of the whole path.  lsa_w = dict(wq, wk, wv, wo); ca_w = dict(wq, wo, wk, wv);
+    v_w = list (one per verified layer) of dict(wq, wk, wv, wo); v_* = lists of per-layer tensors."""
+    dt, i32 = _TORCH_DTYPE[shape.dtype], torch.int32
+    B, M = parent.shape
+    Mq = ca_xq.shape[1]
+    T = lsa_hs.shape[0]
+    W = (M + 63) // 64
+    L, d_in, dh, d = shape.n_layers, shape.d_lsa_in, shape.head_dim, shape.d_model
+    eq, ekvl = shape.lsa_q_heads * dh, shape.lsa_kv_heads * dh
+    e, ekv = shape.n_q_heads * dh, shape.n_kv_heads * dh
+    n = len(v_x)
+    if not all(len(v) == n for v in (v_w, v_kcache, v_vcache, v_out, v_ktree, v_vtree)):
+        raise ValueError("per-layer lists must have the same length")
+    a = _StepArgs()
+    a.shape = C.pointer(shape)
+    a.B, a.M, a.Mq = B, M, Mq
+    a.parent = _dev(parent, i32, B * M, "parent")
+    a.mask = _dev(mask, torch.int64, B * M * W, "mask")
+    a.depth = _dev(depth, i32, B * M, "depth")
+    a.lsa_hs = _dev(lsa_hs, dt, T * L * d_in, "lsa_hs")
+    a.T_lsa = T
+    a.lsa_wq = _dev(lsa_w["wq"], dt, eq * d_in, "lsa wq")
+    a.lsa_wk = _dev(lsa_w["wk"], dt, ekvl * d_in, "lsa wk")
+    a.lsa_wv = _dev(lsa_w["wv"], dt, ekvl * d_in, "lsa wv")
+    a.lsa_wo = _dev(lsa_w["wo"], dt, eq * eq, "lsa wo")
+    a.lsa_out = _dev(lsa_out, dt, T * eq, "lsa_out")
+    a.tok_off = _dev(tok_off, i32, B + 1, "tok_off")
+    a.ca_wk = _dev(ca_w["wk"], dt, ekv * eq, "ca wk")
+    a.ca_wv = _dev(ca_w["wv"], dt, ekv * eq, "ca wv")
+    a.ca_k = _dev(ca_k, dt, B * ekv * ca_P_cap, "ca_k")
+    a.ca_v = _dev(ca_v, dt, B * ekv * ca_P_cap, "ca_v")
+    a.ca_len = _dev(ca_len, i32, B, "ca_len")
+    a.ca_P_cap = ca_P_cap
+    a.ca_xq = _dev(ca_xq, dt, B * Mq * d, "ca_xq")
+    a.ca_wq = _dev(ca_w["wq"], dt, e * d, "ca wq")
+    a.ca_wo = _dev(ca_w["wo"], dt, d * e, "ca wo")
+    a.ca_out = _dev(ca_out, dt, B * Mq * d, "ca_out")
+    a.n_verify_layers = n
+    keep = [
+        _ptr_array(v_x, dt, B * M * d, "v_x"),
+        _ptr_array([w["wq"] for w in v_w], dt, e * d, "v wq"), _ptr_array([w["wk"] for w in v_w], dt, ekv * d, "v wk"),
+        _ptr_array([w["wv"] for w in v_w], dt, ekv * d, "v wv"), _ptr_array([w["wo"] for w in v_w], dt, d * e, "v wo"),
+        _ptr_array(v_kcache, dt, B * ekv * P_cap, "v_kcache"), _ptr_array(v_vcache, dt, B * ekv * P_cap, "v_vcache"),
+        _ptr_array(v_out, dt, B * M * d, "v_out"), _ptr_array(v_ktree, dt, B * ekv * M, "v_ktree"),
+        _ptr_array(v_vtree, dt, B * ekv * M, "v_vtree"),
+    ]
+    (a.v_x_host, a.v_wq_host, a.v_wk_host, a.v_wv_host, a.v_wo_host, a.v_kcache_host, a.v_vcache_host, a.v_out_host,
+     a.v_ktree_host, a.v_vtree_host) = [C.cast(k, C.POINTER(C.c_void_p)) for k in keep]
+    a.prefix_len = _dev(prefix_len, i32, B, "prefix_len")
+    a.P_cap = P_cap
+    a.tok = _dev(tok, i32, B * M, "tok")
+    a.tgt = _dev(tgt, i32, B * M, "tgt")
+    a.path = _dev(path, i32, B * M, "path")
+    a.n_path = _dev(n_path, i32, B, "n_path")
+    a.bonus = _dev(bonus, i32, B, "bonus")
+    a.dev_status = _dev(dev_status, i32, 1, "dev_status")
+    a.ws, a.ws_bytes = _ws(ws)
+    a.stream = _stream(stream)
+    _check(_lib.moa_draft_step(C.byref(a)))

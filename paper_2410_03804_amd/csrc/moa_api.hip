@@ -1,0 +1,443 @@
+// C ABI of libmoa: argument checks on the host, workspace carving, kernel launches on the
+// caller's stream.  No device allocation, no host synchronisation.
+#include "../../include/moa.h"
+#include "moa_common.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+
+using namespace moa;
+
+namespace {
+
+thread_local char g_err[320] = "";
+
+int32_t fail(int32_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int32_t hip_fail(hipError_t e, const char *where)
+{
+    return fail(MOA_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
+}
+
+// While a whole step is being validated no launch may happen: moa_draft_step runs every stage
+// once with g_dry set (checks only), then for real.
+thread_local bool g_dry = false;
+
+#define MOA_TRY_HIP(expr, where)                              \
+    do {                                                      \
+        if (!g_dry) {                                         \
+            hipError_t e_ = (expr);                           \
+            if (e_ != hipSuccess) return hip_fail(e_, where); \
+        }                                                     \
+    } while (0)
+
+size_t esize(int dtype) { return dtype == MOA_BF16 ? 2 : 4; }
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+int32_t check_shape(const moa_shape_t *s, bool need_lsa)
+{
+    if (!s) return fail(MOA_ERR_NULL, "shape is NULL");
+    if (s->dtype != MOA_F32 && s->dtype != MOA_BF16) return fail(MOA_ERR_DTYPE, "dtype %d", s->dtype);
+    if (s->head_dim < 1 || s->head_dim > 256) return fail(MOA_ERR_SHAPE, "head_dim %d outside [1,256]", s->head_dim);
+    if (need_lsa) {
+        if (s->n_layers < 1 || s->d_lsa_in < 1 || s->lsa_q_heads < 1 || s->lsa_kv_heads < 1 ||
+            s->lsa_q_heads % s->lsa_kv_heads)
+            return fail(MOA_ERR_SHAPE, "LSA dims L=%d d_in=%d H_l=%d Hkv_l=%d", s->n_layers, s->d_lsa_in,
+                        s->lsa_q_heads, s->lsa_kv_heads);
+    } else {
+        if (s->d_model < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->n_q_heads % s->n_kv_heads)
+            return fail(MOA_ERR_SHAPE, "dims d=%d H=%d Hkv=%d", s->d_model, s->n_q_heads, s->n_kv_heads);
+    }
+    return MOA_OK;
+}
+
+StoreSpec row_store(void *dst, int64_t ld)
+{
+    StoreSpec st = {};
+    st.mode = StoreSpec::ROW;
+    st.dst = dst;
+    st.ld = ld;
+    st.dh = 1;
+    return st;
+}
+
+StoreSpec heads_store(void *dst, int heads, int dh, int cap, int rows_per_seq)
+{
+    StoreSpec st = {};
+    st.mode = StoreSpec::HEADS;
+    st.dst = dst;
+    st.heads = heads;
+    st.dh = dh;
+    st.cap = cap;
+    st.rows_per_seq = rows_per_seq;
+    return st;
+}
+
+constexpr int64_t LSA_CHUNK = 256;   // tokens projected per pass (bounds the Q/K/V scratch)
+
+size_t lsa_ws_bytes(const moa_shape_t *s, int64_t T)
+{
+    const int64_t tc = T < LSA_CHUNK ? T : LSA_CHUNK;
+    const size_t eq = (size_t)s->lsa_q_heads * s->head_dim, ekv = (size_t)s->lsa_kv_heads * s->head_dim;
+    return align256((size_t)tc * s->n_layers * (eq + 2 * ekv) * esize(s->dtype)) + align256((size_t)tc * eq * esize(s->dtype));
+}
+
+size_t attn_ws_bytes(const moa_shape_t *s, int B, int Mq, int P_cap)
+{
+    const size_t e = (size_t)s->n_q_heads * s->head_dim;
+    return 2 * align256((size_t)B * Mq * e * esize(s->dtype)) +
+           align256(attn_workspace_bytes(s->dtype, B, Mq, s->n_q_heads, s->n_kv_heads, s->head_dim, P_cap));
+}
+
+int32_t check_ws(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return MOA_OK;
+    if (!ws) return fail(MOA_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
+    if (((uintptr_t)ws) & 255) return fail(MOA_ERR_WORKSPACE, "workspace not 256-byte aligned");
+    if (have < need) return fail(MOA_ERR_WORKSPACE, "workspace %zu bytes, %zu needed", have, need);
+    return MOA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *moa_status_str(int32_t status)
+{
+    switch (status) {
+    case MOA_OK: return "MOA_OK";
+    case MOA_ERR_NULL: return "MOA_ERR_NULL";
+    case MOA_ERR_SHAPE: return "MOA_ERR_SHAPE";
+    case MOA_ERR_TREE: return "MOA_ERR_TREE";
+    case MOA_ERR_RANGE: return "MOA_ERR_RANGE";
+    case MOA_ERR_DTYPE: return "MOA_ERR_DTYPE";
+    case MOA_ERR_WORKSPACE: return "MOA_ERR_WORKSPACE";
+    case MOA_ERR_HIP: return "MOA_ERR_HIP";
+    default: return "MOA_ERR_UNKNOWN";
+    }
+}
+
+const char *moa_last_error(void) { return g_err; }
+
+int32_t moa_workspace_bytes(const moa_shape_t *shape, int32_t B, int32_t P_cap, int32_t M, int64_t T_lsa,
+                            size_t *bytes_host)
+{
+    if (!bytes_host) return fail(MOA_ERR_NULL, "bytes_host is NULL");
+    int32_t rc = check_shape(shape, false);
+    if (rc) return rc;
+    if (B < 1 || M < 1 || P_cap < 0 || T_lsa < 0) return fail(MOA_ERR_SHAPE, "B=%d M=%d P_cap=%d T_lsa=%lld", B, M, P_cap, (long long)T_lsa);
+    size_t need = attn_ws_bytes(shape, B, M, P_cap);
+    if (T_lsa > 0) {
+        rc = check_shape(shape, true);
+        if (rc) return rc;
+        const size_t l = lsa_ws_bytes(shape, T_lsa);
+        if (l > need) need = l;
+    }
+    *bytes_host = need;
+    return MOA_OK;
+}
+
+int32_t moa_tree_build(const int32_t *parent, int32_t B, int32_t M, uint64_t *mask, int32_t *depth,
+                       int32_t *dev_status, void *stream)
+{
+    if (!parent || !mask || !depth) return fail(MOA_ERR_NULL, "tree_build: NULL pointer");
+    if (B < 1 || M < 1 || M > MOA_MAX_TREE) return fail(MOA_ERR_SHAPE, "tree_build: B=%d M=%d (M <= %d)", B, M, MOA_MAX_TREE);
+    MOA_TRY_HIP(launch_tree_build(parent, B, M, mask, depth, dev_status, (hipStream_t)stream), "tree_build");
+    return MOA_OK;
+}
+
+int32_t moa_tree_accept(const int32_t *parent, const int32_t *tok, const int32_t *tgt, int32_t B, int32_t M,
+                        int32_t *path, int32_t *n_path, int32_t *bonus, void *stream)
+{
+    if (!parent || !tok || !tgt || !path || !n_path || !bonus) return fail(MOA_ERR_NULL, "tree_accept: NULL pointer");
+    if (B < 1 || M < 1 || M > MOA_MAX_TREE) return fail(MOA_ERR_SHAPE, "tree_accept: B=%d M=%d (M <= %d)", B, M, MOA_MAX_TREE);
+    MOA_TRY_HIP(launch_tree_accept(parent, tok, tgt, B, M, path, n_path, bonus, (hipStream_t)stream), "tree_accept");
+    return MOA_OK;
+}
+
+int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk,
+                const void *wv, const void *wo, void *out, void *ws, size_t ws_bytes, void *stream)
+{
+    int32_t rc = check_shape(shape, true);
+    if (rc) return rc;
+    if (!hs || !out) return fail(MOA_ERR_NULL, "lsa: hs / out is NULL");
+    if (T < 0) return fail(MOA_ERR_SHAPE, "lsa: T=%lld", (long long)T);
+    const int L = shape->n_layers, dh = shape->head_dim, d_in = shape->d_lsa_in;
+    const int eq = shape->lsa_q_heads * dh, ekv = shape->lsa_kv_heads * dh, dt = shape->dtype;
+    if ((!wq && eq != d_in) || (!wk && ekv != d_in) || (!wv && ekv != d_in))
+        return fail(MOA_ERR_SHAPE, "lsa: NULL weight needs matching widths (d_in=%d, H_l*dh=%d, Hkv_l*dh=%d)", d_in, eq, ekv);
+    if (lsa_attn_lds_bytes(dt, L, dh) > 150 * 1024)
+        return fail(MOA_ERR_SHAPE, "lsa: L=%d x head_dim=%d does not fit the LDS-resident score tile", L, dh);
+    if (T == 0) return MOA_OK;
+    rc = check_ws(ws, ws_bytes, lsa_ws_bytes(shape, T));
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t es = esize(dt);
+    const int64_t tc_max = T < LSA_CHUNK ? T : LSA_CHUNK;
+    const int wide = eq + 2 * ekv;
+    char *qkv = (char *)ws;
+    char *abar = qkv + align256((size_t)tc_max * L * wide * es);
+
+    for (int64_t t0 = 0; t0 < T; t0 += LSA_CHUNK) {
+        const int64_t tc = (T - t0) < LSA_CHUNK ? (T - t0) : LSA_CHUNK;
+        const char *x = (const char *)hs + (size_t)t0 * L * d_in * es;
+        LinArgs la = {};
+        la.X = x;
+        la.R = tc * L;
+        la.K = d_in;
+        la.ldx = d_in;
+        LsaAttnArgs aa = {};
+        aa.dtype = dt;
+        auto add = [&](const void *w, int n, int col, const void **ptr, int64_t *ldp) {
+            if (w) {
+                la.seg[la.nseg].W = w;
+                la.seg[la.nseg].N = n;
+                la.seg[la.nseg].st = row_store(qkv + (size_t)col * es, wide);
+                ++la.nseg;
+                *ptr = qkv + (size_t)col * es;
+                *ldp = wide;
+            } else {
+                *ptr = x;
+                *ldp = d_in;
+            }
+        };
+        add(wq, eq, 0, &aa.q, &aa.ldq);
+        add(wk, ekv, eq, &aa.k, &aa.ldk);
+        add(wv, ekv, eq + ekv, &aa.v, &aa.ldv);
+        if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "lsa: projection");
+        aa.T = tc;
+        aa.L = L;
+        aa.Hq = shape->lsa_q_heads;
+        aa.Hkv = shape->lsa_kv_heads;
+        aa.dh = dh;
+        char *orow = (char *)out + (size_t)t0 * eq * es;
+        aa.abar = wo ? (void *)abar : (void *)orow;
+        MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
+        if (wo) {
+            LinArgs lo = {};
+            lo.X = abar;
+            lo.R = tc;
+            lo.K = eq;
+            lo.ldx = eq;
+            lo.nseg = 1;
+            lo.seg[0].W = wo;
+            lo.seg[0].N = eq;
+            lo.seg[0].st = row_store(orow, eq);
+            MOA_TRY_HIP(launch_linear(dt, lo, st), "lsa: output projection");
+        }
+    }
+    return MOA_OK;
+}
+
+int32_t moa_ca_kv_append(const moa_shape_t *shape, const void *mem_new, int64_t T, int32_t d_mem,
+                         const int32_t *tok_off, int32_t B, const void *wk, const void *wv, void *kc, void *vc,
+                         int32_t *ca_len, int32_t P_cap, int32_t *dev_status, void *stream)
+{
+    int32_t rc = check_shape(shape, false);
+    if (rc) return rc;
+    if (!mem_new || !tok_off || !kc || !vc || !ca_len) return fail(MOA_ERR_NULL, "ca_kv_append: NULL pointer");
+    if (B < 1 || T < 0 || d_mem < 1 || P_cap < 1) return fail(MOA_ERR_SHAPE, "ca_kv_append: B=%d T=%lld d_mem=%d P_cap=%d", B, (long long)T, d_mem, P_cap);
+    const int dh = shape->head_dim, ekv = shape->n_kv_heads * dh, dt = shape->dtype;
+    if ((!wk || !wv) && ekv != d_mem) return fail(MOA_ERR_SHAPE, "ca_kv_append: NULL weight needs d_mem == Hkv*dh");
+    hipStream_t st = (hipStream_t)stream;
+    StoreSpec sp = {};
+    sp.mode = StoreSpec::APPEND;
+    sp.heads = shape->n_kv_heads;
+    sp.dh = dh;
+    sp.cap = P_cap;
+    sp.B = B;
+    sp.row_base = ca_len;
+    sp.tok_off = tok_off;
+    sp.dev_status = dev_status;
+    if (T > 0) {
+        LinArgs la = {};
+        la.X = mem_new;
+        la.R = T;
+        la.K = d_mem;
+        la.ldx = d_mem;
+        const void *w[2] = {wk, wv};
+        void *dst[2] = {kc, vc};
+        for (int i = 0; i < 2; ++i) {
+            sp.dst = dst[i];
+            if (w[i]) {
+                la.seg[la.nseg].W = w[i];
+                la.seg[la.nseg].N = ekv;
+                la.seg[la.nseg].st = sp;
+                ++la.nseg;
+            } else {
+                MOA_TRY_HIP(launch_scatter_copy(dt, mem_new, T, ekv, d_mem, sp, st), "ca_kv_append: copy");
+            }
+        }
+        if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "ca_kv_append: projection");
+    }
+    MOA_TRY_HIP(launch_append_lengths(tok_off, B, ca_len, P_cap, dev_status, st), "ca_kv_append: lengths");
+    return MOA_OK;
+}
+
+// shared by cross-attention (mask == NULL) and tree verification
+static int32_t attention_layer(const char *who, const moa_shape_t *shape, const void *x, int32_t B, int32_t M,
+                               const void *wq, const void *wk, const void *wv, const void *wo,
+                               const void *kcache, const void *vcache, const int32_t *len, int32_t P_cap,
+                               const uint64_t *mask, void *out, void *k_tree, void *v_tree, int32_t *dev_status,
+                               void *ws, size_t ws_bytes, hipStream_t st)
+{
+    const int dh = shape->head_dim, H = shape->n_q_heads, Hkv = shape->n_kv_heads, d = shape->d_model;
+    const int e = H * dh, ekv = Hkv * dh, dt = shape->dtype;
+    const size_t es = esize(dt);
+    const int64_t R = (int64_t)B * M;
+    if (!wq && e != d) return fail(MOA_ERR_SHAPE, "%s: NULL wq needs d == H*dh", who);
+    if (mask && ((!wk || !wv) && ekv != d)) return fail(MOA_ERR_SHAPE, "%s: NULL wk/wv needs d == Hkv*dh", who);
+    int32_t rc = check_ws(ws, ws_bytes, attn_ws_bytes(shape, B, M, P_cap));
+    if (rc) return rc;
+    char *qbuf = (char *)ws;
+    char *abuf = qbuf + align256((size_t)R * e * es);
+    char *part = abuf + align256((size_t)R * e * es);
+    const size_t part_bytes = ws_bytes - (size_t)(part - (char *)ws);
+
+    LinArgs la = {};
+    la.X = x;
+    la.R = R;
+    la.K = d;
+    la.ldx = d;
+    const void *q = x;
+    if (wq) {
+        la.seg[la.nseg].W = wq;
+        la.seg[la.nseg].N = e;
+        la.seg[la.nseg].st = row_store(qbuf, e);
+        ++la.nseg;
+        q = qbuf;
+    }
+    if (mask) {
+        const void *w[2] = {wk, wv};
+        void *dst[2] = {k_tree, v_tree};
+        for (int i = 0; i < 2; ++i) {
+            const StoreSpec sp = heads_store(dst[i], Hkv, dh, M, M);
+            if (w[i]) {
+                la.seg[la.nseg].W = w[i];
+                la.seg[la.nseg].N = ekv;
+                la.seg[la.nseg].st = sp;
+                ++la.nseg;
+            } else {
+                MOA_TRY_HIP(launch_scatter_copy(dt, x, R, ekv, d, sp, st), who);
+            }
+        }
+    }
+    if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), who);
+
+    AttnArgs aa = {};
+    aa.dtype = dt;
+    aa.q = q;
+    aa.kcache = kcache;
+    aa.vcache = vcache;
+    aa.ktree = mask ? k_tree : nullptr;
+    aa.vtree = mask ? v_tree : nullptr;
+    aa.len = len;
+    aa.mask = mask;
+    aa.out = wo ? (void *)abuf : out;
+    aa.B = B;
+    aa.Mq = M;
+    aa.Mt = mask ? M : 0;
+    aa.H = H;
+    aa.Hkv = Hkv;
+    aa.dh = dh;
+    aa.P_cap = P_cap;
+    aa.empty_is_error = mask ? 0 : 1;
+    aa.dev_status = dev_status;
+    aa.ws = part;
+    aa.ws_bytes = part_bytes;
+    MOA_TRY_HIP(launch_attn(aa, st), who);
+
+    if (wo) {
+        LinArgs lo = {};
+        lo.X = abuf;
+        lo.R = R;
+        lo.K = e;
+        lo.ldx = e;
+        lo.nseg = 1;
+        lo.seg[0].W = wo;
+        lo.seg[0].N = d;
+        lo.seg[0].st = row_store(out, d);
+        MOA_TRY_HIP(launch_linear(dt, lo, st), who);
+    }
+    return MOA_OK;
+}
+
+int32_t moa_cross_attn_draft(const moa_shape_t *shape, const void *xq, int32_t B, int32_t Mq, const void *wq,
+                             const void *wo, const void *kc, const void *vc, const int32_t *ca_len, int32_t P_cap,
+                             void *out, int32_t *dev_status, void *ws, size_t ws_bytes, void *stream)
+{
+    int32_t rc = check_shape(shape, false);
+    if (rc) return rc;
+    if (!xq || !kc || !vc || !ca_len || !out) return fail(MOA_ERR_NULL, "cross_attn_draft: NULL pointer");
+    if (B < 1 || Mq < 1 || P_cap < 1) return fail(MOA_ERR_SHAPE, "cross_attn_draft: B=%d Mq=%d P_cap=%d", B, Mq, P_cap);
+    if (!wo && shape->n_q_heads * shape->head_dim != shape->d_model)
+        return fail(MOA_ERR_SHAPE, "cross_attn_draft: NULL wo needs d == H*dh");
+    return attention_layer("cross_attn_draft", shape, xq, B, Mq, wq, nullptr, nullptr, wo, kc, vc, ca_len, P_cap,
+                           nullptr, out, nullptr, nullptr, dev_status, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B, int32_t M, const void *wq,
+                             const void *wk, const void *wv, const void *wo, const void *kcache,
+                             const void *vcache, const int32_t *prefix_len, int32_t P_cap, const uint64_t *mask,
+                             void *out, void *k_tree, void *v_tree, int32_t *dev_status, void *ws, size_t ws_bytes,
+                             void *stream)
+{
+    int32_t rc = check_shape(shape, false);
+    if (rc) return rc;
+    if (!x || !prefix_len || !mask || !out || !k_tree || !v_tree) return fail(MOA_ERR_NULL, "tree_verify_attn: NULL pointer");
+    if (P_cap > 0 && (!kcache || !vcache)) return fail(MOA_ERR_NULL, "tree_verify_attn: cache is NULL with P_cap > 0");
+    if (B < 1 || M < 1 || M > MOA_MAX_TREE || P_cap < 0) return fail(MOA_ERR_SHAPE, "tree_verify_attn: B=%d M=%d P_cap=%d (M <= %d)", B, M, P_cap, MOA_MAX_TREE);
+    if (!wo && shape->n_q_heads * shape->head_dim != shape->d_model)
+        return fail(MOA_ERR_SHAPE, "tree_verify_attn: NULL wo needs d == H*dh");
+    return attention_layer("tree_verify_attn", shape, x, B, M, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask,
+                           out, k_tree, v_tree, dev_status, ws, ws_bytes, (hipStream_t)stream);
+}
+
+static int32_t draft_step_stages(const moa_step_args_t *a)
+{
+    int32_t rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, a->stream);
+    if (rc) return rc;
+    rc = moa_lsa(a->shape, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, a->ws,
+                 a->ws_bytes, a->stream);
+    if (rc) return rc;
+    const int d_mem = a->shape->lsa_q_heads * a->shape->head_dim;
+    rc = moa_ca_kv_append(a->shape, a->lsa_out, a->T_lsa, d_mem, a->tok_off, a->B, a->ca_wk, a->ca_wv, a->ca_k,
+                          a->ca_v, a->ca_len, a->ca_P_cap, a->dev_status, a->stream);
+    if (rc) return rc;
+    rc = moa_cross_attn_draft(a->shape, a->ca_xq, a->B, a->Mq, a->ca_wq, a->ca_wo, a->ca_k, a->ca_v, a->ca_len,
+                              a->ca_P_cap, a->ca_out, a->dev_status, a->ws, a->ws_bytes, a->stream);
+    if (rc) return rc;
+    for (int l = 0; l < a->n_verify_layers; ++l) {
+        rc = moa_tree_verify_attn(a->shape, a->v_x_host[l], a->B, a->M, a->v_wq_host[l], a->v_wk_host[l],
+                                  a->v_wv_host[l], a->v_wo_host[l], a->v_kcache_host[l], a->v_vcache_host[l],
+                                  a->prefix_len, a->P_cap, a->mask, a->v_out_host[l], a->v_ktree_host[l],
+                                  a->v_vtree_host[l], a->dev_status, a->ws, a->ws_bytes, a->stream);
+        if (rc) return rc;
+    }
+    return moa_tree_accept(a->parent, a->tok, a->tgt, a->B, a->M, a->path, a->n_path, a->bonus, a->stream);
+}
+
+int32_t moa_draft_step(const moa_step_args_t *a)
+{
+    if (!a) return fail(MOA_ERR_NULL, "draft_step: args is NULL");
+    if (!a->shape) return fail(MOA_ERR_NULL, "draft_step: shape is NULL");
+    if (a->n_verify_layers < 0) return fail(MOA_ERR_SHAPE, "draft_step: n_verify_layers=%d", a->n_verify_layers);
+    if (a->n_verify_layers > 0 &&
+        (!a->v_x_host || !a->v_wq_host || !a->v_wk_host || !a->v_wv_host || !a->v_wo_host || !a->v_kcache_host ||
+         !a->v_vcache_host || !a->v_out_host || !a->v_ktree_host || !a->v_vtree_host))
+        return fail(MOA_ERR_NULL, "draft_step: a per-layer pointer array is NULL");
+    g_dry = true;                       // every stage's host checks first: a bad argument launches nothing
+    int32_t rc = draft_step_stages(a);
+    g_dry = false;
+    if (rc) return rc;
+    return draft_step_stages(a);
+}
+
+}  // extern "C"

@@ -1,0 +1,413 @@
+// Attention core shared by the draft model's cross-attention (no mask, cache rows only) and the
+// tree-masked verification attention (cache rows, then the tree rows filtered by the ancestor
+// bitset).  Input Q is already projected; the output is the concatenated heads before W_o.
+//
+//   k_attn_generic   any dtype / head_dim <= 256: one wavefront per (sequence, query, head),
+//                    64 keys per step, exact online softmax with wavefront shuffles.
+//   k_attn_mfma      bf16, head_dim 64 / 128: split-KV.  A workgroup owns one (sequence, KV head),
+//                    one slice of the key range and up to 128*NBLK query rows (the GQA group's heads
+//                    times the tree tokens are folded into the row dimension, so K/V are read once for
+//                    all of them).  K/V tiles of 32 keys are staged in LDS by 16-byte loads; scores are
+//                    computed transposed (S^T = K Q^T) so that a lane owns one query column and the
+//                    softmax max/sum need a single cross-lane exchange; P^T feeds the second MFMA
+//                    straight from registers and V is transposed on its way into LDS.
+//   k_attn_merge     combines the per-slice (max, sum, accumulator) triples.
+#include "moa_common.h"
+#include "../../include/moa.h"
+
+#include <math.h>
+
+namespace moa {
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__device__ __forceinline__ int clamp_len(int len, int cap, int32_t *dev_status)
+{
+    if (len < 0 || len > cap) {
+        if (dev_status) atomicOr(dev_status, MOA_DEV_BAD_LENGTH);
+        len = len < 0 ? 0 : cap;
+    }
+    return len;
+}
+
+// ------------------------------------------------------------------ generic
+template <typename T>
+__global__ __launch_bounds__(64) void k_attn_generic(AttnArgs a)
+{
+    __shared__ float qs[256];
+    const int lane = threadIdx.x;
+    const int h = blockIdx.x % a.H;
+    const int m = (blockIdx.x / a.H) % a.Mq;
+    const int b = blockIdx.x / (a.H * a.Mq);
+    const int g = h / (a.H / a.Hkv);
+    const int dh = a.dh, W = (a.Mq + 63) >> 6;
+    const float scale = 1.0f / sqrtf((float)dh);
+
+    const T *q = (const T *)a.q + (((int64_t)b * a.Mq + m) * a.H + h) * dh;
+    for (int c = lane; c < dh; c += 64) qs[c] = ld<T>(q + c);
+    __syncthreads();
+
+    const int len = clamp_len(a.len[b], a.P_cap, lane == 0 ? a.dev_status : nullptr);
+    const int Mt = a.mask ? a.Mt : 0;
+    const int total = len + Mt;
+    const T *kc = (const T *)a.kcache + ((int64_t)b * a.Hkv + g) * (int64_t)a.P_cap * dh;
+    const T *vc = (const T *)a.vcache + ((int64_t)b * a.Hkv + g) * (int64_t)a.P_cap * dh;
+    const T *kt = (const T *)a.ktree + ((int64_t)b * a.Hkv + g) * (int64_t)a.Mt * dh;
+    const T *vt = (const T *)a.vtree + ((int64_t)b * a.Hkv + g) * (int64_t)a.Mt * dh;
+    const uint64_t *mrow = a.mask ? a.mask + ((int64_t)b * a.Mq + m) * W : nullptr;
+
+    float mrun = -INFINITY, lrun = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int base = 0; base < total; base += 64) {
+        const int kidx = base + lane;
+        float s = -INFINITY;
+        if (kidx < total) {
+            const T *krow = nullptr;
+            if (kidx < len) {
+                krow = kc + (int64_t)kidx * dh;
+            } else {
+                const int j = kidx - len;
+                if ((mrow[j >> 6] >> (j & 63)) & 1) krow = kt + (int64_t)j * dh;
+            }
+            if (krow) {
+                float d = 0.f;
+                for (int c = 0; c < dh; ++c) d = fmaf(qs[c], ld<T>(krow + c), d);
+                s = d * scale;
+            }
+        }
+        const float mnew = fmaxf(mrun, wave_max(s));
+        if (mnew == -INFINITY) continue;   // nothing visible yet (same decision in every lane)
+        const float p = (s == -INFINITY) ? 0.f : expf(s - mnew);
+        const float corr = expf(mrun - mnew);
+        lrun = lrun * corr + wave_sum(p);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] *= corr;
+        const int nk = min(64, total - base);
+        for (int kk = 0; kk < nk; ++kk) {
+            const float pk = __shfl(p, kk);
+            if (pk == 0.f) continue;
+            const int ki = base + kk;
+            const T *vrow = ki < len ? vc + (int64_t)ki * dh : vt + (int64_t)(ki - len) * dh;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (lane + 64 * c < dh) acc[c] = fmaf(pk, ld<T>(vrow + lane + 64 * c), acc[c]);
+        }
+        mrun = mnew;
+    }
+    T *o = (T *)a.out + (((int64_t)b * a.Mq + m) * a.H + h) * dh;
+    const float inv = lrun > 0.f ? 1.0f / lrun : 0.f;
+    for (int c = 0; c < 4; ++c)
+        if (lane + 64 * c < dh) st<T>(o + lane + 64 * c, acc[c] * inv);
+    if (lrun == 0.f && a.empty_is_error && lane == 0 && a.dev_status) atomicOr(a.dev_status, MOA_DEV_EMPTY_KEYS);
+}
+
+// ------------------------------------------------------------------ MFMA split-KV
+struct SplitGeom {
+    int nsplit;     // key-range slices
+    int rowtiles;   // workgroups along the G*Mq rows of one (sequence, KV head)
+    int rows_pad;   // rowtiles * rows per workgroup
+};
+
+constexpr int KT = 32;        // keys per tile
+constexpr int VLD = KT + 8;   // padded row of the transposed V tile
+
+// position of key k (0..31) inside a transposed V row: bits 2 and 3 swapped, so that the eight
+// keys one lane contributes to a 16-deep MFMA step are contiguous
+__device__ __forceinline__ int vpos(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
+
+template <int DH, int NBLK>
+__global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, float *__restrict__ part_o,
+                                                   float *__restrict__ part_ml)
+{
+    constexpr int KLD = DH + 8;           // padded K row (bf16)
+    constexpr int NKS = DH / 16;          // MFMA steps along head_dim
+    constexpr int NDB = DH / 32;          // 32-wide blocks of head_dim in the output
+    constexpr int CPK = DH / 8;           // 16-byte chunks per key row
+    constexpr int NLD = (KT * CPK) / 256; // chunks per thread per tile (1 for DH 64, 2 for DH 128)
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[KT][KLD];
+    __shared__ __attribute__((aligned(16))) bf16_t Vt[DH][VLD];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int split = blockIdx.x, rowtile = blockIdx.y;
+    const int bg = blockIdx.z, b = bg / a.Hkv, g = bg % a.Hkv;
+    const int G = a.H / a.Hkv, RG = G * a.Mq, W = (a.Mq + 63) >> 6;
+    const float sc = 1.4426950408889634f / sqrtf((float)DH);   // scores are kept in the log2 domain
+
+    const int len = clamp_len(a.len[b], a.P_cap, tid == 0 ? a.dev_status : nullptr);
+    const int nt = (len + KT - 1) / KT;
+    const int per = (nt + geo.nsplit - 1) / geo.nsplit;
+    const int t0 = min(split * per, nt), t1 = min(t0 + per, nt);
+    const int Mt = a.mask ? a.Mt : 0;
+    const int ntree = (split == geo.nsplit - 1) ? (Mt + KT - 1) / KT : 0;
+    const int ntiles = (t1 - t0) + ntree;
+
+    const bf16_t *kc = (const bf16_t *)a.kcache + (int64_t)bg * a.P_cap * DH;
+    const bf16_t *vc = (const bf16_t *)a.vcache + (int64_t)bg * a.P_cap * DH;
+    const bf16_t *ktp = (const bf16_t *)a.ktree + (int64_t)bg * a.Mt * DH;
+    const bf16_t *vtp = (const bf16_t *)a.vtree + (int64_t)bg * a.Mt * DH;
+
+    // query fragments (B operand of S^T = K Q^T): lane = query column l32, 8 head_dim values
+    const int rowbase = rowtile * (128 * NBLK) + wave * (32 * NBLK);
+    bf16x8 qf[NBLK][NKS];
+    int mrow_of[NBLK];
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) {
+        int rho = rowbase + 32 * blk + l32;
+        if (rho > RG - 1) rho = RG - 1;
+        const int m = rho / G, hh = rho - m * G;
+        mrow_of[blk] = m;
+        const bf16_t *qrow = (const bf16_t *)a.q + (((int64_t)b * a.Mq + m) * a.H + g * G + hh) * DH;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qf[blk][ks] = *(const bf16x8 *)(qrow + 16 * ks + 8 * half);
+    }
+
+    f32x16 acc[NBLK][NDB];
+    float mrun[NBLK], lrun[NBLK];
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) {
+        mrun[blk] = -INFINITY;
+        lrun[blk] = 0.f;
+#pragma unroll
+        for (int d = 0; d < NDB; ++d)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[blk][d][e] = 0.f;
+    }
+
+    // tile i of this workgroup: cache tile t0+i, or tree tile i-(t1-t0)
+    uint4 kreg[NLD], vreg[NLD];
+    auto fetch = [&](int i) {
+        const bool tree = i >= (t1 - t0);
+        const int base = tree ? (i - (t1 - t0)) * KT : (t0 + i) * KT;
+        const int limit = tree ? Mt : len;
+        const bf16_t *ksrc = tree ? ktp : kc;
+        const bf16_t *vsrc = tree ? vtp : vc;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int c = tid + 256 * j;
+            int kr = base + c / CPK;                       // K: consecutive lanes walk along one key row
+            if (kr > limit - 1) kr = limit - 1;            // rows past the end repeat the last valid row
+            kreg[j] = *(const uint4 *)(ksrc + (int64_t)kr * DH + (c % CPK) * 8);
+            int vr = base + (c & 31);                      // V: consecutive lanes take consecutive keys
+            if (vr > limit - 1) vr = limit - 1;
+            vreg[j] = *(const uint4 *)(vsrc + (int64_t)vr * DH + (c >> 5) * 8);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int c = tid + 256 * j;
+            *(uint4 *)&Ks[c / CPK][(c % CPK) * 8] = kreg[j];
+            const int key = vpos(c & 31), d0 = (c >> 5) * 8;
+            const uint32_t w[4] = {vreg[j].x, vreg[j].y, vreg[j].z, vreg[j].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Vt[d0 + e][key] = (bf16_t)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    };
+
+    if (ntiles > 0) fetch(0);
+    for (int i = 0; i < ntiles; ++i) {
+        __syncthreads();          // every wave is done reading the previous tile
+        stage();
+        __syncthreads();
+        if (i + 1 < ntiles) fetch(i + 1);
+
+        const bool tree = i >= (t1 - t0);
+        const int base = tree ? (i - (t1 - t0)) * KT : (t0 + i) * KT;
+        const int limit = tree ? Mt : len;
+
+        // S^T tile: keys x queries
+        f32x16 s[NBLK];
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[blk][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const bf16x8 kf = *(const bf16x8 *)&Ks[l32][16 * ks + 8 * half];
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk)
+                s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[blk][ks], s[blk], 0, 0, 0);
+        }
+
+        bf16x8 pf[NBLK][2];
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) {
+            // visibility of the 32 keys of this tile for this lane's query
+            uint32_t vis = 0xffffffffu;
+            if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.Mq + mrow_of[blk]) * W + (base >> 6)] >> (base & 63));
+            const int nvalid = limit - base;               // >= 1
+            if (nvalid < 32) vis &= (1u << nvalid) - 1u;
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = 8 * (v >> 2) + 4 * half + (v & 3);
+                const float x = ((vis >> key) & 1u) ? s[blk][v] * sc : -INFINITY;
+                s[blk][v] = x;
+                tmax = fmaxf(tmax, x);
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            const float mnew = fmaxf(mrun[blk], tmax);
+            const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+            const float corr = exp2f(mrun[blk] - msafe);
+            float psum = 0.f;
+            float p[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { p[v] = exp2f(s[blk][v] - msafe); psum += p[v]; }
+            psum += __shfl_xor(psum, 32);
+            lrun[blk] = lrun[blk] * corr + psum;
+            mrun[blk] = mnew;
+#pragma unroll
+            for (int d = 0; d < NDB; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[blk][d][e] *= corr;
+#pragma unroll
+            for (int st2 = 0; st2 < 2; ++st2)
+#pragma unroll
+                for (int t = 0; t < 8; ++t) pf[blk][st2][t] = (__bf16)p[8 * st2 + t];
+        }
+
+        // O^T += V^T P^T
+#pragma unroll
+        for (int d = 0; d < NDB; ++d)
+#pragma unroll
+            for (int st2 = 0; st2 < 2; ++st2) {
+                const bf16x8 vf = *(const bf16x8 *)&Vt[32 * d + l32][16 * st2 + 8 * half];
+#pragma unroll
+                for (int blk = 0; blk < NBLK; ++blk)
+                    acc[blk][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[blk][st2], acc[blk][d], 0, 0, 0);
+            }
+    }
+
+    // partial results of this slice: un-normalised accumulator, running max (log2 domain), running sum
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) {
+        const int rho = rowbase + 32 * blk + l32;
+        if (rho >= RG) continue;
+        const int64_t prow = ((int64_t)bg * geo.nsplit + split) * geo.rows_pad + rho;
+        if (half == 0) {
+            part_ml[prow * 2 + 0] = mrun[blk];
+            part_ml[prow * 2 + 1] = lrun[blk];
+        }
+#pragma unroll
+        for (int d = 0; d < NDB; ++d)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                f32x4 v = {acc[blk][d][4 * q4], acc[blk][d][4 * q4 + 1], acc[blk][d][4 * q4 + 2], acc[blk][d][4 * q4 + 3]};
+                *(f32x4 *)(part_o + prow * DH + 32 * d + 8 * q4 + 4 * half) = v;
+            }
+    }
+}
+
+// one wavefront per (sequence, query, head)
+template <int DH>
+__global__ __launch_bounds__(64) void k_attn_merge(AttnArgs a, SplitGeom geo, const float *__restrict__ part_o,
+                                                   const float *__restrict__ part_ml)
+{
+    constexpr int CPL = DH / 64;   // components per lane
+    const int lane = threadIdx.x;
+    const int h = blockIdx.x % a.H;
+    const int m = (blockIdx.x / a.H) % a.Mq;
+    const int b = blockIdx.x / (a.H * a.Mq);
+    const int G = a.H / a.Hkv, g = h / G, rho = m * G + (h - g * G);
+    const int64_t bg = (int64_t)b * a.Hkv + g;
+
+    float mstar = -INFINITY;
+    for (int s = 0; s < geo.nsplit; ++s)
+        mstar = fmaxf(mstar, part_ml[((bg * geo.nsplit + s) * geo.rows_pad + rho) * 2]);
+    float lsum = 0.f, o[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) o[c] = 0.f;
+    if (mstar != -INFINITY) {
+        for (int s = 0; s < geo.nsplit; ++s) {
+            const int64_t prow = (bg * geo.nsplit + s) * geo.rows_pad + rho;
+            const float ms = part_ml[prow * 2];
+            if (ms == -INFINITY) continue;
+            const float w = exp2f(ms - mstar);
+            lsum += w * part_ml[prow * 2 + 1];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) o[c] += w * part_o[prow * DH + lane * CPL + c];
+        }
+    }
+    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+    bf16_t *dst = (bf16_t *)a.out + (((int64_t)b * a.Mq + m) * a.H + h) * DH + lane * CPL;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) dst[c] = f2bf(o[c] * inv);
+    if (lsum == 0.f && a.empty_is_error && lane == 0 && a.dev_status) atomicOr(a.dev_status, MOA_DEV_EMPTY_KEYS);
+}
+
+// ------------------------------------------------------------------ host side
+static bool mfma_ok(int dtype, int dh, const AttnArgs *a)
+{
+    if (dtype != DT_BF16 || (dh != 64 && dh != 128)) return false;
+    if (!a) return true;
+    auto al = [](const void *p) { return (((uintptr_t)p) & 15) == 0; };
+    return al(a->q) && al(a->kcache) && al(a->vcache) && al(a->ktree) && al(a->vtree) && al(a->out);
+}
+
+static SplitGeom split_geometry(int B, int Mq, int H, int Hkv, int P_cap)
+{
+    const int RG = (H / Hkv) * Mq;
+    const int nblk = RG > 128 ? 2 : 1;
+    SplitGeom g;
+    g.rowtiles = (RG + 128 * nblk - 1) / (128 * nblk);
+    g.rows_pad = g.rowtiles * 128 * nblk;
+    const int tiles_cap = (P_cap + KT - 1) / KT;
+    int want = 512 / (B * Hkv * g.rowtiles);        // about two workgroups per compute unit
+    int most = tiles_cap / 4;                        // at least four tiles per slice
+    if (want > most) want = most;
+    if (want > 64) want = 64;
+    if (want < 1) want = 1;
+    g.nsplit = want;
+    return g;
+}
+
+size_t attn_workspace_bytes(int dtype, int B, int Mq, int H, int Hkv, int dh, int P_cap)
+{
+    if (!mfma_ok(dtype, dh, nullptr)) return 0;
+    const SplitGeom g = split_geometry(B, Mq, H, Hkv, P_cap);
+    const size_t rows = (size_t)B * Hkv * g.nsplit * g.rows_pad;
+    return rows * (size_t)(dh + 2) * sizeof(float) + 256;
+}
+
+hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
+{
+    const int nblocks = a.B * a.Mq * a.H;
+    if (mfma_ok(a.dtype, a.dh, &a) && a.ws &&
+        a.ws_bytes >= attn_workspace_bytes(a.dtype, a.B, a.Mq, a.H, a.Hkv, a.dh, a.P_cap)) {
+        const SplitGeom g = split_geometry(a.B, a.Mq, a.H, a.Hkv, a.P_cap);
+        const size_t rows = (size_t)a.B * a.Hkv * g.nsplit * g.rows_pad;
+        float *part_o = (float *)a.ws;
+        float *part_ml = part_o + rows * a.dh;
+        const dim3 grid(g.nsplit, g.rowtiles, a.B * a.Hkv);
+        const bool two = (a.H / a.Hkv) * a.Mq > 128;
+        if (a.dh == 128) {
+            if (two) hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml);
+            else hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml);
+        } else {
+            if (two) hipLaunchKernelGGL((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml);
+            else hipLaunchKernelGGL((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (a.dh == 128) hipLaunchKernelGGL(k_attn_merge<128>, dim3(nblocks), dim3(64), 0, stream, a, g, part_o, part_ml);
+        else hipLaunchKernelGGL(k_attn_merge<64>, dim3(nblocks), dim3(64), 0, stream, a, g, part_o, part_ml);
+        return hipGetLastError();
+    }
+    if (a.dh > 256) return hipErrorInvalidValue;
+    if (a.dtype == DT_BF16) hipLaunchKernelGGL(k_attn_generic<bf16_t>, dim3(nblocks), dim3(64), 0, stream, a);
+    else hipLaunchKernelGGL(k_attn_generic<float>, dim3(nblocks), dim3(64), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace moa

@@ -1,0 +1,136 @@
+// Internal declarations shared by the libmoa translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moa {
+
+typedef uint16_t bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float ld(const T *p);
+template <> __device__ __forceinline__ float ld<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t *p) { return bf2f(*p); }
+template <typename T> __device__ __forceinline__ void st(T *p, float v);
+template <> __device__ __forceinline__ void st<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st<bf16_t>(bf16_t *p, float v) { *p = f2bf(v); }
+
+// Where a projection's output element (row r, feature n) goes.
+//  ROW    : dst[r*ld + n]
+//  HEADS  : r = b*rows_per_seq + m, n = g*dh + c -> dst[((b*heads + g)*cap + m)*dh + c]
+//           (the tree rows' K/V slabs)
+//  APPEND : r belongs to the sequence b with tok_off[b] <= r < tok_off[b+1]; position
+//           pos = row_base[b] + r - tok_off[b]; dropped when pos >= cap (cache append)
+struct StoreSpec {
+    enum { ROW = 0, HEADS = 1, APPEND = 2 };
+    int mode;
+    void *dst;
+    int64_t ld;
+    int heads, dh, cap, rows_per_seq, B;
+    const int32_t *row_base;  // APPEND: ca_len
+    const int32_t *tok_off;   // APPEND
+    int32_t *dev_status;
+};
+
+// element offset of (r, n) or -1 when the element is dropped
+__device__ __forceinline__ int64_t store_offset(const StoreSpec &s, int64_t r, int n)
+{
+    if (s.mode == StoreSpec::ROW) return r * s.ld + n;
+    const int g = n / s.dh, c = n - g * s.dh;
+    if (s.mode == StoreSpec::HEADS) {
+        const int64_t b = r / s.rows_per_seq;
+        const int m = (int)(r - b * s.rows_per_seq);
+        return ((b * s.heads + g) * (int64_t)s.cap + m) * s.dh + c;
+    }
+    int b = -1;
+    for (int i = 0; i < s.B; ++i) {
+        if (r >= s.tok_off[i] && r < s.tok_off[i + 1]) { b = i; break; }
+    }
+    if (b < 0) return -1;
+    int base = s.row_base[b];
+    if (base < 0) base = 0;
+    const int64_t pos = (int64_t)base + (r - s.tok_off[b]);
+    if (pos >= s.cap) return -1;
+    return (((int64_t)b * s.heads + g) * (int64_t)s.cap + pos) * s.dh + c;
+}
+
+struct LinSeg {
+    const void *W;  // [N, K] row-major
+    int N;
+    StoreSpec st;
+};
+
+struct LinArgs {
+    const void *X;  // [R, K] with row stride ldx
+    int64_t R;
+    int K;
+    int64_t ldx;
+    int nseg;
+    LinSeg seg[3];
+};
+
+// Y_s = X W_s^T for up to three weight matrices that share X (one launch on the fast path).
+hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream);
+
+// dst(store spec) = X, element by element (NULL-weight projections that still change layout)
+hipError_t launch_scatter_copy(int dtype, const void *X, int64_t R, int N, int64_t ldx, const StoreSpec &st,
+                               hipStream_t stream);
+
+// ---- tree
+hipError_t launch_tree_build(const int32_t *parent, int B, int M, uint64_t *mask, int32_t *depth,
+                             int32_t *dev_status, hipStream_t stream);
+hipError_t launch_tree_accept(const int32_t *parent, const int32_t *tok, const int32_t *tgt, int B, int M,
+                              int32_t *path, int32_t *n_path, int32_t *bonus, hipStream_t stream);
+hipError_t launch_append_lengths(const int32_t *tok_off, int B, int32_t *ca_len, int cap, int32_t *dev_status,
+                                 hipStream_t stream);
+
+// ---- attention core (cross-attention when mask == nullptr / Mt == 0)
+struct AttnArgs {
+    int dtype;
+    const void *q;        // [B*Mq, H*dh] row-major
+    const void *kcache;   // [B, Hkv, P_cap, dh]
+    const void *vcache;
+    const void *ktree;    // [B, Hkv, Mt, dh] or nullptr
+    const void *vtree;
+    const int32_t *len;   // [B] visible cache rows
+    const uint64_t *mask; // [B, Mq, W] or nullptr
+    void *out;            // [B*Mq, H*dh]
+    int B, Mq, Mt, H, Hkv, dh, P_cap;
+    int empty_is_error;   // cross-attention: len == 0 -> flag + zeros
+    int32_t *dev_status;
+    void *ws;
+    size_t ws_bytes;
+};
+size_t attn_workspace_bytes(int dtype, int B, int Mq, int H, int Hkv, int dh, int P_cap);
+hipError_t launch_attn(const AttnArgs &a, hipStream_t stream);
+
+// ---- LSA attention over the layer axis with the mean folded in:
+// abar[t, h*dh + c] = sum_j (1/L sum_i softmax_i(S)[i][j]) V[t, j, g, c]
+struct LsaAttnArgs {
+    int dtype;
+    const void *q, *k, *v;   // row (t*L + l): q + row*ldq + h*dh ; k, v + row*ldk + g*dh
+    int64_t ldq, ldk, ldv;
+    int64_t T;
+    int L, Hq, Hkv, dh;
+    void *abar;              // [T, Hq*dh]
+};
+size_t lsa_attn_lds_bytes(int dtype, int L, int dh);
+hipError_t launch_lsa_attn(const LsaAttnArgs &a, hipStream_t stream);
+
+}  // namespace moa

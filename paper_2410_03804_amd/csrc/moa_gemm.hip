@@ -1,0 +1,346 @@
+// Projections Y = X W^T (W row-major [N, K]) for the Q/K/V/O projections of LSA, CA and
+// tree verification.  Three kernels:
+//   k_linear_generic     any dtype / shape, fp32 FMA, LDS-tiled 64x64 (fp32 path and odd shapes)
+//   k_linear_skinny_bf16 <=64 rows per tile: weight streaming, HBM-bound.  Operands go straight
+//                        from global memory into MFMA 16x16x32 fragments (both are K-contiguous,
+//                        which is exactly the fragment layout), the four waves of a workgroup
+//                        split K and reduce through LDS.
+//   k_linear_tiled_bf16  128x128x64 LDS-tiled MFMA 32x32x16 GEMM for many rows (LSA's T*L rows,
+//                        batched configs).
+// In both MFMA kernels the weight tile is the A operand and the activation tile the B operand,
+// so a lane ends up holding consecutive output features of one row (vector stores).
+#include "moa_common.h"
+
+namespace moa {
+
+// ------------------------------------------------------------------ generic
+template <typename T>
+__global__ __launch_bounds__(256) void k_linear_generic(const T *__restrict__ X, int64_t R, int K, int64_t ldx,
+                                                        const T *__restrict__ W, int N, StoreSpec stp)
+{
+    __shared__ float Xs[16][65];
+    __shared__ float Ws[16][65];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int64_t r0 = (int64_t)blockIdx.y * 64;
+    const int n0 = blockIdx.x * 64;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + 256 * i, rr = idx >> 4, kk = idx & 15;
+            const int64_t r = r0 + rr;
+            const int n = n0 + rr, k = k0 + kk;
+            Xs[kk][rr] = (r < R && k < K) ? ld<T>(X + r * ldx + k) : 0.f;
+            Ws[kk][rr] = (n < N && k < K) ? ld<T>(W + (int64_t)n * K + k) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = Xs[kk][ty * 4 + i]; b[i] = Ws[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    T *dst = (T *)stp.dst;
+    for (int i = 0; i < 4; ++i) {
+        const int64_t r = r0 + ty * 4 + i;
+        if (r >= R) continue;
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n >= N) continue;
+            const int64_t off = store_offset(stp, r, n);
+            if (off >= 0) st<T>(dst + off, acc[i][j]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ skinny bf16 (weight streaming)
+struct SkinnyArgs {
+    LinArgs a;
+    int tile_begin[4];  // first feature tile of each segment, tile_begin[nseg] = total
+};
+
+template <int NB>  // 16*NB output features per workgroup
+__global__ __launch_bounds__(256) void k_linear_skinny_bf16(SkinnyArgs sa)
+{
+    constexpr int FT = 16 * NB;
+    constexpr int RS = FT + 4;  // padded row of the reduction buffer (floats)
+    __shared__ float red[4][64][RS];
+
+    const LinArgs &a = sa.a;
+    int s = 0;
+    while (s + 1 < a.nseg && (int)blockIdx.x >= sa.tile_begin[s + 1]) ++s;
+    const int n0 = ((int)blockIdx.x - sa.tile_begin[s]) * FT;
+    const int64_t r0 = (int64_t)blockIdx.y * 64;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, li = lane & 15, kg = lane >> 4;
+    const int K = a.K, kper = K >> 2;
+    const bf16_t *W = (const bf16_t *)a.seg[s].W;
+    const bf16_t *X = (const bf16_t *)a.X;
+
+    const bf16_t *wp[NB];
+    const bf16_t *xp[4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) wp[nb] = W + (int64_t)(n0 + 16 * nb + li) * K + wave * kper + 8 * kg;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+        int64_t r = r0 + 16 * rb + li;
+        if (r > a.R - 1) r = a.R - 1;   // rows past the end repeat the last row; never stored
+        xp[rb] = X + r * a.ldx + wave * kper + 8 * kg;
+    }
+
+    f32x4 acc[NB][4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) acc[nb][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    bf16x8 wf[2][NB], xf[2][4];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) wf[0][nb] = *(const bf16x8 *)(wp[nb]);
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) xf[0][rb] = *(const bf16x8 *)(xp[rb]);
+
+    const int nsteps = kper >> 5;   // 32 k per MFMA
+    for (int step = 0; step < nsteps; step += 2) {
+        // stage 1 loads (step+1) while stage 0 computes, then the other way round
+        if (step + 1 < nsteps) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) wf[1][nb] = *(const bf16x8 *)(wp[nb] + (step + 1) * 32);
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) xf[1][rb] = *(const bf16x8 *)(xp[rb] + (step + 1) * 32);
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+                acc[nb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[0][nb], xf[0][rb], acc[nb][rb], 0, 0, 0);
+        if (step + 1 < nsteps) {
+            if (step + 2 < nsteps) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) wf[0][nb] = *(const bf16x8 *)(wp[nb] + (step + 2) * 32);
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) xf[0][rb] = *(const bf16x8 *)(xp[rb] + (step + 2) * 32);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+                    acc[nb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[1][nb], xf[1][rb], acc[nb][rb], 0, 0, 0);
+        }
+    }
+
+    // lane holds features 4*kg..4*kg+3 of feature block nb for row 16*rb + li
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+            *(f32x4 *)&red[wave][16 * rb + li][16 * nb + 4 * kg] = acc[nb][rb];
+    __syncthreads();
+
+    bf16_t *dst = (bf16_t *)a.seg[s].st.dst;
+    constexpr int CPR = FT / 8;  // 8-feature chunks per row
+    for (int c = threadIdx.x; c < 64 * CPR; c += 256) {
+        const int row = c / CPR, fc = c % CPR;
+        const int64_t r = r0 + row;
+        if (r >= a.R) continue;
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            v[e] = (red[0][row][8 * fc + e] + red[1][row][8 * fc + e]) + (red[2][row][8 * fc + e] + red[3][row][8 * fc + e]);
+        const int64_t off = store_offset(a.seg[s].st, r, n0 + 8 * fc);
+        if (off < 0) continue;
+        uint4 pk;
+        pk.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+        pk.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+        pk.z = (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
+        pk.w = (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
+        *(uint4 *)(dst + off) = pk;
+    }
+}
+
+// ------------------------------------------------------------------ tiled bf16 (many rows)
+struct TiledArgs {
+    LinArgs a;
+    int tile_begin[4];
+};
+
+__global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
+{
+    constexpr int BM = 128, BN = 128, BK = 64, LDT = BK + 8;  // LDT: padded LDS row (bf16)
+    __shared__ __attribute__((aligned(16))) bf16_t Ws[2][BN][LDT];
+    __shared__ __attribute__((aligned(16))) bf16_t Xs[2][BM][LDT];
+
+    const LinArgs &a = ta.a;
+    int s = 0;
+    while (s + 1 < a.nseg && (int)blockIdx.x >= ta.tile_begin[s + 1]) ++s;
+    const int n0 = ((int)blockIdx.x - ta.tile_begin[s]) * BN;
+    const int64_t r0 = (int64_t)blockIdx.y * BM;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wf0 = (wave & 1) * 64;   // feature offset of this wave inside the tile
+    const int wr0 = (wave >> 1) * 64;  // row offset
+    const int K = a.K;
+    const bf16_t *W = (const bf16_t *)a.seg[s].W;
+    const bf16_t *X = (const bf16_t *)a.X;
+
+    // global -> register staging: 4 x 16 B per operand per thread; 8 lanes cover 128 B of a row
+    const bf16_t *wsrc[4], *xsrc[4];
+    int srow[4], scol[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid + 256 * i;
+        srow[i] = c >> 3;
+        scol[i] = (c & 7) * 8;
+        wsrc[i] = W + (int64_t)(n0 + srow[i]) * K + scol[i];
+        int64_t r = r0 + srow[i];
+        if (r > a.R - 1) r = a.R - 1;
+        xsrc[i] = X + r * a.ldx + scol[i];
+    }
+    uint4 wreg[4], xreg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { wreg[i] = *(const uint4 *)wsrc[i]; xreg[i] = *(const uint4 *)xsrc[i]; }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int nk = K / BK;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *(uint4 *)&Ws[buf][srow[i]][scol[i]] = wreg[i];
+            *(uint4 *)&Xs[buf][srow[i]][scol[i]] = xreg[i];
+        }
+        __syncthreads();   // tile kt visible; everyone is past the reads of tile kt-2 (same buffer)
+        if (kt + 1 < nk) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                wreg[i] = *(const uint4 *)(wsrc[i] + (int64_t)(kt + 1) * BK);
+                xreg[i] = *(const uint4 *)(xsrc[i] + (int64_t)(kt + 1) * BK);
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 af[2], bfr[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                af[i] = *(const bf16x8 *)&Ws[buf][wf0 + 32 * i + l32][16 * ks + 8 * half];
+                bfr[i] = *(const bf16x8 *)&Xs[buf][wr0 + 32 * i + l32][16 * ks + 8 * half];
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // acc[i][j][v]: feature = wf0 + 32 i + 8 (v/4) + 4 half + v%4, row = wr0 + 32 j + l32
+    bf16_t *dst = (bf16_t *)a.seg[s].st.dst;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t r = r0 + wr0 + 32 * j + l32;
+        if (r >= a.R) continue;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wf0 + 32 * i + 8 * q + 4 * half;
+                const int64_t off = store_offset(a.seg[s].st, r, n);
+                if (off < 0) continue;
+                uint2 pk;
+                pk.x = (uint32_t)f2bf(acc[i][j][4 * q + 0]) | ((uint32_t)f2bf(acc[i][j][4 * q + 1]) << 16);
+                pk.y = (uint32_t)f2bf(acc[i][j][4 * q + 2]) | ((uint32_t)f2bf(acc[i][j][4 * q + 3]) << 16);
+                *(uint2 *)(dst + off) = pk;
+            }
+    }
+}
+
+// ------------------------------------------------------------------ dispatch
+static bool aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
+
+hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
+{
+    if (a.R <= 0) return hipSuccess;
+    bool fast = dtype == DT_BF16 && a.K % 128 == 0 && a.ldx % 8 == 0 && aligned16(a.X);
+    for (int s = 0; s < a.nseg && fast; ++s) {
+        const StoreSpec &st = a.seg[s].st;
+        fast = a.seg[s].N % 32 == 0 && aligned16(a.seg[s].W) && aligned16(st.dst) &&
+               (st.mode == StoreSpec::ROW ? st.ld % 8 == 0 : st.dh % 8 == 0);
+    }
+    if (fast) {
+        bool all128 = true;
+        for (int s = 0; s < a.nseg; ++s) all128 = all128 && a.seg[s].N % 128 == 0;
+        if (a.R > 128 && all128) {
+            TiledArgs ta;
+            ta.a = a;
+            int t = 0;
+            for (int s = 0; s < a.nseg; ++s) { ta.tile_begin[s] = t; t += a.seg[s].N / 128; }
+            ta.tile_begin[a.nseg] = t;
+            dim3 grid(t, (unsigned)((a.R + 127) / 128));
+            hipLaunchKernelGGL(k_linear_tiled_bf16, grid, dim3(256), 0, stream, ta);
+            return hipGetLastError();
+        }
+        SkinnyArgs sa;
+        sa.a = a;
+        int t = 0;
+        for (int s = 0; s < a.nseg; ++s) { sa.tile_begin[s] = t; t += a.seg[s].N / 32; }
+        sa.tile_begin[a.nseg] = t;
+        dim3 grid(t, (unsigned)((a.R + 63) / 64));
+        hipLaunchKernelGGL(k_linear_skinny_bf16<2>, grid, dim3(256), 0, stream, sa);
+        return hipGetLastError();
+    }
+    for (int s = 0; s < a.nseg; ++s) {
+        dim3 grid((a.seg[s].N + 63) / 64, (unsigned)((a.R + 63) / 64));
+        if (dtype == DT_BF16)
+            hipLaunchKernelGGL(k_linear_generic<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)a.X, a.R, a.K,
+                               a.ldx, (const bf16_t *)a.seg[s].W, a.seg[s].N, a.seg[s].st);
+        else
+            hipLaunchKernelGGL(k_linear_generic<float>, grid, dim3(256), 0, stream, (const float *)a.X, a.R, a.K,
+                               a.ldx, (const float *)a.seg[s].W, a.seg[s].N, a.seg[s].st);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace moa
+
+// ------------------------------------------------------------------ identity "projection"
+// A NULL weight means the input is already projected; rows still have to reach the layout the
+// store spec describes (e.g. [B, Hkv, M, dh] slabs).
+namespace moa {
+
+template <typename T>
+__global__ void k_scatter_copy(const T *__restrict__ X, int64_t R, int N, int64_t ldx, StoreSpec stp)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= R * N) return;
+    const int64_t r = idx / N;
+    const int n = (int)(idx - r * N);
+    const int64_t off = store_offset(stp, r, n);
+    if (off >= 0) ((T *)stp.dst)[off] = X[r * ldx + n];
+}
+
+hipError_t launch_scatter_copy(int dtype, const void *X, int64_t R, int N, int64_t ldx, const StoreSpec &st,
+                               hipStream_t stream)
+{
+    if (R <= 0) return hipSuccess;
+    const int64_t total = R * N;
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(k_scatter_copy<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)X, R, N, ldx, st);
+    else
+        hipLaunchKernelGGL(k_scatter_copy<float>, grid, dim3(256), 0, stream, (const float *)X, R, N, ldx, st);
+    return hipGetLastError();
+}
+
+}  // namespace moa

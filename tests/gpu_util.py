@@ -1,0 +1,61 @@
+"""Helpers for the GPU parity tests: move seeded numpy inputs to the device, run the library through
+its binding, bring results back as fp64.  Holds none of the method's arithmetic."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import moa_inputs as mi
+import paper_2410_03804_amd as moa
+
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+MDT = {"f32": moa.F32, "bf16": moa.BF16}
+# the benchmark spec bounds (max-abs against the fp64 oracle)
+ABS_TOL = {"f32": 1e-4, "bf16": 2e-2}
+# tighter relative bound (max-abs / rms of the oracle), derived in the design doc from the arithmetic
+REL_TOL = {"f32": 5e-5, "bf16": 3e-2}
+
+
+def dev(x, dtype=None):
+    """numpy -> cuda tensor.  Float arrays hold values already representable in `dtype`."""
+    if x is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype is not None:
+        t = t.to(TDT[dtype])
+    return t.cuda()
+
+
+def host(t):
+    return t.detach().to("cpu", torch.float64).numpy() if t.is_floating_point() else t.cpu().numpy()
+
+
+def shape_of(cfg: mi.Config):
+    return moa.Shape(cfg.L, cfg.d, cfg.H, cfg.Hkv, cfg.dh, cfg.d_lsa_in, cfg.lsa_heads, cfg.Hkv, MDT[cfg.dtype])
+
+
+def workspace(shape, B, P_cap, M, T):
+    n = moa.workspace_bytes(shape, B, P_cap, M, T)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
+
+
+def status_word():
+    return torch.zeros(1, dtype=torch.int32, device="cuda")
+
+
+def mask_u64(mask_t):
+    return mask_t.cpu().numpy().view(np.uint64)
+
+
+def check_close(got, want, dtype, what):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
+    err = float(np.max(np.abs(got - want))) if got.size else 0.0
+    rms = float(np.sqrt(np.mean(want ** 2))) if got.size else 1.0
+    rel = err / max(rms, 1e-30)
+    print(f"[parity] {what}: max-abs {err:.3e}  rms(oracle) {rms:.3e}  max-abs/rms {rel:.3e}", flush=True)
+    assert err <= ABS_TOL[dtype], f"{what}: max-abs {err:.3e} > {ABS_TOL[dtype]}"
+    assert rel <= REL_TOL[dtype], f"{what}: max-abs/rms {rel:.3e} > {REL_TOL[dtype]}"
+    return err, rel
