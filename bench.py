@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the Mixture-of-Attentions draft step on one MI355X.
+
+A "step" is one pass of the whole hot path through moa_draft_step: tree mask -> LSA of the B*M newly
+verified tokens -> CA memory append -> CA of the M tree tokens -> n tree-verify attention layers ->
+accept walk.  Inputs are synthetic (seeded, Llama-3-8B shape by default) and resident in HBM before the
+timed region; several independent buffer sets are rotated so that a step's weights and caches are not
+served from the 256 MiB Infinity Cache.
+
+Prints ONE JSON line: metric = draft-tree tokens/s (B*M / step time), plus
+  "roofline"     : the kernel with the largest share of the step, timed with hipEvents recorded by the
+                   library around that kernel's launches inside the timed region;
+  "cpu_baseline" : the fp64 CPU oracle timed on the same workload on this machine's host cores;
+  "pieces"       : per launch site time, algorithmic bytes / flops and the roofline that bounds it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
+VEC_F32_PEAK_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C1", help="C0..C4 (moa_inputs.CONFIGS); C1 is the headline workload")
+    ap.add_argument("--verify-layers", type=int, default=1, help="tree-verify attention layers per step")
+    ap.add_argument("--sets", type=int, default=3, help="independent buffer sets rotated between steps")
+    ap.add_argument("--profile-steps", type=int, default=12, help="untimed steps with events around every kernel")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--d-lsa-in", type=int, default=0, help="override the LSA input width (default 2*E_kv)")
+    return ap.parse_args()
+
+
+def site_costs(cfg, n_layers):
+    """Algorithmic bytes and flops per launch site for one step: what the call must read and write once
+    (inputs, weights, caches, outputs) and 2*MACs of the contractions as defined."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    B, M, L, d, H, Hkv, dh = cfg.B, cfg.M, cfg.L, cfg.d, cfg.H, cfg.Hkv, cfg.dh
+    T = B * M
+    d_in, eq, ekv = cfg.d_lsa_in, cfg.lsa_heads * dh, cfg.Hkv * dh
+    E = H * dh
+    import moa_inputs as mi
+    plen = mi.prefix_lengths(cfg).astype(float)
+
+    def lin(R, K, N):
+        return dict(bytes=(R * K + N * K + R * N) * es, flops=2.0 * R * K * N)
+
+    c = {}
+    c["tree_build"] = dict(bytes=B * M * 4 + B * M * ((M + 63) // 64) * 8 + B * M * 4, flops=0.0)
+    c["lsa.qkv_proj"] = lin(T * L, d_in, eq + 2 * ekv)
+    c["lsa.layer_attn"] = dict(bytes=(T * L * (eq + 2 * ekv) + T * eq) * es,
+                               flops=2.0 * T * cfg.lsa_heads * L * L * dh + 2.0 * T * cfg.lsa_heads * L * dh)
+    c["lsa.o_proj"] = lin(T, eq, eq)
+    c["ca_append.kv_proj"] = lin(T, eq, 2 * ekv)
+    c["ca_append.lengths"] = dict(bytes=B * 12, flops=0.0)
+    c["ca.q_proj"] = lin(T, d, E)
+    cache_ca = 2.0 * Hkv * dh * es * float(plen.sum())
+    core_flops_ca = 4.0 * M * H * dh * float(plen.sum())
+    c["ca.core"] = dict(bytes=cache_ca + 2 * T * E * es, flops=core_flops_ca)
+    c["ca.o_proj"] = lin(T, E, d)
+    c["verify.qkv_proj"] = {k: v * n_layers for k, v in lin(T, d, E + 2 * ekv).items()}
+    cache_v = 2.0 * Hkv * dh * es * float(plen.sum()) + 2.0 * B * Hkv * M * dh * es
+    core_flops_v = 4.0 * M * H * dh * float((plen + M).sum())
+    c["verify.core"] = dict(bytes=(cache_v + 2 * T * E * es) * n_layers, flops=core_flops_v * n_layers)
+    c["verify.o_proj"] = {k: v * n_layers for k, v in lin(T, E, d).items()}
+    c["tree_accept"] = dict(bytes=B * M * 16 + B * 8, flops=0.0)
+    return c
+
+
+def bound_of(bytes_, flops, peak_tflops):
+    t_hbm = bytes_ / (HBM_PEAK_GBS * 1e9)
+    t_mfma = flops / (peak_tflops * 1e12)
+    return ("mfma", t_mfma) if t_mfma > t_hbm else ("hbm", t_hbm)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py measures the single-GPU draft step only: --gpus {args.gpus} is not supported "
+              "(no collectives or sharding are part of this build; run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import moa_inputs as mi
+    import paper_2410_03804_amd as moa
+    from paper_2410_03804_amd.workload import DeviceStep
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+
+    cfg = mi.CONFIGS[args.config]
+    if args.d_lsa_in:
+        cfg = mi.scaled(cfg, d_lsa_in=args.d_lsa_in)
+    K, Wm, P, NL = args.steps, args.warmup, args.profile_steps, args.verify_layers
+    nsets = max(1, args.sets)
+    total = Wm + P + K
+    slots = math.ceil(total / nsets) + 1
+
+    t_setup = time.perf_counter()
+    works = [mi.step_workload(cfg, NL, variant=i) for i in range(nsets)]
+    sets = []
+    ws = None
+    for w in works:
+        s = DeviceStep(w, n_len_slots=slots, ws=ws)
+        ws = s.ws
+        sets.append(s)
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+
+    counter = [0]
+
+    def one_step():
+        i = counter[0]
+        counter[0] += 1
+        sets[i % nsets].run(len_slot=i // nsets)
+
+    for _ in range(Wm):
+        one_step()
+    torch.cuda.synchronize()
+
+    # untimed pass with events around every kernel: where does a step's time go
+    moa.profile_enable(True)
+    for _ in range(P):
+        one_step()
+    torch.cuda.synchronize()
+    rows = moa.profile_collect()
+    moa.profile_enable(False)
+    per_kernel = {}
+    for site, kern, n, ms in rows:
+        per_kernel[kern] = per_kernel.get(kern, 0.0) + ms
+    dominant = max(per_kernel, key=per_kernel.get) if per_kernel else None
+
+    # timed region: exactly K steps, events only around the dominant kernel's launches
+    moa.profile_enable(True, only_kernel=dominant)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        one_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_rows = moa.profile_collect()
+    moa.profile_enable(False)
+
+    bad = sum(int(s.dev_status.item()) for s in sets)
+    if bad:
+        print(f"device status word non-zero ({bad}): the workload tripped a device-side check", file=sys.stderr)
+        sys.exit(1)
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    tokens = cfg.B * cfg.M
+    value = tokens / (ms_per_step * 1e-3)
+
+    costs = site_costs(cfg, NL)
+    peak_mm = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else VEC_F32_PEAK_TFLOPS
+    pieces = []
+    for site, kern, n, ms in sorted(rows, key=lambda r: -r[3]):
+        c = costs.get(site, dict(bytes=0.0, flops=0.0))
+        us = ms * 1e3 / P                       # per step, all launches of this site
+        bnd, t_min = bound_of(c["bytes"], c["flops"], peak_mm)
+        pieces.append(dict(site=site, kernel=kern, launches_per_step=n / P, us_per_step=round(us, 3),
+                           alg_MiB=round(c["bytes"] / 2 ** 20, 3), gflop=round(c["flops"] / 1e9, 3), bound=bnd,
+                           gbs=round(c["bytes"] / (us * 1e-6) / 1e9, 1) if us > 0 else None,
+                           tflops=round(c["flops"] / (us * 1e-6) / 1e12, 2) if us > 0 else None,
+                           frac_of_bound=round(t_min / (us * 1e-6), 4) if us > 0 else None))
+    kernel_us_sum = sum(p["us_per_step"] for p in pieces)
+
+    roofline = None
+    if dominant and dom_rows:
+        launches = sum(r[2] for r in dom_rows)
+        tot_ms = sum(r[3] for r in dom_rows)
+        avg_us = tot_ms * 1e3 / launches
+        sites = sorted({r[0] for r in dom_rows})
+        per_step_launches = launches / K
+        byt = sum(costs[s]["bytes"] for s in sites) / per_step_launches     # per launch, averaged over its sites
+        flo = sum(costs[s]["flops"] for s in sites) / per_step_launches
+        bnd, _ = bound_of(byt, flo, peak_mm)
+        if bnd == "hbm":
+            ach = byt / (avg_us * 1e-6) / 1e9
+            roofline = dict(bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                            frac=round(ach / HBM_PEAK_GBS, 4), traffic=None)
+        else:
+            ach = flo / (avg_us * 1e-6) / 1e12
+            roofline = dict(bound="mfma", achieved=round(ach, 2), peak=peak_mm, unit="TFLOP/s",
+                            frac=round(ach / peak_mm, 4), traffic=None)
+        roofline.update(kernel=dominant, sites=sites, avg_launch_us=round(avg_us, 3),
+                        launches_per_step=per_step_launches, alg_bytes_per_launch=int(byt),
+                        flops_per_launch=int(flo), share_of_kernel_time=round(per_kernel[dominant] / sum(per_kernel.values()), 4))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.step import run_step
+        import oracle as orc
+        orc.build()
+        tm = {}
+        c0 = time.perf_counter()
+        run_step(works[0], tm)
+        c1 = time.perf_counter()
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = dict(value=round(tokens / (c1 - c0), 3), unit="tokens/s", cores=cores, kind="oracle",
+                   sample=f"the whole {cfg.name} step once (all {tokens} tree tokens, {NL} verify layer(s)), fp64, "
+                          f"{c1 - c0:.2f} s",
+                   seconds=round(c1 - c0, 3), stage_seconds={k: round(v, 4) for k, v in tm.items()})
+
+    out = {
+        "metric": "draft-tree tokens/sec (draft step + verify attn) at Llama-3-8B shape; % HBM peak",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} prefix={cfg.P_min}..{cfg.P_max} tree M={cfg.M} depth={cfg.D} "
+                               f"L={cfg.L} d={cfg.d} H={cfg.H}/{cfg.Hkv} dh={cfg.dh} d_lsa_in={cfg.d_lsa_in}; "
+                               f"LSA on T=B*M={tokens} tokens, {NL} tree-verify layer(s)",
+                   "verify_layers": NL, "buffer_sets": nsets, "profile_steps": P},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "kernel_us_per_step": round(kernel_us_sum, 2), "setup_s": round(setup_s, 1), "pieces": pieces,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -285,3 +285,47 @@ def kv_cache(cfg: Config, which: int = 0, P_cap: int | None = None):
     P_cap = cfg.P_cap if P_cap is None else P_cap
     shape = (cfg.B, cfg.Hkv, P_cap, cfg.dh)
     return normal(rng, shape, cfg.dtype), normal(rng, shape, cfg.dtype)
+
+
+def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0):
+    """All inputs of one draft step as numpy arrays (values already rounded to cfg.dtype).
+
+    Per sequence, the M tokens verified in the previous cycle are new: LSA runs on T = B*M tokens,
+    the cross-attention memory holds P_b - M rows before the step and P_b rows after the append.
+    `variant` draws an independent set of the large tensors (weights, activations, caches) so a
+    benchmark can rotate buffer sets; trees, tokens and lengths stay the same."""
+    v = 50 * variant
+    B, M = cfg.B, cfg.M
+    parent = trees(cfg)
+    tok, tgt = tokens(cfg, parent)
+    plen = prefix_lengths(cfg)
+    if np.any(plen < M):
+        raise ValueError("prefix shorter than the tree")
+    T = B * M
+    rng_w = rng_for(cfg, S_WEIGHT, extra=1 + v)
+    Hl, dh, d_in = cfg.lsa_heads, cfg.dh, cfg.d_lsa_in
+    E = cfg.H * dh
+    lsa_w = dict(wq=weight(rng_w, Hl * dh, d_in, cfg.dtype), wk=weight(rng_w, cfg.E_kv, d_in, cfg.dtype),
+                 wv=weight(rng_w, cfg.E_kv, d_in, cfg.dtype), wo=weight(rng_w, cfg.d_lsa, Hl * dh, cfg.dtype))
+    ca_w = dict(wq=weight(rng_w, E, cfg.d, cfg.dtype), wo=weight(rng_w, cfg.d, E, cfg.dtype),
+                wk=weight(rng_w, cfg.E_kv, cfg.d_lsa, cfg.dtype), wv=weight(rng_w, cfg.E_kv, cfg.d_lsa, cfg.dtype))
+    lsa_hs = normal(rng_for(cfg, S_LSA, extra=v), (T, cfg.L, d_in), cfg.dtype, rms_norm=cfg.rms_norm)
+    ca_xq = normal(rng_for(cfg, S_CAQ, extra=v), (B, M, cfg.d), cfg.dtype, rms_norm=cfg.rms_norm)
+    ca_P_cap = cfg.P_max + 8
+    rng_c = rng_for(cfg, S_CACHE, extra=1000 + v)
+    ca_k = normal(rng_c, (B, cfg.Hkv, ca_P_cap, dh), cfg.dtype)
+    ca_v = normal(rng_c, (B, cfg.Hkv, ca_P_cap, dh), cfg.dtype)
+    layers = []
+    for l in range(n_verify_layers):
+        rl = rng_for(cfg, S_WEIGHT, extra=3 + l + v)
+        w = dict(wq=weight(rl, E, cfg.d, cfg.dtype), wk=weight(rl, cfg.E_kv, cfg.d, cfg.dtype),
+                 wv=weight(rl, cfg.E_kv, cfg.d, cfg.dtype), wo=weight(rl, cfg.d, E, cfg.dtype))
+        x = normal(rng_for(cfg, S_VERIFY, extra=l + v), (B, M, cfg.d), cfg.dtype, rms_norm=cfg.rms_norm)
+        rc = rng_for(cfg, S_CACHE, extra=l + v)
+        kc = normal(rc, (B, cfg.Hkv, cfg.P_cap, dh), cfg.dtype)
+        vc = normal(rc, (B, cfg.Hkv, cfg.P_cap, dh), cfg.dtype)
+        layers.append(dict(w=w, x=x, kcache=kc, vcache=vc))
+    return dict(cfg=cfg, parent=parent, tok=tok, tgt=tgt, prefix_len=plen, P_cap=cfg.P_cap,
+                lsa_w=lsa_w, lsa_hs=lsa_hs, tok_off=(np.arange(B + 1) * M).astype(np.int32),
+                ca_w=ca_w, ca_xq=ca_xq, ca_k=ca_k, ca_v=ca_v, ca_len0=(plen - M).astype(np.int32),
+                ca_P_cap=ca_P_cap, layers=layers)

@@ -60,7 +60,8 @@ class _StepArgs(C.Structure):
 
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
-            "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step"]
+            "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
+            "moa_profile_enable", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -76,8 +77,20 @@ _lib.moa_cross_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _v
 _lib.moa_tree_verify_attn.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
                                       _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moa_draft_step.argtypes = [C.POINTER(_StepArgs)]
-for _n in _SYMBOLS[2:]:
+for _n in _SYMBOLS[2:12]:
     getattr(_lib, _n).restype = C.c_int32
+
+
+class _ProfileRow(C.Structure):
+    _fields_ = [("site", C.c_int32), ("kernel", C.c_int32), ("launches", C.c_int64), ("total_ms", C.c_double)]
+
+
+_lib.moa_profile_enable.argtypes = [_i32, _i32]
+_lib.moa_profile_collect.argtypes = [C.POINTER(_ProfileRow), _i32, C.POINTER(_i32)]
+_lib.moa_profile_kernel_name.restype = C.c_char_p
+_lib.moa_profile_kernel_name.argtypes = [_i32]
+_lib.moa_profile_site_name.restype = C.c_char_p
+_lib.moa_profile_site_name.argtypes = [_i32]
 
 
 def library_path() -> str:
@@ -281,3 +294,27 @@ def draft_step(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok
     a.ws, a.ws_bytes = _ws(ws)
     a.stream = _stream(stream)
     _check(_lib.moa_draft_step(C.byref(a)))
+
+
+def profile_kernel_id(name: str) -> int:
+    i = 0
+    while True:
+        n = _lib.moa_profile_kernel_name(i).decode()
+        if n == "?":
+            raise KeyError(name)
+        if n == name:
+            return i
+        i += 1
+
+
+def profile_enable(on: bool, only_kernel: str | None = None):
+    _check(_lib.moa_profile_enable(1 if on else 0, -1 if only_kernel is None else profile_kernel_id(only_kernel)))
+
+
+def profile_collect():
+    """[(site name, kernel name, launches, total_ms)] since the last collect; waits for the events."""
+    rows = (_ProfileRow * 64)()
+    n = _i32(0)
+    _check(_lib.moa_profile_collect(rows, 64, C.byref(n)))
+    return [(_lib.moa_profile_site_name(r.site).decode(), _lib.moa_profile_kernel_name(r.kernel).decode(),
+             int(r.launches), float(r.total_ms)) for r in rows[: n.value]]

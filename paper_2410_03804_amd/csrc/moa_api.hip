@@ -149,6 +149,7 @@ int32_t moa_tree_build(const int32_t *parent, int32_t B, int32_t M, uint64_t *ma
 {
     if (!parent || !mask || !depth) return fail(MOA_ERR_NULL, "tree_build: NULL pointer");
     if (B < 1 || M < 1 || M > MOA_MAX_TREE) return fail(MOA_ERR_SHAPE, "tree_build: B=%d M=%d (M <= %d)", B, M, MOA_MAX_TREE);
+    prof_set_site(S_TREE_BUILD);
     MOA_TRY_HIP(launch_tree_build(parent, B, M, mask, depth, dev_status, (hipStream_t)stream), "tree_build");
     return MOA_OK;
 }
@@ -158,6 +159,7 @@ int32_t moa_tree_accept(const int32_t *parent, const int32_t *tok, const int32_t
 {
     if (!parent || !tok || !tgt || !path || !n_path || !bonus) return fail(MOA_ERR_NULL, "tree_accept: NULL pointer");
     if (B < 1 || M < 1 || M > MOA_MAX_TREE) return fail(MOA_ERR_SHAPE, "tree_accept: B=%d M=%d (M <= %d)", B, M, MOA_MAX_TREE);
+    prof_set_site(S_TREE_ACCEPT);
     MOA_TRY_HIP(launch_tree_accept(parent, tok, tgt, B, M, path, n_path, bonus, (hipStream_t)stream), "tree_accept");
     return MOA_OK;
 }
@@ -211,6 +213,7 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
         add(wq, eq, 0, &aa.q, &aa.ldq);
         add(wk, ekv, eq, &aa.k, &aa.ldk);
         add(wv, ekv, eq + ekv, &aa.v, &aa.ldv);
+        prof_set_site(S_LSA_QKV);
         if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "lsa: projection");
         aa.T = tc;
         aa.L = L;
@@ -219,6 +222,7 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
         aa.dh = dh;
         char *orow = (char *)out + (size_t)t0 * eq * es;
         aa.abar = wo ? (void *)abar : (void *)orow;
+        prof_set_site(S_LSA_ATTN);
         MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
         if (wo) {
             LinArgs lo = {};
@@ -230,6 +234,7 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
             lo.seg[0].W = wo;
             lo.seg[0].N = eq;
             lo.seg[0].st = row_store(orow, eq);
+            prof_set_site(S_LSA_OPROJ);
             MOA_TRY_HIP(launch_linear(dt, lo, st), "lsa: output projection");
         }
     }
@@ -256,6 +261,7 @@ int32_t moa_ca_kv_append(const moa_shape_t *shape, const void *mem_new, int64_t 
     sp.row_base = ca_len;
     sp.tok_off = tok_off;
     sp.dev_status = dev_status;
+    prof_set_site(S_APPEND_KV);
     if (T > 0) {
         LinArgs la = {};
         la.X = mem_new;
@@ -277,6 +283,7 @@ int32_t moa_ca_kv_append(const moa_shape_t *shape, const void *mem_new, int64_t 
         }
         if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "ca_kv_append: projection");
     }
+    prof_set_site(S_APPEND_LEN);
     MOA_TRY_HIP(launch_append_lengths(tok_off, B, ca_len, P_cap, dev_status, st), "ca_kv_append: lengths");
     return MOA_OK;
 }
@@ -301,6 +308,7 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
     char *part = abuf + align256((size_t)R * e * es);
     const size_t part_bytes = ws_bytes - (size_t)(part - (char *)ws);
 
+    prof_set_site(mask ? S_VERIFY_QKV : S_CA_QPROJ);
     LinArgs la = {};
     la.X = x;
     la.R = R;
@@ -352,6 +360,7 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
     aa.dev_status = dev_status;
     aa.ws = part;
     aa.ws_bytes = part_bytes;
+    prof_set_site(mask ? S_VERIFY_CORE : S_CA_CORE);
     MOA_TRY_HIP(launch_attn(aa, st), who);
 
     if (wo) {
@@ -364,6 +373,7 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
         lo.seg[0].W = wo;
         lo.seg[0].N = d;
         lo.seg[0].st = row_store(out, d);
+        prof_set_site(mask ? S_VERIFY_OPROJ : S_CA_OPROJ);
         MOA_TRY_HIP(launch_linear(dt, lo, st), who);
     }
     return MOA_OK;

@@ -392,21 +392,21 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
         const dim3 grid(g.nsplit, g.rowtiles, a.B * a.Hkv);
         const bool two = (a.H / a.Hkv) * a.Mq > 128;
         if (a.dh == 128) {
-            if (two) hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml);
-            else hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml);
+            if (two) { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
+            else { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
         } else {
-            if (two) hipLaunchKernelGGL((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml);
-            else hipLaunchKernelGGL((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml);
+            if (two) { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
+            else { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        if (a.dh == 128) hipLaunchKernelGGL(k_attn_merge<128>, dim3(nblocks), dim3(64), 0, stream, a, g, part_o, part_ml);
-        else hipLaunchKernelGGL(k_attn_merge<64>, dim3(nblocks), dim3(64), 0, stream, a, g, part_o, part_ml);
+        if (a.dh == 128) { prof_begin(K_ATTN_MERGE, stream); hipLaunchKernelGGL(k_attn_merge<128>, dim3(nblocks), dim3(64), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
+        else { prof_begin(K_ATTN_MERGE, stream); hipLaunchKernelGGL(k_attn_merge<64>, dim3(nblocks), dim3(64), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
         return hipGetLastError();
     }
     if (a.dh > 256) return hipErrorInvalidValue;
-    if (a.dtype == DT_BF16) hipLaunchKernelGGL(k_attn_generic<bf16_t>, dim3(nblocks), dim3(64), 0, stream, a);
-    else hipLaunchKernelGGL(k_attn_generic<float>, dim3(nblocks), dim3(64), 0, stream, a);
+    if (a.dtype == DT_BF16) { prof_begin(K_ATTN_GENERIC, stream); hipLaunchKernelGGL(k_attn_generic<bf16_t>, dim3(nblocks), dim3(64), 0, stream, a); prof_end(stream); }
+    else { prof_begin(K_ATTN_GENERIC, stream); hipLaunchKernelGGL(k_attn_generic<float>, dim3(nblocks), dim3(64), 0, stream, a); prof_end(stream); }
     return hipGetLastError();
 }
 

@@ -70,6 +70,19 @@ __device__ __forceinline__ int64_t store_offset(const StoreSpec &s, int64_t r, i
     return (((int64_t)b * s.heads + g) * (int64_t)s.cap + pos) * s.dh + c;
 }
 
+// ---- optional per-launch timing (hipEvents around single kernels), used by the benchmark only
+enum KernelId {
+    K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_TILED, K_SCATTER,
+    K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_COUNT
+};
+enum SiteId {
+    S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,
+    S_CA_OPROJ, S_VERIFY_QKV, S_VERIFY_CORE, S_VERIFY_OPROJ, S_TREE_ACCEPT, S_COUNT
+};
+void prof_set_site(int site);
+void prof_begin(int kernel, hipStream_t stream);   // no-ops unless profiling is enabled
+void prof_end(hipStream_t stream);
+
 struct LinSeg {
     const void *W;  // [N, K] row-major
     int N;

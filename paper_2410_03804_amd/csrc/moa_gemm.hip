@@ -286,7 +286,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             for (int s = 0; s < a.nseg; ++s) { ta.tile_begin[s] = t; t += a.seg[s].N / 128; }
             ta.tile_begin[a.nseg] = t;
             dim3 grid(t, (unsigned)((a.R + 127) / 128));
-            hipLaunchKernelGGL(k_linear_tiled_bf16, grid, dim3(256), 0, stream, ta);
+            { prof_begin(K_LIN_TILED, stream); hipLaunchKernelGGL(k_linear_tiled_bf16, grid, dim3(256), 0, stream, ta); prof_end(stream); }
             return hipGetLastError();
         }
         SkinnyArgs sa;
@@ -295,17 +295,17 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
         for (int s = 0; s < a.nseg; ++s) { sa.tile_begin[s] = t; t += a.seg[s].N / 32; }
         sa.tile_begin[a.nseg] = t;
         dim3 grid(t, (unsigned)((a.R + 63) / 64));
-        hipLaunchKernelGGL(k_linear_skinny_bf16<2>, grid, dim3(256), 0, stream, sa);
+        { prof_begin(K_LIN_SKINNY, stream); hipLaunchKernelGGL(k_linear_skinny_bf16<2>, grid, dim3(256), 0, stream, sa); prof_end(stream); }
         return hipGetLastError();
     }
     for (int s = 0; s < a.nseg; ++s) {
         dim3 grid((a.seg[s].N + 63) / 64, (unsigned)((a.R + 63) / 64));
         if (dtype == DT_BF16)
-            hipLaunchKernelGGL(k_linear_generic<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)a.X, a.R, a.K,
-                               a.ldx, (const bf16_t *)a.seg[s].W, a.seg[s].N, a.seg[s].st);
+            { prof_begin(K_LIN_GENERIC, stream); hipLaunchKernelGGL(k_linear_generic<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)a.X, a.R, a.K,
+                               a.ldx, (const bf16_t *)a.seg[s].W, a.seg[s].N, a.seg[s].st); prof_end(stream); }
         else
-            hipLaunchKernelGGL(k_linear_generic<float>, grid, dim3(256), 0, stream, (const float *)a.X, a.R, a.K,
-                               a.ldx, (const float *)a.seg[s].W, a.seg[s].N, a.seg[s].st);
+            { prof_begin(K_LIN_GENERIC, stream); hipLaunchKernelGGL(k_linear_generic<float>, grid, dim3(256), 0, stream, (const float *)a.X, a.R, a.K,
+                               a.ldx, (const float *)a.seg[s].W, a.seg[s].N, a.seg[s].st); prof_end(stream); }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -337,9 +337,9 @@ hipError_t launch_scatter_copy(int dtype, const void *X, int64_t R, int N, int64
     const int64_t total = R * N;
     const dim3 grid((unsigned)((total + 255) / 256));
     if (dtype == DT_BF16)
-        hipLaunchKernelGGL(k_scatter_copy<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)X, R, N, ldx, st);
+        { prof_begin(K_SCATTER, stream); hipLaunchKernelGGL(k_scatter_copy<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)X, R, N, ldx, st); prof_end(stream); }
     else
-        hipLaunchKernelGGL(k_scatter_copy<float>, grid, dim3(256), 0, stream, (const float *)X, R, N, ldx, st);
+        { prof_begin(K_SCATTER, stream); hipLaunchKernelGGL(k_scatter_copy<float>, grid, dim3(256), 0, stream, (const float *)X, R, N, ldx, st); prof_end(stream); }
     return hipGetLastError();
 }
 

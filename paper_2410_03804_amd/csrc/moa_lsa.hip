@@ -79,11 +79,11 @@ hipError_t launch_lsa_attn(const LsaAttnArgs &a, hipStream_t stream)
     if (a.dtype == DT_BF16) {
         e = hipFuncSetAttribute((const void *)k_lsa_attn<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k_lsa_attn<bf16_t>, grid, dim3(256), lds, stream, a);
+        { prof_begin(K_LSA_ATTN, stream); hipLaunchKernelGGL(k_lsa_attn<bf16_t>, grid, dim3(256), lds, stream, a); prof_end(stream); }
     } else {
         e = hipFuncSetAttribute((const void *)k_lsa_attn<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k_lsa_attn<float>, grid, dim3(256), lds, stream, a);
+        { prof_begin(K_LSA_ATTN, stream); hipLaunchKernelGGL(k_lsa_attn<float>, grid, dim3(256), lds, stream, a); prof_end(stream); }
     }
     return hipGetLastError();
 }

@@ -1,0 +1,103 @@
+// Optional per-kernel timing for the benchmark: when enabled, a pair of hipEvents is recorded on the
+// caller's stream around every kernel launch (or around the launches of one chosen kernel only).
+// Off by default; nothing here runs on the hot path unless the caller switches it on.
+#include "../../include/moa.h"
+#include "moa_common.h"
+
+#include <mutex>
+#include <vector>
+
+namespace moa {
+
+namespace {
+struct Rec { int site, kernel; hipEvent_t e0, e1; };
+std::mutex g_mu;
+bool g_on = false;
+int g_only_kernel = -1;
+std::vector<Rec> g_recs;
+std::vector<hipEvent_t> g_pool;
+thread_local int t_site = S_NONE;
+thread_local bool t_open = false;
+
+hipEvent_t take_event()
+{
+    if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+const char *const kKernelNames[K_COUNT] = {
+    "k_tree_build", "k_tree_accept", "k_append_lengths", "k_linear_generic", "k_linear_skinny_bf16",
+    "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn"};
+const char *const kSiteNames[S_COUNT] = {
+    "none", "tree_build", "lsa.qkv_proj", "lsa.layer_attn", "lsa.o_proj", "ca_append.kv_proj", "ca_append.lengths",
+    "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept"};
+}  // namespace
+
+void prof_set_site(int site) { t_site = site; }
+
+void prof_begin(int kernel, hipStream_t stream)
+{
+    if (!g_on) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_on || (g_only_kernel >= 0 && kernel != g_only_kernel)) return;
+    Rec r = {t_site, kernel, take_event(), take_event()};
+    if (!r.e0 || !r.e1) return;
+    if (hipEventRecord(r.e0, stream) != hipSuccess) return;
+    g_recs.push_back(r);
+    t_open = true;
+}
+
+void prof_end(hipStream_t stream)
+{
+    if (!t_open) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    t_open = false;
+    if (!g_recs.empty()) (void)hipEventRecord(g_recs.back().e1, stream);
+}
+
+}  // namespace moa
+
+using namespace moa;
+
+extern "C" {
+
+int32_t moa_profile_enable(int32_t on, int32_t only_kernel)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (const Rec &r : g_recs) { g_pool.push_back(r.e0); g_pool.push_back(r.e1); }
+    g_recs.clear();
+    g_on = on != 0;
+    g_only_kernel = (only_kernel >= 0 && only_kernel < K_COUNT) ? only_kernel : -1;
+    return MOA_OK;
+}
+
+int32_t moa_profile_collect(moa_profile_row_t *rows_host, int32_t max_rows, int32_t *n_rows_host)
+{
+    if (!rows_host || !n_rows_host || max_rows < 1) return MOA_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    int n = 0;
+    int32_t rc = MOA_OK;
+    for (const Rec &r : g_recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) {
+            rc = MOA_ERR_HIP;
+        } else {
+            int i = 0;
+            while (i < n && !(rows_host[i].site == r.site && rows_host[i].kernel == r.kernel)) ++i;
+            if (i == n && n < max_rows) { rows_host[n] = {r.site, r.kernel, 0, 0.0}; ++n; }
+            if (i < n) { rows_host[i].launches += 1; rows_host[i].total_ms += ms; }
+        }
+        g_pool.push_back(r.e0);
+        g_pool.push_back(r.e1);
+    }
+    g_recs.clear();
+    *n_rows_host = n;
+    return rc;
+}
+
+const char *moa_profile_kernel_name(int32_t kernel) { return (kernel >= 0 && kernel < K_COUNT) ? kKernelNames[kernel] : "?"; }
+const char *moa_profile_site_name(int32_t site) { return (site >= 0 && site < S_COUNT) ? kSiteNames[site] : "?"; }
+
+}  // extern "C"
