@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, fl
     }
 
     // tile i of this workgroup: cache tile t0+i, or tree tile i-(t1-t0)
-    uint4 kreg[NLD], vreg[NLD];
+    u32x4 kreg[NLD], vreg[NLD];
     auto fetch = [&](int i) {
         const bool tree = i >= (t1 - t0);
         const int base = tree ? (i - (t1 - t0)) * KT : (t0 + i) * KT;
@@ -197,21 +197,20 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, fl
             const int c = tid + 256 * j;
             int kr = base + c / CPK;                       // K: consecutive lanes walk along one key row
             if (kr > limit - 1) kr = limit - 1;            // rows past the end repeat the last valid row
-            kreg[j] = *(const uint4 *)(ksrc + (int64_t)kr * DH + (c % CPK) * 8);
+            kreg[j] = *(const u32x4 *)(ksrc + (int64_t)kr * DH + (c % CPK) * 8);
             int vr = base + (c & 31);                      // V: consecutive lanes take consecutive keys
             if (vr > limit - 1) vr = limit - 1;
-            vreg[j] = *(const uint4 *)(vsrc + (int64_t)vr * DH + (c >> 5) * 8);
+            vreg[j] = *(const u32x4 *)(vsrc + (int64_t)vr * DH + (c >> 5) * 8);
         }
     };
     auto stage = [&]() {
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             const int c = tid + 256 * j;
-            *(uint4 *)&Ks[c / CPK][(c % CPK) * 8] = kreg[j];
+            *(u32x4 *)&Ks[c / CPK][(c % CPK) * 8] = kreg[j];
             const int key = vpos(c & 31), d0 = (c >> 5) * 8;
-            const uint32_t w[4] = {vreg[j].x, vreg[j].y, vreg[j].z, vreg[j].w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) Vt[d0 + e][key] = (bf16_t)(w[e >> 1] >> (16 * (e & 1)));
+            for (int e = 0; e < 8; ++e) Vt[d0 + e][key] = (bf16_t)(vreg[j][e >> 1] >> (16 * (e & 1)));
         }
     };
 

@@ -10,6 +10,10 @@ typedef uint16_t bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+// 16-byte register chunk.  HIP's own uint4 is a class; arrays of it are not promoted to registers
+// (they end up in scratch memory), so staging buffers use this plain vector type instead.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
 

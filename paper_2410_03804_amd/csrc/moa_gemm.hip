@@ -153,12 +153,12 @@ __global__ __launch_bounds__(256) void k_linear_skinny_bf16(SkinnyArgs sa)
             v[e] = (red[0][row][8 * fc + e] + red[1][row][8 * fc + e]) + (red[2][row][8 * fc + e] + red[3][row][8 * fc + e]);
         const int64_t off = store_offset(a.seg[s].st, r, n0 + 8 * fc);
         if (off < 0) continue;
-        uint4 pk;
-        pk.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
-        pk.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
-        pk.z = (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
-        pk.w = (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
-        *(uint4 *)(dst + off) = pk;
+        u32x4 pk;
+        pk[0] = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+        pk[1] = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+        pk[2] = (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
+        pk[3] = (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
+        *(u32x4 *)(dst + off) = pk;
     }
 }
 
@@ -166,6 +166,7 @@ __global__ __launch_bounds__(256) void k_linear_skinny_bf16(SkinnyArgs sa)
 struct TiledArgs {
     LinArgs a;
     int tile_begin[4];
+    int tiles_per_xcd;   // feature tiles owned by one XCD
 };
 
 __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
@@ -175,10 +176,16 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
     __shared__ __attribute__((aligned(16))) bf16_t Xs[2][BM][LDT];
 
     const LinArgs &a = ta.a;
+    // Workgroups are handed to the 8 XCDs round-robin (id % 8), and each XCD has its own L2.  Give every
+    // XCD a contiguous group of feature tiles for all row tiles: its slice of W then stays in its L2 and
+    // each activation tile is fetched once per XCD instead of once per workgroup.
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int ftile = xcd * ta.tiles_per_xcd + j % ta.tiles_per_xcd;
+    if (ftile >= ta.tile_begin[a.nseg]) return;
     int s = 0;
-    while (s + 1 < a.nseg && (int)blockIdx.x >= ta.tile_begin[s + 1]) ++s;
-    const int n0 = ((int)blockIdx.x - ta.tile_begin[s]) * BN;
-    const int64_t r0 = (int64_t)blockIdx.y * BM;
+    while (s + 1 < a.nseg && ftile >= ta.tile_begin[s + 1]) ++s;
+    const int n0 = (ftile - ta.tile_begin[s]) * BN;
+    const int64_t r0 = (int64_t)(j / ta.tiles_per_xcd) * BM;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wf0 = (wave & 1) * 64;   // feature offset of this wave inside the tile
     const int wr0 = (wave >> 1) * 64;  // row offset
@@ -199,9 +206,9 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
         if (r > a.R - 1) r = a.R - 1;
         xsrc[i] = X + r * a.ldx + scol[i];
     }
-    uint4 wreg[4], xreg[4];
+    u32x4 wreg[4], xreg[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { wreg[i] = *(const uint4 *)wsrc[i]; xreg[i] = *(const uint4 *)xsrc[i]; }
+    for (int i = 0; i < 4; ++i) { wreg[i] = *(const u32x4 *)wsrc[i]; xreg[i] = *(const u32x4 *)xsrc[i]; }
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -216,15 +223,15 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
         const int buf = kt & 1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            *(uint4 *)&Ws[buf][srow[i]][scol[i]] = wreg[i];
-            *(uint4 *)&Xs[buf][srow[i]][scol[i]] = xreg[i];
+            *(u32x4 *)&Ws[buf][srow[i]][scol[i]] = wreg[i];
+            *(u32x4 *)&Xs[buf][srow[i]][scol[i]] = xreg[i];
         }
         __syncthreads();   // tile kt visible; everyone is past the reads of tile kt-2 (same buffer)
         if (kt + 1 < nk) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                wreg[i] = *(const uint4 *)(wsrc[i] + (int64_t)(kt + 1) * BK);
-                xreg[i] = *(const uint4 *)(xsrc[i] + (int64_t)(kt + 1) * BK);
+                wreg[i] = *(const u32x4 *)(wsrc[i] + (int64_t)(kt + 1) * BK);
+                xreg[i] = *(const u32x4 *)(xsrc[i] + (int64_t)(kt + 1) * BK);
             }
         }
 #pragma unroll
@@ -256,10 +263,10 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
                 const int n = n0 + wf0 + 32 * i + 8 * q + 4 * half;
                 const int64_t off = store_offset(a.seg[s].st, r, n);
                 if (off < 0) continue;
-                uint2 pk;
-                pk.x = (uint32_t)f2bf(acc[i][j][4 * q + 0]) | ((uint32_t)f2bf(acc[i][j][4 * q + 1]) << 16);
-                pk.y = (uint32_t)f2bf(acc[i][j][4 * q + 2]) | ((uint32_t)f2bf(acc[i][j][4 * q + 3]) << 16);
-                *(uint2 *)(dst + off) = pk;
+                u32x2 pk;
+                pk[0] = (uint32_t)f2bf(acc[i][j][4 * q + 0]) | ((uint32_t)f2bf(acc[i][j][4 * q + 1]) << 16);
+                pk[1] = (uint32_t)f2bf(acc[i][j][4 * q + 2]) | ((uint32_t)f2bf(acc[i][j][4 * q + 3]) << 16);
+                *(u32x2 *)(dst + off) = pk;
             }
     }
 }
@@ -285,7 +292,8 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             int t = 0;
             for (int s = 0; s < a.nseg; ++s) { ta.tile_begin[s] = t; t += a.seg[s].N / 128; }
             ta.tile_begin[a.nseg] = t;
-            dim3 grid(t, (unsigned)((a.R + 127) / 128));
+            ta.tiles_per_xcd = (t + 7) / 8;
+            dim3 grid(8u * ta.tiles_per_xcd * (unsigned)((a.R + 127) / 128));
             { prof_begin(K_LIN_TILED, stream); hipLaunchKernelGGL(k_linear_tiled_bf16, grid, dim3(256), 0, stream, ta); prof_end(stream); }
             return hipGetLastError();
         }
