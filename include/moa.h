@@ -113,13 +113,13 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T,
  * sequence b (tok_off is a device array, tok_off[0] = 0, non-decreasing, tok_off[B] <= T;
  * rows owned by no sequence are ignored); their projections are written to cache rows
  * ca_len[b] .. and ca_len[b] is advanced.  Rows that would pass P_cap are dropped and
- * MOA_DEV_CACHE_FULL is set.
+ * MOA_DEV_CACHE_FULL is set.  The workspace is optional here (NULL: a slower projection kernel).
  *   mem_new [T, d_mem], wk, wv [Hkv*dh, d_mem], kc, vc [B, Hkv, P_cap, dh] */
 int32_t moa_ca_kv_append(const moa_shape_t *shape, const void *mem_new, int64_t T, int32_t d_mem,
                          const int32_t *tok_off /*[B+1]*/, int32_t B,
                          const void *wk, const void *wv, void *kc, void *vc,
                          int32_t *ca_len /*[B] in/out*/, int32_t P_cap,
-                         int32_t *dev_status, void *stream);
+                         int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
 
 /* The draft model's Cross-Attention at generation time (Sec. 3.1.2; Alg. 1, CA_layer(q, kv)):
  * every query row attends all ca_len[b] cached rows, no mask; queries do not see each other

@@ -72,7 +72,7 @@ _lib.moa_workspace_bytes.argtypes = [C.POINTER(Shape), _i32, _i32, _i32, _i64, C
 _lib.moa_tree_build.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.moa_tree_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.moa_lsa.argtypes = [C.POINTER(Shape), _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
-_lib.moa_ca_kv_append.argtypes = [C.POINTER(Shape), _vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
+_lib.moa_ca_kv_append.argtypes = [C.POINTER(Shape), _vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
 _lib.moa_cross_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
 _lib.moa_tree_verify_attn.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
                                       _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -175,18 +175,19 @@ def lsa(shape: Shape, hs, wq, wk, wv, wo, out, ws, stream=None):
                         _dev(wo, dt, eq * eq, "wo"), _dev(out, dt, T * eq, "out"), wsp, wsb, _stream(stream)))
 
 
-def ca_kv_append(shape: Shape, mem_new, tok_off, wk, wv, kc, vc, ca_len, P_cap, dev_status=None, stream=None):
+def ca_kv_append(shape: Shape, mem_new, tok_off, wk, wv, kc, vc, ca_len, P_cap, dev_status=None, ws=None, stream=None):
     dt = _TORCH_DTYPE[shape.dtype]
     T, d_mem = mem_new.shape
     B = ca_len.shape[0]
     ekv = shape.n_kv_heads * shape.head_dim
     cache = B * ekv * P_cap
+    wsp, wsb = _ws(ws)
     _check(_lib.moa_ca_kv_append(C.byref(shape), _dev(mem_new, dt, T * d_mem, "mem_new"), T, d_mem,
                                  _dev(tok_off, torch.int32, B + 1, "tok_off"), B,
                                  _dev(wk, dt, ekv * d_mem, "wk"), _dev(wv, dt, ekv * d_mem, "wv"),
                                  _dev(kc, dt, cache, "kc"), _dev(vc, dt, cache, "vc"),
                                  _dev(ca_len, torch.int32, B, "ca_len"), P_cap,
-                                 _dev(dev_status, torch.int32, 1, "dev_status"), _stream(stream)))
+                                 _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
 
 
 def cross_attn_draft(shape: Shape, xq, wq, wo, kc, vc, ca_len, P_cap, out, ws, dev_status=None, stream=None):

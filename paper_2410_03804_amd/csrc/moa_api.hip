@@ -82,18 +82,40 @@ StoreSpec heads_store(void *dst, int heads, int dh, int cap, int rows_per_seq)
 
 constexpr int64_t LSA_CHUNK = 256;   // tokens projected per pass (bounds the Q/K/V scratch)
 
+size_t max2(size_t a, size_t b) { return a > b ? a : b; }
+
 size_t lsa_ws_bytes(const moa_shape_t *s, int64_t T)
 {
     const int64_t tc = T < LSA_CHUNK ? T : LSA_CHUNK;
     const size_t eq = (size_t)s->lsa_q_heads * s->head_dim, ekv = (size_t)s->lsa_kv_heads * s->head_dim;
-    return align256((size_t)tc * s->n_layers * (eq + 2 * ekv) * esize(s->dtype)) + align256((size_t)tc * eq * esize(s->dtype));
+    return align256((size_t)tc * s->n_layers * (eq + 2 * ekv) * esize(s->dtype)) + align256((size_t)tc * eq * esize(s->dtype)) +
+           align256(linear_workspace_bytes(s->dtype, tc, (int)eq, (int)eq));
+}
+
+// scratch shared by the projections' split-K partials and the attention core's split-KV partials
+size_t attn_scratch_bytes(const moa_shape_t *s, int B, int Mq, int P_cap, bool tree)
+{
+    const int e = s->n_q_heads * s->head_dim, ekv = s->n_kv_heads * s->head_dim;
+    const int64_t R = (int64_t)B * Mq;
+    size_t n = attn_workspace_bytes(s->dtype, B, Mq, s->n_q_heads, s->n_kv_heads, s->head_dim, P_cap);
+    n = max2(n, linear_workspace_bytes(s->dtype, R, s->d_model, e + (tree ? 2 * ekv : 0)));
+    n = max2(n, linear_workspace_bytes(s->dtype, R, s->d_model, e));
+    n = max2(n, linear_workspace_bytes(s->dtype, R, s->d_model, 2 * ekv));
+    n = max2(n, linear_workspace_bytes(s->dtype, R, s->d_model, ekv));
+    n = max2(n, linear_workspace_bytes(s->dtype, R, e, s->d_model));
+    return align256(n);
 }
 
 size_t attn_ws_bytes(const moa_shape_t *s, int B, int Mq, int P_cap)
 {
     const size_t e = (size_t)s->n_q_heads * s->head_dim;
-    return 2 * align256((size_t)B * Mq * e * esize(s->dtype)) +
-           align256(attn_workspace_bytes(s->dtype, B, Mq, s->n_q_heads, s->n_kv_heads, s->head_dim, P_cap));
+    return 2 * align256((size_t)B * Mq * e * esize(s->dtype)) + attn_scratch_bytes(s, B, Mq, P_cap, true);
+}
+
+size_t append_ws_bytes(const moa_shape_t *s, int64_t T, int d_mem)
+{
+    const int ekv = s->n_kv_heads * s->head_dim;
+    return align256(max2(linear_workspace_bytes(s->dtype, T, d_mem, 2 * ekv), linear_workspace_bytes(s->dtype, T, d_mem, ekv)));
 }
 
 int32_t check_ws(const void *ws, size_t have, size_t need)
@@ -137,8 +159,9 @@ int32_t moa_workspace_bytes(const moa_shape_t *shape, int32_t B, int32_t P_cap, 
     if (T_lsa > 0) {
         rc = check_shape(shape, true);
         if (rc) return rc;
-        const size_t l = lsa_ws_bytes(shape, T_lsa);
-        if (l > need) need = l;
+        need = max2(need, lsa_ws_bytes(shape, T_lsa));
+        need = max2(need, append_ws_bytes(shape, T_lsa, shape->lsa_q_heads * shape->head_dim));
+        need = max2(need, append_ws_bytes(shape, T_lsa, shape->d_model));
     }
     *bytes_host = need;
     return MOA_OK;
@@ -186,6 +209,8 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
     const int wide = eq + 2 * ekv;
     char *qkv = (char *)ws;
     char *abar = qkv + align256((size_t)tc_max * L * wide * es);
+    char *lin_ws = abar + align256((size_t)tc_max * eq * es);
+    const size_t lin_ws_bytes = ws_bytes - (size_t)(lin_ws - (char *)ws);
 
     for (int64_t t0 = 0; t0 < T; t0 += LSA_CHUNK) {
         const int64_t tc = (T - t0) < LSA_CHUNK ? (T - t0) : LSA_CHUNK;
@@ -234,6 +259,8 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
             lo.seg[0].W = wo;
             lo.seg[0].N = eq;
             lo.seg[0].st = row_store(orow, eq);
+            lo.ws = lin_ws;
+            lo.ws_bytes = lin_ws_bytes;
             prof_set_site(S_LSA_OPROJ);
             MOA_TRY_HIP(launch_linear(dt, lo, st), "lsa: output projection");
         }
@@ -243,11 +270,12 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
 
 int32_t moa_ca_kv_append(const moa_shape_t *shape, const void *mem_new, int64_t T, int32_t d_mem,
                          const int32_t *tok_off, int32_t B, const void *wk, const void *wv, void *kc, void *vc,
-                         int32_t *ca_len, int32_t P_cap, int32_t *dev_status, void *stream)
+                         int32_t *ca_len, int32_t P_cap, int32_t *dev_status, void *ws, size_t ws_bytes, void *stream)
 {
     int32_t rc = check_shape(shape, false);
     if (rc) return rc;
     if (!mem_new || !tok_off || !kc || !vc || !ca_len) return fail(MOA_ERR_NULL, "ca_kv_append: NULL pointer");
+    if (ws && (((uintptr_t)ws) & 255)) return fail(MOA_ERR_WORKSPACE, "workspace not 256-byte aligned");
     if (B < 1 || T < 0 || d_mem < 1 || P_cap < 1) return fail(MOA_ERR_SHAPE, "ca_kv_append: B=%d T=%lld d_mem=%d P_cap=%d", B, (long long)T, d_mem, P_cap);
     const int dh = shape->head_dim, ekv = shape->n_kv_heads * dh, dt = shape->dtype;
     if ((!wk || !wv) && ekv != d_mem) return fail(MOA_ERR_SHAPE, "ca_kv_append: NULL weight needs d_mem == Hkv*dh");
@@ -268,6 +296,8 @@ int32_t moa_ca_kv_append(const moa_shape_t *shape, const void *mem_new, int64_t 
         la.R = T;
         la.K = d_mem;
         la.ldx = d_mem;
+        la.ws = ws;              // optional here: without it the projection takes the slower kernel
+        la.ws_bytes = ws_bytes;
         const void *w[2] = {wk, wv};
         void *dst[2] = {kc, vc};
         for (int i = 0; i < 2; ++i) {
@@ -314,6 +344,8 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
     la.R = R;
     la.K = d;
     la.ldx = d;
+    la.ws = part;
+    la.ws_bytes = part_bytes;
     const void *q = x;
     if (wq) {
         la.seg[la.nseg].W = wq;
@@ -373,6 +405,8 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
         lo.seg[0].W = wo;
         lo.seg[0].N = d;
         lo.seg[0].st = row_store(out, d);
+        lo.ws = part;
+        lo.ws_bytes = part_bytes;
         prof_set_site(mask ? S_VERIFY_OPROJ : S_CA_OPROJ);
         MOA_TRY_HIP(launch_linear(dt, lo, st), who);
     }
@@ -419,7 +453,7 @@ static int32_t draft_step_stages(const moa_step_args_t *a)
     if (rc) return rc;
     const int d_mem = a->shape->lsa_q_heads * a->shape->head_dim;
     rc = moa_ca_kv_append(a->shape, a->lsa_out, a->T_lsa, d_mem, a->tok_off, a->B, a->ca_wk, a->ca_wv, a->ca_k,
-                          a->ca_v, a->ca_len, a->ca_P_cap, a->dev_status, a->stream);
+                          a->ca_v, a->ca_len, a->ca_P_cap, a->dev_status, a->ws, a->ws_bytes, a->stream);
     if (rc) return rc;
     rc = moa_cross_attn_draft(a->shape, a->ca_xq, a->B, a->Mq, a->ca_wq, a->ca_wo, a->ca_k, a->ca_v, a->ca_len,
                               a->ca_P_cap, a->ca_out, a->dev_status, a->ws, a->ws_bytes, a->stream);

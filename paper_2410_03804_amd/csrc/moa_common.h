@@ -76,7 +76,7 @@ __device__ __forceinline__ int64_t store_offset(const StoreSpec &s, int64_t r, i
 
 // ---- optional per-launch timing (hipEvents around single kernels), used by the benchmark only
 enum KernelId {
-    K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_TILED, K_SCATTER,
+    K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_SPLITK, K_LIN_REDUCE, K_LIN_TILED, K_SCATTER,
     K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_COUNT
 };
 enum SiteId {
@@ -100,10 +100,14 @@ struct LinArgs {
     int64_t ldx;
     int nseg;
     LinSeg seg[3];
+    void *ws;          // optional scratch for the split-K kernel (linear_workspace_bytes)
+    size_t ws_bytes;
 };
 
 // Y_s = X W_s^T for up to three weight matrices that share X (one launch on the fast path).
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream);
+// scratch the fast weight-streaming path wants for R rows and ntot output features in total (0 = not used)
+size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot);
 
 // dst(store spec) = X, element by element (NULL-weight projections that still change layout)
 hipError_t launch_scatter_copy(int dtype, const void *X, int64_t R, int N, int64_t ldx, const StoreSpec &st,

@@ -162,6 +162,127 @@ __global__ __launch_bounds__(256) void k_linear_skinny_bf16(SkinnyArgs sa)
     }
 }
 
+// ------------------------------------------------------------------ split-K bf16 (weight streaming)
+// The HBM-bound projections (<= 128 rows): W is read exactly once, in 64-byte runs per lane, every load of
+// a workgroup's slice issued before anything is waited for.  A workgroup owns 64 output features (16 per
+// wave) and one K slice of 128*NQ; the activation slice [64 rows x 128*NQ] is requested first, parked in
+// LDS and shared by the four waves, so X costs the fill path as much as W and not four times more.
+// Slices are summed by k_linear_splitk_reduce (fp32 partials, fixed order: results do not depend on
+// scheduling).  MFMA k-slots are permuted so that a lane's four 16-byte W loads are contiguous: slot
+// (q, j, kg) reads k = 128 q + 32 kg + 8 j, and the X fragment is read from the same place.
+struct SplitKArgs {
+    LinArgs a;
+    int tile_begin[4];   // first 64-feature tile of each segment; [nseg] = total tiles
+    int splits;          // K slices
+    int ntot;            // total features (all segments), row length of the partial buffer
+    float *part;         // [row tiles][splits][64][ntot]
+};
+
+template <int NQ>
+__global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
+{
+    constexpr int KS = 128 * NQ, LDK = KS + 8, CPR = KS / 8, XL = (64 * CPR) / 256;
+    extern __shared__ __attribute__((aligned(16))) bf16_t Xs[];   // [64][LDK]
+    const LinArgs &a = sa.a;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, kg = lane >> 4;
+    const int tile = blockIdx.x / sa.splits, split = blockIdx.x - tile * sa.splits;
+    int s = 0;
+    while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
+    const int n0 = (tile - sa.tile_begin[s]) * 64 + wave * 16;   // feature inside the segment
+    const int k0 = split * KS;
+    const int64_t r0 = (int64_t)blockIdx.y * 64;
+    const bf16_t *X = (const bf16_t *)a.X;
+    const bf16_t *W = (const bf16_t *)a.seg[s].W;
+
+    u32x4 xr[XL];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+        const int c = tid + 256 * i;
+        int64_t r = r0 + c / CPR;
+        if (r > a.R - 1) r = a.R - 1;          // rows past the end repeat the last row; never stored
+        xr[i] = *(const u32x4 *)(X + r * a.ldx + k0 + 8 * (c % CPR));
+    }
+    bf16x8 wf[NQ][4];
+    const bf16_t *wp = W + (int64_t)(n0 + li) * a.K + k0 + 32 * kg;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wf[q][j] = *(const bf16x8 *)(wp + 128 * q + 8 * j);
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+        const int c = tid + 256 * i;
+        *(u32x4 *)&Xs[(c / CPR) * LDK + 8 * (c % CPR)] = xr[i];
+    }
+    __syncthreads();
+
+    f32x4 acc[4];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bf16x8 xf[4];
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) xf[rb] = *(const bf16x8 *)&Xs[(16 * rb + li) * LDK + 128 * q + 32 * kg + 8 * j];
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[q][j], xf[rb], acc[rb], 0, 0, 0);
+        }
+
+    // lane holds features 4 kg .. 4 kg + 3 of its wave's 16, for row 16 rb + li
+    float *p = sa.part + ((int64_t)blockIdx.y * sa.splits + split) * 64 * sa.ntot + tile * 64 + wave * 16 + 4 * kg;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+        if (r0 + 16 * rb + li < a.R) *(f32x4 *)(p + (int64_t)(16 * rb + li) * sa.ntot) = acc[rb];
+}
+
+// one thread per (row, 8 consecutive features): sum the K slices in order, round once, store
+__global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
+{
+    const LinArgs &a = sa.a;
+    const int per = sa.ntot / 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.R * per) return;
+    const int64_t r = idx / per;
+    const int nt = (int)(idx - r * per) * 8;          // feature in the concatenated space
+    const int tile = nt >> 6;
+    int s = 0;
+    while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
+    const int n = nt - sa.tile_begin[s] * 64;
+    const int64_t rt = r >> 6, rr = r & 63;
+    const float *p = sa.part + (rt * sa.splits * 64 + rr) * sa.ntot + nt;
+    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < sa.splits; ++k) {
+        lo += *(const f32x4 *)(p + (int64_t)k * 64 * sa.ntot);
+        hi += *(const f32x4 *)(p + (int64_t)k * 64 * sa.ntot + 4);
+    }
+    const int64_t off = store_offset(a.seg[s].st, r, n);
+    if (off < 0) return;
+    u32x4 pk;
+    pk[0] = (uint32_t)f2bf(lo[0]) | ((uint32_t)f2bf(lo[1]) << 16);
+    pk[1] = (uint32_t)f2bf(lo[2]) | ((uint32_t)f2bf(lo[3]) << 16);
+    pk[2] = (uint32_t)f2bf(hi[0]) | ((uint32_t)f2bf(hi[1]) << 16);
+    pk[3] = (uint32_t)f2bf(hi[2]) | ((uint32_t)f2bf(hi[3]) << 16);
+    *(u32x4 *)((bf16_t *)a.seg[s].st.dst + off) = pk;
+}
+
+static int splitk_nq(int K)
+{
+    for (int nq = 1; nq <= 8; nq *= 2)
+        if (K % (128 * nq) == 0 && K / (128 * nq) <= 8) return nq;
+    return (K % 1024 == 0) ? 8 : 0;
+}
+
+size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot)
+{
+    if (dtype != DT_BF16 || R > 128 || K % 128 || ntot % 64) return 0;
+    const int nq = splitk_nq(K);
+    if (!nq) return 0;
+    const size_t splits = K / (128 * nq), rowtiles = (size_t)((R + 63) / 64);
+    return rowtiles * splits * 64 * (size_t)ntot * sizeof(float);
+}
+
 // ------------------------------------------------------------------ tiled bf16 (many rows)
 struct TiledArgs {
     LinArgs a;
@@ -295,6 +416,43 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             ta.tiles_per_xcd = (t + 7) / 8;
             dim3 grid(8u * ta.tiles_per_xcd * (unsigned)((a.R + 127) / 128));
             { prof_begin(K_LIN_TILED, stream); hipLaunchKernelGGL(k_linear_tiled_bf16, grid, dim3(256), 0, stream, ta); prof_end(stream); }
+            return hipGetLastError();
+        }
+        bool all64 = true;
+        int ntot = 0;
+        for (int s = 0; s < a.nseg; ++s) { all64 = all64 && a.seg[s].N % 64 == 0; ntot += a.seg[s].N; }
+        const size_t need = all64 ? linear_workspace_bytes(dtype, a.R, a.K, ntot) : 0;
+        if (need && a.ws && a.ws_bytes >= need && (((uintptr_t)a.ws) & 15) == 0) {
+            SplitKArgs ka;
+            ka.a = a;
+            int t = 0;
+            for (int s = 0; s < a.nseg; ++s) { ka.tile_begin[s] = t; t += a.seg[s].N / 64; }
+            ka.tile_begin[a.nseg] = t;
+            const int nq = splitk_nq(a.K);
+            ka.splits = a.K / (128 * nq);
+            ka.ntot = ntot;
+            ka.part = (float *)a.ws;
+            const dim3 grid(t * ka.splits, (unsigned)((a.R + 63) / 64));
+            const size_t lds = (size_t)64 * (128 * nq + 8) * sizeof(bf16_t);
+            hipError_t e = hipSuccess;
+            prof_begin(K_LIN_SPLITK, stream);
+            switch (nq) {
+            case 1: hipLaunchKernelGGL(k_linear_splitk_bf16<1>, grid, dim3(256), lds, stream, ka); break;
+            case 2: hipLaunchKernelGGL(k_linear_splitk_bf16<2>, grid, dim3(256), lds, stream, ka); break;
+            case 4: hipLaunchKernelGGL(k_linear_splitk_bf16<4>, grid, dim3(256), lds, stream, ka); break;
+            default:
+                e = hipFuncSetAttribute((const void *)k_linear_splitk_bf16<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e == hipSuccess) hipLaunchKernelGGL(k_linear_splitk_bf16<8>, grid, dim3(256), lds, stream, ka);
+                break;
+            }
+            prof_end(stream);
+            if (e != hipSuccess) return e;
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            const int64_t items = a.R * (ntot / 8);
+            prof_begin(K_LIN_REDUCE, stream);
+            hipLaunchKernelGGL(k_linear_splitk_reduce, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, ka);
+            prof_end(stream);
             return hipGetLastError();
         }
         SkinnyArgs sa;

@@ -255,8 +255,10 @@ def test_ca_kv_append_parity(G, moa, oracle, case):
     shape = G.shape_of(cfg)
     kc, vc, ca_len = G.dev(kc0, cfg.dtype), G.dev(vc0, cfg.dtype), G.dev(ca_len0)
     st = G.status_word()
+    # with a workspace the bf16 projection takes the split-K weight-streaming kernel, without it the fallback
+    ws = G.workspace(shape, B, P_cap, cfg.M, T) if case.endswith("dh128") else None
     moa.ca_kv_append(shape, G.dev(mem, cfg.dtype), G.dev(tok_off), G.dev(w["wk"], cfg.dtype), G.dev(w["wv"], cfg.dtype),
-                     kc, vc, ca_len, P_cap, st)
+                     kc, vc, ca_len, P_cap, st, ws)
     torch.cuda.synchronize()
     wk_, wv_, wl = kc0.astype(np.float64), vc0.astype(np.float64), ca_len0.copy()
     oracle.ca_kv_append(mem, tok_off, w["wk"], w["wv"], wk_, wv_, wl, cfg.Hkv, cfg.dh)
