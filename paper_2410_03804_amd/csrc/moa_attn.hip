@@ -357,7 +357,7 @@ static bool mfma_ok(int dtype, int dh, const AttnArgs *a)
 static SplitGeom split_geometry(int B, int Mq, int H, int Hkv, int P_cap)
 {
     const int RG = (H / Hkv) * Mq;
-    const int nblk = RG > 128 ? 2 : 1;
+    const int nblk = RG > 256 ? 2 : 1;
     SplitGeom g;
     g.rowtiles = (RG + 128 * nblk - 1) / (128 * nblk);
     g.rows_pad = g.rowtiles * 128 * nblk;
@@ -389,7 +389,7 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
         float *part_o = (float *)a.ws;
         float *part_ml = part_o + rows * a.dh;
         const dim3 grid(g.nsplit, g.rowtiles, a.B * a.Hkv);
-        const bool two = (a.H / a.Hkv) * a.Mq > 128;
+        const bool two = (a.H / a.Hkv) * a.Mq > 256;
         if (a.dh == 128) {
             if (two) { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
             else { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }

@@ -253,9 +253,18 @@ __global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
     const int64_t rt = r >> 6, rr = r & 63;
     const float *p = sa.part + (rt * sa.splits * 64 + rr) * sa.ntot + nt;
     f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-    for (int k = 0; k < sa.splits; ++k) {
-        lo += *(const f32x4 *)(p + (int64_t)k * 64 * sa.ntot);
-        hi += *(const f32x4 *)(p + (int64_t)k * 64 * sa.ntot + 4);
+    const int64_t stride = (int64_t)64 * sa.ntot;
+    int k = 0;
+    for (; k + 8 <= sa.splits; k += 8) {        // eight slices in flight, summed in slice order
+        f32x4 l8[8], h8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { l8[u] = *(const f32x4 *)(p + (k + u) * stride); h8[u] = *(const f32x4 *)(p + (k + u) * stride + 4); }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { lo += l8[u]; hi += h8[u]; }
+    }
+    for (; k < sa.splits; ++k) {
+        lo += *(const f32x4 *)(p + k * stride);
+        hi += *(const f32x4 *)(p + k * stride + 4);
     }
     const int64_t off = store_offset(a.seg[s].st, r, n);
     if (off < 0) return;

@@ -3,8 +3,15 @@
 //     mean_i ( sum_j P[i][j] V[j] ) = sum_j ( (1/L) sum_i P[i][j] ) V[j]
 // so only the column means of the L x L probability matrix are applied to V, and the output
 // projection runs afterwards on one row per token instead of L (both are exact identities).
-// One workgroup per (token, head); the token's Q and K rows of that head are staged in LDS,
-// the L x L scores live in LDS, softmax is fp32.
+//
+//   k_lsa_attn       any dtype / size: one workgroup per (token, head), Q/K rows and the L x L scores in
+//                    LDS, fp32 FMA.
+//   k_lsa_attn_mfma  bf16, head_dim 64/128, L <= 96: one wavefront per (token, head).  Scores are computed
+//                    transposed (S^T = K Q^T, MFMA 32x32x16 fed straight from global memory: both
+//                    operands are head_dim-contiguous rows), so a lane owns one query column: the row
+//                    softmax is an in-register reduction plus one exchange with lane^32, and the column
+//                    means are a 32-lane butterfly.  The L means then weight the V rows with plain
+//                    vector loads (HBM/L2-bound part, no matrix shape left).
 #include "moa_common.h"
 
 #include <math.h>
@@ -65,14 +72,151 @@ __global__ __launch_bounds__(256) void k_lsa_attn(LsaAttnArgs a)
     }
 }
 
+// ------------------------------------------------------------------ MFMA, one wavefront per (token, head)
+template <int DH, int NB>   // NB = ceil(L / 32) blocks of 32 layers
+__global__ __launch_bounds__(256) void k_lsa_attn_mfma(LsaAttnArgs a)
+{
+    constexpr int NKS = DH / 16;
+    __shared__ float pbar_s[4][32 * NB];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+    const int64_t unit = (int64_t)blockIdx.x * 4 + wave;       // (token, head)
+    const bool live = unit < a.T * a.Hq;
+    const int64_t u = live ? unit : a.T * a.Hq - 1;             // idle waves redo the last unit, store nothing
+    const int64_t t = u / a.Hq;
+    const int h = (int)(u - t * a.Hq), g = h / (a.Hq / a.Hkv);
+    const int L = a.L;
+    const bf16_t *q = (const bf16_t *)a.q + t * L * a.ldq + (int64_t)h * DH;
+    const bf16_t *k = (const bf16_t *)a.k + t * L * a.ldk + (int64_t)g * DH;
+    const bf16_t *v = (const bf16_t *)a.v + t * L * a.ldv + (int64_t)g * DH;
+    const float sc = 1.4426950408889634f / sqrtf((float)DH);    // log2 domain
+
+    // K fragments (A operand): row = key layer, 8 head_dim values per lane; rows past L repeat row L-1
+    bf16x8 kf[NB][NKS];
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb) {
+        int row = 32 * jb + l32;
+        if (row > L - 1) row = L - 1;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) kf[jb][ks] = *(const bf16x8 *)(k + (int64_t)row * a.ldk + 16 * ks + 8 * half);
+    }
+
+    // column sums of P, kept in the S^T register layout: csum[jb][v] belongs to key 32 jb + 8 (v/4) + 4 half + v%4
+    float csum[NB][16];
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) csum[jb][e] = 0.f;
+
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib) {
+        int qrow = 32 * ib + l32;
+        const bool qvalid = qrow < L;
+        if (qrow > L - 1) qrow = L - 1;
+        bf16x8 qf[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const bf16x8 *)(q + (int64_t)qrow * a.ldq + 16 * ks + 8 * half);
+        f32x16 s[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[jb][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks)
+                s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[jb][ks], qf[ks], s[jb], 0, 0, 0);
+        }
+        // softmax over the keys of this lane's query
+        float mx = -INFINITY;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = 32 * jb + 8 * (e >> 2) + 4 * half + (e & 3);
+                const float x = key < L ? s[jb][e] * sc : -INFINITY;
+                s[jb][e] = x;
+                mx = fmaxf(mx, x);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float sum = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { const float p = exp2f(s[jb][e] - mx); s[jb][e] = p; sum += p; }
+        sum += __shfl_xor(sum, 32);
+        const float inv = qvalid ? 1.0f / sum : 0.f;      // padded query columns contribute nothing
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) csum[jb][e] += s[jb][e] * inv;
+    }
+
+    // sum over the 32 query lanes of each half, then publish the L column means
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float x = csum[jb][e];
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) x += __shfl_xor(x, o);
+            csum[jb][e] = x;
+        }
+    if (l32 == 0) {
+        const float invL = 1.0f / (float)L;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) pbar_s[wave][32 * jb + 8 * (e >> 2) + 4 * half + (e & 3)] = csum[jb][e] * invL;
+    }
+    __syncthreads();
+
+    // abar[c] = sum_j pbar[j] V[j][c]; lane owns DH/64 consecutive components
+    constexpr int CPL = DH / 64;
+    float o[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) o[c] = 0.f;
+    for (int j = 0; j < L; ++j) {
+        const float pj = pbar_s[wave][j];
+        const bf16_t *vr = v + (int64_t)j * a.ldv + lane * CPL;
+        if (CPL == 2) {
+            const uint32_t w = *(const uint32_t *)vr;
+            o[0] = fmaf(pj, __uint_as_float(w << 16), o[0]);
+            o[CPL - 1] = fmaf(pj, __uint_as_float(w & 0xffff0000u), o[CPL - 1]);
+        } else {
+            o[0] = fmaf(pj, bf2f(vr[0]), o[0]);
+        }
+    }
+    if (live) {
+        bf16_t *dst = (bf16_t *)a.abar + t * (int64_t)a.Hq * DH + (int64_t)h * DH + lane * CPL;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) dst[c] = f2bf(o[c]);
+    }
+}
+
 size_t lsa_attn_lds_bytes(int /*dtype*/, int L, int dh)
 {
     return sizeof(float) * ((size_t)2 * L * (dh + 1) + (size_t)L * (L + 1) + L);
 }
 
+static bool lsa_mfma_ok(const LsaAttnArgs &a)
+{
+    auto al = [](const void *p) { return (((uintptr_t)p) & 15) == 0; };
+    return a.dtype == DT_BF16 && (a.dh == 64 || a.dh == 128) && a.L <= 96 && al(a.q) && al(a.k) && al(a.v) &&
+           al(a.abar) && a.ldq % 8 == 0 && a.ldk % 8 == 0 && a.ldv % 8 == 0;
+}
+
 hipError_t launch_lsa_attn(const LsaAttnArgs &a, hipStream_t stream)
 {
     if (a.T <= 0) return hipSuccess;
+    if (lsa_mfma_ok(a)) {
+        const dim3 grid((unsigned)((a.T * a.Hq + 3) / 4));
+        const int nb = (a.L + 31) / 32;
+        prof_begin(K_LSA_ATTN_MFMA, stream);
+#define MOA_LSA_CASE(DH, NBV) hipLaunchKernelGGL((k_lsa_attn_mfma<DH, NBV>), grid, dim3(256), 0, stream, a)
+        if (a.dh == 128) { if (nb == 1) MOA_LSA_CASE(128, 1); else if (nb == 2) MOA_LSA_CASE(128, 2); else MOA_LSA_CASE(128, 3); }
+        else { if (nb == 1) MOA_LSA_CASE(64, 1); else if (nb == 2) MOA_LSA_CASE(64, 2); else MOA_LSA_CASE(64, 3); }
+#undef MOA_LSA_CASE
+        prof_end(stream);
+        return hipGetLastError();
+    }
     const size_t lds = lsa_attn_lds_bytes(a.dtype, a.L, a.dh);
     const dim3 grid((unsigned)(a.T * a.Hq));
     hipError_t e;

@@ -29,7 +29,7 @@ hipEvent_t take_event()
 
 const char *const kKernelNames[K_COUNT] = {
     "k_tree_build", "k_tree_accept", "k_append_lengths", "k_linear_generic", "k_linear_skinny_bf16", "k_linear_splitk_bf16",
-    "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn"};
+    "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn", "k_lsa_attn_mfma"};
 const char *const kSiteNames[S_COUNT] = {
     "none", "tree_build", "lsa.qkv_proj", "lsa.layer_attn", "lsa.o_proj", "ca_append.kv_proj", "ca_append.lengths",
     "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept"};

@@ -151,6 +151,15 @@ def test_lsa_many_tokens_tiled_projection(G, moa, oracle):
     G.check_close(got, want, cfg.dtype, "lsa[tiled,T=300]")
 
 
+@pytest.mark.parametrize("L,dh", [(80, 128), (40, 64), (33, 128), (96, 64)])
+def test_lsa_layer_counts_beyond_one_block(G, moa, oracle, L, dh):
+    """Llama-2-70B stacks 80 layers: more than one 32-layer block on the layer axis, ragged last block."""
+    cfg = small_cfg("bf16", L=L, d_lsa_in=2 * dh, dh=dh, Hkv=1)
+    print(f"[case] lsa L={L} dh={dh}", flush=True)
+    got, want = run_lsa(G, moa, oracle, cfg, 5)
+    G.check_close(got, want, cfg.dtype, f"lsa[L={L},dh={dh}]")
+
+
 def ca_setup(cfg, Mq):
     w = mi.ca_weights(cfg)
     xq = mi.ca_queries(cfg, Mq)
