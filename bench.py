@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--sets", type=int, default=3, help="independent buffer sets rotated between steps")
     ap.add_argument("--profile-steps", type=int, default=12, help="untimed steps with events around every kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial", action="store_true", help="one stream only (no forked side branch inside the step)")
     ap.add_argument("--d-lsa-in", type=int, default=0, help="override the LSA input width (default 2*E_kv)")
     return ap.parse_args()
 
@@ -119,11 +120,17 @@ def main():
     setup_s = time.perf_counter() - t_setup
 
     counter = [0]
+    # a stream of our own: the legacy default stream synchronises implicitly with other streams
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(stream)
+
+    plans = [sets[i % nsets].plan(len_slot=i // nsets, serial=args.serial) for i in range(total)]
 
     def one_step():
         i = counter[0]
         counter[0] += 1
-        sets[i % nsets].run(len_slot=i // nsets)
+        plans[i].run(stream)
 
     for _ in range(Wm):
         one_step()

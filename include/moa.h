@@ -148,7 +148,12 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
  * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk.
- * The *_host members are HOST arrays of n_verify_layers device pointers. */
+ * The *_host members are HOST arrays of n_verify_layers device pointers.
+ * Scheduling: the LSA chain feeds only the cross-attention core, so when the workspace has room
+ * for two sets of scratch (moa_workspace_bytes asks for it) the cross-attention query projection
+ * and the verification layers run on a second, library-owned stream that is forked from and
+ * joined back into `stream` with events; ordering as seen from `stream` is unchanged, results are
+ * bit-identical to the one-stream schedule. */
 typedef struct {
     const moa_shape_t *shape;
     int32_t B, M, Mq;
@@ -172,6 +177,7 @@ typedef struct {
     /* accept */
     const int32_t *tok, *tgt;  int32_t *path, *n_path, *bonus;
     int32_t *dev_status;  void *ws;  size_t ws_bytes;  void *stream;
+    int32_t serial;               /* non-zero: never fork a second stream, run the stages one after another */
 } moa_step_args_t;
 
 int32_t moa_draft_step(const moa_step_args_t *args);

@@ -56,6 +56,7 @@ class _StepArgs(C.Structure):
         ("tok", C.c_void_p), ("tgt", C.c_void_p), ("path", C.c_void_p), ("n_path", C.c_void_p),
         ("bonus", C.c_void_p),
         ("dev_status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t), ("stream", C.c_void_p),
+        ("serial", C.c_int32),
     ]
 
 
@@ -233,11 +234,12 @@ def _ptr_array(tensors, dtype, numel, name):
     return arr
 
 
-def draft_step(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len,
+def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len,
                ca_P_cap, ca_xq, ca_out, v_x, v_w, v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, P_cap,
-               tok, tgt, path, n_path, bonus, ws, dev_status=None, stream=None):
-    """One pass of the whole path.  lsa_w = dict(wq, wk, wv, wo); ca_w = dict(wq, wo, wk, wv);
-    v_w = list (one per verified layer) of dict(wq, wk, wv, wo); v_* = lists of per-layer tensors."""
+               tok, tgt, path, n_path, bonus, ws, dev_status=None, serial=False):
+    """Marshal (and size-check) the arguments of moa_draft_step once; the returned plan can be run many times.
+    lsa_w = dict(wq, wk, wv, wo); ca_w = dict(wq, wo, wk, wv); v_w = list (one per verified layer) of
+    dict(wq, wk, wv, wo); v_* = lists of per-layer tensors.  The plan keeps the tensors alive."""
     dt, i32 = _TORCH_DTYPE[shape.dtype], torch.int32
     B, M = parent.shape
     Mq = ca_xq.shape[1]
@@ -293,8 +295,31 @@ def draft_step(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok
     a.bonus = _dev(bonus, i32, B, "bonus")
     a.dev_status = _dev(dev_status, i32, 1, "dev_status")
     a.ws, a.ws_bytes = _ws(ws)
-    a.stream = _stream(stream)
-    _check(_lib.moa_draft_step(C.byref(a)))
+    a.serial = 1 if serial else 0
+    tensors = [parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
+               v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, tok, tgt, path, n_path, bonus, ws, dev_status]
+    return StepPlan(a, shape, keep, tensors)
+
+
+class StepPlan:
+    """Pre-marshalled moa_step_args_t.  run() only fills in the stream and calls the library."""
+
+    def __init__(self, args, shape, arrays, tensors):
+        self._args, self._shape, self._arrays, self._tensors = args, shape, arrays, tensors
+        self._ref = C.byref(args)
+
+    def run(self, stream=None):
+        s = torch.cuda.current_stream() if stream is None else stream
+        self._args.stream = s.cuda_stream
+        rc = _lib.moa_draft_step(self._ref)
+        if rc != 0:
+            raise MoaError(rc, last_error())
+
+
+def draft_step(shape: Shape, *, stream=None, **kw):
+    """One pass of the whole path (see draft_step_plan for the arguments)."""
+    draft_step_plan(shape, **kw).run(stream)
+
 
 
 def profile_kernel_id(name: str) -> int:

@@ -6,6 +6,8 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
+
 using namespace moa;
 
 namespace {
@@ -118,6 +120,27 @@ size_t append_ws_bytes(const moa_shape_t *s, int64_t T, int d_mem)
     return align256(max2(linear_workspace_bytes(s->dtype, T, d_mem, 2 * ekv), linear_workspace_bytes(s->dtype, T, d_mem, ekv)));
 }
 
+// workspace split of the two-branch step: [main branch | cross-attention queries | side branch]
+struct StepLayout {
+    size_t main_bytes, caq_bytes, side_bytes;
+    size_t total() const { return main_bytes + caq_bytes + side_bytes; }
+};
+
+StepLayout step_layout(const moa_shape_t *s, int B, int M, int Mq, int P_cap, int ca_P_cap, int64_t T)
+{
+    StepLayout L;
+    const size_t qa = align256((size_t)B * Mq * s->n_q_heads * s->head_dim * esize(s->dtype));
+    size_t m = qa + attn_scratch_bytes(s, B, Mq, ca_P_cap, false);          // CA core + W_o: abuf + scratch
+    if (T > 0) {
+        m = max2(m, lsa_ws_bytes(s, T));
+        m = max2(m, append_ws_bytes(s, T, s->lsa_q_heads * s->head_dim));
+    }
+    L.main_bytes = align256(m);
+    L.caq_bytes = qa;                                                        // CA queries: written by the side branch
+    L.side_bytes = align256(max2(attn_ws_bytes(s, B, M, P_cap), attn_scratch_bytes(s, B, Mq, ca_P_cap, false)));
+    return L;
+}
+
 int32_t check_ws(const void *ws, size_t have, size_t need)
 {
     if (need == 0) return MOA_OK;
@@ -162,6 +185,8 @@ int32_t moa_workspace_bytes(const moa_shape_t *shape, int32_t B, int32_t P_cap, 
         need = max2(need, lsa_ws_bytes(shape, T_lsa));
         need = max2(need, append_ws_bytes(shape, T_lsa, shape->lsa_q_heads * shape->head_dim));
         need = max2(need, append_ws_bytes(shape, T_lsa, shape->d_model));
+        // moa_draft_step runs two branches side by side when each can have its own scratch
+        need = max2(need, step_layout(shape, B, M, M, P_cap, P_cap, T_lsa).total());
     }
     *bytes_host = need;
     return MOA_OK;
@@ -318,43 +343,52 @@ int32_t moa_ca_kv_append(const moa_shape_t *shape, const void *mem_new, int64_t 
     return MOA_OK;
 }
 
-// shared by cross-attention (mask == NULL) and tree verification
-static int32_t attention_layer(const char *who, const moa_shape_t *shape, const void *x, int32_t B, int32_t M,
-                               const void *wq, const void *wk, const void *wv, const void *wo,
-                               const void *kcache, const void *vcache, const int32_t *len, int32_t P_cap,
-                               const uint64_t *mask, void *out, void *k_tree, void *v_tree, int32_t *dev_status,
-                               void *ws, size_t ws_bytes, hipStream_t st)
+// ---- one attention layer = projections, then core + output projection.  Shared by cross-attention
+// (mask == NULL: no K/V projection, no tree rows) and tree verification.  The two halves can be put on
+// different streams by moa_draft_step; each gets its own scratch.
+struct AttnBufs {
+    char *qbuf;        // [B*M, H*dh] projected queries
+    char *abuf;        // [B*M, H*dh] concatenated heads before W_o
+    char *scratch_p;   // split-K partials of the projections
+    size_t scratch_p_bytes;
+    char *scratch_c;   // split-KV partials of the core, then split-K partials of W_o
+    size_t scratch_c_bytes;
+};
+
+static int32_t attn_check(const char *who, const moa_shape_t *shape, const void *wq, const void *wk, const void *wv,
+                          bool tree)
+{
+    const int dh = shape->head_dim, e = shape->n_q_heads * dh, ekv = shape->n_kv_heads * dh, d = shape->d_model;
+    if (!wq && e != d) return fail(MOA_ERR_SHAPE, "%s: NULL wq needs d == H*dh", who);
+    if (tree && ((!wk || !wv) && ekv != d)) return fail(MOA_ERR_SHAPE, "%s: NULL wk/wv needs d == Hkv*dh", who);
+    return MOA_OK;
+}
+
+// Q (and, for verification, the tree rows' K/V) projections; *q_out = where the queries are
+static int32_t attn_stage_project(const char *who, const moa_shape_t *shape, const void *x, int32_t B, int32_t M,
+                                  const void *wq, const void *wk, const void *wv, bool tree, void *k_tree,
+                                  void *v_tree, const AttnBufs &bf, hipStream_t st, const void **q_out)
 {
     const int dh = shape->head_dim, H = shape->n_q_heads, Hkv = shape->n_kv_heads, d = shape->d_model;
     const int e = H * dh, ekv = Hkv * dh, dt = shape->dtype;
-    const size_t es = esize(dt);
     const int64_t R = (int64_t)B * M;
-    if (!wq && e != d) return fail(MOA_ERR_SHAPE, "%s: NULL wq needs d == H*dh", who);
-    if (mask && ((!wk || !wv) && ekv != d)) return fail(MOA_ERR_SHAPE, "%s: NULL wk/wv needs d == Hkv*dh", who);
-    int32_t rc = check_ws(ws, ws_bytes, attn_ws_bytes(shape, B, M, P_cap));
-    if (rc) return rc;
-    char *qbuf = (char *)ws;
-    char *abuf = qbuf + align256((size_t)R * e * es);
-    char *part = abuf + align256((size_t)R * e * es);
-    const size_t part_bytes = ws_bytes - (size_t)(part - (char *)ws);
-
-    prof_set_site(mask ? S_VERIFY_QKV : S_CA_QPROJ);
+    prof_set_site(tree ? S_VERIFY_QKV : S_CA_QPROJ);
     LinArgs la = {};
     la.X = x;
     la.R = R;
     la.K = d;
     la.ldx = d;
-    la.ws = part;
-    la.ws_bytes = part_bytes;
-    const void *q = x;
+    la.ws = bf.scratch_p;
+    la.ws_bytes = bf.scratch_p_bytes;
+    *q_out = x;
     if (wq) {
         la.seg[la.nseg].W = wq;
         la.seg[la.nseg].N = e;
-        la.seg[la.nseg].st = row_store(qbuf, e);
+        la.seg[la.nseg].st = row_store(bf.qbuf, e);
         ++la.nseg;
-        q = qbuf;
+        *q_out = bf.qbuf;
     }
-    if (mask) {
+    if (tree) {
         const void *w[2] = {wk, wv};
         void *dst[2] = {k_tree, v_tree};
         for (int i = 0; i < 2; ++i) {
@@ -370,7 +404,17 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
         }
     }
     if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), who);
+    return MOA_OK;
+}
 
+static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const void *q, int32_t B, int32_t M,
+                               const void *wo, const void *kcache, const void *vcache, const int32_t *len,
+                               int32_t P_cap, const uint64_t *mask, void *out, void *k_tree, void *v_tree,
+                               int32_t *dev_status, const AttnBufs &bf, hipStream_t st)
+{
+    const int dh = shape->head_dim, H = shape->n_q_heads, Hkv = shape->n_kv_heads, d = shape->d_model;
+    const int e = H * dh, dt = shape->dtype;
+    const int64_t R = (int64_t)B * M;
     AttnArgs aa = {};
     aa.dtype = dt;
     aa.q = q;
@@ -380,7 +424,7 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
     aa.vtree = mask ? v_tree : nullptr;
     aa.len = len;
     aa.mask = mask;
-    aa.out = wo ? (void *)abuf : out;
+    aa.out = wo ? (void *)bf.abuf : out;
     aa.B = B;
     aa.Mq = M;
     aa.Mt = mask ? M : 0;
@@ -390,14 +434,13 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
     aa.P_cap = P_cap;
     aa.empty_is_error = mask ? 0 : 1;
     aa.dev_status = dev_status;
-    aa.ws = part;
-    aa.ws_bytes = part_bytes;
+    aa.ws = bf.scratch_c;
+    aa.ws_bytes = bf.scratch_c_bytes;
     prof_set_site(mask ? S_VERIFY_CORE : S_CA_CORE);
     MOA_TRY_HIP(launch_attn(aa, st), who);
-
     if (wo) {
         LinArgs lo = {};
-        lo.X = abuf;
+        lo.X = bf.abuf;
         lo.R = R;
         lo.K = e;
         lo.ldx = e;
@@ -405,12 +448,42 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
         lo.seg[0].W = wo;
         lo.seg[0].N = d;
         lo.seg[0].st = row_store(out, d);
-        lo.ws = part;
-        lo.ws_bytes = part_bytes;
+        lo.ws = bf.scratch_c;
+        lo.ws_bytes = bf.scratch_c_bytes;
         prof_set_site(mask ? S_VERIFY_OPROJ : S_CA_OPROJ);
         MOA_TRY_HIP(launch_linear(dt, lo, st), who);
     }
     return MOA_OK;
+}
+
+// carve [qbuf | abuf | scratch] out of one region; projections and core share the scratch (same stream)
+static AttnBufs attn_carve(const moa_shape_t *shape, int32_t B, int32_t M, void *ws, size_t ws_bytes)
+{
+    const size_t qa = align256((size_t)B * M * shape->n_q_heads * shape->head_dim * esize(shape->dtype));
+    AttnBufs bf;
+    bf.qbuf = (char *)ws;
+    bf.abuf = bf.qbuf + qa;
+    bf.scratch_p = bf.scratch_c = bf.abuf + qa;
+    bf.scratch_p_bytes = bf.scratch_c_bytes = ws_bytes - 2 * qa;
+    return bf;
+}
+
+static int32_t attention_layer(const char *who, const moa_shape_t *shape, const void *x, int32_t B, int32_t M,
+                               const void *wq, const void *wk, const void *wv, const void *wo,
+                               const void *kcache, const void *vcache, const int32_t *len, int32_t P_cap,
+                               const uint64_t *mask, void *out, void *k_tree, void *v_tree, int32_t *dev_status,
+                               void *ws, size_t ws_bytes, hipStream_t st)
+{
+    int32_t rc = attn_check(who, shape, wq, wk, wv, mask != nullptr);
+    if (rc) return rc;
+    rc = check_ws(ws, ws_bytes, attn_ws_bytes(shape, B, M, P_cap));
+    if (rc) return rc;
+    const AttnBufs bf = attn_carve(shape, B, M, ws, ws_bytes);
+    const void *q = nullptr;
+    rc = attn_stage_project(who, shape, x, B, M, wq, wk, wv, mask != nullptr, k_tree, v_tree, bf, st, &q);
+    if (rc) return rc;
+    return attn_stage_core(who, shape, q, B, M, wo, kcache, vcache, len, P_cap, mask, out, k_tree, v_tree, dev_status,
+                           bf, st);
 }
 
 int32_t moa_cross_attn_draft(const moa_shape_t *shape, const void *xq, int32_t B, int32_t Mq, const void *wq,
@@ -468,6 +541,94 @@ static int32_t draft_step_stages(const moa_step_args_t *a)
     return moa_tree_accept(a->parent, a->tok, a->tgt, a->B, a->M, a->path, a->n_path, a->bonus, a->stream);
 }
 
+// ---- the step with its independent branches on two streams.
+// Dependencies inside one step: the LSA chain (projection -> layer attention -> W_o -> memory append) feeds
+// only the cross-attention core; the cross-attention query projection and every verification layer depend on
+// none of it (verification needs the tree mask only).  The main chain is bound by the matrix cores, the other
+// projections by HBM, so running them side by side hides most of the weight streaming.  The side branch runs
+// on a library-owned stream that is forked from and joined back into the caller's stream with events, so the
+// caller still sees one stream's worth of ordering (and a stream capture records both branches).
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, tree = nullptr, caq = nullptr, join = nullptr;
+    bool ok = false;
+};
+
+static SideStream *side_stream_for_current_device()
+{
+    static std::mutex mu;
+    static SideStream pool[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    std::lock_guard<std::mutex> lk(mu);
+    SideStream &s = pool[dev];
+    if (!s.stream) {
+        s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
+               hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&s.tree, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&s.caq, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
+    }
+    return s.ok ? &s : nullptr;
+}
+
+static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
+{
+    const moa_shape_t *sh = a->shape;
+    hipStream_t main = (hipStream_t)a->stream, side = ss->stream;
+    const StepLayout L = step_layout(sh, a->B, a->M, a->Mq, a->P_cap, a->ca_P_cap, a->T_lsa);
+    char *ws_main = (char *)a->ws, *ws_caq = ws_main + L.main_bytes, *ws_side = ws_caq + L.caq_bytes;
+
+    MOA_TRY_HIP(hipEventRecord(ss->fork, main), "draft_step: fork");
+    MOA_TRY_HIP(hipStreamWaitEvent(side, ss->fork, 0), "draft_step: fork");
+
+    // side branch, part 1: cross-attention query projection
+    AttnBufs cab;
+    cab.qbuf = ws_caq;
+    cab.abuf = ws_main;
+    cab.scratch_p = ws_side;
+    cab.scratch_p_bytes = L.side_bytes;
+    cab.scratch_c = ws_main + L.caq_bytes;
+    cab.scratch_c_bytes = L.main_bytes - L.caq_bytes;
+    const void *caq = nullptr;
+    int32_t rc = attn_stage_project("cross_attn_draft", sh, a->ca_xq, a->B, a->Mq, a->ca_wq, nullptr, nullptr, false,
+                                    nullptr, nullptr, cab, side, &caq);
+    if (rc) return rc;
+    MOA_TRY_HIP(hipEventRecord(ss->caq, side), "draft_step: event");
+
+    // main branch: tree mask, then the LSA chain
+    rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, main);
+    if (rc) return rc;
+    MOA_TRY_HIP(hipEventRecord(ss->tree, main), "draft_step: event");
+    rc = moa_lsa(sh, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, ws_main, L.main_bytes,
+                 main);
+    if (rc) return rc;
+    rc = moa_ca_kv_append(sh, a->lsa_out, a->T_lsa, sh->lsa_q_heads * sh->head_dim, a->tok_off, a->B, a->ca_wk, a->ca_wv,
+                          a->ca_k, a->ca_v, a->ca_len, a->ca_P_cap, a->dev_status, ws_main, L.main_bytes, main);
+    if (rc) return rc;
+
+    // side branch, part 2: the verification layers (need the mask)
+    MOA_TRY_HIP(hipStreamWaitEvent(side, ss->tree, 0), "draft_step: wait");
+    for (int l = 0; l < a->n_verify_layers; ++l) {
+        rc = attention_layer("tree_verify_attn", sh, a->v_x_host[l], a->B, a->M, a->v_wq_host[l], a->v_wk_host[l],
+                             a->v_wv_host[l], a->v_wo_host[l], a->v_kcache_host[l], a->v_vcache_host[l], a->prefix_len,
+                             a->P_cap, a->mask, a->v_out_host[l], a->v_ktree_host[l], a->v_vtree_host[l], a->dev_status,
+                             ws_side, L.side_bytes, side);
+        if (rc) return rc;
+    }
+    MOA_TRY_HIP(hipEventRecord(ss->join, side), "draft_step: event");
+
+    // main branch: cross-attention core + W_o once its queries are there, accept walk, join
+    MOA_TRY_HIP(hipStreamWaitEvent(main, ss->caq, 0), "draft_step: wait");
+    rc = attn_stage_core("cross_attn_draft", sh, caq, a->B, a->Mq, a->ca_wo, a->ca_k, a->ca_v, a->ca_len, a->ca_P_cap,
+                         nullptr, a->ca_out, nullptr, nullptr, a->dev_status, cab, main);
+    if (rc) return rc;
+    rc = moa_tree_accept(a->parent, a->tok, a->tgt, a->B, a->M, a->path, a->n_path, a->bonus, main);
+    if (rc) return rc;
+    MOA_TRY_HIP(hipStreamWaitEvent(main, ss->join, 0), "draft_step: join");
+    return MOA_OK;
+}
+
 int32_t moa_draft_step(const moa_step_args_t *a)
 {
     if (!a) return fail(MOA_ERR_NULL, "draft_step: args is NULL");
@@ -481,6 +642,12 @@ int32_t moa_draft_step(const moa_step_args_t *a)
     int32_t rc = draft_step_stages(a);
     g_dry = false;
     if (rc) return rc;
+    // two-branch schedule when the workspace has room for both branches' scratch; otherwise one after another
+    const StepLayout L = step_layout(a->shape, a->B, a->M, a->Mq, a->P_cap, a->ca_P_cap, a->T_lsa);
+    if (!a->serial && a->ws_bytes >= L.total()) {
+        SideStream *ss = side_stream_for_current_device();
+        if (ss) return draft_step_concurrent(a, ss);
+    }
     return draft_step_stages(a);
 }
 

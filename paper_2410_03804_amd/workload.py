@@ -66,12 +66,20 @@ class DeviceStep:
             nbytes = moa.workspace_bytes(self.shape, B, max(self.P_cap, self.ca_P_cap), M, T)
             ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
         self.ws = ws
+        self._plans = {}
 
-    def run(self, len_slot: int = 0, stream=None):
-        moa.draft_step(self.shape, parent=self.parent, mask=self.mask, depth=self.depth, lsa_hs=self.lsa_hs,
-                       lsa_w=self.lsa_w, lsa_out=self.lsa_out, tok_off=self.tok_off, ca_w=self.ca_w, ca_k=self.ca_k,
-                       ca_v=self.ca_v, ca_len=self.ca_len[len_slot], ca_P_cap=self.ca_P_cap, ca_xq=self.ca_xq,
-                       ca_out=self.ca_out, v_x=self.v_x, v_w=self.v_w, v_kcache=self.v_kcache, v_vcache=self.v_vcache,
-                       v_out=self.v_out, v_ktree=self.v_ktree, v_vtree=self.v_vtree, prefix_len=self.prefix_len,
-                       P_cap=self.P_cap, tok=self.tok, tgt=self.tgt, path=self.path, n_path=self.n_path,
-                       bonus=self.bonus, ws=self.ws, dev_status=self.dev_status, stream=stream)
+    def plan(self, len_slot: int = 0, serial: bool = False):
+        key = (len_slot, serial)
+        if key not in self._plans:
+            self._plans[key] = moa.draft_step_plan(
+                self.shape, parent=self.parent, mask=self.mask, depth=self.depth, lsa_hs=self.lsa_hs, lsa_w=self.lsa_w,
+                lsa_out=self.lsa_out, tok_off=self.tok_off, ca_w=self.ca_w, ca_k=self.ca_k, ca_v=self.ca_v,
+                ca_len=self.ca_len[len_slot], ca_P_cap=self.ca_P_cap, ca_xq=self.ca_xq, ca_out=self.ca_out, v_x=self.v_x,
+                v_w=self.v_w, v_kcache=self.v_kcache, v_vcache=self.v_vcache, v_out=self.v_out, v_ktree=self.v_ktree,
+                v_vtree=self.v_vtree, prefix_len=self.prefix_len, P_cap=self.P_cap, tok=self.tok, tgt=self.tgt,
+                path=self.path, n_path=self.n_path, bonus=self.bonus, ws=self.ws, dev_status=self.dev_status,
+                serial=serial)
+        return self._plans[key]
+
+    def run(self, len_slot: int = 0, stream=None, serial: bool = False):
+        self.plan(len_slot, serial).run(stream)

@@ -65,3 +65,22 @@ def test_draft_step_bad_argument_launches_nothing(G):
     torch.cuda.synchronize()
     assert e.value.status == -6
     assert torch.all(step.mask == -1)                                  # tree_build (the first stage) never ran
+
+
+@pytest.mark.parametrize("case", ["small_bf16", "C1_bf16"])
+def test_two_stream_schedule_is_bit_identical_to_serial(G, case):
+    """The step forks its independent branches onto a second stream; the result must not depend on it."""
+    from paper_2410_03804_amd.workload import DeviceStep
+    cfg, nlayers = STEP_CASES[case]
+    work = mi.step_workload(cfg, n_verify_layers=nlayers)
+    outs = []
+    for serial in (True, False, False):
+        step = DeviceStep(work)
+        step.run(serial=serial)
+        torch.cuda.synchronize()
+        assert step.dev_status.item() == 0
+        outs.append([step.lsa_out.clone(), step.ca_k.clone(), step.ca_out.clone(), step.mask.clone(), step.path.clone(),
+                     *[o.clone() for o in step.v_out], *[o.clone() for o in step.v_ktree]])
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
