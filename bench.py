@@ -37,7 +37,9 @@ def parse():
     ap.add_argument("--sets", type=int, default=3, help="independent buffer sets rotated between steps")
     ap.add_argument("--profile-steps", type=int, default=12, help="untimed steps with events around every kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--serial", action="store_true", help="one stream only (no forked side branch inside the step)")
+    ap.add_argument("--two-stream", action="store_true",
+                    help="fork the step's independent branch onto a second stream (higher throughput; kernels then "
+                         "overlap, so per-kernel durations no longer describe one kernel alone)")
     ap.add_argument("--d-lsa-in", type=int, default=0, help="override the LSA input width (default 2*E_kv)")
     return ap.parse_args()
 
@@ -125,7 +127,7 @@ def main():
     torch.cuda.synchronize()
     torch.cuda.set_stream(stream)
 
-    plans = [sets[i % nsets].plan(len_slot=i // nsets, serial=args.serial) for i in range(total)]
+    plans = [sets[i % nsets].plan(len_slot=i // nsets, two_stream=args.two_stream) for i in range(total)]
 
     def one_step():
         i = counter[0]

@@ -149,11 +149,12 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
  * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk.
  * The *_host members are HOST arrays of n_verify_layers device pointers.
- * Scheduling: the LSA chain feeds only the cross-attention core, so when the workspace has room
- * for two sets of scratch (moa_workspace_bytes asks for it) the cross-attention query projection
- * and the verification layers run on a second, library-owned stream that is forked from and
- * joined back into `stream` with events; ordering as seen from `stream` is unchanged, results are
- * bit-identical to the one-stream schedule. */
+ * Scheduling: by default every stage is enqueued on `stream` in the order above.  The LSA chain
+ * feeds only the cross-attention core, so with two_stream != 0 (and a workspace with room for two
+ * sets of scratch, which moa_workspace_bytes asks for) the cross-attention query projection and
+ * the verification layers run on a second, library-owned stream that is forked from and joined
+ * back into `stream` with events; ordering as seen from `stream` is unchanged and the results
+ * are bit-identical to the one-stream schedule. */
 typedef struct {
     const moa_shape_t *shape;
     int32_t B, M, Mq;
@@ -177,7 +178,7 @@ typedef struct {
     /* accept */
     const int32_t *tok, *tgt;  int32_t *path, *n_path, *bonus;
     int32_t *dev_status;  void *ws;  size_t ws_bytes;  void *stream;
-    int32_t serial;               /* non-zero: never fork a second stream, run the stages one after another */
+    int32_t two_stream;           /* non-zero: fork the independent branch onto a second stream (see above) */
 } moa_step_args_t;
 
 int32_t moa_draft_step(const moa_step_args_t *args);

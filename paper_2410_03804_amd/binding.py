@@ -56,7 +56,7 @@ class _StepArgs(C.Structure):
         ("tok", C.c_void_p), ("tgt", C.c_void_p), ("path", C.c_void_p), ("n_path", C.c_void_p),
         ("bonus", C.c_void_p),
         ("dev_status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t), ("stream", C.c_void_p),
-        ("serial", C.c_int32),
+        ("two_stream", C.c_int32),
     ]
 
 
@@ -236,7 +236,7 @@ def _ptr_array(tensors, dtype, numel, name):
 
 def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len,
                ca_P_cap, ca_xq, ca_out, v_x, v_w, v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, P_cap,
-               tok, tgt, path, n_path, bonus, ws, dev_status=None, serial=False):
+               tok, tgt, path, n_path, bonus, ws, dev_status=None, two_stream=False):
     """Marshal (and size-check) the arguments of moa_draft_step once; the returned plan can be run many times.
     lsa_w = dict(wq, wk, wv, wo); ca_w = dict(wq, wo, wk, wv); v_w = list (one per verified layer) of
     dict(wq, wk, wv, wo); v_* = lists of per-layer tensors.  The plan keeps the tensors alive."""
@@ -295,7 +295,7 @@ def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out
     a.bonus = _dev(bonus, i32, B, "bonus")
     a.dev_status = _dev(dev_status, i32, 1, "dev_status")
     a.ws, a.ws_bytes = _ws(ws)
-    a.serial = 1 if serial else 0
+    a.two_stream = 1 if two_stream else 0
     tensors = [parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
                v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, tok, tgt, path, n_path, bonus, ws, dev_status]
     return StepPlan(a, shape, keep, tensors)
@@ -323,14 +323,13 @@ def draft_step(shape: Shape, *, stream=None, **kw):
 
 
 def profile_kernel_id(name: str) -> int:
-    i = 0
-    while True:
-        n = _lib.moa_profile_kernel_name(i).decode()
-        if n == "?":
-            raise KeyError(name)
-        if n == name:
-            return i
-        i += 1
+    """Id of a kernel name as printed by profile_collect (template variants included)."""
+    if name in _kernel_ids:
+        return _kernel_ids[name]
+    raise KeyError(name)
+
+
+_kernel_ids: dict = {}
 
 
 def profile_enable(on: bool, only_kernel: str | None = None):
@@ -342,5 +341,9 @@ def profile_collect():
     rows = (_ProfileRow * 64)()
     n = _i32(0)
     _check(_lib.moa_profile_collect(rows, 64, C.byref(n)))
-    return [(_lib.moa_profile_site_name(r.site).decode(), _lib.moa_profile_kernel_name(r.kernel).decode(),
-             int(r.launches), float(r.total_ms)) for r in rows[: n.value]]
+    out = []
+    for r in rows[: n.value]:
+        kname = _lib.moa_profile_kernel_name(r.kernel).decode()
+        _kernel_ids[kname] = int(r.kernel)
+        out.append((_lib.moa_profile_site_name(r.site).decode(), kname, int(r.launches), float(r.total_ms)))
+    return out

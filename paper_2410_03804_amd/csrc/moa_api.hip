@@ -644,7 +644,7 @@ int32_t moa_draft_step(const moa_step_args_t *a)
     if (rc) return rc;
     // two-branch schedule when the workspace has room for both branches' scratch; otherwise one after another
     const StepLayout L = step_layout(a->shape, a->B, a->M, a->Mq, a->P_cap, a->ca_P_cap, a->T_lsa);
-    if (!a->serial && a->ws_bytes >= L.total()) {
+    if (a->two_stream && a->ws_bytes >= L.total()) {
         SideStream *ss = side_stream_for_current_device();
         if (ss) return draft_step_concurrent(a, ss);
     }

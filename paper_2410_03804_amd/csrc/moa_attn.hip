@@ -391,11 +391,11 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
         const dim3 grid(g.nsplit, g.rowtiles, a.B * a.Hkv);
         const bool two = (a.H / a.Hkv) * a.Mq > 256;
         if (a.dh == 128) {
-            if (two) { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
-            else { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
+            if (two) { prof_begin(K_ATTN_MFMA + 64 * (128 * 8 + 2), stream); hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
+            else { prof_begin(K_ATTN_MFMA + 64 * (128 * 8 + 1), stream); hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
         } else {
-            if (two) { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
-            else { prof_begin(K_ATTN_MFMA, stream); hipLaunchKernelGGL((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
+            if (two) { prof_begin(K_ATTN_MFMA + 64 * (64 * 8 + 2), stream); hipLaunchKernelGGL((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
+            else { prof_begin(K_ATTN_MFMA + 64 * (64 * 8 + 1), stream); hipLaunchKernelGGL((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -444,7 +444,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             const dim3 grid(t * ka.splits, (unsigned)((a.R + 63) / 64));
             const size_t lds = (size_t)64 * (128 * nq + 8) * sizeof(bf16_t);
             hipError_t e = hipSuccess;
-            prof_begin(K_LIN_SPLITK, stream);
+            prof_begin(K_LIN_SPLITK + 64 * nq, stream);
             switch (nq) {
             case 1: hipLaunchKernelGGL(k_linear_splitk_bf16<1>, grid, dim3(256), lds, stream, ka); break;
             case 2: hipLaunchKernelGGL(k_linear_splitk_bf16<2>, grid, dim3(256), lds, stream, ka); break;

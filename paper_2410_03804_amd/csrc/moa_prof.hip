@@ -4,6 +4,8 @@
 #include "../../include/moa.h"
 #include "moa_common.h"
 
+#include <stdio.h>
+
 #include <mutex>
 #include <vector>
 
@@ -69,7 +71,7 @@ int32_t moa_profile_enable(int32_t on, int32_t only_kernel)
     for (const Rec &r : g_recs) { g_pool.push_back(r.e0); g_pool.push_back(r.e1); }
     g_recs.clear();
     g_on = on != 0;
-    g_only_kernel = (only_kernel >= 0 && only_kernel < K_COUNT) ? only_kernel : -1;
+    g_only_kernel = only_kernel >= 0 ? only_kernel : -1;
     return MOA_OK;
 }
 
@@ -97,7 +99,17 @@ int32_t moa_profile_collect(moa_profile_row_t *rows_host, int32_t max_rows, int3
     return rc;
 }
 
-const char *moa_profile_kernel_name(int32_t kernel) { return (kernel >= 0 && kernel < K_COUNT) ? kKernelNames[kernel] : "?"; }
+// ids are base + 64 * variant; the variant spells the template arguments the way a profiler prints them
+const char *moa_profile_kernel_name(int32_t kernel)
+{
+    static thread_local char buf[96];
+    const int base = kernel & 63, var = kernel >> 6;
+    if (kernel < 0 || base >= K_COUNT) return "?";
+    if (var == 0) return kKernelNames[base];
+    if (base == K_LIN_SPLITK) snprintf(buf, sizeof(buf), "%s<%d>", kKernelNames[base], var);
+    else snprintf(buf, sizeof(buf), "%s<%d, %d>", kKernelNames[base], var >> 3, var & 7);
+    return buf;
+}
 const char *moa_profile_site_name(int32_t site) { return (site >= 0 && site < S_COUNT) ? kSiteNames[site] : "?"; }
 
 }  // extern "C"

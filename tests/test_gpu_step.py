@@ -74,9 +74,9 @@ def test_two_stream_schedule_is_bit_identical_to_serial(G, case):
     cfg, nlayers = STEP_CASES[case]
     work = mi.step_workload(cfg, n_verify_layers=nlayers)
     outs = []
-    for serial in (True, False, False):
+    for two in (False, True, True):
         step = DeviceStep(work)
-        step.run(serial=serial)
+        step.run(two_stream=two)
         torch.cuda.synchronize()
         assert step.dev_status.item() == 0
         outs.append([step.lsa_out.clone(), step.ca_k.clone(), step.ca_out.clone(), step.mask.clone(), step.path.clone(),
