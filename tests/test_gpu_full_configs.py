@@ -1,0 +1,145 @@
+"""Full-size configurations (batched Llama-3-8B, Llama-2-70B shape, 32k-token prefixes): the library runs the
+whole batch in the launch configuration the benchmark uses; the oracle recomputes sampled sequences / tokens
+(every sequence and token is independent of the others, so a sample is exact for what it covers)."""
+import numpy as np
+import pytest
+import torch
+
+import moa_inputs as mi
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+@pytest.fixture(scope="module")
+def moa(G):
+    import paper_2410_03804_amd as m
+    return m
+
+
+def sample_sequences(plen, n):
+    order = np.argsort(plen)
+    pick = {int(order[0]), int(order[-1])}
+    for b in order[len(order) // 2:]:
+        if len(pick) >= n:
+            break
+        pick.add(int(b))
+    return sorted(pick)
+
+
+@pytest.mark.parametrize("name,nseq", [("C2", 3), ("C3", 2), ("C4", 2)])
+def test_tree_verify_full_size(G, moa, oracle, name, nseq):
+    cfg = mi.CONFIGS[name]
+    print(f"[case] tree_verify full {name}: B={cfg.B} M={cfg.M} P<={cfg.P_max} d={cfg.d} H={cfg.H}/{cfg.Hkv}", flush=True)
+    w = mi.verify_weights(cfg)
+    x = mi.verify_inputs(cfg)
+    P_cap = cfg.P_cap
+    kc, vc = mi.kv_cache(cfg, which=0, P_cap=P_cap)
+    plen = mi.prefix_lengths(cfg)
+    parent = mi.trees(cfg)
+    mask_np, _ = oracle.tree_build(parent)
+    shape = G.shape_of(cfg)
+    ws = G.workspace(shape, cfg.B, P_cap, cfg.M, 0)
+    tdt = G.TDT[cfg.dtype]
+    out = torch.empty((cfg.B, cfg.M, cfg.d), dtype=tdt, device="cuda")
+    kt = torch.empty((cfg.B, cfg.Hkv, cfg.M, cfg.dh), dtype=tdt, device="cuda")
+    vt = torch.empty_like(kt)
+    st = G.status_word()
+    mask = torch.zeros((cfg.B, cfg.M, (cfg.M + 63) // 64), dtype=torch.int64, device="cuda")
+    depth = torch.zeros((cfg.B, cfg.M), dtype=torch.int32, device="cuda")
+    moa.tree_build(G.dev(parent), mask, depth, st)
+    print("[step] tree_build launched", flush=True)
+    moa.tree_verify_attn(shape, G.dev(x, cfg.dtype), *(G.dev(w[k], cfg.dtype) for k in ("wq", "wk", "wv", "wo")),
+                         G.dev(kc, cfg.dtype), G.dev(vc, cfg.dtype), G.dev(plen), P_cap, mask, out, kt, vt, ws, st)
+    torch.cuda.synchronize()
+    print("[step] tree_verify_attn done", flush=True)
+    assert st.item() == 0
+    assert np.array_equal(G.mask_u64(mask), mask_np)
+    got, gkt = G.host(out), G.host(kt)
+    for b in sample_sequences(plen, nseq):
+        want, wkt, _ = oracle.tree_verify_attn(x[b:b + 1], w["wq"], w["wk"], w["wv"], w["wo"], kc[b:b + 1], vc[b:b + 1],
+                                               plen[b:b + 1], mask_np[b:b + 1], cfg.H, cfg.Hkv, cfg.dh)
+        G.check_close(gkt[b:b + 1], wkt, cfg.dtype, f"tree_verify.k_tree[{name},b={b},P={plen[b]}]")
+        G.check_close(got[b:b + 1], want, cfg.dtype, f"tree_verify[{name},b={b},P={plen[b]}]")
+
+
+@pytest.mark.parametrize("name,nseq", [("C2", 3), ("C3", 2), ("C4", 2)])
+def test_cross_attn_full_size(G, moa, oracle, name, nseq):
+    cfg = mi.CONFIGS[name]
+    Mq = cfg.M
+    print(f"[case] cross_attn full {name}: B={cfg.B} Mq={Mq} P<={cfg.P_max}", flush=True)
+    w = mi.ca_weights(cfg)
+    xq = mi.ca_queries(cfg, Mq)
+    P_cap = cfg.P_max + 8
+    kc, vc = mi.kv_cache(cfg, which=1000, P_cap=P_cap)
+    ca_len = mi.prefix_lengths(cfg)
+    shape = G.shape_of(cfg)
+    ws = G.workspace(shape, cfg.B, P_cap, Mq, 0)
+    out = torch.empty((cfg.B, Mq, cfg.d), dtype=G.TDT[cfg.dtype], device="cuda")
+    st = G.status_word()
+    moa.cross_attn_draft(shape, G.dev(xq, cfg.dtype), G.dev(w["wq"], cfg.dtype), G.dev(w["wo"], cfg.dtype),
+                         G.dev(kc, cfg.dtype), G.dev(vc, cfg.dtype), G.dev(ca_len), P_cap, out, ws, st)
+    torch.cuda.synchronize()
+    print("[step] cross_attn_draft done", flush=True)
+    assert st.item() == 0
+    got = G.host(out)
+    for b in sample_sequences(ca_len, nseq):
+        want = oracle.cross_attn(xq[b:b + 1], w["wq"], w["wo"], kc[b:b + 1], vc[b:b + 1], ca_len[b:b + 1],
+                                 cfg.H, cfg.Hkv, cfg.dh)
+        G.check_close(got[b:b + 1], want, cfg.dtype, f"cross_attn[{name},b={b},P={ca_len[b]}]")
+
+
+@pytest.mark.parametrize("name,d_in", [("C2", 2048), ("C3", 2048), ("C1", 4096)])
+def test_lsa_full_size_sampled_tokens(G, moa, oracle, name, d_in):
+    """LSA at T = B*M tokens (and the d_in = d reading of the LSA input at the 8B shape); tokens are independent,
+    the oracle recomputes the first and last 24."""
+    cfg = mi.scaled(mi.CONFIGS[name], d_lsa_in=d_in)
+    T = cfg.B * cfg.M
+    print(f"[case] lsa full {name}: T={T} L={cfg.L} d_in={d_in}", flush=True)
+    shape = G.shape_of(cfg)
+    w = mi.lsa_weights(cfg)
+    hs = mi.lsa_inputs(cfg, T)
+    ws = G.workspace(shape, cfg.B, cfg.P_cap, cfg.M, T)
+    out = torch.empty((T, cfg.d_lsa), dtype=G.TDT[cfg.dtype], device="cuda")
+    moa.lsa(shape, G.dev(hs, cfg.dtype), *(G.dev(w[k], cfg.dtype) for k in ("wq", "wk", "wv", "wo")), out, ws)
+    torch.cuda.synchronize()
+    print("[step] lsa done", flush=True)
+    got = G.host(out)
+    idx = np.r_[0:min(24, T), max(T - 24, 0):T]
+    idx = np.unique(idx)
+    want = oracle.lsa(hs[idx], w["wq"], w["wk"], w["wv"], w["wo"], cfg.lsa_heads, cfg.Hkv, cfg.dh)
+    G.check_close(got[idx], want, cfg.dtype, f"lsa[{name},d_in={d_in},T={T}]")
+
+
+def test_ca_kv_append_batched_ragged(G, moa, oracle):
+    """C2-shaped append: 16 sequences, ragged numbers of new rows, all through the split-K projection."""
+    cfg = mi.CONFIGS["C2"]
+    w = mi.ca_weights(cfg)
+    B, P_cap = cfg.B, 96
+    rng = mi.rng_for(cfg, mi.S_LSA, extra=9)
+    counts = rng.integers(0, 9, size=B)
+    tok_off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    T = int(tok_off[-1])
+    mem = mi.normal(rng, (T, cfg.d_lsa), cfg.dtype)
+    kc0, vc0 = mi.kv_cache(cfg, which=1000, P_cap=P_cap)
+    ca_len0 = rng.integers(0, 80, size=B).astype(np.int32)
+    print(f"[case] ca_kv_append C2 T={T}", flush=True)
+    shape = G.shape_of(cfg)
+    kc, vc, ca_len = G.dev(kc0, cfg.dtype), G.dev(vc0, cfg.dtype), G.dev(ca_len0)
+    st = G.status_word()
+    ws = G.workspace(shape, B, P_cap, cfg.M, T)
+    moa.ca_kv_append(shape, G.dev(mem, cfg.dtype), G.dev(tok_off), G.dev(w["wk"], cfg.dtype), G.dev(w["wv"], cfg.dtype),
+                     kc, vc, ca_len, P_cap, st, ws)
+    torch.cuda.synchronize()
+    wk_, wv_, wl = kc0.astype(np.float64), vc0.astype(np.float64), ca_len0.copy()
+    oracle.ca_kv_append(mem, tok_off, w["wk"], w["wv"], wk_, wv_, wl, cfg.Hkv, cfg.dh)
+    assert np.array_equal(ca_len.cpu().numpy(), wl) and st.item() == 0
+    G.check_close(G.host(kc), wk_, cfg.dtype, "ca_kv_append.k[C2]")
+    G.check_close(G.host(vc), wv_, cfg.dtype, "ca_kv_append.v[C2]")
