@@ -41,6 +41,9 @@ def parse():
                     help="fork the step's independent branch onto a second stream (higher throughput; kernels then "
                          "overlap, so per-kernel durations no longer describe one kernel alone)")
     ap.add_argument("--d-lsa-in", type=int, default=0, help="override the LSA input width (default 2*E_kv)")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also run three plain device copies of this many MiB (a kernel of known traffic, to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -160,6 +163,15 @@ def main():
     t1 = time.perf_counter()
     dom_rows = moa.profile_collect()
     moa.profile_enable(False)
+
+    if args.calibrate_copy_mib > 0:
+        n = args.calibrate_copy_mib * (1 << 20)
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     bad = sum(int(s.dev_status.item()) for s in sets)
     if bad:

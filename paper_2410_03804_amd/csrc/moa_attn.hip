@@ -16,6 +16,7 @@
 #include "../../include/moa.h"
 
 #include <math.h>
+#include <stdlib.h>
 
 namespace moa {
 
@@ -119,6 +120,9 @@ struct SplitGeom {
     int rows_pad;   // rowtiles * rows per workgroup
 };
 
+typedef _Float16 f16_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+
 constexpr int KT = 32;        // keys per tile
 constexpr int VLD = KT + 8;   // padded row of the transposed V tile
 
@@ -127,7 +131,7 @@ constexpr int VLD = KT + 8;   // padded row of the transposed V tile
 __device__ __forceinline__ int vpos(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
 
 template <int DH, int NBLK>
-__global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, float *__restrict__ part_o,
+__global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, f16_t *__restrict__ part_o,
                                                    float *__restrict__ part_ml)
 {
     constexpr int KLD = DH + 8;           // padded K row (bf16)
@@ -288,7 +292,9 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, fl
             }
     }
 
-    // partial results of this slice: un-normalised accumulator, running max (log2 domain), running sum
+    // partial results of this slice: the slice's own normalised output (a convex combination of V rows, so it
+    // fits fp16 with 2^-12 relative rounding, eight times finer than the bf16 result), running max (log2 domain)
+    // and running sum in fp32
 #pragma unroll
     for (int blk = 0; blk < NBLK; ++blk) {
         const int rho = rowbase + 32 * blk + l32;
@@ -298,19 +304,21 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, fl
             part_ml[prow * 2 + 0] = mrun[blk];
             part_ml[prow * 2 + 1] = lrun[blk];
         }
+        const float inv = lrun[blk] > 0.f ? 1.0f / lrun[blk] : 0.f;
 #pragma unroll
         for (int d = 0; d < NDB; ++d)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                f32x4 v = {acc[blk][d][4 * q4], acc[blk][d][4 * q4 + 1], acc[blk][d][4 * q4 + 2], acc[blk][d][4 * q4 + 3]};
-                *(f32x4 *)(part_o + prow * DH + 32 * d + 8 * q4 + 4 * half) = v;
+                f16x4 v = {(f16_t)(acc[blk][d][4 * q4] * inv), (f16_t)(acc[blk][d][4 * q4 + 1] * inv),
+                           (f16_t)(acc[blk][d][4 * q4 + 2] * inv), (f16_t)(acc[blk][d][4 * q4 + 3] * inv)};
+                *(f16x4 *)(part_o + prow * DH + 32 * d + 8 * q4 + 4 * half) = v;
             }
     }
 }
 
 // one wavefront per (sequence, query, head)
 template <int DH>
-__global__ __launch_bounds__(64) void k_attn_merge(AttnArgs a, SplitGeom geo, const float *__restrict__ part_o,
+__global__ __launch_bounds__(64) void k_attn_merge(AttnArgs a, SplitGeom geo, const f16_t *__restrict__ part_o,
                                                    const float *__restrict__ part_ml)
 {
     constexpr int CPL = DH / 64;   // components per lane
@@ -321,22 +329,40 @@ __global__ __launch_bounds__(64) void k_attn_merge(AttnArgs a, SplitGeom geo, co
     const int G = a.H / a.Hkv, g = h / G, rho = m * G + (h - g * G);
     const int64_t bg = (int64_t)b * a.Hkv + g;
 
-    float mstar = -INFINITY;
-    for (int s = 0; s < geo.nsplit; ++s)
-        mstar = fmaxf(mstar, part_ml[((bg * geo.nsplit + s) * geo.rows_pad + rho) * 2]);
-    float lsum = 0.f, o[CPL];
+    // slices in groups of eight: all (max, sum) pairs and accumulator rows of a group are requested before any
+    // is used; groups are folded with the usual running-max rescale
+    const int64_t stride = geo.rows_pad;
+    const int64_t prow0 = bg * geo.nsplit * stride + rho;
+    float mstar = -INFINITY, lsum = 0.f, o[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) o[c] = 0.f;
-    if (mstar != -INFINITY) {
-        for (int s = 0; s < geo.nsplit; ++s) {
-            const int64_t prow = (bg * geo.nsplit + s) * geo.rows_pad + rho;
-            const float ms = part_ml[prow * 2];
-            if (ms == -INFINITY) continue;
-            const float w = exp2f(ms - mstar);
-            lsum += w * part_ml[prow * 2 + 1];
+    for (int s0 = 0; s0 < geo.nsplit; s0 += 8) {
+        float ms[8], ls[8], ov[8][CPL];
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) o[c] += w * part_o[prow * DH + lane * CPL + c];
+        for (int u = 0; u < 8; ++u) {
+            const int sidx = min(s0 + u, geo.nsplit - 1);
+            const int64_t prow = prow0 + sidx * stride;
+            ms[u] = (s0 + u < geo.nsplit) ? part_ml[prow * 2] : -INFINITY;
+            ls[u] = part_ml[prow * 2 + 1];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) ov[u][c] = (float)part_o[prow * DH + lane * CPL + c];
         }
+        float gmax = mstar;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) gmax = fmaxf(gmax, ms[u]);
+        if (gmax == -INFINITY) continue;
+        const float keep = exp2f(mstar - gmax);      // 0 on the first non-empty group
+        lsum *= keep;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) o[c] *= keep;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float w = (ms[u] == -INFINITY) ? 0.f : exp2f(ms[u] - gmax) * ls[u];   // slice weight
+            lsum += w;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) o[c] += w * ov[u][c];
+        }
+        mstar = gmax;
     }
     const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
     bf16_t *dst = (bf16_t *)a.out + (((int64_t)b * a.Mq + m) * a.H + h) * DH + lane * CPL;
@@ -354,16 +380,16 @@ static bool mfma_ok(int dtype, int dh, const AttnArgs *a)
     return al(a->q) && al(a->kcache) && al(a->vcache) && al(a->ktree) && al(a->vtree) && al(a->out);
 }
 
-static SplitGeom split_geometry(int B, int Mq, int H, int Hkv, int P_cap)
+static SplitGeom split_geometry(int B, int Mq, int H, int Hkv, int dh, int P_cap, bool tree)
 {
     const int RG = (H / Hkv) * Mq;
-    const int nblk = RG > 256 ? 2 : 1;
+    const int tiles_cap = (P_cap + KT - 1) / KT;
     SplitGeom g;
+    const int nblk = RG > 256 ? 2 : 1;
     g.rowtiles = (RG + 128 * nblk - 1) / (128 * nblk);
     g.rows_pad = g.rowtiles * 128 * nblk;
-    const int tiles_cap = (P_cap + KT - 1) / KT;
     int want = 512 / (B * Hkv * g.rowtiles);        // about two workgroups per compute unit
-    int most = tiles_cap / 4;                        // at least four tiles per slice
+    int most = tiles_cap / 2;                        // at least two tiles per slice
     if (want > most) want = most;
     if (want > 64) want = 64;
     if (want < 1) want = 1;
@@ -374,9 +400,9 @@ static SplitGeom split_geometry(int B, int Mq, int H, int Hkv, int P_cap)
 size_t attn_workspace_bytes(int dtype, int B, int Mq, int H, int Hkv, int dh, int P_cap)
 {
     if (!mfma_ok(dtype, dh, nullptr)) return 0;
-    const SplitGeom g = split_geometry(B, Mq, H, Hkv, P_cap);
+    const SplitGeom g = split_geometry(B, Mq, H, Hkv, dh, P_cap, true);
     const size_t rows = (size_t)B * Hkv * g.nsplit * g.rows_pad;
-    return rows * (size_t)(dh + 2) * sizeof(float) + 256;
+    return rows * ((size_t)dh * sizeof(f16_t) + 2 * sizeof(float)) + 256;
 }
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
@@ -384,10 +410,10 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
     const int nblocks = a.B * a.Mq * a.H;
     if (mfma_ok(a.dtype, a.dh, &a) && a.ws &&
         a.ws_bytes >= attn_workspace_bytes(a.dtype, a.B, a.Mq, a.H, a.Hkv, a.dh, a.P_cap)) {
-        const SplitGeom g = split_geometry(a.B, a.Mq, a.H, a.Hkv, a.P_cap);
+        const SplitGeom g = split_geometry(a.B, a.Mq, a.H, a.Hkv, a.dh, a.P_cap, a.mask != nullptr);
         const size_t rows = (size_t)a.B * a.Hkv * g.nsplit * g.rows_pad;
-        float *part_o = (float *)a.ws;
-        float *part_ml = part_o + rows * a.dh;
+        f16_t *part_o = (f16_t *)a.ws;
+        float *part_ml = (float *)(part_o + rows * a.dh);
         const dim3 grid(g.nsplit, g.rowtiles, a.B * a.Hkv);
         const bool two = (a.H / a.Hkv) * a.Mq > 256;
         if (a.dh == 128) {

@@ -11,6 +11,8 @@
 // so a lane ends up holding consecutive output features of one row (vector stores).
 #include "moa_common.h"
 
+#include <stdlib.h>
+
 namespace moa {
 
 // ------------------------------------------------------------------ generic
@@ -299,11 +301,18 @@ struct TiledArgs {
     int tiles_per_xcd;   // feature tiles owned by one XCD
 };
 
+// WF x WR = 32x32 MFMA blocks per wave along features x rows; the four waves sit 2 x 2, so the workgroup
+// tile is (64 WF) features x (64 WR) rows.  A larger wave tile re-uses each LDS fragment more often:
+// 2x2 needs one 1 KB fragment read per MFMA (that alone saturates the 128 B/clk LDS port at full MFMA
+// rate), 4x2 needs 0.75.
+template <int WF, int WR>
 __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
 {
-    constexpr int BM = 128, BN = 128, BK = 64, LDT = BK + 8;  // LDT: padded LDS row (bf16)
-    __shared__ __attribute__((aligned(16))) bf16_t Ws[2][BN][LDT];
-    __shared__ __attribute__((aligned(16))) bf16_t Xs[2][BM][LDT];
+    constexpr int BN = 64 * WF, BM = 64 * WR, BK = 64, LDT = BK + 8;  // LDT: padded LDS row (bf16)
+    constexpr int NW = BN * 8 / 256, NX = BM * 8 / 256;                // 16-byte chunks per thread per k tile
+    extern __shared__ __attribute__((aligned(16))) bf16_t tsm[];
+    bf16_t(*Ws)[BN][LDT] = (bf16_t(*)[BN][LDT])tsm;                     // [2][BN][LDT]
+    bf16_t(*Xs)[BM][LDT] = (bf16_t(*)[BM][LDT])(tsm + 2 * BN * LDT);    // [2][BM][LDT]
 
     const LinArgs &a = ta.a;
     // Workgroups are handed to the 8 XCDs round-robin (id % 8), and each XCD has its own L2.  Give every
@@ -317,88 +326,105 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
     const int n0 = (ftile - ta.tile_begin[s]) * BN;
     const int64_t r0 = (int64_t)(j / ta.tiles_per_xcd) * BM;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-    const int wf0 = (wave & 1) * 64;   // feature offset of this wave inside the tile
-    const int wr0 = (wave >> 1) * 64;  // row offset
+    const int wf0 = (wave & 1) * (32 * WF);   // feature offset of this wave inside the tile
+    const int wr0 = (wave >> 1) * (32 * WR);  // row offset
     const int K = a.K;
     const bf16_t *W = (const bf16_t *)a.seg[s].W;
     const bf16_t *X = (const bf16_t *)a.X;
 
-    // global -> register staging: 4 x 16 B per operand per thread; 8 lanes cover 128 B of a row
-    const bf16_t *wsrc[4], *xsrc[4];
-    int srow[4], scol[4];
+    // global -> register staging: 8 lanes cover 128 B of a row
+    const int srow = tid >> 3, scol = (tid & 7) * 8;
+    const bf16_t *wsrc[NW], *xsrc[NX];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = tid + 256 * i;
-        srow[i] = c >> 3;
-        scol[i] = (c & 7) * 8;
-        wsrc[i] = W + (int64_t)(n0 + srow[i]) * K + scol[i];
-        int64_t r = r0 + srow[i];
+    for (int i = 0; i < NW; ++i) wsrc[i] = W + (int64_t)(n0 + srow + 32 * i) * K + scol;
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+        int64_t r = r0 + srow + 32 * i;
         if (r > a.R - 1) r = a.R - 1;
-        xsrc[i] = X + r * a.ldx + scol[i];
+        xsrc[i] = X + r * a.ldx + scol;
     }
-    u32x4 wreg[4], xreg[4];
+    u32x4 wreg[NW], xreg[NX];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { wreg[i] = *(const u32x4 *)wsrc[i]; xreg[i] = *(const u32x4 *)xsrc[i]; }
+    for (int i = 0; i < NW; ++i) wreg[i] = *(const u32x4 *)wsrc[i];
+#pragma unroll
+    for (int i = 0; i < NX; ++i) xreg[i] = *(const u32x4 *)xsrc[i];
 
-    f32x16 acc[2][2];
+    f32x16 acc[WF][WR];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WF; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int jj = 0; jj < WR; ++jj)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int e = 0; e < 16; ++e) acc[i][jj][e] = 0.f;
 
     const int nk = K / BK;
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *(u32x4 *)&Ws[buf][srow[i]][scol[i]] = wreg[i];
-            *(u32x4 *)&Xs[buf][srow[i]][scol[i]] = xreg[i];
-        }
+        for (int i = 0; i < NW; ++i) *(u32x4 *)&Ws[buf][srow + 32 * i][scol] = wreg[i];
+#pragma unroll
+        for (int i = 0; i < NX; ++i) *(u32x4 *)&Xs[buf][srow + 32 * i][scol] = xreg[i];
         __syncthreads();   // tile kt visible; everyone is past the reads of tile kt-2 (same buffer)
         if (kt + 1 < nk) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                wreg[i] = *(const u32x4 *)(wsrc[i] + (int64_t)(kt + 1) * BK);
-                xreg[i] = *(const u32x4 *)(xsrc[i] + (int64_t)(kt + 1) * BK);
-            }
+            for (int i = 0; i < NW; ++i) wreg[i] = *(const u32x4 *)(wsrc[i] + (int64_t)(kt + 1) * BK);
+#pragma unroll
+            for (int i = 0; i < NX; ++i) xreg[i] = *(const u32x4 *)(xsrc[i] + (int64_t)(kt + 1) * BK);
         }
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[2], bfr[2];
+            bf16x8 af[WF], bfr[WR];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                af[i] = *(const bf16x8 *)&Ws[buf][wf0 + 32 * i + l32][16 * ks + 8 * half];
-                bfr[i] = *(const bf16x8 *)&Xs[buf][wr0 + 32 * i + l32][16 * ks + 8 * half];
-            }
+            for (int i = 0; i < WF; ++i) af[i] = *(const bf16x8 *)&Ws[buf][wf0 + 32 * i + l32][16 * ks + 8 * half];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < WR; ++i) bfr[i] = *(const bf16x8 *)&Xs[buf][wr0 + 32 * i + l32][16 * ks + 8 * half];
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < WF; ++i)
+#pragma unroll
+                for (int jj = 0; jj < WR; ++jj)
+                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[jj], acc[i][jj], 0, 0, 0);
         }
     }
 
-    // acc[i][j][v]: feature = wf0 + 32 i + 8 (v/4) + 4 half + v%4, row = wr0 + 32 j + l32
+    // acc[i][jj][v]: feature = wf0 + 32 i + 8 (v/4) + 4 half + v%4, row = wr0 + 32 jj + l32
     bf16_t *dst = (bf16_t *)a.seg[s].st.dst;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int64_t r = r0 + wr0 + 32 * j + l32;
+    for (int jj = 0; jj < WR; ++jj) {
+        const int64_t r = r0 + wr0 + 32 * jj + l32;
         if (r >= a.R) continue;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < WF; ++i)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int n = n0 + wf0 + 32 * i + 8 * q + 4 * half;
                 const int64_t off = store_offset(a.seg[s].st, r, n);
                 if (off < 0) continue;
                 u32x2 pk;
-                pk[0] = (uint32_t)f2bf(acc[i][j][4 * q + 0]) | ((uint32_t)f2bf(acc[i][j][4 * q + 1]) << 16);
-                pk[1] = (uint32_t)f2bf(acc[i][j][4 * q + 2]) | ((uint32_t)f2bf(acc[i][j][4 * q + 3]) << 16);
+                pk[0] = (uint32_t)f2bf(acc[i][jj][4 * q + 0]) | ((uint32_t)f2bf(acc[i][jj][4 * q + 1]) << 16);
+                pk[1] = (uint32_t)f2bf(acc[i][jj][4 * q + 2]) | ((uint32_t)f2bf(acc[i][jj][4 * q + 3]) << 16);
                 *(u32x2 *)(dst + off) = pk;
             }
     }
+}
+
+template <int WF, int WR>
+static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
+{
+    constexpr int BN = 64 * WF, BM = 64 * WR;
+    TiledArgs ta;
+    ta.a = a;
+    int t = 0;
+    for (int s = 0; s < a.nseg; ++s) { ta.tile_begin[s] = t; t += a.seg[s].N / BN; }
+    ta.tile_begin[a.nseg] = t;
+    ta.tiles_per_xcd = (t + 7) / 8;
+    const dim3 grid(8u * ta.tiles_per_xcd * (unsigned)((a.R + BM - 1) / BM));
+    const size_t lds = (size_t)2 * (BN + BM) * 72 * sizeof(bf16_t);
+    hipError_t e = hipFuncSetAttribute((const void *)k_linear_tiled_bf16<WF, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    prof_begin(K_LIN_TILED + 64 * (WF * 8 + WR), stream);
+    hipLaunchKernelGGL((k_linear_tiled_bf16<WF, WR>), grid, dim3(256), lds, stream, ta);
+    prof_end(stream);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ dispatch
@@ -417,15 +443,13 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
         bool all128 = true;
         for (int s = 0; s < a.nseg; ++s) all128 = all128 && a.seg[s].N % 128 == 0;
         if (a.R > 128 && all128) {
-            TiledArgs ta;
-            ta.a = a;
-            int t = 0;
-            for (int s = 0; s < a.nseg; ++s) { ta.tile_begin[s] = t; t += a.seg[s].N / 128; }
-            ta.tile_begin[a.nseg] = t;
-            ta.tiles_per_xcd = (t + 7) / 8;
-            dim3 grid(8u * ta.tiles_per_xcd * (unsigned)((a.R + 127) / 128));
-            { prof_begin(K_LIN_TILED, stream); hipLaunchKernelGGL(k_linear_tiled_bf16, grid, dim3(256), 0, stream, ta); prof_end(stream); }
-            return hipGetLastError();
+            bool all256 = true;
+            for (int s = 0; s < a.nseg; ++s) all256 = all256 && a.seg[s].N % 256 == 0;
+            // 2x2 blocks per wave keeps two workgroups per CU; the 4x2 variant halves the LDS traffic per MFMA
+            // but drops to one workgroup per CU and measured slower (MOA_TILE=42 selects it for tuning).
+            const char *force = getenv("MOA_TILE");
+            if (all256 && force && force[0] == '4') return launch_tiled<4, 2>(a, stream);
+            return launch_tiled<2, 2>(a, stream);
         }
         bool all64 = true;
         int ntot = 0;
