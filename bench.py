@@ -26,6 +26,16 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 VEC_F32_PEAK_TFLOPS = 157.3
 
+# HBM bytes per launch (MiB) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the counters read for a
+# plain 512 MiB device copy (fetch x2.000, write x1.000): profiles/c1_draft_step_hbm_traffic_pmc.md.  They hold for
+# the default workload only (C1, 2*E_kv-wide LSA input, one verify layer).
+PMC_TRAFFIC_MIB_C1 = {
+    "k_linear_splitk_bf16<4>": 45.02,
+    "k_linear_splitk_bf16<2>": 12.04,
+    "k_linear_tiled_bf16<2, 2>": 91.67,
+    "k_attn_mfma<128, 1>": 18.32,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -214,6 +224,8 @@ def main():
             ach = flo / (avg_us * 1e-6) / 1e12
             roofline = dict(bound="mfma", achieved=round(ach, 2), peak=peak_mm, unit="TFLOP/s",
                             frac=round(ach / peak_mm, 4), traffic=None)
+        if cfg.name == "C1" and not args.d_lsa_in and NL == 1 and dominant in PMC_TRAFFIC_MIB_C1:
+            roofline["traffic"] = int(PMC_TRAFFIC_MIB_C1[dominant] * 2 ** 20)
         roofline.update(kernel=dominant, sites=sites, avg_launch_us=round(avg_us, 3),
                         launches_per_step=per_step_launches, alg_bytes_per_launch=int(byt),
                         flops_per_launch=int(flo), share_of_kernel_time=round(per_kernel[dominant] / sum(per_kernel.values()), 4))
