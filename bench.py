@@ -47,9 +47,10 @@ def parse():
     ap.add_argument("--sets", type=int, default=3, help="independent buffer sets rotated between steps")
     ap.add_argument("--profile-steps", type=int, default=12, help="untimed steps with events around every kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--two-stream", action="store_true",
-                    help="fork the step's independent branch onto a second stream (higher throughput; kernels then "
-                         "overlap, so per-kernel durations no longer describe one kernel alone)")
+    ap.add_argument("--schedule", choices=list(SCHEDULES), default="grouped",
+                    help="grouped: independent same-shape calls share a launch (default); two-stream: fork the "
+                         "step's independent branch onto a second stream (kernels then overlap, so per-kernel "
+                         "durations no longer describe one kernel alone); sequential: one launch per stage")
     ap.add_argument("--d-lsa-in", type=int, default=0, help="override the LSA input width (default 2*E_kv)")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run three plain device copies of this many MiB (a kernel of known traffic, to scale "
@@ -57,7 +58,10 @@ def parse():
     return ap.parse_args()
 
 
-def site_costs(cfg, n_layers):
+SCHEDULES = {"grouped": 0, "two-stream": 1, "sequential": 2}
+
+
+def site_costs(cfg, n_layers, grouped=False):
     """Algorithmic bytes and flops per launch site for one step: what the call must read and write once
     (inputs, weights, caches, outputs) and 2*MACs of the contractions as defined."""
     es = 2 if cfg.dtype == "bf16" else 4
@@ -84,12 +88,25 @@ def site_costs(cfg, n_layers):
     core_flops_ca = 4.0 * M * H * dh * float(plen.sum())
     c["ca.core"] = dict(bytes=cache_ca + 2 * T * E * es, flops=core_flops_ca)
     c["ca.o_proj"] = lin(T, E, d)
-    c["verify.qkv_proj"] = {k: v * n_layers for k, v in lin(T, d, E + 2 * ekv).items()}
     cache_v = 2.0 * Hkv * dh * es * float(plen.sum()) + 2.0 * B * Hkv * M * dh * es
     core_flops_v = 4.0 * M * H * dh * float((plen + M).sum())
-    c["verify.core"] = dict(bytes=(cache_v + 2 * T * E * es) * n_layers, flops=core_flops_v * n_layers)
-    c["verify.o_proj"] = {k: v * n_layers for k, v in lin(T, E, d).items()}
+    one = {"verify.qkv_proj": lin(T, d, E + 2 * ekv),
+           "verify.core": dict(bytes=cache_v + 2 * T * E * es, flops=core_flops_v),
+           "verify.o_proj": lin(T, E, d)}
     c["tree_accept"] = dict(bytes=B * M * 16 + B * 8, flops=0.0)
+
+    def add(*parts):
+        return dict(bytes=sum(p["bytes"] for p in parts), flops=sum(p["flops"] for p in parts))
+
+    # the grouped schedule launches the first verification layer together with the cross-attention
+    alone = n_layers - 1 if grouped else n_layers
+    for k, v in one.items():
+        c[k] = {kk: vv * alone for kk, vv in v.items()}
+    if grouped:
+        c["tree_build+accept+lengths"] = add(c["tree_build"], c["tree_accept"], c["ca_append.lengths"])
+        c["ca.q_proj+verify.qkv_proj"] = add(c["ca.q_proj"], one["verify.qkv_proj"])
+        c["ca.core+verify.core"] = add(c["ca.core"], one["verify.core"])
+        c["ca.o_proj+verify.o_proj"] = add(c["ca.o_proj"], one["verify.o_proj"])
     return c
 
 
@@ -140,7 +157,7 @@ def main():
     torch.cuda.synchronize()
     torch.cuda.set_stream(stream)
 
-    plans = [sets[i % nsets].plan(len_slot=i // nsets, two_stream=args.two_stream) for i in range(total)]
+    plans = [sets[i % nsets].plan(len_slot=i // nsets, schedule=SCHEDULES[args.schedule]) for i in range(total)]
 
     def one_step():
         i = counter[0]
@@ -192,7 +209,7 @@ def main():
     tokens = cfg.B * cfg.M
     value = tokens / (ms_per_step * 1e-3)
 
-    costs = site_costs(cfg, NL)
+    costs = site_costs(cfg, NL, grouped=args.schedule == "grouped")
     peak_mm = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else VEC_F32_PEAK_TFLOPS
     pieces = []
     for site, kern, n, ms in sorted(rows, key=lambda r: -r[3]):

@@ -149,12 +149,23 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
  * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk.
  * The *_host members are HOST arrays of n_verify_layers device pointers.
- * Scheduling: by default every stage is enqueued on `stream` in the order above.  The LSA chain
- * feeds only the cross-attention core, so with two_stream != 0 (and a workspace with room for two
- * sets of scratch, which moa_workspace_bytes asks for) the cross-attention query projection and
- * the verification layers run on a second, library-owned stream that is forked from and joined
- * back into `stream` with events; ordering as seen from `stream` is unchanged and the results
- * are bit-identical to the one-stream schedule. */
+ * Scheduling (`schedule`), all with the same ordering as seen from `stream`:
+ *  MOA_SCHED_GROUPED (0, default): calls of the step that do not depend on each other and have the
+ *    same shape share a launch: the integer kernels; the CA query projection with the first
+ *    verification layer's Q/K/V projection; the two attention cores; the two output projections.
+ *    Needs Mq == M, n_verify_layers >= 1, non-NULL CA and first-layer weights and the workspace
+ *    moa_workspace_bytes asks for; otherwise the step runs as MOA_SCHED_SEQUENTIAL.  tok[], tgt[]
+ *    and ca_len[] are read at the start of the step, so nothing in the step may produce them.
+ *  MOA_SCHED_TWO_STREAM (1): the LSA chain feeds only the CA core, so the CA query projection and
+ *    the verification layers run on a second, library-owned stream that is forked from and joined
+ *    back into `stream` with events (needs the workspace moa_workspace_bytes asks for).
+ *  MOA_SCHED_SEQUENTIAL (2): every stage enqueued on `stream` in the order above, one launch
+ *    per stage, exactly as the single entry points would.
+ * Integer results are identical under all three; floating-point results of 1 and 2 are
+ * bit-identical, those of 0 differ from them only where the two attention cores end up with a
+ * different number of key slices (partials merged in another order). */
+enum { MOA_SCHED_GROUPED = 0, MOA_SCHED_TWO_STREAM = 1, MOA_SCHED_SEQUENTIAL = 2 };
+
 typedef struct {
     const moa_shape_t *shape;
     int32_t B, M, Mq;
@@ -178,7 +189,7 @@ typedef struct {
     /* accept */
     const int32_t *tok, *tgt;  int32_t *path, *n_path, *bonus;
     int32_t *dev_status;  void *ws;  size_t ws_bytes;  void *stream;
-    int32_t two_stream;           /* non-zero: fork the independent branch onto a second stream (see above) */
+    int32_t schedule;             /* MOA_SCHED_*                                                     */
 } moa_step_args_t;
 
 int32_t moa_draft_step(const moa_step_args_t *args);

@@ -56,9 +56,11 @@ class _StepArgs(C.Structure):
         ("tok", C.c_void_p), ("tgt", C.c_void_p), ("path", C.c_void_p), ("n_path", C.c_void_p),
         ("bonus", C.c_void_p),
         ("dev_status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t), ("stream", C.c_void_p),
-        ("two_stream", C.c_int32),
+        ("schedule", C.c_int32),
     ]
 
+
+SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
@@ -236,7 +238,7 @@ def _ptr_array(tensors, dtype, numel, name):
 
 def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len,
                ca_P_cap, ca_xq, ca_out, v_x, v_w, v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, P_cap,
-               tok, tgt, path, n_path, bonus, ws, dev_status=None, two_stream=False):
+               tok, tgt, path, n_path, bonus, ws, dev_status=None, schedule=0):
     """Marshal (and size-check) the arguments of moa_draft_step once; the returned plan can be run many times.
     lsa_w = dict(wq, wk, wv, wo); ca_w = dict(wq, wo, wk, wv); v_w = list (one per verified layer) of
     dict(wq, wk, wv, wo); v_* = lists of per-layer tensors.  The plan keeps the tensors alive."""
@@ -295,7 +297,7 @@ def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out
     a.bonus = _dev(bonus, i32, B, "bonus")
     a.dev_status = _dev(dev_status, i32, 1, "dev_status")
     a.ws, a.ws_bytes = _ws(ws)
-    a.two_stream = 1 if two_stream else 0
+    a.schedule = int(schedule)
     tensors = [parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
                v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, tok, tgt, path, n_path, bonus, ws, dev_status]
     return StepPlan(a, shape, keep, tensors)

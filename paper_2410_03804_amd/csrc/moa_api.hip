@@ -141,6 +141,35 @@ StepLayout step_layout(const moa_shape_t *s, int B, int M, int Mq, int P_cap, in
     return L;
 }
 
+// workspace split of the grouped step:
+// [old lengths | CA queries | CA heads | verify queries | verify heads | scratch shared by every stage in turn]
+struct GroupLayout {
+    size_t len_bytes, qa, attn_each, scratch;
+    size_t total() const { return len_bytes + 4 * qa + scratch; }
+};
+
+GroupLayout group_layout(const moa_shape_t *s, int B, int M, int P_cap, int ca_P_cap, int64_t T)
+{
+    GroupLayout L;
+    const int e = s->n_q_heads * s->head_dim, ekv = s->n_kv_heads * s->head_dim;
+    const int64_t R = (int64_t)B * M;
+    L.len_bytes = align256((size_t)B * sizeof(int32_t));
+    L.qa = align256((size_t)R * e * esize(s->dtype));
+    const int cap = P_cap > ca_P_cap ? P_cap : ca_P_cap;
+    L.attn_each = align256(attn_workspace_bytes(s->dtype, B, M, s->n_q_heads, s->n_kv_heads, s->head_dim, cap));
+    size_t n = 2 * L.attn_each;
+    n = max2(n, linear_workspace_bytes(s->dtype, R, s->d_model, 2 * e + 2 * ekv));
+    n = max2(n, linear_workspace_bytes(s->dtype, R, e, 2 * s->d_model));
+    n = max2(n, attn_ws_bytes(s, B, M, P_cap));                       // verification layers after the first
+    n = max2(n, attn_ws_bytes(s, B, M, ca_P_cap));
+    if (T > 0) {
+        n = max2(n, lsa_ws_bytes(s, T));
+        n = max2(n, append_ws_bytes(s, T, s->lsa_q_heads * s->head_dim));
+    }
+    L.scratch = align256(n);
+    return L;
+}
+
 int32_t check_ws(const void *ws, size_t have, size_t need)
 {
     if (need == 0) return MOA_OK;
@@ -187,6 +216,7 @@ int32_t moa_workspace_bytes(const moa_shape_t *shape, int32_t B, int32_t P_cap, 
         need = max2(need, append_ws_bytes(shape, T_lsa, shape->d_model));
         // moa_draft_step runs two branches side by side when each can have its own scratch
         need = max2(need, step_layout(shape, B, M, M, P_cap, P_cap, T_lsa).total());
+        need = max2(need, group_layout(shape, B, M, P_cap, P_cap, T_lsa).total());
     }
     *bytes_host = need;
     return MOA_OK;
@@ -407,16 +437,12 @@ static int32_t attn_stage_project(const char *who, const moa_shape_t *shape, con
     return MOA_OK;
 }
 
-static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const void *q, int32_t B, int32_t M,
-                               const void *wo, const void *kcache, const void *vcache, const int32_t *len,
-                               int32_t P_cap, const uint64_t *mask, void *out, void *k_tree, void *v_tree,
-                               int32_t *dev_status, const AttnBufs &bf, hipStream_t st)
+static AttnArgs attn_core_args(const moa_shape_t *shape, const void *q, int32_t B, int32_t M, const void *kcache,
+                               const void *vcache, const int32_t *len, int32_t P_cap, const uint64_t *mask, void *dst,
+                               void *k_tree, void *v_tree, int32_t *dev_status, void *scratch, size_t scratch_bytes)
 {
-    const int dh = shape->head_dim, H = shape->n_q_heads, Hkv = shape->n_kv_heads, d = shape->d_model;
-    const int e = H * dh, dt = shape->dtype;
-    const int64_t R = (int64_t)B * M;
     AttnArgs aa = {};
-    aa.dtype = dt;
+    aa.dtype = shape->dtype;
     aa.q = q;
     aa.kcache = kcache;
     aa.vcache = vcache;
@@ -424,30 +450,51 @@ static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const 
     aa.vtree = mask ? v_tree : nullptr;
     aa.len = len;
     aa.mask = mask;
-    aa.out = wo ? (void *)bf.abuf : out;
+    aa.out = dst;
     aa.B = B;
     aa.Mq = M;
     aa.Mt = mask ? M : 0;
-    aa.H = H;
-    aa.Hkv = Hkv;
-    aa.dh = dh;
+    aa.H = shape->n_q_heads;
+    aa.Hkv = shape->n_kv_heads;
+    aa.dh = shape->head_dim;
     aa.P_cap = P_cap;
     aa.empty_is_error = mask ? 0 : 1;
     aa.dev_status = dev_status;
-    aa.ws = bf.scratch_c;
-    aa.ws_bytes = bf.scratch_c_bytes;
+    aa.ws = scratch;
+    aa.ws_bytes = scratch_bytes;
+    return aa;
+}
+
+static LinSeg oproj_seg(const moa_shape_t *shape, const void *heads, const void *wo, void *out)
+{
+    LinSeg sg = {};
+    sg.W = wo;
+    sg.N = shape->d_model;
+    sg.st = row_store(out, shape->d_model);
+    sg.X = heads;
+    sg.ldx = (int64_t)shape->n_q_heads * shape->head_dim;
+    return sg;
+}
+
+static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const void *q, int32_t B, int32_t M,
+                               const void *wo, const void *kcache, const void *vcache, const int32_t *len,
+                               int32_t P_cap, const uint64_t *mask, void *out, void *k_tree, void *v_tree,
+                               int32_t *dev_status, const AttnBufs &bf, hipStream_t st)
+{
+    const int e = shape->n_q_heads * shape->head_dim, dt = shape->dtype;
+    const AttnArgs aa = attn_core_args(shape, q, B, M, kcache, vcache, len, P_cap, mask, wo ? (void *)bf.abuf : out,
+                                       k_tree, v_tree, dev_status, bf.scratch_c, bf.scratch_c_bytes);
     prof_set_site(mask ? S_VERIFY_CORE : S_CA_CORE);
     MOA_TRY_HIP(launch_attn(aa, st), who);
     if (wo) {
         LinArgs lo = {};
         lo.X = bf.abuf;
-        lo.R = R;
+        lo.R = (int64_t)B * M;
         lo.K = e;
         lo.ldx = e;
         lo.nseg = 1;
-        lo.seg[0].W = wo;
-        lo.seg[0].N = d;
-        lo.seg[0].st = row_store(out, d);
+        lo.seg[0] = oproj_seg(shape, nullptr, wo, out);
+        lo.seg[0].ldx = 0;
         lo.ws = bf.scratch_c;
         lo.ws_bytes = bf.scratch_c_bytes;
         prof_set_site(mask ? S_VERIFY_OPROJ : S_CA_OPROJ);
@@ -539,6 +586,150 @@ static int32_t draft_step_stages(const moa_step_args_t *a)
         if (rc) return rc;
     }
     return moa_tree_accept(a->parent, a->tok, a->tgt, a->B, a->M, a->path, a->n_path, a->bonus, a->stream);
+}
+
+// ---- the step with its independent pieces launched together (default schedule).
+// Two calls that do not depend on each other and have the same shape share one launch: the three integer
+// kernels; the cross-attention query projection with the first verification layer's Q/K/V projection; the two
+// attention cores (and their merges); the two output projections.  At decode sizes each of these kernels is
+// short enough that launch latency and the ramp-up/drain of a grid are a visible part of it, and the two
+// halves of a pair fill the chip better than either alone.  Per-output arithmetic is that of the separate
+// launches (same kernels, same split counts along K).
+static bool can_group(const moa_step_args_t *a)
+{
+    if (a->schedule != MOA_SCHED_GROUPED || a->n_verify_layers < 1 || a->Mq != a->M) return false;
+    if (!a->ca_wq || !a->ca_wo || !a->v_wq_host[0] || !a->v_wk_host[0] || !a->v_wv_host[0] || !a->v_wo_host[0]) return false;
+    return a->ws_bytes >= group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa).total();
+}
+
+static int32_t draft_step_grouped(const moa_step_args_t *a)
+{
+    const moa_shape_t *sh = a->shape;
+    hipStream_t st = (hipStream_t)a->stream;
+    const int dh = sh->head_dim, H = sh->n_q_heads, Hkv = sh->n_kv_heads, d = sh->d_model, dt = sh->dtype;
+    const int e = H * dh, ekv = Hkv * dh, B = a->B, M = a->M;
+    const int64_t R = (int64_t)B * M;
+    const GroupLayout L = group_layout(sh, B, M, a->P_cap, a->ca_P_cap, a->T_lsa);
+    char *p = (char *)a->ws;
+    int32_t *old_len = (int32_t *)p;
+    char *q_ca = p + L.len_bytes, *h_ca = q_ca + L.qa, *q_v = h_ca + L.qa, *h_v = q_v + L.qa, *scr = h_v + L.qa;
+
+    // tree masks, accepted paths, memory lengths (the old lengths are kept for the append below)
+    StepSmallArgs sm = {};
+    sm.parent = a->parent;
+    sm.tok = a->tok;
+    sm.tgt = a->tgt;
+    sm.tok_off = a->tok_off;
+    sm.mask = a->mask;
+    sm.depth = a->depth;
+    sm.path = a->path;
+    sm.n_path = a->n_path;
+    sm.bonus = a->bonus;
+    sm.ca_len = a->ca_len;
+    sm.old_len = old_len;
+    sm.dev_status = a->dev_status;
+    sm.B = B;
+    sm.M = M;
+    sm.cap = a->ca_P_cap;
+    prof_set_site(S_STEP_SMALL);
+    MOA_TRY_HIP(launch_step_small(sm, st), "draft_step: tree/lengths");
+
+    // cross-attention queries + first verification layer's Q/K/V
+    {
+        LinArgs la = {};
+        la.X = a->ca_xq;
+        la.R = R;
+        la.K = d;
+        la.ldx = d;
+        la.ws = scr;
+        la.ws_bytes = L.scratch;
+        la.nseg = 4;
+        la.seg[0].W = a->ca_wq;
+        la.seg[0].N = e;
+        la.seg[0].st = row_store(q_ca, e);
+        la.seg[1].W = a->v_wq_host[0];
+        la.seg[1].N = e;
+        la.seg[1].st = row_store(q_v, e);
+        la.seg[2].W = a->v_wk_host[0];
+        la.seg[2].N = ekv;
+        la.seg[2].st = heads_store(a->v_ktree_host[0], Hkv, dh, M, M);
+        la.seg[3].W = a->v_wv_host[0];
+        la.seg[3].N = ekv;
+        la.seg[3].st = heads_store(a->v_vtree_host[0], Hkv, dh, M, M);
+        for (int i = 1; i < 4; ++i) { la.seg[i].X = a->v_x_host[0]; la.seg[i].ldx = d; }
+        prof_set_site(S_PAIR_QKV);
+        MOA_TRY_HIP(launch_linear(dt, la, st), "draft_step: projections");
+    }
+
+    // layer self-attention, then its rows appended to the memory at the old lengths
+    int32_t rc = moa_lsa(sh, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, scr, L.scratch, st);
+    if (rc) return rc;
+    if (a->T_lsa > 0) {
+        const int d_mem = sh->lsa_q_heads * dh;
+        StoreSpec sp = {};
+        sp.mode = StoreSpec::APPEND;
+        sp.heads = Hkv;
+        sp.dh = dh;
+        sp.cap = a->ca_P_cap;
+        sp.B = B;
+        sp.row_base = old_len;
+        sp.tok_off = a->tok_off;
+        sp.dev_status = a->dev_status;
+        LinArgs la = {};
+        la.X = a->lsa_out;
+        la.R = a->T_lsa;
+        la.K = d_mem;
+        la.ldx = d_mem;
+        la.ws = scr;
+        la.ws_bytes = L.scratch;
+        const void *w[2] = {a->ca_wk, a->ca_wv};
+        void *dst[2] = {a->ca_k, a->ca_v};
+        prof_set_site(S_APPEND_KV);
+        for (int i = 0; i < 2; ++i) {
+            sp.dst = dst[i];
+            if (w[i]) {
+                la.seg[la.nseg].W = w[i];
+                la.seg[la.nseg].N = ekv;
+                la.seg[la.nseg].st = sp;
+                ++la.nseg;
+            } else {
+                MOA_TRY_HIP(launch_scatter_copy(dt, a->lsa_out, a->T_lsa, ekv, d_mem, sp, st), "draft_step: append copy");
+            }
+        }
+        if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "draft_step: append projection");
+    }
+
+    // both attention cores, then both output projections
+    {
+        const AttnArgs ca = attn_core_args(sh, q_ca, B, M, a->ca_k, a->ca_v, a->ca_len, a->ca_P_cap, nullptr, h_ca,
+                                           nullptr, nullptr, a->dev_status, scr, L.attn_each);
+        const AttnArgs ve = attn_core_args(sh, q_v, B, M, a->v_kcache_host[0], a->v_vcache_host[0], a->prefix_len,
+                                           a->P_cap, a->mask, h_v, a->v_ktree_host[0], a->v_vtree_host[0],
+                                           a->dev_status, scr + L.attn_each, L.attn_each);
+        prof_set_site(S_PAIR_CORE);
+        MOA_TRY_HIP(launch_attn_pair(ca, ve, st), "draft_step: attention cores");
+        LinArgs lo = {};
+        lo.X = h_ca;
+        lo.R = R;
+        lo.K = e;
+        lo.ldx = e;
+        lo.ws = scr;
+        lo.ws_bytes = L.scratch;
+        lo.nseg = 2;
+        lo.seg[0] = oproj_seg(sh, h_ca, a->ca_wo, a->ca_out);
+        lo.seg[1] = oproj_seg(sh, h_v, a->v_wo_host[0], a->v_out_host[0]);
+        prof_set_site(S_PAIR_OPROJ);
+        MOA_TRY_HIP(launch_linear(dt, lo, st), "draft_step: output projections");
+    }
+
+    for (int l = 1; l < a->n_verify_layers; ++l) {
+        rc = attention_layer("tree_verify_attn", sh, a->v_x_host[l], B, M, a->v_wq_host[l], a->v_wk_host[l],
+                             a->v_wv_host[l], a->v_wo_host[l], a->v_kcache_host[l], a->v_vcache_host[l], a->prefix_len,
+                             a->P_cap, a->mask, a->v_out_host[l], a->v_ktree_host[l], a->v_vtree_host[l], a->dev_status,
+                             scr, L.scratch, st);
+        if (rc) return rc;
+    }
+    return MOA_OK;
 }
 
 // ---- the step with its independent branches on two streams.
@@ -634,6 +825,7 @@ int32_t moa_draft_step(const moa_step_args_t *a)
     if (!a) return fail(MOA_ERR_NULL, "draft_step: args is NULL");
     if (!a->shape) return fail(MOA_ERR_NULL, "draft_step: shape is NULL");
     if (a->n_verify_layers < 0) return fail(MOA_ERR_SHAPE, "draft_step: n_verify_layers=%d", a->n_verify_layers);
+    if (a->schedule < MOA_SCHED_GROUPED || a->schedule > MOA_SCHED_SEQUENTIAL) return fail(MOA_ERR_SHAPE, "draft_step: schedule=%d", a->schedule);
     if (a->n_verify_layers > 0 &&
         (!a->v_x_host || !a->v_wq_host || !a->v_wk_host || !a->v_wv_host || !a->v_wo_host || !a->v_kcache_host ||
          !a->v_vcache_host || !a->v_out_host || !a->v_ktree_host || !a->v_vtree_host))
@@ -642,12 +834,14 @@ int32_t moa_draft_step(const moa_step_args_t *a)
     int32_t rc = draft_step_stages(a);
     g_dry = false;
     if (rc) return rc;
-    // two-branch schedule when the workspace has room for both branches' scratch; otherwise one after another
+    // grouped launches by default; two streams on request when the workspace has room for both branches'
+    // scratch; otherwise one stage after another
     const StepLayout L = step_layout(a->shape, a->B, a->M, a->Mq, a->P_cap, a->ca_P_cap, a->T_lsa);
-    if (a->two_stream && a->ws_bytes >= L.total()) {
+    if (a->schedule == MOA_SCHED_TWO_STREAM && a->ws_bytes >= L.total()) {
         SideStream *ss = side_stream_for_current_device();
         if (ss) return draft_step_concurrent(a, ss);
     }
+    if (can_group(a)) return draft_step_grouped(a);
     return draft_step_stages(a);
 }
 

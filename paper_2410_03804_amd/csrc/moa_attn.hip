@@ -123,6 +123,12 @@ struct SplitGeom {
 typedef _Float16 f16_t;
 typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 
+// up to two independent calls of the same shape in one launch (blockIdx.z / nbg picks the call)
+struct AttnGroup {
+    AttnArgs a[2];
+    int nbg;   // B * Hkv of one call
+};
+
 constexpr int KT = 32;        // keys per tile
 constexpr int VLD = KT + 8;   // padded row of the transposed V tile
 
@@ -131,9 +137,12 @@ constexpr int VLD = KT + 8;   // padded row of the transposed V tile
 __device__ __forceinline__ int vpos(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
 
 template <int DH, int NBLK>
-__global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, f16_t *__restrict__ part_o,
-                                                   float *__restrict__ part_ml)
+__global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
 {
+    const int call = blockIdx.z / grp.nbg;
+    const AttnArgs &a = grp.a[call];
+    f16_t *__restrict__ part_o = (f16_t *)a.ws;
+    float *__restrict__ part_ml = (float *)(part_o + (size_t)grp.nbg * geo.nsplit * geo.rows_pad * DH);
     constexpr int KLD = DH + 8;           // padded K row (bf16)
     constexpr int NKS = DH / 16;          // MFMA steps along head_dim
     constexpr int NDB = DH / 32;          // 32-wide blocks of head_dim in the output
@@ -144,7 +153,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, f1
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int split = blockIdx.x, rowtile = blockIdx.y;
-    const int bg = blockIdx.z, b = bg / a.Hkv, g = bg % a.Hkv;
+    const int bg = blockIdx.z - call * grp.nbg, b = bg / a.Hkv, g = bg % a.Hkv;
     const int G = a.H / a.Hkv, RG = G * a.Mq, W = (a.Mq + 63) >> 6;
     const float sc = 1.4426950408889634f / sqrtf((float)DH);   // scores are kept in the log2 domain
 
@@ -318,14 +327,18 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnArgs a, SplitGeom geo, f1
 
 // one wavefront per (sequence, query, head)
 template <int DH>
-__global__ __launch_bounds__(64) void k_attn_merge(AttnArgs a, SplitGeom geo, const f16_t *__restrict__ part_o,
-                                                   const float *__restrict__ part_ml)
+__global__ __launch_bounds__(64) void k_attn_merge(AttnGroup grp, SplitGeom geo)
 {
     constexpr int CPL = DH / 64;   // components per lane
     const int lane = threadIdx.x;
-    const int h = blockIdx.x % a.H;
-    const int m = (blockIdx.x / a.H) % a.Mq;
-    const int b = blockIdx.x / (a.H * a.Mq);
+    const int per_call = grp.a[0].B * grp.a[0].Mq * grp.a[0].H;
+    const int call = blockIdx.x / per_call, blk = blockIdx.x - call * per_call;
+    const AttnArgs &a = grp.a[call];
+    const f16_t *__restrict__ part_o = (const f16_t *)a.ws;
+    const float *__restrict__ part_ml = (const float *)(part_o + (size_t)grp.nbg * geo.nsplit * geo.rows_pad * DH);
+    const int h = blk % a.H;
+    const int m = (blk / a.H) % a.Mq;
+    const int b = blk / (a.H * a.Mq);
     const int G = a.H / a.Hkv, g = h / G, rho = m * G + (h - g * G);
     const int64_t bg = (int64_t)b * a.Hkv + g;
 
@@ -405,34 +418,70 @@ size_t attn_workspace_bytes(int dtype, int B, int Mq, int H, int Hkv, int dh, in
     return rows * ((size_t)dh * sizeof(f16_t) + 2 * sizeof(float)) + 256;
 }
 
-hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
+static hipError_t launch_attn_generic(const AttnArgs &a, hipStream_t stream)
 {
     const int nblocks = a.B * a.Mq * a.H;
-    if (mfma_ok(a.dtype, a.dh, &a) && a.ws &&
-        a.ws_bytes >= attn_workspace_bytes(a.dtype, a.B, a.Mq, a.H, a.Hkv, a.dh, a.P_cap)) {
-        const SplitGeom g = split_geometry(a.B, a.Mq, a.H, a.Hkv, a.dh, a.P_cap, a.mask != nullptr);
-        const size_t rows = (size_t)a.B * a.Hkv * g.nsplit * g.rows_pad;
-        f16_t *part_o = (f16_t *)a.ws;
-        float *part_ml = (float *)(part_o + rows * a.dh);
-        const dim3 grid(g.nsplit, g.rowtiles, a.B * a.Hkv);
-        const bool two = (a.H / a.Hkv) * a.Mq > 256;
-        if (a.dh == 128) {
-            if (two) { prof_begin(K_ATTN_MFMA + 64 * (128 * 8 + 2), stream); hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
-            else { prof_begin(K_ATTN_MFMA + 64 * (128 * 8 + 1), stream); hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
-        } else {
-            if (two) { prof_begin(K_ATTN_MFMA + 64 * (64 * 8 + 2), stream); hipLaunchKernelGGL((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
-            else { prof_begin(K_ATTN_MFMA + 64 * (64 * 8 + 1), stream); hipLaunchKernelGGL((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        if (a.dh == 128) { prof_begin(K_ATTN_MERGE, stream); hipLaunchKernelGGL(k_attn_merge<128>, dim3(nblocks), dim3(64), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
-        else { prof_begin(K_ATTN_MERGE, stream); hipLaunchKernelGGL(k_attn_merge<64>, dim3(nblocks), dim3(64), 0, stream, a, g, part_o, part_ml); prof_end(stream); }
-        return hipGetLastError();
-    }
     if (a.dh > 256) return hipErrorInvalidValue;
     if (a.dtype == DT_BF16) { prof_begin(K_ATTN_GENERIC, stream); hipLaunchKernelGGL(k_attn_generic<bf16_t>, dim3(nblocks), dim3(64), 0, stream, a); prof_end(stream); }
     else { prof_begin(K_ATTN_GENERIC, stream); hipLaunchKernelGGL(k_attn_generic<float>, dim3(nblocks), dim3(64), 0, stream, a); prof_end(stream); }
     return hipGetLastError();
+}
+
+static bool attn_fast_ok(const AttnArgs &a, int P_cap_geo)
+{
+    return mfma_ok(a.dtype, a.dh, &a) && a.ws && (((uintptr_t)a.ws) & 15) == 0 &&
+           a.ws_bytes >= attn_workspace_bytes(a.dtype, a.B, a.Mq, a.H, a.Hkv, a.dh, P_cap_geo);
+}
+
+// n = 1 or 2 calls of identical shape (B, Mq, H, Hkv, dh); the slice geometry comes from the larger capacity
+static hipError_t launch_attn_group(const AttnArgs *calls, int n, hipStream_t stream)
+{
+    const AttnArgs &a = calls[0];
+    const int cap = n == 2 && calls[1].P_cap > a.P_cap ? calls[1].P_cap : a.P_cap;
+    const SplitGeom g = split_geometry(a.B, a.Mq, a.H, a.Hkv, a.dh, cap, true);
+    AttnGroup grp;
+    grp.a[0] = calls[0];
+    grp.a[1] = calls[n - 1];
+    grp.nbg = a.B * a.Hkv;
+    const dim3 grid(g.nsplit, g.rowtiles, n * grp.nbg);
+    const int nblocks = n * a.B * a.Mq * a.H;
+    const bool two = (a.H / a.Hkv) * a.Mq > 256;
+    const int var = a.dh * 8 + (two ? 2 : 1);
+    prof_begin(K_ATTN_MFMA + 64 * var, stream);
+    if (a.dh == 128) {
+        if (two) hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, grp, g);
+        else hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, grp, g);
+    } else {
+        if (two) hipLaunchKernelGGL((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, grp, g);
+        else hipLaunchKernelGGL((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, grp, g);
+    }
+    prof_end(stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    prof_begin(K_ATTN_MERGE + 64 * (a.dh * 8), stream);
+    if (a.dh == 128) hipLaunchKernelGGL(k_attn_merge<128>, dim3(nblocks), dim3(64), 0, stream, grp, g);
+    else hipLaunchKernelGGL(k_attn_merge<64>, dim3(nblocks), dim3(64), 0, stream, grp, g);
+    prof_end(stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
+{
+    if (attn_fast_ok(a, a.P_cap)) return launch_attn_group(&a, 1, stream);
+    return launch_attn_generic(a, stream);
+}
+
+hipError_t launch_attn_pair(const AttnArgs &a0, const AttnArgs &a1, hipStream_t stream)
+{
+    const int cap = a0.P_cap > a1.P_cap ? a0.P_cap : a1.P_cap;
+    const bool same = a0.dtype == a1.dtype && a0.B == a1.B && a0.Mq == a1.Mq && a0.H == a1.H && a0.Hkv == a1.Hkv && a0.dh == a1.dh;
+    if (same && attn_fast_ok(a0, cap) && attn_fast_ok(a1, cap)) {
+        const AttnArgs both[2] = {a0, a1};
+        return launch_attn_group(both, 2, stream);
+    }
+    hipError_t e = launch_attn(a0, stream);
+    if (e != hipSuccess) return e;
+    return launch_attn(a1, stream);
 }
 
 }  // namespace moa

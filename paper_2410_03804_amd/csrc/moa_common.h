@@ -77,11 +77,12 @@ __device__ __forceinline__ int64_t store_offset(const StoreSpec &s, int64_t r, i
 // ---- optional per-launch timing (hipEvents around single kernels), used by the benchmark only
 enum KernelId {
     K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_SPLITK, K_LIN_REDUCE, K_LIN_TILED, K_SCATTER,
-    K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_LSA_ATTN_MFMA, K_COUNT
+    K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_LSA_ATTN_MFMA, K_STEP_SMALL, K_COUNT
 };
 enum SiteId {
     S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,
-    S_CA_OPROJ, S_VERIFY_QKV, S_VERIFY_CORE, S_VERIFY_OPROJ, S_TREE_ACCEPT, S_COUNT
+    S_CA_OPROJ, S_VERIFY_QKV, S_VERIFY_CORE, S_VERIFY_OPROJ, S_TREE_ACCEPT, S_STEP_SMALL, S_PAIR_QKV, S_PAIR_CORE,
+    S_PAIR_OPROJ, S_COUNT
 };
 void prof_set_site(int site);
 void prof_begin(int kernel, hipStream_t stream);   // no-ops unless profiling is enabled
@@ -91,6 +92,8 @@ struct LinSeg {
     const void *W;  // [N, K] row-major
     int N;
     StoreSpec st;
+    const void *X;  // this segment's own activations [R, K] (nullptr: LinArgs::X); same R and K for all segments
+    int64_t ldx;
 };
 
 struct LinArgs {
@@ -99,12 +102,12 @@ struct LinArgs {
     int K;
     int64_t ldx;
     int nseg;
-    LinSeg seg[3];
+    LinSeg seg[4];
     void *ws;          // optional scratch for the split-K kernel (linear_workspace_bytes)
     size_t ws_bytes;
 };
 
-// Y_s = X W_s^T for up to three weight matrices that share X (one launch on the fast path).
+// Y_s = X_s W_s^T for up to four weight matrices (one launch on the fast paths; segments usually share X).
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream);
 // scratch the fast weight-streaming path wants for R rows and ntot output features in total (0 = not used)
 size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot);
@@ -120,6 +123,15 @@ hipError_t launch_tree_accept(const int32_t *parent, const int32_t *tok, const i
                               int32_t *path, int32_t *n_path, int32_t *bonus, hipStream_t stream);
 hipError_t launch_append_lengths(const int32_t *tok_off, int B, int32_t *ca_len, int cap, int32_t *dev_status,
                                  hipStream_t stream);
+// tree mask + accept walk + cache length update of one step in a single launch; old_len[B] receives the
+// (clamped) lengths from before the update, which is where the append writes its rows
+struct StepSmallArgs {
+    const int32_t *parent, *tok, *tgt, *tok_off;
+    uint64_t *mask;
+    int32_t *depth, *path, *n_path, *bonus, *ca_len, *old_len, *dev_status;
+    int B, M, cap;
+};
+hipError_t launch_step_small(const StepSmallArgs &a, hipStream_t stream);
 
 // ---- attention core (cross-attention when mask == nullptr / Mt == 0)
 struct AttnArgs {
@@ -140,6 +152,9 @@ struct AttnArgs {
 };
 size_t attn_workspace_bytes(int dtype, int B, int Mq, int H, int Hkv, int dh, int P_cap);
 hipError_t launch_attn(const AttnArgs &a, hipStream_t stream);
+// Two independent cores of the same shape (cross-attention and one verification layer) in one launch; P_cap may
+// differ, each call's ws must hold attn_workspace_bytes for the larger one.  Falls back to two launches.
+hipError_t launch_attn_pair(const AttnArgs &a0, const AttnArgs &a1, hipStream_t stream);
 
 // ---- LSA attention over the layer axis with the mean folded in:
 // abar[t, h*dh + c] = sum_j (1/L sum_i softmax_i(S)[i][j]) V[t, j, g, c]

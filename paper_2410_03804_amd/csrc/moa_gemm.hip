@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void k_linear_generic(const T *__restrict__ X,
 // ------------------------------------------------------------------ skinny bf16 (weight streaming)
 struct SkinnyArgs {
     LinArgs a;
-    int tile_begin[4];  // first feature tile of each segment, tile_begin[nseg] = total
+    int tile_begin[5];  // first feature tile of each segment, tile_begin[nseg] = total
 };
 
 template <int NB>  // 16*NB output features per workgroup
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void k_linear_skinny_bf16(SkinnyArgs sa)
 // (q, j, kg) reads k = 128 q + 32 kg + 8 j, and the X fragment is read from the same place.
 struct SplitKArgs {
     LinArgs a;
-    int tile_begin[4];   // first 64-feature tile of each segment; [nseg] = total tiles
+    int tile_begin[5];   // first 64-feature tile of each segment; [nseg] = total tiles
     int splits;          // K slices
     int ntot;            // total features (all segments), row length of the partial buffer
     float *part;         // [row tiles][splits][64][ntot]
@@ -193,7 +193,8 @@ __global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
     const int n0 = (tile - sa.tile_begin[s]) * 64 + wave * 16;   // feature inside the segment
     const int k0 = split * KS;
     const int64_t r0 = (int64_t)blockIdx.y * 64;
-    const bf16_t *X = (const bf16_t *)a.X;
+    const bf16_t *X = (const bf16_t *)(a.seg[s].X ? a.seg[s].X : a.X);
+    const int64_t ldx = a.seg[s].X ? a.seg[s].ldx : a.ldx;
     const bf16_t *W = (const bf16_t *)a.seg[s].W;
 
     u32x4 xr[XL];
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
         const int c = tid + 256 * i;
         int64_t r = r0 + c / CPR;
         if (r > a.R - 1) r = a.R - 1;          // rows past the end repeat the last row; never stored
-        xr[i] = *(const u32x4 *)(X + r * a.ldx + k0 + 8 * (c % CPR));
+        xr[i] = *(const u32x4 *)(X + r * ldx + k0 + 8 * (c % CPR));
     }
     bf16x8 wf[NQ][4];
     const bf16_t *wp = W + (int64_t)(n0 + li) * a.K + k0 + 32 * kg;
@@ -297,7 +298,7 @@ size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot)
 // ------------------------------------------------------------------ tiled bf16 (many rows)
 struct TiledArgs {
     LinArgs a;
-    int tile_begin[4];
+    int tile_begin[5];
     int tiles_per_xcd;   // feature tiles owned by one XCD
 };
 
@@ -430,10 +431,29 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
 // ------------------------------------------------------------------ dispatch
 static bool aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 
+// only the split-K kernel reads per-segment activations; every other path gets one call per segment
+static hipError_t launch_linear_each(int dtype, const LinArgs &a, hipStream_t stream)
+{
+    for (int s = 0; s < a.nseg; ++s) {
+        LinArgs one = a;
+        one.nseg = 1;
+        one.seg[0] = a.seg[s];
+        if (a.seg[s].X) { one.X = a.seg[s].X; one.ldx = a.seg[s].ldx; }
+        one.seg[0].X = nullptr;
+        hipError_t e = launch_linear(dtype, one, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
 {
     if (a.R <= 0) return hipSuccess;
+    bool own_x = false;
+    for (int s = 0; s < a.nseg; ++s) own_x = own_x || a.seg[s].X != nullptr;
     bool fast = dtype == DT_BF16 && a.K % 128 == 0 && a.ldx % 8 == 0 && aligned16(a.X);
+    for (int s = 0; s < a.nseg && fast; ++s)
+        if (a.seg[s].X) fast = a.seg[s].ldx % 8 == 0 && aligned16(a.seg[s].X);
     for (int s = 0; s < a.nseg && fast; ++s) {
         const StoreSpec &st = a.seg[s].st;
         fast = a.seg[s].N % 32 == 0 && aligned16(a.seg[s].W) && aligned16(st.dst) &&
@@ -442,6 +462,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
     if (fast) {
         bool all128 = true;
         for (int s = 0; s < a.nseg; ++s) all128 = all128 && a.seg[s].N % 128 == 0;
+        if (own_x && (a.R > 128 || !a.ws)) return launch_linear_each(dtype, a, stream);
         if (a.R > 128 && all128) {
             bool all256 = true;
             for (int s = 0; s < a.nseg; ++s) all256 = all256 && a.seg[s].N % 256 == 0;
@@ -488,6 +509,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             prof_end(stream);
             return hipGetLastError();
         }
+        if (own_x) return launch_linear_each(dtype, a, stream);
         SkinnyArgs sa;
         sa.a = a;
         int t = 0;
@@ -497,6 +519,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
         { prof_begin(K_LIN_SKINNY, stream); hipLaunchKernelGGL(k_linear_skinny_bf16<2>, grid, dim3(256), 0, stream, sa); prof_end(stream); }
         return hipGetLastError();
     }
+    if (own_x) return launch_linear_each(dtype, a, stream);
     for (int s = 0; s < a.nseg; ++s) {
         dim3 grid((a.seg[s].N + 63) / 64, (unsigned)((a.R + 63) / 64));
         if (dtype == DT_BF16)

@@ -31,10 +31,11 @@ hipEvent_t take_event()
 
 const char *const kKernelNames[K_COUNT] = {
     "k_tree_build", "k_tree_accept", "k_append_lengths", "k_linear_generic", "k_linear_skinny_bf16", "k_linear_splitk_bf16",
-    "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn", "k_lsa_attn_mfma"};
+    "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn", "k_lsa_attn_mfma", "k_step_small"};
 const char *const kSiteNames[S_COUNT] = {
     "none", "tree_build", "lsa.qkv_proj", "lsa.layer_attn", "lsa.o_proj", "ca_append.kv_proj", "ca_append.lengths",
-    "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept"};
+    "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept",
+    "tree_build+accept+lengths", "ca.q_proj+verify.qkv_proj", "ca.core+verify.core", "ca.o_proj+verify.o_proj"};
 }  // namespace
 
 void prof_set_site(int site) { t_site = site; }
@@ -107,6 +108,7 @@ const char *moa_profile_kernel_name(int32_t kernel)
     if (kernel < 0 || base >= K_COUNT) return "?";
     if (var == 0) return kKernelNames[base];
     if (base == K_LIN_SPLITK) snprintf(buf, sizeof(buf), "%s<%d>", kKernelNames[base], var);
+    else if (base == K_ATTN_MERGE) snprintf(buf, sizeof(buf), "%s<%d>", kKernelNames[base], var >> 3);
     else snprintf(buf, sizeof(buf), "%s<%d, %d>", kKernelNames[base], var >> 3, var & 7);
     return buf;
 }

@@ -68,8 +68,8 @@ class DeviceStep:
         self.ws = ws
         self._plans = {}
 
-    def plan(self, len_slot: int = 0, two_stream: bool = False):
-        key = (len_slot, two_stream)
+    def plan(self, len_slot: int = 0, schedule: int = 0):
+        key = (len_slot, schedule)
         if key not in self._plans:
             self._plans[key] = moa.draft_step_plan(
                 self.shape, parent=self.parent, mask=self.mask, depth=self.depth, lsa_hs=self.lsa_hs, lsa_w=self.lsa_w,
@@ -78,8 +78,8 @@ class DeviceStep:
                 v_w=self.v_w, v_kcache=self.v_kcache, v_vcache=self.v_vcache, v_out=self.v_out, v_ktree=self.v_ktree,
                 v_vtree=self.v_vtree, prefix_len=self.prefix_len, P_cap=self.P_cap, tok=self.tok, tgt=self.tgt,
                 path=self.path, n_path=self.n_path, bonus=self.bonus, ws=self.ws, dev_status=self.dev_status,
-                two_stream=two_stream)
+                schedule=schedule)
         return self._plans[key]
 
-    def run(self, len_slot: int = 0, stream=None, two_stream: bool = False):
-        self.plan(len_slot, two_stream).run(stream)
+    def run(self, len_slot: int = 0, stream=None, schedule: int = 0):
+        self.plan(len_slot, schedule).run(stream)

@@ -24,15 +24,19 @@ STEP_CASES = {
 }
 
 
+SCHEDULES = {"grouped": 0, "two_stream": 1, "sequential": 2}
+
+
+@pytest.mark.parametrize("schedule", ["grouped", "sequential"])
 @pytest.mark.parametrize("case", list(STEP_CASES))
-def test_draft_step_parity(G, oracle, case):
+def test_draft_step_parity(G, oracle, case, schedule):
     from oracle.step import run_step
     from paper_2410_03804_amd.workload import DeviceStep
     cfg, nlayers = STEP_CASES[case]
-    print(f"[case] draft_step {case} B={cfg.B} M={cfg.M} layers={nlayers}", flush=True)
+    print(f"[case] draft_step {case} {schedule} B={cfg.B} M={cfg.M} layers={nlayers}", flush=True)
     work = mi.step_workload(cfg, n_verify_layers=nlayers)
     step = DeviceStep(work)
-    step.run()
+    step.run(schedule=SCHEDULES[schedule])
     torch.cuda.synchronize()
     want = run_step(work)
     dt = cfg.dtype
@@ -67,20 +71,56 @@ def test_draft_step_bad_argument_launches_nothing(G):
     assert torch.all(step.mask == -1)                                  # tree_build (the first stage) never ran
 
 
+def _step_outputs(step):
+    exact = [step.lsa_out, step.ca_k, step.ca_v, step.ca_len[0], step.mask, step.depth, step.path, step.n_path, step.bonus,
+             *step.v_ktree, *step.v_vtree]
+    merged = [step.ca_out, *step.v_out]          # results that pass through the split-KV merge
+    return [t.clone() for t in exact], [t.clone() for t in merged]
+
+
 @pytest.mark.parametrize("case", ["small_bf16", "C1_bf16"])
-def test_two_stream_schedule_is_bit_identical_to_serial(G, case):
-    """The step forks its independent branches onto a second stream; the result must not depend on it."""
+def test_schedules_agree(G, case):
+    """The step's result must not depend on how its independent pieces are launched: the two-stream schedule is
+    bit-identical to the sequential one; the grouped one too, except that the two attention cores may get another
+    number of key slices (their merged outputs then agree to rounding)."""
     from paper_2410_03804_amd.workload import DeviceStep
     cfg, nlayers = STEP_CASES[case]
     work = mi.step_workload(cfg, n_verify_layers=nlayers)
-    outs = []
-    for two in (False, True, True):
+    outs = {}
+    for name in ("sequential", "two_stream", "two_stream", "grouped", "grouped"):
+        print(f"[case] schedules {case} {name}", flush=True)
         step = DeviceStep(work)
-        step.run(two_stream=two)
+        step.run(schedule=SCHEDULES[name])
         torch.cuda.synchronize()
         assert step.dev_status.item() == 0
-        outs.append([step.lsa_out.clone(), step.ca_k.clone(), step.ca_out.clone(), step.mask.clone(), step.path.clone(),
-                     *[o.clone() for o in step.v_out], *[o.clone() for o in step.v_ktree]])
-    for other in outs[1:]:
-        for a, b in zip(outs[0], other):
-            assert torch.equal(a, b)
+        outs.setdefault(name, []).append(_step_outputs(step))
+    ref_exact, ref_merged = outs["sequential"][0]
+    for name, runs in outs.items():
+        for exact, merged in runs:
+            for a, b in zip(ref_exact, exact):
+                assert torch.equal(a, b), name
+            for a, b in zip(ref_merged, merged):
+                if name == "grouped":
+                    assert torch.allclose(a.float(), b.float(), atol=G.ABS_TOL[cfg.dtype], rtol=G.REL_TOL[cfg.dtype]), name
+                else:
+                    assert torch.equal(a, b), name
+    for a, b in zip(outs["grouped"][0][1], outs["grouped"][1][1]):
+        assert torch.equal(a, b)                 # and each schedule is deterministic
+
+
+def test_grouped_schedule_full_memory_flags_and_matches_sequential(G):
+    """A cross-attention memory that cannot take all new rows: both schedules drop the same rows and raise the
+    same device flag."""
+    from paper_2410_03804_amd.workload import DeviceStep
+    cfg, nlayers = STEP_CASES["small_bf16"]
+    work = mi.step_workload(cfg, n_verify_layers=nlayers)
+    res = []
+    for name in ("sequential", "grouped"):
+        step = DeviceStep(work)
+        step.ca_len[0].fill_(step.ca_P_cap - 5)                      # room for 5 of the M new rows per sequence
+        step.run(schedule=SCHEDULES[name])
+        torch.cuda.synchronize()
+        res.append((step.dev_status.item(), _step_outputs(step)))
+    assert res[0][0] == res[1][0] and res[0][0] != 0
+    for a, b in zip(res[0][1][0], res[1][1][0]):
+        assert torch.equal(a, b)
