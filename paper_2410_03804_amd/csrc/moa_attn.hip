@@ -126,7 +126,8 @@ typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 // up to two independent calls of the same shape in one launch (blockIdx.z / nbg picks the call)
 struct AttnGroup {
     AttnArgs a[2];
-    int nbg;   // B * Hkv of one call
+    int nbg;      // B * Hkv of one call
+    int ncalls;   // 1 or 2
 };
 
 constexpr int KT = 32;        // keys per tile
@@ -325,6 +326,252 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
     }
 }
 
+
+// ------------------------------------------------------------------ MFMA, whole key range in one workgroup
+// One workgroup owns 32 query rows of one (sequence, KV head) and ALL of its keys: wave w takes the key tiles
+// w, w + NW, ... with its own running (max, sum, accumulator), and the NW triples are combined through LDS at
+// the end, in wave order, so no partial results go through HBM and no merge kernel follows.  The key loop has
+// no workgroup barrier: each wave stages its tiles in a private LDS buffer.
+//  - Global loads are row-contiguous (16 lanes cover 256 B): the memory pipeline handles one cache line per
+//    lane group per clock, so loads in which every lane touches its own line run at a quarter of the rate.
+//  - K goes to LDS row-major and comes back as MFMA operands (lane = key, 8 head_dim values).
+//  - V goes to LDS row-major too and comes back TRANSPOSED by the LDS transpose read (within 16 lanes, lane i
+//    receives element i%4 of the 8-byte datum addressed by lane i/4 + 4t, t = 0..3): the 16 lanes address 4
+//    keys x 16 head_dim values, and lane i ends up with head_dim i for the 4 keys, which is the operand layout
+//    of O^T += V^T P^T.  Two such reads (keys +0..3 and +8..11 of the lane's half) give the 8 keys that match
+//    the key order of P^T in the score registers.
+// Every row block re-reads the (sequence, KV head)'s K/V, which is why this form is used for short key ranges
+// only; the blocks that share K/V are placed on the same XCD so that the re-reads hit its L2.
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    // LDS traffic of one wavefront is processed in order; this only keeps the compiler from moving a read of
+    // another lane's data above the write that produced it
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int DH, int NW>
+struct FusedLds {
+    static constexpr int KLD = DH + 8;    // K / Q row (bf16): 16-byte operand reads of 16 rows hit 64 different banks
+    static constexpr int VSLD = DH + 32;  // V row: the 4 rows x 2 column groups of a transpose read hit different banks
+    static constexpr int NV = (DH / 32) * 16;
+    static constexpr size_t q_bytes = (size_t)32 * KLD * sizeof(bf16_t);
+    static constexpr size_t stage_bytes = (size_t)32 * VSLD * sizeof(bf16_t);
+    static constexpr size_t loop_bytes = q_bytes + NW * stage_bytes;
+    static constexpr size_t merge_bytes = ((size_t)NW * NV * 64 + 2 * NW * 32) * sizeof(float);
+    static constexpr size_t bytes = loop_bytes > merge_bytes ? loop_bytes : merge_bytes;
+};
+
+template <int DH, int NW>
+__global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
+{
+    using L = FusedLds<DH, NW>;
+    constexpr int KLD = L::KLD, VSLD = L::VSLD;
+    constexpr int NKS = DH / 16;          // MFMA steps along head_dim
+    constexpr int NDB = DH / 32;          // 32-wide blocks of head_dim in the output
+    constexpr int CPK = DH / 8;           // 16-byte pieces per row
+    constexpr int RPI = 64 / CPK;         // rows covered by one load instruction of the wave
+    constexpr int NLD = KT / RPI;         // load instructions per tile
+    constexpr int NV = L::NV;             // accumulator values per lane
+    constexpr int VPW = NV / NW;          // accumulator values each wave finalises
+    static_assert(VPW % 4 == 0, "finalisation stores four head_dim values at a time");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    // workgroup -> (unit, row block): the hardware deals consecutive workgroups round-robin to the 8 XCDs
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int u = xcd + 8 * (slot / nrb), rb = slot - (slot / nrb) * nrb;
+    if (u >= grp.ncalls * grp.nbg) return;          // the whole workgroup leaves before any barrier
+    const int call = u / grp.nbg, bg = u - call * grp.nbg;
+    const AttnArgs &a = grp.a[call];
+    const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+    const int G = a.H / a.Hkv, RG = G * a.Mq, W = (a.Mq + 63) >> 6;
+    const float sc = 1.4426950408889634f / sqrtf((float)DH);   // scores are kept in the log2 domain
+
+    const int len = clamp_len(a.len[b], a.P_cap, tid == 0 ? a.dev_status : nullptr);
+    const int Mt = a.mask ? a.Mt : 0;
+    const int ntc = (len + KT - 1) / KT, nt = ntc + (Mt + KT - 1) / KT;
+
+    const bf16_t *kc = (const bf16_t *)a.kcache + (int64_t)bg * a.P_cap * DH;
+    const bf16_t *vc = (const bf16_t *)a.vcache + (int64_t)bg * a.P_cap * DH;
+    const bf16_t *ktp = (const bf16_t *)a.ktree + (int64_t)bg * a.Mt * DH;
+    const bf16_t *vtp = (const bf16_t *)a.vtree + (int64_t)bg * a.Mt * DH;
+
+    // the K/V tile as the wave loads it: instruction j covers rows RPI j .. RPI j + RPI - 1, 16 bytes per lane
+    const int ld_row = lane / CPK, ld_piece = lane % CPK;
+    u32x4 kreg[NLD], vreg[NLD];
+    auto fetch = [&](int i) {
+        const bool tree = i >= ntc;
+        const int base = tree ? (i - ntc) * KT : i * KT;
+        const int limit = tree ? Mt : len;
+        const bf16_t *ksrc = tree ? ktp : kc;
+        const bf16_t *vsrc = tree ? vtp : vc;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            int row = base + RPI * j + ld_row;
+            if (row > limit - 1) row = limit - 1;              // rows past the end repeat the last valid row
+            const int64_t off = (int64_t)row * DH + 8 * ld_piece;
+            kreg[j] = *(const u32x4 *)(ksrc + off);
+            vreg[j] = *(const u32x4 *)(vsrc + off);
+        }
+    };
+    if (wave < nt) fetch(wave);
+
+    // the block's 32 query rows: loaded once by the workgroup, row-contiguous, then read as MFMA operands
+    bf16_t *Qs = (bf16_t *)smem;
+    for (int c = tid; c < 32 * CPK; c += 64 * NW) {
+        int rho = rb * 32 + c / CPK;
+        if (rho > RG - 1) rho = RG - 1;
+        const int m = rho / G, hh = rho - m * G;
+        const bf16_t *qrow = (const bf16_t *)a.q + (((int64_t)b * a.Mq + m) * a.H + g * G + hh) * DH;
+        *(u32x4 *)&Qs[(c / CPK) * KLD + 8 * (c % CPK)] = *(const u32x4 *)(qrow + 8 * (c % CPK));
+    }
+    __syncthreads();
+    bf16x8 qf[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const bf16x8 *)&Qs[l32 * KLD + 16 * ks + 8 * half];
+
+    int rho = rb * 32 + l32;                        // this lane's query column
+    const bool row_ok = rho < RG;
+    if (!row_ok) rho = RG - 1;
+    const int mrow = rho / G, hh = rho - mrow * G;
+
+    f32x16 acc[NDB];
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[d][e] = 0.f;
+    float mrun = -INFINITY, lrun = 0.f;
+
+    bf16_t *stg = (bf16_t *)(smem + L::q_bytes + wave * L::stage_bytes);   // this wave's tile buffer
+    // transpose read: lane j of a 16-lane group addresses key (j >> 2), head_dim 4 (j & 3) of the group's 16
+    const int tr_off = ((lane & 15) >> 2) * VSLD + 16 * ((lane >> 4) & 1) + 4 * (lane & 3) + 4 * half * VSLD;
+
+    if (wave < nt) {
+        const int last = wave + ((nt - 1 - wave) / NW) * NW;
+        for (int i = wave; i <= last; i += NW) {
+            const bool tree = i >= ntc;
+            const int base = tree ? (i - ntc) * KT : i * KT;
+            const int limit = tree ? Mt : len;
+            // K tile -> LDS -> S^T = K Q^T (keys x queries)
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) *(u32x4 *)&stg[(RPI * j + ld_row) * KLD + 8 * ld_piece] = kreg[j];
+            wave_lds_sync();
+            f32x16 s;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const bf16x8 kf = *(const bf16x8 *)&stg[l32 * KLD + 16 * ks + 8 * half];
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
+            }
+            wave_lds_sync();
+            // V tile into the same buffer, then the next tile's loads (clamped to the wave's last tile: a
+            // repeated load of valid memory whose result is not used) fly during the softmax and the second MFMA
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) *(u32x4 *)&stg[(RPI * j + ld_row) * VSLD + 8 * ld_piece] = vreg[j];
+            wave_lds_sync();
+            fetch(min(i + NW, last));
+
+            uint32_t vis = 0xffffffffu;
+            if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.Mq + mrow) * W + (base >> 6)] >> (base & 63));
+            const int nvalid = limit - base;                   // >= 1
+            if (nvalid < 32) vis &= (1u << nvalid) - 1u;
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = 8 * (v >> 2) + 4 * half + (v & 3);
+                const float x = ((vis >> key) & 1u) ? s[v] * sc : -INFINITY;
+                s[v] = x;
+                tmax = fmaxf(tmax, x);
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            const float mnew = fmaxf(mrun, tmax);
+            const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+            const float corr = exp2f(mrun - msafe);
+            float psum = 0.f;
+            float p[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { p[v] = exp2f(s[v] - msafe); psum += p[v]; }
+            psum += __shfl_xor(psum, 32);
+            lrun = lrun * corr + psum;
+            mrun = mnew;
+            if (__any(corr != 1.0f)) {                          // the running max moved in some column
+#pragma unroll
+                for (int d = 0; d < NDB; ++d)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[d][e] *= corr;
+            }
+            // O^T += V^T P^T; P^T slot t of step st2 is key 16 st2 + 8 (t >> 2) + 4 half + (t & 3)
+#pragma unroll
+            for (int st2 = 0; st2 < 2; ++st2) {
+                bf16x8 pf;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) pf[t] = (__bf16)p[8 * st2 + t];
+#pragma unroll
+                for (int d = 0; d < NDB; ++d) {
+                    const bf16_t *vp = stg + tr_off + 16 * st2 * VSLD + 32 * d;
+                    union { i16x4 h[2]; bf16x8 v; } vf;
+                    vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)vp);
+                    vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(vp + 8 * VSLD));
+                    acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf, acc[d], 0, 0, 0);
+                }
+            }
+            wave_lds_sync();
+        }
+    }
+
+    // combine the waves' triples: out = sum_w 2^(m_w - m*) acc_w / sum_w 2^(m_w - m*) l_w, waves in order
+    __syncthreads();                                            // the tile buffers are dead; their memory is reused
+    float *red = (float *)smem;                                 // [NW][NV][64]
+    float *msh = red + NW * NV * 64;                            // [NW][32]
+    float *lsh = msh + NW * 32;
+    if (half == 0) {
+        msh[wave * 32 + l32] = mrun;
+        lsh[wave * 32 + l32] = lrun;
+    }
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[((wave * NDB + d) * 16 + e) * 64 + lane] = acc[d][e];
+    __syncthreads();
+
+    float wgt[NW], mstar = -INFINITY, lsum = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { wgt[w] = msh[w * 32 + l32]; mstar = fmaxf(mstar, wgt[w]); }
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        wgt[w] = (wgt[w] == -INFINITY) ? 0.f : exp2f(wgt[w] - mstar);
+        lsum += wgt[w] * lsh[w * 32 + l32];
+    }
+    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+    bf16_t *orow = (bf16_t *)a.out + (((int64_t)b * a.Mq + mrow) * a.H + g * G + hh) * DH;
+#pragma unroll
+    for (int t4 = 0; t4 < VPW / 4; ++t4) {
+        const int v0 = wave * VPW + 4 * t4;                     // accumulator values v0 .. v0+3: four consecutive head_dim
+        float o[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) sum += wgt[w] * red[(w * NV + v0 + t) * 64 + lane];
+            o[t] = sum * inv;
+        }
+        const int dcol = 32 * (v0 >> 4) + 8 * ((v0 & 15) >> 2) + 4 * half;
+        if (row_ok) {
+            u32x2 pk;
+            pk[0] = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
+            pk[1] = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
+            *(u32x2 *)(orow + dcol) = pk;
+        }
+    }
+    if (wave == 0 && half == 0 && row_ok && lsum == 0.f && a.empty_is_error && a.dev_status)
+        atomicOr(a.dev_status, MOA_DEV_EMPTY_KEYS);
+}
+
 // one wavefront per (sequence, query, head)
 template <int DH>
 __global__ __launch_bounds__(64) void k_attn_merge(AttnGroup grp, SplitGeom geo)
@@ -427,14 +674,61 @@ static hipError_t launch_attn_generic(const AttnArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-static bool attn_fast_ok(const AttnArgs &a, int P_cap_geo)
+static bool attn_split_ok(const AttnArgs &a, int P_cap_geo)
 {
     return mfma_ok(a.dtype, a.dh, &a) && a.ws && (((uintptr_t)a.ws) & 15) == 0 &&
            a.ws_bytes >= attn_workspace_bytes(a.dtype, a.B, a.Mq, a.H, a.Hkv, a.dh, P_cap_geo);
 }
 
-// n = 1 or 2 calls of identical shape (B, Mq, H, Hkv, dh); the slice geometry comes from the larger capacity
-static hipError_t launch_attn_group(const AttnArgs *calls, int n, hipStream_t stream)
+// Which MFMA kernel: the whole-key-range form re-reads K/V once per 32 query rows (from L2), the split form
+// once per 128 or 256 rows but pays for partial results and a merge; the first wins while the key range is
+// short.  MOA_ATTN=split / fused overrides the choice (tuning and tests).
+constexpr int FUSED_MAX_KEYS = 8192;
+static bool want_fused(const AttnArgs &a)
+{
+    const char *e = getenv("MOA_ATTN");
+    if (e && e[0] == 's') return false;
+    if (e && e[0] == 'f') return true;
+    return a.P_cap + a.Mt <= FUSED_MAX_KEYS;
+}
+
+// n = 1 or 2 calls of identical shape (B, Mq, H, Hkv, dh)
+template <int DH, int NW>
+static hipError_t launch_fused_as(const AttnGroup &grp, int nrb, unsigned grid, hipStream_t stream)
+{
+    constexpr size_t lds = FusedLds<DH, NW>::bytes;
+    static bool raised[16] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 16 || !raised[dev]) {
+        e = hipFuncSetAttribute((const void *)k_attn_fused<DH, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 16) raised[dev] = true;
+    }
+    prof_begin(K_ATTN_FUSED + 64 * (DH * 8 + NW / 4), stream);
+    hipLaunchKernelGGL((k_attn_fused<DH, NW>), dim3(grid), dim3(64 * NW), lds, stream, grp, nrb);
+    prof_end(stream);
+    return hipGetLastError();
+}
+
+static hipError_t launch_attn_fused(const AttnArgs *calls, int n, hipStream_t stream)
+{
+    const AttnArgs &a = calls[0];
+    AttnGroup grp;
+    grp.a[0] = calls[0];
+    grp.a[1] = calls[n - 1];
+    grp.nbg = a.B * a.Hkv;
+    grp.ncalls = n;
+    const int nrb = ((a.H / a.Hkv) * a.Mq + 31) / 32;
+    const int64_t units8 = ((int64_t)n * grp.nbg + 7) / 8;
+    const int64_t grid = 8 * units8 * nrb;
+    if (grid > 0x7fffffff) return hipErrorInvalidValue;
+    if (a.dh == 128) return launch_fused_as<128, 8>(grp, nrb, (unsigned)grid, stream);
+    return launch_fused_as<64, 8>(grp, nrb, (unsigned)grid, stream);
+}
+
+static hipError_t launch_attn_split(const AttnArgs *calls, int n, hipStream_t stream)
 {
     const AttnArgs &a = calls[0];
     const int cap = n == 2 && calls[1].P_cap > a.P_cap ? calls[1].P_cap : a.P_cap;
@@ -443,6 +737,7 @@ static hipError_t launch_attn_group(const AttnArgs *calls, int n, hipStream_t st
     grp.a[0] = calls[0];
     grp.a[1] = calls[n - 1];
     grp.nbg = a.B * a.Hkv;
+    grp.ncalls = n;
     const dim3 grid(g.nsplit, g.rowtiles, n * grp.nbg);
     const int nblocks = n * a.B * a.Mq * a.H;
     const bool two = (a.H / a.Hkv) * a.Mq > 256;
@@ -467,7 +762,8 @@ static hipError_t launch_attn_group(const AttnArgs *calls, int n, hipStream_t st
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
 {
-    if (attn_fast_ok(a, a.P_cap)) return launch_attn_group(&a, 1, stream);
+    if (mfma_ok(a.dtype, a.dh, &a) && want_fused(a)) return launch_attn_fused(&a, 1, stream);
+    if (attn_split_ok(a, a.P_cap)) return launch_attn_split(&a, 1, stream);
     return launch_attn_generic(a, stream);
 }
 
@@ -475,9 +771,11 @@ hipError_t launch_attn_pair(const AttnArgs &a0, const AttnArgs &a1, hipStream_t 
 {
     const int cap = a0.P_cap > a1.P_cap ? a0.P_cap : a1.P_cap;
     const bool same = a0.dtype == a1.dtype && a0.B == a1.B && a0.Mq == a1.Mq && a0.H == a1.H && a0.Hkv == a1.Hkv && a0.dh == a1.dh;
-    if (same && attn_fast_ok(a0, cap) && attn_fast_ok(a1, cap)) {
-        const AttnArgs both[2] = {a0, a1};
-        return launch_attn_group(both, 2, stream);
+    const AttnArgs both[2] = {a0, a1};
+    if (same && mfma_ok(a0.dtype, a0.dh, &a0) && mfma_ok(a1.dtype, a1.dh, &a1)) {
+        if (want_fused(a0) && want_fused(a1)) return launch_attn_fused(both, 2, stream);
+        if (!want_fused(a0) && !want_fused(a1) && attn_split_ok(a0, cap) && attn_split_ok(a1, cap))
+            return launch_attn_split(both, 2, stream);
     }
     hipError_t e = launch_attn(a0, stream);
     if (e != hipSuccess) return e;

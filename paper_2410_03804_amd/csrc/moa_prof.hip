@@ -31,7 +31,7 @@ hipEvent_t take_event()
 
 const char *const kKernelNames[K_COUNT] = {
     "k_tree_build", "k_tree_accept", "k_append_lengths", "k_linear_generic", "k_linear_skinny_bf16", "k_linear_splitk_bf16",
-    "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn", "k_lsa_attn_mfma", "k_step_small"};
+    "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn", "k_lsa_attn_mfma", "k_step_small", "k_attn_fused"};
 const char *const kSiteNames[S_COUNT] = {
     "none", "tree_build", "lsa.qkv_proj", "lsa.layer_attn", "lsa.o_proj", "ca_append.kv_proj", "ca_append.lengths",
     "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept",
@@ -108,6 +108,7 @@ const char *moa_profile_kernel_name(int32_t kernel)
     if (kernel < 0 || base >= K_COUNT) return "?";
     if (var == 0) return kKernelNames[base];
     if (base == K_LIN_SPLITK) snprintf(buf, sizeof(buf), "%s<%d>", kKernelNames[base], var);
+    else if (base == K_ATTN_FUSED) snprintf(buf, sizeof(buf), "%s<%d, %d>", kKernelNames[base], var >> 3, 4 * (var & 7));
     else if (base == K_ATTN_MERGE) snprintf(buf, sizeof(buf), "%s<%d>", kKernelNames[base], var >> 3);
     else snprintf(buf, sizeof(buf), "%s<%d, %d>", kKernelNames[base], var >> 3, var & 7);
     return buf;

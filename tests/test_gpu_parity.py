@@ -169,8 +169,16 @@ def ca_setup(cfg, Mq):
     return w, xq, kc, vc, ca_len, P_cap
 
 
+@pytest.fixture(params=["split", "fused"])
+def attn_kernel(request, monkeypatch):
+    """Both MFMA forms of the attention core (split-KV + merge, whole key range per workgroup) on every case;
+    without the override the library picks by key-range length.  No effect on the generic (fp32, odd head_dim) path."""
+    monkeypatch.setenv("MOA_ATTN", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("case", list(CASES))
-def test_cross_attn_parity(G, moa, oracle, case):
+def test_cross_attn_parity(G, moa, oracle, case, attn_kernel):
     cfg = CASES[case]
     Mq = cfg.M
     w, xq, kc, vc, ca_len, P_cap = ca_setup(cfg, Mq)
@@ -188,7 +196,7 @@ def test_cross_attn_parity(G, moa, oracle, case):
 
 
 @pytest.mark.parametrize("case", list(CASES))
-def test_tree_verify_parity(G, moa, oracle, case):
+def test_tree_verify_parity(G, moa, oracle, case, attn_kernel):
     cfg = CASES[case]
     w = mi.verify_weights(cfg)
     x = mi.verify_inputs(cfg)
@@ -218,7 +226,7 @@ def test_tree_verify_parity(G, moa, oracle, case):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_tree_verify_empty_prefix_and_peaked_scores(G, moa, oracle, dtype):
+def test_tree_verify_empty_prefix_and_peaked_scores(G, moa, oracle, dtype, attn_kernel):
     """prefix_len = 0 (tree-only keys) for one sequence; queries scaled so the softmax is peaked."""
     cfg = small_cfg(dtype, B=2, M=33, D=6, P_max=40, dh=64, H=4, Hkv=2, d=256)
     w = mi.verify_weights(cfg)
@@ -294,7 +302,7 @@ def test_ca_kv_append_overflow_is_flagged_and_clamped(G, moa):
     assert st.item() & moa.DEV_CACHE_FULL
 
 
-def test_cross_attn_empty_memory_is_flagged(G, moa):
+def test_cross_attn_empty_memory_is_flagged(G, moa, attn_kernel):
     cfg = CASES["small_bf16_dh128"]
     w, xq, kc, vc, ca_len, P_cap = ca_setup(cfg, 4)
     ca_len = ca_len.copy()
