@@ -61,7 +61,7 @@ def parse():
 SCHEDULES = {"grouped": 0, "two-stream": 1, "sequential": 2}
 
 
-def site_costs(cfg, n_layers, grouped=False):
+def site_costs(cfg, n_layers, schedule="grouped"):
     """Algorithmic bytes and flops per launch site for one step: what the call must read and write once
     (inputs, weights, caches, outputs) and 2*MACs of the contractions as defined."""
     es = 2 if cfg.dtype == "bf16" else 4
@@ -98,11 +98,13 @@ def site_costs(cfg, n_layers, grouped=False):
     def add(*parts):
         return dict(bytes=sum(p["bytes"] for p in parts), flops=sum(p["flops"] for p in parts))
 
-    # the grouped schedule launches the first verification layer together with the cross-attention
-    alone = n_layers - 1 if grouped else n_layers
+    # grouped: the first verification layer is launched together with the cross-attention; two-stream: only its
+    # projections are (cores and output projections run on different streams)
+    paired = {"grouped": set(one), "two-stream": {"verify.qkv_proj"}}.get(schedule, set())
     for k, v in one.items():
+        alone = n_layers - 1 if k in paired else n_layers
         c[k] = {kk: vv * alone for kk, vv in v.items()}
-    if grouped:
+    if paired:
         c["tree_build+accept+lengths"] = add(c["tree_build"], c["tree_accept"], c["ca_append.lengths"])
         c["ca.q_proj+verify.qkv_proj"] = add(c["ca.q_proj"], one["verify.qkv_proj"])
         c["ca.core+verify.core"] = add(c["ca.core"], one["verify.core"])
@@ -209,7 +211,7 @@ def main():
     tokens = cfg.B * cfg.M
     value = tokens / (ms_per_step * 1e-3)
 
-    costs = site_costs(cfg, NL, grouped=args.schedule == "grouped")
+    costs = site_costs(cfg, NL, schedule=args.schedule)
     peak_mm = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else VEC_F32_PEAK_TFLOPS
     pieces = []
     for site, kern, n, ms in sorted(rows, key=lambda r: -r[3]):

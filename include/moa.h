@@ -156,9 +156,10 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
  *    Needs Mq == M, n_verify_layers >= 1, non-NULL CA and first-layer weights and the workspace
  *    moa_workspace_bytes asks for; otherwise the step runs as MOA_SCHED_SEQUENTIAL.  tok[], tgt[]
  *    and ca_len[] are read at the start of the step, so nothing in the step may produce them.
- *  MOA_SCHED_TWO_STREAM (1): the LSA chain feeds only the CA core, so the CA query projection and
- *    the verification layers run on a second, library-owned stream that is forked from and joined
- *    back into `stream` with events (needs the workspace moa_workspace_bytes asks for).
+ *  MOA_SCHED_TWO_STREAM (1): the LSA chain feeds only the CA core, so the projections (grouped as
+ *    above) and the verification layers run on a second, library-owned stream that is forked from
+ *    and joined back into `stream` with events, beside the LSA chain and the CA core on `stream`.
+ *    Same requirements as MOA_SCHED_GROUPED.
  *  MOA_SCHED_SEQUENTIAL (2): every stage enqueued on `stream` in the order above, one launch
  *    per stage, exactly as the single entry points would.
  * Integer results are identical under all three; floating-point results of 1 and 2 are

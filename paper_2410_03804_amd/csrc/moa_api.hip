@@ -120,27 +120,6 @@ size_t append_ws_bytes(const moa_shape_t *s, int64_t T, int d_mem)
     return align256(max2(linear_workspace_bytes(s->dtype, T, d_mem, 2 * ekv), linear_workspace_bytes(s->dtype, T, d_mem, ekv)));
 }
 
-// workspace split of the two-branch step: [main branch | cross-attention queries | side branch]
-struct StepLayout {
-    size_t main_bytes, caq_bytes, side_bytes;
-    size_t total() const { return main_bytes + caq_bytes + side_bytes; }
-};
-
-StepLayout step_layout(const moa_shape_t *s, int B, int M, int Mq, int P_cap, int ca_P_cap, int64_t T)
-{
-    StepLayout L;
-    const size_t qa = align256((size_t)B * Mq * s->n_q_heads * s->head_dim * esize(s->dtype));
-    size_t m = qa + attn_scratch_bytes(s, B, Mq, ca_P_cap, false);          // CA core + W_o: abuf + scratch
-    if (T > 0) {
-        m = max2(m, lsa_ws_bytes(s, T));
-        m = max2(m, append_ws_bytes(s, T, s->lsa_q_heads * s->head_dim));
-    }
-    L.main_bytes = align256(m);
-    L.caq_bytes = qa;                                                        // CA queries: written by the side branch
-    L.side_bytes = align256(max2(attn_ws_bytes(s, B, M, P_cap), attn_scratch_bytes(s, B, Mq, ca_P_cap, false)));
-    return L;
-}
-
 // workspace split of the grouped step:
 // [old lengths | CA queries | CA heads | verify queries | verify heads | scratch shared by every stage in turn]
 struct GroupLayout {
@@ -214,9 +193,9 @@ int32_t moa_workspace_bytes(const moa_shape_t *shape, int32_t B, int32_t P_cap, 
         need = max2(need, lsa_ws_bytes(shape, T_lsa));
         need = max2(need, append_ws_bytes(shape, T_lsa, shape->lsa_q_heads * shape->head_dim));
         need = max2(need, append_ws_bytes(shape, T_lsa, shape->d_model));
-        // moa_draft_step runs two branches side by side when each can have its own scratch
-        need = max2(need, step_layout(shape, B, M, M, P_cap, P_cap, T_lsa).total());
-        need = max2(need, group_layout(shape, B, M, P_cap, P_cap, T_lsa).total());
+        // moa_draft_step: grouped buffers, plus a second scratch region when it runs two branches side by side
+        const GroupLayout L = group_layout(shape, B, M, P_cap, P_cap, T_lsa);
+        need = max2(need, L.total() + L.scratch);
     }
     *bytes_host = need;
     return MOA_OK;
@@ -588,33 +567,28 @@ static int32_t draft_step_stages(const moa_step_args_t *a)
     return moa_tree_accept(a->parent, a->tok, a->tgt, a->B, a->M, a->path, a->n_path, a->bonus, a->stream);
 }
 
-// ---- the step with its independent pieces launched together (default schedule).
+// ---- the step with its independent pieces launched together.
 // Two calls that do not depend on each other and have the same shape share one launch: the three integer
 // kernels; the cross-attention query projection with the first verification layer's Q/K/V projection; the two
-// attention cores (and their merges); the two output projections.  At decode sizes each of these kernels is
-// short enough that launch latency and the ramp-up/drain of a grid are a visible part of it, and the two
-// halves of a pair fill the chip better than either alone.  Per-output arithmetic is that of the separate
-// launches (same kernels, same split counts along K).
-static bool can_group(const moa_step_args_t *a)
+// attention cores; the two output projections.  At decode sizes each of these kernels is short enough that
+// launch latency and the ramp-up/drain of a grid are a visible part of it, and the two halves of a pair fill
+// the chip better than either alone.  Per-output arithmetic is that of the separate launches (same kernels,
+// same split counts along K).  The pieces below are shared by the one-stream (grouped) and the two-stream
+// schedule.
+struct StepBufs {
+    int32_t *old_len;              // memory lengths before this step's append
+    char *q_ca, *h_ca, *q_v, *h_v; // projected queries / concatenated heads of the CA and of verification layer 0
+};
+
+static bool pieces_ok(const moa_step_args_t *a)
 {
-    if (a->schedule != MOA_SCHED_GROUPED || a->n_verify_layers < 1 || a->Mq != a->M) return false;
-    if (!a->ca_wq || !a->ca_wo || !a->v_wq_host[0] || !a->v_wk_host[0] || !a->v_wv_host[0] || !a->v_wo_host[0]) return false;
-    return a->ws_bytes >= group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa).total();
+    if (a->n_verify_layers < 1 || a->Mq != a->M) return false;
+    return a->ca_wq && a->ca_wo && a->v_wq_host[0] && a->v_wk_host[0] && a->v_wv_host[0] && a->v_wo_host[0];
 }
 
-static int32_t draft_step_grouped(const moa_step_args_t *a)
+// tree masks, accepted paths, memory lengths (the old lengths are kept for the append)
+static int32_t piece_small(const moa_step_args_t *a, const StepBufs &bf, hipStream_t st)
 {
-    const moa_shape_t *sh = a->shape;
-    hipStream_t st = (hipStream_t)a->stream;
-    const int dh = sh->head_dim, H = sh->n_q_heads, Hkv = sh->n_kv_heads, d = sh->d_model, dt = sh->dtype;
-    const int e = H * dh, ekv = Hkv * dh, B = a->B, M = a->M;
-    const int64_t R = (int64_t)B * M;
-    const GroupLayout L = group_layout(sh, B, M, a->P_cap, a->ca_P_cap, a->T_lsa);
-    char *p = (char *)a->ws;
-    int32_t *old_len = (int32_t *)p;
-    char *q_ca = p + L.len_bytes, *h_ca = q_ca + L.qa, *q_v = h_ca + L.qa, *h_v = q_v + L.qa, *scr = h_v + L.qa;
-
-    // tree masks, accepted paths, memory lengths (the old lengths are kept for the append below)
     StepSmallArgs sm = {};
     sm.parent = a->parent;
     sm.tok = a->tok;
@@ -626,122 +600,183 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
     sm.n_path = a->n_path;
     sm.bonus = a->bonus;
     sm.ca_len = a->ca_len;
-    sm.old_len = old_len;
+    sm.old_len = bf.old_len;
     sm.dev_status = a->dev_status;
-    sm.B = B;
-    sm.M = M;
+    sm.B = a->B;
+    sm.M = a->M;
     sm.cap = a->ca_P_cap;
     prof_set_site(S_STEP_SMALL);
     MOA_TRY_HIP(launch_step_small(sm, st), "draft_step: tree/lengths");
+    return MOA_OK;
+}
 
-    // cross-attention queries + first verification layer's Q/K/V
-    {
-        LinArgs la = {};
-        la.X = a->ca_xq;
-        la.R = R;
-        la.K = d;
-        la.ldx = d;
-        la.ws = scr;
-        la.ws_bytes = L.scratch;
-        la.nseg = 4;
-        la.seg[0].W = a->ca_wq;
-        la.seg[0].N = e;
-        la.seg[0].st = row_store(q_ca, e);
-        la.seg[1].W = a->v_wq_host[0];
-        la.seg[1].N = e;
-        la.seg[1].st = row_store(q_v, e);
-        la.seg[2].W = a->v_wk_host[0];
-        la.seg[2].N = ekv;
-        la.seg[2].st = heads_store(a->v_ktree_host[0], Hkv, dh, M, M);
-        la.seg[3].W = a->v_wv_host[0];
-        la.seg[3].N = ekv;
-        la.seg[3].st = heads_store(a->v_vtree_host[0], Hkv, dh, M, M);
-        for (int i = 1; i < 4; ++i) { la.seg[i].X = a->v_x_host[0]; la.seg[i].ldx = d; }
-        prof_set_site(S_PAIR_QKV);
-        MOA_TRY_HIP(launch_linear(dt, la, st), "draft_step: projections");
-    }
+// cross-attention queries + first verification layer's Q/K/V in one launch
+static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st)
+{
+    const moa_shape_t *sh = a->shape;
+    const int dh = sh->head_dim, Hkv = sh->n_kv_heads, d = sh->d_model, M = a->M;
+    const int e = sh->n_q_heads * dh, ekv = Hkv * dh;
+    LinArgs la = {};
+    la.X = a->ca_xq;
+    la.R = (int64_t)a->B * M;
+    la.K = d;
+    la.ldx = d;
+    la.ws = scr;
+    la.ws_bytes = scr_bytes;
+    la.nseg = 4;
+    la.seg[0].W = a->ca_wq;
+    la.seg[0].N = e;
+    la.seg[0].st = row_store(bf.q_ca, e);
+    la.seg[1].W = a->v_wq_host[0];
+    la.seg[1].N = e;
+    la.seg[1].st = row_store(bf.q_v, e);
+    la.seg[2].W = a->v_wk_host[0];
+    la.seg[2].N = ekv;
+    la.seg[2].st = heads_store(a->v_ktree_host[0], Hkv, dh, M, M);
+    la.seg[3].W = a->v_wv_host[0];
+    la.seg[3].N = ekv;
+    la.seg[3].st = heads_store(a->v_vtree_host[0], Hkv, dh, M, M);
+    for (int i = 1; i < 4; ++i) { la.seg[i].X = a->v_x_host[0]; la.seg[i].ldx = d; }
+    prof_set_site(S_PAIR_QKV);
+    MOA_TRY_HIP(launch_linear(sh->dtype, la, st), "draft_step: projections");
+    return MOA_OK;
+}
 
-    // layer self-attention, then its rows appended to the memory at the old lengths
-    int32_t rc = moa_lsa(sh, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, scr, L.scratch, st);
-    if (rc) return rc;
-    if (a->T_lsa > 0) {
-        const int d_mem = sh->lsa_q_heads * dh;
-        StoreSpec sp = {};
-        sp.mode = StoreSpec::APPEND;
-        sp.heads = Hkv;
-        sp.dh = dh;
-        sp.cap = a->ca_P_cap;
-        sp.B = B;
-        sp.row_base = old_len;
-        sp.tok_off = a->tok_off;
-        sp.dev_status = a->dev_status;
-        LinArgs la = {};
-        la.X = a->lsa_out;
-        la.R = a->T_lsa;
-        la.K = d_mem;
-        la.ldx = d_mem;
-        la.ws = scr;
-        la.ws_bytes = L.scratch;
-        const void *w[2] = {a->ca_wk, a->ca_wv};
-        void *dst[2] = {a->ca_k, a->ca_v};
-        prof_set_site(S_APPEND_KV);
-        for (int i = 0; i < 2; ++i) {
-            sp.dst = dst[i];
-            if (w[i]) {
-                la.seg[la.nseg].W = w[i];
-                la.seg[la.nseg].N = ekv;
-                la.seg[la.nseg].st = sp;
-                ++la.nseg;
-            } else {
-                MOA_TRY_HIP(launch_scatter_copy(dt, a->lsa_out, a->T_lsa, ekv, d_mem, sp, st), "draft_step: append copy");
-            }
+// layer self-attention, then its rows appended to the memory at the old lengths
+static int32_t piece_lsa_append(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st)
+{
+    const moa_shape_t *sh = a->shape;
+    const int dh = sh->head_dim, Hkv = sh->n_kv_heads, ekv = Hkv * dh, dt = sh->dtype;
+    int32_t rc = moa_lsa(sh, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, scr, scr_bytes, st);
+    if (rc || a->T_lsa <= 0) return rc;
+    const int d_mem = sh->lsa_q_heads * dh;
+    StoreSpec sp = {};
+    sp.mode = StoreSpec::APPEND;
+    sp.heads = Hkv;
+    sp.dh = dh;
+    sp.cap = a->ca_P_cap;
+    sp.B = a->B;
+    sp.row_base = bf.old_len;
+    sp.tok_off = a->tok_off;
+    sp.dev_status = a->dev_status;
+    LinArgs la = {};
+    la.X = a->lsa_out;
+    la.R = a->T_lsa;
+    la.K = d_mem;
+    la.ldx = d_mem;
+    la.ws = scr;
+    la.ws_bytes = scr_bytes;
+    const void *w[2] = {a->ca_wk, a->ca_wv};
+    void *dst[2] = {a->ca_k, a->ca_v};
+    prof_set_site(S_APPEND_KV);
+    for (int i = 0; i < 2; ++i) {
+        sp.dst = dst[i];
+        if (w[i]) {
+            la.seg[la.nseg].W = w[i];
+            la.seg[la.nseg].N = ekv;
+            la.seg[la.nseg].st = sp;
+            ++la.nseg;
+        } else {
+            MOA_TRY_HIP(launch_scatter_copy(dt, a->lsa_out, a->T_lsa, ekv, d_mem, sp, st), "draft_step: append copy");
         }
-        if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "draft_step: append projection");
     }
+    if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "draft_step: append projection");
+    return MOA_OK;
+}
 
-    // both attention cores, then both output projections
-    {
-        const AttnArgs ca = attn_core_args(sh, q_ca, B, M, a->ca_k, a->ca_v, a->ca_len, a->ca_P_cap, nullptr, h_ca,
-                                           nullptr, nullptr, a->dev_status, scr, L.attn_each);
-        const AttnArgs ve = attn_core_args(sh, q_v, B, M, a->v_kcache_host[0], a->v_vcache_host[0], a->prefix_len,
-                                           a->P_cap, a->mask, h_v, a->v_ktree_host[0], a->v_vtree_host[0],
-                                           a->dev_status, scr + L.attn_each, L.attn_each);
-        prof_set_site(S_PAIR_CORE);
-        MOA_TRY_HIP(launch_attn_pair(ca, ve, st), "draft_step: attention cores");
-        LinArgs lo = {};
-        lo.X = h_ca;
-        lo.R = R;
-        lo.K = e;
-        lo.ldx = e;
-        lo.ws = scr;
-        lo.ws_bytes = L.scratch;
-        lo.nseg = 2;
-        lo.seg[0] = oproj_seg(sh, h_ca, a->ca_wo, a->ca_out);
-        lo.seg[1] = oproj_seg(sh, h_v, a->v_wo_host[0], a->v_out_host[0]);
-        prof_set_site(S_PAIR_OPROJ);
-        MOA_TRY_HIP(launch_linear(dt, lo, st), "draft_step: output projections");
-    }
+static AttnArgs piece_ca_core_args(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes)
+{
+    return attn_core_args(a->shape, bf.q_ca, a->B, a->M, a->ca_k, a->ca_v, a->ca_len, a->ca_P_cap, nullptr, bf.h_ca,
+                          nullptr, nullptr, a->dev_status, scr, scr_bytes);
+}
 
+static AttnArgs piece_verify_core_args(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes)
+{
+    return attn_core_args(a->shape, bf.q_v, a->B, a->M, a->v_kcache_host[0], a->v_vcache_host[0], a->prefix_len,
+                          a->P_cap, a->mask, bf.h_v, a->v_ktree_host[0], a->v_vtree_host[0], a->dev_status, scr,
+                          scr_bytes);
+}
+
+// output projections: which = 1 (cross-attention), 2 (verification layer 0) or 3 (both in one launch)
+static int32_t piece_oproj(const moa_step_args_t *a, const StepBufs &bf, int which, void *scr, size_t scr_bytes, hipStream_t st)
+{
+    const moa_shape_t *sh = a->shape;
+    const int e = sh->n_q_heads * sh->head_dim;
+    LinArgs lo = {};
+    lo.R = (int64_t)a->B * a->M;
+    lo.K = e;
+    lo.ldx = e;
+    lo.ws = scr;
+    lo.ws_bytes = scr_bytes;
+    if (which & 1) lo.seg[lo.nseg++] = oproj_seg(sh, bf.h_ca, a->ca_wo, a->ca_out);
+    if (which & 2) lo.seg[lo.nseg++] = oproj_seg(sh, bf.h_v, a->v_wo_host[0], a->v_out_host[0]);
+    lo.X = lo.seg[0].X;
+    prof_set_site(which == 3 ? S_PAIR_OPROJ : which == 1 ? S_CA_OPROJ : S_VERIFY_OPROJ);
+    MOA_TRY_HIP(launch_linear(sh->dtype, lo, st), "draft_step: output projections");
+    return MOA_OK;
+}
+
+static int32_t piece_more_verify_layers(const moa_step_args_t *a, void *scr, size_t scr_bytes, hipStream_t st)
+{
     for (int l = 1; l < a->n_verify_layers; ++l) {
-        rc = attention_layer("tree_verify_attn", sh, a->v_x_host[l], B, M, a->v_wq_host[l], a->v_wk_host[l],
-                             a->v_wv_host[l], a->v_wo_host[l], a->v_kcache_host[l], a->v_vcache_host[l], a->prefix_len,
-                             a->P_cap, a->mask, a->v_out_host[l], a->v_ktree_host[l], a->v_vtree_host[l], a->dev_status,
-                             scr, L.scratch, st);
+        int32_t rc = attention_layer("tree_verify_attn", a->shape, a->v_x_host[l], a->B, a->M, a->v_wq_host[l],
+                                     a->v_wk_host[l], a->v_wv_host[l], a->v_wo_host[l], a->v_kcache_host[l],
+                                     a->v_vcache_host[l], a->prefix_len, a->P_cap, a->mask, a->v_out_host[l],
+                                     a->v_ktree_host[l], a->v_vtree_host[l], a->dev_status, scr, scr_bytes, st);
         if (rc) return rc;
     }
     return MOA_OK;
 }
 
-// ---- the step with its independent branches on two streams.
+static StepBufs carve_step_bufs(const moa_step_args_t *a, const GroupLayout &L, char **scr)
+{
+    char *p = (char *)a->ws;
+    StepBufs bf;
+    bf.old_len = (int32_t *)p;
+    bf.q_ca = p + L.len_bytes;
+    bf.h_ca = bf.q_ca + L.qa;
+    bf.q_v = bf.h_ca + L.qa;
+    bf.h_v = bf.q_v + L.qa;
+    *scr = bf.h_v + L.qa;
+    return bf;
+}
+
+static bool can_group(const moa_step_args_t *a)
+{
+    return pieces_ok(a) && a->ws_bytes >= group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa).total();
+}
+
+static int32_t draft_step_grouped(const moa_step_args_t *a)
+{
+    hipStream_t st = (hipStream_t)a->stream;
+    const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
+    char *scr = nullptr;
+    const StepBufs bf = carve_step_bufs(a, L, &scr);
+    int32_t rc = piece_small(a, bf, st);
+    if (rc) return rc;
+    rc = piece_projections(a, bf, scr, L.scratch, st);
+    if (rc) return rc;
+    rc = piece_lsa_append(a, bf, scr, L.scratch, st);
+    if (rc) return rc;
+    const AttnArgs ca = piece_ca_core_args(a, bf, scr, L.attn_each);
+    const AttnArgs ve = piece_verify_core_args(a, bf, scr + L.attn_each, L.attn_each);
+    prof_set_site(S_PAIR_CORE);
+    MOA_TRY_HIP(launch_attn_pair(ca, ve, st), "draft_step: attention cores");
+    rc = piece_oproj(a, bf, 3, scr, L.scratch, st);
+    if (rc) return rc;
+    return piece_more_verify_layers(a, scr, L.scratch, st);
+}
+
+// ---- the same pieces on two streams.
 // Dependencies inside one step: the LSA chain (projection -> layer attention -> W_o -> memory append) feeds
-// only the cross-attention core; the cross-attention query projection and every verification layer depend on
-// none of it (verification needs the tree mask only).  The main chain is bound by the matrix cores, the other
-// projections by HBM, so running them side by side hides most of the weight streaming.  The side branch runs
-// on a library-owned stream that is forked from and joined back into the caller's stream with events, so the
+// only the cross-attention core; the projections of the cross-attention queries and every verification layer
+// depend on none of it.  The LSA chain is bound by the matrix cores and by launch latency, the projections by
+// HBM, so running them side by side hides most of the weight streaming.  The side branch runs on a
+// library-owned stream that is forked from and joined back into the caller's stream with events, so the
 // caller still sees one stream's worth of ordering (and a stream capture records both branches).
 struct SideStream {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, tree = nullptr, caq = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, caq = nullptr, join = nullptr;
     bool ok = false;
 };
 
@@ -756,65 +791,51 @@ static SideStream *side_stream_for_current_device()
     if (!s.stream) {
         s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
                hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&s.tree, hipEventDisableTiming) == hipSuccess &&
                hipEventCreateWithFlags(&s.caq, hipEventDisableTiming) == hipSuccess &&
                hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
     }
     return s.ok ? &s : nullptr;
 }
 
+// the grouped layout with a second scratch region for the side branch
+static size_t two_stream_bytes(const moa_step_args_t *a)
+{
+    const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
+    return L.total() + L.scratch;
+}
+
 static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
 {
-    const moa_shape_t *sh = a->shape;
     hipStream_t main = (hipStream_t)a->stream, side = ss->stream;
-    const StepLayout L = step_layout(sh, a->B, a->M, a->Mq, a->P_cap, a->ca_P_cap, a->T_lsa);
-    char *ws_main = (char *)a->ws, *ws_caq = ws_main + L.main_bytes, *ws_side = ws_caq + L.caq_bytes;
+    const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
+    char *scr_main = nullptr;
+    const StepBufs bf = carve_step_bufs(a, L, &scr_main);
+    char *scr_side = scr_main + L.scratch;
 
+    int32_t rc = piece_small(a, bf, main);                    // the mask is needed by the side branch
+    if (rc) return rc;
     MOA_TRY_HIP(hipEventRecord(ss->fork, main), "draft_step: fork");
     MOA_TRY_HIP(hipStreamWaitEvent(side, ss->fork, 0), "draft_step: fork");
 
-    // side branch, part 1: cross-attention query projection
-    AttnBufs cab;
-    cab.qbuf = ws_caq;
-    cab.abuf = ws_main;
-    cab.scratch_p = ws_side;
-    cab.scratch_p_bytes = L.side_bytes;
-    cab.scratch_c = ws_main + L.caq_bytes;
-    cab.scratch_c_bytes = L.main_bytes - L.caq_bytes;
-    const void *caq = nullptr;
-    int32_t rc = attn_stage_project("cross_attn_draft", sh, a->ca_xq, a->B, a->Mq, a->ca_wq, nullptr, nullptr, false,
-                                    nullptr, nullptr, cab, side, &caq);
+    // side branch: projections, then verification layer 0's core and W_o, then the other layers
+    rc = piece_projections(a, bf, scr_side, L.scratch, side);
     if (rc) return rc;
     MOA_TRY_HIP(hipEventRecord(ss->caq, side), "draft_step: event");
-
-    // main branch: tree mask, then the LSA chain
-    rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, main);
+    prof_set_site(S_VERIFY_CORE);
+    MOA_TRY_HIP(launch_attn(piece_verify_core_args(a, bf, scr_side, L.scratch), side), "draft_step: verification core");
+    rc = piece_oproj(a, bf, 2, scr_side, L.scratch, side);
     if (rc) return rc;
-    MOA_TRY_HIP(hipEventRecord(ss->tree, main), "draft_step: event");
-    rc = moa_lsa(sh, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, ws_main, L.main_bytes,
-                 main);
+    rc = piece_more_verify_layers(a, scr_side, L.scratch, side);
     if (rc) return rc;
-    rc = moa_ca_kv_append(sh, a->lsa_out, a->T_lsa, sh->lsa_q_heads * sh->head_dim, a->tok_off, a->B, a->ca_wk, a->ca_wv,
-                          a->ca_k, a->ca_v, a->ca_len, a->ca_P_cap, a->dev_status, ws_main, L.main_bytes, main);
-    if (rc) return rc;
-
-    // side branch, part 2: the verification layers (need the mask)
-    MOA_TRY_HIP(hipStreamWaitEvent(side, ss->tree, 0), "draft_step: wait");
-    for (int l = 0; l < a->n_verify_layers; ++l) {
-        rc = attention_layer("tree_verify_attn", sh, a->v_x_host[l], a->B, a->M, a->v_wq_host[l], a->v_wk_host[l],
-                             a->v_wv_host[l], a->v_wo_host[l], a->v_kcache_host[l], a->v_vcache_host[l], a->prefix_len,
-                             a->P_cap, a->mask, a->v_out_host[l], a->v_ktree_host[l], a->v_vtree_host[l], a->dev_status,
-                             ws_side, L.side_bytes, side);
-        if (rc) return rc;
-    }
     MOA_TRY_HIP(hipEventRecord(ss->join, side), "draft_step: event");
 
-    // main branch: cross-attention core + W_o once its queries are there, accept walk, join
-    MOA_TRY_HIP(hipStreamWaitEvent(main, ss->caq, 0), "draft_step: wait");
-    rc = attn_stage_core("cross_attn_draft", sh, caq, a->B, a->Mq, a->ca_wo, a->ca_k, a->ca_v, a->ca_len, a->ca_P_cap,
-                         nullptr, a->ca_out, nullptr, nullptr, a->dev_status, cab, main);
+    // main branch: LSA chain, then the cross-attention core + W_o once its queries are there, join
+    rc = piece_lsa_append(a, bf, scr_main, L.scratch, main);
     if (rc) return rc;
-    rc = moa_tree_accept(a->parent, a->tok, a->tgt, a->B, a->M, a->path, a->n_path, a->bonus, main);
+    MOA_TRY_HIP(hipStreamWaitEvent(main, ss->caq, 0), "draft_step: wait");
+    prof_set_site(S_CA_CORE);
+    MOA_TRY_HIP(launch_attn(piece_ca_core_args(a, bf, scr_main, L.scratch), main), "draft_step: cross-attention core");
+    rc = piece_oproj(a, bf, 1, scr_main, L.scratch, main);
     if (rc) return rc;
     MOA_TRY_HIP(hipStreamWaitEvent(main, ss->join, 0), "draft_step: join");
     return MOA_OK;
@@ -836,12 +857,11 @@ int32_t moa_draft_step(const moa_step_args_t *a)
     if (rc) return rc;
     // grouped launches by default; two streams on request when the workspace has room for both branches'
     // scratch; otherwise one stage after another
-    const StepLayout L = step_layout(a->shape, a->B, a->M, a->Mq, a->P_cap, a->ca_P_cap, a->T_lsa);
-    if (a->schedule == MOA_SCHED_TWO_STREAM && a->ws_bytes >= L.total()) {
+    if (a->schedule == MOA_SCHED_TWO_STREAM && pieces_ok(a) && a->ws_bytes >= two_stream_bytes(a)) {
         SideStream *ss = side_stream_for_current_device();
         if (ss) return draft_step_concurrent(a, ss);
     }
-    if (can_group(a)) return draft_step_grouped(a);
+    if (a->schedule != MOA_SCHED_SEQUENTIAL && can_group(a)) return draft_step_grouped(a);
     return draft_step_stages(a);
 }
 
