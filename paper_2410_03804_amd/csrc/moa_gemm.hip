@@ -303,17 +303,23 @@ struct TiledArgs {
 };
 
 // WF x WR = 32x32 MFMA blocks per wave along features x rows; the four waves sit 2 x 2, so the workgroup
-// tile is (64 WF) features x (64 WR) rows.  A larger wave tile re-uses each LDS fragment more often:
-// 2x2 needs one 1 KB fragment read per MFMA (that alone saturates the 128 B/clk LDS port at full MFMA
-// rate), 4x2 needs 0.75.
+// tile is (64 WF) features x (64 WR) rows, walked along K in tiles of 64.
+// The k tiles go from global memory straight into LDS (no register staging, no LDS write instructions): one
+// wave instruction moves 64 x 16 B = 8 rows of 128 B into 1 KB of contiguous LDS, so rows are unpadded, and
+// the bank conflicts that would cause in the operand reads are removed by a swizzle: 16-byte chunk c of tile
+// row r lives at position c ^ ((r >> 1) & 7), applied to the global address each lane fetches (the eight
+// lanes of a row still cover the same 128 bytes).  The loads of tile kt+1 are issued before the MFMAs of tile
+// kt and complete behind them; one barrier per k tile publishes the new tile and retires the old one.
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
+
 template <int WF, int WR>
 __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
 {
-    constexpr int BN = 64 * WF, BM = 64 * WR, BK = 64, LDT = BK + 8;  // LDT: padded LDS row (bf16)
-    constexpr int NW = BN * 8 / 256, NX = BM * 8 / 256;                // 16-byte chunks per thread per k tile
-    extern __shared__ __attribute__((aligned(16))) bf16_t tsm[];
-    bf16_t(*Ws)[BN][LDT] = (bf16_t(*)[BN][LDT])tsm;                     // [2][BN][LDT]
-    bf16_t(*Xs)[BM][LDT] = (bf16_t(*)[BM][LDT])(tsm + 2 * BN * LDT);    // [2][BM][LDT]
+    constexpr int BN = 64 * WF, BM = 64 * WR, BK = 64;
+    constexpr int STAGE = (BN + BM) * BK;                     // bf16 elements per LDS stage: W rows, then X rows
+    constexpr int NWI = BN / 32, NXI = BM / 32;               // 8-row load instructions per wave per stage
+    extern __shared__ __attribute__((aligned(16))) bf16_t tsm[];   // [2][STAGE]
 
     const LinArgs &a = ta.a;
     // Workgroups are handed to the 8 XCDs round-robin (id % 8), and each XCD has its own L2.  Give every
@@ -333,22 +339,33 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
     const bf16_t *W = (const bf16_t *)a.seg[s].W;
     const bf16_t *X = (const bf16_t *)a.X;
 
-    // global -> register staging: 8 lanes cover 128 B of a row
-    const int srow = tid >> 3, scol = (tid & 7) * 8;
-    const bf16_t *wsrc[NW], *xsrc[NX];
+    // wave w moves tile rows (BN/4) w .. of W and (BM/4) w .. of X, eight rows per instruction
+    const int lrow = lane >> 3, lpos = lane & 7;
+    const bf16_t *wsrc[NWI], *xsrc[NXI];
 #pragma unroll
-    for (int i = 0; i < NW; ++i) wsrc[i] = W + (int64_t)(n0 + srow + 32 * i) * K + scol;
-#pragma unroll
-    for (int i = 0; i < NX; ++i) {
-        int64_t r = r0 + srow + 32 * i;
-        if (r > a.R - 1) r = a.R - 1;
-        xsrc[i] = X + r * a.ldx + scol;
+    for (int i = 0; i < NWI; ++i) {
+        const int row = (BN / 4) * wave + 8 * i + lrow;
+        wsrc[i] = W + (int64_t)(n0 + row) * K + 8 * (lpos ^ ((row >> 1) & 7));
     }
-    u32x4 wreg[NW], xreg[NX];
 #pragma unroll
-    for (int i = 0; i < NW; ++i) wreg[i] = *(const u32x4 *)wsrc[i];
+    for (int i = 0; i < NXI; ++i) {
+        const int row = (BM / 4) * wave + 8 * i + lrow;
+        int64_t r = r0 + row;
+        if (r > a.R - 1) r = a.R - 1;          // rows past the end repeat the last row; never stored
+        xsrc[i] = X + r * a.ldx + 8 * (lpos ^ ((row >> 1) & 7));
+    }
+    auto issue = [&](int buf, int kt) {
+        bf16_t *wb = tsm + buf * STAGE;
+        bf16_t *xb = wb + BN * BK;
 #pragma unroll
-    for (int i = 0; i < NX; ++i) xreg[i] = *(const u32x4 *)xsrc[i];
+        for (int i = 0; i < NWI; ++i)
+            __builtin_amdgcn_global_load_lds((global_void_t *)(wsrc[i] + (int64_t)kt * BK),
+                                             (lds_void_t *)(wb + ((BN / 4) * wave + 8 * i) * BK), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NXI; ++i)
+            __builtin_amdgcn_global_load_lds((global_void_t *)(xsrc[i] + (int64_t)kt * BK),
+                                             (lds_void_t *)(xb + ((BM / 4) * wave + 8 * i) * BK), 16, 0, 0);
+    };
 
     f32x16 acc[WF][WR];
 #pragma unroll
@@ -359,32 +376,35 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
             for (int e = 0; e < 16; ++e) acc[i][jj][e] = 0.f;
 
     const int nk = K / BK;
+    issue(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): this wave's share of tile 0 has landed in LDS
+    __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
-#pragma unroll
-        for (int i = 0; i < NW; ++i) *(u32x4 *)&Ws[buf][srow + 32 * i][scol] = wreg[i];
-#pragma unroll
-        for (int i = 0; i < NX; ++i) *(u32x4 *)&Xs[buf][srow + 32 * i][scol] = xreg[i];
-        __syncthreads();   // tile kt visible; everyone is past the reads of tile kt-2 (same buffer)
-        if (kt + 1 < nk) {
-#pragma unroll
-            for (int i = 0; i < NW; ++i) wreg[i] = *(const u32x4 *)(wsrc[i] + (int64_t)(kt + 1) * BK);
-#pragma unroll
-            for (int i = 0; i < NX; ++i) xreg[i] = *(const u32x4 *)(xsrc[i] + (int64_t)(kt + 1) * BK);
-        }
+        if (kt + 1 < nk) issue(buf ^ 1, kt + 1);   // everyone is past the reads of tile kt-1 (same buffer)
+        const bf16_t *wb = tsm + buf * STAGE;
+        const bf16_t *xb = wb + BN * BK;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 af[WF], bfr[WR];
 #pragma unroll
-            for (int i = 0; i < WF; ++i) af[i] = *(const bf16x8 *)&Ws[buf][wf0 + 32 * i + l32][16 * ks + 8 * half];
+            for (int i = 0; i < WF; ++i) {
+                const int row = wf0 + 32 * i + l32;
+                af[i] = *(const bf16x8 *)&wb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
+            }
 #pragma unroll
-            for (int i = 0; i < WR; ++i) bfr[i] = *(const bf16x8 *)&Xs[buf][wr0 + 32 * i + l32][16 * ks + 8 * half];
+            for (int i = 0; i < WR; ++i) {
+                const int row = wr0 + 32 * i + l32;
+                bfr[i] = *(const bf16x8 *)&xb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
+            }
 #pragma unroll
             for (int i = 0; i < WF; ++i)
 #pragma unroll
                 for (int jj = 0; jj < WR; ++jj)
                     acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[jj], acc[i][jj], 0, 0, 0);
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);    // tile kt+1 of this wave is in LDS
+        __syncthreads();
     }
 
     // acc[i][jj][v]: feature = wf0 + 32 i + 8 (v/4) + 4 half + v%4, row = wr0 + 32 jj + l32
@@ -419,7 +439,7 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
     ta.tile_begin[a.nseg] = t;
     ta.tiles_per_xcd = (t + 7) / 8;
     const dim3 grid(8u * ta.tiles_per_xcd * (unsigned)((a.R + BM - 1) / BM));
-    const size_t lds = (size_t)2 * (BN + BM) * 72 * sizeof(bf16_t);
+    const size_t lds = (size_t)2 * (BN + BM) * 64 * sizeof(bf16_t);
     hipError_t e = hipFuncSetAttribute((const void *)k_linear_tiled_bf16<WF, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     prof_begin(K_LIN_TILED + 64 * (WF * 8 + WR), stream);
