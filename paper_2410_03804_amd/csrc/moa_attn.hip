@@ -344,6 +344,10 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
 // only; the blocks that share K/V are placed on the same XCD so that the re-reads hit its L2.
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 
+// 2^x by the hardware instruction alone: arguments here are <= 0 and results below the normal range may
+// become 0, which a softmax weight may
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ void wave_lds_sync()
 {
     // LDS traffic of one wavefront is processed in order; this only keeps the compiler from moving a read of
@@ -391,6 +395,19 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
     const int G = a.H / a.Hkv, RG = G * a.Mq, W = (a.Mq + 63) >> 6;
     const float sc = 1.4426950408889634f / sqrtf((float)DH);   // scores are kept in the log2 domain
 
+    // the block's 32 query rows: requested first (they do not depend on the sequence length), row-contiguous
+    constexpr int QPT = (32 * CPK + 64 * NW - 1) / (64 * NW);
+    u32x4 qreg[QPT];
+#pragma unroll
+    for (int i = 0; i < QPT; ++i) {
+        const int c = min(tid + 64 * NW * i, 32 * CPK - 1);
+        int rq = rb * 32 + c / CPK;
+        if (rq > RG - 1) rq = RG - 1;
+        const int m = rq / G, hq = rq - m * G;
+        const bf16_t *qrow = (const bf16_t *)a.q + (((int64_t)b * a.Mq + m) * a.H + g * G + hq) * DH;
+        qreg[i] = *(const u32x4 *)(qrow + 8 * (c % CPK));
+    }
+
     const int len = clamp_len(a.len[b], a.P_cap, tid == 0 ? a.dev_status : nullptr);
     const int Mt = a.mask ? a.Mt : 0;
     const int ntc = (len + KT - 1) / KT, nt = ntc + (Mt + KT - 1) / KT;
@@ -400,10 +417,21 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
     const bf16_t *ktp = (const bf16_t *)a.ktree + (int64_t)bg * a.Mt * DH;
     const bf16_t *vtp = (const bf16_t *)a.vtree + (int64_t)bg * a.Mt * DH;
 
-    // the K/V tile as the wave loads it: instruction j covers rows RPI j .. RPI j + RPI - 1, 16 bytes per lane
+    // the K/V tile as the wave loads it: instruction j covers rows RPI j .. RPI j + RPI - 1, 16 bytes per lane.
+    // A cache tile that lies wholly below the length needs no row clamp: one base address, constant offsets.
     const int ld_row = lane / CPK, ld_piece = lane % CPK;
+    const int ld_off = ld_row * DH + 8 * ld_piece;
     u32x4 kreg[NLD], vreg[NLD];
     auto fetch = [&](int i) {
+        if (i < ntc && (i + 1) * KT <= len) {
+            const bf16_t *kp = kc + (int64_t)i * KT * DH + ld_off, *vp = vc + (int64_t)i * KT * DH + ld_off;
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                kreg[j] = *(const u32x4 *)(kp + j * RPI * DH);
+                vreg[j] = *(const u32x4 *)(vp + j * RPI * DH);
+            }
+            return;
+        }
         const bool tree = i >= ntc;
         const int base = tree ? (i - ntc) * KT : i * KT;
         const int limit = tree ? Mt : len;
@@ -420,14 +448,11 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
     };
     if (wave < nt) fetch(wave);
 
-    // the block's 32 query rows: loaded once by the workgroup, row-contiguous, then read as MFMA operands
     bf16_t *Qs = (bf16_t *)smem;
-    for (int c = tid; c < 32 * CPK; c += 64 * NW) {
-        int rho = rb * 32 + c / CPK;
-        if (rho > RG - 1) rho = RG - 1;
-        const int m = rho / G, hh = rho - m * G;
-        const bf16_t *qrow = (const bf16_t *)a.q + (((int64_t)b * a.Mq + m) * a.H + g * G + hh) * DH;
-        *(u32x4 *)&Qs[(c / CPK) * KLD + 8 * (c % CPK)] = *(const u32x4 *)(qrow + 8 * (c % CPK));
+#pragma unroll
+    for (int i = 0; i < QPT; ++i) {
+        const int c = tid + 64 * NW * i;
+        if (c < 32 * CPK) *(u32x4 *)&Qs[(c / CPK) * KLD + 8 * (c % CPK)] = qreg[i];
     }
     __syncthreads();
     bf16x8 qf[NKS];
@@ -444,7 +469,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
     for (int d = 0; d < NDB; ++d)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[d][e] = 0.f;
-    float mrun = -INFINITY, lrun = 0.f;
+    float mrun = -INFINITY, lrun = 0.f;              // running max (scaled, log2 domain) and sum
 
     bf16_t *stg = (bf16_t *)(smem + L::q_bytes + wave * L::stage_bytes);   // this wave's tile buffer
     // transpose read: lane j of a 16-lane group addresses key (j >> 2), head_dim 4 (j & 3) of the group's 16
@@ -453,9 +478,6 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
     if (wave < nt) {
         const int last = wave + ((nt - 1 - wave) / NW) * NW;
         for (int i = wave; i <= last; i += NW) {
-            const bool tree = i >= ntc;
-            const int base = tree ? (i - ntc) * KT : i * KT;
-            const int limit = tree ? Mt : len;
             // K tile -> LDS -> S^T = K Q^T (keys x queries)
 #pragma unroll
             for (int j = 0; j < NLD; ++j) *(u32x4 *)&stg[(RPI * j + ld_row) * KLD + 8 * ld_piece] = kreg[j];
@@ -476,30 +498,37 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
             wave_lds_sync();
             fetch(min(i + NW, last));
 
-            uint32_t vis = 0xffffffffu;
-            if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.Mq + mrow) * W + (base >> 6)] >> (base & 63));
-            const int nvalid = limit - base;                   // >= 1
-            if (nvalid < 32) vis &= (1u << nvalid) - 1u;
-            float tmax = -INFINITY;
+            // keys that do not count (tree rows outside the ancestor set, rows past the end) get -inf; a cache
+            // tile wholly below the length has none (the decision is the same for the whole wavefront)
+            if (!(i < ntc && (i + 1) * KT <= len)) {
+                const bool tree = i >= ntc;
+                const int base = tree ? (i - ntc) * KT : i * KT;
+                const int nvalid = (tree ? Mt : len) - base;   // >= 1
+                uint32_t vis = 0xffffffffu;
+                if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.Mq + mrow) * W + (base >> 6)] >> (base & 63));
+                if (nvalid < 32) vis &= (1u << nvalid) - 1u;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = 8 * (v >> 2) + 4 * half + (v & 3);
-                const float x = ((vis >> key) & 1u) ? s[v] * sc : -INFINITY;
-                s[v] = x;
-                tmax = fmaxf(tmax, x);
+                for (int v = 0; v < 16; ++v) {
+                    const int key = 8 * (v >> 2) + 4 * half + (v & 3);
+                    if (!((vis >> key) & 1u)) s[v] = -INFINITY;
+                }
             }
+            float tmax = s[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const float mnew = fmaxf(mrun, tmax);
+            const float mnew = fmaxf(mrun, tmax * sc);         // sc > 0: scaling keeps the order (and -inf)
             const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-            const float corr = exp2f(mrun - msafe);
+            const float corr = fast_exp2(mrun - msafe);
             float psum = 0.f;
             float p[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { p[v] = exp2f(s[v] - msafe); psum += p[v]; }
+            for (int v = 0; v < 16; ++v) { p[v] = fast_exp2(fmaf(s[v], sc, -msafe)); psum += p[v]; }
             psum += __shfl_xor(psum, 32);
             lrun = lrun * corr + psum;
             mrun = mnew;
             if (__any(corr != 1.0f)) {                          // the running max moved in some column
+                asm volatile("" ::: "memory");                  // keep this a real branch: 64 multiplies skipped
 #pragma unroll
                 for (int d = 0; d < NDB; ++d)
 #pragma unroll
