@@ -100,6 +100,22 @@ __global__ __launch_bounds__(256) void k_lsa_attn_mfma(LsaAttnArgs a)
         for (int ks = 0; ks < NKS; ++ks) kf[jb][ks] = *(const bf16x8 *)(k + (int64_t)row * a.ldk + 16 * ks + 8 * half);
     }
 
+    // V rows, requested now so that they arrive behind the score computation: 16 lanes cover one 256-byte
+    // row piece (8 head_dim values per lane), instruction i of block jb holds row 32 jb + 4 i + lane / 16
+    constexpr int CPR = DH / 8;            // 16-byte pieces per V row
+    constexpr int RPI = 64 / CPR;          // rows per load instruction
+    constexpr int NVI = 32 / RPI;          // load instructions per block of 32 rows
+    const int vrow0 = lane / CPR, vpiece = lane % CPR;
+    u32x4 vreg[NB][NVI];
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int i = 0; i < NVI; ++i) {
+            int row = 32 * jb + RPI * i + vrow0;
+            if (row > L - 1) row = L - 1;      // weight 0 below
+            vreg[jb][i] = *(const u32x4 *)(v + (int64_t)row * a.ldv + 8 * vpiece);
+        }
+
     // column sums of P, kept in the S^T register layout: csum[jb][v] belongs to key 32 jb + 8 (v/4) + 4 half + v%4
     float csum[NB][16];
 #pragma unroll
@@ -168,26 +184,33 @@ __global__ __launch_bounds__(256) void k_lsa_attn_mfma(LsaAttnArgs a)
     }
     __syncthreads();
 
-    // abar[c] = sum_j pbar[j] V[j][c]; lane owns DH/64 consecutive components
-    constexpr int CPL = DH / 64;
-    float o[CPL];
+    // abar[c] = sum_j pbar[j] V[j][c]: each lane weights its rows' 8 components, then the RPI row groups of
+    // the wavefront are added up (lanes that differ in lane / CPR)
+    float o[8];
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) o[c] = 0.f;
-    for (int j = 0; j < L; ++j) {
-        const float pj = pbar_s[wave][j];
-        const bf16_t *vr = v + (int64_t)j * a.ldv + lane * CPL;
-        if (CPL == 2) {
-            const uint32_t w = *(const uint32_t *)vr;
-            o[0] = fmaf(pj, __uint_as_float(w << 16), o[0]);
-            o[CPL - 1] = fmaf(pj, __uint_as_float(w & 0xffff0000u), o[CPL - 1]);
-        } else {
-            o[0] = fmaf(pj, bf2f(vr[0]), o[0]);
+    for (int c = 0; c < 8; ++c) o[c] = 0.f;
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int i = 0; i < NVI; ++i) {
+            const int row = 32 * jb + RPI * i + vrow0;
+            const float pj = row < L ? pbar_s[wave][row] : 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t x = vreg[jb][i][w];
+                o[2 * w] = fmaf(pj, __uint_as_float(x << 16), o[2 * w]);
+                o[2 * w + 1] = fmaf(pj, __uint_as_float(x & 0xffff0000u), o[2 * w + 1]);
+            }
         }
-    }
-    if (live) {
-        bf16_t *dst = (bf16_t *)a.abar + t * (int64_t)a.Hq * DH + (int64_t)h * DH + lane * CPL;
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) dst[c] = f2bf(o[c]);
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int off = CPR; off < 64; off <<= 1) o[c] += __shfl_xor(o[c], off);
+    if (live && lane < CPR) {
+        u32x4 pk;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) pk[w] = (uint32_t)f2bf(o[2 * w]) | ((uint32_t)f2bf(o[2 * w + 1]) << 16);
+        *(u32x4 *)((bf16_t *)a.abar + t * (int64_t)a.Hq * DH + (int64_t)h * DH + 8 * lane) = pk;
     }
 }
 
