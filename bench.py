@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--sets", type=int, default=3, help="independent buffer sets rotated between steps")
     ap.add_argument("--profile-steps", type=int, default=12, help="untimed steps with events around every kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sample-every", type=int, default=7,
+                    help="in the timed region, put events around every n-th launch of the dominant kernel only "
+                         "(an event pair costs the stream a few microseconds)")
     ap.add_argument("--schedule", choices=list(SCHEDULES), default="grouped",
                     help="grouped: independent same-shape calls share a launch (default); two-stream: fork the "
                          "step's independent branch onto a second stream (kernels then overlap, so per-kernel "
@@ -183,7 +186,11 @@ def main():
     dominant = max(per_kernel, key=per_kernel.get) if per_kernel else None
 
     # timed region: exactly K steps, events only around the dominant kernel's launches
-    moa.profile_enable(True, only_kernel=dominant)
+    dom_lps = max(1, round(sum(n for site, kern, n, ms in rows if kern == dominant) / P))
+    every = max(1, args.sample_every)
+    while math.gcd(every, dom_lps) != 1:       # so that the samples rotate through the kernel's launch sites
+        every += 1
+    moa.profile_enable(True, only_kernel=dominant, every=every)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(K):
@@ -231,9 +238,12 @@ def main():
         tot_ms = sum(r[3] for r in dom_rows)
         avg_us = tot_ms * 1e3 / launches
         sites = sorted({r[0] for r in dom_rows})
-        per_step_launches = launches / K
-        byt = sum(costs[s]["bytes"] for s in sites) / per_step_launches     # per launch, averaged over its sites
-        flo = sum(costs[s]["flops"] for s in sites) / per_step_launches
+        # launches per step of each site (from the profiling pass); the timed region samples every n-th launch,
+        # so bytes and flops are weighted by the launches that were actually bracketed
+        site_lps = {site: n / P for site, kern, n, ms in rows if kern == dominant}
+        per_step_launches = sum(site_lps.values())
+        byt = sum(r[2] * costs[r[0]]["bytes"] / site_lps[r[0]] for r in dom_rows) / launches
+        flo = sum(r[2] * costs[r[0]]["flops"] / site_lps[r[0]] for r in dom_rows) / launches
         bnd, _ = bound_of(byt, flo, peak_mm)
         if bnd == "hbm":
             ach = byt / (avg_us * 1e-6) / 1e9
@@ -247,7 +257,7 @@ def main():
             roofline["traffic"] = int(PMC_TRAFFIC_MIB_C1[dominant] * 2 ** 20)
         roofline.update(kernel=dominant, sites=sites, avg_launch_us=round(avg_us, 3),
                         launches_per_step=per_step_launches, alg_bytes_per_launch=int(byt),
-                        flops_per_launch=int(flo), share_of_kernel_time=round(per_kernel[dominant] / sum(per_kernel.values()), 4))
+                        flops_per_launch=int(flo), sampled_launches=launches, share_of_kernel_time=round(per_kernel[dominant] / sum(per_kernel.values()), 4))
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -201,9 +201,13 @@ int32_t moa_draft_step(const moa_step_args_t *args);
  * kernel only -- so a benchmark can attribute time to single kernels.  Off by default; events
  * are created on first use and recycled.  moa_profile_collect waits for the recorded events
  * (host synchronisation), sums them per (launch site, kernel) into rows_host and forgets them.
+ * moa_profile_sample_every(n) brackets only every n-th eligible launch (n >= 1, default 1): two
+ * event records cost the stream a few microseconds, which a timed region should not pay on
+ * every launch.
  * Kernel and site ids are the indices accepted by the *_name functions ("?" past the end). */
 typedef struct { int32_t site, kernel; int64_t launches; double total_ms; } moa_profile_row_t;
 int32_t moa_profile_enable(int32_t on, int32_t only_kernel);
+int32_t moa_profile_sample_every(int32_t n);
 int32_t moa_profile_collect(moa_profile_row_t *rows_host, int32_t max_rows, int32_t *n_rows_host);
 const char *moa_profile_kernel_name(int32_t kernel);
 const char *moa_profile_site_name(int32_t site);

@@ -64,7 +64,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
-            "moa_profile_enable", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name"]
+            "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -89,6 +89,7 @@ class _ProfileRow(C.Structure):
 
 
 _lib.moa_profile_enable.argtypes = [_i32, _i32]
+_lib.moa_profile_sample_every.argtypes = [_i32]
 _lib.moa_profile_collect.argtypes = [C.POINTER(_ProfileRow), _i32, C.POINTER(_i32)]
 _lib.moa_profile_kernel_name.restype = C.c_char_p
 _lib.moa_profile_kernel_name.argtypes = [_i32]
@@ -334,7 +335,9 @@ def profile_kernel_id(name: str) -> int:
 _kernel_ids: dict = {}
 
 
-def profile_enable(on: bool, only_kernel: str | None = None):
+def profile_enable(on: bool, only_kernel: str | None = None, every: int = 1):
+    """Events around every `every`-th launch (of `only_kernel` only, when given)."""
+    _check(_lib.moa_profile_sample_every(every))
     _check(_lib.moa_profile_enable(1 if on else 0, -1 if only_kernel is None else profile_kernel_id(only_kernel)))
 
 

@@ -16,6 +16,7 @@ struct Rec { int site, kernel; hipEvent_t e0, e1; };
 std::mutex g_mu;
 bool g_on = false;
 int g_only_kernel = -1;
+int g_every = 1, g_seen = 0;
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 thread_local int t_site = S_NONE;
@@ -45,6 +46,7 @@ void prof_begin(int kernel, hipStream_t stream)
     if (!g_on) return;
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_on || (g_only_kernel >= 0 && kernel != g_only_kernel)) return;
+    if (g_seen++ % g_every) return;
     Rec r = {t_site, kernel, take_event(), take_event()};
     if (!r.e0 || !r.e1) return;
     if (hipEventRecord(r.e0, stream) != hipSuccess) return;
@@ -73,6 +75,16 @@ int32_t moa_profile_enable(int32_t on, int32_t only_kernel)
     g_recs.clear();
     g_on = on != 0;
     g_only_kernel = only_kernel >= 0 ? only_kernel : -1;
+    g_seen = 0;
+    return MOA_OK;
+}
+
+int32_t moa_profile_sample_every(int32_t n)
+{
+    if (n < 1) return MOA_ERR_SHAPE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_every = n;
+    g_seen = 0;
     return MOA_OK;
 }
 
