@@ -223,6 +223,8 @@ def main():
     pieces = []
     for site, kern, n, ms in sorted(rows, key=lambda r: -r[3]):
         c = costs.get(site, dict(bytes=0.0, flops=0.0))
+        if "reduce" in kern or "merge" in kern:      # second pass of a site: its algorithmic cost is counted once, above
+            c = dict(bytes=0.0, flops=0.0)
         us = ms * 1e3 / P                       # per step, all launches of this site
         bnd, t_min = bound_of(c["bytes"], c["flops"], peak_mm)
         pieces.append(dict(site=site, kernel=kern, launches_per_step=n / P, us_per_step=round(us, 3),

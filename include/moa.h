@@ -196,14 +196,13 @@ typedef struct {
 int32_t moa_draft_step(const moa_step_args_t *args);
 
 /* Measurement aid (not part of the method; paper Appendix "Complexity Analysis" is the only place
- * that discusses where time goes).  When enabled, two hipEvents are recorded on the caller's
- * stream around every kernel launch -- or, with only_kernel >= 0, around the launches of that
- * kernel only -- so a benchmark can attribute time to single kernels.  Off by default; events
- * are created on first use and recycled.  moa_profile_collect waits for the recorded events
- * (host synchronisation), sums them per (launch site, kernel) into rows_host and forgets them.
- * moa_profile_sample_every(n) brackets only every n-th eligible launch (n >= 1, default 1): two
- * event records cost the stream a few microseconds, which a timed region should not pay on
- * every launch.
+ * that discusses where time goes).  When enabled, every kernel launch -- or, with only_kernel >= 0,
+ * every launch of that kernel -- carries a start and a stop hipEvent attached to the dispatch
+ * itself, so their difference is the kernel's own begin-to-end time on the device and a benchmark
+ * can attribute time to single kernels.  Off by default; events are created on first use and
+ * recycled.  moa_profile_collect waits for the recorded events (host synchronisation), sums them
+ * per (launch site, kernel) into rows_host and forgets them.
+ * moa_profile_sample_every(n) times only every n-th eligible launch (n >= 1, default 1).
  * Kernel and site ids are the indices accepted by the *_name functions ("?" past the end). */
 typedef struct { int32_t site, kernel; int64_t launches; double total_ms; } moa_profile_row_t;
 int32_t moa_profile_enable(int32_t on, int32_t only_kernel);

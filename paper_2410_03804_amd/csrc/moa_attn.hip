@@ -698,8 +698,8 @@ static hipError_t launch_attn_generic(const AttnArgs &a, hipStream_t stream)
 {
     const int nblocks = a.B * a.Mq * a.H;
     if (a.dh > 256) return hipErrorInvalidValue;
-    if (a.dtype == DT_BF16) { prof_begin(K_ATTN_GENERIC, stream); hipLaunchKernelGGL(k_attn_generic<bf16_t>, dim3(nblocks), dim3(64), 0, stream, a); prof_end(stream); }
-    else { prof_begin(K_ATTN_GENERIC, stream); hipLaunchKernelGGL(k_attn_generic<float>, dim3(nblocks), dim3(64), 0, stream, a); prof_end(stream); }
+    if (a.dtype == DT_BF16) { prof_begin(K_ATTN_GENERIC, stream); MOA_KLAUNCH(k_attn_generic<bf16_t>, dim3(nblocks), dim3(64), 0, stream, a); prof_end(stream); }
+    else { prof_begin(K_ATTN_GENERIC, stream); MOA_KLAUNCH(k_attn_generic<float>, dim3(nblocks), dim3(64), 0, stream, a); prof_end(stream); }
     return hipGetLastError();
 }
 
@@ -736,7 +736,7 @@ static hipError_t launch_fused_as(const AttnGroup &grp, int nrb, unsigned grid, 
         if (dev >= 0 && dev < 16) raised[dev] = true;
     }
     prof_begin(K_ATTN_FUSED + 64 * (DH * 8 + NW / 4), stream);
-    hipLaunchKernelGGL((k_attn_fused<DH, NW>), dim3(grid), dim3(64 * NW), lds, stream, grp, nrb);
+    MOA_KLAUNCH((k_attn_fused<DH, NW>), dim3(grid), dim3(64 * NW), lds, stream, grp, nrb);
     prof_end(stream);
     return hipGetLastError();
 }
@@ -773,18 +773,18 @@ static hipError_t launch_attn_split(const AttnArgs *calls, int n, hipStream_t st
     const int var = a.dh * 8 + (two ? 2 : 1);
     prof_begin(K_ATTN_MFMA + 64 * var, stream);
     if (a.dh == 128) {
-        if (two) hipLaunchKernelGGL((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, grp, g);
-        else hipLaunchKernelGGL((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, grp, g);
+        if (two) MOA_KLAUNCH((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, grp, g);
+        else MOA_KLAUNCH((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, grp, g);
     } else {
-        if (two) hipLaunchKernelGGL((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, grp, g);
-        else hipLaunchKernelGGL((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, grp, g);
+        if (two) MOA_KLAUNCH((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, grp, g);
+        else MOA_KLAUNCH((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, grp, g);
     }
     prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     prof_begin(K_ATTN_MERGE + 64 * (a.dh * 8), stream);
-    if (a.dh == 128) hipLaunchKernelGGL(k_attn_merge<128>, dim3(nblocks), dim3(64), 0, stream, grp, g);
-    else hipLaunchKernelGGL(k_attn_merge<64>, dim3(nblocks), dim3(64), 0, stream, grp, g);
+    if (a.dh == 128) MOA_KLAUNCH(k_attn_merge<128>, dim3(nblocks), dim3(64), 0, stream, grp, g);
+    else MOA_KLAUNCH(k_attn_merge<64>, dim3(nblocks), dim3(64), 0, stream, grp, g);
     prof_end(stream);
     return hipGetLastError();
 }

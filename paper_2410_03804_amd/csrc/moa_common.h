@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace moa {
@@ -87,6 +88,12 @@ enum SiteId {
 void prof_set_site(int site);
 void prof_begin(int kernel, hipStream_t stream);   // no-ops unless profiling is enabled
 void prof_end(hipStream_t stream);
+// Events of the launch opened by prof_begin (nullptr when it is not being timed).  They are attached to the
+// dispatch itself, so they carry the kernel's own begin and end timestamps and cost the stream nothing.
+hipEvent_t prof_start_event();
+hipEvent_t prof_stop_event();
+#define MOA_KLAUNCH(kernel, grid, block, lds, stream, ...) \
+    hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ::moa::prof_start_event(), ::moa::prof_stop_event(), 0, __VA_ARGS__)
 
 struct LinSeg {
     const void *W;  // [N, K] row-major

@@ -443,7 +443,7 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
     hipError_t e = hipFuncSetAttribute((const void *)k_linear_tiled_bf16<WF, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     prof_begin(K_LIN_TILED + 64 * (WF * 8 + WR), stream);
-    hipLaunchKernelGGL((k_linear_tiled_bf16<WF, WR>), grid, dim3(256), lds, stream, ta);
+    MOA_KLAUNCH((k_linear_tiled_bf16<WF, WR>), grid, dim3(256), lds, stream, ta);
     prof_end(stream);
     return hipGetLastError();
 }
@@ -511,12 +511,12 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             hipError_t e = hipSuccess;
             prof_begin(K_LIN_SPLITK + 64 * nq, stream);
             switch (nq) {
-            case 1: hipLaunchKernelGGL(k_linear_splitk_bf16<1>, grid, dim3(256), lds, stream, ka); break;
-            case 2: hipLaunchKernelGGL(k_linear_splitk_bf16<2>, grid, dim3(256), lds, stream, ka); break;
-            case 4: hipLaunchKernelGGL(k_linear_splitk_bf16<4>, grid, dim3(256), lds, stream, ka); break;
+            case 1: MOA_KLAUNCH(k_linear_splitk_bf16<1>, grid, dim3(256), lds, stream, ka); break;
+            case 2: MOA_KLAUNCH(k_linear_splitk_bf16<2>, grid, dim3(256), lds, stream, ka); break;
+            case 4: MOA_KLAUNCH(k_linear_splitk_bf16<4>, grid, dim3(256), lds, stream, ka); break;
             default:
                 e = hipFuncSetAttribute((const void *)k_linear_splitk_bf16<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-                if (e == hipSuccess) hipLaunchKernelGGL(k_linear_splitk_bf16<8>, grid, dim3(256), lds, stream, ka);
+                if (e == hipSuccess) MOA_KLAUNCH(k_linear_splitk_bf16<8>, grid, dim3(256), lds, stream, ka);
                 break;
             }
             prof_end(stream);
@@ -525,7 +525,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             if (e != hipSuccess) return e;
             const int64_t items = a.R * (ntot / 8);
             prof_begin(K_LIN_REDUCE, stream);
-            hipLaunchKernelGGL(k_linear_splitk_reduce, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, ka);
+            MOA_KLAUNCH(k_linear_splitk_reduce, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, ka);
             prof_end(stream);
             return hipGetLastError();
         }
@@ -536,17 +536,17 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
         for (int s = 0; s < a.nseg; ++s) { sa.tile_begin[s] = t; t += a.seg[s].N / 32; }
         sa.tile_begin[a.nseg] = t;
         dim3 grid(t, (unsigned)((a.R + 63) / 64));
-        { prof_begin(K_LIN_SKINNY, stream); hipLaunchKernelGGL(k_linear_skinny_bf16<2>, grid, dim3(256), 0, stream, sa); prof_end(stream); }
+        { prof_begin(K_LIN_SKINNY, stream); MOA_KLAUNCH(k_linear_skinny_bf16<2>, grid, dim3(256), 0, stream, sa); prof_end(stream); }
         return hipGetLastError();
     }
     if (own_x) return launch_linear_each(dtype, a, stream);
     for (int s = 0; s < a.nseg; ++s) {
         dim3 grid((a.seg[s].N + 63) / 64, (unsigned)((a.R + 63) / 64));
         if (dtype == DT_BF16)
-            { prof_begin(K_LIN_GENERIC, stream); hipLaunchKernelGGL(k_linear_generic<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)a.X, a.R, a.K,
+            { prof_begin(K_LIN_GENERIC, stream); MOA_KLAUNCH(k_linear_generic<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)a.X, a.R, a.K,
                                a.ldx, (const bf16_t *)a.seg[s].W, a.seg[s].N, a.seg[s].st); prof_end(stream); }
         else
-            { prof_begin(K_LIN_GENERIC, stream); hipLaunchKernelGGL(k_linear_generic<float>, grid, dim3(256), 0, stream, (const float *)a.X, a.R, a.K,
+            { prof_begin(K_LIN_GENERIC, stream); MOA_KLAUNCH(k_linear_generic<float>, grid, dim3(256), 0, stream, (const float *)a.X, a.R, a.K,
                                a.ldx, (const float *)a.seg[s].W, a.seg[s].N, a.seg[s].st); prof_end(stream); }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -579,9 +579,9 @@ hipError_t launch_scatter_copy(int dtype, const void *X, int64_t R, int N, int64
     const int64_t total = R * N;
     const dim3 grid((unsigned)((total + 255) / 256));
     if (dtype == DT_BF16)
-        { prof_begin(K_SCATTER, stream); hipLaunchKernelGGL(k_scatter_copy<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)X, R, N, ldx, st); prof_end(stream); }
+        { prof_begin(K_SCATTER, stream); MOA_KLAUNCH(k_scatter_copy<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)X, R, N, ldx, st); prof_end(stream); }
     else
-        { prof_begin(K_SCATTER, stream); hipLaunchKernelGGL(k_scatter_copy<float>, grid, dim3(256), 0, stream, (const float *)X, R, N, ldx, st); prof_end(stream); }
+        { prof_begin(K_SCATTER, stream); MOA_KLAUNCH(k_scatter_copy<float>, grid, dim3(256), 0, stream, (const float *)X, R, N, ldx, st); prof_end(stream); }
     return hipGetLastError();
 }
 

@@ -233,7 +233,7 @@ hipError_t launch_lsa_attn(const LsaAttnArgs &a, hipStream_t stream)
         const dim3 grid((unsigned)((a.T * a.Hq + 3) / 4));
         const int nb = (a.L + 31) / 32;
         prof_begin(K_LSA_ATTN_MFMA + 64 * (a.dh * 8 + nb), stream);
-#define MOA_LSA_CASE(DH, NBV) hipLaunchKernelGGL((k_lsa_attn_mfma<DH, NBV>), grid, dim3(256), 0, stream, a)
+#define MOA_LSA_CASE(DH, NBV) MOA_KLAUNCH((k_lsa_attn_mfma<DH, NBV>), grid, dim3(256), 0, stream, a)
         if (a.dh == 128) { if (nb == 1) MOA_LSA_CASE(128, 1); else if (nb == 2) MOA_LSA_CASE(128, 2); else MOA_LSA_CASE(128, 3); }
         else { if (nb == 1) MOA_LSA_CASE(64, 1); else if (nb == 2) MOA_LSA_CASE(64, 2); else MOA_LSA_CASE(64, 3); }
 #undef MOA_LSA_CASE
@@ -246,11 +246,11 @@ hipError_t launch_lsa_attn(const LsaAttnArgs &a, hipStream_t stream)
     if (a.dtype == DT_BF16) {
         e = hipFuncSetAttribute((const void *)k_lsa_attn<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        { prof_begin(K_LSA_ATTN, stream); hipLaunchKernelGGL(k_lsa_attn<bf16_t>, grid, dim3(256), lds, stream, a); prof_end(stream); }
+        { prof_begin(K_LSA_ATTN, stream); MOA_KLAUNCH(k_lsa_attn<bf16_t>, grid, dim3(256), lds, stream, a); prof_end(stream); }
     } else {
         e = hipFuncSetAttribute((const void *)k_lsa_attn<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        { prof_begin(K_LSA_ATTN, stream); hipLaunchKernelGGL(k_lsa_attn<float>, grid, dim3(256), lds, stream, a); prof_end(stream); }
+        { prof_begin(K_LSA_ATTN, stream); MOA_KLAUNCH(k_lsa_attn<float>, grid, dim3(256), lds, stream, a); prof_end(stream); }
     }
     return hipGetLastError();
 }

@@ -21,6 +21,7 @@ std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 thread_local int t_site = S_NONE;
 thread_local bool t_open = false;
+thread_local hipEvent_t t_e0 = nullptr, t_e1 = nullptr;
 
 hipEvent_t take_event()
 {
@@ -49,18 +50,21 @@ void prof_begin(int kernel, hipStream_t stream)
     if (g_seen++ % g_every) return;
     Rec r = {t_site, kernel, take_event(), take_event()};
     if (!r.e0 || !r.e1) return;
-    if (hipEventRecord(r.e0, stream) != hipSuccess) return;
     g_recs.push_back(r);
+    t_e0 = r.e0;
+    t_e1 = r.e1;
     t_open = true;
+    (void)stream;
 }
 
-void prof_end(hipStream_t stream)
+void prof_end(hipStream_t)
 {
-    if (!t_open) return;
-    std::lock_guard<std::mutex> lk(g_mu);
     t_open = false;
-    if (!g_recs.empty()) (void)hipEventRecord(g_recs.back().e1, stream);
+    t_e0 = t_e1 = nullptr;
 }
+
+hipEvent_t prof_start_event() { return t_open ? t_e0 : nullptr; }
+hipEvent_t prof_stop_event() { return t_open ? t_e1 : nullptr; }
 
 }  // namespace moa
 

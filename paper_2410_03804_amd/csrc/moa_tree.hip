@@ -134,21 +134,21 @@ __global__ __launch_bounds__(64) void k_step_small(StepSmallArgs a)
 hipError_t launch_tree_build(const int32_t *parent, int B, int M, uint64_t *mask, int32_t *depth,
                              int32_t *dev_status, hipStream_t stream)
 {
-    { prof_begin(K_TREE_BUILD, stream); hipLaunchKernelGGL(k_tree_build, dim3(B), dim3(64), 0, stream, parent, M, mask, depth, dev_status); prof_end(stream); }
+    { prof_begin(K_TREE_BUILD, stream); MOA_KLAUNCH(k_tree_build, dim3(B), dim3(64), 0, stream, parent, M, mask, depth, dev_status); prof_end(stream); }
     return hipGetLastError();
 }
 
 hipError_t launch_tree_accept(const int32_t *parent, const int32_t *tok, const int32_t *tgt, int B, int M,
                               int32_t *path, int32_t *n_path, int32_t *bonus, hipStream_t stream)
 {
-    { prof_begin(K_TREE_ACCEPT, stream); hipLaunchKernelGGL(k_tree_accept, dim3(B), dim3(64), 0, stream, parent, tok, tgt, M, path, n_path, bonus); prof_end(stream); }
+    { prof_begin(K_TREE_ACCEPT, stream); MOA_KLAUNCH(k_tree_accept, dim3(B), dim3(64), 0, stream, parent, tok, tgt, M, path, n_path, bonus); prof_end(stream); }
     return hipGetLastError();
 }
 
 hipError_t launch_step_small(const StepSmallArgs &a, hipStream_t stream)
 {
     prof_begin(K_STEP_SMALL, stream);
-    hipLaunchKernelGGL(k_step_small, dim3(2 * a.B + 1), dim3(64), 0, stream, a);
+    MOA_KLAUNCH(k_step_small, dim3(2 * a.B + 1), dim3(64), 0, stream, a);
     prof_end(stream);
     return hipGetLastError();
 }
@@ -156,7 +156,7 @@ hipError_t launch_step_small(const StepSmallArgs &a, hipStream_t stream)
 hipError_t launch_append_lengths(const int32_t *tok_off, int B, int32_t *ca_len, int cap, int32_t *dev_status,
                                  hipStream_t stream)
 {
-    { prof_begin(K_APPEND_LEN, stream); hipLaunchKernelGGL(k_append_lengths, dim3((B + 63) / 64), dim3(64), 0, stream, tok_off, B, ca_len, cap,
+    { prof_begin(K_APPEND_LEN, stream); MOA_KLAUNCH(k_append_lengths, dim3((B + 63) / 64), dim3(64), 0, stream, tok_off, B, ca_len, cap,
                        dev_status); prof_end(stream); }
     return hipGetLastError();
 }
