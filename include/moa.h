@@ -211,6 +211,15 @@ int32_t moa_profile_collect(moa_profile_row_t *rows_host, int32_t max_rows, int3
 const char *moa_profile_kernel_name(int32_t kernel);
 const char *moa_profile_site_name(int32_t site);
 
+/* Two probes of what the device delivers in practice, timed like any other kernel through the aid
+ * above (kernels "k_probe_read", "k_probe_mfma"); a benchmark prints them beside the published
+ * peaks.  moa_probe_read streams `bytes` (multiple of 16, 16-byte aligned device buffer) once with
+ * plain coalesced loads.  moa_probe_mfma runs iters x 4 independent register-resident bf16
+ * 32x32x16 MFMAs in each of 4096 wavefronts and returns the flop count in *flops_host.
+ * scratch4: 4 writable device bytes (never written in practice).  Not part of the method. */
+int32_t moa_probe_read(const void *buf, size_t bytes, void *scratch4, void *stream);
+int32_t moa_probe_mfma(int32_t iters, void *scratch4, int64_t *flops_host, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

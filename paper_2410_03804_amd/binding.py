@@ -64,7 +64,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
-            "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name"]
+            "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -95,6 +95,8 @@ _lib.moa_profile_kernel_name.restype = C.c_char_p
 _lib.moa_profile_kernel_name.argtypes = [_i32]
 _lib.moa_profile_site_name.restype = C.c_char_p
 _lib.moa_profile_site_name.argtypes = [_i32]
+_lib.moa_probe_read.argtypes = [_vp, _sz, _vp, _vp]
+_lib.moa_probe_mfma.argtypes = [_i32, _vp, C.POINTER(_i64), _vp]
 
 
 def library_path() -> str:
@@ -339,6 +341,19 @@ def profile_enable(on: bool, only_kernel: str | None = None, every: int = 1):
     """Events around every `every`-th launch (of `only_kernel` only, when given)."""
     _check(_lib.moa_profile_sample_every(every))
     _check(_lib.moa_profile_enable(1 if on else 0, -1 if only_kernel is None else profile_kernel_id(only_kernel)))
+
+
+def probe_read(buf, scratch4, stream=None):
+    """One plain streaming read of the whole tensor (a measurement probe)."""
+    _check(_lib.moa_probe_read(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                               C.c_void_p(scratch4.data_ptr()), _stream(stream)))
+
+
+def probe_mfma(iters: int, scratch4, stream=None) -> int:
+    """Register-resident bf16 MFMA loop (a measurement probe); returns the flops it executes."""
+    fl = _i64(0)
+    _check(_lib.moa_probe_mfma(iters, C.c_void_p(scratch4.data_ptr()), C.byref(fl), _stream(stream)))
+    return fl.value
 
 
 def profile_collect():

@@ -5,6 +5,7 @@
 #include "moa_common.h"
 
 #include <stdio.h>
+#include <stdlib.h>
 
 #include <mutex>
 #include <vector>
@@ -33,11 +34,11 @@ hipEvent_t take_event()
 
 const char *const kKernelNames[K_COUNT] = {
     "k_tree_build", "k_tree_accept", "k_append_lengths", "k_linear_generic", "k_linear_skinny_bf16", "k_linear_splitk_bf16",
-    "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn", "k_lsa_attn_mfma", "k_step_small", "k_attn_fused"};
+    "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn", "k_lsa_attn_mfma", "k_step_small", "k_attn_fused", "k_probe_read", "k_probe_mfma"};
 const char *const kSiteNames[S_COUNT] = {
     "none", "tree_build", "lsa.qkv_proj", "lsa.layer_attn", "lsa.o_proj", "ca_append.kv_proj", "ca_append.lengths",
     "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept",
-    "tree_build+accept+lengths", "ca.q_proj+verify.qkv_proj", "ca.core+verify.core", "ca.o_proj+verify.o_proj"};
+    "tree_build+accept+lengths", "ca.q_proj+verify.qkv_proj", "ca.core+verify.core", "ca.o_proj+verify.o_proj", "probe"};
 }  // namespace
 
 void prof_set_site(int site) { t_site = site; }
@@ -65,6 +66,44 @@ void prof_end(hipStream_t)
 
 hipEvent_t prof_start_event() { return t_open ? t_e0 : nullptr; }
 hipEvent_t prof_stop_event() { return t_open ? t_e1 : nullptr; }
+
+// ---- two probes of what this device delivers in practice, to put beside the published peaks
+// plain streaming read: every lane 16 bytes, consecutive lanes consecutive addresses, eight loads in flight
+__global__ __launch_bounds__(256) void k_probe_read(const u32x4 *__restrict__ p, size_t n16, uint32_t *sink)
+{
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    for (; i < n16; i += stride) acc ^= p[i];
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) *sink = acc[0];   // keeps the loads alive
+}
+
+// register-resident bf16 MFMA 32x32x16, four independent accumulators per wavefront, 16 wavefronts per CU
+__global__ __launch_bounds__(256) void k_probe_mfma(int iters, float *sink)
+{
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(0.001f * (float)(threadIdx.x + e)); b[e] = (__bf16)(0.002f * (float)(threadIdx.x - e)); }
+    f32x16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[q], 0, 0, 0);
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) s += acc[q][0] + acc[q][15];
+    if (s == 123456.789f) *sink = s;
+}
 
 }  // namespace moa
 
@@ -114,6 +153,31 @@ int32_t moa_profile_collect(moa_profile_row_t *rows_host, int32_t max_rows, int3
     g_recs.clear();
     *n_rows_host = n;
     return rc;
+}
+
+int32_t moa_probe_read(const void *buf, size_t bytes, void *scratch4, void *stream)
+{
+    if (!buf || !scratch4 || bytes < 16 || (((uintptr_t)buf) & 15)) return MOA_ERR_NULL;
+    prof_set_site(S_PROBE);
+    prof_begin(K_PROBE_READ, (hipStream_t)stream);
+    // one long-lived workgroup per compute unit streams fastest here (6.5 TB/s; 5.1 TB/s with eight per unit)
+    int dev = 0, pg = 256;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&pg, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || pg < 1) pg = 256;
+    MOA_KLAUNCH(k_probe_read, dim3(pg), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)buf, bytes / 16, (uint32_t *)scratch4);
+    prof_end((hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? MOA_OK : MOA_ERR_HIP;
+}
+
+int32_t moa_probe_mfma(int32_t iters, void *scratch4, int64_t *flops_host, void *stream)
+{
+    if (!scratch4 || !flops_host || iters < 1) return MOA_ERR_NULL;
+    const int blocks = 256 * 4;                       // four workgroups of four wavefronts per compute unit
+    *flops_host = (int64_t)blocks * 4 * iters * 4 * (2LL * 32 * 32 * 16);
+    prof_set_site(S_PROBE);
+    prof_begin(K_PROBE_MFMA, (hipStream_t)stream);
+    MOA_KLAUNCH(k_probe_mfma, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (int)iters, (float *)scratch4);
+    prof_end((hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? MOA_OK : MOA_ERR_HIP;
 }
 
 // ids are base + 64 * variant; the variant spells the template arguments the way a profiler prints them
