@@ -30,10 +30,10 @@ VEC_F32_PEAK_TFLOPS = 157.3
 # plain 512 MiB device copy (fetch x2.000, write x1.000): profiles/c1_draft_step_hbm_traffic_pmc.md.  They hold for
 # the default workload only (C1, 2*E_kv-wide LSA input, one verify layer).
 PMC_TRAFFIC_MIB_C1 = {
-    "k_linear_splitk_bf16<4>": 45.02,
-    "k_linear_splitk_bf16<2>": 12.04,
-    "k_linear_tiled_bf16<2, 2>": 91.67,
-    "k_attn_mfma<128, 1>": 18.32,
+    "k_linear_splitk_bf16<4>": 89.89,     # mean of the two grouped launches of the default schedule
+    "k_linear_splitk_bf16<2>": 12.03,
+    "k_linear_tiled_bf16<2, 2>": 94.91,
+    "k_attn_fused<128, 8>": 10.27,
 }
 
 
@@ -291,7 +291,8 @@ def main():
             ach = flo / (avg_us * 1e-6) / 1e12
             roofline = dict(bound="mfma", achieved=round(ach, 2), peak=peak_mm, unit="TFLOP/s",
                             frac=round(ach / peak_mm, 4), traffic=None)
-        if cfg.name == "C1" and not args.d_lsa_in and NL == 1 and dominant in PMC_TRAFFIC_MIB_C1:
+        if (cfg.name == "C1" and not args.d_lsa_in and NL == 1 and args.schedule == "grouped"
+                and dominant in PMC_TRAFFIC_MIB_C1):
             roofline["traffic"] = int(PMC_TRAFFIC_MIB_C1[dominant] * 2 ** 20)
         if ceilings:
             ceil = ceilings["hbm_read_gbs"] if roofline["bound"] == "hbm" else ceilings["mfma_bf16_tflops"]
