@@ -82,16 +82,17 @@ StoreSpec heads_store(void *dst, int heads, int dh, int cap, int rows_per_seq)
     return st;
 }
 
-constexpr int64_t LSA_CHUNK = 256;   // tokens projected per pass (bounds the Q/K/V scratch)
+constexpr int64_t LSA_CHUNK = 256;    // tokens projected per pass (bounds the Q/K/V scratch)
+constexpr int64_t LSA_OBLOCK = 4096;  // tokens per output-projection pass (one GEMM over many chunks' mean-folded heads)
 
 size_t max2(size_t a, size_t b) { return a > b ? a : b; }
 
 size_t lsa_ws_bytes(const moa_shape_t *s, int64_t T)
 {
-    const int64_t tc = T < LSA_CHUNK ? T : LSA_CHUNK;
+    const int64_t tc = T < LSA_CHUNK ? T : LSA_CHUNK, ob = T < LSA_OBLOCK ? T : LSA_OBLOCK;
     const size_t eq = (size_t)s->lsa_q_heads * s->head_dim, ekv = (size_t)s->lsa_kv_heads * s->head_dim;
-    return align256((size_t)tc * s->n_layers * (eq + 2 * ekv) * esize(s->dtype)) + align256((size_t)tc * eq * esize(s->dtype)) +
-           align256(linear_workspace_bytes(s->dtype, tc, (int)eq, (int)eq));
+    return align256((size_t)tc * s->n_layers * (eq + 2 * ekv) * esize(s->dtype)) + align256((size_t)ob * eq * esize(s->dtype)) +
+           align256(linear_workspace_bytes(s->dtype, ob, (int)eq, (int)eq));
 }
 
 // scratch shared by the projections' split-K partials and the attention core's split-KV partials
@@ -239,15 +240,17 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     const size_t es = esize(dt);
-    const int64_t tc_max = T < LSA_CHUNK ? T : LSA_CHUNK;
+    const int64_t tc_max = T < LSA_CHUNK ? T : LSA_CHUNK, ob_max = T < LSA_OBLOCK ? T : LSA_OBLOCK;
     const int wide = eq + 2 * ekv;
     char *qkv = (char *)ws;
-    char *abar = qkv + align256((size_t)tc_max * L * wide * es);
-    char *lin_ws = abar + align256((size_t)tc_max * eq * es);
+    char *abar0 = qkv + align256((size_t)tc_max * L * wide * es);
+    char *lin_ws = abar0 + align256((size_t)ob_max * eq * es);
     const size_t lin_ws_bytes = ws_bytes - (size_t)(lin_ws - (char *)ws);
 
     for (int64_t t0 = 0; t0 < T; t0 += LSA_CHUNK) {
         const int64_t tc = (T - t0) < LSA_CHUNK ? (T - t0) : LSA_CHUNK;
+        const int64_t b0 = (t0 / LSA_OBLOCK) * LSA_OBLOCK;            // first token of this output-projection block
+        char *abar = abar0 + (size_t)(t0 - b0) * eq * es;
         const char *x = (const char *)hs + (size_t)t0 * L * d_in * es;
         LinArgs la = {};
         la.X = x;
@@ -283,16 +286,17 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
         aa.abar = wo ? (void *)abar : (void *)orow;
         prof_set_site(S_LSA_ATTN);
         MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
-        if (wo) {
+        const bool block_done = t0 + tc >= T || (t0 + tc) % LSA_OBLOCK == 0;
+        if (wo && block_done) {                                      // W_o once per block, on one row per token
             LinArgs lo = {};
-            lo.X = abar;
-            lo.R = tc;
+            lo.X = abar0;
+            lo.R = t0 + tc - b0;
             lo.K = eq;
             lo.ldx = eq;
             lo.nseg = 1;
             lo.seg[0].W = wo;
             lo.seg[0].N = eq;
-            lo.seg[0].st = row_store(orow, eq);
+            lo.seg[0].st = row_store((char *)out + (size_t)b0 * eq * es, eq);
             lo.ws = lin_ws;
             lo.ws_bytes = lin_ws_bytes;
             prof_set_site(S_LSA_OPROJ);

@@ -53,15 +53,16 @@ struct StoreSpec {
     int32_t *dev_status;
 };
 
-// element offset of (r, n) or -1 when the element is dropped
-__device__ __forceinline__ int64_t store_offset(const StoreSpec &s, int64_t r, int n)
+// The element offset of (r, n) is store_row_part(r) + store_feat_part(n); a negative row part means the row is
+// dropped.  Kernels that store many features of one row compute the row part once (for an append it contains
+// the search for the row's sequence).
+__device__ __forceinline__ int64_t store_row_part(const StoreSpec &s, int64_t r)
 {
-    if (s.mode == StoreSpec::ROW) return r * s.ld + n;
-    const int g = n / s.dh, c = n - g * s.dh;
+    if (s.mode == StoreSpec::ROW) return r * s.ld;
     if (s.mode == StoreSpec::HEADS) {
         const int64_t b = r / s.rows_per_seq;
         const int m = (int)(r - b * s.rows_per_seq);
-        return ((b * s.heads + g) * (int64_t)s.cap + m) * s.dh + c;
+        return (b * s.heads * (int64_t)s.cap + m) * s.dh;
     }
     int b = -1;
     for (int i = 0; i < s.B; ++i) {
@@ -72,7 +73,21 @@ __device__ __forceinline__ int64_t store_offset(const StoreSpec &s, int64_t r, i
     if (base < 0) base = 0;
     const int64_t pos = (int64_t)base + (r - s.tok_off[b]);
     if (pos >= s.cap) return -1;
-    return (((int64_t)b * s.heads + g) * (int64_t)s.cap + pos) * s.dh + c;
+    return ((int64_t)b * s.heads * (int64_t)s.cap + pos) * s.dh;
+}
+
+__device__ __forceinline__ int64_t store_feat_part(const StoreSpec &s, int n)
+{
+    if (s.mode == StoreSpec::ROW) return n;
+    const int g = n / s.dh, c = n - g * s.dh;
+    return (int64_t)g * s.cap * s.dh + c;
+}
+
+// element offset of (r, n) or -1 when the element is dropped
+__device__ __forceinline__ int64_t store_offset(const StoreSpec &s, int64_t r, int n)
+{
+    const int64_t rp = store_row_part(s, r);
+    return rp < 0 ? -1 : rp + store_feat_part(s, n);
 }
 
 // ---- optional per-launch timing (hipEvents around single kernels), used by the benchmark only

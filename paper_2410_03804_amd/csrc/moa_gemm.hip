@@ -192,52 +192,63 @@ __global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
     while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
     const int n0 = (tile - sa.tile_begin[s]) * 64 + wave * 16;   // feature inside the segment
     const int k0 = split * KS;
-    const int64_t r0 = (int64_t)blockIdx.y * 64;
     const bf16_t *X = (const bf16_t *)(a.seg[s].X ? a.seg[s].X : a.X);
     const int64_t ldx = a.seg[s].X ? a.seg[s].ldx : a.ldx;
     const bf16_t *W = (const bf16_t *)a.seg[s].W;
+    const int rowtiles = (int)((a.R + 63) >> 6);
 
+    // X slice of row tile rt into registers (rows past the end repeat the last row; never stored)
     u32x4 xr[XL];
+    auto load_x = [&](int rt) {
 #pragma unroll
-    for (int i = 0; i < XL; ++i) {
-        const int c = tid + 256 * i;
-        int64_t r = r0 + c / CPR;
-        if (r > a.R - 1) r = a.R - 1;          // rows past the end repeat the last row; never stored
-        xr[i] = *(const u32x4 *)(X + r * ldx + k0 + 8 * (c % CPR));
-    }
+        for (int i = 0; i < XL; ++i) {
+            const int c = tid + 256 * i;
+            int64_t r = (int64_t)rt * 64 + c / CPR;
+            if (r > a.R - 1) r = a.R - 1;
+            xr[i] = *(const u32x4 *)(X + r * ldx + k0 + 8 * (c % CPR));
+        }
+    };
+    load_x(0);
     bf16x8 wf[NQ][4];
     const bf16_t *wp = W + (int64_t)(n0 + li) * a.K + k0 + 32 * kg;
 #pragma unroll
     for (int q = 0; q < NQ; ++q)
 #pragma unroll
         for (int j = 0; j < 4; ++j) wf[q][j] = *(const bf16x8 *)(wp + 128 * q + 8 * j);
-#pragma unroll
-    for (int i = 0; i < XL; ++i) {
-        const int c = tid + 256 * i;
-        *(u32x4 *)&Xs[(c / CPR) * LDK + 8 * (c % CPR)] = xr[i];
-    }
-    __syncthreads();
 
-    f32x4 acc[4];
+    // The weights stay in registers while the workgroup walks the row tiles (one at decode sizes): W is
+    // streamed once however many rows there are; the next tile's X slice is requested before this one is used.
+    for (int rt = 0; rt < rowtiles; ++rt) {
+        if (rt > 0) __syncthreads();           // every wave is done reading the previous slice
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int q = 0; q < NQ; ++q)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            bf16x8 xf[4];
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) xf[rb] = *(const bf16x8 *)&Xs[(16 * rb + li) * LDK + 128 * q + 32 * kg + 8 * j];
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb)
-                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[q][j], xf[rb], acc[rb], 0, 0, 0);
+        for (int i = 0; i < XL; ++i) {
+            const int c = tid + 256 * i;
+            *(u32x4 *)&Xs[(c / CPR) * LDK + 8 * (c % CPR)] = xr[i];
         }
+        __syncthreads();
+        if (rt + 1 < rowtiles) load_x(rt + 1);
 
-    // lane holds features 4 kg .. 4 kg + 3 of its wave's 16, for row 16 rb + li
-    float *p = sa.part + ((int64_t)blockIdx.y * sa.splits + split) * 64 * sa.ntot + tile * 64 + wave * 16 + 4 * kg;
+        f32x4 acc[4];
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
-        if (r0 + 16 * rb + li < a.R) *(f32x4 *)(p + (int64_t)(16 * rb + li) * sa.ntot) = acc[rb];
+        for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bf16x8 xf[4];
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) xf[rb] = *(const bf16x8 *)&Xs[(16 * rb + li) * LDK + 128 * q + 32 * kg + 8 * j];
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[q][j], xf[rb], acc[rb], 0, 0, 0);
+            }
+
+        // lane holds features 4 kg .. 4 kg + 3 of its wave's 16, for row 16 rb + li of this row tile
+        float *p = sa.part + ((int64_t)rt * sa.splits + split) * 64 * sa.ntot + tile * 64 + wave * 16 + 4 * kg;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+            if ((int64_t)rt * 64 + 16 * rb + li < a.R) *(f32x4 *)(p + (int64_t)(16 * rb + li) * sa.ntot) = acc[rb];
+    }
 }
 
 // one thread per (row, 8 consecutive features): sum the K slices in order, round once, store
@@ -279,6 +290,11 @@ __global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
     *(u32x4 *)((bf16_t *)a.seg[s].st.dst + off) = pk;
 }
 
+// rows up to which the weight-streaming kernel is used (it walks 64-row tiles with the weights in registers).
+// Its fp32 partial sums are 128 * row tiles / (K slice) of the weight bytes: a quarter at one row tile of 512-wide
+// slices, as much as the weights at four, so above two row tiles the tiled kernel takes over
+constexpr int64_t SPLITK_MAX_ROWS = 128;
+
 static int splitk_nq(int K)
 {
     for (int nq = 1; nq <= 8; nq *= 2)
@@ -288,7 +304,7 @@ static int splitk_nq(int K)
 
 size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot)
 {
-    if (dtype != DT_BF16 || R > 128 || K % 128 || ntot % 64) return 0;
+    if (dtype != DT_BF16 || R > SPLITK_MAX_ROWS || K % 128 || ntot % 64) return 0;
     const int nq = splitk_nq(K);
     if (!nq) return 0;
     const size_t splits = K / (128 * nq), rowtiles = (size_t)((R + 63) / 64);
@@ -337,7 +353,8 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
     const int wr0 = (wave >> 1) * (32 * WR);  // row offset
     const int K = a.K;
     const bf16_t *W = (const bf16_t *)a.seg[s].W;
-    const bf16_t *X = (const bf16_t *)a.X;
+    const bf16_t *X = (const bf16_t *)(a.seg[s].X ? a.seg[s].X : a.X);
+    const int64_t ldx = a.seg[s].X ? a.seg[s].ldx : a.ldx;
 
     // wave w moves tile rows (BN/4) w .. of W and (BM/4) w .. of X, eight rows per instruction
     const int lrow = lane >> 3, lpos = lane & 7;
@@ -352,7 +369,7 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
         const int row = (BM / 4) * wave + 8 * i + lrow;
         int64_t r = r0 + row;
         if (r > a.R - 1) r = a.R - 1;          // rows past the end repeat the last row; never stored
-        xsrc[i] = X + r * a.ldx + 8 * (lpos ^ ((row >> 1) & 7));
+        xsrc[i] = X + r * ldx + 8 * (lpos ^ ((row >> 1) & 7));
     }
     auto issue = [&](int buf, int kt) {
         bf16_t *wb = tsm + buf * STAGE;
@@ -413,13 +430,14 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
     for (int jj = 0; jj < WR; ++jj) {
         const int64_t r = r0 + wr0 + 32 * jj + l32;
         if (r >= a.R) continue;
+        const int64_t rp = store_row_part(a.seg[s].st, r);
+        if (rp < 0) continue;
 #pragma unroll
         for (int i = 0; i < WF; ++i)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int n = n0 + wf0 + 32 * i + 8 * q + 4 * half;
-                const int64_t off = store_offset(a.seg[s].st, r, n);
-                if (off < 0) continue;
+                const int64_t off = rp + store_feat_part(a.seg[s].st, n);
                 u32x2 pk;
                 pk[0] = (uint32_t)f2bf(acc[i][jj][4 * q + 0]) | ((uint32_t)f2bf(acc[i][jj][4 * q + 1]) << 16);
                 pk[1] = (uint32_t)f2bf(acc[i][jj][4 * q + 2]) | ((uint32_t)f2bf(acc[i][jj][4 * q + 3]) << 16);
@@ -482,8 +500,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
     if (fast) {
         bool all128 = true;
         for (int s = 0; s < a.nseg; ++s) all128 = all128 && a.seg[s].N % 128 == 0;
-        if (own_x && (a.R > 128 || !a.ws)) return launch_linear_each(dtype, a, stream);
-        if (a.R > 128 && all128) {
+        if (a.R > SPLITK_MAX_ROWS && all128) {
             bool all256 = true;
             for (int s = 0; s < a.nseg; ++s) all256 = all256 && a.seg[s].N % 256 == 0;
             // 2x2 blocks per wave keeps two workgroups per CU; the 4x2 variant halves the LDS traffic per MFMA
@@ -506,7 +523,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             ka.splits = a.K / (128 * nq);
             ka.ntot = ntot;
             ka.part = (float *)a.ws;
-            const dim3 grid(t * ka.splits, (unsigned)((a.R + 63) / 64));
+            const dim3 grid(t * ka.splits);
             const size_t lds = (size_t)64 * (128 * nq + 8) * sizeof(bf16_t);
             hipError_t e = hipSuccess;
             prof_begin(K_LIN_SPLITK + 64 * nq, stream);
