@@ -4,13 +4,17 @@
 //
 //   k_attn_generic   any dtype / head_dim <= 256: one wavefront per (sequence, query, head),
 //                    64 keys per step, exact online softmax with wavefront shuffles.
-//   k_attn_mfma      bf16, head_dim 64 / 128: split-KV.  A workgroup owns one (sequence, KV head),
-//                    one slice of the key range and up to 128*NBLK query rows (the GQA group's heads
-//                    times the tree tokens are folded into the row dimension, so K/V are read once for
-//                    all of them).  K/V tiles of 32 keys are staged in LDS by 16-byte loads; scores are
-//                    computed transposed (S^T = K Q^T) so that a lane owns one query column and the
-//                    softmax max/sum need a single cross-lane exchange; P^T feeds the second MFMA
-//                    straight from registers and V is transposed on its way into LDS.
+//   k_attn_fused     bf16, head_dim 64 / 128, short key ranges: a workgroup owns 32 query rows and the
+//                    whole key range (its waves split the keys and are combined through LDS), so there
+//                    are no partial results and no second launch.  Described at the kernel.
+//   k_attn_mfma      bf16, head_dim 64 / 128, long key ranges: split-KV.  A workgroup owns one
+//                    (sequence, KV head), one slice of the key range and up to 128*NBLK query rows (the
+//                    GQA group's heads times the tree tokens are folded into the row dimension, so K/V
+//                    are read once for all of them).  K/V tiles of 32 keys are staged row-major in LDS by
+//                    row-contiguous 16-byte loads; scores are computed transposed (S^T = K Q^T) so that a
+//                    lane owns one query column and the softmax max/sum need a single cross-lane
+//                    exchange; P^T feeds the second MFMA straight from registers and V^T comes out of
+//                    the LDS transpose read.
 //   k_attn_merge     combines the per-slice (max, sum, accumulator) triples.
 #include "moa_common.h"
 #include "../../include/moa.h"
@@ -130,12 +134,13 @@ struct AttnGroup {
     int ncalls;   // 1 or 2
 };
 
-constexpr int KT = 32;        // keys per tile
-constexpr int VLD = KT + 8;   // padded row of the transposed V tile
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 
-// position of key k (0..31) inside a transposed V row: bits 2 and 3 swapped, so that the eight
-// keys one lane contributes to a 16-deep MFMA step are contiguous
-__device__ __forceinline__ int vpos(int k) { return (k & ~12) | ((k & 4) << 1) | ((k & 8) >> 1); }
+// 2^x by the hardware instruction alone: arguments here are <= 0 and results below the normal range may
+// become 0, which a softmax weight may
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr int KT = 32;        // keys per tile
 
 template <int DH, int NBLK>
 __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
@@ -144,13 +149,14 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
     const AttnArgs &a = grp.a[call];
     f16_t *__restrict__ part_o = (f16_t *)a.ws;
     float *__restrict__ part_ml = (float *)(part_o + (size_t)grp.nbg * geo.nsplit * geo.rows_pad * DH);
-    constexpr int KLD = DH + 8;           // padded K row (bf16)
+    constexpr int KLD = DH + 8;           // padded K row (bf16): 16-byte operand reads of 16 rows hit 64 different banks
+    constexpr int VSLD = DH + 32;         // padded V row: the 4 rows x 2 column groups of a transpose read hit different banks
     constexpr int NKS = DH / 16;          // MFMA steps along head_dim
     constexpr int NDB = DH / 32;          // 32-wide blocks of head_dim in the output
     constexpr int CPK = DH / 8;           // 16-byte chunks per key row
     constexpr int NLD = (KT * CPK) / 256; // chunks per thread per tile (1 for DH 64, 2 for DH 128)
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[KT][KLD];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[DH][VLD];
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[KT * KLD];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[KT * VSLD];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int split = blockIdx.x, rowtile = blockIdx.y;
@@ -198,9 +204,21 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
             for (int e = 0; e < 16; ++e) acc[blk][d][e] = 0.f;
     }
 
-    // tile i of this workgroup: cache tile t0+i, or tree tile i-(t1-t0)
+    // tile i of this workgroup: cache tile t0+i, or tree tile i-(t1-t0).  K and V rows are fetched row-contiguously
+    // (16 lanes cover a 256-byte row), staged row-major in LDS; V comes back transposed by the LDS transpose read.
     u32x4 kreg[NLD], vreg[NLD];
+    auto full_tile = [&](int i) { return i < (t1 - t0) && (t0 + i + 1) * KT <= len; };
     auto fetch = [&](int i) {
+        if (full_tile(i)) {
+            const int64_t off0 = (int64_t)(t0 + i) * KT * DH;
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                const int c = tid + 256 * j;
+                kreg[j] = *(const u32x4 *)(kc + off0 + (c / CPK) * DH + (c % CPK) * 8);
+                vreg[j] = *(const u32x4 *)(vc + off0 + (c / CPK) * DH + (c % CPK) * 8);
+            }
+            return;
+        }
         const bool tree = i >= (t1 - t0);
         const int base = tree ? (i - (t1 - t0)) * KT : (t0 + i) * KT;
         const int limit = tree ? Mt : len;
@@ -209,24 +227,22 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             const int c = tid + 256 * j;
-            int kr = base + c / CPK;                       // K: consecutive lanes walk along one key row
-            if (kr > limit - 1) kr = limit - 1;            // rows past the end repeat the last valid row
-            kreg[j] = *(const u32x4 *)(ksrc + (int64_t)kr * DH + (c % CPK) * 8);
-            int vr = base + (c & 31);                      // V: consecutive lanes take consecutive keys
-            if (vr > limit - 1) vr = limit - 1;
-            vreg[j] = *(const u32x4 *)(vsrc + (int64_t)vr * DH + (c >> 5) * 8);
+            int row = base + c / CPK;
+            if (row > limit - 1) row = limit - 1;          // rows past the end repeat the last valid row
+            kreg[j] = *(const u32x4 *)(ksrc + (int64_t)row * DH + (c % CPK) * 8);
+            vreg[j] = *(const u32x4 *)(vsrc + (int64_t)row * DH + (c % CPK) * 8);
         }
     };
     auto stage = [&]() {
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             const int c = tid + 256 * j;
-            *(u32x4 *)&Ks[c / CPK][(c % CPK) * 8] = kreg[j];
-            const int key = vpos(c & 31), d0 = (c >> 5) * 8;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) Vt[d0 + e][key] = (bf16_t)(vreg[j][e >> 1] >> (16 * (e & 1)));
+            *(u32x4 *)&Ks[(c / CPK) * KLD + (c % CPK) * 8] = kreg[j];
+            *(u32x4 *)&Vs[(c / CPK) * VSLD + (c % CPK) * 8] = vreg[j];
         }
     };
+    // transpose read: lane j of a 16-lane group addresses key (j >> 2), head_dim 4 (j & 3) of the group's 16
+    const int tr_off = ((lane & 15) >> 2) * VSLD + 16 * ((lane >> 4) & 1) + 4 * (lane & 3) + 4 * half * VSLD;
 
     if (ntiles > 0) fetch(0);
     for (int i = 0; i < ntiles; ++i) {
@@ -234,10 +250,6 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
         stage();
         __syncthreads();
         if (i + 1 < ntiles) fetch(i + 1);
-
-        const bool tree = i >= (t1 - t0);
-        const int base = tree ? (i - (t1 - t0)) * KT : (t0 + i) * KT;
-        const int limit = tree ? Mt : len;
 
         // S^T tile: keys x queries
         f32x16 s[NBLK];
@@ -247,58 +259,73 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
             for (int e = 0; e < 16; ++e) s[blk][e] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const bf16x8 kf = *(const bf16x8 *)&Ks[l32][16 * ks + 8 * half];
+            const bf16x8 kf = *(const bf16x8 *)&Ks[l32 * KLD + 16 * ks + 8 * half];
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk)
                 s[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[blk][ks], s[blk], 0, 0, 0);
         }
 
+        // keys that do not count (tree rows outside the ancestor set, rows past the end) get -inf; a cache tile
+        // wholly below the length has none (the decision is the same for the whole workgroup)
+        if (!full_tile(i)) {
+            const bool tree = i >= (t1 - t0);
+            const int base = tree ? (i - (t1 - t0)) * KT : (t0 + i) * KT;
+            const int nvalid = (tree ? Mt : len) - base;       // >= 1
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+                uint32_t vis = 0xffffffffu;
+                if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.Mq + mrow_of[blk]) * W + (base >> 6)] >> (base & 63));
+                if (nvalid < 32) vis &= (1u << nvalid) - 1u;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = 8 * (v >> 2) + 4 * half + (v & 3);
+                    if (!((vis >> key) & 1u)) s[blk][v] = -INFINITY;
+                }
+            }
+        }
+
         bf16x8 pf[NBLK][2];
 #pragma unroll
         for (int blk = 0; blk < NBLK; ++blk) {
-            // visibility of the 32 keys of this tile for this lane's query
-            uint32_t vis = 0xffffffffu;
-            if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.Mq + mrow_of[blk]) * W + (base >> 6)] >> (base & 63));
-            const int nvalid = limit - base;               // >= 1
-            if (nvalid < 32) vis &= (1u << nvalid) - 1u;
-            float tmax = -INFINITY;
+            float tmax = s[blk][0];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = 8 * (v >> 2) + 4 * half + (v & 3);
-                const float x = ((vis >> key) & 1u) ? s[blk][v] * sc : -INFINITY;
-                s[blk][v] = x;
-                tmax = fmaxf(tmax, x);
-            }
+            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[blk][v]);
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const float mnew = fmaxf(mrun[blk], tmax);
+            const float mnew = fmaxf(mrun[blk], tmax * sc);    // sc > 0: scaling keeps the order (and -inf)
             const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-            const float corr = exp2f(mrun[blk] - msafe);
+            const float corr = fast_exp2(mrun[blk] - msafe);
             float psum = 0.f;
             float p[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { p[v] = exp2f(s[blk][v] - msafe); psum += p[v]; }
+            for (int v = 0; v < 16; ++v) { p[v] = fast_exp2(fmaf(s[blk][v], sc, -msafe)); psum += p[v]; }
             psum += __shfl_xor(psum, 32);
             lrun[blk] = lrun[blk] * corr + psum;
             mrun[blk] = mnew;
+            if (__any(corr != 1.0f)) {                          // the running max moved in some column
+                asm volatile("" ::: "memory");                  // keep this a real branch: the multiplies are skipped
 #pragma unroll
-            for (int d = 0; d < NDB; ++d)
+                for (int d = 0; d < NDB; ++d)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[blk][d][e] *= corr;
+                    for (int e = 0; e < 16; ++e) acc[blk][d][e] *= corr;
+            }
 #pragma unroll
             for (int st2 = 0; st2 < 2; ++st2)
 #pragma unroll
                 for (int t = 0; t < 8; ++t) pf[blk][st2][t] = (__bf16)p[8 * st2 + t];
         }
 
-        // O^T += V^T P^T
+        // O^T += V^T P^T; P^T slot t of step st2 is key 16 st2 + 8 (t >> 2) + 4 half + (t & 3)
 #pragma unroll
         for (int d = 0; d < NDB; ++d)
 #pragma unroll
             for (int st2 = 0; st2 < 2; ++st2) {
-                const bf16x8 vf = *(const bf16x8 *)&Vt[32 * d + l32][16 * st2 + 8 * half];
+                const bf16_t *vp = Vs + tr_off + 16 * st2 * VSLD + 32 * d;
+                union { i16x4 h[2]; bf16x8 v; } vf;
+                vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)vp);
+                vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(vp + 8 * VSLD));
 #pragma unroll
                 for (int blk = 0; blk < NBLK; ++blk)
-                    acc[blk][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[blk][st2], acc[blk][d], 0, 0, 0);
+                    acc[blk][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[blk][st2], acc[blk][d], 0, 0, 0);
             }
     }
 
@@ -342,12 +369,6 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
 //    the key order of P^T in the score registers.
 // Every row block re-reads the (sequence, KV head)'s K/V, which is why this form is used for short key ranges
 // only; the blocks that share K/V are placed on the same XCD so that the re-reads hit its L2.
-typedef short i16x4 __attribute__((ext_vector_type(4)));
-
-// 2^x by the hardware instruction alone: arguments here are <= 0 and results below the normal range may
-// become 0, which a softmax weight may
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
 __device__ __forceinline__ void wave_lds_sync()
 {
     // LDS traffic of one wavefront is processed in order; this only keeps the compiler from moving a read of
