@@ -155,8 +155,8 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
     constexpr int NDB = DH / 32;          // 32-wide blocks of head_dim in the output
     constexpr int CPK = DH / 8;           // 16-byte chunks per key row
     constexpr int NLD = (KT * CPK) / 256; // chunks per thread per tile (1 for DH 64, 2 for DH 128)
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[KT * KLD];
-    __shared__ __attribute__((aligned(16))) bf16_t Vs[KT * VSLD];
+    __shared__ __attribute__((aligned(16))) bf16_t Ks2[2][KT * KLD];    // two stages: one barrier per tile
+    __shared__ __attribute__((aligned(16))) bf16_t Vs2[2][KT * VSLD];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int split = blockIdx.x, rowtile = blockIdx.y;
@@ -233,23 +233,27 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
             vreg[j] = *(const u32x4 *)(vsrc + (int64_t)row * DH + (c % CPK) * 8);
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             const int c = tid + 256 * j;
-            *(u32x4 *)&Ks[(c / CPK) * KLD + (c % CPK) * 8] = kreg[j];
-            *(u32x4 *)&Vs[(c / CPK) * VSLD + (c % CPK) * 8] = vreg[j];
+            *(u32x4 *)&Ks2[buf][(c / CPK) * KLD + (c % CPK) * 8] = kreg[j];
+            *(u32x4 *)&Vs2[buf][(c / CPK) * VSLD + (c % CPK) * 8] = vreg[j];
         }
     };
     // transpose read: lane j of a 16-lane group addresses key (j >> 2), head_dim 4 (j & 3) of the group's 16
     const int tr_off = ((lane & 15) >> 2) * VSLD + 16 * ((lane >> 4) & 1) + 4 * (lane & 3) + 4 * half * VSLD;
 
-    if (ntiles > 0) fetch(0);
+    // tile i+1 is staged into the other buffer after tile i has been computed (its registers were filled during
+    // that computation); the barrier at the end of an iteration publishes it and retires the reads of tile i
+    if (ntiles > 0) {
+        fetch(0);
+        stage(0);
+        if (ntiles > 1) fetch(1);
+    }
+    __syncthreads();
     for (int i = 0; i < ntiles; ++i) {
-        __syncthreads();          // every wave is done reading the previous tile
-        stage();
-        __syncthreads();
-        if (i + 1 < ntiles) fetch(i + 1);
+        const bf16_t *Ks = Ks2[i & 1], *Vs = Vs2[i & 1];
 
         // S^T tile: keys x queries
         f32x16 s[NBLK];
@@ -327,6 +331,11 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
                 for (int blk = 0; blk < NBLK; ++blk)
                     acc[blk][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[blk][st2], acc[blk][d], 0, 0, 0);
             }
+        if (i + 1 < ntiles) {
+            stage((i + 1) & 1);
+            if (i + 2 < ntiles) fetch(i + 2);
+        }
+        __syncthreads();
     }
 
     // partial results of this slice: the slice's own normalised output (a convex combination of V rows, so it
@@ -690,12 +699,22 @@ static bool mfma_ok(int dtype, int dh, const AttnArgs *a)
     return al(a->q) && al(a->kcache) && al(a->vcache) && al(a->ktree) && al(a->vtree) && al(a->out);
 }
 
+// 32-row blocks per wave of the split-KV kernel
+static int attn_nblk(int RG)
+{
+    // one block per wave keeps two workgroups per CU, which measured 25 % faster than two blocks per wave at
+    // RG = 512 even though K/V are then read by twice as many row tiles (MOA_NBLK=2 selects the other for tuning)
+    const char *e = getenv("MOA_NBLK");
+    (void)RG;
+    return (e && e[0] == '2') ? 2 : 1;
+}
+
 static SplitGeom split_geometry(int B, int Mq, int H, int Hkv, int dh, int P_cap, bool tree)
 {
     const int RG = (H / Hkv) * Mq;
     const int tiles_cap = (P_cap + KT - 1) / KT;
     SplitGeom g;
-    const int nblk = RG > 256 ? 2 : 1;
+    const int nblk = attn_nblk(RG);
     g.rowtiles = (RG + 128 * nblk - 1) / (128 * nblk);
     g.rows_pad = g.rowtiles * 128 * nblk;
     int want = 512 / (B * Hkv * g.rowtiles);        // about two workgroups per compute unit
@@ -790,7 +809,7 @@ static hipError_t launch_attn_split(const AttnArgs *calls, int n, hipStream_t st
     grp.ncalls = n;
     const dim3 grid(g.nsplit, g.rowtiles, n * grp.nbg);
     const int nblocks = n * a.B * a.Mq * a.H;
-    const bool two = (a.H / a.Hkv) * a.Mq > 256;
+    const bool two = attn_nblk((a.H / a.Hkv) * a.Mq) == 2;
     const int var = a.dh * 8 + (two ? 2 : 1);
     prof_begin(K_ATTN_MFMA + 64 * var, stream);
     if (a.dh == 128) {

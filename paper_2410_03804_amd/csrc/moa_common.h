@@ -107,8 +107,12 @@ void prof_end(hipStream_t stream);
 // dispatch itself, so they carry the kernel's own begin and end timestamps and cost the stream nothing.
 hipEvent_t prof_start_event();
 hipEvent_t prof_stop_event();
-#define MOA_KLAUNCH(kernel, grid, block, lds, stream, ...) \
-    hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ::moa::prof_start_event(), ::moa::prof_stop_event(), 0, __VA_ARGS__)
+#define MOA_KLAUNCH(kernel, grid, block, lds, stream, ...)                                                      \
+    do {                                                                                                        \
+        hipEvent_t e0_ = ::moa::prof_start_event(), e1_ = ::moa::prof_stop_event();                             \
+        if (e0_ && e1_) hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, e0_, e1_, 0, __VA_ARGS__);      \
+        else hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                                 \
+    } while (0)
 
 struct LinSeg {
     const void *W;  // [N, K] row-major

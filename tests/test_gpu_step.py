@@ -124,3 +124,88 @@ def test_grouped_schedule_full_memory_flags_and_matches_sequential(G):
     assert res[0][0] == res[1][0] and res[0][0] != 0
     for a, b in zip(res[0][1][0], res[1][1][0]):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("schedule", ["grouped", "two_stream"])
+def test_step_captured_in_a_hip_graph_replays_like_eager(G, schedule):
+    """The step allocates nothing, synchronises nothing and reads its lengths on the device, so it can be captured;
+    every replay (with other eager work and synchronisations in between) must reproduce the eager step bit for bit."""
+    from paper_2410_03804_amd.workload import DeviceStep
+    cfg, nlayers = STEP_CASES["small_bf16"]
+    work = mi.step_workload(cfg, n_verify_layers=nlayers)
+    ref = DeviceStep(work)
+    ref.run(schedule=SCHEDULES[schedule])
+    torch.cuda.synchronize()
+    want_exact, want_merged = _step_outputs(ref)
+
+    step = DeviceStep(work)
+    saved = [t.clone() for t in (step.ca_len[0], step.ca_k, step.ca_v)]
+
+    def reset():
+        for dst, src in zip((step.ca_len[0], step.ca_k, step.ca_v), saved):
+            dst.copy_(src)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step.run(stream=stream, schedule=SCHEDULES[schedule])      # warm-up outside the capture (library-owned stream/events)
+        stream.synchronize()
+        reset()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step.plan(0, SCHEDULES[schedule]).run(torch.cuda.current_stream())
+        for rep in range(3):
+            reset()
+            for t in (step.ca_out, step.lsa_out, *step.v_out):
+                t.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            got_exact, got_merged = _step_outputs(step)
+            for a, b in zip(want_exact + want_merged, got_exact + got_merged):
+                assert torch.equal(a, b), f"replay {rep}"
+            x = torch.randn(256, 256, device="cuda")                 # unrelated eager work between replays
+            (x @ x).sum().item()
+    assert step.dev_status.item() == 0
+
+
+def test_measurement_aid_times_kernels_and_samples(G):
+    """The profiling aid attributes device time to kernels; sampling every n-th launch keeps a share of them;
+    the two ceiling probes run and report plausible rates for this device."""
+    import paper_2410_03804_amd as moa
+    from paper_2410_03804_amd.workload import DeviceStep
+    cfg, nlayers = STEP_CASES["small_bf16"]
+    step = DeviceStep(mi.step_workload(cfg, n_verify_layers=nlayers), n_len_slots=12)
+    step.run(len_slot=0)
+    torch.cuda.synchronize()
+    moa.profile_enable(True)
+    for i in range(4):
+        step.run(len_slot=1 + i)
+    torch.cuda.synchronize()
+    rows = moa.profile_collect()
+    moa.profile_enable(False)
+    assert rows and all(n > 0 and 0.0 < ms < 1e3 for _, _, n, ms in rows)
+    kern = rows[0][1]
+    full = sum(n for _, k, n, _ in rows if k == kern)
+    moa.profile_enable(True, only_kernel=kern, every=3)
+    for i in range(4):
+        step.run(len_slot=5 + i)
+    torch.cuda.synchronize()
+    sampled = moa.profile_collect()
+    moa.profile_enable(False)
+    assert {k for _, k, _, _ in sampled} == {kern}
+    assert sum(n for _, _, n, _ in sampled) == (full + 2) // 3
+    assert moa.profile_collect() == []                                  # off: nothing is recorded
+
+    buf = torch.ones(64 << 20, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.uint8, device="cuda")
+    moa.probe_read(buf, sink)
+    moa.probe_mfma(200, sink)
+    torch.cuda.synchronize()
+    moa.profile_enable(True)
+    moa.probe_read(buf, sink)
+    flops = moa.probe_mfma(200, sink)
+    torch.cuda.synchronize()
+    t = {k: ms for _, k, n, ms in moa.profile_collect()}
+    moa.profile_enable(False)
+    assert 0.2e12 < buf.numel() / (t["k_probe_read"] * 1e-3) < 40e12     # between a fifth of a TB/s and L2 speed
+    assert 0.2e15 < flops / (t["k_probe_mfma"] * 1e-3) < 2.6e15
+    assert torch.all(sink == 0)
