@@ -151,11 +151,12 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
  * The *_host members are HOST arrays of n_verify_layers device pointers.
  * Scheduling (`schedule`), all with the same ordering as seen from `stream`:
  *  MOA_SCHED_GROUPED (0, default): calls of the step that do not depend on each other and have the
- *    same shape share a launch: the integer kernels; the CA query projection with the first
- *    verification layer's Q/K/V projection; the two attention cores; the two output projections.
+ *    same shape share a launch: the CA query projection with the first verification layer's Q/K/V
+ *    projection (the integer work -- tree masks, accept walk, memory lengths -- rides in the first
+ *    workgroups of that grid); the two attention cores; the two output projections.
  *    Needs Mq == M, n_verify_layers >= 1, non-NULL CA and first-layer weights and the workspace
  *    moa_workspace_bytes asks for; otherwise the step runs as MOA_SCHED_SEQUENTIAL.  tok[], tgt[]
- *    and ca_len[] are read at the start of the step, so nothing in the step may produce them.
+ *    and ca_len[] are read by the first launch of the step, so nothing in the step may produce them.
  *  MOA_SCHED_TWO_STREAM (1): the LSA chain feeds only the CA core, so the projections (grouped as
  *    above) and the verification layers run on a second, library-owned stream that is forked from
  *    and joined back into `stream` with events, beside the LSA chain and the CA core on `stream`.

@@ -5,6 +5,7 @@
 
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include <mutex>
 
@@ -591,7 +592,7 @@ static bool pieces_ok(const moa_step_args_t *a)
 }
 
 // tree masks, accepted paths, memory lengths (the old lengths are kept for the append)
-static int32_t piece_small(const moa_step_args_t *a, const StepBufs &bf, hipStream_t st)
+static StepSmallArgs small_args(const moa_step_args_t *a, const StepBufs &bf)
 {
     StepSmallArgs sm = {};
     sm.parent = a->parent;
@@ -609,13 +610,21 @@ static int32_t piece_small(const moa_step_args_t *a, const StepBufs &bf, hipStre
     sm.B = a->B;
     sm.M = a->M;
     sm.cap = a->ca_P_cap;
+    return sm;
+}
+
+static int32_t piece_small(const moa_step_args_t *a, const StepBufs &bf, hipStream_t st)
+{
     prof_set_site(S_STEP_SMALL);
-    MOA_TRY_HIP(launch_step_small(sm, st), "draft_step: tree/lengths");
+    MOA_TRY_HIP(launch_step_small(small_args(a, bf), st), "draft_step: tree/lengths");
     return MOA_OK;
 }
 
 // cross-attention queries + first verification layer's Q/K/V in one launch
-static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st)
+// with_small: the integer work rides in spare workgroups at the end of this launch's grid instead of being a
+// launch of its own (nothing before the LSA chain's append and the attention cores needs its results)
+static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st,
+                                 bool with_small)
 {
     const moa_shape_t *sh = a->shape;
     const int dh = sh->head_dim, Hkv = sh->n_kv_heads, d = sh->d_model, M = a->M;
@@ -641,6 +650,10 @@ static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, v
     la.seg[3].N = ekv;
     la.seg[3].st = heads_store(a->v_vtree_host[0], Hkv, dh, M, M);
     for (int i = 1; i < 4; ++i) { la.seg[i].X = a->v_x_host[0]; la.seg[i].ldx = d; }
+    if (with_small) {
+        la.rider = small_args(a, bf);
+        la.rider_units = 2 * a->B + 1;
+    }
     prof_set_site(S_PAIR_QKV);
     MOA_TRY_HIP(launch_linear(sh->dtype, la, st), "draft_step: projections");
     return MOA_OK;
@@ -756,9 +769,7 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
     const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
     char *scr = nullptr;
     const StepBufs bf = carve_step_bufs(a, L, &scr);
-    int32_t rc = piece_small(a, bf, st);
-    if (rc) return rc;
-    rc = piece_projections(a, bf, scr, L.scratch, st);
+    int32_t rc = piece_projections(a, bf, scr, L.scratch, st, true);
     if (rc) return rc;
     rc = piece_lsa_append(a, bf, scr, L.scratch, st);
     if (rc) return rc;
@@ -822,7 +833,7 @@ static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
     MOA_TRY_HIP(hipStreamWaitEvent(side, ss->fork, 0), "draft_step: fork");
 
     // side branch: projections, then verification layer 0's core and W_o, then the other layers
-    rc = piece_projections(a, bf, scr_side, L.scratch, side);
+    rc = piece_projections(a, bf, scr_side, L.scratch, side, false);
     if (rc) return rc;
     MOA_TRY_HIP(hipEventRecord(ss->caq, side), "draft_step: event");
     prof_set_site(S_VERIFY_CORE);

@@ -114,6 +114,15 @@ hipEvent_t prof_stop_event();
         else hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                                 \
     } while (0)
 
+// the integer work of a step (tree masks, accept walk, memory lengths): 2 B + 1 units of one wavefront each
+struct StepSmallArgs {
+    const int32_t *parent, *tok, *tgt, *tok_off;
+    uint64_t *mask;
+    int32_t *depth, *path, *n_path, *bonus, *ca_len, *old_len, *dev_status;
+    int B, M, cap;
+};
+hipError_t launch_step_small(const StepSmallArgs &a, hipStream_t stream);
+
 struct LinSeg {
     const void *W;  // [N, K] row-major
     int N;
@@ -131,6 +140,8 @@ struct LinArgs {
     LinSeg seg[4];
     void *ws;          // optional scratch for the split-K kernel (linear_workspace_bytes)
     size_t ws_bytes;
+    StepSmallArgs rider;   // optional: integer work carried in rider_units spare workgroups of the projection's grid
+    int rider_units;       // 0 = none; the work is done when the projection kernel has finished
 };
 
 // Y_s = X_s W_s^T for up to four weight matrices (one launch on the fast paths; segments usually share X).
@@ -151,13 +162,7 @@ hipError_t launch_append_lengths(const int32_t *tok_off, int B, int32_t *ca_len,
                                  hipStream_t stream);
 // tree mask + accept walk + cache length update of one step in a single launch; old_len[B] receives the
 // (clamped) lengths from before the update, which is where the append writes its rows
-struct StepSmallArgs {
-    const int32_t *parent, *tok, *tgt, *tok_off;
-    uint64_t *mask;
-    int32_t *depth, *path, *n_path, *bonus, *ca_len, *old_len, *dev_status;
-    int B, M, cap;
-};
-hipError_t launch_step_small(const StepSmallArgs &a, hipStream_t stream);
+
 
 // ---- attention core (cross-attention when mask == nullptr / Mt == 0)
 struct AttnArgs {

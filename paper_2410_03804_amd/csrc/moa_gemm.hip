@@ -10,6 +10,7 @@
 // In both MFMA kernels the weight tile is the A operand and the activation tile the B operand,
 // so a lane ends up holding consecutive output features of one row (vector stores).
 #include "moa_common.h"
+#include "moa_tree_device.h"
 
 #include <stdlib.h>
 
@@ -178,6 +179,7 @@ struct SplitKArgs {
     int splits;          // K slices
     int ntot;            // total features (all segments), row length of the partial buffer
     float *part;         // [row tiles][splits][64][ntot]
+    int lead_blocks;     // workgroups in front of the projection's own (LinArgs::rider, padded to the XCD count)
 };
 
 template <int NQ>
@@ -186,8 +188,14 @@ __global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
     constexpr int KS = 128 * NQ, LDK = KS + 8, CPR = KS / 8, XL = (64 * CPR) / 256;
     extern __shared__ __attribute__((aligned(16))) bf16_t Xs[];   // [64][LDK]
     const LinArgs &a = sa.a;
+    if ((int)blockIdx.x < sa.lead_blocks) {        // the first workgroups of the grid carry the integer work
+        if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
+            step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)Xs, (int32_t *)Xs + MOA_MAX_TREE);
+        return;
+    }
+    const int bx = (int)blockIdx.x - sa.lead_blocks;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, kg = lane >> 4;
-    const int tile = blockIdx.x / sa.splits, split = blockIdx.x - tile * sa.splits;
+    const int tile = bx / sa.splits, split = bx - tile * sa.splits;
     int s = 0;
     while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
     const int n0 = (tile - sa.tile_begin[s]) * 64 + wave * 16;   // feature inside the segment
@@ -316,6 +324,7 @@ struct TiledArgs {
     LinArgs a;
     int tile_begin[5];
     int tiles_per_xcd;   // feature tiles owned by one XCD
+    int lead_blocks;     // workgroups in front of the projection's own (LinArgs::rider, padded to the XCD count)
 };
 
 // WF x WR = 32x32 MFMA blocks per wave along features x rows; the four waves sit 2 x 2, so the workgroup
@@ -338,10 +347,16 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
     extern __shared__ __attribute__((aligned(16))) bf16_t tsm[];   // [2][STAGE]
 
     const LinArgs &a = ta.a;
+    if ((int)blockIdx.x < ta.lead_blocks) {        // the first workgroups of the grid carry the integer work
+        if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
+            step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)tsm, (int32_t *)tsm + MOA_MAX_TREE);
+        return;
+    }
+    const int bx = (int)blockIdx.x - ta.lead_blocks;
     // Workgroups are handed to the 8 XCDs round-robin (id % 8), and each XCD has its own L2.  Give every
     // XCD a contiguous group of feature tiles for all row tiles: its slice of W then stays in its L2 and
     // each activation tile is fetched once per XCD instead of once per workgroup.
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int xcd = bx & 7, j = bx >> 3;
     const int ftile = xcd * ta.tiles_per_xcd + j % ta.tiles_per_xcd;
     if (ftile >= ta.tile_begin[a.nseg]) return;
     int s = 0;
@@ -456,7 +471,8 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
     for (int s = 0; s < a.nseg; ++s) { ta.tile_begin[s] = t; t += a.seg[s].N / BN; }
     ta.tile_begin[a.nseg] = t;
     ta.tiles_per_xcd = (t + 7) / 8;
-    const dim3 grid(8u * ta.tiles_per_xcd * (unsigned)((a.R + BM - 1) / BM));
+    ta.lead_blocks = (a.rider_units + 7) & ~7;      // a multiple of the XCD count: the tile mapping keeps its phase
+    const dim3 grid((unsigned)(ta.lead_blocks + 8 * ta.tiles_per_xcd * (int)((a.R + BM - 1) / BM)));
     const size_t lds = (size_t)2 * (BN + BM) * 64 * sizeof(bf16_t);
     hipError_t e = hipFuncSetAttribute((const void *)k_linear_tiled_bf16<WF, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -469,23 +485,29 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
 // ------------------------------------------------------------------ dispatch
 static bool aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 
-// only the split-K kernel reads per-segment activations; every other path gets one call per segment
+static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode);
+
+// kernels without per-segment activation support get one call per segment
 static hipError_t launch_linear_each(int dtype, const LinArgs &a, hipStream_t stream)
 {
     for (int s = 0; s < a.nseg; ++s) {
         LinArgs one = a;
+        one.rider_units = 0;
         one.nseg = 1;
         one.seg[0] = a.seg[s];
         if (a.seg[s].X) { one.X = a.seg[s].X; one.ldx = a.seg[s].ldx; }
         one.seg[0].X = nullptr;
-        hipError_t e = launch_linear(dtype, one, stream);
+        bool rode = false;
+        hipError_t e = launch_linear_impl(dtype, one, stream, &rode);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
+// *rode is set when the launch carried a.rider in its grid
+static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode)
 {
+    *rode = false;
     if (a.R <= 0) return hipSuccess;
     bool own_x = false;
     for (int s = 0; s < a.nseg; ++s) own_x = own_x || a.seg[s].X != nullptr;
@@ -506,6 +528,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             // 2x2 blocks per wave keeps two workgroups per CU; the 4x2 variant halves the LDS traffic per MFMA
             // but drops to one workgroup per CU and measured slower (MOA_TILE=42 selects it for tuning).
             const char *force = getenv("MOA_TILE");
+            *rode = a.rider_units > 0;
             if (all256 && force && force[0] == '4') return launch_tiled<4, 2>(a, stream);
             return launch_tiled<2, 2>(a, stream);
         }
@@ -523,7 +546,9 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
             ka.splits = a.K / (128 * nq);
             ka.ntot = ntot;
             ka.part = (float *)a.ws;
-            const dim3 grid(t * ka.splits);
+            ka.lead_blocks = (a.rider_units + 7) & ~7;
+            *rode = a.rider_units > 0;
+            const dim3 grid((unsigned)(ka.lead_blocks + t * ka.splits));
             const size_t lds = (size_t)64 * (128 * nq + 8) * sizeof(bf16_t);
             hipError_t e = hipSuccess;
             prof_begin(K_LIN_SPLITK + 64 * nq, stream);
@@ -569,6 +594,14 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
+{
+    bool rode = false;
+    hipError_t e = launch_linear_impl(dtype, a, stream, &rode);
+    if (e != hipSuccess || a.rider_units <= 0 || rode) return e;
+    return launch_step_small(a.rider, stream);      // the kernel that ran has no spare workgroups for it
 }
 
 }  // namespace moa
