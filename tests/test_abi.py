@@ -75,3 +75,37 @@ def test_null_and_range_errors_launch_nothing(moa):
     assert b"workspace" in lib.moa_last_error()
     lib.moa_draft_step.restype = C.c_int32
     assert lib.moa_draft_step(None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N above 1 must exit with a message that says so (before any GPU use)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, str(ROOT / "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0
+    assert "single-GPU" in r.stderr and "--gpus 2" in r.stderr
+    assert r.stdout.strip() == ""
+
+
+def test_product_path_does_not_use_the_oracle():
+    """The oracle is test infrastructure: nothing in the package may import, load or call it (and the other way round)."""
+    pkg = ROOT / "paper_2410_03804_amd"
+    for f in list(pkg.glob("*.py")) + list((pkg / "csrc").glob("*")):
+        text = f.read_text()
+        assert not re.search(r"\boracle\b|moa_ref", text), f
+    for f in (ROOT / "oracle").glob("*"):
+        if f.suffix in (".py", ".c", ".h"):
+            assert "paper_2410_03804_amd" not in f.read_text() and "libmoa.so" not in f.read_text(), f
+    gen = (ROOT / "moa_inputs" / "__init__.py").read_text()          # the shared input generators import neither side
+    assert not re.search(r"^\s*(import|from)\s+(oracle|paper_2410_03804_amd)", gen, flags=re.M)
+
+
+def test_draft_step_rejects_unknown_schedule_before_any_launch(moa):
+    import ctypes as C
+    from paper_2410_03804_amd import binding
+    args = binding._StepArgs()
+    shape = moa.Shape(4, 256, 4, 2, 64, 256, 4, 2, moa.F32)
+    args.shape = C.pointer(shape)
+    args.schedule = 7
+    rc = binding._lib.moa_draft_step(C.byref(args))
+    assert rc == -2 and "schedule" in moa.last_error()
