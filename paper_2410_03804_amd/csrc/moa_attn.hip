@@ -143,7 +143,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 constexpr int KT = 32;        // keys per tile
 
 template <int DH, int NBLK>
-__global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
+__global__ __launch_bounds__(256, NBLK == 1 ? 2 : 1) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
 {
     const int call = blockIdx.z / grp.nbg;
     const AttnArgs &a = grp.a[call];
@@ -206,16 +206,19 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
 
     // tile i of this workgroup: cache tile t0+i, or tree tile i-(t1-t0).  K and V rows are fetched row-contiguously
     // (16 lanes cover a 256-byte row), staged row-major in LDS; V comes back transposed by the LDS transpose read.
-    u32x4 kreg[NLD], vreg[NLD];
+    // A ring of RD register stages: the loads of tile i+RD are issued when tile i has been computed, so a tile has
+    // RD-1 whole iterations to arrive (memory latency under load is longer than one iteration).
+    constexpr int RD = 3;
+    u32x4 kreg[RD][NLD], vreg[RD][NLD];
     auto full_tile = [&](int i) { return i < (t1 - t0) && (t0 + i + 1) * KT <= len; };
-    auto fetch = [&](int i) {
+    auto fetch = [&](int i, u32x4 (&kr)[NLD], u32x4 (&vr)[NLD]) {
         if (full_tile(i)) {
             const int64_t off0 = (int64_t)(t0 + i) * KT * DH;
 #pragma unroll
             for (int j = 0; j < NLD; ++j) {
                 const int c = tid + 256 * j;
-                kreg[j] = *(const u32x4 *)(kc + off0 + (c / CPK) * DH + (c % CPK) * 8);
-                vreg[j] = *(const u32x4 *)(vc + off0 + (c / CPK) * DH + (c % CPK) * 8);
+                kr[j] = *(const u32x4 *)(kc + off0 + (c / CPK) * DH + (c % CPK) * 8);
+                vr[j] = *(const u32x4 *)(vc + off0 + (c / CPK) * DH + (c % CPK) * 8);
             }
             return;
         }
@@ -229,30 +232,34 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
             const int c = tid + 256 * j;
             int row = base + c / CPK;
             if (row > limit - 1) row = limit - 1;          // rows past the end repeat the last valid row
-            kreg[j] = *(const u32x4 *)(ksrc + (int64_t)row * DH + (c % CPK) * 8);
-            vreg[j] = *(const u32x4 *)(vsrc + (int64_t)row * DH + (c % CPK) * 8);
+            kr[j] = *(const u32x4 *)(ksrc + (int64_t)row * DH + (c % CPK) * 8);
+            vr[j] = *(const u32x4 *)(vsrc + (int64_t)row * DH + (c % CPK) * 8);
         }
     };
-    auto stage = [&](int buf) {
+    auto stage = [&](int buf, const u32x4 (&kr)[NLD], const u32x4 (&vr)[NLD]) {
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             const int c = tid + 256 * j;
-            *(u32x4 *)&Ks2[buf][(c / CPK) * KLD + (c % CPK) * 8] = kreg[j];
-            *(u32x4 *)&Vs2[buf][(c / CPK) * VSLD + (c % CPK) * 8] = vreg[j];
+            *(u32x4 *)&Ks2[buf][(c / CPK) * KLD + (c % CPK) * 8] = kr[j];
+            *(u32x4 *)&Vs2[buf][(c / CPK) * VSLD + (c % CPK) * 8] = vr[j];
         }
     };
     // transpose read: lane j of a 16-lane group addresses key (j >> 2), head_dim 4 (j & 3) of the group's 16
     const int tr_off = ((lane & 15) >> 2) * VSLD + 16 * ((lane >> 4) & 1) + 4 * (lane & 3) + 4 * half * VSLD;
 
-    // tile i+1 is staged into the other buffer after tile i has been computed (its registers were filled during
-    // that computation); the barrier at the end of an iteration publishes it and retires the reads of tile i
-    if (ntiles > 0) {
-        fetch(0);
-        stage(0);
-        if (ntiles > 1) fetch(1);
-    }
+    // Tile i+1 is staged into the other LDS buffer after tile i has been computed; the barrier at the end of an
+    // iteration publishes it and retires the reads of tile i.  Three iterations per trip so that the register
+    // stages are addressed statically.
+#pragma unroll
+    for (int d = 0; d < RD; ++d)
+        if (d < ntiles) fetch(d, kreg[d], vreg[d]);
+    if (ntiles > 0) stage(0, kreg[0], vreg[0]);
     __syncthreads();
-    for (int i = 0; i < ntiles; ++i) {
+    for (int i0 = 0; i0 < ntiles; i0 += RD) {
+#pragma unroll
+    for (int d = 0; d < RD; ++d) {
+        const int i = i0 + d;
+        if (i >= ntiles) continue;                             // same decision in the whole workgroup
         const bf16_t *Ks = Ks2[i & 1], *Vs = Vs2[i & 1];
 
         // S^T tile: keys x queries
@@ -331,11 +338,10 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnGroup grp, SplitGeom geo)
                 for (int blk = 0; blk < NBLK; ++blk)
                     acc[blk][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[blk][st2], acc[blk][d], 0, 0, 0);
             }
-        if (i + 1 < ntiles) {
-            stage((i + 1) & 1);
-            if (i + 2 < ntiles) fetch(i + 2);
-        }
+        if (i + 1 < ntiles) stage((i + 1) & 1, kreg[(d + 1) % RD], vreg[(d + 1) % RD]);
+        if (i + RD < ntiles) fetch(i + RD, kreg[d], vreg[d]);
         __syncthreads();
+    }
     }
 
     // partial results of this slice: the slice's own normalised output (a convex combination of V rows, so it
