@@ -637,14 +637,20 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
         atomicOr(a.dev_status, MOA_DEV_EMPTY_KEYS);
 }
 
-// one wavefront per (sequence, query, head)
+// DH/8 lanes per (sequence, query, head) row, 8 head_dim values (one 16-byte load per slice) per lane; a
+// workgroup of 256 threads folds 2048/DH rows
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
 template <int DH>
-__global__ __launch_bounds__(64) void k_attn_merge(AttnGroup grp, SplitGeom geo)
+__global__ __launch_bounds__(256) void k_attn_merge(AttnGroup grp, SplitGeom geo)
 {
-    constexpr int CPL = DH / 64;   // components per lane
-    const int lane = threadIdx.x;
+    constexpr int LPR = DH / 8;            // lanes per row
+    constexpr int RPB = 256 / LPR;         // rows per workgroup
     const int per_call = grp.a[0].B * grp.a[0].Mq * grp.a[0].H;
-    const int call = blockIdx.x / per_call, blk = blockIdx.x - call * per_call;
+    const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / LPR;
+    if (row >= (int64_t)grp.ncalls * per_call) return;
+    const int call = (int)(row / per_call), blk = (int)(row - (int64_t)call * per_call);
+    const int piece = threadIdx.x % LPR;
     const AttnArgs &a = grp.a[call];
     const f16_t *__restrict__ part_o = (const f16_t *)a.ws;
     const float *__restrict__ part_ml = (const float *)(part_o + (size_t)grp.nbg * geo.nsplit * geo.rows_pad * DH);
@@ -654,46 +660,47 @@ __global__ __launch_bounds__(64) void k_attn_merge(AttnGroup grp, SplitGeom geo)
     const int G = a.H / a.Hkv, g = h / G, rho = m * G + (h - g * G);
     const int64_t bg = (int64_t)b * a.Hkv + g;
 
-    // slices in groups of eight: all (max, sum) pairs and accumulator rows of a group are requested before any
+    // slices in groups of four: all (max, sum) pairs and accumulator pieces of a group are requested before any
     // is used; groups are folded with the usual running-max rescale
     const int64_t stride = geo.rows_pad;
     const int64_t prow0 = bg * geo.nsplit * stride + rho;
-    float mstar = -INFINITY, lsum = 0.f, o[CPL];
+    float mstar = -INFINITY, lsum = 0.f, o[8];
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) o[c] = 0.f;
-    for (int s0 = 0; s0 < geo.nsplit; s0 += 8) {
-        float ms[8], ls[8], ov[8][CPL];
+    for (int c = 0; c < 8; ++c) o[c] = 0.f;
+    for (int s0 = 0; s0 < geo.nsplit; s0 += 4) {
+        float ms[4], ls[4];
+        f16x8 ov[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 4; ++u) {
             const int sidx = min(s0 + u, geo.nsplit - 1);
             const int64_t prow = prow0 + sidx * stride;
             ms[u] = (s0 + u < geo.nsplit) ? part_ml[prow * 2] : -INFINITY;
             ls[u] = part_ml[prow * 2 + 1];
-#pragma unroll
-            for (int c = 0; c < CPL; ++c) ov[u][c] = (float)part_o[prow * DH + lane * CPL + c];
+            ov[u] = *(const f16x8 *)(part_o + prow * DH + 8 * piece);
         }
         float gmax = mstar;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) gmax = fmaxf(gmax, ms[u]);
+        for (int u = 0; u < 4; ++u) gmax = fmaxf(gmax, ms[u]);
         if (gmax == -INFINITY) continue;
         const float keep = exp2f(mstar - gmax);      // 0 on the first non-empty group
         lsum *= keep;
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) o[c] *= keep;
+        for (int c = 0; c < 8; ++c) o[c] *= keep;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 4; ++u) {
             const float w = (ms[u] == -INFINITY) ? 0.f : exp2f(ms[u] - gmax) * ls[u];   // slice weight
             lsum += w;
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) o[c] += w * ov[u][c];
+            for (int c = 0; c < 8; ++c) o[c] += w * (float)ov[u][c];
         }
         mstar = gmax;
     }
     const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
-    bf16_t *dst = (bf16_t *)a.out + (((int64_t)b * a.Mq + m) * a.H + h) * DH + lane * CPL;
+    u32x4 pk;
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) dst[c] = f2bf(o[c] * inv);
-    if (lsum == 0.f && a.empty_is_error && lane == 0 && a.dev_status) atomicOr(a.dev_status, MOA_DEV_EMPTY_KEYS);
+    for (int w = 0; w < 4; ++w) pk[w] = (uint32_t)f2bf(o[2 * w] * inv) | ((uint32_t)f2bf(o[2 * w + 1] * inv) << 16);
+    *(u32x4 *)((bf16_t *)a.out + (((int64_t)b * a.Mq + m) * a.H + h) * DH + 8 * piece) = pk;
+    if (lsum == 0.f && a.empty_is_error && piece == 0 && a.dev_status) atomicOr(a.dev_status, MOA_DEV_EMPTY_KEYS);
 }
 
 // ------------------------------------------------------------------ host side
@@ -755,16 +762,21 @@ static bool attn_split_ok(const AttnArgs &a, int P_cap_geo)
            a.ws_bytes >= attn_workspace_bytes(a.dtype, a.B, a.Mq, a.H, a.Hkv, a.dh, P_cap_geo);
 }
 
-// Which MFMA kernel: the whole-key-range form re-reads K/V once per 32 query rows (from L2), the split form
-// once per 128 or 256 rows but pays for partial results and a merge; the first wins while the key range is
-// short.  MOA_ATTN=split / fused overrides the choice (tuning and tests).
+// Which MFMA kernel.  The whole-key-range form needs one launch, writes no partial results and has the shorter
+// fixed part, but re-reads K/V once per 32 query rows and runs one workgroup per CU: it wins while the call is
+// latency-bound, i.e. while its workgroups fit the chip in one round and the key range is short (C1: 14.5 us
+// against 17.8 + 6.8 us).  With more work the split form (128 rows per workgroup, two workgroups per CU, then the
+// merge) is ahead (B = 16, prefixes up to 2048: 122 against 166 us).  MOA_ATTN=split / fused overrides the
+// choice (tuning and tests).
 constexpr int FUSED_MAX_KEYS = 8192;
+constexpr int FUSED_MAX_WORKGROUPS = 256;
 static bool want_fused(const AttnArgs &a)
 {
     const char *e = getenv("MOA_ATTN");
     if (e && e[0] == 's') return false;
     if (e && e[0] == 'f') return true;
-    return a.P_cap + a.Mt <= FUSED_MAX_KEYS;
+    const int64_t wgs = (int64_t)a.B * a.Hkv * (((a.H / a.Hkv) * a.Mq + 31) / 32);
+    return a.P_cap + a.Mt <= FUSED_MAX_KEYS && wgs <= FUSED_MAX_WORKGROUPS;
 }
 
 // n = 1 or 2 calls of identical shape (B, Mq, H, Hkv, dh)
@@ -829,8 +841,10 @@ static hipError_t launch_attn_split(const AttnArgs *calls, int n, hipStream_t st
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     prof_begin(K_ATTN_MERGE + 64 * (a.dh * 8), stream);
-    if (a.dh == 128) MOA_KLAUNCH(k_attn_merge<128>, dim3(nblocks), dim3(64), 0, stream, grp, g);
-    else MOA_KLAUNCH(k_attn_merge<64>, dim3(nblocks), dim3(64), 0, stream, grp, g);
+    const int rpb = 2048 / a.dh;                      // rows per merge workgroup
+    const unsigned mblocks = (unsigned)(((int64_t)nblocks + rpb - 1) / rpb);
+    if (a.dh == 128) MOA_KLAUNCH(k_attn_merge<128>, dim3(mblocks), dim3(256), 0, stream, grp, g);
+    else MOA_KLAUNCH(k_attn_merge<64>, dim3(mblocks), dim3(256), 0, stream, grp, g);
     prof_end(stream);
     return hipGetLastError();
 }
