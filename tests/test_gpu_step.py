@@ -21,6 +21,12 @@ STEP_CASES = {
     "small_bf16": (mi.Config(name="S", index=8, dtype="bf16", B=3, P_min=80, P_max=300, M=37, D=5, max_branch=4, L=6,
                              d=512, H=8, Hkv=2, dh=128, d_lsa_in=512, rms_norm=True), 2),
     "C1_bf16": (mi.CONFIGS["C1"], 1),
+    # degenerate trees: the root alone (M = 1: nothing drafted, the bonus token is the only result) and a prefix
+    # shorter than one key tile
+    "single_node_bf16": (mi.Config(name="M1", index=9, dtype="bf16", B=2, P_min=5, P_max=40, M=1, D=0, max_branch=4, L=3,
+                                   d=256, H=4, Hkv=2, dh=64, d_lsa_in=256, rms_norm=True), 1),
+    "single_node_f32": (mi.Config(name="M1f", index=10, dtype="f32", B=1, P_min=3, P_max=3, M=1, D=0, max_branch=4, L=2,
+                                  d=128, H=2, Hkv=2, dh=64, d_lsa_in=128, rms_norm=False), 2),
 }
 
 
