@@ -117,6 +117,7 @@ CASES = {
     "bf16_two_rowtiles_M70": small_cfg("bf16", B=2, H=8, Hkv=2, M=70, D=7, P_max=150),
     "bf16_M130_three_words": small_cfg("bf16", B=2, H=4, Hkv=2, d=512, M=130, D=10, P_max=97),
     "bf16_generic_dh32": small_cfg("bf16", d=256, H=8, Hkv=4, dh=32, d_lsa_in=128, M=21, D=4),
+    "bf16_M256_largest_tree": small_cfg("bf16", B=1, H=4, Hkv=2, d=512, M=256, D=20, P_max=70, L=2),
     "C1_bf16": mi.CONFIGS["C1"],
 }
 
