@@ -56,6 +56,9 @@ def parse():
                          "step's independent branch onto a second stream (kernels then overlap, so per-kernel "
                          "durations no longer describe one kernel alone); sequential: one launch per stage")
     ap.add_argument("--d-lsa-in", type=int, default=0, help="override the LSA input width (default 2*E_kv)")
+    ap.add_argument("--lsa-tokens", default="tree",
+                    help="tokens per sequence that are new to the Layer Self-Attention in a step: 'tree' (M, the "
+                         "headline), 'prefix' (first cycle: the whole prompt) or an integer (accepted tokens, ~5)")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run three plain device copies of this many MiB (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -65,12 +68,22 @@ def parse():
 SCHEDULES = {"grouped": 0, "two-stream": 1, "sequential": 2}
 
 
-def site_costs(cfg, n_layers, schedule="grouped"):
+def lsa_token_count(cfg, lsa_tokens):
+    import moa_inputs as mi
+    if lsa_tokens == "tree":
+        return cfg.B * cfg.M
+    if lsa_tokens == "prefix":
+        return int(mi.prefix_lengths(cfg).sum())
+    return cfg.B * int(lsa_tokens)
+
+
+def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree"):
     """Algorithmic bytes and flops per launch site for one step: what the call must read and write once
     (inputs, weights, caches, outputs) and 2*MACs of the contractions as defined."""
     es = 2 if cfg.dtype == "bf16" else 4
     B, M, L, d, H, Hkv, dh = cfg.B, cfg.M, cfg.L, cfg.d, cfg.H, cfg.Hkv, cfg.dh
     T = B * M
+    Tl = lsa_token_count(cfg, lsa_tokens)           # rows of the LSA and of the memory append
     d_in, eq, ekv = cfg.d_lsa_in, cfg.lsa_heads * dh, cfg.Hkv * dh
     E = H * dh
     import moa_inputs as mi
@@ -81,11 +94,11 @@ def site_costs(cfg, n_layers, schedule="grouped"):
 
     c = {}
     c["tree_build"] = dict(bytes=B * M * 4 + B * M * ((M + 63) // 64) * 8 + B * M * 4, flops=0.0)
-    c["lsa.qkv_proj"] = lin(T * L, d_in, eq + 2 * ekv)
-    c["lsa.layer_attn"] = dict(bytes=(T * L * (eq + 2 * ekv) + T * eq) * es,
-                               flops=2.0 * T * cfg.lsa_heads * L * L * dh + 2.0 * T * cfg.lsa_heads * L * dh)
-    c["lsa.o_proj"] = lin(T, eq, eq)
-    c["ca_append.kv_proj"] = lin(T, eq, 2 * ekv)
+    c["lsa.qkv_proj"] = lin(Tl * L, d_in, eq + 2 * ekv)
+    c["lsa.layer_attn"] = dict(bytes=(Tl * L * (eq + 2 * ekv) + Tl * eq) * es,
+                               flops=2.0 * Tl * cfg.lsa_heads * L * L * dh + 2.0 * Tl * cfg.lsa_heads * L * dh)
+    c["lsa.o_proj"] = lin(Tl, eq, eq)
+    c["ca_append.kv_proj"] = lin(Tl, eq, 2 * ekv)
     c["ca_append.lengths"] = dict(bytes=B * 12, flops=0.0)
     c["ca.q_proj"] = lin(T, d, E)
     cache_ca = 2.0 * Hkv * dh * es * float(plen.sum())
@@ -148,7 +161,8 @@ def main():
     slots = math.ceil(total / nsets) + 1 + hot_steps      # one fresh length slot per step a set runs
 
     t_setup = time.perf_counter()
-    works = [mi.step_workload(cfg, NL, variant=i) for i in range(nsets)]
+    lsa_tokens = args.lsa_tokens if args.lsa_tokens in ("tree", "prefix") else int(args.lsa_tokens)
+    works = [mi.step_workload(cfg, NL, variant=i, lsa_tokens=lsa_tokens) for i in range(nsets)]
     sets = []
     ws = None
     for w in works:
@@ -254,7 +268,7 @@ def main():
     tokens = cfg.B * cfg.M
     value = tokens / (ms_per_step * 1e-3)
 
-    costs = site_costs(cfg, NL, schedule=args.schedule)
+    costs = site_costs(cfg, NL, schedule=args.schedule, lsa_tokens=lsa_tokens)
     peak_mm = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else VEC_F32_PEAK_TFLOPS
     pieces = []
     for site, kern, n, ms in sorted(rows, key=lambda r: -r[3]):
@@ -323,7 +337,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} prefix={cfg.P_min}..{cfg.P_max} tree M={cfg.M} depth={cfg.D} "
                                f"L={cfg.L} d={cfg.d} H={cfg.H}/{cfg.Hkv} dh={cfg.dh} d_lsa_in={cfg.d_lsa_in}; "
-                               f"LSA on T=B*M={tokens} tokens, {NL} tree-verify layer(s)",
+                               f"LSA on T={lsa_token_count(cfg, lsa_tokens)} tokens ({lsa_tokens}), {NL} tree-verify layer(s)",
                    "verify_layers": NL, "buffer_sets": nsets, "profile_steps": P},
         "roofline": roofline, "cpu_baseline": cpu, "ceilings": ceilings,
         "hot_cache": {"ms_per_step": round(hot_ms, 5), "steps": hot_steps,

@@ -287,11 +287,13 @@ def kv_cache(cfg: Config, which: int = 0, P_cap: int | None = None):
     return normal(rng, shape, cfg.dtype), normal(rng, shape, cfg.dtype)
 
 
-def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0):
+def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0, lsa_tokens="tree"):
     """All inputs of one draft step as numpy arrays (values already rounded to cfg.dtype).
 
-    Per sequence, the M tokens verified in the previous cycle are new: LSA runs on T = B*M tokens,
-    the cross-attention memory holds P_b - M rows before the step and P_b rows after the append.
+    `lsa_tokens` says how many tokens per sequence are new to the Layer Self-Attention in this step:
+    "tree" = M (every token of the last tree, the default), "prefix" = P_b (first cycle: the whole prompt,
+    empty memory before), or an integer A (the accepted tokens of the last cycle).  LSA runs on their sum T;
+    the cross-attention memory holds P_b minus that many rows before the step and P_b rows after the append.
     `variant` draws an independent set of the large tensors (weights, activations, caches) so a
     benchmark can rotate buffer sets; trees, tokens and lengths stay the same."""
     v = 50 * variant
@@ -299,9 +301,15 @@ def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0):
     parent = trees(cfg)
     tok, tgt = tokens(cfg, parent)
     plen = prefix_lengths(cfg)
-    if np.any(plen < M):
-        raise ValueError("prefix shorter than the tree")
-    T = B * M
+    if isinstance(lsa_tokens, str):
+        if lsa_tokens not in ("tree", "prefix"):
+            raise ValueError(f"lsa_tokens: {lsa_tokens!r}")
+        new_tok = np.full(B, M, dtype=np.int64) if lsa_tokens == "tree" else plen.astype(np.int64)
+    else:
+        new_tok = np.full(B, int(lsa_tokens), dtype=np.int64)
+    if np.any(new_tok < 1) or np.any(plen < new_tok):
+        raise ValueError("prefix shorter than the tokens that are new to it")
+    T = int(new_tok.sum())
     rng_w = rng_for(cfg, S_WEIGHT, extra=1 + v)
     Hl, dh, d_in = cfg.lsa_heads, cfg.dh, cfg.d_lsa_in
     E = cfg.H * dh
@@ -326,6 +334,6 @@ def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0):
         vc = normal(rc, (B, cfg.Hkv, cfg.P_cap, dh), cfg.dtype)
         layers.append(dict(w=w, x=x, kcache=kc, vcache=vc))
     return dict(cfg=cfg, parent=parent, tok=tok, tgt=tgt, prefix_len=plen, P_cap=cfg.P_cap,
-                lsa_w=lsa_w, lsa_hs=lsa_hs, tok_off=(np.arange(B + 1) * M).astype(np.int32),
-                ca_w=ca_w, ca_xq=ca_xq, ca_k=ca_k, ca_v=ca_v, ca_len0=(plen - M).astype(np.int32),
+                lsa_w=lsa_w, lsa_hs=lsa_hs, tok_off=np.concatenate([[0], np.cumsum(new_tok)]).astype(np.int32),
+                ca_w=ca_w, ca_xq=ca_xq, ca_k=ca_k, ca_v=ca_v, ca_len0=(plen - new_tok).astype(np.int32),
                 ca_P_cap=ca_P_cap, layers=layers)

@@ -92,8 +92,13 @@ size_t lsa_ws_bytes(const moa_shape_t *s, int64_t T)
 {
     const int64_t tc = T < LSA_CHUNK ? T : LSA_CHUNK, ob = T < LSA_OBLOCK ? T : LSA_OBLOCK;
     const size_t eq = (size_t)s->lsa_q_heads * s->head_dim, ekv = (size_t)s->lsa_kv_heads * s->head_dim;
+    // the projections of a short chunk (the first and the last one can be) stream the weights and keep partial sums
+    const int64_t tail = T % LSA_CHUNK;
+    size_t lin = linear_workspace_bytes(s->dtype, ob, (int)eq, (int)eq);
+    lin = max2(lin, linear_workspace_bytes(s->dtype, tc * s->n_layers, s->d_lsa_in, (int)(eq + 2 * ekv)));
+    if (tail) lin = max2(lin, linear_workspace_bytes(s->dtype, tail * s->n_layers, s->d_lsa_in, (int)(eq + 2 * ekv)));
     return align256((size_t)tc * s->n_layers * (eq + 2 * ekv) * esize(s->dtype)) + align256((size_t)ob * eq * esize(s->dtype)) +
-           align256(linear_workspace_bytes(s->dtype, ob, (int)eq, (int)eq));
+           align256(lin);
 }
 
 // scratch shared by the projections' split-K partials and the attention core's split-KV partials
@@ -258,6 +263,8 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
         la.R = tc * L;
         la.K = d_in;
         la.ldx = d_in;
+        la.ws = lin_ws;
+        la.ws_bytes = lin_ws_bytes;
         LsaAttnArgs aa = {};
         aa.dtype = dt;
         auto add = [&](const void *w, int n, int col, const void **ptr, int64_t *ldp) {

@@ -298,10 +298,13 @@ __global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
     *(u32x4 *)((bf16_t *)a.seg[s].st.dst + off) = pk;
 }
 
-// rows up to which the weight-streaming kernel is used (it walks 64-row tiles with the weights in registers).
-// Its fp32 partial sums are 128 * row tiles / (K slice) of the weight bytes: a quarter at one row tile of 512-wide
-// slices, as much as the weights at four, so above two row tiles the tiled kernel takes over
+// The weight-streaming kernel walks 64-row tiles with the weights in registers.  Its fp32 partial sums are
+// (row tiles * 128 / K slice) of the weight bytes.  Up to two row tiles it is always used (K slices chosen for the
+// number of workgroups); at three row tiles with 512-wide K slices (partial sums three quarters of the weights):
+// the tiled kernel has too few workgroups there to hide its per-tile latency (LSA on five tokens: 35 -> 17 us).
+// Four row tiles would need 1024-wide slices, one workgroup per CU: measured twice as slow as the tiled kernel.
 constexpr int64_t SPLITK_MAX_ROWS = 128;
+constexpr int64_t SPLITK_MAX_ROWS_WIDE = 192;
 
 static int splitk_nq(int K)
 {
@@ -310,10 +313,23 @@ static int splitk_nq(int K)
     return (K % 1024 == 0) ? 8 : 0;
 }
 
+// K slice width (in units of 128) for R rows, 0 = do not use the weight-streaming kernel
+static int splitk_plan(int64_t R, int K)
+{
+    if (R <= 0 || K % 128) return 0;
+    const int nq0 = splitk_nq(K);
+    if (!nq0 || R <= SPLITK_MAX_ROWS) return nq0;
+    if (R > SPLITK_MAX_ROWS_WIDE) return 0;
+    const int64_t rowtiles = (R + 63) / 64;
+    for (int nq = nq0; nq <= 4; nq *= 2)
+        if (K % (128 * nq) == 0 && rowtiles * 4 <= 3 * nq) return nq;      // rowtiles * 128 / (128 nq) <= 3/4
+    return 0;
+}
+
 size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot)
 {
-    if (dtype != DT_BF16 || R > SPLITK_MAX_ROWS || K % 128 || ntot % 64) return 0;
-    const int nq = splitk_nq(K);
+    if (dtype != DT_BF16 || ntot % 64) return 0;
+    const int nq = splitk_plan(R, K);
     if (!nq) return 0;
     const size_t splits = K / (128 * nq), rowtiles = (size_t)((R + 63) / 64);
     return rowtiles * splits * 64 * (size_t)ntot * sizeof(float);
@@ -522,7 +538,7 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
     if (fast) {
         bool all128 = true;
         for (int s = 0; s < a.nseg; ++s) all128 = all128 && a.seg[s].N % 128 == 0;
-        if (a.R > SPLITK_MAX_ROWS && all128) {
+        if (!splitk_plan(a.R, a.K) && all128) {
             bool all256 = true;
             for (int s = 0; s < a.nseg; ++s) all256 = all256 && a.seg[s].N % 256 == 0;
             // 2x2 blocks per wave keeps two workgroups per CU; the 4x2 variant halves the LDS traffic per MFMA
@@ -542,7 +558,7 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
             int t = 0;
             for (int s = 0; s < a.nseg; ++s) { ka.tile_begin[s] = t; t += a.seg[s].N / 64; }
             ka.tile_begin[a.nseg] = t;
-            const int nq = splitk_nq(a.K);
+            const int nq = splitk_plan(a.R, a.K);
             ka.splits = a.K / (128 * nq);
             ka.ntot = ntot;
             ka.part = (float *)a.ws;

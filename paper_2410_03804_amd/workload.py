@@ -33,7 +33,7 @@ class DeviceStep:
         dt = cfg.dtype
         self.cfg, self.shape = cfg, shape_of(cfg)
         B, M = cfg.B, cfg.M
-        T = B * M
+        T = int(work["lsa_hs"].shape[0])
         W = (M + 63) // 64
         tdt = _TDT[dt]
         self.parent, self.tok, self.tgt = _dev(work["parent"]), _dev(work["tok"]), _dev(work["tgt"])

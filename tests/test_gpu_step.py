@@ -27,7 +27,17 @@ STEP_CASES = {
                                    d=256, H=4, Hkv=2, dh=64, d_lsa_in=256, rms_norm=True), 1),
     "single_node_f32": (mi.Config(name="M1f", index=10, dtype="f32", B=1, P_min=3, P_max=3, M=1, D=0, max_branch=4, L=2,
                                   d=128, H=2, Hkv=2, dh=64, d_lsa_in=128, rms_norm=False), 2),
+    # the other two token counts the Layer Self-Attention sees (Sec. 3, Alg. 1): the whole prompt on the first cycle
+    # (empty memory before the append) and only the accepted tokens of the last cycle (5 per sequence)
+    "first_cycle_bf16": (mi.Config(name="FC", index=11, dtype="bf16", B=2, P_min=70, P_max=200, M=37, D=5, max_branch=4,
+                                   L=6, d=512, H=8, Hkv=2, dh=128, d_lsa_in=512, rms_norm=True), 1, "prefix"),
+    "accepted_only_bf16": (mi.CONFIGS["C1"], 1, 5),
 }
+
+
+def _case(case):
+    cfg, nlayers, *rest = STEP_CASES[case]
+    return cfg, nlayers, (rest[0] if rest else "tree")
 
 
 SCHEDULES = {"grouped": 0, "two_stream": 1, "sequential": 2}
@@ -38,9 +48,9 @@ SCHEDULES = {"grouped": 0, "two_stream": 1, "sequential": 2}
 def test_draft_step_parity(G, oracle, case, schedule):
     from oracle.step import run_step
     from paper_2410_03804_amd.workload import DeviceStep
-    cfg, nlayers = STEP_CASES[case]
-    print(f"[case] draft_step {case} {schedule} B={cfg.B} M={cfg.M} layers={nlayers}", flush=True)
-    work = mi.step_workload(cfg, n_verify_layers=nlayers)
+    cfg, nlayers, lsa_tokens = _case(case)
+    print(f"[case] draft_step {case} {schedule} B={cfg.B} M={cfg.M} layers={nlayers} lsa_tokens={lsa_tokens}", flush=True)
+    work = mi.step_workload(cfg, n_verify_layers=nlayers, lsa_tokens=lsa_tokens)
     step = DeviceStep(work)
     step.run(schedule=SCHEDULES[schedule])
     torch.cuda.synchronize()

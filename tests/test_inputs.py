@@ -81,3 +81,19 @@ def test_seeds_are_reproducible_and_ragged():
     c = mi.CONFIGS["C2"]
     p1, p2 = mi.prefix_lengths(c), mi.prefix_lengths(c)
     assert np.array_equal(p1, p2) and p1.min() >= 512 and p1.max() <= 2048 and len(set(p1)) > 1
+
+
+@pytest.mark.parametrize("lsa_tokens,per_seq", [("tree", None), ("prefix", None), (5, 5)])
+def test_step_workload_lsa_token_regimes(lsa_tokens, per_seq):
+    """The three token counts the Layer Self-Attention sees (Alg. 1: whole prompt first, then what the last cycle
+    verified): rows of the LSA input, the per-sequence offsets and the memory length before the append must agree."""
+    cfg = mi.Config(name="R", index=12, dtype="f32", B=3, P_min=20, P_max=50, M=9, D=3, max_branch=3, L=2,
+                    d=128, H=2, Hkv=2, dh=64, d_lsa_in=128, rms_norm=False)
+    w = mi.step_workload(cfg, 1, lsa_tokens=lsa_tokens)
+    plen = w["prefix_len"].astype(np.int64)
+    new = {"tree": np.full(cfg.B, cfg.M), "prefix": plen}.get(lsa_tokens, np.full(cfg.B, per_seq))
+    assert w["lsa_hs"].shape == (int(new.sum()), cfg.L, cfg.d_lsa_in)
+    assert np.array_equal(w["tok_off"], np.concatenate([[0], np.cumsum(new)]))
+    assert np.array_equal(w["ca_len0"] + new, plen)
+    with pytest.raises(ValueError):
+        mi.step_workload(cfg, 1, lsa_tokens=int(plen.min()) + 1)
