@@ -256,6 +256,29 @@ def lsa_inputs(cfg: Config, T: int):
     return normal(rng_for(cfg, S_LSA), (T, cfg.L, cfg.d_lsa_in), cfg.dtype, rms_norm=cfg.rms_norm)
 
 
+def sa_kv_heads(cfg: Config) -> int:
+    """KV heads of the draft Self-Attention layer: its key/value width is half of the LLM's E_kv
+    (appendix table: 512 against 1024 at the 8B shape), at the LLM's head_dim."""
+    return max(1, cfg.Hkv // 2)
+
+
+def sa_weights(cfg: Config, variant: int = 0):
+    """Self-Attention layer on draft-token embeddings: embedding d, H query heads, sa_kv_heads KV heads."""
+    rng = rng_for(cfg, S_WEIGHT, extra=2 + 50 * variant)
+    E, ekv = cfg.H * cfg.dh, sa_kv_heads(cfg) * cfg.dh
+    return dict(wq=weight(rng, E, cfg.d, cfg.dtype), wk=weight(rng, ekv, cfg.d, cfg.dtype),
+                wv=weight(rng, ekv, cfg.d, cfg.dtype), wo=weight(rng, cfg.d, E, cfg.dtype))
+
+
+def sa_inputs(cfg: Config, variant: int = 0):
+    """Token embeddings of the M tree nodes [B, M, d] and the layer's K/V cache of the verified tokens
+    [B, sa_kv_heads, P_cap, dh] (N(0,1), like the other caches)."""
+    emb = normal(rng_for(cfg, S_CAQ, extra=7 + 50 * variant), (cfg.B, cfg.M, cfg.d), cfg.dtype, rms_norm=cfg.rms_norm)
+    rc = rng_for(cfg, S_CACHE, extra=2000 + 50 * variant)
+    shape = (cfg.B, sa_kv_heads(cfg), cfg.P_cap, cfg.dh)
+    return emb, normal(rc, shape, cfg.dtype), normal(rc, shape, cfg.dtype)
+
+
 def ca_weights(cfg: Config):
     rng = rng_for(cfg, S_WEIGHT, extra=2)
     E = cfg.H * cfg.dh

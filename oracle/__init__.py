@@ -148,6 +148,29 @@ def tree_verify_attn(x, wq, wk, wv, wo, kcache, vcache, prefix_len, mask, H, Hkv
     return out, kt, vt
 
 
+def self_attn_draft(emb, parent, node0, wq, wk, wv, wo, kcache, vcache, prefix_len, k_draft, v_draft, H, Hkv, dh):
+    """SA layer on the embeddings of the tree nodes node0 .. node0+Mn-1 (emb [B, Mn, d]); k_draft / v_draft
+    [B, Hkv, M, dh] (float64, C-contiguous) are updated in place.  Returns out [B, Mn, d_out]."""
+    emb = _f64(emb)
+    B, Mn, d = emb.shape
+    parent = _i32(parent)
+    M = parent.shape[1]
+    wq, wk, wv, wo = _f64(wq), _f64(wk), _f64(wv), _f64(wo)
+    kcache, vcache = _f64(kcache), _f64(vcache)
+    prefix_len = _i32(prefix_len)
+    for a in (k_draft, v_draft):
+        if a.dtype != np.float64 or not a.flags.c_contiguous or a.shape != (B, Hkv, M, dh):
+            raise ValueError("draft cache must be C-contiguous float64 [B, Hkv, M, dh]")
+    P_cap = 0 if kcache is None else kcache.shape[2]
+    d_out = H * dh if wo is None else wo.shape[0]
+    out = np.empty((B, Mn, d_out), dtype=np.float64)
+    rc = lib().moa_ref_self_attn_draft(_p(emb), B, M, int(node0), Mn, d, H, Hkv, dh, _p(wq), _p(wk), _p(wv), _p(wo),
+                                       d_out, _p(kcache), _p(vcache), _p(prefix_len, C.c_int32), P_cap,
+                                       _p(parent, C.c_int32), _p(out), _p(k_draft), _p(v_draft))
+    _check(rc, "self_attn_draft")
+    return out
+
+
 def tree_accept(parent, tok, tgt):
     parent, tok, tgt = _i32(parent), _i32(tok), _i32(tgt)
     B, M = parent.shape

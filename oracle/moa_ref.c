@@ -268,6 +268,88 @@ int moa_ref_cross_attn(const double *xq, int B, int Mq, int d, int H, int Hkv, i
     return MOA_REF_OK;
 }
 
+/* ------------------------------------------------------------ draft self-attention */
+
+int moa_ref_self_attn_draft(const double *emb, int B, int M, int node0, int Mn, int d, int H, int Hkv, int dh,
+                            const double *wq, const double *wk, const double *wv,
+                            const double *wo, int d_out,
+                            const double *kcache, const double *vcache,
+                            const int32_t *prefix_len, int P_cap, const int32_t *parent,
+                            double *out, double *k_draft, double *v_draft)
+{
+    if (!emb || !prefix_len || !parent || !out || !k_draft || !v_draft || B < 1 || M < 1 || Mn < 1 ||
+        M > 4096 || node0 < 0 || node0 + Mn > M || d < 1 || H < 1 || Hkv < 1 || dh < 1 || d_out < 1 || P_cap < 0)
+        return MOA_REF_BAD_ARG;
+    if (H % Hkv) return MOA_REF_BAD_ARG;
+    const int E = H * dh, Ekv = Hkv * dh, G = H / Hkv;
+    if ((!wq && E != d) || (!wk && Ekv != d) || (!wv && Ekv != d) || (!wo && d_out != E))
+        return MOA_REF_BAD_ARG;
+    for (int b = 0; b < B; ++b) {
+        if (prefix_len[b] < 0 || prefix_len[b] > P_cap) return MOA_REF_BAD_ARG;
+        if (prefix_len[b] > 0 && (!kcache || !vcache)) return MOA_REF_BAD_ARG;
+        if (parent[(int64_t)b * M] != -1) return MOA_REF_BAD_TREE;
+        for (int i = 1; i < M; ++i)
+            if (parent[(int64_t)b * M + i] < 0 || parent[(int64_t)b * M + i] >= i) return MOA_REF_BAD_TREE;
+    }
+    const double inv_sqrt = 1.0 / sqrt((double)dh);
+    const int64_t R = (int64_t)B * Mn;
+    double *Q = (double *)malloc(sizeof(double) * (size_t)R * E);
+    double *Kn = (double *)malloc(sizeof(double) * (size_t)R * Ekv);
+    double *Vn = (double *)malloc(sizeof(double) * (size_t)R * Ekv);
+    double *A = (double *)malloc(sizeof(double) * (size_t)R * E);
+    if (!Q || !Kn || !Vn || !A) { free(Q); free(Kn); free(Vn); free(A); return MOA_REF_BAD_ARG; }
+    moa_ref_linear(emb, R, d, wq, E, Q);
+    moa_ref_linear(emb, R, d, wk, Ekv, Kn);
+    moa_ref_linear(emb, R, d, wv, Ekv, Vn);
+
+    /* the new nodes' keys / values join the draft cache of this cycle */
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hkv; ++g)
+            for (int t = 0; t < Mn; ++t)
+                for (int c = 0; c < dh; ++c) {
+                    const int64_t o = (((int64_t)b * Hkv + g) * M + node0 + t) * dh + c;
+                    k_draft[o] = Kn[((int64_t)b * Mn + t) * Ekv + g * dh + c];
+                    v_draft[o] = Vn[((int64_t)b * Mn + t) * Ekv + g * dh + c];
+                }
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t rh = 0; rh < R * H; ++rh) {
+        const int64_t r = rh / H;
+        const int h = (int)(rh % H), g = h / G, b = (int)(r / Mn), i = node0 + (int)(r % Mn);
+        const int P = prefix_len[b];
+        const double *q = Q + r * E + h * dh;
+        /* the drafted tokens before node i in its own sequence: i, parent(i), ..., root */
+        int path[4096];
+        int np = 0;
+        for (int j = i; j >= 0 && np < 4096; j = parent[(int64_t)b * M + j]) path[np++] = j;
+        const int n = P + np;
+        double *s = (double *)malloc(sizeof(double) * (size_t)n);
+        double *vv = (double *)malloc(sizeof(double) * (size_t)n * dh);
+        for (int p = 0; p < P; ++p) {
+            const double *kr = kcache + (((int64_t)b * Hkv + g) * P_cap + p) * dh;
+            const double *vr = vcache + (((int64_t)b * Hkv + g) * P_cap + p) * dh;
+            double acc = 0.0;
+            for (int c = 0; c < dh; ++c) acc += q[c] * kr[c];
+            s[p] = acc * inv_sqrt;
+            for (int c = 0; c < dh; ++c) vv[(int64_t)p * dh + c] = vr[c];
+        }
+        for (int u = 0; u < np; ++u) {                /* root first, node i last: sequence order */
+            const int j = path[np - 1 - u];
+            const double *kr = k_draft + (((int64_t)b * Hkv + g) * M + j) * dh;
+            const double *vr = v_draft + (((int64_t)b * Hkv + g) * M + j) * dh;
+            double acc = 0.0;
+            for (int c = 0; c < dh; ++c) acc += q[c] * kr[c];
+            s[P + u] = acc * inv_sqrt;
+            for (int c = 0; c < dh; ++c) vv[(int64_t)(P + u) * dh + c] = vr[c];
+        }
+        moa_ref_softmax_weighted_sum(s, vv, n, dh, A + r * E + h * dh, NULL);
+        free(s); free(vv);
+    }
+    moa_ref_linear(A, R, E, wo, d_out, out);
+    free(Q); free(Kn); free(Vn); free(A);
+    return MOA_REF_OK;
+}
+
 /* ------------------------------------------------------------ tree verify */
 
 int moa_ref_tree_verify_attn(const double *x, int B, int M, int d, int H, int Hkv, int dh,

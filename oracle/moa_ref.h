@@ -90,6 +90,26 @@ int moa_ref_tree_verify_attn(const double *x /*[B,M,d]*/, int B, int M, int d,
                              double *out /*[B,M,d_out]*/,
                              double *k_tree, double *v_tree /*[B,Hkv,M,dh]*/);
 
+/* Self-Attention layer of the draft model on draft-token embeddings, tree form
+ * (Sec. 3.1 "Self-Attention": a causal self-attention on the CA queries, so that a
+ * drafted token knows the tokens drafted before it; Alg. 1 "q <- SA_layer(token_embed(y))";
+ * widths from the appendix table: embedding 4096, keys/values 512).  Causal over the
+ * token sequence that leads to a node: node i attends the verified tokens' cached
+ * keys/values (rows 0..prefix_len[b]-1) and the nodes on its own path root..i, found by
+ * walking parent[] (no bitset here).  Drafting goes level by level: this call handles
+ * the nodes node0 .. node0+Mn-1 (emb holds only their rows), writes their projected
+ * keys/values into rows node0.. of the per-cycle draft cache and reads the earlier
+ * rows of that cache as they are.  Every ancestor of a new node must be < node0+Mn. */
+int moa_ref_self_attn_draft(const double *emb /*[B,Mn,d]*/, int B, int M, int node0, int Mn, int d,
+                            int H, int Hkv, int dh,
+                            const double *wq /*[H*dh,d]*/, const double *wk /*[Hkv*dh,d]*/,
+                            const double *wv, const double *wo /*[d_out,H*dh]*/, int d_out,
+                            const double *kcache, const double *vcache /*[B,Hkv,P_cap,dh]*/,
+                            const int32_t *prefix_len /*[B]*/, int P_cap,
+                            const int32_t *parent /*[B,M]*/,
+                            double *out /*[B,Mn,d_out]*/,
+                            double *k_draft, double *v_draft /*[B,Hkv,M,dh] in/out*/);
+
 /* Greedy acceptance (Sec. 2.2: everything after the first mismatch is dropped).
  * tok[i] is the token drafted at node i; tgt[i] is the LLM's greedy token after
  * node i.  Walk from the root to the lowest-index child whose token equals the
