@@ -145,6 +145,31 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
                              const uint64_t *mask, void *out, void *k_tree, void *v_tree,
                              int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
 
+/* Self-Attention layer of the draft model on draft-token embeddings, tree form (Sec. 3.1,
+ * "Self-Attention": a causal self-attention on the queries of the Cross-Attention, so that a
+ * drafted token is aware of the tokens drafted before it; Alg. 1, q <- SA_layer(token_embed(y));
+ * appendix table: embedding 4096, keys/values 512, i.e. shape->n_kv_heads = 4 at head_dim 128).
+ * Causal over the token sequence that leads to a node: node i attends the layer's cached keys /
+ * values of the verified tokens (rows 0..prefix_len[b]-1) and the drafted nodes on its own path
+ * (bit j of mask[b][i]).  Drafting proceeds level by level, so a call covers the Mn nodes
+ * node_begin .. node_begin+Mn-1 of a tree of M nodes:
+ *   emb [B, Mn, d] (rows of the new nodes only); mask [B, M, W] of the whole tree (rows of
+ *   nodes not yet drafted are not read; every ancestor of a new node is < node_begin+Mn);
+ *   k_draft, v_draft [B, Hkv, M, dh]: the per-cycle draft cache; rows node_begin.. are written
+ *   (the new nodes' projected keys / values), rows below are read as earlier calls left them;
+ *   the caller drops the cache after verification (Alg. 1, "discard")
+ *   -> out [B, Mn, d]: the Cross-Attention queries of the new nodes.
+ * node_begin = 0, Mn = M handles a whole tree at once.  MOA_ERR_RANGE if the node range leaves
+ * the tree.  Weights, caches, workspace and dev_status as for moa_tree_verify_attn (workspace:
+ * moa_workspace_bytes with this shape, Mn as the tree size is enough; M always is). */
+int32_t moa_self_attn_draft(const moa_shape_t *shape, const void *emb, int32_t B, int32_t M,
+                            int32_t node_begin, int32_t Mn,
+                            const void *wq, const void *wk, const void *wv, const void *wo,
+                            const void *kcache, const void *vcache,
+                            const int32_t *prefix_len /*[B]*/, int32_t P_cap,
+                            const uint64_t *mask, void *out, void *k_draft, void *v_draft,
+                            int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
+
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
  * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk.

@@ -64,7 +64,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
-            "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_self_attn_draft", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -80,7 +80,9 @@ _lib.moa_cross_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _v
 _lib.moa_tree_verify_attn.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
                                       _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moa_draft_step.argtypes = [C.POINTER(_StepArgs)]
-for _n in _SYMBOLS[2:12]:
+_lib.moa_self_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
+                                     _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+for _n in _SYMBOLS[2:11]:
     getattr(_lib, _n).restype = C.c_int32
 
 
@@ -229,6 +231,28 @@ def tree_verify_attn(shape: Shape, x, wq, wk, wv, wo, kcache, vcache, prefix_len
                                      _dev(mask, torch.int64, B * M * W, "mask"), _dev(out, dt, B * M * d, "out"),
                                      _dev(k_tree, dt, B * ekv * M, "k_tree"), _dev(v_tree, dt, B * ekv * M, "v_tree"),
                                      _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
+
+
+def self_attn_draft(shape: Shape, emb, node_begin, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask, out, k_draft, v_draft,
+                    ws, dev_status=None, stream=None):
+    """Draft Self-Attention layer on the nodes node_begin .. node_begin+Mn-1 (emb [B, Mn, d]) of the tree whose
+    mask [B, M, W] is given; k_draft / v_draft [B, Hkv, M, dh] are updated in place."""
+    dt = _TORCH_DTYPE[shape.dtype]
+    B, Mn, d = emb.shape
+    M = mask.shape[1]
+    W = (M + 63) // 64
+    dh = shape.head_dim
+    e, ekv = shape.n_q_heads * dh, shape.n_kv_heads * dh
+    cache = B * ekv * P_cap
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_self_attn_draft(C.byref(shape), _dev(emb, dt, B * Mn * d, "emb"), B, M, int(node_begin), Mn,
+                                    _dev(wq, dt, e * d, "wq"), _dev(wk, dt, ekv * d, "wk"), _dev(wv, dt, ekv * d, "wv"),
+                                    _dev(wo, dt, d * e, "wo"),
+                                    _dev(kcache, dt, cache, "kcache"), _dev(vcache, dt, cache, "vcache"),
+                                    _dev(prefix_len, torch.int32, B, "prefix_len"), P_cap,
+                                    _dev(mask, torch.int64, B * M * W, "mask"), _dev(out, dt, B * Mn * d, "out"),
+                                    _dev(k_draft, dt, B * ekv * M, "k_draft"), _dev(v_draft, dt, B * ekv * M, "v_draft"),
+                                    _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
 
 
 def _ptr_array(tensors, dtype, numel, name):

@@ -386,9 +386,12 @@ static int32_t attn_check(const char *who, const moa_shape_t *shape, const void 
 }
 
 // Q (and, for verification, the tree rows' K/V) projections; *q_out = where the queries are
+// A call may cover only the nodes node0 .. node0+M-1 of a tree of M_total nodes (0 = the whole tree): the new
+// rows' K/V then go to rows node0.. of slabs that hold M_total rows.
 static int32_t attn_stage_project(const char *who, const moa_shape_t *shape, const void *x, int32_t B, int32_t M,
                                   const void *wq, const void *wk, const void *wv, bool tree, void *k_tree,
-                                  void *v_tree, const AttnBufs &bf, hipStream_t st, const void **q_out)
+                                  void *v_tree, const AttnBufs &bf, hipStream_t st, const void **q_out,
+                                  int32_t M_total = 0, int32_t node0 = 0)
 {
     const int dh = shape->head_dim, H = shape->n_q_heads, Hkv = shape->n_kv_heads, d = shape->d_model;
     const int e = H * dh, ekv = Hkv * dh, dt = shape->dtype;
@@ -411,9 +414,10 @@ static int32_t attn_stage_project(const char *who, const moa_shape_t *shape, con
     }
     if (tree) {
         const void *w[2] = {wk, wv};
-        void *dst[2] = {k_tree, v_tree};
+        const size_t skip = (size_t)node0 * dh * esize(dt);          // first new row inside every slab
+        void *dst[2] = {(char *)k_tree + skip, (char *)v_tree + skip};
         for (int i = 0; i < 2; ++i) {
-            const StoreSpec sp = heads_store(dst[i], Hkv, dh, M, M);
+            const StoreSpec sp = heads_store(dst[i], Hkv, dh, M_total ? M_total : M, M);
             if (w[i]) {
                 la.seg[la.nseg].W = w[i];
                 la.seg[la.nseg].N = ekv;
@@ -430,7 +434,8 @@ static int32_t attn_stage_project(const char *who, const moa_shape_t *shape, con
 
 static AttnArgs attn_core_args(const moa_shape_t *shape, const void *q, int32_t B, int32_t M, const void *kcache,
                                const void *vcache, const int32_t *len, int32_t P_cap, const uint64_t *mask, void *dst,
-                               void *k_tree, void *v_tree, int32_t *dev_status, void *scratch, size_t scratch_bytes)
+                               void *k_tree, void *v_tree, int32_t *dev_status, void *scratch, size_t scratch_bytes,
+                               int32_t M_total = 0, int32_t node0 = 0)
 {
     AttnArgs aa = {};
     aa.dtype = shape->dtype;
@@ -444,7 +449,12 @@ static AttnArgs attn_core_args(const moa_shape_t *shape, const void *q, int32_t 
     aa.out = dst;
     aa.B = B;
     aa.Mq = M;
-    aa.Mt = mask ? M : 0;
+    aa.Mt = mask ? node0 + M : 0;        // keys: every node up to the last new one
+    if (mask && M_total) {
+        aa.tree_cap = M_total;
+        aa.mask_rows = M_total;
+        aa.mask_row0 = node0;
+    }
     aa.H = shape->n_q_heads;
     aa.Hkv = shape->n_kv_heads;
     aa.dh = shape->head_dim;
@@ -470,11 +480,12 @@ static LinSeg oproj_seg(const moa_shape_t *shape, const void *heads, const void 
 static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const void *q, int32_t B, int32_t M,
                                const void *wo, const void *kcache, const void *vcache, const int32_t *len,
                                int32_t P_cap, const uint64_t *mask, void *out, void *k_tree, void *v_tree,
-                               int32_t *dev_status, const AttnBufs &bf, hipStream_t st)
+                               int32_t *dev_status, const AttnBufs &bf, hipStream_t st, int32_t M_total = 0,
+                               int32_t node0 = 0)
 {
     const int e = shape->n_q_heads * shape->head_dim, dt = shape->dtype;
     const AttnArgs aa = attn_core_args(shape, q, B, M, kcache, vcache, len, P_cap, mask, wo ? (void *)bf.abuf : out,
-                                       k_tree, v_tree, dev_status, bf.scratch_c, bf.scratch_c_bytes);
+                                       k_tree, v_tree, dev_status, bf.scratch_c, bf.scratch_c_bytes, M_total, node0);
     prof_set_site(mask ? S_VERIFY_CORE : S_CA_CORE);
     MOA_TRY_HIP(launch_attn(aa, st), who);
     if (wo) {
@@ -510,7 +521,7 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
                                const void *wq, const void *wk, const void *wv, const void *wo,
                                const void *kcache, const void *vcache, const int32_t *len, int32_t P_cap,
                                const uint64_t *mask, void *out, void *k_tree, void *v_tree, int32_t *dev_status,
-                               void *ws, size_t ws_bytes, hipStream_t st)
+                               void *ws, size_t ws_bytes, hipStream_t st, int32_t M_total = 0, int32_t node0 = 0)
 {
     int32_t rc = attn_check(who, shape, wq, wk, wv, mask != nullptr);
     if (rc) return rc;
@@ -518,10 +529,10 @@ static int32_t attention_layer(const char *who, const moa_shape_t *shape, const 
     if (rc) return rc;
     const AttnBufs bf = attn_carve(shape, B, M, ws, ws_bytes);
     const void *q = nullptr;
-    rc = attn_stage_project(who, shape, x, B, M, wq, wk, wv, mask != nullptr, k_tree, v_tree, bf, st, &q);
+    rc = attn_stage_project(who, shape, x, B, M, wq, wk, wv, mask != nullptr, k_tree, v_tree, bf, st, &q, M_total, node0);
     if (rc) return rc;
     return attn_stage_core(who, shape, q, B, M, wo, kcache, vcache, len, P_cap, mask, out, k_tree, v_tree, dev_status,
-                           bf, st);
+                           bf, st, M_total, node0);
 }
 
 int32_t moa_cross_attn_draft(const moa_shape_t *shape, const void *xq, int32_t B, int32_t Mq, const void *wq,
@@ -553,6 +564,26 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
         return fail(MOA_ERR_SHAPE, "tree_verify_attn: NULL wo needs d == H*dh");
     return attention_layer("tree_verify_attn", shape, x, B, M, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask,
                            out, k_tree, v_tree, dev_status, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int32_t moa_self_attn_draft(const moa_shape_t *shape, const void *emb, int32_t B, int32_t M, int32_t node_begin,
+                            int32_t Mn, const void *wq, const void *wk, const void *wv, const void *wo,
+                            const void *kcache, const void *vcache, const int32_t *prefix_len, int32_t P_cap,
+                            const uint64_t *mask, void *out, void *k_draft, void *v_draft, int32_t *dev_status,
+                            void *ws, size_t ws_bytes, void *stream)
+{
+    int32_t rc = check_shape(shape, false);
+    if (rc) return rc;
+    if (!emb || !prefix_len || !mask || !out || !k_draft || !v_draft) return fail(MOA_ERR_NULL, "self_attn_draft: NULL pointer");
+    if (P_cap > 0 && (!kcache || !vcache)) return fail(MOA_ERR_NULL, "self_attn_draft: cache is NULL with P_cap > 0");
+    if (B < 1 || M < 1 || M > MOA_MAX_TREE || P_cap < 0)
+        return fail(MOA_ERR_SHAPE, "self_attn_draft: B=%d M=%d P_cap=%d (M <= %d)", B, M, P_cap, MOA_MAX_TREE);
+    if (node_begin < 0 || Mn < 1 || node_begin + Mn > M)
+        return fail(MOA_ERR_RANGE, "self_attn_draft: nodes %d..%d of a tree of %d", node_begin, node_begin + Mn - 1, M);
+    if (!wo && shape->n_q_heads * shape->head_dim != shape->d_model)
+        return fail(MOA_ERR_SHAPE, "self_attn_draft: NULL wo needs d == H*dh");
+    return attention_layer("self_attn_draft", shape, emb, B, Mn, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask,
+                           out, k_draft, v_draft, dev_status, ws, ws_bytes, (hipStream_t)stream, M, node_begin);
 }
 
 static int32_t draft_step_stages(const moa_step_args_t *a)

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(64) void k_attn_generic(AttnArgs a)
     const int m = (blockIdx.x / a.H) % a.Mq;
     const int b = blockIdx.x / (a.H * a.Mq);
     const int g = h / (a.H / a.Hkv);
-    const int dh = a.dh, W = (a.Mq + 63) >> 6;
+    const int dh = a.dh, W = (a.mask_rows + 63) >> 6;
     const float scale = 1.0f / sqrtf((float)dh);
 
     const T *q = (const T *)a.q + (((int64_t)b * a.Mq + m) * a.H + h) * dh;
@@ -68,9 +68,9 @@ __global__ __launch_bounds__(64) void k_attn_generic(AttnArgs a)
     const int total = len + Mt;
     const T *kc = (const T *)a.kcache + ((int64_t)b * a.Hkv + g) * (int64_t)a.P_cap * dh;
     const T *vc = (const T *)a.vcache + ((int64_t)b * a.Hkv + g) * (int64_t)a.P_cap * dh;
-    const T *kt = (const T *)a.ktree + ((int64_t)b * a.Hkv + g) * (int64_t)a.Mt * dh;
-    const T *vt = (const T *)a.vtree + ((int64_t)b * a.Hkv + g) * (int64_t)a.Mt * dh;
-    const uint64_t *mrow = a.mask ? a.mask + ((int64_t)b * a.Mq + m) * W : nullptr;
+    const T *kt = (const T *)a.ktree + ((int64_t)b * a.Hkv + g) * (int64_t)a.tree_cap * dh;
+    const T *vt = (const T *)a.vtree + ((int64_t)b * a.Hkv + g) * (int64_t)a.tree_cap * dh;
+    const uint64_t *mrow = a.mask ? a.mask + ((int64_t)b * a.mask_rows + a.mask_row0 + m) * W : nullptr;
 
     float mrun = -INFINITY, lrun = 0.f;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(256, NBLK == 1 ? 2 : 1) void k_attn_mfma(AttnGroup 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int split = blockIdx.x, rowtile = blockIdx.y;
     const int bg = blockIdx.z - call * grp.nbg, b = bg / a.Hkv, g = bg % a.Hkv;
-    const int G = a.H / a.Hkv, RG = G * a.Mq, W = (a.Mq + 63) >> 6;
+    const int G = a.H / a.Hkv, RG = G * a.Mq, W = (a.mask_rows + 63) >> 6;
     const float sc = 1.4426950408889634f / sqrtf((float)DH);   // scores are kept in the log2 domain
 
     const int len = clamp_len(a.len[b], a.P_cap, tid == 0 ? a.dev_status : nullptr);
@@ -174,8 +174,8 @@ __global__ __launch_bounds__(256, NBLK == 1 ? 2 : 1) void k_attn_mfma(AttnGroup 
 
     const bf16_t *kc = (const bf16_t *)a.kcache + (int64_t)bg * a.P_cap * DH;
     const bf16_t *vc = (const bf16_t *)a.vcache + (int64_t)bg * a.P_cap * DH;
-    const bf16_t *ktp = (const bf16_t *)a.ktree + (int64_t)bg * a.Mt * DH;
-    const bf16_t *vtp = (const bf16_t *)a.vtree + (int64_t)bg * a.Mt * DH;
+    const bf16_t *ktp = (const bf16_t *)a.ktree + (int64_t)bg * a.tree_cap * DH;
+    const bf16_t *vtp = (const bf16_t *)a.vtree + (int64_t)bg * a.tree_cap * DH;
 
     // query fragments (B operand of S^T = K Q^T): lane = query column l32, 8 head_dim values
     const int rowbase = rowtile * (128 * NBLK) + wave * (32 * NBLK);
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(256, NBLK == 1 ? 2 : 1) void k_attn_mfma(AttnGroup 
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk) {
                 uint32_t vis = 0xffffffffu;
-                if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.Mq + mrow_of[blk]) * W + (base >> 6)] >> (base & 63));
+                if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.mask_rows + a.mask_row0 + mrow_of[blk]) * W + (base >> 6)] >> (base & 63));
                 if (nvalid < 32) vis &= (1u << nvalid) - 1u;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -428,7 +428,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
     const int call = u / grp.nbg, bg = u - call * grp.nbg;
     const AttnArgs &a = grp.a[call];
     const int b = bg / a.Hkv, g = bg - b * a.Hkv;
-    const int G = a.H / a.Hkv, RG = G * a.Mq, W = (a.Mq + 63) >> 6;
+    const int G = a.H / a.Hkv, RG = G * a.Mq, W = (a.mask_rows + 63) >> 6;
     const float sc = 1.4426950408889634f / sqrtf((float)DH);   // scores are kept in the log2 domain
 
     // the block's 32 query rows: requested first (they do not depend on the sequence length), row-contiguous
@@ -450,8 +450,8 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
 
     const bf16_t *kc = (const bf16_t *)a.kcache + (int64_t)bg * a.P_cap * DH;
     const bf16_t *vc = (const bf16_t *)a.vcache + (int64_t)bg * a.P_cap * DH;
-    const bf16_t *ktp = (const bf16_t *)a.ktree + (int64_t)bg * a.Mt * DH;
-    const bf16_t *vtp = (const bf16_t *)a.vtree + (int64_t)bg * a.Mt * DH;
+    const bf16_t *ktp = (const bf16_t *)a.ktree + (int64_t)bg * a.tree_cap * DH;
+    const bf16_t *vtp = (const bf16_t *)a.vtree + (int64_t)bg * a.tree_cap * DH;
 
     // the K/V tile as the wave loads it: instruction j covers rows RPI j .. RPI j + RPI - 1, 16 bytes per lane.
     // A cache tile that lies wholly below the length needs no row clamp: one base address, constant offsets.
@@ -541,7 +541,7 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
                 const int base = tree ? (i - ntc) * KT : i * KT;
                 const int nvalid = (tree ? Mt : len) - base;   // >= 1
                 uint32_t vis = 0xffffffffu;
-                if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.Mq + mrow) * W + (base >> 6)] >> (base & 63));
+                if (tree) vis = (uint32_t)(a.mask[((int64_t)b * a.mask_rows + a.mask_row0 + mrow) * W + (base >> 6)] >> (base & 63));
                 if (nvalid < 32) vis &= (1u << nvalid) - 1u;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -849,15 +849,27 @@ static hipError_t launch_attn_split(const AttnArgs *calls, int n, hipStream_t st
     return hipGetLastError();
 }
 
-hipError_t launch_attn(const AttnArgs &a, hipStream_t stream)
+// whole-tree defaults of the tree window; false when the window does not fit its tree
+static bool tree_window(AttnArgs &a)
 {
+    if (!a.tree_cap) a.tree_cap = a.Mt;
+    if (!a.mask_rows) a.mask_rows = a.Mq;
+    return a.mask_row0 >= 0 && a.mask_row0 + a.Mq <= a.mask_rows && a.Mt <= a.tree_cap;
+}
+
+hipError_t launch_attn(const AttnArgs &a_in, hipStream_t stream)
+{
+    AttnArgs a = a_in;
+    if (!tree_window(a)) return hipErrorInvalidValue;
     if (mfma_ok(a.dtype, a.dh, &a) && want_fused(a)) return launch_attn_fused(&a, 1, stream);
     if (attn_split_ok(a, a.P_cap)) return launch_attn_split(&a, 1, stream);
     return launch_attn_generic(a, stream);
 }
 
-hipError_t launch_attn_pair(const AttnArgs &a0, const AttnArgs &a1, hipStream_t stream)
+hipError_t launch_attn_pair(const AttnArgs &a0_in, const AttnArgs &a1_in, hipStream_t stream)
 {
+    AttnArgs a0 = a0_in, a1 = a1_in;
+    if (!tree_window(a0) || !tree_window(a1)) return hipErrorInvalidValue;
     const int cap = a0.P_cap > a1.P_cap ? a0.P_cap : a1.P_cap;
     const bool same = a0.dtype == a1.dtype && a0.B == a1.B && a0.Mq == a1.Mq && a0.H == a1.H && a0.Hkv == a1.Hkv && a0.dh == a1.dh;
     const AttnArgs both[2] = {a0, a1};

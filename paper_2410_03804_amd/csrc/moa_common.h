@@ -176,6 +176,10 @@ struct AttnArgs {
     const uint64_t *mask; // [B, Mq, W] or nullptr
     void *out;            // [B*Mq, H*dh]
     int B, Mq, Mt, H, Hkv, dh, P_cap;
+    // A call on part of a tree (level-by-level drafting): the Mq queries are the nodes mask_row0 .. of a tree of
+    // mask_rows nodes (mask is [B, mask_rows, ceil(mask_rows/64)]), the tree slabs have tree_cap rows of which the
+    // first Mt are keys.  Zero = the whole tree: mask_rows = Mq, tree_cap = Mt (filled in by launch_attn).
+    int tree_cap, mask_rows, mask_row0;
     int empty_is_error;   // cross-attention: len == 0 -> flag + zeros
     int32_t *dev_status;
     void *ws;
