@@ -59,6 +59,9 @@ def parse():
     ap.add_argument("--lsa-tokens", default="tree",
                     help="tokens per sequence that are new to the Layer Self-Attention in a step: 'tree' (M, the "
                          "headline), 'prefix' (first cycle: the whole prompt) or an integer (accepted tokens, ~5)")
+    ap.add_argument("--with-sa", action="store_true",
+                    help="run the drafter's Self-Attention layer in front of the cross-attention (its output becomes "
+                         "the CA queries); not part of the headline step")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run three plain device copies of this many MiB (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -77,7 +80,7 @@ def lsa_token_count(cfg, lsa_tokens):
     return cfg.B * int(lsa_tokens)
 
 
-def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree"):
+def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree", with_sa=False):
     """Algorithmic bytes and flops per launch site for one step: what the call must read and write once
     (inputs, weights, caches, outputs) and 2*MACs of the contractions as defined."""
     es = 2 if cfg.dtype == "bf16" else 4
@@ -111,6 +114,12 @@ def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree"):
            "verify.core": dict(bytes=cache_v + 2 * T * E * es, flops=core_flops_v),
            "verify.o_proj": lin(T, E, d)}
     c["tree_accept"] = dict(bytes=B * M * 16 + B * 8, flops=0.0)
+    if with_sa:
+        ekv_s = mi.sa_kv_heads(cfg) * dh
+        c["sa.qkv_proj"] = lin(T, d, E + 2 * ekv_s)
+        c["sa.core"] = dict(bytes=2.0 * ekv_s * es * float(plen.sum()) + 2.0 * B * ekv_s * M * es + 2 * T * E * es,
+                            flops=core_flops_v)
+        c["sa.o_proj"] = lin(T, E, d)
 
     def add(*parts):
         return dict(bytes=sum(p["bytes"] for p in parts), flops=sum(p["flops"] for p in parts))
@@ -162,7 +171,7 @@ def main():
 
     t_setup = time.perf_counter()
     lsa_tokens = args.lsa_tokens if args.lsa_tokens in ("tree", "prefix") else int(args.lsa_tokens)
-    works = [mi.step_workload(cfg, NL, variant=i, lsa_tokens=lsa_tokens) for i in range(nsets)]
+    works = [mi.step_workload(cfg, NL, variant=i, lsa_tokens=lsa_tokens, with_sa=args.with_sa) for i in range(nsets)]
     sets = []
     ws = None
     for w in works:
@@ -268,7 +277,7 @@ def main():
     tokens = cfg.B * cfg.M
     value = tokens / (ms_per_step * 1e-3)
 
-    costs = site_costs(cfg, NL, schedule=args.schedule, lsa_tokens=lsa_tokens)
+    costs = site_costs(cfg, NL, schedule=args.schedule, lsa_tokens=lsa_tokens, with_sa=args.with_sa)
     peak_mm = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else VEC_F32_PEAK_TFLOPS
     pieces = []
     for site, kern, n, ms in sorted(rows, key=lambda r: -r[3]):
@@ -337,7 +346,8 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} prefix={cfg.P_min}..{cfg.P_max} tree M={cfg.M} depth={cfg.D} "
                                f"L={cfg.L} d={cfg.d} H={cfg.H}/{cfg.Hkv} dh={cfg.dh} d_lsa_in={cfg.d_lsa_in}; "
-                               f"LSA on T={lsa_token_count(cfg, lsa_tokens)} tokens ({lsa_tokens}), {NL} tree-verify layer(s)",
+                               f"LSA on T={lsa_token_count(cfg, lsa_tokens)} tokens ({lsa_tokens}), {NL} tree-verify layer(s)"
+                               + ("; Self-Attention layer in front of the CA" if args.with_sa else ""),
                    "verify_layers": NL, "buffer_sets": nsets, "profile_steps": P},
         "roofline": roofline, "cpu_baseline": cpu, "ceilings": ceilings,
         "hot_cache": {"ms_per_step": round(hot_ms, 5), "steps": hot_steps,

@@ -172,7 +172,8 @@ int32_t moa_self_attn_draft(const moa_shape_t *shape, const void *emb, int32_t B
 
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
- * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk.
+ * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk;
+ * optionally (sa_emb != NULL) the drafter's Self-Attention layer produces the CA's queries first.
  * The *_host members are HOST arrays of n_verify_layers device pointers.
  * Scheduling (`schedule`), all with the same ordering as seen from `stream`:
  *  MOA_SCHED_GROUPED (0, default): calls of the step that do not depend on each other and have the
@@ -217,6 +218,17 @@ typedef struct {
     const int32_t *tok, *tgt;  int32_t *path, *n_path, *bonus;
     int32_t *dev_status;  void *ws;  size_t ws_bytes;  void *stream;
     int32_t schedule;             /* MOA_SCHED_*                                                     */
+    /* optional Self-Attention layer in front of the CA (Alg. 1: q <- SA_layer(token_embed(y)), then
+     * CA_layer(q, kv)): with sa_emb != NULL the step first runs moa_self_attn_draft on the whole
+     * tree (after the tree mask) and the CA takes sa_out as its queries; ca_xq is then ignored and
+     * Mq must equal M.  sa_shape is `shape` with the layer's own n_kv_heads.                        */
+    const moa_shape_t *sa_shape;
+    const void *sa_emb;                           /* [B, M, d] token embeddings of the tree nodes    */
+    const void *sa_wq, *sa_wk, *sa_wv, *sa_wo;
+    const void *sa_kcache, *sa_vcache;            /* [B, Hkv_sa, sa_P_cap, dh], prefix_len[b] rows   */
+    int32_t sa_P_cap;
+    void *sa_k_draft, *sa_v_draft;                /* [B, Hkv_sa, M, dh] per-cycle draft cache (out)  */
+    void *sa_out;                                 /* [B, M, d]: the CA's queries                     */
 } moa_step_args_t;
 
 int32_t moa_draft_step(const moa_step_args_t *args);

@@ -310,7 +310,7 @@ def kv_cache(cfg: Config, which: int = 0, P_cap: int | None = None):
     return normal(rng, shape, cfg.dtype), normal(rng, shape, cfg.dtype)
 
 
-def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0, lsa_tokens="tree"):
+def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0, lsa_tokens="tree", with_sa: bool = False):
     """All inputs of one draft step as numpy arrays (values already rounded to cfg.dtype).
 
     `lsa_tokens` says how many tokens per sequence are new to the Layer Self-Attention in this step:
@@ -318,7 +318,9 @@ def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0, lsa_t
     empty memory before), or an integer A (the accepted tokens of the last cycle).  LSA runs on their sum T;
     the cross-attention memory holds P_b minus that many rows before the step and P_b rows after the append.
     `variant` draws an independent set of the large tensors (weights, activations, caches) so a
-    benchmark can rotate buffer sets; trees, tokens and lengths stay the same."""
+    benchmark can rotate buffer sets; trees, tokens and lengths stay the same.
+    `with_sa` adds the drafter's Self-Attention layer in front of the cross-attention (key "sa": its weights, the
+    tree nodes' token embeddings and its K/V cache of the verified tokens); the layer's output then replaces `ca_xq`."""
     v = 50 * variant
     B, M = cfg.B, cfg.M
     parent = trees(cfg)
@@ -356,7 +358,11 @@ def step_workload(cfg: Config, n_verify_layers: int = 1, variant: int = 0, lsa_t
         kc = normal(rc, (B, cfg.Hkv, cfg.P_cap, dh), cfg.dtype)
         vc = normal(rc, (B, cfg.Hkv, cfg.P_cap, dh), cfg.dtype)
         layers.append(dict(w=w, x=x, kcache=kc, vcache=vc))
-    return dict(cfg=cfg, parent=parent, tok=tok, tgt=tgt, prefix_len=plen, P_cap=cfg.P_cap,
+    sa = None
+    if with_sa:
+        emb, sk, sv = sa_inputs(cfg, variant)
+        sa = dict(w=sa_weights(cfg, variant), emb=emb, kcache=sk, vcache=sv)
+    return dict(cfg=cfg, sa=sa, parent=parent, tok=tok, tgt=tgt, prefix_len=plen, P_cap=cfg.P_cap,
                 lsa_w=lsa_w, lsa_hs=lsa_hs, tok_off=np.concatenate([[0], np.cumsum(new_tok)]).astype(np.int32),
                 ca_w=ca_w, ca_xq=ca_xq, ca_k=ca_k, ca_v=ca_v, ca_len0=(plen - new_tok).astype(np.int32),
                 ca_P_cap=ca_P_cap, layers=layers)

@@ -57,6 +57,10 @@ class _StepArgs(C.Structure):
         ("bonus", C.c_void_p),
         ("dev_status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_size_t), ("stream", C.c_void_p),
         ("schedule", C.c_int32),
+        ("sa_shape", C.POINTER(Shape)), ("sa_emb", C.c_void_p),
+        ("sa_wq", C.c_void_p), ("sa_wk", C.c_void_p), ("sa_wv", C.c_void_p), ("sa_wo", C.c_void_p),
+        ("sa_kcache", C.c_void_p), ("sa_vcache", C.c_void_p), ("sa_P_cap", C.c_int32),
+        ("sa_k_draft", C.c_void_p), ("sa_v_draft", C.c_void_p), ("sa_out", C.c_void_p),
     ]
 
 
@@ -265,10 +269,12 @@ def _ptr_array(tensors, dtype, numel, name):
 
 def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len,
                ca_P_cap, ca_xq, ca_out, v_x, v_w, v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, P_cap,
-               tok, tgt, path, n_path, bonus, ws, dev_status=None, schedule=0):
+               tok, tgt, path, n_path, bonus, ws, dev_status=None, schedule=0, sa=None):
     """Marshal (and size-check) the arguments of moa_draft_step once; the returned plan can be run many times.
     lsa_w = dict(wq, wk, wv, wo); ca_w = dict(wq, wo, wk, wv); v_w = list (one per verified layer) of
-    dict(wq, wk, wv, wo); v_* = lists of per-layer tensors.  The plan keeps the tensors alive."""
+    dict(wq, wk, wv, wo); v_* = lists of per-layer tensors.  The plan keeps the tensors alive.
+    sa (optional) = dict(shape, emb, w=dict(wq, wk, wv, wo), kcache, vcache, P_cap, k_draft, v_draft, out): the
+    Self-Attention layer in front of the cross-attention (ca_xq may then be None)."""
     dt, i32 = _TORCH_DTYPE[shape.dtype], torch.int32
     B, M = parent.shape
     Mq = ca_xq.shape[1]
@@ -300,7 +306,7 @@ def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out
     a.ca_v = _dev(ca_v, dt, B * ekv * ca_P_cap, "ca_v")
     a.ca_len = _dev(ca_len, i32, B, "ca_len")
     a.ca_P_cap = ca_P_cap
-    a.ca_xq = _dev(ca_xq, dt, B * Mq * d, "ca_xq")
+    a.ca_xq = None if (sa is not None and ca_xq is None) else _dev(ca_xq, dt, B * Mq * d, "ca_xq")
     a.ca_wq = _dev(ca_w["wq"], dt, e * d, "ca wq")
     a.ca_wo = _dev(ca_w["wo"], dt, d * e, "ca wo")
     a.ca_out = _dev(ca_out, dt, B * Mq * d, "ca_out")
@@ -325,7 +331,23 @@ def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out
     a.dev_status = _dev(dev_status, i32, 1, "dev_status")
     a.ws, a.ws_bytes = _ws(ws)
     a.schedule = int(schedule)
-    tensors = [parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
+    if sa is not None:
+        ssh = sa["shape"]
+        ekv_s = ssh.n_kv_heads * dh
+        a.sa_shape = C.pointer(ssh)
+        a.sa_emb = _dev(sa["emb"], dt, B * M * d, "sa emb")
+        a.sa_wq = _dev(sa["w"]["wq"], dt, e * d, "sa wq")
+        a.sa_wk = _dev(sa["w"]["wk"], dt, ekv_s * d, "sa wk")
+        a.sa_wv = _dev(sa["w"]["wv"], dt, ekv_s * d, "sa wv")
+        a.sa_wo = _dev(sa["w"]["wo"], dt, d * e, "sa wo")
+        a.sa_P_cap = int(sa["P_cap"])
+        a.sa_kcache = _dev(sa["kcache"], dt, B * ekv_s * a.sa_P_cap, "sa kcache")
+        a.sa_vcache = _dev(sa["vcache"], dt, B * ekv_s * a.sa_P_cap, "sa vcache")
+        a.sa_k_draft = _dev(sa["k_draft"], dt, B * ekv_s * M, "sa k_draft")
+        a.sa_v_draft = _dev(sa["v_draft"], dt, B * ekv_s * M, "sa v_draft")
+        a.sa_out = _dev(sa["out"], dt, B * M * d, "sa out")
+        keep = keep + [ssh]
+    tensors = [sa, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
                v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, tok, tgt, path, n_path, bonus, ws, dev_status]
     return StepPlan(a, shape, keep, tensors)
 

@@ -376,6 +376,9 @@ struct AttnBufs {
     size_t scratch_c_bytes;
 };
 
+// launch sites of the layer being run, {projections, core, output projection}; nullptr = by kind of layer
+static thread_local const int *t_sites = nullptr;
+
 static int32_t attn_check(const char *who, const moa_shape_t *shape, const void *wq, const void *wk, const void *wv,
                           bool tree)
 {
@@ -396,7 +399,7 @@ static int32_t attn_stage_project(const char *who, const moa_shape_t *shape, con
     const int dh = shape->head_dim, H = shape->n_q_heads, Hkv = shape->n_kv_heads, d = shape->d_model;
     const int e = H * dh, ekv = Hkv * dh, dt = shape->dtype;
     const int64_t R = (int64_t)B * M;
-    prof_set_site(tree ? S_VERIFY_QKV : S_CA_QPROJ);
+    prof_set_site(t_sites ? t_sites[0] : (tree ? S_VERIFY_QKV : S_CA_QPROJ));
     LinArgs la = {};
     la.X = x;
     la.R = R;
@@ -486,7 +489,7 @@ static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const 
     const int e = shape->n_q_heads * shape->head_dim, dt = shape->dtype;
     const AttnArgs aa = attn_core_args(shape, q, B, M, kcache, vcache, len, P_cap, mask, wo ? (void *)bf.abuf : out,
                                        k_tree, v_tree, dev_status, bf.scratch_c, bf.scratch_c_bytes, M_total, node0);
-    prof_set_site(mask ? S_VERIFY_CORE : S_CA_CORE);
+    prof_set_site(t_sites ? t_sites[1] : (mask ? S_VERIFY_CORE : S_CA_CORE));
     MOA_TRY_HIP(launch_attn(aa, st), who);
     if (wo) {
         LinArgs lo = {};
@@ -499,7 +502,7 @@ static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const 
         lo.seg[0].ldx = 0;
         lo.ws = bf.scratch_c;
         lo.ws_bytes = bf.scratch_c_bytes;
-        prof_set_site(mask ? S_VERIFY_OPROJ : S_CA_OPROJ);
+        prof_set_site(t_sites ? t_sites[2] : (mask ? S_VERIFY_OPROJ : S_CA_OPROJ));
         MOA_TRY_HIP(launch_linear(dt, lo, st), who);
     }
     return MOA_OK;
@@ -582,8 +585,26 @@ int32_t moa_self_attn_draft(const moa_shape_t *shape, const void *emb, int32_t B
         return fail(MOA_ERR_RANGE, "self_attn_draft: nodes %d..%d of a tree of %d", node_begin, node_begin + Mn - 1, M);
     if (!wo && shape->n_q_heads * shape->head_dim != shape->d_model)
         return fail(MOA_ERR_SHAPE, "self_attn_draft: NULL wo needs d == H*dh");
-    return attention_layer("self_attn_draft", shape, emb, B, Mn, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask,
-                           out, k_draft, v_draft, dev_status, ws, ws_bytes, (hipStream_t)stream, M, node_begin);
+    static const int sites[3] = {S_SA_QKV, S_SA_CORE, S_SA_OPROJ};
+    t_sites = sites;
+    rc = attention_layer("self_attn_draft", shape, emb, B, Mn, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask,
+                         out, k_draft, v_draft, dev_status, ws, ws_bytes, (hipStream_t)stream, M, node_begin);
+    t_sites = nullptr;
+    return rc;
+}
+
+// the optional Self-Attention layer in front of the cross-attention: tree mask, then the layer on the whole tree
+static int32_t step_self_attn(const moa_step_args_t *a)
+{
+    if (!a->sa_shape || !a->sa_out) return fail(MOA_ERR_NULL, "draft_step: sa_shape / sa_out is NULL");
+    if (a->Mq != a->M) return fail(MOA_ERR_SHAPE, "draft_step: the Self-Attention layer needs Mq == M");
+    if (a->sa_shape->d_model != a->shape->d_model || a->sa_shape->dtype != a->shape->dtype)
+        return fail(MOA_ERR_SHAPE, "draft_step: sa_shape must have the step's d_model and dtype");
+    int32_t rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, a->stream);
+    if (rc) return rc;
+    return moa_self_attn_draft(a->sa_shape, a->sa_emb, a->B, a->M, 0, a->M, a->sa_wq, a->sa_wk, a->sa_wv, a->sa_wo,
+                               a->sa_kcache, a->sa_vcache, a->prefix_len, a->sa_P_cap, a->mask, a->sa_out,
+                               a->sa_k_draft, a->sa_v_draft, a->dev_status, a->ws, a->ws_bytes, a->stream);
 }
 
 static int32_t draft_step_stages(const moa_step_args_t *a)
@@ -894,20 +915,35 @@ static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
     return MOA_OK;
 }
 
-int32_t moa_draft_step(const moa_step_args_t *a)
+int32_t moa_draft_step(const moa_step_args_t *args)
 {
-    if (!a) return fail(MOA_ERR_NULL, "draft_step: args is NULL");
-    if (!a->shape) return fail(MOA_ERR_NULL, "draft_step: shape is NULL");
-    if (a->n_verify_layers < 0) return fail(MOA_ERR_SHAPE, "draft_step: n_verify_layers=%d", a->n_verify_layers);
-    if (a->schedule < MOA_SCHED_GROUPED || a->schedule > MOA_SCHED_SEQUENTIAL) return fail(MOA_ERR_SHAPE, "draft_step: schedule=%d", a->schedule);
-    if (a->n_verify_layers > 0 &&
-        (!a->v_x_host || !a->v_wq_host || !a->v_wk_host || !a->v_wv_host || !a->v_wo_host || !a->v_kcache_host ||
-         !a->v_vcache_host || !a->v_out_host || !a->v_ktree_host || !a->v_vtree_host))
+    if (!args) return fail(MOA_ERR_NULL, "draft_step: args is NULL");
+    if (!args->shape) return fail(MOA_ERR_NULL, "draft_step: shape is NULL");
+    if (args->n_verify_layers < 0) return fail(MOA_ERR_SHAPE, "draft_step: n_verify_layers=%d", args->n_verify_layers);
+    if (args->schedule < MOA_SCHED_GROUPED || args->schedule > MOA_SCHED_SEQUENTIAL) return fail(MOA_ERR_SHAPE, "draft_step: schedule=%d", args->schedule);
+    if (args->n_verify_layers > 0 &&
+        (!args->v_x_host || !args->v_wq_host || !args->v_wk_host || !args->v_wv_host || !args->v_wo_host || !args->v_kcache_host ||
+         !args->v_vcache_host || !args->v_out_host || !args->v_ktree_host || !args->v_vtree_host))
         return fail(MOA_ERR_NULL, "draft_step: a per-layer pointer array is NULL");
+    // With the Self-Attention layer in front, the cross-attention's queries are that layer's output.
+    const bool sa = args->sa_emb != nullptr;
+    moa_step_args_t with_sa;
+    const moa_step_args_t *a = args;
+    if (sa) {
+        with_sa = *args;
+        with_sa.ca_xq = args->sa_out;
+        a = &with_sa;
+    }
     g_dry = true;                       // every stage's host checks first: a bad argument launches nothing
-    int32_t rc = draft_step_stages(a);
+    int32_t rc = sa ? step_self_attn(args) : MOA_OK;
+    if (rc == MOA_OK) rc = draft_step_stages(a);
     g_dry = false;
     if (rc) return rc;
+    // The layer runs in front of whichever schedule follows (whose first launch writes the same masks again).
+    if (sa) {
+        rc = step_self_attn(args);
+        if (rc) return rc;
+    }
     // grouped launches by default; two streams on request when the workspace has room for both branches'
     // scratch; otherwise one stage after another
     if (a->schedule == MOA_SCHED_TWO_STREAM && pieces_ok(a) && a->ws_bytes >= two_stream_bytes(a)) {

@@ -98,7 +98,7 @@ enum KernelId {
 enum SiteId {
     S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,
     S_CA_OPROJ, S_VERIFY_QKV, S_VERIFY_CORE, S_VERIFY_OPROJ, S_TREE_ACCEPT, S_STEP_SMALL, S_PAIR_QKV, S_PAIR_CORE,
-    S_PAIR_OPROJ, S_PROBE, S_COUNT
+    S_PAIR_OPROJ, S_PROBE, S_SA_QKV, S_SA_CORE, S_SA_OPROJ, S_COUNT
 };
 void prof_set_site(int site);
 void prof_begin(int kernel, hipStream_t stream);   // no-ops unless profiling is enabled

@@ -38,7 +38,8 @@ const char *const kKernelNames[K_COUNT] = {
 const char *const kSiteNames[S_COUNT] = {
     "none", "tree_build", "lsa.qkv_proj", "lsa.layer_attn", "lsa.o_proj", "ca_append.kv_proj", "ca_append.lengths",
     "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept",
-    "tree_build+accept+lengths", "ca.q_proj+verify.qkv_proj", "ca.core+verify.core", "ca.o_proj+verify.o_proj", "probe"};
+    "tree_build+accept+lengths", "ca.q_proj+verify.qkv_proj", "ca.core+verify.core", "ca.o_proj+verify.o_proj", "probe",
+    "sa.qkv_proj", "sa.core", "sa.o_proj"};
 }  // namespace
 
 void prof_set_site(int site) { t_site = site; }

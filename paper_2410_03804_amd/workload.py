@@ -62,6 +62,16 @@ class DeviceStep:
         self.n_path = torch.zeros((B,), dtype=torch.int32, device="cuda")
         self.bonus = torch.zeros((B,), dtype=torch.int32, device="cuda")
         self.dev_status = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        self.sa = None
+        if work.get("sa") is not None:            # the Self-Attention layer in front of the cross-attention
+            sa = work["sa"]
+            hkv_s = sa["w"]["wk"].shape[0] // cfg.dh
+            self.sa = dict(shape=moa.Shape(cfg.L, cfg.d, cfg.H, hkv_s, cfg.dh, cfg.d_lsa_in, cfg.lsa_heads, cfg.Hkv, _MDT[dt]),
+                           emb=_dev(sa["emb"], dt), w={k: _dev(v, dt) for k, v in sa["w"].items()},
+                           kcache=_dev(sa["kcache"], dt), vcache=_dev(sa["vcache"], dt), P_cap=int(sa["kcache"].shape[2]),
+                           k_draft=torch.zeros((B, hkv_s, M, cfg.dh), dtype=tdt, device="cuda"),
+                           v_draft=torch.zeros((B, hkv_s, M, cfg.dh), dtype=tdt, device="cuda"),
+                           out=torch.zeros((B, M, cfg.d), dtype=tdt, device="cuda"))
         if ws is None:
             nbytes = moa.workspace_bytes(self.shape, B, max(self.P_cap, self.ca_P_cap), M, T)
             ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
@@ -78,7 +88,7 @@ class DeviceStep:
                 v_w=self.v_w, v_kcache=self.v_kcache, v_vcache=self.v_vcache, v_out=self.v_out, v_ktree=self.v_ktree,
                 v_vtree=self.v_vtree, prefix_len=self.prefix_len, P_cap=self.P_cap, tok=self.tok, tgt=self.tgt,
                 path=self.path, n_path=self.n_path, bonus=self.bonus, ws=self.ws, dev_status=self.dev_status,
-                schedule=schedule)
+                schedule=schedule, sa=self.sa)
         return self._plans[key]
 
     def run(self, len_slot: int = 0, stream=None, schedule: int = 0):

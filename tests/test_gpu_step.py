@@ -32,12 +32,18 @@ STEP_CASES = {
     "first_cycle_bf16": (mi.Config(name="FC", index=11, dtype="bf16", B=2, P_min=70, P_max=200, M=37, D=5, max_branch=4,
                                    L=6, d=512, H=8, Hkv=2, dh=128, d_lsa_in=512, rms_norm=True), 1, "prefix"),
     "accepted_only_bf16": (mi.CONFIGS["C1"], 1, 5),
+    # the drafter's Self-Attention layer in front of the cross-attention (Alg. 1: q <- SA_layer(token_embed(y)))
+    "small_f32_with_sa": (mi.Config(name="SAf", index=14, dtype="f32", B=2, P_min=20, P_max=90, M=19, D=4, max_branch=3, L=3,
+                                    d=192, H=6, Hkv=3, dh=32, d_lsa_in=96, rms_norm=True), 1, "tree", True),
+    "small_bf16_with_sa": (mi.Config(name="SAb", index=15, dtype="bf16", B=3, P_min=80, P_max=300, M=37, D=5, max_branch=4,
+                                     L=6, d=512, H=8, Hkv=4, dh=128, d_lsa_in=512, rms_norm=True), 2, "tree", True),
+    "C1_bf16_with_sa": (mi.CONFIGS["C1"], 1, "tree", True),
 }
 
 
 def _case(case):
     cfg, nlayers, *rest = STEP_CASES[case]
-    return cfg, nlayers, (rest[0] if rest else "tree")
+    return cfg, nlayers, (rest[0] if rest else "tree"), (rest[1] if len(rest) > 1 else False)
 
 
 SCHEDULES = {"grouped": 0, "two_stream": 1, "sequential": 2}
@@ -48,9 +54,9 @@ SCHEDULES = {"grouped": 0, "two_stream": 1, "sequential": 2}
 def test_draft_step_parity(G, oracle, case, schedule):
     from oracle.step import run_step
     from paper_2410_03804_amd.workload import DeviceStep
-    cfg, nlayers, lsa_tokens = _case(case)
-    print(f"[case] draft_step {case} {schedule} B={cfg.B} M={cfg.M} layers={nlayers} lsa_tokens={lsa_tokens}", flush=True)
-    work = mi.step_workload(cfg, n_verify_layers=nlayers, lsa_tokens=lsa_tokens)
+    cfg, nlayers, lsa_tokens, with_sa = _case(case)
+    print(f"[case] draft_step {case} {schedule} B={cfg.B} M={cfg.M} layers={nlayers} lsa_tokens={lsa_tokens} sa={with_sa}", flush=True)
+    work = mi.step_workload(cfg, n_verify_layers=nlayers, lsa_tokens=lsa_tokens, with_sa=with_sa)
     step = DeviceStep(work)
     step.run(schedule=SCHEDULES[schedule])
     torch.cuda.synchronize()
@@ -63,6 +69,10 @@ def test_draft_step_parity(G, oracle, case, schedule):
     assert np.array_equal(step.ca_len[0].cpu().numpy(), want["ca_len"])
     G.check_close(G.host(step.ca_k), want["ca_k"], dt, f"step.ca_k[{case}]")
     G.check_close(G.host(step.ca_v), want["ca_v"], dt, f"step.ca_v[{case}]")
+    if with_sa:
+        G.check_close(G.host(step.sa["out"]), want["sa_out"], dt, f"step.sa_out[{case}]")
+        G.check_close(G.host(step.sa["k_draft"]), want["sa_k_draft"], dt, f"step.sa_k_draft[{case}]")
+        G.check_close(G.host(step.sa["v_draft"]), want["sa_v_draft"], dt, f"step.sa_v_draft[{case}]")
     G.check_close(G.host(step.ca_out), want["ca_out"], dt, f"step.ca_out[{case}]")
     for l in range(nlayers):
         G.check_close(G.host(step.v_out[l]), want["v_out"][l], dt, f"step.verify{l}[{case}]")
