@@ -171,6 +171,39 @@ def self_attn_draft(emb, parent, node0, wq, wk, wv, wo, kcache, vcache, prefix_l
     return out
 
 
+def rope(v, pos, theta):
+    """Rotary embedding of one head vector (returns a rotated copy)."""
+    v = np.array(v, dtype=np.float64)
+    lib().moa_ref_rope.restype = None
+    lib().moa_ref_rope(_p(v), int(v.shape[0]), C.c_double(float(pos)), C.c_double(float(theta)))
+    return v
+
+
+def tli_decoder_layer(x, parent, node0, w, kcache, vcache, prefix_len, k_draft, v_draft, H, Hkv, dh, rms_eps, rope_theta):
+    """One reused LLM decoder layer on the tree nodes node0 .. node0+Mn-1 (x [B, Mn, d]); w = dict(g_attn, wq, wk, wv,
+    wo, g_mlp, w_gate, w_up, w_down); k_draft / v_draft [B, Hkv, M, dh] float64, updated in place."""
+    x = _f64(x)
+    B, Mn, d = x.shape
+    parent = _i32(parent)
+    M = parent.shape[1]
+    ww = {k: _f64(v) for k, v in w.items()}
+    kcache, vcache = _f64(kcache), _f64(vcache)
+    prefix_len = _i32(prefix_len)
+    for a in (k_draft, v_draft):
+        if a.dtype != np.float64 or not a.flags.c_contiguous or a.shape != (B, Hkv, M, dh):
+            raise ValueError("draft cache must be C-contiguous float64 [B, Hkv, M, dh]")
+    P_cap = 0 if kcache is None else kcache.shape[2]
+    d_ff = ww["w_gate"].shape[0]
+    out = np.empty((B, Mn, d), dtype=np.float64)
+    rc = lib().moa_ref_tli_decoder_layer(
+        _p(x), B, M, int(node0), Mn, d, H, Hkv, dh, d_ff, C.c_double(rms_eps), C.c_double(rope_theta),
+        _p(ww["g_attn"]), _p(ww["wq"]), _p(ww["wk"]), _p(ww["wv"]), _p(ww["wo"]), _p(ww["g_mlp"]), _p(ww["w_gate"]),
+        _p(ww["w_up"]), _p(ww["w_down"]), _p(kcache), _p(vcache), _p(prefix_len, C.c_int32), P_cap,
+        _p(parent, C.c_int32), _p(out), _p(k_draft), _p(v_draft))
+    _check(rc, "tli_decoder_layer")
+    return out
+
+
 def tree_accept(parent, tok, tgt):
     parent, tok, tgt = _i32(parent), _i32(tok), _i32(tgt)
     B, M = parent.shape

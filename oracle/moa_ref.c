@@ -350,6 +350,134 @@ int moa_ref_self_attn_draft(const double *emb, int B, int M, int node0, int Mn, 
     return MOA_REF_OK;
 }
 
+/* ------------------------------------------------------------ reused decoder layer (TLI) */
+
+void moa_ref_rope(double *v, int dh, double pos, double theta)
+{
+    const int half = dh / 2;
+    for (int c = 0; c < half; ++c) {
+        const double ang = pos * pow(theta, -2.0 * (double)c / (double)dh);
+        const double cs = cos(ang), sn = sin(ang);
+        const double a = v[c], b = v[c + half];
+        v[c] = a * cs - b * sn;
+        v[c + half] = b * cs + a * sn;
+    }
+}
+
+static void ref_rmsnorm(const double *x, int64_t R, int d, const double *g, double eps, double *y)
+{
+    for (int64_t r = 0; r < R; ++r) {
+        double ss = 0.0;
+        for (int c = 0; c < d; ++c) ss += x[r * d + c] * x[r * d + c];
+        const double inv = 1.0 / sqrt(ss / (double)d + eps);
+        for (int c = 0; c < d; ++c) y[r * d + c] = x[r * d + c] * inv * g[c];
+    }
+}
+
+int moa_ref_tli_decoder_layer(const double *x, int B, int M, int node0, int Mn, int d, int H, int Hkv, int dh,
+                              int d_ff, double rms_eps, double rope_theta,
+                              const double *g_attn, const double *wq, const double *wk, const double *wv,
+                              const double *wo, const double *g_mlp, const double *w_gate, const double *w_up,
+                              const double *w_down, const double *kcache, const double *vcache,
+                              const int32_t *prefix_len, int P_cap, const int32_t *parent,
+                              double *out, double *k_draft, double *v_draft)
+{
+    if (!x || !g_attn || !wq || !wk || !wv || !wo || !g_mlp || !w_gate || !w_up || !w_down || !prefix_len ||
+        !parent || !out || !k_draft || !v_draft)
+        return MOA_REF_BAD_ARG;
+    if (B < 1 || M < 1 || M > 4096 || Mn < 1 || node0 < 0 || node0 + Mn > M || d < 1 || H < 1 || Hkv < 1 ||
+        dh < 2 || (dh & 1) || d_ff < 1 || P_cap < 0 || H % Hkv || !(rms_eps >= 0.0) || !(rope_theta > 0.0))
+        return MOA_REF_BAD_ARG;
+    for (int b = 0; b < B; ++b) {
+        if (prefix_len[b] < 0 || prefix_len[b] > P_cap) return MOA_REF_BAD_ARG;
+        if (prefix_len[b] > 0 && (!kcache || !vcache)) return MOA_REF_BAD_ARG;
+        if (parent[(int64_t)b * M] != -1) return MOA_REF_BAD_TREE;
+        for (int i = 1; i < M; ++i)
+            if (parent[(int64_t)b * M + i] < 0 || parent[(int64_t)b * M + i] >= i) return MOA_REF_BAD_TREE;
+    }
+    const int E = H * dh, Ekv = Hkv * dh, G = H / Hkv;
+    const double inv_sqrt = 1.0 / sqrt((double)dh);
+    const int64_t R = (int64_t)B * Mn;
+    double *n1 = (double *)malloc(sizeof(double) * (size_t)R * d);
+    double *Q = (double *)malloc(sizeof(double) * (size_t)R * E);
+    double *Kn = (double *)malloc(sizeof(double) * (size_t)R * Ekv);
+    double *Vn = (double *)malloc(sizeof(double) * (size_t)R * Ekv);
+    double *A = (double *)malloc(sizeof(double) * (size_t)R * E);
+    double *h1 = (double *)malloc(sizeof(double) * (size_t)R * d);
+    double *gt = (double *)malloc(sizeof(double) * (size_t)R * d_ff);
+    double *up = (double *)malloc(sizeof(double) * (size_t)R * d_ff);
+    if (!n1 || !Q || !Kn || !Vn || !A || !h1 || !gt || !up) {
+        free(n1); free(Q); free(Kn); free(Vn); free(A); free(h1); free(gt); free(up);
+        return MOA_REF_BAD_ARG;
+    }
+    ref_rmsnorm(x, R, d, g_attn, rms_eps, n1);
+    moa_ref_linear(n1, R, d, wq, E, Q);
+    moa_ref_linear(n1, R, d, wk, Ekv, Kn);
+    moa_ref_linear(n1, R, d, wv, Ekv, Vn);
+
+    /* positions: a node sits depth(node) tokens after the verified prefix */
+    for (int64_t r = 0; r < R; ++r) {
+        const int b = (int)(r / Mn), i = node0 + (int)(r % Mn);
+        int depth = 0;
+        for (int j = parent[(int64_t)b * M + i]; j >= 0; j = parent[(int64_t)b * M + j]) ++depth;
+        const double pos = (double)prefix_len[b] + (double)depth;
+        for (int h = 0; h < H; ++h) moa_ref_rope(Q + r * E + h * dh, dh, pos, rope_theta);
+        for (int g = 0; g < Hkv; ++g) moa_ref_rope(Kn + r * Ekv + g * dh, dh, pos, rope_theta);
+    }
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hkv; ++g)
+            for (int t = 0; t < Mn; ++t)
+                for (int c = 0; c < dh; ++c) {
+                    const int64_t o = (((int64_t)b * Hkv + g) * M + node0 + t) * dh + c;
+                    k_draft[o] = Kn[((int64_t)b * Mn + t) * Ekv + g * dh + c];
+                    v_draft[o] = Vn[((int64_t)b * Mn + t) * Ekv + g * dh + c];
+                }
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t rh = 0; rh < R * H; ++rh) {
+        const int64_t r = rh / H;
+        const int h = (int)(rh % H), g = h / G, b = (int)(r / Mn), i = node0 + (int)(r % Mn);
+        const int P = prefix_len[b];
+        const double *q = Q + r * E + h * dh;
+        int path[4096];
+        int np = 0;
+        for (int j = i; j >= 0 && np < 4096; j = parent[(int64_t)b * M + j]) path[np++] = j;
+        const int n = P + np;
+        double *s = (double *)malloc(sizeof(double) * (size_t)n);
+        double *vv = (double *)malloc(sizeof(double) * (size_t)n * dh);
+        for (int p = 0; p < P; ++p) {
+            const double *kr = kcache + (((int64_t)b * Hkv + g) * P_cap + p) * dh;
+            const double *vr = vcache + (((int64_t)b * Hkv + g) * P_cap + p) * dh;
+            double acc = 0.0;
+            for (int c = 0; c < dh; ++c) acc += q[c] * kr[c];
+            s[p] = acc * inv_sqrt;
+            for (int c = 0; c < dh; ++c) vv[(int64_t)p * dh + c] = vr[c];
+        }
+        for (int u = 0; u < np; ++u) {
+            const int j = path[np - 1 - u];
+            const double *kr = k_draft + (((int64_t)b * Hkv + g) * M + j) * dh;
+            const double *vr = v_draft + (((int64_t)b * Hkv + g) * M + j) * dh;
+            double acc = 0.0;
+            for (int c = 0; c < dh; ++c) acc += q[c] * kr[c];
+            s[P + u] = acc * inv_sqrt;
+            for (int c = 0; c < dh; ++c) vv[(int64_t)(P + u) * dh + c] = vr[c];
+        }
+        moa_ref_softmax_weighted_sum(s, vv, n, dh, A + r * E + h * dh, NULL);
+        free(s); free(vv);
+    }
+    moa_ref_linear(A, R, E, wo, d, h1);
+    for (int64_t e = 0; e < R * d; ++e) h1[e] += x[e];                     /* first residual */
+
+    ref_rmsnorm(h1, R, d, g_mlp, rms_eps, n1);
+    moa_ref_linear(n1, R, d, w_gate, d_ff, gt);
+    moa_ref_linear(n1, R, d, w_up, d_ff, up);
+    for (int64_t e = 0; e < R * d_ff; ++e) gt[e] = gt[e] / (1.0 + exp(-gt[e])) * up[e];   /* silu(gate) * up */
+    moa_ref_linear(gt, R, d_ff, w_down, d, out);
+    for (int64_t e = 0; e < R * d; ++e) out[e] += h1[e];                  /* second residual */
+    free(n1); free(Q); free(Kn); free(Vn); free(A); free(h1); free(gt); free(up);
+    return MOA_REF_OK;
+}
+
 /* ------------------------------------------------------------ tree verify */
 
 int moa_ref_tree_verify_attn(const double *x, int B, int M, int d, int H, int Hkv, int dh,

@@ -110,6 +110,29 @@ int moa_ref_self_attn_draft(const double *emb /*[B,Mn,d]*/, int B, int M, int no
                             double *out /*[B,Mn,d_out]*/,
                             double *k_draft, double *v_draft /*[B,Hkv,M,dh] in/out*/);
 
+/* One reused LLM decoder layer under Target Layer Inference (Sec. 3.2: f^l_decoder((h^l_<=t, h^l_draft), o^l),
+ * applied to the drafted tokens with the layer's KV cache of the verified ones), tree form.
+ * The layer itself is the LLM's, a Llama-family pre-norm block (the paper's base models):
+ *   n1 = rmsnorm(x) * g_attn;  q, k, v = n1 Wq^T, n1 Wk^T, n1 Wv^T;
+ *   q, k rotated (RoPE, half-split pairs (c, c + dh/2), angle pos * theta^(-2c/dh)) at position
+ *   pos = prefix_len[b] + depth(node) -- the place the token would have in its own sequence;
+ *   h1 = x + concat_h(softmax(q K^T / sqrt(dh)) V) Wo^T over the cached rows and the node's own path;
+ *   n2 = rmsnorm(h1) * g_mlp;  out = h1 + (silu(n2 Wgate^T) * (n2 Wup^T)) Wdown^T.
+ * rmsnorm(x) = x / sqrt(mean(x^2) + eps).  The cache holds keys already rotated at their positions.
+ * Node range, draft cache and parent[] as for moa_ref_self_attn_draft (k_draft holds rotated keys). */
+int moa_ref_tli_decoder_layer(const double *x /*[B,Mn,d]*/, int B, int M, int node0, int Mn, int d,
+                              int H, int Hkv, int dh, int d_ff, double rms_eps, double rope_theta,
+                              const double *g_attn /*[d]*/, const double *wq, const double *wk,
+                              const double *wv, const double *wo /*[d,H*dh]*/,
+                              const double *g_mlp /*[d]*/, const double *w_gate /*[d_ff,d]*/,
+                              const double *w_up, const double *w_down /*[d,d_ff]*/,
+                              const double *kcache, const double *vcache /*[B,Hkv,P_cap,dh]*/,
+                              const int32_t *prefix_len, int P_cap, const int32_t *parent /*[B,M]*/,
+                              double *out /*[B,Mn,d]*/, double *k_draft, double *v_draft /*[B,Hkv,M,dh]*/);
+
+/* Rotary position embedding of one head vector in place (the convention above). */
+void moa_ref_rope(double *v /*[dh]*/, int dh, double pos, double theta);
+
 /* Greedy acceptance (Sec. 2.2: everything after the first mismatch is dropped).
  * tok[i] is the token drafted at node i; tgt[i] is the LLM's greedy token after
  * node i.  Walk from the root to the lowest-index child whose token equals the
