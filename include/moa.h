@@ -170,6 +170,32 @@ int32_t moa_self_attn_draft(const moa_shape_t *shape, const void *emb, int32_t B
                             const uint64_t *mask, void *out, void *k_draft, void *v_draft,
                             int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
 
+/* One reused LLM decoder layer under Target Layer Inference (Sec. 3.2: the last TLI layers of the
+ * LLM, f^l_decoder, run on the drafted tokens with their KV cache of the verified ones; Alg. 1, the
+ * loop over l = L-N .. L).  The layer is the LLM's own; for the paper's base models that is a
+ * Llama-family pre-norm block, which is what is built:
+ *   n1 = rmsnorm(x) * g_attn; q, k, v = n1 Wq^T, n1 Wk^T, n1 Wv^T; q and k rotated (rotary
+ *   embedding, pairs (c, c + dh/2), angle pos * theta^(-2c/dh)) at pos = prefix_len[b] + depth of the
+ *   node; h1 = x + TreeAttention(q; cache, draft rows on the node's path) Wo^T;
+ *   n2 = rmsnorm(h1) * g_mlp; out = h1 + (silu(n2 Wgate^T) * (n2 Wup^T)) Wdown^T,
+ *   rmsnorm(x) = x / sqrt(mean(x^2) + rms_eps).
+ * Node range, mask and per-cycle draft cache as for moa_self_attn_draft (k_draft holds rotated keys,
+ * the cache too, as the LLM stored them); depth [B, M] as written by moa_tree_build.
+ *   x [B, Mn, d]; g_attn, g_mlp [d]; wq [H*dh, d], wk, wv [Hkv*dh, d], wo [d, H*dh];
+ *   w_gate, w_up [d_ff, d], w_down [d, d_ff] -> out [B, Mn, d].
+ * All weights are required.  Workspace: moa_tli_workspace_bytes (host only, launches nothing). */
+typedef struct { int32_t d_ff; float rms_eps; float rope_theta; } moa_decoder_cfg_t;
+int32_t moa_tli_workspace_bytes(const moa_shape_t *shape, const moa_decoder_cfg_t *cfg, int32_t B,
+                                int32_t P_cap, int32_t M, size_t *bytes_host);
+int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t *cfg, const void *x,
+                              int32_t B, int32_t M, int32_t node_begin, int32_t Mn,
+                              const void *g_attn, const void *wq, const void *wk, const void *wv,
+                              const void *wo, const void *g_mlp, const void *w_gate, const void *w_up,
+                              const void *w_down, const void *kcache, const void *vcache,
+                              const int32_t *prefix_len /*[B]*/, int32_t P_cap, const uint64_t *mask,
+                              const int32_t *depth, void *out, void *k_draft, void *v_draft,
+                              int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
+
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
  * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk;

@@ -279,6 +279,22 @@ def sa_inputs(cfg: Config, variant: int = 0):
     return emb, normal(rc, shape, cfg.dtype), normal(rc, shape, cfg.dtype)
 
 
+def tli_d_ff(cfg: Config) -> int:
+    """MLP width of the LLM's decoder layer: 3.5 d (14336 at the Llama-3-8B shape)."""
+    return 7 * cfg.d // 2
+
+
+def tli_weights(cfg: Config, layer: int = 0):
+    """One reused LLM decoder layer: norm gains near 1, attention and gated-MLP weights ~ N(0, 1/in_features)."""
+    rng = rng_for(cfg, S_WEIGHT, extra=500 + layer)
+    E, ekv, d, dff = cfg.H * cfg.dh, cfg.E_kv, cfg.d, tli_d_ff(cfg)
+    gain = lambda: quantize(1.0 + 0.1 * rng.standard_normal(d), cfg.dtype)
+    return dict(g_attn=gain(), wq=weight(rng, E, d, cfg.dtype), wk=weight(rng, ekv, d, cfg.dtype),
+                wv=weight(rng, ekv, d, cfg.dtype), wo=weight(rng, d, E, cfg.dtype), g_mlp=gain(),
+                w_gate=weight(rng, dff, d, cfg.dtype), w_up=weight(rng, dff, d, cfg.dtype),
+                w_down=weight(rng, d, dff, cfg.dtype))
+
+
 def ca_weights(cfg: Config):
     rng = rng_for(cfg, S_WEIGHT, extra=2)
     E = cfg.H * cfg.dh

@@ -68,7 +68,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
-            "moa_self_attn_draft", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -86,7 +86,17 @@ _lib.moa_tree_verify_attn.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _v
 _lib.moa_draft_step.argtypes = [C.POINTER(_StepArgs)]
 _lib.moa_self_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
                                      _vp, _vp, _vp, _vp, _vp, _sz, _vp]
-for _n in _SYMBOLS[2:11]:
+
+
+class DecoderCfg(C.Structure):
+    """moa_decoder_cfg_t: MLP width, RMS-norm epsilon and rotary base of a reused LLM decoder layer."""
+    _fields_ = [("d_ff", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+_lib.moa_tli_workspace_bytes.argtypes = [C.POINTER(Shape), C.POINTER(DecoderCfg), _i32, _i32, _i32, C.POINTER(_sz)]
+_lib.moa_tli_decoder_layer.argtypes = [C.POINTER(Shape), C.POINTER(DecoderCfg), _vp, _i32, _i32, _i32, _i32] + [_vp] * 11 + [
+    _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+for _n in _SYMBOLS[2:13]:
     getattr(_lib, _n).restype = C.c_int32
 
 
@@ -257,6 +267,36 @@ def self_attn_draft(shape: Shape, emb, node_begin, wq, wk, wv, wo, kcache, vcach
                                     _dev(mask, torch.int64, B * M * W, "mask"), _dev(out, dt, B * Mn * d, "out"),
                                     _dev(k_draft, dt, B * ekv * M, "k_draft"), _dev(v_draft, dt, B * ekv * M, "v_draft"),
                                     _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
+
+
+def tli_workspace_bytes(shape: Shape, cfg: DecoderCfg, B: int, P_cap: int, M: int) -> int:
+    out = _sz(0)
+    _check(_lib.moa_tli_workspace_bytes(C.byref(shape), C.byref(cfg), B, P_cap, M, C.byref(out)))
+    return int(out.value)
+
+
+def tli_decoder_layer(shape: Shape, cfg: DecoderCfg, x, node_begin, w, kcache, vcache, prefix_len, P_cap, mask, depth, out,
+                      k_draft, v_draft, ws, dev_status=None, stream=None):
+    """One reused LLM decoder layer on the nodes node_begin .. node_begin+Mn-1 (x [B, Mn, d]); w = dict(g_attn, wq, wk,
+    wv, wo, g_mlp, w_gate, w_up, w_down); k_draft / v_draft [B, Hkv, M, dh] are updated in place."""
+    dt = _TORCH_DTYPE[shape.dtype]
+    B, Mn, d = x.shape
+    M = mask.shape[1]
+    W = (M + 63) // 64
+    dh = shape.head_dim
+    e, ekv, dff = shape.n_q_heads * dh, shape.n_kv_heads * dh, cfg.d_ff
+    cache = B * ekv * P_cap
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_tli_decoder_layer(
+        C.byref(shape), C.byref(cfg), _dev(x, dt, B * Mn * d, "x"), B, M, int(node_begin), Mn,
+        _dev(w["g_attn"], dt, d, "g_attn"), _dev(w["wq"], dt, e * d, "wq"), _dev(w["wk"], dt, ekv * d, "wk"),
+        _dev(w["wv"], dt, ekv * d, "wv"), _dev(w["wo"], dt, d * e, "wo"), _dev(w["g_mlp"], dt, d, "g_mlp"),
+        _dev(w["w_gate"], dt, dff * d, "w_gate"), _dev(w["w_up"], dt, dff * d, "w_up"), _dev(w["w_down"], dt, d * dff, "w_down"),
+        _dev(kcache, dt, cache, "kcache"), _dev(vcache, dt, cache, "vcache"),
+        _dev(prefix_len, torch.int32, B, "prefix_len"), P_cap, _dev(mask, torch.int64, B * M * W, "mask"),
+        _dev(depth, torch.int32, B * M, "depth"), _dev(out, dt, B * Mn * d, "out"),
+        _dev(k_draft, dt, B * ekv * M, "k_draft"), _dev(v_draft, dt, B * ekv * M, "v_draft"),
+        _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
 
 
 def _ptr_array(tensors, dtype, numel, name):

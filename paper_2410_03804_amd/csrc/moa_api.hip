@@ -607,6 +607,138 @@ static int32_t step_self_attn(const moa_step_args_t *a)
                                a->sa_k_draft, a->sa_v_draft, a->dev_status, a->ws, a->ws_bytes, a->stream);
 }
 
+// ---- a reused LLM decoder layer (Target Layer Inference)
+// workspace: [attention stage (queries | heads | scratch) | split-K scratch of the MLP projections |
+//             normed rows | projection result | residual stream (fp32) | gate, up | activation]
+struct TliBufs {
+    char *attn, *lin, *n, *tmp, *gu, *act;
+    float *h1;
+    size_t attn_bytes, lin_bytes, total;
+};
+
+static TliBufs tli_carve(const moa_shape_t *s, int32_t d_ff, int32_t B, int32_t Mn, int32_t P_cap, void *ws)
+{
+    const int64_t R = (int64_t)B * Mn;
+    const size_t es = esize(s->dtype), d = (size_t)s->d_model;
+    TliBufs t;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *p = (char *)ws + off; off += align256(bytes); return p; };
+    t.attn_bytes = align256(attn_ws_bytes(s, B, Mn, P_cap));
+    t.attn = take(t.attn_bytes);
+    t.lin_bytes = align256(max2(linear_workspace_bytes(s->dtype, R, s->d_model, 2 * d_ff),
+                                linear_workspace_bytes(s->dtype, R, d_ff, s->d_model)));
+    t.lin = take(t.lin_bytes);
+    t.n = take((size_t)R * d * es);
+    t.tmp = take((size_t)R * d * es);
+    t.h1 = (float *)take((size_t)R * d * sizeof(float));
+    t.gu = take((size_t)R * 2 * d_ff * es);
+    t.act = take((size_t)R * d_ff * es);
+    t.total = off;
+    return t;
+}
+
+int32_t moa_tli_workspace_bytes(const moa_shape_t *shape, const moa_decoder_cfg_t *cfg, int32_t B, int32_t P_cap,
+                                int32_t M, size_t *bytes_host)
+{
+    if (!bytes_host || !cfg) return fail(MOA_ERR_NULL, "tli_workspace_bytes: NULL pointer");
+    int32_t rc = check_shape(shape, false);
+    if (rc) return rc;
+    if (B < 1 || M < 1 || P_cap < 0 || cfg->d_ff < 1) return fail(MOA_ERR_SHAPE, "B=%d M=%d P_cap=%d d_ff=%d", B, M, P_cap, cfg->d_ff);
+    *bytes_host = tli_carve(shape, cfg->d_ff, B, M, P_cap, nullptr).total;
+    return MOA_OK;
+}
+
+int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t *cfg, const void *x, int32_t B,
+                              int32_t M, int32_t node_begin, int32_t Mn, const void *g_attn, const void *wq,
+                              const void *wk, const void *wv, const void *wo, const void *g_mlp, const void *w_gate,
+                              const void *w_up, const void *w_down, const void *kcache, const void *vcache,
+                              const int32_t *prefix_len, int32_t P_cap, const uint64_t *mask, const int32_t *depth,
+                              void *out, void *k_draft, void *v_draft, int32_t *dev_status, void *ws, size_t ws_bytes,
+                              void *stream)
+{
+    const char *who = "tli_decoder_layer";
+    int32_t rc = check_shape(shape, false);
+    if (rc) return rc;
+    if (!cfg || !x || !g_attn || !wq || !wk || !wv || !wo || !g_mlp || !w_gate || !w_up || !w_down || !prefix_len ||
+        !mask || !depth || !out || !k_draft || !v_draft)
+        return fail(MOA_ERR_NULL, "%s: NULL pointer", who);
+    if (P_cap > 0 && (!kcache || !vcache)) return fail(MOA_ERR_NULL, "%s: cache is NULL with P_cap > 0", who);
+    if (B < 1 || M < 1 || M > MOA_MAX_TREE || P_cap < 0)
+        return fail(MOA_ERR_SHAPE, "%s: B=%d M=%d P_cap=%d (M <= %d)", who, B, M, P_cap, MOA_MAX_TREE);
+    if (node_begin < 0 || Mn < 1 || node_begin + Mn > M)
+        return fail(MOA_ERR_RANGE, "%s: nodes %d..%d of a tree of %d", who, node_begin, node_begin + Mn - 1, M);
+    if (cfg->d_ff < 1 || !(cfg->rms_eps >= 0.f) || !(cfg->rope_theta > 0.f) || (shape->head_dim & 1))
+        return fail(MOA_ERR_SHAPE, "%s: d_ff=%d rms_eps=%g rope_theta=%g head_dim=%d (even)", who, cfg->d_ff,
+                    (double)cfg->rms_eps, (double)cfg->rope_theta, shape->head_dim);
+    const TliBufs t = tli_carve(shape, cfg->d_ff, B, Mn, P_cap, ws);
+    rc = check_ws(ws, ws_bytes, t.total);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int dt = shape->dtype, d = shape->d_model, d_ff = cfg->d_ff;
+    const int64_t R = (int64_t)B * Mn;
+    const size_t es = esize(dt);
+
+    // attention block: norm, Q/K/V, rotary positions, tree attention over cache + own path, output projection
+    prof_set_site(S_TLI_NORM);
+    MOA_TRY_HIP(launch_rmsnorm(dt, x, nullptr, R, d, g_attn, cfg->rms_eps, nullptr, t.n, st), who);
+    static const int sites[3] = {S_TLI_QKV, S_TLI_CORE, S_TLI_OPROJ};
+    t_sites = sites;
+    const AttnBufs bf = attn_carve(shape, B, Mn, t.attn, t.attn_bytes);
+    const void *q = nullptr;
+    rc = attn_stage_project(who, shape, t.n, B, Mn, wq, wk, wv, true, k_draft, v_draft, bf, st, &q, M, node_begin);
+    if (rc == MOA_OK) {
+        prof_set_site(S_TLI_ROPE);
+        if (!g_dry) {
+            const hipError_t e = launch_rope(dt, bf.qbuf, k_draft, prefix_len, depth, B, Mn, M, node_begin, shape->n_q_heads,
+                                             shape->n_kv_heads, shape->head_dim, (double)cfg->rope_theta, P_cap, st);
+            if (e != hipSuccess) rc = hip_fail(e, who);
+        }
+    }
+    if (rc == MOA_OK)
+        rc = attn_stage_core(who, shape, q, B, Mn, wo, kcache, vcache, prefix_len, P_cap, mask, t.tmp, k_draft, v_draft,
+                             dev_status, bf, st, M, node_begin);
+    t_sites = nullptr;
+    if (rc) return rc;
+
+    // MLP block: residual + norm, gate and up projections side by side, gated activation, down projection, residual
+    prof_set_site(S_TLI_NORM);
+    MOA_TRY_HIP(launch_rmsnorm(dt, x, t.tmp, R, d, g_mlp, cfg->rms_eps, t.h1, t.n, st), who);
+    LinArgs lg = {};
+    lg.X = t.n;
+    lg.R = R;
+    lg.K = d;
+    lg.ldx = d;
+    lg.nseg = 2;
+    lg.seg[0].W = w_gate;
+    lg.seg[0].N = d_ff;
+    lg.seg[0].st = row_store(t.gu, 2 * (int64_t)d_ff);
+    lg.seg[1].W = w_up;
+    lg.seg[1].N = d_ff;
+    lg.seg[1].st = row_store(t.gu + (size_t)d_ff * es, 2 * (int64_t)d_ff);
+    lg.ws = t.lin;
+    lg.ws_bytes = t.lin_bytes;
+    prof_set_site(S_TLI_GATE_UP);
+    MOA_TRY_HIP(launch_linear(dt, lg, st), who);
+    prof_set_site(S_TLI_ACT);
+    MOA_TRY_HIP(launch_swiglu(dt, t.gu, R, d_ff, t.act, st), who);
+    LinArgs ld = {};
+    ld.X = t.act;
+    ld.R = R;
+    ld.K = d_ff;
+    ld.ldx = d_ff;
+    ld.nseg = 1;
+    ld.seg[0].W = w_down;
+    ld.seg[0].N = d;
+    ld.seg[0].st = row_store(t.tmp, d);
+    ld.ws = t.lin;
+    ld.ws_bytes = t.lin_bytes;
+    prof_set_site(S_TLI_DOWN);
+    MOA_TRY_HIP(launch_linear(dt, ld, st), who);
+    prof_set_site(S_TLI_ADD);
+    MOA_TRY_HIP(launch_add_out(dt, t.h1, t.tmp, R * d, out, st), who);
+    return MOA_OK;
+}
+
 static int32_t draft_step_stages(const moa_step_args_t *a)
 {
     int32_t rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, a->stream);

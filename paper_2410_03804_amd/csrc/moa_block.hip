@@ -1,0 +1,142 @@
+// Row-wise pieces of a reused LLM decoder layer (Target Layer Inference, Sec. 3.2): RMS normalisation with the
+// residual add folded in, rotary positions for the projected queries / keys of the tree nodes, the gated
+// activation of the MLP, and the final residual add.  All are a few hundred KB of traffic at decode sizes:
+// launch latency, not bandwidth, is what they cost, so each does as much per launch as the data flow allows.
+#include "moa_common.h"
+
+namespace moa {
+
+// h = x (+ res); n = h / sqrt(mean(h^2) + eps) * g.  One workgroup per row; h is kept in fp32 when asked for
+// (the residual stream is rounded to the storage type only once, at the end of the layer).
+template <typename T>
+__global__ __launch_bounds__(256) void k_rmsnorm(const T *__restrict__ x, const T *__restrict__ res, int d,
+                                                 const T *__restrict__ g, float eps, float *__restrict__ h_out,
+                                                 T *__restrict__ n_out)
+{
+    __shared__ float part[4];
+    const int64_t r = blockIdx.x;
+    const T *xr = x + r * d;
+    const T *rr = res ? res + r * d : nullptr;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        const float v = ld<T>(xr + c) + (rr ? ld<T>(rr + c) : 0.f);
+        ss += v * v;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int c = threadIdx.x; c < d; c += 256) {
+        const float v = ld<T>(xr + c) + (rr ? ld<T>(rr + c) : 0.f);
+        if (h_out) h_out[r * d + c] = v;
+        st<T>(n_out + r * d + c, v * inv * ld<T>(g + c));
+    }
+}
+
+// Rotary positions, pairs (c, c + dh/2), angle = pos * theta^(-2c/dh), pos = prefix_len[b] + depth[b][node]:
+// the place the drafted token would take in its own sequence.  Queries [B*Mn, H*dh] and the new rows of the
+// draft key slabs [B, Hkv, M, dh] in place.  The angle is formed in double precision: at position 32768 a
+// single-precision angle is only good to 4e-3 rad, which would be the largest error of the whole layer.
+template <typename T>
+__global__ __launch_bounds__(256) void k_rope(T *__restrict__ q, T *__restrict__ k_draft, const int32_t *__restrict__ prefix_len,
+                                              const int32_t *__restrict__ depth, int B, int Mn, int M, int node0, int H,
+                                              int Hkv, int dh, double log_theta, int P_cap)
+{
+    const int half = dh >> 1;
+    const int64_t per_row = (int64_t)(H + Hkv) * half;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)B * Mn * per_row) return;
+    const int64_t r = idx / per_row;
+    const int e = (int)(idx - r * per_row), hh = e / half, c = e - hh * half;
+    const int b = (int)(r / Mn), i = node0 + (int)(r - (int64_t)b * Mn);
+    int plen = prefix_len[b];
+    plen = plen < 0 ? 0 : (plen > P_cap ? P_cap : plen);           // the attention core flags a bad length
+    const double pos = (double)plen + (double)depth[(int64_t)b * M + i];
+    const double ang = pos * exp(-2.0 * (double)c / (double)dh * log_theta);
+    double sn, cs;
+    sincos(ang, &sn, &cs);
+    T *v = hh < H ? q + (r * H + hh) * dh : k_draft + (((int64_t)b * Hkv + (hh - H)) * M + i) * dh;
+    const float a = ld<T>(v + c), bb = ld<T>(v + c + half);
+    st<T>(v + c, (float)((double)a * cs - (double)bb * sn));
+    st<T>(v + c + half, (float)((double)bb * cs + (double)a * sn));
+}
+
+// act[r, j] = silu(gu[r, j]) * gu[r, d_ff + j]   (gate and up projections side by side in one row)
+template <typename T>
+__global__ __launch_bounds__(256) void k_swiglu(const T *__restrict__ gu, int64_t R, int d_ff, T *__restrict__ act)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= R * d_ff) return;
+    const int64_t r = idx / d_ff;
+    const int j = (int)(idx - r * d_ff);
+    const float gt = ld<T>(gu + r * 2 * d_ff + j), up = ld<T>(gu + r * 2 * d_ff + d_ff + j);
+    st<T>(act + idx, gt / (1.0f + __expf(-gt)) * up);
+}
+
+// out = h (fp32 residual stream) + t
+template <typename T>
+__global__ __launch_bounds__(256) void k_add_out(const float *__restrict__ h, const T *__restrict__ t, int64_t n, T *__restrict__ out)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx < n) st<T>(out + idx, h[idx] + ld<T>(t + idx));
+}
+
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *res, int64_t R, int d, const void *g, float eps,
+                          float *h_out, void *n_out, hipStream_t stream)
+{
+    if (R <= 0) return hipSuccess;
+    prof_begin(K_RMSNORM, stream);
+    if (dtype == DT_BF16)
+        MOA_KLAUNCH(k_rmsnorm<bf16_t>, dim3((unsigned)R), dim3(256), 0, stream, (const bf16_t *)x, (const bf16_t *)res, d,
+                    (const bf16_t *)g, eps, h_out, (bf16_t *)n_out);
+    else
+        MOA_KLAUNCH(k_rmsnorm<float>, dim3((unsigned)R), dim3(256), 0, stream, (const float *)x, (const float *)res, d,
+                    (const float *)g, eps, h_out, (float *)n_out);
+    prof_end(stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope(int dtype, void *q, void *k_draft, const int32_t *prefix_len, const int32_t *depth, int B, int Mn,
+                       int M, int node0, int H, int Hkv, int dh, double theta, int P_cap, hipStream_t stream)
+{
+    const int64_t n = (int64_t)B * Mn * (H + Hkv) * (dh / 2);
+    if (n <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((n + 255) / 256));
+    const double lt = log(theta);
+    prof_begin(K_ROPE, stream);
+    if (dtype == DT_BF16)
+        MOA_KLAUNCH(k_rope<bf16_t>, grid, dim3(256), 0, stream, (bf16_t *)q, (bf16_t *)k_draft, prefix_len, depth, B, Mn, M,
+                    node0, H, Hkv, dh, lt, P_cap);
+    else
+        MOA_KLAUNCH(k_rope<float>, grid, dim3(256), 0, stream, (float *)q, (float *)k_draft, prefix_len, depth, B, Mn, M,
+                    node0, H, Hkv, dh, lt, P_cap);
+    prof_end(stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_swiglu(int dtype, const void *gu, int64_t R, int d_ff, void *act, hipStream_t stream)
+{
+    const int64_t n = R * d_ff;
+    if (n <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((n + 255) / 256));
+    prof_begin(K_SWIGLU, stream);
+    if (dtype == DT_BF16) MOA_KLAUNCH(k_swiglu<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)gu, R, d_ff, (bf16_t *)act);
+    else MOA_KLAUNCH(k_swiglu<float>, grid, dim3(256), 0, stream, (const float *)gu, R, d_ff, (float *)act);
+    prof_end(stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_add_out(int dtype, const float *h, const void *t, int64_t n, void *out, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((n + 255) / 256));
+    prof_begin(K_ADD_OUT, stream);
+    if (dtype == DT_BF16) MOA_KLAUNCH(k_add_out<bf16_t>, grid, dim3(256), 0, stream, h, (const bf16_t *)t, n, (bf16_t *)out);
+    else MOA_KLAUNCH(k_add_out<float>, grid, dim3(256), 0, stream, h, (const float *)t, n, (float *)out);
+    prof_end(stream);
+    return hipGetLastError();
+}
+
+}  // namespace moa

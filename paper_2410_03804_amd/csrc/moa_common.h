@@ -93,12 +93,14 @@ __device__ __forceinline__ int64_t store_offset(const StoreSpec &s, int64_t r, i
 // ---- optional per-launch timing (hipEvents around single kernels), used by the benchmark only
 enum KernelId {
     K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_SPLITK, K_LIN_REDUCE, K_LIN_TILED, K_SCATTER,
-    K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_LSA_ATTN_MFMA, K_STEP_SMALL, K_ATTN_FUSED, K_PROBE_READ, K_PROBE_MFMA, K_COUNT
+    K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_LSA_ATTN_MFMA, K_STEP_SMALL, K_ATTN_FUSED, K_PROBE_READ, K_PROBE_MFMA,
+    K_RMSNORM, K_ROPE, K_SWIGLU, K_ADD_OUT, K_COUNT
 };
 enum SiteId {
     S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,
     S_CA_OPROJ, S_VERIFY_QKV, S_VERIFY_CORE, S_VERIFY_OPROJ, S_TREE_ACCEPT, S_STEP_SMALL, S_PAIR_QKV, S_PAIR_CORE,
-    S_PAIR_OPROJ, S_PROBE, S_SA_QKV, S_SA_CORE, S_SA_OPROJ, S_COUNT
+    S_PAIR_OPROJ, S_PROBE, S_SA_QKV, S_SA_CORE, S_SA_OPROJ, S_TLI_QKV, S_TLI_CORE, S_TLI_OPROJ, S_TLI_NORM, S_TLI_ROPE,
+    S_TLI_GATE_UP, S_TLI_ACT, S_TLI_DOWN, S_TLI_ADD, S_COUNT
 };
 void prof_set_site(int site);
 void prof_begin(int kernel, hipStream_t stream);   // no-ops unless profiling is enabled
@@ -190,6 +192,14 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t stream);
 // Two independent cores of the same shape (cross-attention and one verification layer) in one launch; P_cap may
 // differ, each call's ws must hold attn_workspace_bytes for the larger one.  Falls back to two launches.
 hipError_t launch_attn_pair(const AttnArgs &a0, const AttnArgs &a1, hipStream_t stream);
+
+// ---- row-wise pieces of a reused decoder layer
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *res, int64_t R, int d, const void *g, float eps,
+                          float *h_out, void *n_out, hipStream_t stream);
+hipError_t launch_rope(int dtype, void *q, void *k_draft, const int32_t *prefix_len, const int32_t *depth, int B, int Mn,
+                       int M, int node0, int H, int Hkv, int dh, double theta, int P_cap, hipStream_t stream);
+hipError_t launch_swiglu(int dtype, const void *gu, int64_t R, int d_ff, void *act, hipStream_t stream);
+hipError_t launch_add_out(int dtype, const float *h, const void *t, int64_t n, void *out, hipStream_t stream);
 
 // ---- LSA attention over the layer axis with the mean folded in:
 // abar[t, h*dh + c] = sum_j (1/L sum_i softmax_i(S)[i][j]) V[t, j, g, c]

@@ -47,15 +47,27 @@ def mask_u64(mask_t):
     return mask_t.cpu().numpy().view(np.uint64)
 
 
-def check_close(got, want, dtype, what):
+# A residual stream is not confined to |y| < 2: one bf16 rounding of a value in [4, 8) is already 1.6e-2.  Where a
+# result is of that kind (the decoder layer: output rounded once, rotated keys twice), the absolute bound holds up
+# to |y| = 2 and becomes this relative one above (bf16: 2^-9 per rounding, a few roundings; fp32 likewise scaled)
+BIG_VALUE_REL = {"f32": 5e-5, "bf16": 1e-2}
+
+
+def check_close(got, want, dtype, what, residual_stream=False):
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (what, got.shape, want.shape)
     assert np.all(np.isfinite(got)), f"{what}: non-finite output"
-    err = float(np.max(np.abs(got - want))) if got.size else 0.0
+    diff = np.abs(got - want)
+    err = float(np.max(diff)) if got.size else 0.0
     rms = float(np.sqrt(np.mean(want ** 2))) if got.size else 1.0
     rel = err / max(rms, 1e-30)
     print(f"[parity] {what}: max-abs {err:.3e}  rms(oracle) {rms:.3e}  max-abs/rms {rel:.3e}", flush=True)
-    assert err <= ABS_TOL[dtype], f"{what}: max-abs {err:.3e} > {ABS_TOL[dtype]}"
+    if residual_stream:
+        bound = np.maximum(ABS_TOL[dtype], BIG_VALUE_REL[dtype] * np.abs(want))
+        worst = float(np.max(diff / bound)) if got.size else 0.0
+        assert worst <= 1.0, f"{what}: error {worst:.2f} x the bound max({ABS_TOL[dtype]}, {BIG_VALUE_REL[dtype]} |y|)"
+    else:
+        assert err <= ABS_TOL[dtype], f"{what}: max-abs {err:.3e} > {ABS_TOL[dtype]}"
     assert rel <= REL_TOL[dtype], f"{what}: max-abs/rms {rel:.3e} > {REL_TOL[dtype]}"
     return err, rel
