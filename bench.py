@@ -62,6 +62,9 @@ def parse():
     ap.add_argument("--with-sa", action="store_true",
                     help="run the drafter's Self-Attention layer in front of the cross-attention (its output becomes "
                          "the CA queries); not part of the headline step")
+    ap.add_argument("--tli-layers", type=int, default=0,
+                    help="after the timed region, also time this many reused LLM decoder layers (Target Layer Inference) "
+                         "on the tree tokens, each with its own weights; reported under 'tli', not in the headline")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run three plain device copies of this many MiB (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -136,6 +139,65 @@ def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree", with_sa=Fal
         c["ca.core+verify.core"] = add(c["ca.core"], one["verify.core"])
         c["ca.o_proj+verify.o_proj"] = add(c["ca.o_proj"], one["verify.o_proj"])
     return c
+
+
+def time_tli_layers(cfg, n_layers, stream, moa, mi, reps=20):
+    """n_layers reused LLM decoder layers back to back on the tree tokens (each with its own weights and KV cache, so
+    nothing is cache-resident when it is touched again), timed as a whole and per kernel."""
+    import torch
+    from paper_2410_03804_amd.workload import shape_of
+    import numpy as np
+    dt = cfg.dtype
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+    shape = shape_of(cfg)
+    dcfg = moa.DecoderCfg(mi.tli_d_ff(cfg), 1e-5, 500000.0)
+    B, M = cfg.B, cfg.M
+    dev = lambda a, t=None: (torch.from_numpy(np.ascontiguousarray(a)).to(t) if t else torch.from_numpy(np.ascontiguousarray(a))).cuda()
+    parent = mi.trees(cfg)
+    W = (M + 63) // 64
+    mask = torch.zeros((B, M, W), dtype=torch.int64, device="cuda")
+    depth = torch.zeros((B, M), dtype=torch.int32, device="cuda")
+    moa.tree_build(dev(parent), mask, depth)
+    plen = dev(mi.prefix_lengths(cfg))
+    layers = []
+    for l in range(n_layers):
+        w = {k: dev(v, tdt) for k, v in mi.tli_weights(cfg, l).items()}
+        kc, vc = mi.kv_cache(cfg, which=20 + l)
+        layers.append((w, dev(kc, tdt), dev(vc, tdt),
+                       torch.zeros((B, cfg.Hkv, M, cfg.dh), dtype=tdt, device="cuda"),
+                       torch.zeros((B, cfg.Hkv, M, cfg.dh), dtype=tdt, device="cuda")))
+    P_cap = cfg.P_cap
+    ws = torch.empty(moa.tli_workspace_bytes(shape, dcfg, B, P_cap, M), dtype=torch.uint8, device="cuda")
+    xs = [dev(mi.verify_inputs(cfg), tdt), torch.zeros((B, M, cfg.d), dtype=tdt, device="cuda")]
+    st = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def once():
+        for l, (w, kc, vc, kd, vd) in enumerate(layers):
+            moa.tli_decoder_layer(shape, dcfg, xs[l & 1], 0, w, kc, vc, plen, P_cap, mask, depth, xs[(l + 1) & 1], kd, vd, ws, st, stream)
+
+    for _ in range(3):
+        once()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        once()
+    torch.cuda.synchronize()
+    us_layer = (time.perf_counter() - t0) * 1e6 / (reps * n_layers)
+    moa.profile_enable(True)
+    for _ in range(4):
+        once()
+    torch.cuda.synchronize()
+    rows = moa.profile_collect()
+    moa.profile_enable(False)
+    es = 2 if dt == "bf16" else 4
+    E, ekv, d, dff = cfg.H * cfg.dh, cfg.E_kv, cfg.d, mi.tli_d_ff(cfg)
+    plen_sum = float(mi.prefix_lengths(cfg).sum())
+    byt = (E * d * 2 + 2 * ekv * d + 3 * dff * d) * es + 2 * ekv * es * plen_sum + 2 * B * M * d * es
+    pieces = sorted(({"site": s_, "kernel": k_, "us_per_layer": round(ms * 1e3 / (4 * n_layers), 2)} for s_, k_, n, ms in rows),
+                    key=lambda p: -p["us_per_layer"])
+    return {"layers": n_layers, "us_per_layer": round(us_layer, 2), "alg_MiB_per_layer": round(byt / 2 ** 20, 1),
+            "gbs": round(byt / (us_layer * 1e-6) / 1e9, 1), "frac_of_hbm_peak": round(byt / (us_layer * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+            "tokens_per_s": round(B * M / (us_layer * 1e-6), 1), "pieces": pieces}
 
 
 def bound_of(bytes_, flops, peak_tflops):
@@ -259,6 +321,10 @@ def main():
                         how="plain coalesced 1 GiB read; 4096 wavefronts x 4 independent 32x32x16 bf16 MFMA chains")
         del big
 
+    tli = None
+    if args.tli_layers > 0:
+        tli = time_tli_layers(cfg, args.tli_layers, stream, moa, mi)
+
     if args.calibrate_copy_mib > 0:
         n = args.calibrate_copy_mib * (1 << 20)
         src = torch.ones(n, dtype=torch.uint8, device="cuda")
@@ -350,6 +416,7 @@ def main():
                                + ("; Self-Attention layer in front of the CA" if args.with_sa else ""),
                    "verify_layers": NL, "buffer_sets": nsets, "profile_steps": P},
         "roofline": roofline, "cpu_baseline": cpu, "ceilings": ceilings,
+        "tli": tli,
         "hot_cache": {"ms_per_step": round(hot_ms, 5), "steps": hot_steps,
                       "note": "one buffer set reused: operands stay in the Infinity Cache; not the headline"},
         "kernel_us_per_step": round(kernel_us_sum, 2), "setup_s": round(setup_s, 1), "pieces": pieces,

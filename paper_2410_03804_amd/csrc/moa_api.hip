@@ -717,10 +717,10 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     lg.seg[1].st = row_store(t.gu + (size_t)d_ff * es, 2 * (int64_t)d_ff);
     lg.ws = t.lin;
     lg.ws_bytes = t.lin_bytes;
+    lg.epi = LinArgs::EPI_SWIGLU;            // act = silu(gate) * up, by the kernel that sums the K slices when there is one
+    lg.epi_out = t.act;
     prof_set_site(S_TLI_GATE_UP);
     MOA_TRY_HIP(launch_linear(dt, lg, st), who);
-    prof_set_site(S_TLI_ACT);
-    MOA_TRY_HIP(launch_swiglu(dt, t.gu, R, d_ff, t.act, st), who);
     LinArgs ld = {};
     ld.X = t.act;
     ld.R = R;
@@ -732,10 +732,11 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     ld.seg[0].st = row_store(t.tmp, d);
     ld.ws = t.lin;
     ld.ws_bytes = t.lin_bytes;
+    ld.epi = LinArgs::EPI_ADD_F32;           // out = h1 + down projection (second residual)
+    ld.epi_res = t.h1;
+    ld.epi_out = out;
     prof_set_site(S_TLI_DOWN);
     MOA_TRY_HIP(launch_linear(dt, ld, st), who);
-    prof_set_site(S_TLI_ADD);
-    MOA_TRY_HIP(launch_add_out(dt, t.h1, t.tmp, R * d, out, st), who);
     return MOA_OK;
 }
 

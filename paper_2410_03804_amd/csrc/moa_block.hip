@@ -35,6 +35,63 @@ __global__ __launch_bounds__(256) void k_rmsnorm(const T *__restrict__ x, const 
     }
 }
 
+// bf16 rows of up to 256 * 8 * NCH values (d a multiple of 8, 16-byte aligned rows): every lane requests its
+// 16-byte pieces up front and keeps them in registers for both passes.
+template <int NCH>
+__global__ __launch_bounds__(256) void k_rmsnorm_bf16v(const bf16_t *__restrict__ x, const bf16_t *__restrict__ res, int d,
+                                                      const bf16_t *__restrict__ g, float eps, float *__restrict__ h_out,
+                                                      bf16_t *__restrict__ n_out)
+{
+    __shared__ float part[4];
+    const int64_t r = blockIdx.x;
+    const int nch = d >> 3;
+    u32x4 xv[NCH], rv[NCH], gv[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        const int cc = c < nch ? c : 0;
+        xv[i] = *(const u32x4 *)(x + r * d + 8 * cc);
+        rv[i] = res ? *(const u32x4 *)(res + r * d + 8 * cc) : u32x4{0u, 0u, 0u, 0u};
+        gv[i] = *(const u32x4 *)(g + 8 * cc);
+    }
+    float v[NCH][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const bool live = threadIdx.x + 256 * i < nch;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float lo = __uint_as_float(xv[i][e] << 16) + __uint_as_float(rv[i][e] << 16);
+            const float hi = __uint_as_float(xv[i][e] & 0xffff0000u) + __uint_as_float(rv[i][e] & 0xffff0000u);
+            v[i][2 * e] = lo;
+            v[i][2 * e + 1] = hi;
+            if (live) ss += lo * lo + hi * hi;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        if (c >= nch) continue;
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float glo = __uint_as_float(gv[i][e] << 16), ghi = __uint_as_float(gv[i][e] & 0xffff0000u);
+            o[e] = (uint32_t)f2bf(v[i][2 * e] * inv * glo) | ((uint32_t)f2bf(v[i][2 * e + 1] * inv * ghi) << 16);
+        }
+        *(u32x4 *)(n_out + r * d + 8 * c) = o;
+        if (h_out) {
+            *(f32x4 *)(h_out + r * d + 8 * c) = f32x4{v[i][0], v[i][1], v[i][2], v[i][3]};
+            *(f32x4 *)(h_out + r * d + 8 * c + 4) = f32x4{v[i][4], v[i][5], v[i][6], v[i][7]};
+        }
+    }
+}
+
 // Rotary positions, pairs (c, c + dh/2), angle = pos * theta^(-2c/dh), pos = prefix_len[b] + depth[b][node]:
 // the place the drafted token would take in its own sequence.  Queries [B*Mn, H*dh] and the new rows of the
 // draft key slabs [B, Hkv, M, dh] in place.  The angle is formed in double precision: at position 32768 a
@@ -88,7 +145,15 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *res, int64_t R, 
 {
     if (R <= 0) return hipSuccess;
     prof_begin(K_RMSNORM, stream);
-    if (dtype == DT_BF16)
+    const bool vec = dtype == DT_BF16 && d % 8 == 0 && d <= 256 * 8 * 4 &&
+                     ((((uintptr_t)x) | ((uintptr_t)res) | ((uintptr_t)g) | ((uintptr_t)n_out) | ((uintptr_t)h_out)) & 15) == 0;
+    if (vec && d <= 256 * 8 * 2)
+        MOA_KLAUNCH(k_rmsnorm_bf16v<2>, dim3((unsigned)R), dim3(256), 0, stream, (const bf16_t *)x, (const bf16_t *)res, d,
+                    (const bf16_t *)g, eps, h_out, (bf16_t *)n_out);
+    else if (vec)
+        MOA_KLAUNCH(k_rmsnorm_bf16v<4>, dim3((unsigned)R), dim3(256), 0, stream, (const bf16_t *)x, (const bf16_t *)res, d,
+                    (const bf16_t *)g, eps, h_out, (bf16_t *)n_out);
+    else if (dtype == DT_BF16)
         MOA_KLAUNCH(k_rmsnorm<bf16_t>, dim3((unsigned)R), dim3(256), 0, stream, (const bf16_t *)x, (const bf16_t *)res, d,
                     (const bf16_t *)g, eps, h_out, (bf16_t *)n_out);
     else

@@ -144,6 +144,15 @@ struct LinArgs {
     size_t ws_bytes;
     StepSmallArgs rider;   // optional: integer work carried in rider_units spare workgroups of the projection's grid
     int rider_units;       // 0 = none; the work is done when the projection kernel has finished
+    // Optional row-wise step on the projection's result.  Where partial sums are added up by a second kernel that
+    // kernel does it and the projected values themselves are never stored; on the other paths the projection is
+    // stored as its segments say and a small kernel follows.
+    //  EPI_ADD_F32: one segment; epi_out[r, n] = epi_res[r, n] + y[r, n]   (row length N)
+    //  EPI_SWIGLU : two segments of equal N stored side by side in one row of 2N; epi_out[r, j] = silu(y0[r, j]) * y1[r, j]
+    enum { EPI_NONE = 0, EPI_ADD_F32 = 1, EPI_SWIGLU = 2 };
+    int epi;
+    const float *epi_res;
+    void *epi_out;
 };
 
 // Y_s = X_s W_s^T for up to four weight matrices (one launch on the fast paths; segments usually share X).

@@ -260,21 +260,10 @@ __global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
 }
 
 // one thread per (row, 8 consecutive features): sum the K slices in order, round once, store
-__global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
+__device__ __forceinline__ void splitk_sum8(const SplitKArgs &sa, const float *p, f32x4 &lo, f32x4 &hi)
 {
-    const LinArgs &a = sa.a;
-    const int per = sa.ntot / 8;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= a.R * per) return;
-    const int64_t r = idx / per;
-    const int nt = (int)(idx - r * per) * 8;          // feature in the concatenated space
-    const int tile = nt >> 6;
-    int s = 0;
-    while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
-    const int n = nt - sa.tile_begin[s] * 64;
-    const int64_t rt = r >> 6, rr = r & 63;
-    const float *p = sa.part + (rt * sa.splits * 64 + rr) * sa.ntot + nt;
-    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+    lo = f32x4{0.f, 0.f, 0.f, 0.f};
+    hi = f32x4{0.f, 0.f, 0.f, 0.f};
     const int64_t stride = (int64_t)64 * sa.ntot;
     int k = 0;
     for (; k + 8 <= sa.splits; k += 8) {        // eight slices in flight, summed in slice order
@@ -288,14 +277,62 @@ __global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
         lo += *(const f32x4 *)(p + k * stride);
         hi += *(const f32x4 *)(p + k * stride + 4);
     }
-    const int64_t off = store_offset(a.seg[s].st, r, n);
-    if (off < 0) return;
+}
+
+__device__ __forceinline__ u32x4 pack8(const f32x4 &lo, const f32x4 &hi)
+{
     u32x4 pk;
     pk[0] = (uint32_t)f2bf(lo[0]) | ((uint32_t)f2bf(lo[1]) << 16);
     pk[1] = (uint32_t)f2bf(lo[2]) | ((uint32_t)f2bf(lo[3]) << 16);
     pk[2] = (uint32_t)f2bf(hi[0]) | ((uint32_t)f2bf(hi[1]) << 16);
     pk[3] = (uint32_t)f2bf(hi[2]) | ((uint32_t)f2bf(hi[3]) << 16);
-    *(u32x4 *)((bf16_t *)a.seg[s].st.dst + off) = pk;
+    return pk;
+}
+
+__global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
+{
+    const LinArgs &a = sa.a;
+    const int width = a.epi == LinArgs::EPI_SWIGLU ? sa.ntot / 2 : sa.ntot;   // features a row of threads walks
+    const int per = width / 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.R * per) return;
+    const int64_t r = idx / per;
+    const int nt = (int)(idx - r * per) * 8;          // feature in the concatenated space
+    const int64_t rt = r >> 6, rr = r & 63;
+    const float *p = sa.part + (rt * sa.splits * 64 + rr) * sa.ntot + nt;
+    f32x4 lo, hi;
+    splitk_sum8(sa, p, lo, hi);
+    if (a.epi == LinArgs::EPI_SWIGLU) {              // gate in the first half of the row, up in the second
+        f32x4 ulo, uhi;
+        splitk_sum8(sa, p + width, ulo, uhi);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            // the gate goes through the storage type, as it does when the projection is stored first
+            const float gl = bf2f(f2bf(lo[e])), gh = bf2f(f2bf(hi[e]));
+            lo[e] = gl / (1.0f + __expf(-gl)) * bf2f(f2bf(ulo[e]));
+            hi[e] = gh / (1.0f + __expf(-gh)) * bf2f(f2bf(uhi[e]));
+        }
+        *(u32x4 *)((bf16_t *)a.epi_out + r * width + nt) = pack8(lo, hi);
+        return;
+    }
+    if (a.epi == LinArgs::EPI_ADD_F32) {
+        const float *h = a.epi_res + r * width + nt;
+        const f32x4 h0 = *(const f32x4 *)h, h1 = *(const f32x4 *)(h + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            lo[e] = h0[e] + bf2f(f2bf(lo[e]));
+            hi[e] = h1[e] + bf2f(f2bf(hi[e]));
+        }
+        *(u32x4 *)((bf16_t *)a.epi_out + r * width + nt) = pack8(lo, hi);
+        return;
+    }
+    const int tile = nt >> 6;
+    int s = 0;
+    while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
+    const int n = nt - sa.tile_begin[s] * 64;
+    const int64_t off = store_offset(a.seg[s].st, r, n);
+    if (off < 0) return;
+    *(u32x4 *)((bf16_t *)a.seg[s].st.dst + off) = pack8(lo, hi);
 }
 
 // The weight-streaming kernel walks 64-row tiles with the weights in registers.  Its fp32 partial sums are
@@ -308,8 +345,11 @@ constexpr int64_t SPLITK_MAX_ROWS_WIDE = 192;
 
 static int splitk_nq(int K)
 {
-    for (int nq = 1; nq <= 8; nq *= 2)
+    for (int nq = 1; nq <= 4; nq *= 2)
         if (K % (128 * nq) == 0 && K / (128 * nq) <= 8) return nq;
+    // long rows: 512-wide slices keep two workgroups per CU (1024-wide ones need 132 KB of LDS); the partial sums
+    // are a quarter of the weights per row tile, whatever the number of slices
+    if (K % 512 == 0) return 4;
     return (K % 1024 == 0) ? 8 : 0;
 }
 
@@ -501,7 +541,7 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
 // ------------------------------------------------------------------ dispatch
 static bool aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 
-static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode);
+static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode, bool *fused);
 
 // kernels without per-segment activation support get one call per segment
 static hipError_t launch_linear_each(int dtype, const LinArgs &a, hipStream_t stream)
@@ -513,17 +553,19 @@ static hipError_t launch_linear_each(int dtype, const LinArgs &a, hipStream_t st
         one.seg[0] = a.seg[s];
         if (a.seg[s].X) { one.X = a.seg[s].X; one.ldx = a.seg[s].ldx; }
         one.seg[0].X = nullptr;
-        bool rode = false;
-        hipError_t e = launch_linear_impl(dtype, one, stream, &rode);
+        one.epi = LinArgs::EPI_NONE;
+        bool rode = false, fused = false;
+        hipError_t e = launch_linear_impl(dtype, one, stream, &rode, &fused);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-// *rode is set when the launch carried a.rider in its grid
-static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode)
+// *rode is set when the launch carried a.rider in its grid, *fused when it applied a.epi
+static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode, bool *fused)
 {
     *rode = false;
+    *fused = false;
     if (a.R <= 0) return hipSuccess;
     bool own_x = false;
     for (int s = 0; s < a.nseg; ++s) own_x = own_x || a.seg[s].X != nullptr;
@@ -581,7 +623,8 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
             if (e != hipSuccess) return e;
             e = hipGetLastError();
             if (e != hipSuccess) return e;
-            const int64_t items = a.R * (ntot / 8);
+            const int64_t items = a.R * ((a.epi == LinArgs::EPI_SWIGLU ? ntot / 2 : ntot) / 8);
+            *fused = a.epi != LinArgs::EPI_NONE;
             prof_begin(K_LIN_REDUCE, stream);
             MOA_KLAUNCH(k_linear_splitk_reduce, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, ka);
             prof_end(stream);
@@ -614,9 +657,17 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
 
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
 {
-    bool rode = false;
-    hipError_t e = launch_linear_impl(dtype, a, stream, &rode);
-    if (e != hipSuccess || a.rider_units <= 0 || rode) return e;
+    if (a.epi == LinArgs::EPI_ADD_F32 && a.nseg != 1) return hipErrorInvalidValue;
+    if (a.epi == LinArgs::EPI_SWIGLU && (a.nseg != 2 || a.seg[0].N != a.seg[1].N)) return hipErrorInvalidValue;
+    bool rode = false, fused = false;
+    hipError_t e = launch_linear_impl(dtype, a, stream, &rode, &fused);
+    if (e != hipSuccess) return e;
+    if (a.epi != LinArgs::EPI_NONE && !fused) {     // the projection was stored as its segments say: finish row-wise
+        if (a.epi == LinArgs::EPI_SWIGLU) e = launch_swiglu(dtype, a.seg[0].st.dst, a.R, a.seg[0].N, a.epi_out, stream);
+        else e = launch_add_out(dtype, a.epi_res, a.seg[0].st.dst, a.R * a.seg[0].N, a.epi_out, stream);
+        if (e != hipSuccess) return e;
+    }
+    if (a.rider_units <= 0 || rode) return hipSuccess;
     return launch_step_small(a.rider, stream);      // the kernel that ran has no spare workgroups for it
 }
 
