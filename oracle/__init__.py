@@ -204,6 +204,48 @@ def tli_decoder_layer(x, parent, node0, w, kcache, vcache, prefix_len, k_draft, 
     return out
 
 
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def tree_expand_level(level, child_logp, child_tok, cand_logp, cand_tok, cand_parent, frontier):
+    """One level of the draft-tree construction for ONE sequence; the cand_* arrays (float32 / int32, length
+    >= Bw + (D-1) Bw^2) and frontier (int32 [Bw]) are updated in place."""
+    child_logp, child_tok = _f32(child_logp), _i32(child_tok)
+    Bw = child_logp.shape[-1]
+    for a, t in ((cand_logp, np.float32), (cand_tok, np.int32), (cand_parent, np.int32), (frontier, np.int32)):
+        if a.dtype != t or not a.flags.c_contiguous:
+            raise ValueError("state arrays must be C-contiguous float32 / int32")
+    rc = lib().moa_ref_tree_expand_level(int(level), Bw, _p(child_logp, C.c_float), _p(child_tok, C.c_int32),
+                                         _p(cand_logp, C.c_float), _p(cand_tok, C.c_int32),
+                                         _p(cand_parent, C.c_int32), _p(frontier, C.c_int32))
+    _check(rc, "tree_expand_level")
+
+
+def tree_finalize(n_cand, m, root_tok, cand_logp, cand_tok, cand_parent):
+    """-> parent [M], tok [M], node_cand [M] of the kept tree (root first), M = 1 + min(m, n_cand)."""
+    cand_logp, cand_tok, cand_parent = _f32(cand_logp), _i32(cand_tok), _i32(cand_parent)
+    parent = np.full(1 + m, -9, dtype=np.int32)
+    tok = np.full(1 + m, -9, dtype=np.int32)
+    node_cand = np.full(1 + m, -9, dtype=np.int32)
+    M = C.c_int32(0)
+    rc = lib().moa_ref_tree_finalize(int(n_cand), int(m), int(root_tok), _p(cand_logp, C.c_float), _p(cand_tok, C.c_int32),
+                                     _p(cand_parent, C.c_int32), _p(parent, C.c_int32), _p(tok, C.c_int32),
+                                     _p(node_cand, C.c_int32), C.byref(M))
+    _check(rc, "tree_finalize")
+    return parent[:M.value], tok[:M.value], node_cand[:M.value]
+
+
+def topk_logprob(logits, Bw):
+    """-> tok [F, Bw] int32, logp [F, Bw] float64: the Bw most probable tokens of each row and their log-probabilities."""
+    logits = _f64(logits)
+    F, V = logits.shape
+    tok = np.empty((F, Bw), dtype=np.int32)
+    logp = np.empty((F, Bw), dtype=np.float64)
+    _check(lib().moa_ref_topk_logprob(_p(logits), F, V, int(Bw), _p(tok, C.c_int32), _p(logp)), "topk_logprob")
+    return tok, logp
+
+
 def tree_accept(parent, tok, tgt):
     parent, tok, tgt = _i32(parent), _i32(tok), _i32(tgt)
     B, M = parent.shape

@@ -478,6 +478,114 @@ int moa_ref_tli_decoder_layer(const double *x, int B, int M, int node0, int Mn, 
     return MOA_REF_OK;
 }
 
+/* ------------------------------------------------------------ draft-tree construction */
+
+/* a ranks before b: larger joint log-probability, then lower index */
+static int cand_before(const float *lp, int a, int b)
+{
+    if (lp[a] != lp[b]) return lp[a] > lp[b];
+    return a < b;
+}
+
+int moa_ref_tree_expand_level(int level, int Bw, const float *child_logp, const int32_t *child_tok,
+                              float *cand_logp, int32_t *cand_tok, int32_t *cand_parent, int32_t *frontier)
+{
+    if (level < 1 || Bw < 1 || !child_logp || !child_tok || !cand_logp || !cand_tok || !cand_parent || !frontier)
+        return MOA_REF_BAD_ARG;
+    const int F = level == 1 ? 1 : Bw;
+    const int base = level == 1 ? 0 : Bw + (level - 2) * Bw * Bw;
+    const int n = F * Bw;
+    for (int f = 0; f < F; ++f)
+        for (int j = 0; j < Bw; ++j) {
+            const int c = base + f * Bw + j;
+            float lp = child_logp[f * Bw + j];
+            if (lp > 0.0f) lp = 0.0f;
+            if (level == 1) {
+                cand_logp[c] = lp;
+                cand_parent[c] = -1;
+            } else {
+                cand_logp[c] = cand_logp[frontier[f]] + lp;      /* one single-precision addition */
+                cand_parent[c] = frontier[f];
+            }
+            cand_tok[c] = child_tok[f * Bw + j];
+        }
+    /* the Bw best of this level's expansions, best first (all of them at level 1) */
+    int32_t *next = (int32_t *)malloc(sizeof(int32_t) * (size_t)Bw);
+    if (!next) return MOA_REF_BAD_ARG;
+    const int keep = n < Bw ? n : Bw;
+    for (int r = 0; r < keep; ++r) {
+        int best = -1;
+        for (int c = base; c < base + n; ++c) {
+            int taken = 0;
+            for (int q = 0; q < r; ++q) if (next[q] == c) taken = 1;
+            if (taken) continue;
+            if (best < 0 || cand_before(cand_logp, c, best)) best = c;
+        }
+        next[r] = best;
+    }
+    for (int r = 0; r < keep; ++r) frontier[r] = next[r];
+    free(next);
+    return MOA_REF_OK;
+}
+
+int moa_ref_tree_finalize(int n_cand, int m, int32_t root_tok, const float *cand_logp, const int32_t *cand_tok,
+                          const int32_t *cand_parent, int32_t *parent, int32_t *tok, int32_t *node_cand,
+                          int32_t *M_out)
+{
+    if (n_cand < 0 || m < 0 || !parent || !tok || !node_cand || !M_out) return MOA_REF_BAD_ARG;
+    if (n_cand > 0 && (!cand_logp || !cand_tok || !cand_parent)) return MOA_REF_BAD_ARG;
+    const int keep = m < n_cand ? m : n_cand;
+    /* rank of every candidate = how many rank before it */
+    int32_t *node_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_cand > 0 ? n_cand : 1));
+    if (!node_of) return MOA_REF_BAD_ARG;
+    int M = 1;
+    parent[0] = -1;
+    tok[0] = root_tok;
+    node_cand[0] = -1;
+    for (int c = 0; c < n_cand; ++c) {
+        int rank = 0;
+        for (int u = 0; u < n_cand; ++u) if (u != c && cand_before(cand_logp, u, c)) ++rank;
+        node_of[c] = -1;
+        if (rank < keep) {                            /* kept; candidate order is node order */
+            const int p = cand_parent[c];
+            if (p >= c || (p >= 0 && node_of[p] < 0)) { free(node_of); return MOA_REF_BAD_TREE; }
+            node_of[c] = M;
+            parent[M] = p < 0 ? 0 : node_of[p];
+            tok[M] = cand_tok[c];
+            node_cand[M] = c;
+            ++M;
+        }
+    }
+    *M_out = M;
+    free(node_of);
+    return MOA_REF_OK;
+}
+
+int moa_ref_topk_logprob(const double *logits, int F, int V, int Bw, int32_t *tok, double *logp)
+{
+    if (!logits || !tok || !logp || F < 1 || V < 1 || Bw < 1 || Bw > V) return MOA_REF_BAD_ARG;
+    for (int f = 0; f < F; ++f) {
+        const double *row = logits + (int64_t)f * V;
+        double mx = row[0];
+        for (int v = 1; v < V; ++v) if (row[v] > mx) mx = row[v];
+        double den = 0.0;
+        for (int v = 0; v < V; ++v) den += exp(row[v] - mx);
+        const double lse = mx + log(den);
+        for (int r = 0; r < Bw; ++r) {
+            int best = -1;
+            for (int v = 0; v < V; ++v) {
+                int taken = 0;
+                for (int q = 0; q < r; ++q) if (tok[f * Bw + q] == v) taken = 1;
+                if (taken) continue;
+                if (best < 0 || row[v] > row[best]) best = v;      /* strict: the lower id wins a tie */
+            }
+            tok[f * Bw + r] = best;
+            logp[f * Bw + r] = row[best] - lse;
+        }
+    }
+    return MOA_REF_OK;
+}
+
 /* ------------------------------------------------------------ tree verify */
 
 int moa_ref_tree_verify_attn(const double *x, int B, int M, int d, int H, int Hkv, int dh,

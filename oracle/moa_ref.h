@@ -133,6 +133,37 @@ int moa_ref_tli_decoder_layer(const double *x /*[B,Mn,d]*/, int B, int M, int no
 /* Rotary position embedding of one head vector in place (the convention above). */
 void moa_ref_rope(double *v /*[dh]*/, int dh, double pos, double theta);
 
+/* ---- draft-tree construction (Sec. 2.2, tree drafting as in EAGLE-2: from the root the Bw most
+ * probable tokens; then, level by level, each of the Bw current branches proposes its Bw most probable
+ * children, the Bw*Bw expansions are ranked by joint probability and the best Bw become the branches of
+ * the next level; at the end the m most probable of all Bw + (D-1) Bw^2 candidates are kept).
+ * Joint probabilities are sums of log-probabilities in SINGLE precision (one addition per candidate), so
+ * that a device implementation takes every ranking decision on identical numbers.  Ties: lower candidate
+ * index first.  Candidates are numbered level by level: level 1 -> 0..Bw-1, level l >= 2 ->
+ * Bw + (l-2) Bw^2 + f*Bw + j for child j of the f-th branch.  Per sequence:
+ *   cand_logp/tok/parent [n_max]  (parent = candidate index, -1 for children of the root)
+ *   frontier [Bw] = candidate indices of the current branches, best first. */
+
+/* One level.  level == 1: child_logp/tok hold one row (the root's children); level >= 2: Bw rows,
+ * row f = children of frontier[f].  Log-probabilities above 0 are taken as 0. */
+int moa_ref_tree_expand_level(int level, int Bw, const float *child_logp /*[F,Bw]*/,
+                              const int32_t *child_tok /*[F,Bw]*/, float *cand_logp, int32_t *cand_tok,
+                              int32_t *cand_parent, int32_t *frontier /*[Bw] in/out*/);
+
+/* Keep the m best of the first n_cand candidates; nodes are the root (token root_tok) followed by the
+ * kept candidates in candidate order (which is depth order).  Writes parent[] (node indices, -1 for the
+ * root), tok[], node_cand[] (candidate index of each node, -1 for the root) for M = 1 + min(m, n_cand)
+ * nodes and returns M in *M_out.  A kept candidate's parent is always kept (its joint probability is not
+ * smaller and its index is lower). */
+int moa_ref_tree_finalize(int n_cand, int m, int32_t root_tok, const float *cand_logp,
+                          const int32_t *cand_tok, const int32_t *cand_parent,
+                          int32_t *parent /*[1+m]*/, int32_t *tok, int32_t *node_cand, int32_t *M_out);
+
+/* The Bw most probable tokens of each row of logits with their log-probabilities
+ * logit - logsumexp(row) (fp64 here).  Ties: lower token id first. */
+int moa_ref_topk_logprob(const double *logits /*[F,V]*/, int F, int V, int Bw,
+                         int32_t *tok /*[F,Bw]*/, double *logp /*[F,Bw]*/);
+
 /* Greedy acceptance (Sec. 2.2: everything after the first mismatch is dropped).
  * tok[i] is the token drafted at node i; tgt[i] is the LLM's greedy token after
  * node i.  Walk from the root to the lowest-index child whose token equals the
