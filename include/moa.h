@@ -196,6 +196,40 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
                               const int32_t *depth, void *out, void *k_draft, void *v_draft,
                               int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
 
+/* Draft-tree construction on the device (Sec. 2.2, tree drafting as in EAGLE-2: from the root the Bw
+ * most probable tokens; then, level by level, each of the Bw current branches proposes its Bw most
+ * probable children, the Bw*Bw expansions are ranked by joint probability and the best Bw become the
+ * branches of the next level; at the end the m most probable of all Bw + (D-1) Bw^2 candidates are
+ * kept for verification).  Joint probabilities are sums of log-probabilities in single precision, one
+ * addition per candidate; ties go to the lower candidate index; a log-probability above 0 counts as 0
+ * and NaN as -inf, so a child is never ranked before its parent and the kept set is always a tree.
+ * Candidates are numbered level by level: level 1 -> 0..Bw-1; level l >= 2 -> Bw + (l-2) Bw^2 + f Bw + j
+ * for child j of the f-th branch.  State per sequence b (device, caller-owned, row length n_max >=
+ * Bw + (D-1) Bw^2): cand_logp (fp32), cand_tok, cand_parent (candidate index, -1 = child of the root),
+ * and frontier [B, Bw] = candidate indices of the current branches, best first.
+ * moa_tree_expand_level: child_logp / child_tok [B, F, Bw] with F = 1 at level 1 (the root's children)
+ *   and F = Bw above (row f = children of frontier[f]); writes the level's candidates and the new
+ *   frontier.  1 <= Bw <= 16.  MOA_ERR_RANGE if the level does not fit n_max.
+ * moa_tree_finalize: of the first n_cand candidates (<= 4096) keeps the min(m, n_cand) best; node 0 is
+ *   the root (token root_tok[b]), the kept candidates follow in candidate order, which is depth order.
+ *   Writes parent / tok / node_cand [B, 1+m] (node_cand = candidate index of the node, -1 for the
+ *   root); rows have M = 1 + min(m, n_cand) valid entries, 1 + m <= MOA_MAX_TREE.  parent[] is exactly
+ *   what moa_tree_build takes.  If the candidate arrays were not written by moa_tree_expand_level and a
+ *   kept candidate's parent is not kept, the node hangs off the root and MOA_DEV_BAD_PARENT is set.
+ * moa_topk_logprob: the Bw most probable tokens of each row of logits [F, V] (dtype MOA_F32 or
+ *   MOA_BF16) with log-probabilities logit - logsumexp(row) in fp32; ties go to the lower token id.
+ *   tok, logp [F, Bw]: the child_tok / child_logp of the next moa_tree_expand_level. */
+int32_t moa_tree_expand_level(int32_t level, int32_t B, int32_t Bw, int32_t n_max,
+                              const float *child_logp, const int32_t *child_tok,
+                              float *cand_logp, int32_t *cand_tok, int32_t *cand_parent,
+                              int32_t *frontier, void *stream);
+int32_t moa_tree_finalize(int32_t B, int32_t n_cand, int32_t n_max, int32_t m, const int32_t *root_tok,
+                          const float *cand_logp, const int32_t *cand_tok, const int32_t *cand_parent,
+                          int32_t *parent, int32_t *tok, int32_t *node_cand, int32_t *dev_status,
+                          void *stream);
+int32_t moa_topk_logprob(int32_t dtype, const void *logits, int32_t F, int32_t V, int32_t Bw,
+                         int32_t *tok, float *logp, void *stream);
+
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
  * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk;

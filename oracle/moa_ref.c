@@ -499,6 +499,7 @@ int moa_ref_tree_expand_level(int level, int Bw, const float *child_logp, const 
         for (int j = 0; j < Bw; ++j) {
             const int c = base + f * Bw + j;
             float lp = child_logp[f * Bw + j];
+            if (!(lp == lp)) lp = -INFINITY;                     /* NaN counts as impossible */
             if (lp > 0.0f) lp = 0.0f;
             if (level == 1) {
                 cand_logp[c] = lp;

@@ -145,7 +145,7 @@ void moa_ref_rope(double *v /*[dh]*/, int dh, double pos, double theta);
  *   frontier [Bw] = candidate indices of the current branches, best first. */
 
 /* One level.  level == 1: child_logp/tok hold one row (the root's children); level >= 2: Bw rows,
- * row f = children of frontier[f].  Log-probabilities above 0 are taken as 0. */
+ * row f = children of frontier[f].  Log-probabilities above 0 are taken as 0, NaN as -inf. */
 int moa_ref_tree_expand_level(int level, int Bw, const float *child_logp /*[F,Bw]*/,
                               const int32_t *child_tok /*[F,Bw]*/, float *cand_logp, int32_t *cand_tok,
                               int32_t *cand_parent, int32_t *frontier /*[Bw] in/out*/);

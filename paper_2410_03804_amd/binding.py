@@ -68,7 +68,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
-            "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -96,7 +96,10 @@ class DecoderCfg(C.Structure):
 _lib.moa_tli_workspace_bytes.argtypes = [C.POINTER(Shape), C.POINTER(DecoderCfg), _i32, _i32, _i32, C.POINTER(_sz)]
 _lib.moa_tli_decoder_layer.argtypes = [C.POINTER(Shape), C.POINTER(DecoderCfg), _vp, _i32, _i32, _i32, _i32] + [_vp] * 11 + [
     _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
-for _n in _SYMBOLS[2:13]:
+_lib.moa_tree_expand_level.argtypes = [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.moa_tree_finalize.argtypes = [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.moa_topk_logprob.argtypes = [_i32, _vp, _i32, _i32, _i32, _vp, _vp, _vp]
+for _n in _SYMBOLS[2:16]:
     getattr(_lib, _n).restype = C.c_int32
 
 
@@ -297,6 +300,37 @@ def tli_decoder_layer(shape: Shape, cfg: DecoderCfg, x, node_begin, w, kcache, v
         _dev(depth, torch.int32, B * M, "depth"), _dev(out, dt, B * Mn * d, "out"),
         _dev(k_draft, dt, B * ekv * M, "k_draft"), _dev(v_draft, dt, B * ekv * M, "v_draft"),
         _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
+
+
+def tree_expand_level(level, child_logp, child_tok, cand_logp, cand_tok, cand_parent, frontier, stream=None):
+    """One level of the draft-tree construction: child_logp (fp32) / child_tok (int32) [B, F, Bw]; the state tensors
+    cand_logp (fp32), cand_tok, cand_parent [B, n_max] and frontier [B, Bw] (int32) are updated in place."""
+    B, F, Bw = child_logp.shape
+    n_max = cand_logp.shape[1]
+    f32, i32 = torch.float32, torch.int32
+    _check(_lib.moa_tree_expand_level(int(level), B, Bw, n_max, _dev(child_logp, f32, B * F * Bw, "child_logp"),
+                                      _dev(child_tok, i32, B * F * Bw, "child_tok"), _dev(cand_logp, f32, B * n_max, "cand_logp"),
+                                      _dev(cand_tok, i32, B * n_max, "cand_tok"), _dev(cand_parent, i32, B * n_max, "cand_parent"),
+                                      _dev(frontier, i32, B * Bw, "frontier"), _stream(stream)))
+
+
+def tree_finalize(n_cand, m, root_tok, cand_logp, cand_tok, cand_parent, parent, tok, node_cand, dev_status=None, stream=None):
+    """Keep the m best candidates: parent / tok / node_cand [B, 1+m] (int32) receive the tree, root first."""
+    B, n_max = cand_logp.shape
+    f32, i32 = torch.float32, torch.int32
+    _check(_lib.moa_tree_finalize(B, int(n_cand), n_max, int(m), _dev(root_tok, i32, B, "root_tok"),
+                                  _dev(cand_logp, f32, B * n_max, "cand_logp"), _dev(cand_tok, i32, B * n_max, "cand_tok"),
+                                  _dev(cand_parent, i32, B * n_max, "cand_parent"), _dev(parent, i32, B * (1 + m), "parent"),
+                                  _dev(tok, i32, B * (1 + m), "tok"), _dev(node_cand, i32, B * (1 + m), "node_cand"),
+                                  _dev(dev_status, i32, 1, "dev_status"), _stream(stream)))
+
+
+def topk_logprob(logits, Bw, tok, logp, stream=None):
+    """The Bw most probable tokens of each row of logits [F, V] (fp32 or bf16) -> tok (int32), logp (fp32) [F, Bw]."""
+    F, V = logits.shape
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[logits.dtype]
+    _check(_lib.moa_topk_logprob(dtype, _dev(logits, logits.dtype, F * V, "logits"), F, V, int(Bw),
+                                 _dev(tok, torch.int32, F * Bw, "tok"), _dev(logp, torch.float32, F * Bw, "logp"), _stream(stream)))
 
 
 def _ptr_array(tensors, dtype, numel, name):

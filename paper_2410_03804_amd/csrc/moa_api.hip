@@ -24,6 +24,15 @@ int32_t fail(int32_t code, const char *fmt, ...)
     return code;
 }
 
+}  // namespace
+
+// the same error record for entry points that live in other files
+namespace moa {
+int32_t api_fail(int32_t code, const char *msg) { return fail(code, "%s", msg); }
+}  // namespace moa
+
+namespace {
+
 int32_t hip_fail(hipError_t e, const char *where)
 {
     return fail(MOA_ERR_HIP, "%s: %s", where, hipGetErrorString(e));

@@ -1,0 +1,246 @@
+// Draft-tree construction on the device (Sec. 2.2, tree drafting as in EAGLE-2): per level, the joint
+// log-probabilities of the Bw*Bw expansions and the best Bw of them; at the end the m best of all candidates,
+// relabelled so that parents come first; and the Bw most probable tokens of a row of logits.
+// Every ranking decision is taken on single-precision numbers formed by one addition, ties to the lower index,
+// so results are a pure function of the inputs.  These are latency-sized kernels: one workgroup per sequence
+// (or per row of logits), everything in LDS / registers.
+#include "moa_common.h"
+#include "../../include/moa.h"
+
+namespace moa {
+
+constexpr int TREE_MAX_BREADTH = 16;      // Bw*Bw expansions fit one 256-thread workgroup
+constexpr int TREE_MAX_CAND = 4096;       // candidates ranked in LDS by moa_tree_finalize
+
+__device__ __forceinline__ bool ranks_before(float a, int ia, float b, int ib) { return a > b || (a == b && ia < ib); }
+
+__global__ __launch_bounds__(256) void k_tree_expand(int level, int Bw, int n_max, const float *__restrict__ child_logp,
+                                                     const int32_t *__restrict__ child_tok, float *__restrict__ cand_logp,
+                                                     int32_t *__restrict__ cand_tok, int32_t *__restrict__ cand_parent,
+                                                     int32_t *__restrict__ frontier)
+{
+    __shared__ float lp[256];
+    const int b = blockIdx.x, t = threadIdx.x;
+    const int F = level == 1 ? 1 : Bw, n = F * Bw;
+    const int base = level == 1 ? 0 : Bw + (level - 2) * Bw * Bw;
+    float *clp = cand_logp + (int64_t)b * n_max;
+    int32_t *ctk = cand_tok + (int64_t)b * n_max, *cpr = cand_parent + (int64_t)b * n_max, *fr = frontier + (int64_t)b * Bw;
+    float mine = 0.f;
+    if (t < n) {
+        const int f = t / Bw;
+        float v = child_logp[(int64_t)b * n + t];
+        v = v == v ? fminf(v, 0.0f) : -INFINITY;          // a child is never more likely than its parent
+        int par = -1;
+        if (level > 1) {
+            par = fr[f];
+            par = par < 0 ? 0 : (par >= base ? base - 1 : par);      // a corrupt frontier cannot leave the array
+            v = clp[par] + v;                                        // one single-precision addition
+        }
+        clp[base + t] = v;
+        ctk[base + t] = child_tok[(int64_t)b * n + t];
+        cpr[base + t] = par;
+        lp[t] = v;
+        mine = v;
+    }
+    __syncthreads();                                       // every read of the old frontier is done
+    if (t < n) {
+        int rank = 0;
+        for (int u = 0; u < n; ++u) rank += ranks_before(lp[u], u, mine, t) ? 1 : 0;
+        if (rank < Bw) fr[rank] = base + t;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int keep, int ld_out, const int32_t *__restrict__ root_tok,
+                                                       const float *__restrict__ cand_logp, const int32_t *__restrict__ cand_tok,
+                                                       const int32_t *__restrict__ cand_parent, int32_t *__restrict__ parent,
+                                                       int32_t *__restrict__ tok, int32_t *__restrict__ node_cand,
+                                                       int32_t *dev_status)
+{
+    __shared__ float lp[TREE_MAX_CAND];
+    __shared__ int32_t node_of[TREE_MAX_CAND];
+    __shared__ int32_t cnt[256];
+    const int b = blockIdx.x, t = threadIdx.x;
+    const float *clp = cand_logp + (int64_t)b * n_max;
+    const int32_t *ctk = cand_tok + (int64_t)b * n_max, *cpr = cand_parent + (int64_t)b * n_max;
+    int32_t *po = parent + (int64_t)b * ld_out, *to = tok + (int64_t)b * ld_out, *no = node_cand + (int64_t)b * ld_out;
+    for (int c = t; c < n; c += 256) {
+        const float v = clp[c];
+        lp[c] = v == v ? v : -INFINITY;
+    }
+    __syncthreads();
+    // each thread owns a run of consecutive candidates, so that node numbers follow candidate order
+    const int per = (n + 255) / 256, c0 = t * per, c1 = min(c0 + per, n);
+    int kept = 0;
+    for (int c = c0; c < c1; ++c) {
+        const float v = lp[c];
+        int rank = 0;
+        for (int u = 0; u < n; ++u) rank += ranks_before(lp[u], u, v, c) ? 1 : 0;
+        const bool k = rank < keep;
+        node_of[c] = k ? 1 : 0;
+        kept += k ? 1 : 0;
+    }
+    cnt[t] = kept;
+    __syncthreads();
+    if (t == 0) {                                          // 256 counts: a serial scan is a few hundred cycles
+        int run = 1;                                       // node 0 is the root
+        for (int i = 0; i < 256; ++i) { const int k = cnt[i]; cnt[i] = run; run += k; }
+        po[0] = -1;
+        to[0] = root_tok[b];
+        no[0] = -1;
+    }
+    __syncthreads();
+    int next = cnt[t];
+    for (int c = c0; c < c1; ++c) node_of[c] = node_of[c] ? next++ : -1;
+    __syncthreads();
+    for (int c = c0; c < c1; ++c) {
+        const int i = node_of[c];
+        if (i < 0) continue;
+        const int p = cpr[c];
+        int pn = 0;
+        if (p >= 0) {
+            pn = (p < c) ? node_of[p] : -1;
+            if (pn < 0) {                                  // cannot happen with arrays written by k_tree_expand
+                pn = 0;
+                if (dev_status) atomicOr(dev_status, MOA_DEV_BAD_PARENT);
+            }
+        }
+        po[i] = pn;
+        to[i] = ctk[c];
+        no[i] = c;
+    }
+}
+
+// ---- the Bw most probable tokens of a row of logits, with log-probabilities
+template <typename T> __device__ __forceinline__ float logit_at(const T *row, int v) { return ld<T>(row + v); }
+
+__global__ __launch_bounds__(256) void k_topk_logprob_f32_or_bf16(int is_bf16, const void *__restrict__ logits, int V, int Bw,
+                                                                  int32_t *__restrict__ tok, float *__restrict__ logp)
+{
+    constexpr int KMAX = TREE_MAX_BREADTH;
+    __shared__ float wv[4];
+    __shared__ int wi[4], wt[4];
+    __shared__ float red_m[4], red_s[4];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int64_t r = blockIdx.x;
+    const float *rf = (const float *)logits + r * V;
+    const bf16_t *rb = (const bf16_t *)logits + r * V;
+    float val[KMAX];
+    int id[KMAX];
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) { val[k] = -INFINITY; id[k] = 0x7fffffff; }
+    float m = -INFINITY, s = 0.f;
+    for (int v = t; v < V; v += 256) {                     // ids grow within a thread: an equal value never overtakes
+        const float x = is_bf16 ? bf2f(rb[v]) : rf[v];
+        if (x > m) { s = s * __expf(m - x) + 1.0f; m = x; }
+        else s += __expf(x - m);
+        if (x > val[KMAX - 1]) {
+            val[KMAX - 1] = x;
+            id[KMAX - 1] = v;
+#pragma unroll
+            for (int k = KMAX - 1; k > 0; --k) {
+                if (val[k] > val[k - 1]) {
+                    const float tv = val[k]; val[k] = val[k - 1]; val[k - 1] = tv;
+                    const int ti = id[k]; id[k] = id[k - 1]; id[k - 1] = ti;
+                }
+            }
+        }
+    }
+    // log-sum-exp of the row
+    float mm = m;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) mm = fmaxf(mm, __shfl_xor(mm, o));
+    float ss = (m == -INFINITY) ? 0.f : s * __expf(m - mm);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+    if (lane == 0) { red_m[wave] = mm; red_s[wave] = ss; }
+    __syncthreads();
+    const float mt = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+    float st = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) st += red_m[w] == -INFINITY ? 0.f : red_s[w] * __expf(red_m[w] - mt);
+    const float lse = mt + __logf(st);
+    // Bw rounds: the best head of all threads' lists wins and is popped
+    for (int round = 0; round < Bw; ++round) {
+        float bv = val[0];
+        int bi = id[0], bt = t;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+            const float ov = __shfl_xor(bv, o);
+            const int oi = __shfl_xor(bi, o), ot = __shfl_xor(bt, o);
+            if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; bt = ot; }
+        }
+        __syncthreads();                                   // the previous round's winners have been read
+        if (lane == 0) { wv[wave] = bv; wi[wave] = bi; wt[wave] = bt; }
+        __syncthreads();
+        float gv = wv[0];
+        int gi = wi[0], gt = wt[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w)
+            if (ranks_before(wv[w], wi[w], gv, gi)) { gv = wv[w]; gi = wi[w]; gt = wt[w]; }
+        if (t == 0) {
+            tok[r * Bw + round] = gi;
+            logp[r * Bw + round] = gv - lse;
+        }
+        if (t == gt) {                                     // pop the head
+#pragma unroll
+            for (int k = 0; k < KMAX - 1; ++k) { val[k] = val[k + 1]; id[k] = id[k + 1]; }
+            val[KMAX - 1] = -INFINITY;
+            id[KMAX - 1] = 0x7fffffff;
+        }
+    }
+}
+
+}  // namespace moa
+
+using namespace moa;
+
+extern "C" {
+
+static int32_t tree_fail(int32_t code, const char *msg) { return moa::api_fail(code, msg); }
+
+int32_t moa_tree_expand_level(int32_t level, int32_t B, int32_t Bw, int32_t n_max, const float *child_logp,
+                              const int32_t *child_tok, float *cand_logp, int32_t *cand_tok, int32_t *cand_parent,
+                              int32_t *frontier, void *stream)
+{
+    if (!child_logp || !child_tok || !cand_logp || !cand_tok || !cand_parent || !frontier) return tree_fail(MOA_ERR_NULL, "tree_expand_level: NULL pointer");
+    if (level < 1 || B < 1 || Bw < 1 || Bw > TREE_MAX_BREADTH) return tree_fail(MOA_ERR_SHAPE, "tree_expand_level: level >= 1, B >= 1, 1 <= breadth <= 16");
+    const int64_t end = level == 1 ? Bw : (int64_t)Bw + (int64_t)(level - 1) * Bw * Bw;
+    if (end > n_max) return tree_fail(MOA_ERR_RANGE, "tree_expand_level: the level's candidates do not fit n_max");
+    prof_set_site(S_TREE_EXPAND);
+    prof_begin(K_TREE_EXPAND, (hipStream_t)stream);
+    MOA_KLAUNCH(k_tree_expand, dim3(B), dim3(256), 0, (hipStream_t)stream, level, Bw, n_max, child_logp, child_tok, cand_logp,
+                cand_tok, cand_parent, frontier);
+    prof_end((hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? MOA_OK : tree_fail(MOA_ERR_HIP, "tree_expand_level: launch failed");
+}
+
+int32_t moa_tree_finalize(int32_t B, int32_t n_cand, int32_t n_max, int32_t m, const int32_t *root_tok,
+                          const float *cand_logp, const int32_t *cand_tok, const int32_t *cand_parent, int32_t *parent,
+                          int32_t *tok, int32_t *node_cand, int32_t *dev_status, void *stream)
+{
+    if (!root_tok || !cand_logp || !cand_tok || !cand_parent || !parent || !tok || !node_cand) return tree_fail(MOA_ERR_NULL, "tree_finalize: NULL pointer");
+    if (B < 1 || n_cand < 0 || n_cand > n_max || n_cand > TREE_MAX_CAND || m < 0 || 1 + m > MOA_MAX_TREE)
+        return tree_fail(MOA_ERR_SHAPE, "tree_finalize: 0 <= n_cand <= min(n_max, 4096), 1 + m <= 256");
+    const int keep = m < n_cand ? m : n_cand;
+    prof_set_site(S_TREE_FINALIZE);
+    prof_begin(K_TREE_FINALIZE, (hipStream_t)stream);
+    MOA_KLAUNCH(k_tree_finalize, dim3(B), dim3(256), 0, (hipStream_t)stream, n_cand, n_max, keep, 1 + m, root_tok, cand_logp,
+                cand_tok, cand_parent, parent, tok, node_cand, dev_status);
+    prof_end((hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? MOA_OK : tree_fail(MOA_ERR_HIP, "tree_finalize: launch failed");
+}
+
+int32_t moa_topk_logprob(int32_t dtype, const void *logits, int32_t F, int32_t V, int32_t Bw, int32_t *tok, float *logp,
+                         void *stream)
+{
+    if (!logits || !tok || !logp) return tree_fail(MOA_ERR_NULL, "topk_logprob: NULL pointer");
+    if (dtype != MOA_F32 && dtype != MOA_BF16) return tree_fail(MOA_ERR_DTYPE, "topk_logprob: dtype");
+    if (F < 1 || V < 1 || Bw < 1 || Bw > TREE_MAX_BREADTH || Bw > V) return tree_fail(MOA_ERR_SHAPE, "topk_logprob: F >= 1, 1 <= breadth <= min(16, V)");
+    prof_set_site(S_TOPK_LOGPROB);
+    prof_begin(K_TOPK_LOGPROB, (hipStream_t)stream);
+    MOA_KLAUNCH(k_topk_logprob_f32_or_bf16, dim3(F), dim3(256), 0, (hipStream_t)stream, dtype == MOA_BF16 ? 1 : 0, logits, V, Bw, tok, logp);
+    prof_end((hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? MOA_OK : tree_fail(MOA_ERR_HIP, "topk_logprob: launch failed");
+}
+
+}  // extern "C"
