@@ -218,7 +218,8 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
  *   kept candidate's parent is not kept, the node hangs off the root and MOA_DEV_BAD_PARENT is set.
  * moa_topk_logprob: the Bw most probable tokens of each row of logits [F, V] (dtype MOA_F32 or
  *   MOA_BF16) with log-probabilities logit - logsumexp(row) in fp32; ties go to the lower token id.
- *   tok, logp [F, Bw]: the child_tok / child_logp of the next moa_tree_expand_level. */
+ *   tok, logp [F, Bw]: the child_tok / child_logp of the next moa_tree_expand_level.  Logits are
+ *   expected finite.  Workspace: moa_topk_workspace_bytes(F, V, Bw), 256-byte aligned. */
 int32_t moa_tree_expand_level(int32_t level, int32_t B, int32_t Bw, int32_t n_max,
                               const float *child_logp, const int32_t *child_tok,
                               float *cand_logp, int32_t *cand_tok, int32_t *cand_parent,
@@ -227,8 +228,19 @@ int32_t moa_tree_finalize(int32_t B, int32_t n_cand, int32_t n_max, int32_t m, c
                           const float *cand_logp, const int32_t *cand_tok, const int32_t *cand_parent,
                           int32_t *parent, int32_t *tok, int32_t *node_cand, int32_t *dev_status,
                           void *stream);
+int32_t moa_topk_workspace_bytes(int32_t F, int32_t V, int32_t Bw, size_t *bytes_host);
 int32_t moa_topk_logprob(int32_t dtype, const void *logits, int32_t F, int32_t V, int32_t Bw,
-                         int32_t *tok, float *logp, void *stream);
+                         int32_t *tok, float *logp, void *ws, size_t ws_bytes, void *stream);
+
+/* Greedy token of the LLM at every tree node (Sec. 2.1, y ~ Softmax(LM_head(o)); greedy verification
+ * takes the arg max): tgt[r] = argmax_v x[r] . w[v] over the vocabulary, the tgt[] the accept walk
+ * reads.  The logits are never stored: one pass over w per 64 rows.  Ties: lower token id.
+ *   x [R, d], w [V, d] (bf16, 16-byte aligned, d a multiple of 128) -> tgt [R] (int32) and, if best
+ *   is not NULL, best [R] (fp32: the winning logit).  Workspace: moa_lm_head_workspace_bytes(V),
+ *   256-byte aligned.  MOA_ERR_DTYPE for fp32 inputs (project and reduce them on the caller's side). */
+int32_t moa_lm_head_workspace_bytes(int32_t V, size_t *bytes_host);
+int32_t moa_lm_head_argmax(int32_t dtype, const void *x, int32_t R, int32_t d, const void *w, int32_t V,
+                           int32_t *tgt, float *best, void *ws, size_t ws_bytes, void *stream);
 
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->

@@ -246,6 +246,17 @@ def topk_logprob(logits, Bw):
     return tok, logp
 
 
+def lm_head_argmax(x, w):
+    """-> tgt [R] int32 (arg max over the vocabulary of x @ w.T, lower id on ties), best [R] (the winning logit)."""
+    x, w = _f64(x), _f64(w)
+    R, d = x.shape
+    V = w.shape[0]
+    tgt = np.empty(R, dtype=np.int32)
+    best = np.empty(R, dtype=np.float64)
+    _check(lib().moa_ref_lm_head_argmax(_p(x), R, d, _p(w), V, _p(tgt, C.c_int32), _p(best)), "lm_head_argmax")
+    return tgt, best
+
+
 def tree_accept(parent, tok, tgt):
     parent, tok, tgt = _i32(parent), _i32(tok), _i32(tgt)
     B, M = parent.shape

@@ -587,6 +587,26 @@ int moa_ref_topk_logprob(const double *logits, int F, int V, int Bw, int32_t *to
     return MOA_REF_OK;
 }
 
+/* ------------------------------------------------------------ LM head, greedy token */
+
+int moa_ref_lm_head_argmax(const double *x, int R, int d, const double *w, int V, int32_t *tgt, double *best)
+{
+    if (!x || !w || !tgt || R < 1 || d < 1 || V < 1) return MOA_REF_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < R; ++r) {
+        int arg = 0;
+        double top = 0.0;
+        for (int v = 0; v < V; ++v) {
+            double acc = 0.0;
+            for (int k = 0; k < d; ++k) acc += x[(int64_t)r * d + k] * w[(int64_t)v * d + k];
+            if (v == 0 || acc > top) { top = acc; arg = v; }        /* strict: the lower id wins a tie */
+        }
+        tgt[r] = arg;
+        if (best) best[r] = top;
+    }
+    return MOA_REF_OK;
+}
+
 /* ------------------------------------------------------------ tree verify */
 
 int moa_ref_tree_verify_attn(const double *x, int B, int M, int d, int H, int Hkv, int dh,

@@ -164,6 +164,12 @@ int moa_ref_tree_finalize(int n_cand, int m, int32_t root_tok, const float *cand
 int moa_ref_topk_logprob(const double *logits /*[F,V]*/, int F, int V, int Bw,
                          int32_t *tok /*[F,Bw]*/, double *logp /*[F,Bw]*/);
 
+/* Greedy token of the LLM at every tree node: tgt[r] = argmax_v (x[r] . W[v]) over the vocabulary
+ * (Sec. 2.1: y ~ Softmax(LM_head(o)); greedy verification takes the arg max; the result is the tgt[]
+ * that the accept walk reads).  Ties: lower token id.  Also returns the winning logit. */
+int moa_ref_lm_head_argmax(const double *x /*[R,d]*/, int R, int d, const double *w /*[V,d]*/, int V,
+                           int32_t *tgt /*[R]*/, double *best /*[R]*/);
+
 /* Greedy acceptance (Sec. 2.2: everything after the first mismatch is dropped).
  * tok[i] is the token drafted at node i; tgt[i] is the LLM's greedy token after
  * node i.  Walk from the root to the lowest-index child whose token equals the

@@ -68,7 +68,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
-            "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -98,8 +98,11 @@ _lib.moa_tli_decoder_layer.argtypes = [C.POINTER(Shape), C.POINTER(DecoderCfg), 
     _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moa_tree_expand_level.argtypes = [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.moa_tree_finalize.argtypes = [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
-_lib.moa_topk_logprob.argtypes = [_i32, _vp, _i32, _i32, _i32, _vp, _vp, _vp]
-for _n in _SYMBOLS[2:16]:
+_lib.moa_topk_logprob.argtypes = [_i32, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _sz, _vp]
+_lib.moa_topk_workspace_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(_sz)]
+_lib.moa_lm_head_workspace_bytes.argtypes = [_i32, C.POINTER(_sz)]
+_lib.moa_lm_head_argmax.argtypes = [_i32, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
+for _n in _SYMBOLS[2:19]:
     getattr(_lib, _n).restype = C.c_int32
 
 
@@ -325,12 +328,36 @@ def tree_finalize(n_cand, m, root_tok, cand_logp, cand_tok, cand_parent, parent,
                                   _dev(dev_status, i32, 1, "dev_status"), _stream(stream)))
 
 
-def topk_logprob(logits, Bw, tok, logp, stream=None):
+def topk_workspace_bytes(F: int, V: int, Bw: int) -> int:
+    out = _sz(0)
+    _check(_lib.moa_topk_workspace_bytes(int(F), int(V), int(Bw), C.byref(out)))
+    return int(out.value)
+
+
+def topk_logprob(logits, Bw, tok, logp, ws, stream=None):
     """The Bw most probable tokens of each row of logits [F, V] (fp32 or bf16) -> tok (int32), logp (fp32) [F, Bw]."""
     F, V = logits.shape
     dtype = {torch.float32: F32, torch.bfloat16: BF16}[logits.dtype]
+    wsp, wsb = _ws(ws)
     _check(_lib.moa_topk_logprob(dtype, _dev(logits, logits.dtype, F * V, "logits"), F, V, int(Bw),
-                                 _dev(tok, torch.int32, F * Bw, "tok"), _dev(logp, torch.float32, F * Bw, "logp"), _stream(stream)))
+                                 _dev(tok, torch.int32, F * Bw, "tok"), _dev(logp, torch.float32, F * Bw, "logp"),
+                                 wsp, wsb, _stream(stream)))
+
+
+def lm_head_workspace_bytes(V: int) -> int:
+    out = _sz(0)
+    _check(_lib.moa_lm_head_workspace_bytes(int(V), C.byref(out)))
+    return int(out.value)
+
+
+def lm_head_argmax(x, w, tgt, ws, best=None, stream=None):
+    """tgt[r] = argmax over the vocabulary of x[r] . w[v] (x [R, d], w [V, d] bf16; tgt int32 [R]; best fp32 [R] or None)."""
+    R, d = x.shape
+    V = w.shape[0]
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_lm_head_argmax(BF16 if x.dtype == torch.bfloat16 else F32, _dev(x, x.dtype, R * d, "x"), R, d,
+                                   _dev(w, x.dtype, V * d, "w"), V, _dev(tgt, torch.int32, R, "tgt"),
+                                   _dev(best, torch.float32, R, "best"), wsp, wsb, _stream(stream)))
 
 
 def _ptr_array(tensors, dtype, numel, name):

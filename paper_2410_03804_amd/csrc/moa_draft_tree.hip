@@ -111,82 +111,131 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
 }
 
 // ---- the Bw most probable tokens of a row of logits, with log-probabilities
-template <typename T> __device__ __forceinline__ float logit_at(const T *row, int v) { return ld<T>(row + v); }
+// A row of the vocabulary is cut into S slices, one workgroup each, so that a handful of rows still fills the chip.
+// A thread holds its (at most 32) values in registers; the slice's Bw best are found by Bw rounds of "the best value
+// that ranks after the previous winner" (value descending, id ascending: a total order, so ties need no care), each
+// round one pass over registers and one workgroup-wide reduction.  A second kernel ranks the S*Bw survivors of a
+// row and merges the slices' (max, sum of exponentials).
+constexpr int TOPK_EPT = 32;              // values a thread keeps
+constexpr int TOPK_MIN_SLICES = 32;
 
-__global__ __launch_bounds__(256) void k_topk_logprob_f32_or_bf16(int is_bf16, const void *__restrict__ logits, int V, int Bw,
-                                                                  int32_t *__restrict__ tok, float *__restrict__ logp)
+static int topk_slices(int V)
 {
-    constexpr int KMAX = TREE_MAX_BREADTH;
-    __shared__ float wv[4];
-    __shared__ int wi[4], wt[4];
-    __shared__ float red_m[4], red_s[4];
+    const int need = (V + 256 * TOPK_EPT - 1) / (256 * TOPK_EPT);
+    return need > TOPK_MIN_SLICES ? need : TOPK_MIN_SLICES;
+}
+
+// scratch per (row, slice): Bw values, Bw ids, max, sum
+__global__ __launch_bounds__(256) void k_topk_slices(int is_bf16, const void *__restrict__ logits, int V, int Bw, int S,
+                                                     float *__restrict__ sval, int32_t *__restrict__ sid,
+                                                     float *__restrict__ smax, float *__restrict__ ssum)
+{
+    __shared__ float wv[4], wm[4], wsum[4];
+    __shared__ int wi[4];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int64_t r = blockIdx.x;
+    const int s = blockIdx.x % S;
+    const int64_t r = blockIdx.x / S;
+    const int Vs = (V + S - 1) / S, v0 = s * Vs, v1 = min(v0 + Vs, V);
     const float *rf = (const float *)logits + r * V;
     const bf16_t *rb = (const bf16_t *)logits + r * V;
-    float val[KMAX];
-    int id[KMAX];
+    float x[TOPK_EPT];
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k) { val[k] = -INFINITY; id[k] = 0x7fffffff; }
-    float m = -INFINITY, s = 0.f;
-    for (int v = t; v < V; v += 256) {                     // ids grow within a thread: an equal value never overtakes
-        const float x = is_bf16 ? bf2f(rb[v]) : rf[v];
-        if (x > m) { s = s * __expf(m - x) + 1.0f; m = x; }
-        else s += __expf(x - m);
-        if (x > val[KMAX - 1]) {
-            val[KMAX - 1] = x;
-            id[KMAX - 1] = v;
-#pragma unroll
-            for (int k = KMAX - 1; k > 0; --k) {
-                if (val[k] > val[k - 1]) {
-                    const float tv = val[k]; val[k] = val[k - 1]; val[k - 1] = tv;
-                    const int ti = id[k]; id[k] = id[k - 1]; id[k - 1] = ti;
-                }
-            }
-        }
+    for (int i = 0; i < TOPK_EPT; ++i) {
+        const int v = v0 + t + 256 * i;
+        x[i] = v < v1 ? (is_bf16 ? bf2f(rb[v]) : rf[v]) : -INFINITY;
     }
-    // log-sum-exp of the row
-    float mm = m;
+    // the slice's log-sum-exp pieces
+    float m = -INFINITY;
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) mm = fmaxf(mm, __shfl_xor(mm, o));
-    float ss = (m == -INFINITY) ? 0.f : s * __expf(m - mm);
+    for (int i = 0; i < TOPK_EPT; ++i) m = fmaxf(m, x[i]);
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
-    if (lane == 0) { red_m[wave] = mm; red_s[wave] = ss; }
+    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) wm[wave] = m;
     __syncthreads();
-    const float mt = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
-    float st = 0.f;
+    m = fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3]));
+    float sum = 0.f;
+    if (m > -INFINITY) {
 #pragma unroll
-    for (int w = 0; w < 4; ++w) st += red_m[w] == -INFINITY ? 0.f : red_s[w] * __expf(red_m[w] - mt);
-    const float lse = mt + __logf(st);
-    // Bw rounds: the best head of all threads' lists wins and is popped
+        for (int i = 0; i < TOPK_EPT; ++i) sum += __expf(x[i] - m);      // exp(-inf) = 0 for the padding
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) wsum[wave] = sum;
+    __syncthreads();
+    const int64_t slot = r * S + s;
+    if (t == 0) { smax[slot] = m; ssum[slot] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]); }
+    // Bw rounds of selection
+    float lastv = INFINITY;
+    int lasti = -1;
     for (int round = 0; round < Bw; ++round) {
-        float bv = val[0];
-        int bi = id[0], bt = t;
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < TOPK_EPT; ++i) {
+            const int v = v0 + t + 256 * i;
+            const bool after = v < v1 && ranks_before(lastv, lasti, x[i], v);
+            if (after && ranks_before(x[i], v, bv, bi)) { bv = x[i]; bi = v; }
+        }
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) {
             const float ov = __shfl_xor(bv, o);
-            const int oi = __shfl_xor(bi, o), ot = __shfl_xor(bt, o);
-            if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; bt = ot; }
+            const int oi = __shfl_xor(bi, o);
+            if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
         }
-        __syncthreads();                                   // the previous round's winners have been read
-        if (lane == 0) { wv[wave] = bv; wi[wave] = bi; wt[wave] = bt; }
         __syncthreads();
-        float gv = wv[0];
-        int gi = wi[0], gt = wt[0];
+        if (lane == 0) { wv[wave] = bv; wi[wave] = bi; }
+        __syncthreads();
+        bv = wv[0];
+        bi = wi[0];
 #pragma unroll
         for (int w = 1; w < 4; ++w)
-            if (ranks_before(wv[w], wi[w], gv, gi)) { gv = wv[w]; gi = wi[w]; gt = wt[w]; }
-        if (t == 0) {
-            tok[r * Bw + round] = gi;
-            logp[r * Bw + round] = gv - lse;
-        }
-        if (t == gt) {                                     // pop the head
+            if (ranks_before(wv[w], wi[w], bv, bi)) { bv = wv[w]; bi = wi[w]; }
+        if (t == 0) { sval[slot * Bw + round] = bv; sid[slot * Bw + round] = bi; }   // (-inf, INT_MAX) when the slice ran out
+        lastv = bv;
+        lasti = bi;
+    }
+}
+
+// one workgroup per row: rank the S*Bw survivors, merge the log-sum-exp
+__global__ __launch_bounds__(256) void k_topk_merge(int Bw, int S, const float *__restrict__ sval, const int32_t *__restrict__ sid,
+                                                    const float *__restrict__ smax, const float *__restrict__ ssum,
+                                                    int32_t *__restrict__ tok, float *__restrict__ logp)
+{
+    extern __shared__ float cv[];                          // [n] values, then [n] ids
+    __shared__ float red[4];
+    __shared__ float lse_s;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int64_t r = blockIdx.x;
+    const int n = S * Bw;
+    int32_t *ci = (int32_t *)(cv + n);
+    for (int c = t; c < n; c += 256) { cv[c] = sval[r * n + c]; ci[c] = sid[r * n + c]; }
+    float m = -INFINITY;
+    for (int k = t; k < S; k += 256) m = fmaxf(m, smax[r * S + k]);
 #pragma unroll
-            for (int k = 0; k < KMAX - 1; ++k) { val[k] = val[k + 1]; id[k] = id[k + 1]; }
-            val[KMAX - 1] = -INFINITY;
-            id[KMAX - 1] = 0x7fffffff;
-        }
+    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float sum = 0.f;
+    for (int k = t; k < S; k += 256) {
+        const float mk = smax[r * S + k];
+        if (mk > -INFINITY) sum += ssum[r * S + k] * __expf(mk - m);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) red[wave] = sum;
+    __syncthreads();
+    if (t == 0) lse_s = m + __logf((red[0] + red[1]) + (red[2] + red[3]));
+    __syncthreads();
+    const float lse = lse_s;
+    for (int c = t; c < n; c += 256) {
+        const float v = cv[c];
+        const int id = ci[c];
+        if (id == 0x7fffffff) continue;                    // an exhausted slice's filler
+        int rank = 0;
+        for (int u = 0; u < n; ++u) rank += ranks_before(cv[u], ci[u], v, id) ? 1 : 0;
+        if (rank < Bw) { tok[r * Bw + rank] = id; logp[r * Bw + rank] = v - lse; }
     }
 }
 
@@ -230,16 +279,41 @@ int32_t moa_tree_finalize(int32_t B, int32_t n_cand, int32_t n_max, int32_t m, c
     return hipGetLastError() == hipSuccess ? MOA_OK : tree_fail(MOA_ERR_HIP, "tree_finalize: launch failed");
 }
 
+int32_t moa_topk_workspace_bytes(int32_t F, int32_t V, int32_t Bw, size_t *bytes_host)
+{
+    if (!bytes_host) return tree_fail(MOA_ERR_NULL, "topk_workspace_bytes: bytes_host is NULL");
+    if (F < 1 || V < 1 || Bw < 1 || Bw > TREE_MAX_BREADTH) return tree_fail(MOA_ERR_SHAPE, "topk_workspace_bytes: F >= 1, V >= 1, 1 <= breadth <= 16");
+    const size_t S = (size_t)topk_slices(V);
+    *bytes_host = (size_t)F * S * ((size_t)Bw * 8 + 8);
+    return MOA_OK;
+}
+
 int32_t moa_topk_logprob(int32_t dtype, const void *logits, int32_t F, int32_t V, int32_t Bw, int32_t *tok, float *logp,
-                         void *stream)
+                         void *ws, size_t ws_bytes, void *stream)
 {
     if (!logits || !tok || !logp) return tree_fail(MOA_ERR_NULL, "topk_logprob: NULL pointer");
     if (dtype != MOA_F32 && dtype != MOA_BF16) return tree_fail(MOA_ERR_DTYPE, "topk_logprob: dtype");
     if (F < 1 || V < 1 || Bw < 1 || Bw > TREE_MAX_BREADTH || Bw > V) return tree_fail(MOA_ERR_SHAPE, "topk_logprob: F >= 1, 1 <= breadth <= min(16, V)");
+    const int S = topk_slices(V);
+    const size_t n = (size_t)F * S;
+    if ((int64_t)F * S > 0x7fffffff) return tree_fail(MOA_ERR_SHAPE, "topk_logprob: too many rows");
+    const size_t need = n * ((size_t)Bw * 8 + 8);
+    if (!ws || (((uintptr_t)ws) & 255) || ws_bytes < need) return tree_fail(MOA_ERR_WORKSPACE, "topk_logprob: workspace NULL, misaligned or smaller than moa_topk_workspace_bytes");
+    float *sval = (float *)ws;
+    int32_t *sid = (int32_t *)(sval + n * Bw);
+    float *smax = (float *)(sid + n * Bw);
+    float *ssum = smax + n;
+    hipStream_t st = (hipStream_t)stream;
     prof_set_site(S_TOPK_LOGPROB);
-    prof_begin(K_TOPK_LOGPROB, (hipStream_t)stream);
-    MOA_KLAUNCH(k_topk_logprob_f32_or_bf16, dim3(F), dim3(256), 0, (hipStream_t)stream, dtype == MOA_BF16 ? 1 : 0, logits, V, Bw, tok, logp);
-    prof_end((hipStream_t)stream);
+    prof_begin(K_TOPK_LOGPROB, st);
+    MOA_KLAUNCH(k_topk_slices, dim3((unsigned)n), dim3(256), 0, st, dtype == MOA_BF16 ? 1 : 0, logits, V, Bw, S, sval, sid, smax, ssum);
+    prof_end(st);
+    if (hipGetLastError() != hipSuccess) return tree_fail(MOA_ERR_HIP, "topk_logprob: launch failed");
+    const size_t lds = (size_t)S * Bw * 8;
+    if (lds > 60 * 1024) return tree_fail(MOA_ERR_SHAPE, "topk_logprob: vocabulary too large for the merge");
+    prof_begin(K_TOPK_MERGE, st);
+    MOA_KLAUNCH(k_topk_merge, dim3(F), dim3(256), lds, st, Bw, S, sval, sid, smax, ssum, tok, logp);
+    prof_end(st);
     return hipGetLastError() == hipSuccess ? MOA_OK : tree_fail(MOA_ERR_HIP, "topk_logprob: launch failed");
 }
 

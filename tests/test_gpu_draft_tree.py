@@ -125,8 +125,42 @@ def test_topk_logprob_parity(G, moa, oracle, dtype, F, V, Bw):
     print(f"[case] topk_logprob {dtype} F={F} V={V} breadth={Bw}", flush=True)
     tok = torch.zeros((F, Bw), dtype=torch.int32, device="cuda")
     logp = torch.zeros((F, Bw), dtype=torch.float32, device="cuda")
-    moa.topk_logprob(G.dev(logits, dtype), Bw, tok, logp)
+    ws = torch.empty(max(moa.topk_workspace_bytes(F, V, Bw), 256), dtype=torch.uint8, device="cuda")
+    moa.topk_logprob(G.dev(logits, dtype), Bw, tok, logp, ws)
     torch.cuda.synchronize()
     wt, wl = oracle.topk_logprob(logits, Bw)
     assert np.array_equal(tok.cpu().numpy(), wt)             # bf16 logits tie often: lower id first, exactly
     assert np.max(np.abs(logp.cpu().numpy().astype(np.float64) - wl)) < 1e-5 * max(1.0, np.abs(wl).max())
+
+
+@pytest.mark.parametrize("R,d,V", [(60, 4096, 128256), (64, 512, 1000), (7, 256, 70), (130, 384, 5000), (1, 128, 64)])
+def test_lm_head_argmax_parity(G, moa, oracle, R, d, V):
+    """The greedy token per row.  The device accumulates bf16 products in fp32, the oracle in fp64, so where two logits
+    are closer than that difference either token is a correct answer: the chosen token's oracle logit must be within
+    rounding of the oracle's maximum, and equal to it where the runner-up is further away."""
+    rng = np.random.default_rng(R + V)
+    x = mi.quantize(rng.standard_normal((R, d)).astype(np.float32), "bf16")
+    w = mi.quantize((rng.standard_normal((V, d)) / np.sqrt(d)).astype(np.float32), "bf16")
+    if V > 100:
+        w[V - 3] = w[11]                                        # two tokens with identical logits: the lower id must win
+        x[0] = mi.quantize(w[11] * 8.0, "bf16")
+    print(f"[case] lm_head_argmax R={R} d={d} V={V}", flush=True)
+    tgt = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+    best = torch.zeros((R,), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(moa.lm_head_workspace_bytes(V), 256), dtype=torch.uint8, device="cuda")
+    moa.lm_head_argmax(G.dev(x, "bf16"), G.dev(w, "bf16"), tgt, ws, best)
+    torch.cuda.synchronize()
+    got = tgt.cpu().numpy()
+    logits = x.astype(np.float64) @ w.astype(np.float64).T                      # what the oracle maximises, all of it
+    wt, wb = oracle.lm_head_argmax(x, w) if V <= 5000 else (np.argmax(logits, axis=1).astype(np.int32), logits.max(axis=1))
+    assert np.array_equal(wt, np.argmax(logits, axis=1))
+    tol = 1e-5 * np.sqrt(d)
+    assert np.all(got >= 0) and np.all(got < V)
+    chosen = logits[np.arange(R), got]
+    assert np.all(wb - chosen <= tol), "a token whose logit is not the maximum"
+    srt = np.sort(logits, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) > tol
+    assert np.array_equal(got[clear], wt[clear])
+    if V > 100:
+        assert got[0] == 11
+    assert np.max(np.abs(best.cpu().numpy() - chosen)) <= 2e-4 * np.sqrt(d)

@@ -138,3 +138,19 @@ def test_topk_logprob_against_library(oracle):
         assert np.allclose(logp[f], ref[f, order], atol=1e-12)
     assert list(tok[2, :2]) == [17, 400]
     assert np.allclose(np.exp(oracle.topk_logprob(logits[:1, :6], 6)[1]).sum(), 1.0, atol=1e-12)
+
+
+def test_lm_head_argmax_pins(oracle):
+    """One-hot head rows select a component of x, so the greedy token is the position of its largest entry; a general
+    head agrees with numpy; equal logits go to the lower id."""
+    rng = np.random.default_rng(21)
+    x = rng.standard_normal((7, 12))
+    tgt, best = oracle.lm_head_argmax(x, np.eye(12))
+    assert list(tgt) == list(np.argmax(x, axis=1)) and np.allclose(best, x.max(axis=1))
+    w = rng.standard_normal((300, 12))
+    w[250] = w[40]                                                            # two tokens with the same logits
+    tgt, best = oracle.lm_head_argmax(x, w)
+    logits = x @ w.T
+    assert list(tgt) == list(np.argmax(logits, axis=1)) and np.allclose(best, logits.max(axis=1), atol=1e-12)
+    x2 = w[40:41] * 3.0                                                       # this row prefers token 40 = 250
+    assert list(oracle.lm_head_argmax(x2, w)[0]) == [40]
