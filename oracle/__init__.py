@@ -257,6 +257,41 @@ def lm_head_argmax(x, w):
     return tgt, best
 
 
+def msg_pack_tree(tok, parent):
+    tok, parent = _i32(tok), _i32(parent)
+    B, M = tok.shape
+    msg = np.empty((B, 4 * M), dtype=np.uint8)
+    _check(lib().moa_ref_msg_pack_tree(_p(tok, C.c_int32), _p(parent, C.c_int32), B, M, _p(msg, C.c_uint8)), "msg_pack_tree")
+    return msg
+
+
+def msg_unpack_tree(msg):
+    msg = np.ascontiguousarray(msg, dtype=np.uint8)
+    B, M = msg.shape[0], msg.shape[1] // 4
+    tok = np.empty((B, M), dtype=np.int32)
+    parent = np.empty((B, M), dtype=np.int32)
+    _check(lib().moa_ref_msg_unpack_tree(_p(msg, C.c_uint8), B, M, _p(tok, C.c_int32), _p(parent, C.c_int32)), "msg_unpack_tree")
+    return tok, parent
+
+
+def msg_pack_accept(tok, x):
+    """tok [A], x [A, n_vec, n] (float32) -> bytes [A, 3 + n_vec (4 + n)]"""
+    tok, x = _i32(tok), _f32(x)
+    A, n_vec, n = x.shape
+    msg = np.empty((A, 3 + n_vec * (4 + n)), dtype=np.uint8)
+    _check(lib().moa_ref_msg_pack_accept(_p(tok, C.c_int32), _p(x, C.c_float), A, n_vec, n, _p(msg, C.c_uint8)), "msg_pack_accept")
+    return msg
+
+
+def msg_unpack_accept(msg, n_vec, n):
+    msg = np.ascontiguousarray(msg, dtype=np.uint8)
+    A = msg.shape[0]
+    tok = np.empty(A, dtype=np.int32)
+    x = np.empty((A, n_vec, n), dtype=np.float32)
+    _check(lib().moa_ref_msg_unpack_accept(_p(msg, C.c_uint8), A, n_vec, n, _p(tok, C.c_int32), _p(x, C.c_float)), "msg_unpack_accept")
+    return tok, x
+
+
 def tree_accept(parent, tok, tgt):
     parent, tok, tgt = _i32(parent), _i32(tok), _i32(tgt)
     B, M = parent.shape

@@ -607,6 +607,77 @@ int moa_ref_lm_head_argmax(const double *x, int R, int d, const double *w, int V
     return MOA_REF_OK;
 }
 
+/* ------------------------------------------------------------ client-server messages */
+
+int moa_ref_msg_pack_tree(const int32_t *tok, const int32_t *parent, int B, int M, uint8_t *msg)
+{
+    if (!tok || !parent || !msg || B < 1 || M < 1 || M > 256) return MOA_REF_BAD_ARG;
+    for (int64_t i = 0; i < (int64_t)B * M; ++i) {
+        const int32_t t = tok[i], p = parent[i];
+        if (t < 0 || t >= (1 << 24) || p < -1 || p >= 255) return MOA_REF_BAD_ARG;
+        msg[4 * i + 0] = (uint8_t)(t & 0xff);
+        msg[4 * i + 1] = (uint8_t)((t >> 8) & 0xff);
+        msg[4 * i + 2] = (uint8_t)((t >> 16) & 0xff);
+        msg[4 * i + 3] = p < 0 ? 0xff : (uint8_t)p;
+    }
+    return MOA_REF_OK;
+}
+
+int moa_ref_msg_unpack_tree(const uint8_t *msg, int B, int M, int32_t *tok, int32_t *parent)
+{
+    if (!tok || !parent || !msg || B < 1 || M < 1 || M > 256) return MOA_REF_BAD_ARG;
+    for (int64_t i = 0; i < (int64_t)B * M; ++i) {
+        tok[i] = (int32_t)msg[4 * i] | ((int32_t)msg[4 * i + 1] << 8) | ((int32_t)msg[4 * i + 2] << 16);
+        parent[i] = msg[4 * i + 3] == 0xff ? -1 : (int32_t)msg[4 * i + 3];
+    }
+    return MOA_REF_OK;
+}
+
+int moa_ref_msg_pack_accept(const int32_t *tok, const float *x, int A, int n_vec, int n, uint8_t *msg)
+{
+    if (!tok || !x || !msg || A < 0 || n_vec < 0 || n < 1) return MOA_REF_BAD_ARG;
+    const int64_t per = 3 + (int64_t)n_vec * (4 + n);
+    for (int a = 0; a < A; ++a) {
+        uint8_t *m = msg + a * per;
+        const int32_t t = tok[a];
+        if (t < 0 || t >= (1 << 24)) return MOA_REF_BAD_ARG;
+        m[0] = (uint8_t)(t & 0xff); m[1] = (uint8_t)((t >> 8) & 0xff); m[2] = (uint8_t)((t >> 16) & 0xff);
+        for (int v = 0; v < n_vec; ++v) {
+            const float *xv = x + ((int64_t)a * n_vec + v) * n;
+            uint8_t *mv = m + 3 + (int64_t)v * (4 + n);
+            float amax = 0.0f;
+            for (int c = 0; c < n; ++c) { const float ab = fabsf(xv[c]); if (ab > amax) amax = ab; }
+            const float scale = amax / 127.0f;
+            memcpy(mv, &scale, 4);
+            for (int c = 0; c < n; ++c) {
+                float q = scale > 0.0f ? rintf(xv[c] / scale) : 0.0f;
+                if (q > 127.0f) q = 127.0f;
+                if (q < -127.0f) q = -127.0f;
+                mv[4 + c] = (uint8_t)(int8_t)q;
+            }
+        }
+    }
+    return MOA_REF_OK;
+}
+
+int moa_ref_msg_unpack_accept(const uint8_t *msg, int A, int n_vec, int n, int32_t *tok, float *x)
+{
+    if (!tok || !x || !msg || A < 0 || n_vec < 0 || n < 1) return MOA_REF_BAD_ARG;
+    const int64_t per = 3 + (int64_t)n_vec * (4 + n);
+    for (int a = 0; a < A; ++a) {
+        const uint8_t *m = msg + a * per;
+        tok[a] = (int32_t)m[0] | ((int32_t)m[1] << 8) | ((int32_t)m[2] << 16);
+        for (int v = 0; v < n_vec; ++v) {
+            const uint8_t *mv = m + 3 + (int64_t)v * (4 + n);
+            float scale;
+            memcpy(&scale, mv, 4);
+            float *xv = x + ((int64_t)a * n_vec + v) * n;
+            for (int c = 0; c < n; ++c) xv[c] = (float)(int8_t)mv[4 + c] * scale;
+        }
+    }
+    return MOA_REF_OK;
+}
+
 /* ------------------------------------------------------------ tree verify */
 
 int moa_ref_tree_verify_attn(const double *x, int B, int M, int d, int H, int Hkv, int dh,

@@ -170,6 +170,20 @@ int moa_ref_topk_logprob(const double *logits /*[F,V]*/, int F, int V, int Bw,
 int moa_ref_lm_head_argmax(const double *x /*[R,d]*/, int R, int d, const double *w /*[V,d]*/, int V,
                            int32_t *tgt /*[R]*/, double *best /*[R]*/);
 
+/* ---- client-server messages (Sec. 4.2 and the table of message lengths in the appendix).
+ * Client -> server: every node of the draft tree as 3 bytes of token id (little-endian, id < 2^24)
+ * and 1 byte for its position in the tree = the index of its parent (0xFF for the root): 4 M bytes.
+ * Server -> client: per accepted token 3 bytes of token id and its activations, (TLI+1) vectors of
+ * 2 E_kv values, quantised to 8 bits.  The paper does not say how; here: per vector, symmetric,
+ * scale = absmax / 127 in single precision, code = rint(x / scale) clamped to [-127, 127] (0 when the
+ * vector is all zero), the scale sent as 4 bytes in front of the vector's codes.  Token layout:
+ * [3 B id][n_vec x ([4 B scale][n codes])].  All arithmetic in single precision. */
+int moa_ref_msg_pack_tree(const int32_t *tok, const int32_t *parent /*[B,M]*/, int B, int M, uint8_t *msg /*[B,4M]*/);
+int moa_ref_msg_unpack_tree(const uint8_t *msg, int B, int M, int32_t *tok, int32_t *parent);
+int moa_ref_msg_pack_accept(const int32_t *tok /*[A]*/, const float *x /*[A,n_vec,n]*/, int A, int n_vec, int n,
+                            uint8_t *msg /*[A, 3 + n_vec (4 + n)]*/);
+int moa_ref_msg_unpack_accept(const uint8_t *msg, int A, int n_vec, int n, int32_t *tok, float *x);
+
 /* Greedy acceptance (Sec. 2.2: everything after the first mismatch is dropped).
  * tok[i] is the token drafted at node i; tgt[i] is the LLM's greedy token after
  * node i.  Walk from the root to the lowest-index child whose token equals the
