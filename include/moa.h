@@ -56,6 +56,7 @@ enum {
     MOA_DEV_BAD_LENGTH = 2,   /* prefix_len / ca_len outside [0, P_cap] (clamped)           */
     MOA_DEV_EMPTY_KEYS = 4,   /* cross-attention over an empty memory (output row = 0)      */
     MOA_DEV_CACHE_FULL = 8,   /* kv append would pass P_cap (rows beyond it are dropped)    */
+    MOA_DEV_BAD_MESSAGE = 16, /* a token id or tree position does not fit its message field */
 };
 
 #define MOA_MAX_TREE 256      /* a tree position fits one byte (client message format, Sec. 4.2) */
@@ -241,6 +242,29 @@ int32_t moa_topk_logprob(int32_t dtype, const void *logits, int32_t F, int32_t V
 int32_t moa_lm_head_workspace_bytes(int32_t V, size_t *bytes_host);
 int32_t moa_lm_head_argmax(int32_t dtype, const void *x, int32_t R, int32_t d, const void *w, int32_t V,
                            int32_t *tgt, float *best, void *ws, size_t ws_bytes, void *stream);
+
+/* Client-server messages (Sec. 4.2; appendix table of message lengths).
+ * Client -> server: each node of the draft tree as 3 bytes of token id (little-endian) and 1 byte for
+ * its position in the tree = the index of its parent, 0xFF for the root: msg [B, 4 M] bytes (4-byte
+ * aligned).  A token id outside [0, 2^24) or a parent outside [-1, 254] sets MOA_DEV_BAD_MESSAGE (the
+ * low bits are sent).  moa_msg_unpack_tree is the inverse.
+ * Server -> client: per accepted token 3 bytes of token id and its activations, n_vec vectors of n
+ * values (for this method n_vec = TLI + 1 and n = 2 E_kv), 8 bits per value.  The paper does not give
+ * the quantiser; this one is per vector and symmetric: scale = absmax / 127 in single precision,
+ * code = rint(x / scale) clamped to [-127, 127] (0 for an all-zero vector), the scale sent as 4
+ * bytes in front of the vector's codes.  Layout of a token: [3 B id][n_vec x ([4 B scale][n codes])];
+ * msg holds moa_msg_accept_bytes(A, n_vec, n) bytes.  x [A, n_vec, n] in `dtype`;
+ * moa_msg_unpack_accept returns fp32 values code * scale.  The gzip pass over the first message of a
+ * conversation is host work and not part of this library. */
+int32_t moa_msg_pack_tree(const int32_t *tok, const int32_t *parent, int32_t B, int32_t M, void *msg,
+                          int32_t *dev_status, void *stream);
+int32_t moa_msg_unpack_tree(const void *msg, int32_t B, int32_t M, int32_t *tok, int32_t *parent,
+                            void *stream);
+int32_t moa_msg_accept_bytes(int32_t A, int32_t n_vec, int32_t n, size_t *bytes_host);
+int32_t moa_msg_pack_accept(int32_t dtype, const int32_t *tok, const void *x, int32_t A, int32_t n_vec,
+                            int32_t n, void *msg, int32_t *dev_status, void *stream);
+int32_t moa_msg_unpack_accept(const void *msg, int32_t A, int32_t n_vec, int32_t n, int32_t *tok,
+                              float *x, void *stream);
 
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->

@@ -20,7 +20,7 @@ _lib = C.CDLL(str(_LIB_PATH))
 
 F32, BF16 = 0, 1
 MAX_TREE = 256
-DEV_BAD_PARENT, DEV_BAD_LENGTH, DEV_EMPTY_KEYS, DEV_CACHE_FULL = 1, 2, 4, 8
+DEV_BAD_PARENT, DEV_BAD_LENGTH, DEV_EMPTY_KEYS, DEV_CACHE_FULL, DEV_BAD_MESSAGE = 1, 2, 4, 8, 16
 _TORCH_DTYPE = {F32: torch.float32, BF16: torch.bfloat16}
 
 
@@ -68,7 +68,8 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
-            "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
+            "moa_msg_unpack_accept", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -102,7 +103,12 @@ _lib.moa_topk_logprob.argtypes = [_i32, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _s
 _lib.moa_topk_workspace_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(_sz)]
 _lib.moa_lm_head_workspace_bytes.argtypes = [_i32, C.POINTER(_sz)]
 _lib.moa_lm_head_argmax.argtypes = [_i32, _vp, _i32, _i32, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
-for _n in _SYMBOLS[2:19]:
+_lib.moa_msg_pack_tree.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp, _vp]
+_lib.moa_msg_unpack_tree.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
+_lib.moa_msg_accept_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(_sz)]
+_lib.moa_msg_pack_accept.argtypes = [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp]
+_lib.moa_msg_unpack_accept.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
+for _n in _SYMBOLS[2:24]:
     getattr(_lib, _n).restype = C.c_int32
 
 
@@ -358,6 +364,40 @@ def lm_head_argmax(x, w, tgt, ws, best=None, stream=None):
     _check(_lib.moa_lm_head_argmax(BF16 if x.dtype == torch.bfloat16 else F32, _dev(x, x.dtype, R * d, "x"), R, d,
                                    _dev(w, x.dtype, V * d, "w"), V, _dev(tgt, torch.int32, R, "tgt"),
                                    _dev(best, torch.float32, R, "best"), wsp, wsb, _stream(stream)))
+
+
+def msg_pack_tree(tok, parent, msg, dev_status=None, stream=None):
+    """tok, parent [B, M] int32 -> msg [B, 4 M] uint8 (3-byte token id + 1-byte parent index per node)."""
+    B, M = tok.shape
+    _check(_lib.moa_msg_pack_tree(_dev(tok, torch.int32, B * M, "tok"), _dev(parent, torch.int32, B * M, "parent"), B, M,
+                                  _dev(msg, torch.uint8, 4 * B * M, "msg"), _dev(dev_status, torch.int32, 1, "dev_status"), _stream(stream)))
+
+
+def msg_unpack_tree(msg, tok, parent, stream=None):
+    B, M = tok.shape
+    _check(_lib.moa_msg_unpack_tree(_dev(msg, torch.uint8, 4 * B * M, "msg"), B, M, _dev(tok, torch.int32, B * M, "tok"),
+                                    _dev(parent, torch.int32, B * M, "parent"), _stream(stream)))
+
+
+def msg_accept_bytes(A: int, n_vec: int, n: int) -> int:
+    out = _sz(0)
+    _check(_lib.moa_msg_accept_bytes(int(A), int(n_vec), int(n), C.byref(out)))
+    return int(out.value)
+
+
+def msg_pack_accept(tok, x, msg, dev_status=None, stream=None):
+    """tok [A] int32, x [A, n_vec, n] (fp32 or bf16) -> msg (uint8, msg_accept_bytes(A, n_vec, n))."""
+    A, n_vec, n = x.shape
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[x.dtype]
+    _check(_lib.moa_msg_pack_accept(dtype, _dev(tok, torch.int32, A, "tok"), _dev(x, x.dtype, A * n_vec * n, "x"), A, n_vec, n,
+                                    _dev(msg, torch.uint8, msg_accept_bytes(A, n_vec, n), "msg"),
+                                    _dev(dev_status, torch.int32, 1, "dev_status"), _stream(stream)))
+
+
+def msg_unpack_accept(msg, tok, x, stream=None):
+    A, n_vec, n = x.shape
+    _check(_lib.moa_msg_unpack_accept(_dev(msg, torch.uint8, msg_accept_bytes(A, n_vec, n), "msg"), A, n_vec, n,
+                                      _dev(tok, torch.int32, A, "tok"), _dev(x, torch.float32, A * n_vec * n, "x"), _stream(stream)))
 
 
 def _ptr_array(tensors, dtype, numel, name):

@@ -95,13 +95,13 @@ enum KernelId {
     K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_SPLITK, K_LIN_REDUCE, K_LIN_TILED, K_SCATTER,
     K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_LSA_ATTN_MFMA, K_STEP_SMALL, K_ATTN_FUSED, K_PROBE_READ, K_PROBE_MFMA,
     K_RMSNORM, K_ROPE, K_SWIGLU, K_ADD_OUT, K_TREE_EXPAND, K_TREE_FINALIZE, K_TOPK_LOGPROB,
-    K_LM_HEAD, K_LM_HEAD_REDUCE, K_TOPK_MERGE, K_COUNT
+    K_LM_HEAD, K_LM_HEAD_REDUCE, K_TOPK_MERGE, K_MSG_TREE, K_MSG_ACCEPT, K_COUNT
 };
 enum SiteId {
     S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,
     S_CA_OPROJ, S_VERIFY_QKV, S_VERIFY_CORE, S_VERIFY_OPROJ, S_TREE_ACCEPT, S_STEP_SMALL, S_PAIR_QKV, S_PAIR_CORE,
     S_PAIR_OPROJ, S_PROBE, S_SA_QKV, S_SA_CORE, S_SA_OPROJ, S_TLI_QKV, S_TLI_CORE, S_TLI_OPROJ, S_TLI_NORM, S_TLI_ROPE,
-    S_TLI_GATE_UP, S_TLI_ACT, S_TLI_DOWN, S_TLI_ADD, S_TREE_EXPAND, S_TREE_FINALIZE, S_TOPK_LOGPROB, S_LM_HEAD, S_COUNT
+    S_TLI_GATE_UP, S_TLI_ACT, S_TLI_DOWN, S_TLI_ADD, S_TREE_EXPAND, S_TREE_FINALIZE, S_TOPK_LOGPROB, S_LM_HEAD, S_MSG, S_COUNT
 };
 // records the message moa_last_error returns and hands the code back (entry points outside moa_api.hip)
 int32_t api_fail(int32_t code, const char *msg);
