@@ -266,6 +266,14 @@ int32_t moa_msg_pack_accept(int32_t dtype, const int32_t *tok, const void *x, in
 int32_t moa_msg_unpack_accept(const void *msg, int32_t A, int32_t n_vec, int32_t n, int32_t *tok,
                               float *x, void *stream);
 
+/* y = x w^T, the projection every layer of the path is made of, for the ones the path leaves to the
+ * caller (the drafter's LM head when the logits themselves are wanted, Sec. 2.1 LM_head(o); an MLP).
+ *   x [R, K], w [N, K] row-major -> y [R, N], all in `dtype`.  Workspace optional
+ *   (moa_linear_workspace_bytes; without it short-and-wide shapes take a slower kernel). */
+int32_t moa_linear_workspace_bytes(int32_t dtype, int64_t R, int32_t K, int32_t N, size_t *bytes_host);
+int32_t moa_linear(int32_t dtype, const void *x, int64_t R, int32_t K, const void *w, int32_t N, void *y,
+                   void *ws, size_t ws_bytes, void *stream);
+
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
  * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk;

@@ -69,7 +69,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
             "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
-            "moa_msg_unpack_accept", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_msg_unpack_accept", "moa_linear_workspace_bytes", "moa_linear", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -108,7 +108,9 @@ _lib.moa_msg_unpack_tree.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
 _lib.moa_msg_accept_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(_sz)]
 _lib.moa_msg_pack_accept.argtypes = [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.moa_msg_unpack_accept.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
-for _n in _SYMBOLS[2:24]:
+_lib.moa_linear_workspace_bytes.argtypes = [_i32, _i64, _i32, _i32, C.POINTER(_sz)]
+_lib.moa_linear.argtypes = [_i32, _vp, _i64, _i32, _vp, _i32, _vp, _vp, _sz, _vp]
+for _n in _SYMBOLS[2:26]:
     getattr(_lib, _n).restype = C.c_int32
 
 
@@ -398,6 +400,22 @@ def msg_unpack_accept(msg, tok, x, stream=None):
     A, n_vec, n = x.shape
     _check(_lib.moa_msg_unpack_accept(_dev(msg, torch.uint8, msg_accept_bytes(A, n_vec, n), "msg"), A, n_vec, n,
                                       _dev(tok, torch.int32, A, "tok"), _dev(x, torch.float32, A * n_vec * n, "x"), _stream(stream)))
+
+
+def linear_workspace_bytes(dtype: int, R: int, K: int, N: int) -> int:
+    out = _sz(0)
+    _check(_lib.moa_linear_workspace_bytes(dtype, R, K, N, C.byref(out)))
+    return int(out.value)
+
+
+def linear(x, w, y, ws=None, stream=None):
+    """y [R, N] = x [R, K] @ w [N, K].T (fp32 or bf16, all the same dtype)."""
+    R, K = x.shape
+    N = w.shape[0]
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[x.dtype]
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_linear(dtype, _dev(x, x.dtype, R * K, "x"), R, K, _dev(w, x.dtype, N * K, "w"), N, _dev(y, x.dtype, R * N, "y"),
+                           wsp, wsb, _stream(stream)))
 
 
 def _ptr_array(tensors, dtype, numel, name):

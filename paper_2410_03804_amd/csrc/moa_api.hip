@@ -749,6 +749,39 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     return MOA_OK;
 }
 
+int32_t moa_linear_workspace_bytes(int32_t dtype, int64_t R, int32_t K, int32_t N, size_t *bytes_host)
+{
+    if (!bytes_host) return fail(MOA_ERR_NULL, "linear_workspace_bytes: bytes_host is NULL");
+    if (dtype != MOA_F32 && dtype != MOA_BF16) return fail(MOA_ERR_DTYPE, "dtype %d", dtype);
+    if (R < 0 || K < 1 || N < 1) return fail(MOA_ERR_SHAPE, "linear_workspace_bytes: R=%lld K=%d N=%d", (long long)R, K, N);
+    *bytes_host = align256(linear_workspace_bytes(dtype, R, K, N));
+    return MOA_OK;
+}
+
+int32_t moa_linear(int32_t dtype, const void *x, int64_t R, int32_t K, const void *w, int32_t N, void *y, void *ws,
+                   size_t ws_bytes, void *stream)
+{
+    if (!x || !w || !y) return fail(MOA_ERR_NULL, "linear: NULL pointer");
+    if (dtype != MOA_F32 && dtype != MOA_BF16) return fail(MOA_ERR_DTYPE, "dtype %d", dtype);
+    if (R < 0 || K < 1 || N < 1) return fail(MOA_ERR_SHAPE, "linear: R=%lld K=%d N=%d", (long long)R, K, N);
+    if (ws && (((uintptr_t)ws) & 255)) return fail(MOA_ERR_WORKSPACE, "workspace not 256-byte aligned");
+    if (R == 0) return MOA_OK;
+    LinArgs la = {};
+    la.X = x;
+    la.R = R;
+    la.K = K;
+    la.ldx = K;
+    la.nseg = 1;
+    la.seg[0].W = w;
+    la.seg[0].N = N;
+    la.seg[0].st = row_store(y, N);
+    la.ws = ws;                      // optional: without it a slower kernel takes the short-and-wide shapes
+    la.ws_bytes = ws_bytes;
+    prof_set_site(S_LINEAR);
+    MOA_TRY_HIP(launch_linear(dtype, la, (hipStream_t)stream), "linear");
+    return MOA_OK;
+}
+
 static int32_t draft_step_stages(const moa_step_args_t *a)
 {
     int32_t rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, a->stream);
