@@ -404,6 +404,21 @@ def main():
                    sample=f"the whole {cfg.name} step once (all {tokens} tree tokens, {NL} verify layer(s)), fp64, "
                           f"{c1 - c0:.2f} s",
                    seconds=round(c1 - c0, 3), stage_seconds={k: round(v, 4) for k, v in tm.items()})
+        # the same once more on a single thread when that stays within the budget of this leg (~30 s)
+        if (c1 - c0) * cores <= 30.0:
+            import ctypes
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            s0 = time.perf_counter()
+            run_step(works[0])
+            s1 = time.perf_counter()
+            gomp.omp_set_num_threads(cores)
+            cpu["one_thread"] = dict(value=round(tokens / (s1 - s0), 3), seconds=round(s1 - s0, 3))
+        try:
+            model = next(l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name"))
+        except (OSError, StopIteration):
+            model = "unknown"
+        cpu["host"] = dict(cpu_model=model, logical_cpus=os.cpu_count())
 
     out = {
         "metric": "draft-tree tokens/sec (draft step + verify attn) at Llama-3-8B shape; % HBM peak",
