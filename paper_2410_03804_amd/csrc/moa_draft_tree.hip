@@ -45,7 +45,8 @@ __global__ __launch_bounds__(256) void k_tree_expand(int level, int Bw, int n_ma
     __syncthreads();                                       // every read of the old frontier is done
     if (t < n) {
         int rank = 0;
-        for (int u = 0; u < n; ++u) rank += ranks_before(lp[u], u, mine, t) ? 1 : 0;
+#pragma unroll 8
+        for (int u = 0; u < n; ++u) rank += ranks_before(lp[u], u, mine, t) ? 1 : 0;     // unrolled: LDS reads in flight together
         if (rank < Bw) fr[rank] = base + t;
     }
 }
@@ -74,6 +75,7 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
     for (int c = c0; c < c1; ++c) {
         const float v = lp[c];
         int rank = 0;
+#pragma unroll 8
         for (int u = 0; u < n; ++u) rank += ranks_before(lp[u], u, v, c) ? 1 : 0;
         const bool k = rank < keep;
         node_of[c] = k ? 1 : 0;
@@ -234,6 +236,7 @@ __global__ __launch_bounds__(256) void k_topk_merge(int Bw, int S, const float *
         const int id = ci[c];
         if (id == 0x7fffffff) continue;                    // an exhausted slice's filler
         int rank = 0;
+#pragma unroll 8
         for (int u = 0; u < n; ++u) rank += ranks_before(cv[u], ci[u], v, id) ? 1 : 0;
         if (rank < Bw) { tok[r * Bw + rank] = id; logp[r * Bw + rank] = v - lse; }
     }
