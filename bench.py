@@ -62,6 +62,8 @@ def parse():
     ap.add_argument("--with-sa", action="store_true",
                     help="run the drafter's Self-Attention layer in front of the cross-attention (its output becomes "
                          "the CA queries); not part of the headline step")
+    ap.add_argument("--no-fold", action="store_true",
+                    help="keep the memory's K/V projection a launch of its own instead of folding ca_wk/ca_wv with lsa_wo")
     ap.add_argument("--tli-layers", type=int, default=0,
                     help="after the timed region, also time this many reused LLM decoder layers (Target Layer Inference) "
                          "on the tree tokens, each with its own weights; reported under 'tli', not in the headline")
@@ -83,7 +85,7 @@ def lsa_token_count(cfg, lsa_tokens):
     return cfg.B * int(lsa_tokens)
 
 
-def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree", with_sa=False):
+def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree", with_sa=False, fold=True):
     """Algorithmic bytes and flops per launch site for one step: what the call must read and write once
     (inputs, weights, caches, outputs) and 2*MACs of the contractions as defined."""
     es = 2 if cfg.dtype == "bf16" else 4
@@ -103,7 +105,8 @@ def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree", with_sa=Fal
     c["lsa.qkv_proj"] = lin(Tl * L, d_in, eq + 2 * ekv)
     c["lsa.layer_attn"] = dict(bytes=(Tl * L * (eq + 2 * ekv) + Tl * eq) * es,
                                flops=2.0 * Tl * cfg.lsa_heads * L * L * dh + 2.0 * Tl * cfg.lsa_heads * L * dh)
-    c["lsa.o_proj"] = lin(Tl, eq, eq)
+    folded = fold and schedule != "sequential" and Tl <= 4096       # one launch: LSA output + the memory's new K/V rows
+    c["lsa.o_proj"] = lin(Tl, eq, eq + 2 * ekv) if folded else lin(Tl, eq, eq)
     c["ca_append.kv_proj"] = lin(Tl, eq, 2 * ekv)
     c["ca_append.lengths"] = dict(bytes=B * 12, flops=0.0)
     c["ca.q_proj"] = lin(T, d, E)
@@ -237,7 +240,7 @@ def main():
     sets = []
     ws = None
     for w in works:
-        s = DeviceStep(w, n_len_slots=slots, ws=ws)
+        s = DeviceStep(w, n_len_slots=slots, ws=ws, fold=not args.no_fold)
         ws = s.ws
         sets.append(s)
     torch.cuda.synchronize()
@@ -343,7 +346,7 @@ def main():
     tokens = cfg.B * cfg.M
     value = tokens / (ms_per_step * 1e-3)
 
-    costs = site_costs(cfg, NL, schedule=args.schedule, lsa_tokens=lsa_tokens, with_sa=args.with_sa)
+    costs = site_costs(cfg, NL, schedule=args.schedule, lsa_tokens=lsa_tokens, with_sa=args.with_sa, fold=not args.no_fold)
     peak_mm = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else VEC_F32_PEAK_TFLOPS
     pieces = []
     for site, kern, n, ms in sorted(rows, key=lambda r: -r[3]):

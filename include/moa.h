@@ -274,6 +274,11 @@ int32_t moa_linear_workspace_bytes(int32_t dtype, int64_t R, int32_t K, int32_t 
 int32_t moa_linear(int32_t dtype, const void *x, int64_t R, int32_t K, const void *w, int32_t N, void *y,
                    void *ws, size_t ws_bytes, void *stream);
 
+/* out [N, K] = w_outer [N, J] w_inner [J, K]: the product of two projection matrices that are applied
+ * one after the other, computed once (fp32 accumulation, result in `dtype`).  Not on the hot path. */
+int32_t moa_fold_projection(int32_t dtype, const void *w_outer, const void *w_inner, int32_t N, int32_t J,
+                            int32_t K, void *out, void *stream);
+
 /* One pass of the whole path on one stream (Alg. 1, one iteration of the outer loop with the
  * tree form of drafting): tree mask -> LSA of T_lsa new tokens -> CA memory append ->
  * CA of Mq query rows per sequence -> n_verify_layers tree-verify attentions -> accept walk;
@@ -333,6 +338,11 @@ typedef struct {
     int32_t sa_P_cap;
     void *sa_k_draft, *sa_v_draft;                /* [B, Hkv_sa, M, dh] per-cycle draft cache (out)  */
     void *sa_out;                                 /* [B, M, d]: the CA's queries                     */
+    /* optional: the products ca_wk lsa_wo and ca_wv lsa_wo ([Hkv*dh, H_l*dh], computed once with
+     * moa_fold_projection).  With both, the grouped and two-stream schedules project the memory's new
+     * keys / values straight from LSA's mean-folded heads in the launch that also applies lsa_wo
+     * ((a Wo^T) Wk^T = a (Wk Wo)^T, exact in real arithmetic); lsa_out is still written.            */
+    const void *ca_wk_lsa_wo, *ca_wv_lsa_wo;
 } moa_step_args_t;
 
 int32_t moa_draft_step(const moa_step_args_t *args);

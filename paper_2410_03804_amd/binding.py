@@ -61,6 +61,7 @@ class _StepArgs(C.Structure):
         ("sa_wq", C.c_void_p), ("sa_wk", C.c_void_p), ("sa_wv", C.c_void_p), ("sa_wo", C.c_void_p),
         ("sa_kcache", C.c_void_p), ("sa_vcache", C.c_void_p), ("sa_P_cap", C.c_int32),
         ("sa_k_draft", C.c_void_p), ("sa_v_draft", C.c_void_p), ("sa_out", C.c_void_p),
+        ("ca_wk_lsa_wo", C.c_void_p), ("ca_wv_lsa_wo", C.c_void_p),
     ]
 
 
@@ -69,7 +70,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
             "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
-            "moa_msg_unpack_accept", "moa_linear_workspace_bytes", "moa_linear", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_msg_unpack_accept", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -110,7 +111,8 @@ _lib.moa_msg_pack_accept.argtypes = [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp,
 _lib.moa_msg_unpack_accept.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.moa_linear_workspace_bytes.argtypes = [_i32, _i64, _i32, _i32, C.POINTER(_sz)]
 _lib.moa_linear.argtypes = [_i32, _vp, _i64, _i32, _vp, _i32, _vp, _vp, _sz, _vp]
-for _n in _SYMBOLS[2:26]:
+_lib.moa_fold_projection.argtypes = [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp]
+for _n in _SYMBOLS[2:27]:
     getattr(_lib, _n).restype = C.c_int32
 
 
@@ -418,6 +420,18 @@ def linear(x, w, y, ws=None, stream=None):
                            wsp, wsb, _stream(stream)))
 
 
+def fold_projection(w_outer, w_inner, out=None, stream=None):
+    """out [N, K] = w_outer [N, J] @ w_inner [J, K] (two projections applied one after the other, folded once)."""
+    N, J = w_outer.shape
+    K = w_inner.shape[1]
+    if out is None:
+        out = torch.empty((N, K), dtype=w_outer.dtype, device=w_outer.device)
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}[w_outer.dtype]
+    _check(_lib.moa_fold_projection(dtype, _dev(w_outer, w_outer.dtype, N * J, "w_outer"), _dev(w_inner, w_outer.dtype, J * K, "w_inner"),
+                                    N, J, K, _dev(out, w_outer.dtype, N * K, "out"), _stream(stream)))
+    return out
+
+
 def _ptr_array(tensors, dtype, numel, name):
     arr = (C.c_void_p * len(tensors))()
     for i, t in enumerate(tensors):
@@ -428,12 +442,14 @@ def _ptr_array(tensors, dtype, numel, name):
 
 def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len,
                ca_P_cap, ca_xq, ca_out, v_x, v_w, v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, P_cap,
-               tok, tgt, path, n_path, bonus, ws, dev_status=None, schedule=0, sa=None):
+               tok, tgt, path, n_path, bonus, ws, dev_status=None, schedule=0, sa=None, folded=None):
     """Marshal (and size-check) the arguments of moa_draft_step once; the returned plan can be run many times.
     lsa_w = dict(wq, wk, wv, wo); ca_w = dict(wq, wo, wk, wv); v_w = list (one per verified layer) of
     dict(wq, wk, wv, wo); v_* = lists of per-layer tensors.  The plan keeps the tensors alive.
     sa (optional) = dict(shape, emb, w=dict(wq, wk, wv, wo), kcache, vcache, P_cap, k_draft, v_draft, out): the
-    Self-Attention layer in front of the cross-attention (ca_xq may then be None)."""
+    Self-Attention layer in front of the cross-attention (ca_xq may then be None).
+    folded (optional) = (ca_wk @ lsa_wo, ca_wv @ lsa_wo) from fold_projection: the memory append then shares the LSA
+    output projection's launch."""
     dt, i32 = _TORCH_DTYPE[shape.dtype], torch.int32
     B, M = parent.shape
     Mq = ca_xq.shape[1]
@@ -490,6 +506,9 @@ def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out
     a.dev_status = _dev(dev_status, i32, 1, "dev_status")
     a.ws, a.ws_bytes = _ws(ws)
     a.schedule = int(schedule)
+    if folded is not None:
+        a.ca_wk_lsa_wo = _dev(folded[0], dt, ekv * eq, "ca_wk lsa_wo")
+        a.ca_wv_lsa_wo = _dev(folded[1], dt, ekv * eq, "ca_wv lsa_wo")
     if sa is not None:
         ssh = sa["shape"]
         ekv_s = ssh.n_kv_heads * dh
@@ -506,7 +525,7 @@ def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out
         a.sa_v_draft = _dev(sa["v_draft"], dt, B * ekv_s * M, "sa v_draft")
         a.sa_out = _dev(sa["out"], dt, B * M * d, "sa out")
         keep = keep + [ssh]
-    tensors = [sa, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
+    tensors = [sa, folded, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
                v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, tok, tgt, path, n_path, bonus, ws, dev_status]
     return StepPlan(a, shape, keep, tensors)
 

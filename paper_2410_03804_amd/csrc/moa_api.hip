@@ -103,7 +103,9 @@ size_t lsa_ws_bytes(const moa_shape_t *s, int64_t T)
     const size_t eq = (size_t)s->lsa_q_heads * s->head_dim, ekv = (size_t)s->lsa_kv_heads * s->head_dim;
     // the projections of a short chunk (the first and the last one can be) stream the weights and keep partial sums
     const int64_t tail = T % LSA_CHUNK;
-    size_t lin = linear_workspace_bytes(s->dtype, ob, (int)eq, (int)eq);
+    // the output projection may carry the memory's folded K/V projections as two more segments (draft step)
+    size_t lin = linear_workspace_bytes(s->dtype, ob, (int)eq, (int)(eq + 2 * (size_t)s->n_kv_heads * s->head_dim));
+    lin = max2(lin, linear_workspace_bytes(s->dtype, ob, (int)eq, (int)eq));
     lin = max2(lin, linear_workspace_bytes(s->dtype, tc * s->n_layers, s->d_lsa_in, (int)(eq + 2 * ekv)));
     if (tail) lin = max2(lin, linear_workspace_bytes(s->dtype, tail * s->n_layers, s->d_lsa_in, (int)(eq + 2 * ekv)));
     return align256((size_t)tc * s->n_layers * (eq + 2 * ekv) * esize(s->dtype)) + align256((size_t)ob * eq * esize(s->dtype)) +
@@ -237,6 +239,16 @@ int32_t moa_tree_accept(const int32_t *parent, const int32_t *tok, const int32_t
     return MOA_OK;
 }
 
+}  // extern "C"
+
+// Segments a caller inside the library adds to the LSA output projection's launch (same activations: the
+// mean-folded heads); only honoured when all tokens fall into one output-projection block.  *taken reports it.
+static thread_local const LinSeg *t_lsa_extra = nullptr;
+static thread_local int t_lsa_nextra = 0;
+static thread_local bool t_lsa_extra_taken = false;
+
+extern "C" {
+
 int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk,
                 const void *wv, const void *wo, void *out, void *ws, size_t ws_bytes, void *stream)
 {
@@ -314,6 +326,10 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
             lo.seg[0].W = wo;
             lo.seg[0].N = eq;
             lo.seg[0].st = row_store((char *)out + (size_t)b0 * eq * es, eq);
+            if (t_lsa_nextra > 0 && T <= LSA_OBLOCK) {
+                for (int i = 0; i < t_lsa_nextra && lo.nseg < 4; ++i) lo.seg[lo.nseg++] = t_lsa_extra[i];
+                t_lsa_extra_taken = true;
+            }
             lo.ws = lin_ws;
             lo.ws_bytes = lin_ws_bytes;
             prof_set_site(S_LSA_OPROJ);
@@ -749,6 +765,16 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     return MOA_OK;
 }
 
+int32_t moa_fold_projection(int32_t dtype, const void *w_outer, const void *w_inner, int32_t N, int32_t J, int32_t K,
+                            void *out, void *stream)
+{
+    if (!w_outer || !w_inner || !out) return fail(MOA_ERR_NULL, "fold_projection: NULL pointer");
+    if (dtype != MOA_F32 && dtype != MOA_BF16) return fail(MOA_ERR_DTYPE, "dtype %d", dtype);
+    if (N < 1 || J < 1 || K < 1) return fail(MOA_ERR_SHAPE, "fold_projection: N=%d J=%d K=%d", N, J, K);
+    MOA_TRY_HIP(launch_fold_weights(dtype, w_outer, w_inner, N, J, K, out, (hipStream_t)stream), "fold_projection");
+    return MOA_OK;
+}
+
 int32_t moa_linear_workspace_bytes(int32_t dtype, int64_t R, int32_t K, int32_t N, size_t *bytes_host)
 {
     if (!bytes_host) return fail(MOA_ERR_NULL, "linear_workspace_bytes: bytes_host is NULL");
@@ -858,7 +884,7 @@ static int32_t piece_small(const moa_step_args_t *a, const StepBufs &bf, hipStre
 // with_small: the integer work rides in spare workgroups at the end of this launch's grid instead of being a
 // launch of its own (nothing before the LSA chain's append and the attention cores needs its results)
 static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st,
-                                 bool with_small)
+                                 bool with_small, void *own_partials = nullptr)
 {
     const moa_shape_t *sh = a->shape;
     const int dh = sh->head_dim, Hkv = sh->n_kv_heads, d = sh->d_model, M = a->M;
@@ -888,6 +914,10 @@ static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, v
         la.rider = small_args(a, bf);
         la.rider_units = 2 * a->B + 1;
     }
+    if (own_partials) {          // partial sums in a region nobody else uses: their summing pass may ride in the next launch
+        la.ws = own_partials;
+        la.defer_reduce = 1;
+    }
     prof_set_site(S_PAIR_QKV);
     MOA_TRY_HIP(launch_linear(sh->dtype, la, st), "draft_step: projections");
     return MOA_OK;
@@ -898,9 +928,6 @@ static int32_t piece_lsa_append(const moa_step_args_t *a, const StepBufs &bf, vo
 {
     const moa_shape_t *sh = a->shape;
     const int dh = sh->head_dim, Hkv = sh->n_kv_heads, ekv = Hkv * dh, dt = sh->dtype;
-    int32_t rc = moa_lsa(sh, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, scr, scr_bytes, st);
-    if (rc || a->T_lsa <= 0) return rc;
-    const int d_mem = sh->lsa_q_heads * dh;
     StoreSpec sp = {};
     sp.mode = StoreSpec::APPEND;
     sp.heads = Hkv;
@@ -910,6 +937,28 @@ static int32_t piece_lsa_append(const moa_step_args_t *a, const StepBufs &bf, vo
     sp.row_base = bf.old_len;
     sp.tok_off = a->tok_off;
     sp.dev_status = a->dev_status;
+    // With the products ca_wk lsa_wo and ca_wv lsa_wo at hand, the memory's keys / values are projected straight from
+    // the mean-folded heads, in the launch that also projects the LSA output: (a Wo^T) Wk^T = a (Wk Wo)^T.
+    LinSeg folded[2] = {};
+    const bool fold = a->ca_wk_lsa_wo && a->ca_wv_lsa_wo && a->lsa_wo && a->ca_wk && a->ca_wv;
+    if (fold) {
+        const void *wf[2] = {a->ca_wk_lsa_wo, a->ca_wv_lsa_wo};
+        void *dstf[2] = {a->ca_k, a->ca_v};
+        for (int i = 0; i < 2; ++i) {
+            folded[i].W = wf[i];
+            folded[i].N = ekv;
+            folded[i].st = sp;
+            folded[i].st.dst = dstf[i];
+        }
+        t_lsa_extra = folded;
+        t_lsa_nextra = 2;
+    }
+    t_lsa_extra_taken = false;
+    int32_t rc = moa_lsa(sh, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, scr, scr_bytes, st);
+    t_lsa_extra = nullptr;
+    t_lsa_nextra = 0;
+    if (rc || a->T_lsa <= 0 || (t_lsa_extra_taken && !g_dry)) return rc;
+    const int d_mem = sh->lsa_q_heads * dh;
     LinArgs la = {};
     la.X = a->lsa_out;
     la.R = a->T_lsa;
@@ -1003,10 +1052,17 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
     const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
     char *scr = nullptr;
     const StepBufs bf = carve_step_bufs(a, L, &scr);
-    int32_t rc = piece_projections(a, bf, scr, L.scratch, st, true);
+    // With room for a second scratch region the projections keep their partial sums there, and the pass that adds them
+    // up rides in the LSA projection's launch (which does not depend on it) instead of being a launch of its own.
+    const bool defer = a->T_lsa > 0 && a->ws_bytes >= L.total() + L.scratch;
+    int32_t rc = piece_projections(a, bf, scr, L.scratch, st, true, defer ? scr + L.scratch : nullptr);
     if (rc) return rc;
     rc = piece_lsa_append(a, bf, scr, L.scratch, st);
-    if (rc) return rc;
+    {   // nothing rode along (or the LSA stage failed): add the slices up now, so that nothing stays pending
+        const hipError_t ef = g_dry ? hipSuccess : launch_linear_flush(st);
+        if (rc) return rc;
+        if (ef != hipSuccess) return hip_fail(ef, "draft_step: projections");
+    }
     const AttnArgs ca = piece_ca_core_args(a, bf, scr, L.attn_each);
     const AttnArgs ve = piece_verify_core_args(a, bf, scr + L.attn_each, L.attn_each);
     prof_set_site(S_PAIR_CORE);

@@ -140,6 +140,35 @@ __global__ __launch_bounds__(256) void k_add_out(const float *__restrict__ h, co
     if (idx < n) st<T>(out + idx, h[idx] + ld<T>(t + idx));
 }
 
+// out[n, k] = sum_j a[n, j] b[j, k]: the product of two projection matrices applied one after the other.  Run once
+// per pair of weights, so a plain LDS-tiled kernel with fp32 accumulation.
+template <typename T>
+__global__ __launch_bounds__(256) void k_fold_weights(const T *__restrict__ a, const T *__restrict__ b, int N, int J, int K,
+                                                      T *__restrict__ out)
+{
+    __shared__ float as[16][17], bs[16][17];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int n = blockIdx.y * 16 + ty, k = blockIdx.x * 16 + tx;
+    float acc = 0.f;
+    for (int j0 = 0; j0 < J; j0 += 16) {
+        as[ty][tx] = (n < N && j0 + tx < J) ? ld<T>(a + (int64_t)n * J + j0 + tx) : 0.f;
+        bs[ty][tx] = (j0 + ty < J && k < K) ? ld<T>(b + (int64_t)(j0 + ty) * K + k) : 0.f;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc += as[ty][j] * bs[j][tx];
+        __syncthreads();
+    }
+    if (n < N && k < K) st<T>(out + (int64_t)n * K + k, acc);
+}
+
+hipError_t launch_fold_weights(int dtype, const void *a, const void *b, int N, int J, int K, void *out, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((K + 15) / 16), (unsigned)((N + 15) / 16));
+    if (dtype == DT_BF16) hipLaunchKernelGGL(k_fold_weights<bf16_t>, grid, dim3(256), 0, stream, (const bf16_t *)a, (const bf16_t *)b, N, J, K, (bf16_t *)out);
+    else hipLaunchKernelGGL(k_fold_weights<float>, grid, dim3(256), 0, stream, (const float *)a, (const float *)b, N, J, K, (float *)out);
+    return hipGetLastError();
+}
+
 hipError_t launch_rmsnorm(int dtype, const void *x, const void *res, int64_t R, int d, const void *g, float eps,
                           float *h_out, void *n_out, hipStream_t stream)
 {

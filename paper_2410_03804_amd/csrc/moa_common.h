@@ -156,10 +156,16 @@ struct LinArgs {
     int epi;
     const float *epi_res;
     void *epi_out;
+    // Weight-streaming path only: leave the summing of the K slices pending instead of launching it.  The next
+    // launch_linear on this thread and stream carries it in spare workgroups if it runs the tiled kernel (the sums
+    // are then ready when that launch has finished), otherwise it is launched first; launch_linear_flush launches
+    // whatever is still pending.  The partial sums (ws) must stay untouched until then.
+    int defer_reduce;
 };
 
 // Y_s = X_s W_s^T for up to four weight matrices (one launch on the fast paths; segments usually share X).
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream);
+hipError_t launch_linear_flush(hipStream_t stream);
 // scratch the fast weight-streaming path wants for R rows and ntot output features in total (0 = not used)
 size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot);
 
@@ -210,6 +216,7 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *res, int64_t R, 
                           float *h_out, void *n_out, hipStream_t stream);
 hipError_t launch_rope(int dtype, void *q, void *k_draft, const int32_t *prefix_len, const int32_t *depth, int B, int Mn,
                        int M, int node0, int H, int Hkv, int dh, double theta, int P_cap, hipStream_t stream);
+hipError_t launch_fold_weights(int dtype, const void *a, const void *b, int N, int J, int K, void *out, hipStream_t stream);
 hipError_t launch_swiglu(int dtype, const void *gu, int64_t R, int d_ff, void *act, hipStream_t stream);
 hipError_t launch_add_out(int dtype, const float *h, const void *t, int64_t n, void *out, hipStream_t stream);
 

@@ -289,12 +289,12 @@ __device__ __forceinline__ u32x4 pack8(const f32x4 &lo, const f32x4 &hi)
     return pk;
 }
 
-__global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
+__device__ __forceinline__ void splitk_reduce_block(const SplitKArgs &sa, int block)
 {
     const LinArgs &a = sa.a;
     const int width = a.epi == LinArgs::EPI_SWIGLU ? sa.ntot / 2 : sa.ntot;   // features a row of threads walks
     const int per = width / 8;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = (int64_t)block * 256 + threadIdx.x;
     if (idx >= a.R * per) return;
     const int64_t r = idx / per;
     const int nt = (int)(idx - r * per) * 8;          // feature in the concatenated space
@@ -334,6 +334,16 @@ __global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa)
     if (off < 0) return;
     *(u32x4 *)((bf16_t *)a.seg[s].st.dst + off) = pack8(lo, hi);
 }
+
+__global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa) { splitk_reduce_block(sa, (int)blockIdx.x); }
+
+// a summing pass left pending by LinArgs::defer_reduce
+static thread_local struct {
+    bool valid;
+    SplitKArgs ka;
+    int blocks;
+    hipStream_t stream;
+} t_pending = {};
 
 // The weight-streaming kernel walks 64-row tiles with the weights in registers.  Its fp32 partial sums are
 // (row tiles * 128 / K slice) of the weight bytes.  Up to two row tiles it is always used (K slices chosen for the
@@ -380,7 +390,10 @@ struct TiledArgs {
     LinArgs a;
     int tile_begin[5];
     int tiles_per_xcd;   // feature tiles owned by one XCD
-    int lead_blocks;     // workgroups in front of the projection's own (LinArgs::rider, padded to the XCD count)
+    int lead_blocks;     // workgroups in front of the projection's own: LinArgs::rider, then a pending summing pass
+    int small_lead;      // the first of them carry LinArgs::rider (padded to the XCD count)
+    int red_blocks;      // workgroups of the pending summing pass `red` (0 = none)
+    SplitKArgs red;
 };
 
 // WF x WR = 32x32 MFMA blocks per wave along features x rows; the four waves sit 2 x 2, so the workgroup
@@ -403,9 +416,13 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
     extern __shared__ __attribute__((aligned(16))) bf16_t tsm[];   // [2][STAGE]
 
     const LinArgs &a = ta.a;
-    if ((int)blockIdx.x < ta.lead_blocks) {        // the first workgroups of the grid carry the integer work
-        if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
-            step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)tsm, (int32_t *)tsm + MOA_MAX_TREE);
+    if ((int)blockIdx.x < ta.lead_blocks) {        // the first workgroups of the grid carry work of other calls
+        if ((int)blockIdx.x < ta.small_lead) {
+            if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
+                step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)tsm, (int32_t *)tsm + MOA_MAX_TREE);
+        } else if ((int)blockIdx.x - ta.small_lead < ta.red_blocks) {
+            splitk_reduce_block(ta.red, (int)blockIdx.x - ta.small_lead);
+        }
         return;
     }
     const int bx = (int)blockIdx.x - ta.lead_blocks;
@@ -527,7 +544,14 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
     for (int s = 0; s < a.nseg; ++s) { ta.tile_begin[s] = t; t += a.seg[s].N / BN; }
     ta.tile_begin[a.nseg] = t;
     ta.tiles_per_xcd = (t + 7) / 8;
-    ta.lead_blocks = (a.rider_units + 7) & ~7;      // a multiple of the XCD count: the tile mapping keeps its phase
+    ta.small_lead = (a.rider_units + 7) & ~7;       // multiples of the XCD count: the tile mapping keeps its phase
+    ta.red_blocks = 0;
+    if (t_pending.valid && t_pending.stream == stream) {      // carry the pending summing pass of an earlier projection
+        ta.red = t_pending.ka;
+        ta.red_blocks = t_pending.blocks;
+        t_pending.valid = false;
+    }
+    ta.lead_blocks = ta.small_lead + ((ta.red_blocks + 7) & ~7);
     const dim3 grid((unsigned)(ta.lead_blocks + 8 * ta.tiles_per_xcd * (int)((a.R + BM - 1) / BM)));
     const size_t lds = (size_t)2 * (BN + BM) * 64 * sizeof(bf16_t);
     hipError_t e = hipFuncSetAttribute((const void *)k_linear_tiled_bf16<WF, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -625,6 +649,14 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
             if (e != hipSuccess) return e;
             const int64_t items = a.R * ((a.epi == LinArgs::EPI_SWIGLU ? ntot / 2 : ntot) / 8);
             *fused = a.epi != LinArgs::EPI_NONE;
+            if (a.defer_reduce) {                    // someone else launches (or carries) the summing pass
+                ka.a.rider_units = 0;
+                t_pending.valid = true;
+                t_pending.ka = ka;
+                t_pending.blocks = (int)((items + 255) / 256);
+                t_pending.stream = stream;
+                return hipSuccess;
+            }
             prof_begin(K_LIN_REDUCE, stream);
             MOA_KLAUNCH(k_linear_splitk_reduce, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, ka);
             prof_end(stream);
@@ -655,8 +687,36 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
     return hipSuccess;
 }
 
+hipError_t launch_linear_flush(hipStream_t stream)
+{
+    if (!t_pending.valid) return hipSuccess;
+    t_pending.valid = false;
+    prof_begin(K_LIN_REDUCE, t_pending.stream);
+    MOA_KLAUNCH(k_linear_splitk_reduce, dim3((unsigned)t_pending.blocks), dim3(256), 0, t_pending.stream, t_pending.ka);
+    prof_end(t_pending.stream);
+    (void)stream;
+    return hipGetLastError();
+}
+
+// the tiled kernel is the one that can carry a pending summing pass: same conditions as in launch_linear_impl
+static bool takes_tiled_kernel(int dtype, const LinArgs &a)
+{
+    if (dtype != DT_BF16 || a.R <= 0 || a.K % 128 || a.ldx % 8 || !aligned16(a.X) || splitk_plan(a.R, a.K)) return false;
+    for (int s = 0; s < a.nseg; ++s) {
+        const StoreSpec &st = a.seg[s].st;
+        if (a.seg[s].X && (a.seg[s].ldx % 8 || !aligned16(a.seg[s].X))) return false;
+        if (a.seg[s].N % 128 || !aligned16(a.seg[s].W) || !aligned16(st.dst)) return false;
+        if (st.mode == StoreSpec::ROW ? st.ld % 8 != 0 : st.dh % 8 != 0) return false;
+    }
+    return true;
+}
+
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
 {
+    if (t_pending.valid && !(t_pending.stream == stream && takes_tiled_kernel(dtype, a))) {
+        const hipError_t ef = launch_linear_flush(stream);
+        if (ef != hipSuccess) return ef;
+    }
     if (a.epi == LinArgs::EPI_ADD_F32 && a.nseg != 1) return hipErrorInvalidValue;
     if (a.epi == LinArgs::EPI_SWIGLU && (a.nseg != 2 || a.seg[0].N != a.seg[1].N)) return hipErrorInvalidValue;
     bool rode = false, fused = false;

@@ -28,7 +28,7 @@ class DeviceStep:
     """All tensors of one step on the GPU.  `n_len_slots` independent copies of the (tiny) cross-attention
     length array let a benchmark run that many steps back to back without resetting anything."""
 
-    def __init__(self, work, n_len_slots: int = 1, ws: torch.Tensor | None = None):
+    def __init__(self, work, n_len_slots: int = 1, ws: torch.Tensor | None = None, fold: bool = True):
         cfg = work["cfg"]
         dt = cfg.dtype
         self.cfg, self.shape = cfg, shape_of(cfg)
@@ -45,6 +45,9 @@ class DeviceStep:
         self.lsa_hs = _dev(work["lsa_hs"], dt)
         self.lsa_out = torch.zeros((T, cfg.d_lsa), dtype=tdt, device="cuda")
         self.ca_w = {k: _dev(v, dt) for k, v in work["ca_w"].items()}
+        # one-time fold of the two projections between LSA's heads and the memory's keys / values
+        self.folded = (moa.fold_projection(self.ca_w["wk"], self.lsa_w["wo"]),
+                       moa.fold_projection(self.ca_w["wv"], self.lsa_w["wo"])) if fold else None
         self.ca_xq = _dev(work["ca_xq"], dt)
         self.ca_k, self.ca_v = _dev(work["ca_k"], dt), _dev(work["ca_v"], dt)
         self.ca_len0 = _dev(work["ca_len0"])
@@ -88,7 +91,7 @@ class DeviceStep:
                 v_w=self.v_w, v_kcache=self.v_kcache, v_vcache=self.v_vcache, v_out=self.v_out, v_ktree=self.v_ktree,
                 v_vtree=self.v_vtree, prefix_len=self.prefix_len, P_cap=self.P_cap, tok=self.tok, tgt=self.tgt,
                 path=self.path, n_path=self.n_path, bonus=self.bonus, ws=self.ws, dev_status=self.dev_status,
-                schedule=schedule, sa=self.sa)
+                schedule=schedule, sa=self.sa, folded=self.folded)
         return self._plans[key]
 
     def run(self, len_slot: int = 0, stream=None, schedule: int = 0):

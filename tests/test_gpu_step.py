@@ -104,18 +104,18 @@ def _step_outputs(step):
     return [t.clone() for t in exact], [t.clone() for t in merged]
 
 
-@pytest.mark.parametrize("case", ["small_bf16", "C1_bf16"])
+@pytest.mark.parametrize("case", ["small_bf16", "C1_bf16", "small_bf16_with_sa"])
 def test_schedules_agree(G, case):
     """The step's result must not depend on how its independent pieces are launched: the two-stream schedule is
     bit-identical to the sequential one; the grouped one too, except that the two attention cores may get another
     number of key slices (their merged outputs then agree to rounding)."""
     from paper_2410_03804_amd.workload import DeviceStep
-    cfg, nlayers = STEP_CASES[case]
-    work = mi.step_workload(cfg, n_verify_layers=nlayers)
+    cfg, nlayers, lsa_tokens, with_sa = _case(case)
+    work = mi.step_workload(cfg, n_verify_layers=nlayers, lsa_tokens=lsa_tokens, with_sa=with_sa)
     outs = {}
     for name in ("sequential", "two_stream", "two_stream", "grouped", "grouped"):
         print(f"[case] schedules {case} {name}", flush=True)
-        step = DeviceStep(work)
+        step = DeviceStep(work, fold=False)         # the folded memory projection is another arithmetic: tested below
         step.run(schedule=SCHEDULES[name])
         torch.cuda.synchronize()
         assert step.dev_status.item() == 0
@@ -134,6 +134,29 @@ def test_schedules_agree(G, case):
         assert torch.equal(a, b)                 # and each schedule is deterministic
 
 
+@pytest.mark.parametrize("case", ["small_bf16", "C1_bf16", "C0_f32"])
+def test_folded_memory_projection_agrees_with_the_two_projections(G, case):
+    """With ca_wk lsa_wo and ca_wv lsa_wo folded once, the memory's new rows come straight from LSA's mean-folded heads
+    ((a Wo^T) Wk^T = a (Wk Wo)^T): same rows to rounding, everything else bit for bit."""
+    from paper_2410_03804_amd.workload import DeviceStep
+    cfg, nlayers, lsa_tokens, with_sa = _case(case)
+    work = mi.step_workload(cfg, n_verify_layers=nlayers)
+    res = []
+    for fold in (False, True):
+        step = DeviceStep(work, fold=fold)
+        step.run()
+        torch.cuda.synchronize()
+        assert step.dev_status.item() == 0
+        res.append(step)
+    a, b = res
+    for name in ("lsa_out", "mask", "path", "n_path", "bonus"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    assert torch.equal(a.ca_len[0], b.ca_len[0])
+    for x, y in ((a.ca_k, b.ca_k), (a.ca_v, b.ca_v), (a.ca_out, b.ca_out)):
+        assert torch.allclose(x.float(), y.float(), atol=G.ABS_TOL[cfg.dtype], rtol=G.REL_TOL[cfg.dtype])
+    assert not torch.equal(a.ca_k, b.ca_k) or cfg.dtype == "f32"      # the folded path really ran (bf16 rounds differently)
+
+
 def test_grouped_schedule_full_memory_flags_and_matches_sequential(G):
     """A cross-attention memory that cannot take all new rows: both schedules drop the same rows and raise the
     same device flag."""
@@ -142,7 +165,7 @@ def test_grouped_schedule_full_memory_flags_and_matches_sequential(G):
     work = mi.step_workload(cfg, n_verify_layers=nlayers)
     res = []
     for name in ("sequential", "grouped"):
-        step = DeviceStep(work)
+        step = DeviceStep(work, fold=False)
         step.ca_len[0].fill_(step.ca_P_cap - 5)                      # room for 5 of the M new rows per sequence
         step.run(schedule=SCHEDULES[name])
         torch.cuda.synchronize()
