@@ -31,8 +31,8 @@ VEC_F32_PEAK_TFLOPS = 157.3
 # the default workload only (C1, 2*E_kv-wide LSA input, one verify layer).
 PMC_TRAFFIC_MIB_C1 = {
     "k_linear_splitk_bf16<4>": 89.99,     # mean of the two grouped launches of the default schedule
-    "k_linear_splitk_bf16<2>": 12.08,
-    "k_linear_tiled_bf16<2, 2>": 93.01,
+    "k_linear_splitk_bf16<2>": 23.83,
+    "k_linear_tiled_bf16<2, 2>": 111.51,
     "k_attn_fused<128, 8>": 10.28,
 }
 
