@@ -10,9 +10,10 @@ import paper_2410_03804_amd as moa
 
 TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
 MDT = {"f32": moa.F32, "bf16": moa.BF16}
-# the benchmark spec bounds (max-abs against the fp64 oracle)
+# absolute bounds (max-abs against the fp64 oracle): fp32 and bf16 storage
 ABS_TOL = {"f32": 1e-4, "bf16": 2e-2}
-# tighter relative bound (max-abs / rms of the oracle), derived in the design doc from the arithmetic
+# tighter relative bound (max-abs / rms of the oracle): a few units of the storage type's rounding step, times the
+# growth of rounding error over the sums on the path
 REL_TOL = {"f32": 5e-5, "bf16": 3e-2}
 
 
