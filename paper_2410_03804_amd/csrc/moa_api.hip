@@ -247,91 +247,134 @@ static thread_local const LinSeg *t_lsa_extra = nullptr;
 static thread_local int t_lsa_nextra = 0;
 static thread_local bool t_lsa_extra_taken = false;
 
-extern "C" {
-
-int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk,
-                const void *wv, const void *wo, void *out, void *ws, size_t ws_bytes, void *stream)
+// ---- the LSA stage in pieces: moa_lsa runs them in order; the grouped draft step puts other launches between them
+static int32_t lsa_check(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk,
+                         const void *wv, const void *out, const void *ws, size_t ws_bytes)
 {
     int32_t rc = check_shape(shape, true);
     if (rc) return rc;
     if (!hs || !out) return fail(MOA_ERR_NULL, "lsa: hs / out is NULL");
     if (T < 0) return fail(MOA_ERR_SHAPE, "lsa: T=%lld", (long long)T);
     const int L = shape->n_layers, dh = shape->head_dim, d_in = shape->d_lsa_in;
-    const int eq = shape->lsa_q_heads * dh, ekv = shape->lsa_kv_heads * dh, dt = shape->dtype;
+    const int eq = shape->lsa_q_heads * dh, ekv = shape->lsa_kv_heads * dh;
     if ((!wq && eq != d_in) || (!wk && ekv != d_in) || (!wv && ekv != d_in))
         return fail(MOA_ERR_SHAPE, "lsa: NULL weight needs matching widths (d_in=%d, H_l*dh=%d, Hkv_l*dh=%d)", d_in, eq, ekv);
-    if (lsa_attn_lds_bytes(dt, L, dh) > 150 * 1024)
+    if (lsa_attn_lds_bytes(shape->dtype, L, dh) > 150 * 1024)
         return fail(MOA_ERR_SHAPE, "lsa: L=%d x head_dim=%d does not fit the LDS-resident score tile", L, dh);
     if (T == 0) return MOA_OK;
-    rc = check_ws(ws, ws_bytes, lsa_ws_bytes(shape, T));
-    if (rc) return rc;
+    return check_ws(ws, ws_bytes, lsa_ws_bytes(shape, T));
+}
+
+struct LsaBufs {
+    char *qkv;        // [chunk tokens * L, eq + 2 ekv] projected rows of one chunk
+    char *abar0;      // [output block tokens, eq] mean-folded heads
+    char *lin_ws;     // partial sums of the projections
+    size_t lin_ws_bytes;
+};
+
+static LsaBufs lsa_carve(const moa_shape_t *shape, int64_t T, void *ws, size_t ws_bytes)
+{
+    const size_t es = esize(shape->dtype);
+    const int eq = shape->lsa_q_heads * shape->head_dim, ekv = shape->lsa_kv_heads * shape->head_dim;
+    const int64_t tc_max = T < LSA_CHUNK ? T : LSA_CHUNK, ob_max = T < LSA_OBLOCK ? T : LSA_OBLOCK;
+    LsaBufs b;
+    b.qkv = (char *)ws;
+    b.abar0 = b.qkv + align256((size_t)tc_max * shape->n_layers * (eq + 2 * ekv) * es);
+    b.lin_ws = b.abar0 + align256((size_t)ob_max * eq * es);
+    b.lin_ws_bytes = ws_bytes - (size_t)(b.lin_ws - (char *)ws);
+    return b;
+}
+
+// tokens t0 .. t0 + tc: the Q/K/V projection (la->nseg == 0: nothing to project) and the attention over the layers
+// that follows it.  The attention writes the mean-folded heads into `abar`.
+static void lsa_chunk_args(const moa_shape_t *shape, const void *hs, int64_t t0, int64_t tc, const void *wq,
+                           const void *wk, const void *wv, void *abar, const LsaBufs &b, LinArgs *la, LsaAttnArgs *aa)
+{
+    const int L = shape->n_layers, dh = shape->head_dim, d_in = shape->d_lsa_in;
+    const int eq = shape->lsa_q_heads * dh, ekv = shape->lsa_kv_heads * dh, wide = eq + 2 * ekv;
+    const size_t es = esize(shape->dtype);
+    const char *x = (const char *)hs + (size_t)t0 * L * d_in * es;
+    *la = LinArgs{};
+    la->X = x;
+    la->R = tc * L;
+    la->K = d_in;
+    la->ldx = d_in;
+    la->ws = b.lin_ws;
+    la->ws_bytes = b.lin_ws_bytes;
+    *aa = LsaAttnArgs{};
+    aa->dtype = shape->dtype;
+    auto add = [&](const void *w, int n, int col, const void **ptr, int64_t *ldp) {
+        if (w) {
+            la->seg[la->nseg].W = w;
+            la->seg[la->nseg].N = n;
+            la->seg[la->nseg].st = row_store(b.qkv + (size_t)col * es, wide);
+            ++la->nseg;
+            *ptr = b.qkv + (size_t)col * es;
+            *ldp = wide;
+        } else {
+            *ptr = x;
+            *ldp = d_in;
+        }
+    };
+    add(wq, eq, 0, &aa->q, &aa->ldq);
+    add(wk, ekv, eq, &aa->k, &aa->ldk);
+    add(wv, ekv, eq + ekv, &aa->v, &aa->ldv);
+    aa->T = tc;
+    aa->L = L;
+    aa->Hq = shape->lsa_q_heads;
+    aa->Hkv = shape->lsa_kv_heads;
+    aa->dh = dh;
+    aa->abar = abar;
+}
+
+// W_o on `rows` mean-folded tokens starting at token b0, plus up to three more segments on the same activations
+static LinArgs lsa_oproj_args(const moa_shape_t *shape, int64_t b0, int64_t rows, const void *wo, void *out,
+                              const LsaBufs &b, const LinSeg *extra, int nextra)
+{
+    const int eq = shape->lsa_q_heads * shape->head_dim;
+    LinArgs lo = {};
+    lo.X = b.abar0;
+    lo.R = rows;
+    lo.K = eq;
+    lo.ldx = eq;
+    lo.nseg = 1;
+    lo.seg[0].W = wo;
+    lo.seg[0].N = eq;
+    lo.seg[0].st = row_store((char *)out + (size_t)b0 * eq * esize(shape->dtype), eq);
+    for (int i = 0; i < nextra && lo.nseg < 4; ++i) lo.seg[lo.nseg++] = extra[i];
+    lo.ws = b.lin_ws;
+    lo.ws_bytes = b.lin_ws_bytes;
+    return lo;
+}
+
+extern "C" {
+
+int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk,
+                const void *wv, const void *wo, void *out, void *ws, size_t ws_bytes, void *stream)
+{
+    int32_t rc = lsa_check(shape, hs, T, wq, wk, wv, out, ws, ws_bytes);
+    if (rc || T == 0) return rc;
+    const int dt = shape->dtype, eq = shape->lsa_q_heads * shape->head_dim;
     hipStream_t st = (hipStream_t)stream;
     const size_t es = esize(dt);
-    const int64_t tc_max = T < LSA_CHUNK ? T : LSA_CHUNK, ob_max = T < LSA_OBLOCK ? T : LSA_OBLOCK;
-    const int wide = eq + 2 * ekv;
-    char *qkv = (char *)ws;
-    char *abar0 = qkv + align256((size_t)tc_max * L * wide * es);
-    char *lin_ws = abar0 + align256((size_t)ob_max * eq * es);
-    const size_t lin_ws_bytes = ws_bytes - (size_t)(lin_ws - (char *)ws);
+    const LsaBufs b = lsa_carve(shape, T, ws, ws_bytes);
 
     for (int64_t t0 = 0; t0 < T; t0 += LSA_CHUNK) {
         const int64_t tc = (T - t0) < LSA_CHUNK ? (T - t0) : LSA_CHUNK;
         const int64_t b0 = (t0 / LSA_OBLOCK) * LSA_OBLOCK;            // first token of this output-projection block
-        char *abar = abar0 + (size_t)(t0 - b0) * eq * es;
-        const char *x = (const char *)hs + (size_t)t0 * L * d_in * es;
-        LinArgs la = {};
-        la.X = x;
-        la.R = tc * L;
-        la.K = d_in;
-        la.ldx = d_in;
-        la.ws = lin_ws;
-        la.ws_bytes = lin_ws_bytes;
-        LsaAttnArgs aa = {};
-        aa.dtype = dt;
-        auto add = [&](const void *w, int n, int col, const void **ptr, int64_t *ldp) {
-            if (w) {
-                la.seg[la.nseg].W = w;
-                la.seg[la.nseg].N = n;
-                la.seg[la.nseg].st = row_store(qkv + (size_t)col * es, wide);
-                ++la.nseg;
-                *ptr = qkv + (size_t)col * es;
-                *ldp = wide;
-            } else {
-                *ptr = x;
-                *ldp = d_in;
-            }
-        };
-        add(wq, eq, 0, &aa.q, &aa.ldq);
-        add(wk, ekv, eq, &aa.k, &aa.ldk);
-        add(wv, ekv, eq + ekv, &aa.v, &aa.ldv);
+        char *abar = wo ? b.abar0 + (size_t)(t0 - b0) * eq * es : (char *)out + (size_t)t0 * eq * es;
+        LinArgs la;
+        LsaAttnArgs aa;
+        lsa_chunk_args(shape, hs, t0, tc, wq, wk, wv, abar, b, &la, &aa);
         prof_set_site(S_LSA_QKV);
         if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "lsa: projection");
-        aa.T = tc;
-        aa.L = L;
-        aa.Hq = shape->lsa_q_heads;
-        aa.Hkv = shape->lsa_kv_heads;
-        aa.dh = dh;
-        char *orow = (char *)out + (size_t)t0 * eq * es;
-        aa.abar = wo ? (void *)abar : (void *)orow;
         prof_set_site(S_LSA_ATTN);
         MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
         const bool block_done = t0 + tc >= T || (t0 + tc) % LSA_OBLOCK == 0;
         if (wo && block_done) {                                      // W_o once per block, on one row per token
-            LinArgs lo = {};
-            lo.X = abar0;
-            lo.R = t0 + tc - b0;
-            lo.K = eq;
-            lo.ldx = eq;
-            lo.nseg = 1;
-            lo.seg[0].W = wo;
-            lo.seg[0].N = eq;
-            lo.seg[0].st = row_store((char *)out + (size_t)b0 * eq * es, eq);
-            if (t_lsa_nextra > 0 && T <= LSA_OBLOCK) {
-                for (int i = 0; i < t_lsa_nextra && lo.nseg < 4; ++i) lo.seg[lo.nseg++] = t_lsa_extra[i];
-                t_lsa_extra_taken = true;
-            }
-            lo.ws = lin_ws;
-            lo.ws_bytes = lin_ws_bytes;
+            const bool extras = t_lsa_nextra > 0 && T <= LSA_OBLOCK;
+            const LinArgs lo = lsa_oproj_args(shape, b0, t0 + tc - b0, wo, out, b, t_lsa_extra, extras ? t_lsa_nextra : 0);
+            if (extras) t_lsa_extra_taken = true;
             prof_set_site(S_LSA_OPROJ);
             MOA_TRY_HIP(launch_linear(dt, lo, st), "lsa: output projection");
         }
@@ -881,10 +924,12 @@ static int32_t piece_small(const moa_step_args_t *a, const StepBufs &bf, hipStre
 }
 
 // cross-attention queries + first verification layer's Q/K/V in one launch
-// with_small: the integer work rides in spare workgroups at the end of this launch's grid instead of being a
-// launch of its own (nothing before the LSA chain's append and the attention cores needs its results)
+// with_small: the integer work rides in spare workgroups of this launch's grid instead of being a launch of its
+// own (nothing before the LSA chain's append and the attention cores needs its results).  sum_out: the pass that
+// adds up this projection's K slices is left to the caller (scr is then a region nobody else writes until that pass
+// has run).
 static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st,
-                                 bool with_small, void *own_partials = nullptr)
+                                 bool with_small, SumArgs *sum_out = nullptr)
 {
     const moa_shape_t *sh = a->shape;
     const int dh = sh->head_dim, Hkv = sh->n_kv_heads, d = sh->d_model, M = a->M;
@@ -914,51 +959,51 @@ static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, v
         la.rider = small_args(a, bf);
         la.rider_units = 2 * a->B + 1;
     }
-    if (own_partials) {          // partial sums in a region nobody else uses: their summing pass may ride in the next launch
-        la.ws = own_partials;
-        la.defer_reduce = 1;
-    }
+    la.sum_out = sum_out;
     prof_set_site(S_PAIR_QKV);
     MOA_TRY_HIP(launch_linear(sh->dtype, la, st), "draft_step: projections");
     return MOA_OK;
 }
 
-// layer self-attention, then its rows appended to the memory at the old lengths
-static int32_t piece_lsa_append(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st)
+// where the memory's new rows go: appended at the lengths from before this step
+static StoreSpec append_spec(const moa_step_args_t *a, const StepBufs &bf)
 {
-    const moa_shape_t *sh = a->shape;
-    const int dh = sh->head_dim, Hkv = sh->n_kv_heads, ekv = Hkv * dh, dt = sh->dtype;
     StoreSpec sp = {};
     sp.mode = StoreSpec::APPEND;
-    sp.heads = Hkv;
-    sp.dh = dh;
+    sp.heads = a->shape->n_kv_heads;
+    sp.dh = a->shape->head_dim;
     sp.cap = a->ca_P_cap;
     sp.B = a->B;
     sp.row_base = bf.old_len;
     sp.tok_off = a->tok_off;
     sp.dev_status = a->dev_status;
-    // With the products ca_wk lsa_wo and ca_wv lsa_wo at hand, the memory's keys / values are projected straight from
-    // the mean-folded heads, in the launch that also projects the LSA output: (a Wo^T) Wk^T = a (Wk Wo)^T.
-    LinSeg folded[2] = {};
-    const bool fold = a->ca_wk_lsa_wo && a->ca_wv_lsa_wo && a->lsa_wo && a->ca_wk && a->ca_wv;
-    if (fold) {
-        const void *wf[2] = {a->ca_wk_lsa_wo, a->ca_wv_lsa_wo};
-        void *dstf[2] = {a->ca_k, a->ca_v};
-        for (int i = 0; i < 2; ++i) {
-            folded[i].W = wf[i];
-            folded[i].N = ekv;
-            folded[i].st = sp;
-            folded[i].st.dst = dstf[i];
-        }
-        t_lsa_extra = folded;
-        t_lsa_nextra = 2;
+    return sp;
+}
+
+// With the products ca_wk lsa_wo and ca_wv lsa_wo at hand, the memory's keys / values are projected straight from
+// the mean-folded heads, in the launch that also projects the LSA output: (a Wo^T) Wk^T = a (Wk Wo)^T.
+// Fills folded[2] and returns true when that applies.
+static bool folded_segments(const moa_step_args_t *a, const StepBufs &bf, LinSeg *folded)
+{
+    if (!(a->ca_wk_lsa_wo && a->ca_wv_lsa_wo && a->lsa_wo && a->ca_wk && a->ca_wv)) return false;
+    const void *wf[2] = {a->ca_wk_lsa_wo, a->ca_wv_lsa_wo};
+    void *dstf[2] = {a->ca_k, a->ca_v};
+    for (int i = 0; i < 2; ++i) {
+        folded[i] = LinSeg{};
+        folded[i].W = wf[i];
+        folded[i].N = a->shape->n_kv_heads * a->shape->head_dim;
+        folded[i].st = append_spec(a, bf);
+        folded[i].st.dst = dstf[i];
     }
-    t_lsa_extra_taken = false;
-    int32_t rc = moa_lsa(sh, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, scr, scr_bytes, st);
-    t_lsa_extra = nullptr;
-    t_lsa_nextra = 0;
-    if (rc || a->T_lsa <= 0 || (t_lsa_extra_taken && !g_dry)) return rc;
-    const int d_mem = sh->lsa_q_heads * dh;
+    return true;
+}
+
+// the LSA output's rows projected (or copied) into the memory
+static int32_t piece_append(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st)
+{
+    const moa_shape_t *sh = a->shape;
+    const int dh = sh->head_dim, ekv = sh->n_kv_heads * dh, dt = sh->dtype, d_mem = sh->lsa_q_heads * dh;
+    StoreSpec sp = append_spec(a, bf);
     LinArgs la = {};
     la.X = a->lsa_out;
     la.R = a->T_lsa;
@@ -982,6 +1027,65 @@ static int32_t piece_lsa_append(const moa_step_args_t *a, const StepBufs &bf, vo
     }
     if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "draft_step: append projection");
     return MOA_OK;
+}
+
+// layer self-attention, then its rows appended to the memory at the old lengths
+static int32_t piece_lsa_append(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st)
+{
+    LinSeg folded[2];
+    if (folded_segments(a, bf, folded)) {
+        t_lsa_extra = folded;
+        t_lsa_nextra = 2;
+    }
+    t_lsa_extra_taken = false;
+    int32_t rc = moa_lsa(a->shape, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, scr, scr_bytes, st);
+    t_lsa_extra = nullptr;
+    t_lsa_nextra = 0;
+    if (rc || a->T_lsa <= 0 || (t_lsa_extra_taken && !g_dry)) return rc;
+    return piece_append(a, bf, scr, scr_bytes, st);
+}
+
+// The step's first projections and the LSA chain of at most LSA_CHUNK tokens, with the small kernels riding in
+// launches that do not depend on them:
+//   1. CA query + verification Q/K/V projections  + the step's integer work
+//   2. LSA Q/K/V projection                        + the pass that adds up launch 1's K slices (tiled kernel; else that
+//                                                    pass is a launch of its own)
+//   3. attention over the layers    4. LSA W_o (+ the memory's folded K/V)
+// scr2 is the second scratch region: launch 1's partial sums live there while the LSA chain uses the first.
+static int32_t piece_lsa_interleaved(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes, char *scr2,
+                                     hipStream_t st)
+{
+    const moa_shape_t *sh = a->shape;
+    const int dt = sh->dtype;
+    const int64_t T = a->T_lsa;
+    int32_t rc = lsa_check(sh, a->lsa_hs, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_out, scr, scr_bytes);
+    if (rc) return rc;
+    SumArgs sum_pair = {};
+    rc = piece_projections(a, bf, scr2, scr_bytes, st, true, &sum_pair);
+    if (rc) return rc;
+    const LsaBufs b = lsa_carve(sh, T, scr, scr_bytes);
+    LinArgs la;
+    LsaAttnArgs aa;
+    lsa_chunk_args(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo ? (void *)b.abar0 : a->lsa_out, b, &la, &aa);
+    if (la.nseg) {
+        la.carry_sum = &sum_pair;
+        prof_set_site(S_LSA_QKV);
+        MOA_TRY_HIP(launch_linear(dt, la, st), "lsa: projection");
+    } else {
+        prof_set_site(S_PAIR_QKV);
+        MOA_TRY_HIP(launch_splitk_sum(sum_pair, st), "draft_step: projections");
+    }
+    prof_set_site(S_LSA_ATTN);
+    MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
+    LinSeg folded[2];
+    const bool fold = a->lsa_wo && folded_segments(a, bf, folded);
+    if (a->lsa_wo) {
+        const LinArgs lo = lsa_oproj_args(sh, 0, T, a->lsa_wo, a->lsa_out, b, folded, fold ? 2 : 0);
+        prof_set_site(S_LSA_OPROJ);
+        MOA_TRY_HIP(launch_linear(dt, lo, st), "lsa: output projection");
+    }
+    if (fold) return MOA_OK;
+    return piece_append(a, bf, scr, scr_bytes, st);
 }
 
 static AttnArgs piece_ca_core_args(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes)
@@ -1052,16 +1156,17 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
     const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
     char *scr = nullptr;
     const StepBufs bf = carve_step_bufs(a, L, &scr);
-    // With room for a second scratch region the projections keep their partial sums there, and the pass that adds them
-    // up rides in the LSA projection's launch (which does not depend on it) instead of being a launch of its own.
-    const bool defer = a->T_lsa > 0 && a->ws_bytes >= L.total() + L.scratch;
-    int32_t rc = piece_projections(a, bf, scr, L.scratch, st, true, defer ? scr + L.scratch : nullptr);
-    if (rc) return rc;
-    rc = piece_lsa_append(a, bf, scr, L.scratch, st);
-    {   // nothing rode along (or the LSA stage failed): add the slices up now, so that nothing stays pending
-        const hipError_t ef = g_dry ? hipSuccess : launch_linear_flush(st);
+    // With room for a second scratch region (the first projections keep their partial sums there while the LSA chain
+    // uses the first) and all LSA tokens in one chunk, the two are interleaved; else one after the other.
+    int32_t rc;
+    if (a->T_lsa > 0 && a->T_lsa <= LSA_CHUNK && a->ws_bytes >= L.total() + L.scratch) {
+        rc = piece_lsa_interleaved(a, bf, scr, L.scratch, scr + L.scratch, st);
         if (rc) return rc;
-        if (ef != hipSuccess) return hip_fail(ef, "draft_step: projections");
+    } else {
+        rc = piece_projections(a, bf, scr, L.scratch, st, true);
+        if (rc) return rc;
+        rc = piece_lsa_append(a, bf, scr, L.scratch, st);
+        if (rc) return rc;
     }
     const AttnArgs ca = piece_ca_core_args(a, bf, scr, L.attn_each);
     const AttnArgs ve = piece_verify_core_args(a, bf, scr + L.attn_each, L.attn_each);

@@ -128,6 +128,34 @@ struct StepSmallArgs {
 };
 hipError_t launch_step_small(const StepSmallArgs &a, hipStream_t stream);
 
+// ---- LSA attention over the layer axis with the mean folded in:
+// abar[t, h*dh + c] = sum_j (1/L sum_i softmax_i(S)[i][j]) V[t, j, g, c]
+struct LsaAttnArgs {
+    int dtype;
+    const void *q, *k, *v;   // row (t*L + l): q + row*ldq + h*dh ; k, v + row*ldk + g*dh
+    int64_t ldq, ldk, ldv;
+    int64_t T;
+    int L, Hq, Hkv, dh;
+    void *abar;              // [T, Hq*dh]
+};
+
+// The pass that adds up the K slices of a weight-streaming projection, as data: what launch_linear leaves behind
+// when asked not to launch it (LinArgs::sum_out), what another launch can carry (LinArgs::carry_sum) and what
+// launch_splitk_sum runs.
+struct SumArgs {
+    int blocks;          // workgroups of 256 threads; 0 = nothing to do
+    int64_t R;
+    int nseg;
+    StoreSpec st[4];     // where each segment's sums go
+    int tile_begin[5];   // first 64-feature tile of each segment; [nseg] = total tiles
+    int splits, ntot;    // K slices; total features = row length of the partial buffer
+    const float *part;   // [row tiles][splits][64][ntot]
+    int epi;             // LinArgs::EPI_*
+    const float *epi_res;
+    void *epi_out;
+};
+hipError_t launch_splitk_sum(const SumArgs &s, hipStream_t stream);
+
 struct LinSeg {
     const void *W;  // [N, K] row-major
     int N;
@@ -156,16 +184,19 @@ struct LinArgs {
     int epi;
     const float *epi_res;
     void *epi_out;
-    // Weight-streaming path only: leave the summing of the K slices pending instead of launching it.  The next
-    // launch_linear on this thread and stream carries it in spare workgroups if it runs the tiled kernel (the sums
-    // are then ready when that launch has finished), otherwise it is launched first; launch_linear_flush launches
-    // whatever is still pending.  The partial sums (ws) must stay untouched until then.
-    int defer_reduce;
+    // The summing pass of an earlier weight-streaming projection, carried in spare workgroups at the front of this
+    // launch's grid: it is done when this launch has finished, and must neither feed this projection nor depend on
+    // it.  Only the tiled kernel carries; on the other paths the pass is launched apart, first.  A host pointer, read
+    // during the call; NULL or blocks == 0 = nothing.
+    const SumArgs *carry_sum;
+    // Weight-streaming path only: do not launch the pass that adds up the K slices but describe it here (blocks = 0
+    // when another kernel ran and nothing is left to do).  The caller has it carried by a later launch or runs
+    // launch_splitk_sum; the partial sums (ws) must stay untouched until then.
+    SumArgs *sum_out;
 };
 
 // Y_s = X_s W_s^T for up to four weight matrices (one launch on the fast paths; segments usually share X).
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream);
-hipError_t launch_linear_flush(hipStream_t stream);
 // scratch the fast weight-streaming path wants for R rows and ntot output features in total (0 = not used)
 size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot);
 
@@ -220,16 +251,7 @@ hipError_t launch_fold_weights(int dtype, const void *a, const void *b, int N, i
 hipError_t launch_swiglu(int dtype, const void *gu, int64_t R, int d_ff, void *act, hipStream_t stream);
 hipError_t launch_add_out(int dtype, const float *h, const void *t, int64_t n, void *out, hipStream_t stream);
 
-// ---- LSA attention over the layer axis with the mean folded in:
-// abar[t, h*dh + c] = sum_j (1/L sum_i softmax_i(S)[i][j]) V[t, j, g, c]
-struct LsaAttnArgs {
-    int dtype;
-    const void *q, *k, *v;   // row (t*L + l): q + row*ldq + h*dh ; k, v + row*ldk + g*dh
-    int64_t ldq, ldk, ldv;
-    int64_t T;
-    int L, Hq, Hkv, dh;
-    void *abar;              // [T, Hq*dh]
-};
+// ---- LSA attention over the layer axis (LsaAttnArgs is declared above, beside the projections that can carry it)
 size_t lsa_attn_lds_bytes(int dtype, int L, int dh);
 hipError_t launch_lsa_attn(const LsaAttnArgs &a, hipStream_t stream);
 

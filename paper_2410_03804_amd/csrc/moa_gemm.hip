@@ -260,7 +260,7 @@ __global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
 }
 
 // one thread per (row, 8 consecutive features): sum the K slices in order, round once, store
-__device__ __forceinline__ void splitk_sum8(const SplitKArgs &sa, const float *p, f32x4 &lo, f32x4 &hi)
+__device__ __forceinline__ void splitk_sum8(const SumArgs &sa, const float *p, f32x4 &lo, f32x4 &hi)
 {
     lo = f32x4{0.f, 0.f, 0.f, 0.f};
     hi = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -289,20 +289,19 @@ __device__ __forceinline__ u32x4 pack8(const f32x4 &lo, const f32x4 &hi)
     return pk;
 }
 
-__device__ __forceinline__ void splitk_reduce_block(const SplitKArgs &sa, int block)
+__device__ __forceinline__ void splitk_reduce_block(const SumArgs &sa, int block)
 {
-    const LinArgs &a = sa.a;
-    const int width = a.epi == LinArgs::EPI_SWIGLU ? sa.ntot / 2 : sa.ntot;   // features a row of threads walks
+    const int width = sa.epi == LinArgs::EPI_SWIGLU ? sa.ntot / 2 : sa.ntot;   // features a row of threads walks
     const int per = width / 8;
     const int64_t idx = (int64_t)block * 256 + threadIdx.x;
-    if (idx >= a.R * per) return;
+    if (idx >= sa.R * per) return;
     const int64_t r = idx / per;
     const int nt = (int)(idx - r * per) * 8;          // feature in the concatenated space
     const int64_t rt = r >> 6, rr = r & 63;
     const float *p = sa.part + (rt * sa.splits * 64 + rr) * sa.ntot + nt;
     f32x4 lo, hi;
     splitk_sum8(sa, p, lo, hi);
-    if (a.epi == LinArgs::EPI_SWIGLU) {              // gate in the first half of the row, up in the second
+    if (sa.epi == LinArgs::EPI_SWIGLU) {              // gate in the first half of the row, up in the second
         f32x4 ulo, uhi;
         splitk_sum8(sa, p + width, ulo, uhi);
 #pragma unroll
@@ -312,38 +311,39 @@ __device__ __forceinline__ void splitk_reduce_block(const SplitKArgs &sa, int bl
             lo[e] = gl / (1.0f + __expf(-gl)) * bf2f(f2bf(ulo[e]));
             hi[e] = gh / (1.0f + __expf(-gh)) * bf2f(f2bf(uhi[e]));
         }
-        *(u32x4 *)((bf16_t *)a.epi_out + r * width + nt) = pack8(lo, hi);
+        *(u32x4 *)((bf16_t *)sa.epi_out + r * width + nt) = pack8(lo, hi);
         return;
     }
-    if (a.epi == LinArgs::EPI_ADD_F32) {
-        const float *h = a.epi_res + r * width + nt;
+    if (sa.epi == LinArgs::EPI_ADD_F32) {
+        const float *h = sa.epi_res + r * width + nt;
         const f32x4 h0 = *(const f32x4 *)h, h1 = *(const f32x4 *)(h + 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             lo[e] = h0[e] + bf2f(f2bf(lo[e]));
             hi[e] = h1[e] + bf2f(f2bf(hi[e]));
         }
-        *(u32x4 *)((bf16_t *)a.epi_out + r * width + nt) = pack8(lo, hi);
+        *(u32x4 *)((bf16_t *)sa.epi_out + r * width + nt) = pack8(lo, hi);
         return;
     }
     const int tile = nt >> 6;
     int s = 0;
-    while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
+    while (s + 1 < sa.nseg && tile >= sa.tile_begin[s + 1]) ++s;
     const int n = nt - sa.tile_begin[s] * 64;
-    const int64_t off = store_offset(a.seg[s].st, r, n);
+    const int64_t off = store_offset(sa.st[s], r, n);
     if (off < 0) return;
-    *(u32x4 *)((bf16_t *)a.seg[s].st.dst + off) = pack8(lo, hi);
+    *(u32x4 *)((bf16_t *)sa.st[s].dst + off) = pack8(lo, hi);
 }
 
-__global__ __launch_bounds__(256) void k_linear_splitk_reduce(SplitKArgs sa) { splitk_reduce_block(sa, (int)blockIdx.x); }
+__global__ __launch_bounds__(256) void k_linear_splitk_reduce(SumArgs sa) { splitk_reduce_block(sa, (int)blockIdx.x); }
 
-// a summing pass left pending by LinArgs::defer_reduce
-static thread_local struct {
-    bool valid;
-    SplitKArgs ka;
-    int blocks;
-    hipStream_t stream;
-} t_pending = {};
+hipError_t launch_splitk_sum(const SumArgs &sa, hipStream_t stream)
+{
+    if (sa.blocks <= 0) return hipSuccess;
+    prof_begin(K_LIN_REDUCE, stream);
+    MOA_KLAUNCH(k_linear_splitk_reduce, dim3((unsigned)sa.blocks), dim3(256), 0, stream, sa);
+    prof_end(stream);
+    return hipGetLastError();
+}
 
 // The weight-streaming kernel walks 64-row tiles with the weights in registers.  Its fp32 partial sums are
 // (row tiles * 128 / K slice) of the weight bytes.  Up to two row tiles it is always used (K slices chosen for the
@@ -390,10 +390,10 @@ struct TiledArgs {
     LinArgs a;
     int tile_begin[5];
     int tiles_per_xcd;   // feature tiles owned by one XCD
-    int lead_blocks;     // workgroups in front of the projection's own: LinArgs::rider, then a pending summing pass
+    int lead_blocks;     // workgroups in front of the projection's own: LinArgs::rider, then LinArgs::carry_sum
     int small_lead;      // the first of them carry LinArgs::rider (padded to the XCD count)
-    int red_blocks;      // workgroups of the pending summing pass `red` (0 = none)
-    SplitKArgs red;
+    int red_blocks;      // workgroups of the carried summing pass `red` (0 = none)
+    SumArgs red;
 };
 
 // WF x WR = 32x32 MFMA blocks per wave along features x rows; the four waves sit 2 x 2, so the workgroup
@@ -546,10 +546,10 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
     ta.tiles_per_xcd = (t + 7) / 8;
     ta.small_lead = (a.rider_units + 7) & ~7;       // multiples of the XCD count: the tile mapping keeps its phase
     ta.red_blocks = 0;
-    if (t_pending.valid && t_pending.stream == stream) {      // carry the pending summing pass of an earlier projection
-        ta.red = t_pending.ka;
-        ta.red_blocks = t_pending.blocks;
-        t_pending.valid = false;
+    ta.red = SumArgs{};
+    if (a.carry_sum && a.carry_sum->blocks > 0) {
+        ta.red = *a.carry_sum;
+        ta.red_blocks = a.carry_sum->blocks;
     }
     ta.lead_blocks = ta.small_lead + ((ta.red_blocks + 7) & ~7);
     const dim3 grid((unsigned)(ta.lead_blocks + 8 * ta.tiles_per_xcd * (int)((a.R + BM - 1) / BM)));
@@ -565,6 +565,41 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
 // ------------------------------------------------------------------ dispatch
 static bool aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 
+// which kernel a call gets; decided from shapes and alignment alone, so that launch_linear knows beforehand whether
+// the launch can carry what LinArgs::carry_sum names
+enum LinPath { P_TILED, P_SPLITK, P_SKINNY, P_EACH, P_GENERIC };
+
+static LinPath linear_path(int dtype, const LinArgs &a, int *nq_out)
+{
+    *nq_out = 0;
+    bool own_x = false;
+    for (int s = 0; s < a.nseg; ++s) own_x = own_x || a.seg[s].X != nullptr;
+    bool fast = dtype == DT_BF16 && a.K % 128 == 0 && a.ldx % 8 == 0 && aligned16(a.X);
+    for (int s = 0; s < a.nseg && fast; ++s)
+        if (a.seg[s].X) fast = a.seg[s].ldx % 8 == 0 && aligned16(a.seg[s].X);
+    for (int s = 0; s < a.nseg && fast; ++s) {
+        const StoreSpec &st = a.seg[s].st;
+        fast = a.seg[s].N % 32 == 0 && aligned16(a.seg[s].W) && aligned16(st.dst) &&
+               (st.mode == StoreSpec::ROW ? st.ld % 8 == 0 : st.dh % 8 == 0);
+    }
+    if (!fast) return own_x ? P_EACH : P_GENERIC;
+    bool all128 = true, all64 = true;
+    int ntot = 0;
+    for (int s = 0; s < a.nseg; ++s) {
+        all128 = all128 && a.seg[s].N % 128 == 0;
+        all64 = all64 && a.seg[s].N % 64 == 0;
+        ntot += a.seg[s].N;
+    }
+    const int nq = splitk_plan(a.R, a.K);
+    if (!nq && all128) return P_TILED;
+    const size_t need = all64 ? linear_workspace_bytes(dtype, a.R, a.K, ntot) : 0;
+    if (need && a.ws && a.ws_bytes >= need && (((uintptr_t)a.ws) & 15) == 0) {
+        *nq_out = nq;
+        return P_SPLITK;
+    }
+    return own_x ? P_EACH : P_SKINNY;
+}
+
 static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode, bool *fused);
 
 // kernels without per-segment activation support get one call per segment
@@ -573,6 +608,8 @@ static hipError_t launch_linear_each(int dtype, const LinArgs &a, hipStream_t st
     for (int s = 0; s < a.nseg; ++s) {
         LinArgs one = a;
         one.rider_units = 0;
+        one.carry_sum = nullptr;
+        one.sum_out = nullptr;
         one.nseg = 1;
         one.seg[0] = a.seg[s];
         if (a.seg[s].X) { one.X = a.seg[s].X; one.ldx = a.seg[s].ldx; }
@@ -585,84 +622,75 @@ static hipError_t launch_linear_each(int dtype, const LinArgs &a, hipStream_t st
     return hipSuccess;
 }
 
-// *rode is set when the launch carried a.rider in its grid, *fused when it applied a.epi
+// *rode is set when the launch carried a.rider in its grid, *fused when it applied a.epi.  a.carry_sum is only
+// set where the path can carry it (launch_linear sees to that).
 static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode, bool *fused)
 {
     *rode = false;
     *fused = false;
     if (a.R <= 0) return hipSuccess;
-    bool own_x = false;
-    for (int s = 0; s < a.nseg; ++s) own_x = own_x || a.seg[s].X != nullptr;
-    bool fast = dtype == DT_BF16 && a.K % 128 == 0 && a.ldx % 8 == 0 && aligned16(a.X);
-    for (int s = 0; s < a.nseg && fast; ++s)
-        if (a.seg[s].X) fast = a.seg[s].ldx % 8 == 0 && aligned16(a.seg[s].X);
-    for (int s = 0; s < a.nseg && fast; ++s) {
-        const StoreSpec &st = a.seg[s].st;
-        fast = a.seg[s].N % 32 == 0 && aligned16(a.seg[s].W) && aligned16(st.dst) &&
-               (st.mode == StoreSpec::ROW ? st.ld % 8 == 0 : st.dh % 8 == 0);
+    int nq = 0;
+    const LinPath path = linear_path(dtype, a, &nq);
+    if (path == P_TILED) {
+        bool all256 = true;
+        for (int s = 0; s < a.nseg; ++s) all256 = all256 && a.seg[s].N % 256 == 0;
+        // 2x2 blocks per wave keeps two workgroups per CU; the 4x2 variant halves the LDS traffic per MFMA
+        // but drops to one workgroup per CU and measured slower (MOA_TILE=42 selects it for tuning).
+        const char *force = getenv("MOA_TILE");
+        *rode = a.rider_units > 0;
+        if (all256 && force && force[0] == '4') return launch_tiled<4, 2>(a, stream);
+        return launch_tiled<2, 2>(a, stream);
     }
-    if (fast) {
-        bool all128 = true;
-        for (int s = 0; s < a.nseg; ++s) all128 = all128 && a.seg[s].N % 128 == 0;
-        if (!splitk_plan(a.R, a.K) && all128) {
-            bool all256 = true;
-            for (int s = 0; s < a.nseg; ++s) all256 = all256 && a.seg[s].N % 256 == 0;
-            // 2x2 blocks per wave keeps two workgroups per CU; the 4x2 variant halves the LDS traffic per MFMA
-            // but drops to one workgroup per CU and measured slower (MOA_TILE=42 selects it for tuning).
-            const char *force = getenv("MOA_TILE");
-            *rode = a.rider_units > 0;
-            if (all256 && force && force[0] == '4') return launch_tiled<4, 2>(a, stream);
-            return launch_tiled<2, 2>(a, stream);
+    if (path == P_SPLITK) {
+        SplitKArgs ka;
+        ka.a = a;
+        int t = 0, ntot = 0;
+        for (int s = 0; s < a.nseg; ++s) { ka.tile_begin[s] = t; t += a.seg[s].N / 64; ntot += a.seg[s].N; }
+        ka.tile_begin[a.nseg] = t;
+        ka.splits = a.K / (128 * nq);
+        ka.ntot = ntot;
+        ka.part = (float *)a.ws;
+        ka.lead_blocks = (a.rider_units + 7) & ~7;
+        *rode = a.rider_units > 0;
+        const dim3 grid((unsigned)(ka.lead_blocks + t * ka.splits));
+        const size_t lds = (size_t)64 * (128 * nq + 8) * sizeof(bf16_t);
+        hipError_t e = hipSuccess;
+        prof_begin(K_LIN_SPLITK + 64 * nq, stream);
+        switch (nq) {
+        case 1: MOA_KLAUNCH(k_linear_splitk_bf16<1>, grid, dim3(256), lds, stream, ka); break;
+        case 2: MOA_KLAUNCH(k_linear_splitk_bf16<2>, grid, dim3(256), lds, stream, ka); break;
+        case 4: MOA_KLAUNCH(k_linear_splitk_bf16<4>, grid, dim3(256), lds, stream, ka); break;
+        default:
+            e = hipFuncSetAttribute((const void *)k_linear_splitk_bf16<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e == hipSuccess) MOA_KLAUNCH(k_linear_splitk_bf16<8>, grid, dim3(256), lds, stream, ka);
+            break;
         }
-        bool all64 = true;
-        int ntot = 0;
-        for (int s = 0; s < a.nseg; ++s) { all64 = all64 && a.seg[s].N % 64 == 0; ntot += a.seg[s].N; }
-        const size_t need = all64 ? linear_workspace_bytes(dtype, a.R, a.K, ntot) : 0;
-        if (need && a.ws && a.ws_bytes >= need && (((uintptr_t)a.ws) & 15) == 0) {
-            SplitKArgs ka;
-            ka.a = a;
-            int t = 0;
-            for (int s = 0; s < a.nseg; ++s) { ka.tile_begin[s] = t; t += a.seg[s].N / 64; }
-            ka.tile_begin[a.nseg] = t;
-            const int nq = splitk_plan(a.R, a.K);
-            ka.splits = a.K / (128 * nq);
-            ka.ntot = ntot;
-            ka.part = (float *)a.ws;
-            ka.lead_blocks = (a.rider_units + 7) & ~7;
-            *rode = a.rider_units > 0;
-            const dim3 grid((unsigned)(ka.lead_blocks + t * ka.splits));
-            const size_t lds = (size_t)64 * (128 * nq + 8) * sizeof(bf16_t);
-            hipError_t e = hipSuccess;
-            prof_begin(K_LIN_SPLITK + 64 * nq, stream);
-            switch (nq) {
-            case 1: MOA_KLAUNCH(k_linear_splitk_bf16<1>, grid, dim3(256), lds, stream, ka); break;
-            case 2: MOA_KLAUNCH(k_linear_splitk_bf16<2>, grid, dim3(256), lds, stream, ka); break;
-            case 4: MOA_KLAUNCH(k_linear_splitk_bf16<4>, grid, dim3(256), lds, stream, ka); break;
-            default:
-                e = hipFuncSetAttribute((const void *)k_linear_splitk_bf16<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-                if (e == hipSuccess) MOA_KLAUNCH(k_linear_splitk_bf16<8>, grid, dim3(256), lds, stream, ka);
-                break;
-            }
-            prof_end(stream);
-            if (e != hipSuccess) return e;
-            e = hipGetLastError();
-            if (e != hipSuccess) return e;
-            const int64_t items = a.R * ((a.epi == LinArgs::EPI_SWIGLU ? ntot / 2 : ntot) / 8);
-            *fused = a.epi != LinArgs::EPI_NONE;
-            if (a.defer_reduce) {                    // someone else launches (or carries) the summing pass
-                ka.a.rider_units = 0;
-                t_pending.valid = true;
-                t_pending.ka = ka;
-                t_pending.blocks = (int)((items + 255) / 256);
-                t_pending.stream = stream;
-                return hipSuccess;
-            }
-            prof_begin(K_LIN_REDUCE, stream);
-            MOA_KLAUNCH(k_linear_splitk_reduce, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, ka);
-            prof_end(stream);
-            return hipGetLastError();
+        prof_end(stream);
+        if (e != hipSuccess) return e;
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        *fused = a.epi != LinArgs::EPI_NONE;
+        SumArgs sum = {};
+        const int64_t items = a.R * ((a.epi == LinArgs::EPI_SWIGLU ? ntot / 2 : ntot) / 8);
+        sum.blocks = (int)((items + 255) / 256);
+        sum.R = a.R;
+        sum.nseg = a.nseg;
+        for (int s = 0; s < a.nseg; ++s) sum.st[s] = a.seg[s].st;
+        for (int s = 0; s <= a.nseg; ++s) sum.tile_begin[s] = ka.tile_begin[s];
+        sum.splits = ka.splits;
+        sum.ntot = ntot;
+        sum.part = ka.part;
+        sum.epi = a.epi;
+        sum.epi_res = a.epi_res;
+        sum.epi_out = a.epi_out;
+        if (a.sum_out) {                         // the caller has it carried by a later launch, or launches it
+            *a.sum_out = sum;
+            return hipSuccess;
         }
-        if (own_x) return launch_linear_each(dtype, a, stream);
+        return launch_splitk_sum(sum, stream);
+    }
+    if (path == P_EACH) return launch_linear_each(dtype, a, stream);
+    if (path == P_SKINNY) {
         SkinnyArgs sa;
         sa.a = a;
         int t = 0;
@@ -672,7 +700,6 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
         { prof_begin(K_LIN_SKINNY, stream); MOA_KLAUNCH(k_linear_skinny_bf16<2>, grid, dim3(256), 0, stream, sa); prof_end(stream); }
         return hipGetLastError();
     }
-    if (own_x) return launch_linear_each(dtype, a, stream);
     for (int s = 0; s < a.nseg; ++s) {
         dim3 grid((a.seg[s].N + 63) / 64, (unsigned)((a.R + 63) / 64));
         if (dtype == DT_BF16)
@@ -687,40 +714,23 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
     return hipSuccess;
 }
 
-hipError_t launch_linear_flush(hipStream_t stream)
-{
-    if (!t_pending.valid) return hipSuccess;
-    t_pending.valid = false;
-    prof_begin(K_LIN_REDUCE, t_pending.stream);
-    MOA_KLAUNCH(k_linear_splitk_reduce, dim3((unsigned)t_pending.blocks), dim3(256), 0, t_pending.stream, t_pending.ka);
-    prof_end(t_pending.stream);
-    (void)stream;
-    return hipGetLastError();
-}
-
-// the tiled kernel is the one that can carry a pending summing pass: same conditions as in launch_linear_impl
-static bool takes_tiled_kernel(int dtype, const LinArgs &a)
-{
-    if (dtype != DT_BF16 || a.R <= 0 || a.K % 128 || a.ldx % 8 || !aligned16(a.X) || splitk_plan(a.R, a.K)) return false;
-    for (int s = 0; s < a.nseg; ++s) {
-        const StoreSpec &st = a.seg[s].st;
-        if (a.seg[s].X && (a.seg[s].ldx % 8 || !aligned16(a.seg[s].X))) return false;
-        if (a.seg[s].N % 128 || !aligned16(a.seg[s].W) || !aligned16(st.dst)) return false;
-        if (st.mode == StoreSpec::ROW ? st.ld % 8 != 0 : st.dh % 8 != 0) return false;
-    }
-    return true;
-}
-
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
 {
-    if (t_pending.valid && !(t_pending.stream == stream && takes_tiled_kernel(dtype, a))) {
-        const hipError_t ef = launch_linear_flush(stream);
-        if (ef != hipSuccess) return ef;
-    }
+    if (a.sum_out) *a.sum_out = SumArgs{};
     if (a.epi == LinArgs::EPI_ADD_F32 && a.nseg != 1) return hipErrorInvalidValue;
     if (a.epi == LinArgs::EPI_SWIGLU && (a.nseg != 2 || a.seg[0].N != a.seg[1].N)) return hipErrorInvalidValue;
+    // A carried pass rides in the tiled kernel only: that one keeps several workgroups per CU busy with matrix work,
+    // so a few hundred short workgroups in front cost it nothing.  In the weight-streaming kernel (two workgroups per
+    // CU, bound by the same memory path the pass uses) riding measured slower than a launch of its own.
+    int nq = 0;
+    LinArgs b = a;
+    if (a.carry_sum && a.carry_sum->blocks > 0 && !(a.R > 0 && linear_path(dtype, a, &nq) == P_TILED)) {
+        const hipError_t es = launch_splitk_sum(*a.carry_sum, stream);
+        if (es != hipSuccess) return es;
+        b.carry_sum = nullptr;
+    }
     bool rode = false, fused = false;
-    hipError_t e = launch_linear_impl(dtype, a, stream, &rode, &fused);
+    hipError_t e = launch_linear_impl(dtype, b, stream, &rode, &fused);
     if (e != hipSuccess) return e;
     if (a.epi != LinArgs::EPI_NONE && !fused) {     // the projection was stored as its segments say: finish row-wise
         if (a.epi == LinArgs::EPI_SWIGLU) e = launch_swiglu(dtype, a.seg[0].st.dst, a.R, a.seg[0].N, a.epi_out, stream);
