@@ -204,6 +204,35 @@ def tli_decoder_layer(x, parent, node0, w, kcache, vcache, prefix_len, k_draft, 
     return out
 
 
+def rmsnorm(x, g, eps):
+    """x / sqrt(mean(x^2) + eps) * g over the last axis."""
+    x = _f64(x)
+    g = _f64(g)
+    d = x.shape[-1]
+    out = np.empty_like(x)
+    rc = lib().moa_ref_rmsnorm(_p(x), C.c_int64(x.size // d), d, _p(g), C.c_double(eps), _p(out))
+    _check(rc, "rmsnorm")
+    return out
+
+
+def mlp_block(x, res, g, w_gate, w_up, w_down, eps):
+    """h = x + res (res may be None); out = h + W_down(silu(W_gate n) * W_up n), n = rmsnorm(h) * g."""
+    x = _f64(x)
+    res = None if res is None else _f64(res)
+    if res is not None and res.shape != x.shape:
+        raise ValueError("res must have the shape of x")
+    g, w_gate, w_up, w_down = _f64(g), _f64(w_gate), _f64(w_up), _f64(w_down)
+    d = x.shape[-1]
+    d_ff = w_gate.shape[0]
+    if w_gate.shape != (d_ff, d) or w_up.shape != (d_ff, d) or w_down.shape != (d, d_ff) or g.shape != (d,):
+        raise ValueError("mlp_block: weight shapes")
+    out = np.empty_like(x)
+    rc = lib().moa_ref_mlp_block(_p(x), _p(res), C.c_int64(x.size // d), d, d_ff, _p(g), _p(w_gate), _p(w_up),
+                                 _p(w_down), C.c_double(eps), _p(out))
+    _check(rc, "mlp_block")
+    return out
+
+
 def _f32(a):
     return np.ascontiguousarray(a, dtype=np.float32)
 

@@ -374,6 +374,35 @@ static void ref_rmsnorm(const double *x, int64_t R, int d, const double *g, doub
     }
 }
 
+int moa_ref_rmsnorm(const double *x, int64_t R, int d, const double *g, double eps, double *out)
+{
+    if (!x || !g || !out || R < 0 || d < 1 || !(eps >= 0.0)) return MOA_REF_BAD_ARG;
+    ref_rmsnorm(x, R, d, g, eps, out);
+    return MOA_REF_OK;
+}
+
+int moa_ref_mlp_block(const double *x, const double *res, int64_t R, int d, int d_ff, const double *g,
+                      const double *w_gate, const double *w_up, const double *w_down, double eps, double *out)
+{
+    if (!x || !g || !w_gate || !w_up || !w_down || !out || R < 0 || d < 1 || d_ff < 1 || !(eps >= 0.0))
+        return MOA_REF_BAD_ARG;
+    if (R == 0) return MOA_REF_OK;
+    double *h = (double *)malloc(sizeof(double) * (size_t)R * d);
+    double *n = (double *)malloc(sizeof(double) * (size_t)R * d);
+    double *gt = (double *)malloc(sizeof(double) * (size_t)R * d_ff);
+    double *up = (double *)malloc(sizeof(double) * (size_t)R * d_ff);
+    if (!h || !n || !gt || !up) { free(h); free(n); free(gt); free(up); return MOA_REF_BAD_ARG; }
+    for (int64_t e = 0; e < R * d; ++e) h[e] = x[e] + (res ? res[e] : 0.0);     /* the stream the block sits on */
+    ref_rmsnorm(h, R, d, g, eps, n);
+    moa_ref_linear(n, R, d, w_gate, d_ff, gt);
+    moa_ref_linear(n, R, d, w_up, d_ff, up);
+    for (int64_t e = 0; e < R * d_ff; ++e) gt[e] = gt[e] / (1.0 + exp(-gt[e])) * up[e];   /* silu(gate) * up */
+    moa_ref_linear(gt, R, d_ff, w_down, d, out);
+    for (int64_t e = 0; e < R * d; ++e) out[e] += h[e];
+    free(h); free(n); free(gt); free(up);
+    return MOA_REF_OK;
+}
+
 int moa_ref_tli_decoder_layer(const double *x, int B, int M, int node0, int Mn, int d, int H, int Hkv, int dh,
                               int d_ff, double rms_eps, double rope_theta,
                               const double *g_attn, const double *wq, const double *wk, const double *wv,

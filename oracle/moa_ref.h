@@ -130,6 +130,19 @@ int moa_ref_tli_decoder_layer(const double *x /*[B,Mn,d]*/, int B, int M, int no
                               const int32_t *prefix_len, int P_cap, const int32_t *parent /*[B,M]*/,
                               double *out /*[B,Mn,d]*/, double *k_draft, double *v_draft /*[B,Hkv,M,dh]*/);
 
+/* The drafter's own layers (Sec. 3.1: Layer Self-Attention, Self-Attention, Cross-Attention) each come with an MLP
+ * (appendix architecture table: projection sizes 6144, 512 and 7168); the paper states neither its form nor the
+ * normalisation and residual wiring.  Reading taken: the form of the LLM's own block (above), i.e. a pre-norm
+ * residual sub-block with a gated MLP,
+ *   h = x + res (res may be NULL);  n = rmsnorm(h) * g;  out = h + (silu(n Wgate^T) * (n Wup^T)) Wdown^T,
+ * where res is the output of the attention sub-layer that precedes the MLP and x the stream it was added to. */
+int moa_ref_mlp_block(const double *x /*[R,d]*/, const double *res /*[R,d] or NULL*/, int64_t R, int d, int d_ff,
+                      const double *g /*[d]*/, const double *w_gate /*[d_ff,d]*/, const double *w_up,
+                      const double *w_down /*[d,d_ff]*/, double eps, double *out /*[R,d]*/);
+/* out = x / sqrt(mean(x^2) + eps) * g, row by row: the pre-norm in front of an attention sub-layer. */
+int moa_ref_rmsnorm(const double *x /*[R,d]*/, int64_t R, int d, const double *g /*[d]*/, double eps,
+                    double *out /*[R,d]*/);
+
 /* Rotary position embedding of one head vector in place (the convention above). */
 void moa_ref_rope(double *v /*[dh]*/, int dh, double pos, double theta);
 
