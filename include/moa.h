@@ -197,6 +197,29 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
                               const int32_t *depth, void *out, void *k_draft, void *v_draft,
                               int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
 
+/* The wrappers of the drafter's own layers (Sec. 3.1: Layer Self-Attention, Self-Attention,
+ * Cross-Attention; appendix architecture table: an MLP projection of 6144 after LSA, 512 after SA, 7168
+ * after CA).  The paper states neither the MLP's form nor the normalisation and residual wiring; the
+ * form of the LLM's own block (moa_tli_decoder_layer) is taken: a pre-norm residual sub-block with a
+ * gated MLP,
+ *   h = x + res (res may be NULL);  n = rmsnorm(h) * g;  out = h + (silu(n Wgate^T) * (n Wup^T)) Wdown^T,
+ * where res is the output of the attention sub-layer in front of the MLP and x the stream that output
+ * is added to; moa_rmsnorm is the pre-norm in front of such an attention sub-layer:
+ *   out = x / sqrt(mean(x^2) + rms_eps) * g.
+ * A drafter layer is then  a = Attn(moa_rmsnorm(x));  y = moa_mlp_block(x, a)  with Attn one of
+ * moa_self_attn_draft / moa_cross_attn_draft, and  mem = moa_mlp_block(moa_lsa(...), NULL)  for LSA, whose
+ * mean over the layers leaves no stream to add to.
+ *   x, res, out [R, d] (device, `dtype`; out may alias x or res); g [d]; w_gate, w_up [d_ff, d];
+ *   w_down [d, d_ff]; the stream h is kept in single precision between the two halves.
+ * R = 0 is a no-op.  Workspace: moa_mlp_block_workspace_bytes (host only, launches nothing); the caller
+ * owns it.  Errors: MOA_ERR_NULL / _DTYPE / _SHAPE / _WORKSPACE before anything is launched. */
+int32_t moa_mlp_block_workspace_bytes(int32_t dtype, int64_t R, int32_t d, int32_t d_ff, size_t *bytes_host);
+int32_t moa_mlp_block(int32_t dtype, const void *x, const void *res, int64_t R, int32_t d, int32_t d_ff,
+                      const void *g, const void *w_gate, const void *w_up, const void *w_down,
+                      float rms_eps, void *out, void *ws, size_t ws_bytes, void *stream);
+int32_t moa_rmsnorm(int32_t dtype, const void *x, int64_t R, int32_t d, const void *g, float rms_eps,
+                    void *out, void *stream);
+
 /* Draft-tree construction on the device (Sec. 2.2, tree drafting as in EAGLE-2: from the root the Bw
  * most probable tokens; then, level by level, each of the Bw current branches proposes its Bw most
  * probable children, the Bw*Bw expansions are ranked by joint probability and the best Bw become the

@@ -295,6 +295,26 @@ def tli_weights(cfg: Config, layer: int = 0):
                 w_down=weight(rng, d, dff, cfg.dtype))
 
 
+def drafter_mlp_sizes(cfg: Config):
+    """(stream width, MLP projection size) of the MLPs behind the drafter's three attention layers, in the proportions
+    of the appendix architecture table: 6144 after LSA (width 2048), 512 after SA and 7168 after CA (width 4096)."""
+    return dict(lsa=(cfg.d_lsa, 3 * cfg.d_lsa), sa=(cfg.d, max(32, cfg.d // 8)), ca=(cfg.d, 7 * cfg.d // 4))
+
+
+def drafter_mlp_weights(cfg: Config, which: str):
+    """Pre-norm gain (near 1) and gated-MLP weights ~ N(0, 1/in_features) of one of the drafter's MLP sub-blocks."""
+    d, dff = drafter_mlp_sizes(cfg)[which]
+    rng = rng_for(cfg, S_WEIGHT, extra=700 + {"lsa": 0, "sa": 1, "ca": 2}[which])
+    return dict(g=quantize(1.0 + 0.1 * rng.standard_normal(d), cfg.dtype), w_gate=weight(rng, dff, d, cfg.dtype),
+                w_up=weight(rng, dff, d, cfg.dtype), w_down=weight(rng, d, dff, cfg.dtype))
+
+
+def drafter_norm_gain(cfg: Config, which: str):
+    """Gain of the pre-norm in front of the drafter's SA / CA sub-layer."""
+    rng = rng_for(cfg, S_WEIGHT, extra=720 + {"sa": 1, "ca": 2}[which])
+    return quantize(1.0 + 0.1 * rng.standard_normal(cfg.d), cfg.dtype)
+
+
 def ca_weights(cfg: Config):
     rng = rng_for(cfg, S_WEIGHT, extra=2)
     E = cfg.H * cfg.dh

@@ -70,7 +70,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
             "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
-            "moa_msg_unpack_accept", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_msg_unpack_accept", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -112,7 +112,10 @@ _lib.moa_msg_unpack_accept.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.moa_linear_workspace_bytes.argtypes = [_i32, _i64, _i32, _i32, C.POINTER(_sz)]
 _lib.moa_linear.argtypes = [_i32, _vp, _i64, _i32, _vp, _i32, _vp, _vp, _sz, _vp]
 _lib.moa_fold_projection.argtypes = [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp]
-for _n in _SYMBOLS[2:27]:
+_lib.moa_mlp_block_workspace_bytes.argtypes = [_i32, _i64, _i32, _i32, C.POINTER(_sz)]
+_lib.moa_mlp_block.argtypes = [_i32, _vp, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp, C.c_float, _vp, _vp, _sz, _vp]
+_lib.moa_rmsnorm.argtypes = [_i32, _vp, _i64, _i32, _vp, C.c_float, _vp, _vp]
+for _n in _SYMBOLS[2:30]:
     getattr(_lib, _n).restype = C.c_int32
 
 
@@ -313,6 +316,34 @@ def tli_decoder_layer(shape: Shape, cfg: DecoderCfg, x, node_begin, w, kcache, v
         _dev(depth, torch.int32, B * M, "depth"), _dev(out, dt, B * Mn * d, "out"),
         _dev(k_draft, dt, B * ekv * M, "k_draft"), _dev(v_draft, dt, B * ekv * M, "v_draft"),
         _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
+
+
+def mlp_block_workspace_bytes(dtype, R, d, d_ff) -> int:
+    out = C.c_size_t(0)
+    _check(_lib.moa_mlp_block_workspace_bytes(int(dtype), int(R), int(d), int(d_ff), C.byref(out)))
+    return int(out.value)
+
+
+def mlp_block(dtype, x, res, g, w_gate, w_up, w_down, rms_eps, out, ws, stream=None):
+    """out = h + W_down(silu(W_gate n) * W_up n), h = x + res (res may be None), n = rmsnorm(h) * g; x [..., d]."""
+    dt = _TORCH_DTYPE[dtype]
+    d = x.shape[-1]
+    R = x.numel() // d
+    d_ff = w_gate.shape[0]
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_mlp_block(int(dtype), _dev(x, dt, R * d, "x"), _dev(res, dt, R * d, "res"), R, d, d_ff,
+                              _dev(g, dt, d, "g"), _dev(w_gate, dt, d_ff * d, "w_gate"), _dev(w_up, dt, d_ff * d, "w_up"),
+                              _dev(w_down, dt, d * d_ff, "w_down"), float(rms_eps), _dev(out, dt, R * d, "out"), wsp, wsb,
+                              _stream(stream)))
+
+
+def rmsnorm(dtype, x, g, rms_eps, out, stream=None):
+    """out = x / sqrt(mean(x^2) + rms_eps) * g over the last axis."""
+    dt = _TORCH_DTYPE[dtype]
+    d = x.shape[-1]
+    R = x.numel() // d
+    _check(_lib.moa_rmsnorm(int(dtype), _dev(x, dt, R * d, "x"), R, d, _dev(g, dt, d, "g"), float(rms_eps),
+                            _dev(out, dt, R * d, "out"), _stream(stream)))
 
 
 def tree_expand_level(level, child_logp, child_tok, cand_logp, cand_tok, cand_parent, frontier, stream=None):

@@ -678,6 +678,63 @@ static int32_t step_self_attn(const moa_step_args_t *a)
 // ---- a reused LLM decoder layer (Target Layer Inference)
 // workspace: [attention stage (queries | heads | scratch) | split-K scratch of the MLP projections |
 //             normed rows | projection result | residual stream (fp32) | gate, up | activation]
+// scratch of the MLP half of a pre-norm block
+struct MlpBufs {
+    char *lin;        // partial sums of the projections
+    size_t lin_bytes;
+    char *n;          // [R, d] normalised stream
+    char *tmp;        // [R, d] down projection where no kernel adds the residual on the way out
+    float *h;         // [R, d] the stream in single precision
+    char *gu;         // [R, 2 d_ff] gate | up where no kernel applies the activation on the way out
+    char *act;        // [R, d_ff]
+};
+
+// h = x + res (res may be NULL); out = h + Wdown(silu(Wgate n) * Wup n), n = rmsnorm(h) * g.
+// sites = launch sites of {norm, gate/up projection, down projection}
+static int32_t mlp_block_run(const char *who, int dt, const void *x, const void *res, int64_t R, int d, int d_ff,
+                             const void *g, const void *w_gate, const void *w_up, const void *w_down, float eps, void *out,
+                             const MlpBufs &b, const int *sites, hipStream_t st)
+{
+    const size_t es = esize(dt);
+    prof_set_site(sites[0]);
+    MOA_TRY_HIP(launch_rmsnorm(dt, x, res, R, d, g, eps, b.h, b.n, st), who);
+    LinArgs lg = {};
+    lg.X = b.n;
+    lg.R = R;
+    lg.K = d;
+    lg.ldx = d;
+    lg.nseg = 2;
+    lg.seg[0].W = w_gate;
+    lg.seg[0].N = d_ff;
+    lg.seg[0].st = row_store(b.gu, 2 * (int64_t)d_ff);
+    lg.seg[1].W = w_up;
+    lg.seg[1].N = d_ff;
+    lg.seg[1].st = row_store(b.gu + (size_t)d_ff * es, 2 * (int64_t)d_ff);
+    lg.ws = b.lin;
+    lg.ws_bytes = b.lin_bytes;
+    lg.epi = LinArgs::EPI_SWIGLU;            // act = silu(gate) * up, by the kernel that sums the K slices when there is one
+    lg.epi_out = b.act;
+    prof_set_site(sites[1]);
+    MOA_TRY_HIP(launch_linear(dt, lg, st), who);
+    LinArgs ld = {};
+    ld.X = b.act;
+    ld.R = R;
+    ld.K = d_ff;
+    ld.ldx = d_ff;
+    ld.nseg = 1;
+    ld.seg[0].W = w_down;
+    ld.seg[0].N = d;
+    ld.seg[0].st = row_store(b.tmp, d);
+    ld.ws = b.lin;
+    ld.ws_bytes = b.lin_bytes;
+    ld.epi = LinArgs::EPI_ADD_F32;           // out = h + down projection (the block's residual)
+    ld.epi_res = b.h;
+    ld.epi_out = out;
+    prof_set_site(sites[2]);
+    MOA_TRY_HIP(launch_linear(dt, ld, st), who);
+    return MOA_OK;
+}
+
 struct TliBufs {
     char *attn, *lin, *n, *tmp, *gu, *act;
     float *h1;
@@ -744,7 +801,6 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     hipStream_t st = (hipStream_t)stream;
     const int dt = shape->dtype, d = shape->d_model, d_ff = cfg->d_ff;
     const int64_t R = (int64_t)B * Mn;
-    const size_t es = esize(dt);
 
     // attention block: norm, Q/K/V, rotary positions, tree attention over cache + own path, output projection
     prof_set_site(S_TLI_NORM);
@@ -769,42 +825,79 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     if (rc) return rc;
 
     // MLP block: residual + norm, gate and up projections side by side, gated activation, down projection, residual
-    prof_set_site(S_TLI_NORM);
-    MOA_TRY_HIP(launch_rmsnorm(dt, x, t.tmp, R, d, g_mlp, cfg->rms_eps, t.h1, t.n, st), who);
-    LinArgs lg = {};
-    lg.X = t.n;
-    lg.R = R;
-    lg.K = d;
-    lg.ldx = d;
-    lg.nseg = 2;
-    lg.seg[0].W = w_gate;
-    lg.seg[0].N = d_ff;
-    lg.seg[0].st = row_store(t.gu, 2 * (int64_t)d_ff);
-    lg.seg[1].W = w_up;
-    lg.seg[1].N = d_ff;
-    lg.seg[1].st = row_store(t.gu + (size_t)d_ff * es, 2 * (int64_t)d_ff);
-    lg.ws = t.lin;
-    lg.ws_bytes = t.lin_bytes;
-    lg.epi = LinArgs::EPI_SWIGLU;            // act = silu(gate) * up, by the kernel that sums the K slices when there is one
-    lg.epi_out = t.act;
-    prof_set_site(S_TLI_GATE_UP);
-    MOA_TRY_HIP(launch_linear(dt, lg, st), who);
-    LinArgs ld = {};
-    ld.X = t.act;
-    ld.R = R;
-    ld.K = d_ff;
-    ld.ldx = d_ff;
-    ld.nseg = 1;
-    ld.seg[0].W = w_down;
-    ld.seg[0].N = d;
-    ld.seg[0].st = row_store(t.tmp, d);
-    ld.ws = t.lin;
-    ld.ws_bytes = t.lin_bytes;
-    ld.epi = LinArgs::EPI_ADD_F32;           // out = h1 + down projection (second residual)
-    ld.epi_res = t.h1;
-    ld.epi_out = out;
-    prof_set_site(S_TLI_DOWN);
-    MOA_TRY_HIP(launch_linear(dt, ld, st), who);
+    MlpBufs mb;
+    mb.lin = t.lin;
+    mb.lin_bytes = t.lin_bytes;
+    mb.n = t.n;
+    mb.tmp = t.tmp;
+    mb.h = t.h1;
+    mb.gu = t.gu;
+    mb.act = t.act;
+    static const int mlp_sites[3] = {S_TLI_NORM, S_TLI_GATE_UP, S_TLI_DOWN};
+    return mlp_block_run(who, dt, x, t.tmp, R, d, d_ff, g_mlp, w_gate, w_up, w_down, cfg->rms_eps, out, mb, mlp_sites, st);
+}
+
+// ---- the drafter's own layers: pre-norm in front of an attention sub-layer, MLP sub-block behind it
+static MlpBufs mlp_carve(int dtype, int64_t R, int d, int d_ff, void *ws, size_t *total)
+{
+    const size_t es = esize(dtype);
+    MlpBufs b;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *p = (char *)ws + off; off += align256(bytes); return p; };
+    b.lin_bytes = align256(max2(linear_workspace_bytes(dtype, R, d, 2 * d_ff), linear_workspace_bytes(dtype, R, d_ff, d)));
+    b.lin = take(b.lin_bytes);
+    b.n = take((size_t)R * d * es);
+    b.tmp = take((size_t)R * d * es);
+    b.h = (float *)take((size_t)R * d * sizeof(float));
+    b.gu = take((size_t)R * 2 * d_ff * es);
+    b.act = take((size_t)R * d_ff * es);
+    *total = off;
+    return b;
+}
+
+static int32_t mlp_check(const char *who, int32_t dtype, int64_t R, int32_t d, int32_t d_ff, float eps)
+{
+    if (dtype != MOA_F32 && dtype != MOA_BF16) return fail(MOA_ERR_DTYPE, "%s: dtype %d", who, dtype);
+    if (R < 0 || d < 1 || d_ff < 1 || R * (int64_t)(2 * (int64_t)d_ff > d ? 2 * (int64_t)d_ff : d) > ((int64_t)1 << 40))
+        return fail(MOA_ERR_SHAPE, "%s: R=%lld d=%d d_ff=%d", who, (long long)R, d, d_ff);
+    if (!(eps >= 0.f)) return fail(MOA_ERR_SHAPE, "%s: rms_eps=%g", who, (double)eps);
+    return MOA_OK;
+}
+
+int32_t moa_mlp_block_workspace_bytes(int32_t dtype, int64_t R, int32_t d, int32_t d_ff, size_t *bytes_host)
+{
+    if (!bytes_host) return fail(MOA_ERR_NULL, "mlp_block_workspace_bytes: NULL pointer");
+    int32_t rc = mlp_check("mlp_block_workspace_bytes", dtype, R, d, d_ff, 0.f);
+    if (rc) return rc;
+    mlp_carve(dtype, R, d, d_ff, nullptr, bytes_host);
+    return MOA_OK;
+}
+
+int32_t moa_mlp_block(int32_t dtype, const void *x, const void *res, int64_t R, int32_t d, int32_t d_ff, const void *g,
+                      const void *w_gate, const void *w_up, const void *w_down, float rms_eps, void *out, void *ws,
+                      size_t ws_bytes, void *stream)
+{
+    const char *who = "mlp_block";
+    int32_t rc = mlp_check(who, dtype, R, d, d_ff, rms_eps);
+    if (rc) return rc;
+    if (R == 0) return MOA_OK;             // nothing is touched, so nothing has to be there
+    if (!x || !g || !w_gate || !w_up || !w_down || !out) return fail(MOA_ERR_NULL, "%s: NULL pointer", who);
+    size_t need = 0;
+    const MlpBufs mb = mlp_carve(dtype, R, d, d_ff, ws, &need);
+    rc = check_ws(ws, ws_bytes, need);
+    if (rc) return rc;
+    static const int sites[3] = {S_MLP_NORM, S_MLP_GATE_UP, S_MLP_DOWN};
+    return mlp_block_run(who, dtype, x, res, R, d, d_ff, g, w_gate, w_up, w_down, rms_eps, out, mb, sites, (hipStream_t)stream);
+}
+
+int32_t moa_rmsnorm(int32_t dtype, const void *x, int64_t R, int32_t d, const void *g, float rms_eps, void *out, void *stream)
+{
+    int32_t rc = mlp_check("rmsnorm", dtype, R, d, 1, rms_eps);
+    if (rc) return rc;
+    if (R == 0) return MOA_OK;
+    if (!x || !g || !out) return fail(MOA_ERR_NULL, "rmsnorm: NULL pointer");
+    prof_set_site(S_MLP_NORM);
+    MOA_TRY_HIP(launch_rmsnorm(dtype, x, nullptr, R, d, g, rms_eps, nullptr, out, (hipStream_t)stream), "rmsnorm");
     return MOA_OK;
 }
 

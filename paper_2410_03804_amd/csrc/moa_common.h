@@ -101,7 +101,7 @@ enum SiteId {
     S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,
     S_CA_OPROJ, S_VERIFY_QKV, S_VERIFY_CORE, S_VERIFY_OPROJ, S_TREE_ACCEPT, S_STEP_SMALL, S_PAIR_QKV, S_PAIR_CORE,
     S_PAIR_OPROJ, S_PROBE, S_SA_QKV, S_SA_CORE, S_SA_OPROJ, S_TLI_QKV, S_TLI_CORE, S_TLI_OPROJ, S_TLI_NORM, S_TLI_ROPE,
-    S_TLI_GATE_UP, S_TLI_ACT, S_TLI_DOWN, S_TLI_ADD, S_TREE_EXPAND, S_TREE_FINALIZE, S_TOPK_LOGPROB, S_LM_HEAD, S_MSG, S_LINEAR, S_COUNT
+    S_TLI_GATE_UP, S_TLI_ACT, S_TLI_DOWN, S_TLI_ADD, S_TREE_EXPAND, S_TREE_FINALIZE, S_TOPK_LOGPROB, S_LM_HEAD, S_MSG, S_LINEAR, S_MLP_NORM, S_MLP_GATE_UP, S_MLP_DOWN, S_COUNT
 };
 // records the message moa_last_error returns and hands the code back (entry points outside moa_api.hip)
 int32_t api_fail(int32_t code, const char *msg);

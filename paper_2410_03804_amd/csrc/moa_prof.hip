@@ -41,7 +41,7 @@ const char *const kSiteNames[S_COUNT] = {
     "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept",
     "tree_build+accept+lengths", "ca.q_proj+verify.qkv_proj", "ca.core+verify.core", "ca.o_proj+verify.o_proj", "probe",
     "sa.qkv_proj", "sa.core", "sa.o_proj", "tli.qkv_proj", "tli.core", "tli.o_proj", "tli.rmsnorm", "tli.rope",
-    "tli.gate_up_proj", "tli.swiglu", "tli.down_proj", "tli.residual", "tree_expand", "tree_finalize", "topk_logprob", "lm_head", "message", "linear"};
+    "tli.gate_up_proj", "tli.swiglu", "tli.down_proj", "tli.residual", "tree_expand", "tree_finalize", "topk_logprob", "lm_head", "message", "linear", "mlp.rmsnorm", "mlp.gate_up_proj", "mlp.down_proj"};
 }  // namespace
 
 void prof_set_site(int site) { t_site = site; }
