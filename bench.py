@@ -64,6 +64,9 @@ def parse():
                          "the CA queries); not part of the headline step")
     ap.add_argument("--no-fold", action="store_true",
                     help="keep the memory's K/V projection a launch of its own instead of folding ca_wk/ca_wv with lsa_wo")
+    ap.add_argument("--drafter-blocks", action="store_true",
+                    help="also time the MLP sub-blocks behind the drafter's LSA / SA / CA layers (moa_mlp_block at the "
+                         "sizes of the appendix table) on the tree tokens; reported under 'drafter_blocks'")
     ap.add_argument("--tli-layers", type=int, default=0,
                     help="after the timed region, also time this many reused LLM decoder layers (Target Layer Inference) "
                          "on the tree tokens, each with its own weights; reported under 'tli', not in the headline")
@@ -203,6 +206,47 @@ def time_tli_layers(cfg, n_layers, stream, moa, mi, reps=20):
             "tokens_per_s": round(B * M / (us_layer * 1e-6), 1), "pieces": pieces}
 
 
+def time_drafter_blocks(cfg, stream, moa, mi, reps=30):
+    """moa_mlp_block behind each of the drafter's three attention layers, on B*M rows, rotating through enough weight
+    sets that none is cache-resident when it is touched again."""
+    import torch
+    import numpy as np
+    dt = cfg.dtype
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+    mdt = moa.BF16 if dt == "bf16" else moa.F32
+    es = 2 if dt == "bf16" else 4
+    R = cfg.B * cfg.M
+    out = {}
+    for which, (d, dff) in mi.drafter_mlp_sizes(cfg).items():
+        w0 = mi.drafter_mlp_weights(cfg, which)
+        wbytes = 3 * d * dff * es
+        nsets = max(2, int(math.ceil(600e6 / wbytes)))
+        rng = torch.Generator(device="cuda").manual_seed(7)
+        sets = []
+        for i in range(nsets):      # the first set is the seeded one; the others only have to be different memory
+            sets.append([torch.from_numpy(np.ascontiguousarray(w0[k])).to(tdt).cuda() if i == 0 else
+                         (torch.randn(w0[k].shape, device="cuda", generator=rng) * float(np.std(w0[k]))).to(tdt)
+                         for k in ("g", "w_gate", "w_up", "w_down")])
+        x = torch.randn((R, d), device="cuda", generator=rng).to(tdt)
+        res = (0.5 * torch.randn((R, d), device="cuda", generator=rng)).to(tdt)
+        y = torch.empty_like(x)
+        ws = torch.empty(max(moa.mlp_block_workspace_bytes(mdt, R, d, dff), 256), dtype=torch.uint8, device="cuda")
+        for i in range(min(nsets, 3)):
+            moa.mlp_block(mdt, x, res, *sets[i], 1e-5, y, ws, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(reps):
+            moa.mlp_block(mdt, x, res, *sets[i % nsets], 1e-5, y, ws, stream)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / reps
+        byt = wbytes + d * es + 3 * R * d * es
+        out[which] = {"rows": R, "d": d, "d_ff": dff, "us": round(us, 2), "alg_MiB": round(byt / 2 ** 20, 1),
+                      "gbs": round(byt / (us * 1e-6) / 1e9, 1), "frac_of_hbm_peak": round(byt / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                      "weight_sets": nsets}
+        del sets
+    return out
+
+
 def bound_of(bytes_, flops, peak_tflops):
     t_hbm = bytes_ / (HBM_PEAK_GBS * 1e9)
     t_mfma = flops / (peak_tflops * 1e12)
@@ -324,6 +368,7 @@ def main():
                         how="plain coalesced 1 GiB read; 4096 wavefronts x 4 independent 32x32x16 bf16 MFMA chains")
         del big
 
+    drafter_blocks = time_drafter_blocks(cfg, stream, moa, mi) if args.drafter_blocks else None
     tli = None
     if args.tli_layers > 0:
         tli = time_tli_layers(cfg, args.tli_layers, stream, moa, mi)
@@ -434,7 +479,7 @@ def main():
                                + ("; Self-Attention layer in front of the CA" if args.with_sa else ""),
                    "verify_layers": NL, "buffer_sets": nsets, "profile_steps": P},
         "roofline": roofline, "cpu_baseline": cpu, "ceilings": ceilings,
-        "tli": tli,
+        "tli": tli, "drafter_blocks": drafter_blocks,
         "hot_cache": {"ms_per_step": round(hot_ms, 5), "steps": hot_steps,
                       "note": "one buffer set reused: operands stay in the Infinity Cache; not the headline"},
         "kernel_us_per_step": round(kernel_us_sum, 2), "setup_s": round(setup_s, 1), "pieces": pieces,
