@@ -858,7 +858,8 @@ static MlpBufs mlp_carve(int dtype, int64_t R, int d, int d_ff, void *ws, size_t
 static int32_t mlp_check(const char *who, int32_t dtype, int64_t R, int32_t d, int32_t d_ff, float eps)
 {
     if (dtype != MOA_F32 && dtype != MOA_BF16) return fail(MOA_ERR_DTYPE, "%s: dtype %d", who, dtype);
-    if (R < 0 || d < 1 || d_ff < 1 || R * (int64_t)(2 * (int64_t)d_ff > d ? 2 * (int64_t)d_ff : d) > ((int64_t)1 << 40))
+    const int64_t widest = 2 * (int64_t)d_ff > d ? 2 * (int64_t)d_ff : d;      // longest row any kernel of the block walks
+    if (R < 0 || d < 1 || d_ff < 1 || R > ((int64_t)1 << 40) / widest)
         return fail(MOA_ERR_SHAPE, "%s: R=%lld d=%d d_ff=%d", who, (long long)R, d, d_ff);
     if (!(eps >= 0.f)) return fail(MOA_ERR_SHAPE, "%s: rms_eps=%g", who, (double)eps);
     return MOA_OK;
