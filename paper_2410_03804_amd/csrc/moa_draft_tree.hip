@@ -14,12 +14,27 @@ constexpr int TREE_MAX_CAND = 4096;       // candidates ranked in LDS by moa_tre
 
 __device__ __forceinline__ bool ranks_before(float a, int ia, float b, int ib) { return a > b || (a == b && ia < ib); }
 
+// how many of the entries (lp[u], u), u < n, rank before (v, c); lp is a 16-byte aligned LDS array, read four
+// entries at a time (every lane reads the same address: one broadcast read instead of four)
+__device__ __forceinline__ int rank_among(const float *lp, int n, float v, int c)
+{
+    int rank = 0;
+    const int n4 = n & ~3;
+    for (int u = 0; u < n4; u += 4) {
+        const f32x4 a = *(const f32x4 *)&lp[u];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) rank += ranks_before(a[e], u + e, v, c) ? 1 : 0;
+    }
+    for (int u = n4; u < n; ++u) rank += ranks_before(lp[u], u, v, c) ? 1 : 0;
+    return rank;
+}
+
 __global__ __launch_bounds__(256) void k_tree_expand(int level, int Bw, int n_max, const float *__restrict__ child_logp,
                                                      const int32_t *__restrict__ child_tok, float *__restrict__ cand_logp,
                                                      int32_t *__restrict__ cand_tok, int32_t *__restrict__ cand_parent,
                                                      int32_t *__restrict__ frontier)
 {
-    __shared__ float lp[256];
+    __shared__ __attribute__((aligned(16))) float lp[256];
     const int b = blockIdx.x, t = threadIdx.x;
     const int F = level == 1 ? 1 : Bw, n = F * Bw;
     const int base = level == 1 ? 0 : Bw + (level - 2) * Bw * Bw;
@@ -44,9 +59,7 @@ __global__ __launch_bounds__(256) void k_tree_expand(int level, int Bw, int n_ma
     }
     __syncthreads();                                       // every read of the old frontier is done
     if (t < n) {
-        int rank = 0;
-#pragma unroll 8
-        for (int u = 0; u < n; ++u) rank += ranks_before(lp[u], u, mine, t) ? 1 : 0;     // unrolled: LDS reads in flight together
+        const int rank = rank_among(lp, n, mine, t);
         if (rank < Bw) fr[rank] = base + t;
     }
 }
@@ -57,7 +70,7 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
                                                        int32_t *__restrict__ tok, int32_t *__restrict__ node_cand,
                                                        int32_t *dev_status)
 {
-    __shared__ float lp[TREE_MAX_CAND];
+    __shared__ __attribute__((aligned(16))) float lp[TREE_MAX_CAND];
     __shared__ int32_t node_of[TREE_MAX_CAND];
     __shared__ int32_t cnt[256];
     const int b = blockIdx.x, t = threadIdx.x;
@@ -74,24 +87,27 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
     int kept = 0;
     for (int c = c0; c < c1; ++c) {
         const float v = lp[c];
-        int rank = 0;
-#pragma unroll 8
-        for (int u = 0; u < n; ++u) rank += ranks_before(lp[u], u, v, c) ? 1 : 0;
-        const bool k = rank < keep;
+        const bool k = rank_among(lp, n, v, c) < keep;
         node_of[c] = k ? 1 : 0;
         kept += k ? 1 : 0;
     }
-    cnt[t] = kept;
-    __syncthreads();
-    if (t == 0) {                                          // 256 counts: a serial scan is a few hundred cycles
-        int run = 1;                                       // node 0 is the root
-        for (int i = 0; i < 256; ++i) { const int k = cnt[i]; cnt[i] = run; run += k; }
+    // exclusive prefix sum of the 256 counts, starting at 1 (node 0 is the root): within a wave by shuffles, the
+    // four wave totals through LDS
+    int incl = kept;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if ((t & 63) >= o) incl += up;
+    }
+    if ((t & 63) == 63) cnt[t >> 6] = incl;
+    if (t == 0) {
         po[0] = -1;
         to[0] = root_tok[b];
         no[0] = -1;
     }
     __syncthreads();
-    int next = cnt[t];
+    int next = 1 + incl - kept;
+    for (int w = 0; w < (t >> 6); ++w) next += cnt[w];
     for (int c = c0; c < c1; ++c) node_of[c] = node_of[c] ? next++ : -1;
     __syncthreads();
     for (int c = c0; c < c1; ++c) {
@@ -118,6 +134,7 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
 // that ranks after the previous winner" (value descending, id ascending: a total order, so ties need no care), each
 // round one pass over registers and one workgroup-wide reduction.  A second kernel ranks the S*Bw survivors of a
 // row and merges the slices' (max, sum of exponentials).
+typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
 constexpr int TOPK_EPT = 32;              // values a thread keeps
 constexpr int TOPK_MIN_SLICES = 32;
 
@@ -203,16 +220,20 @@ __global__ __launch_bounds__(256) void k_topk_merge(int Bw, int S, const float *
                                                     const float *__restrict__ smax, const float *__restrict__ ssum,
                                                     int32_t *__restrict__ tok, float *__restrict__ logp)
 {
-    extern __shared__ float cv[];                          // [n] values, then [n] ids
+    extern __shared__ __attribute__((aligned(16))) float cv[];   // [n] values, [n] ids, [S] slice maxima, [S] slice sums
     __shared__ float red[4];
     __shared__ float lse_s;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int64_t r = blockIdx.x;
     const int n = S * Bw;
     int32_t *ci = (int32_t *)(cv + n);
+    float *sm = cv + 2 * n, *ss = sm + S;
+    // everything the row needs is requested at once: one trip to memory instead of three
     for (int c = t; c < n; c += 256) { cv[c] = sval[r * n + c]; ci[c] = sid[r * n + c]; }
+    for (int k = t; k < S; k += 256) { sm[k] = smax[r * S + k]; ss[k] = ssum[r * S + k]; }
+    __syncthreads();
     float m = -INFINITY;
-    for (int k = t; k < S; k += 256) m = fmaxf(m, smax[r * S + k]);
+    for (int k = t; k < S; k += 256) m = fmaxf(m, sm[k]);
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
     if (lane == 0) red[wave] = m;
@@ -221,8 +242,8 @@ __global__ __launch_bounds__(256) void k_topk_merge(int Bw, int S, const float *
     __syncthreads();
     float sum = 0.f;
     for (int k = t; k < S; k += 256) {
-        const float mk = smax[r * S + k];
-        if (mk > -INFINITY) sum += ssum[r * S + k] * __expf(mk - m);
+        const float mk = sm[k];
+        if (mk > -INFINITY) sum += ss[k] * __expf(mk - m);
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
@@ -236,8 +257,17 @@ __global__ __launch_bounds__(256) void k_topk_merge(int Bw, int S, const float *
         const int id = ci[c];
         if (id == 0x7fffffff) continue;                    // an exhausted slice's filler
         int rank = 0;
+        if ((n & 3) == 0) {                                // four survivors per LDS read
+            for (int u = 0; u < n; u += 4) {
+                const f32x4 a = *(const f32x4 *)&cv[u];
+                const i32x4 b = *(const i32x4 *)&ci[u];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rank += ranks_before(a[e], b[e], v, id) ? 1 : 0;
+            }
+        } else {
 #pragma unroll 8
-        for (int u = 0; u < n; ++u) rank += ranks_before(cv[u], ci[u], v, id) ? 1 : 0;
+            for (int u = 0; u < n; ++u) rank += ranks_before(cv[u], ci[u], v, id) ? 1 : 0;
+        }
         if (rank < Bw) { tok[r * Bw + rank] = id; logp[r * Bw + rank] = v - lse; }
     }
 }
@@ -312,7 +342,7 @@ int32_t moa_topk_logprob(int32_t dtype, const void *logits, int32_t F, int32_t V
     MOA_KLAUNCH(k_topk_slices, dim3((unsigned)n), dim3(256), 0, st, dtype == MOA_BF16 ? 1 : 0, logits, V, Bw, S, sval, sid, smax, ssum);
     prof_end(st);
     if (hipGetLastError() != hipSuccess) return tree_fail(MOA_ERR_HIP, "topk_logprob: launch failed");
-    const size_t lds = (size_t)S * Bw * 8;
+    const size_t lds = (size_t)S * Bw * 8 + (size_t)S * 8;
     if (lds > 60 * 1024) return tree_fail(MOA_ERR_SHAPE, "topk_logprob: vocabulary too large for the merge");
     prof_begin(K_TOPK_MERGE, st);
     MOA_KLAUNCH(k_topk_merge, dim3(F), dim3(256), lds, st, Bw, S, sval, sid, smax, ssum, tok, logp);
