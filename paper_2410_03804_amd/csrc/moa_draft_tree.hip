@@ -130,11 +130,45 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
 
 // ---- the Bw most probable tokens of a row of logits, with log-probabilities
 // A row of the vocabulary is cut into S slices, one workgroup each, so that a handful of rows still fills the chip.
-// A thread holds its (at most 32) values in registers; the slice's Bw best are found by Bw rounds of "the best value
-// that ranks after the previous winner" (value descending, id ascending: a total order, so ties need no care), each
-// round one pass over registers and one workgroup-wide reduction.  A second kernel ranks the S*Bw survivors of a
-// row and merges the slices' (max, sum of exponentials).
+// A thread holds its (at most 32) values in registers and sorts them once, best first (value descending, id
+// ascending: a total order, so ties need no care); the slice's Bw best are then found by Bw rounds that compare only
+// the heads of the 256 lists (one workgroup-wide reduction per round).  A second kernel ranks the S*Bw survivors of
+// a row and merges the slices' (max, sum of exponentials).
 typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
+
+// Wavefront-wide maximum / minimum of an unsigned value by data-parallel-primitive moves inside the vector ALU (four
+// shifts within the rows of 16 lanes, then two row broadcasts), read from lane 63: a dozen ALU instructions where
+// the shuffle form makes six trips through the LDS crossbar.  Lanes a move does not reach keep their own value,
+// which is harmless for max and min.
+template <bool MAX>
+__device__ __forceinline__ uint32_t wave_reduce_u32(uint32_t x)
+{
+#define MOA_DPP_STEP(ctrl)                                                                                   \
+    {                                                                                                        \
+        const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, ctrl, 0xf, 0xf, false);     \
+        x = MAX ? (o > x ? o : x) : (o < x ? o : x);                                                         \
+    }
+    MOA_DPP_STEP(0x111)   // row_shr:1
+    MOA_DPP_STEP(0x112)   // row_shr:2
+    MOA_DPP_STEP(0x114)   // row_shr:4
+    MOA_DPP_STEP(0x118)   // row_shr:8   -> lane 15 of a row holds the row's result
+    MOA_DPP_STEP(0x142)   // row_bcast:15 -> lane 31: rows 0-1, lane 63: rows 2-3
+    MOA_DPP_STEP(0x143)   // row_bcast:31 -> lane 63: all four rows
+#undef MOA_DPP_STEP
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
+// a float as an unsigned integer of the same order (-inf lowest)
+__device__ __forceinline__ uint32_t orderable(float v)
+{
+    const uint32_t u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float from_orderable(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
 constexpr int TOPK_EPT = 32;              // values a thread keeps
 constexpr int TOPK_MIN_SLICES = 32;
 
@@ -145,6 +179,7 @@ static int topk_slices(int V)
 }
 
 // scratch per (row, slice): Bw values, Bw ids, max, sum
+template <int EPT>
 __global__ __launch_bounds__(256) void k_topk_slices(int is_bf16, const void *__restrict__ logits, int V, int Bw, int S,
                                                      float *__restrict__ sval, int32_t *__restrict__ sid,
                                                      float *__restrict__ smax, float *__restrict__ ssum)
@@ -157,16 +192,16 @@ __global__ __launch_bounds__(256) void k_topk_slices(int is_bf16, const void *__
     const int Vs = (V + S - 1) / S, v0 = s * Vs, v1 = min(v0 + Vs, V);
     const float *rf = (const float *)logits + r * V;
     const bf16_t *rb = (const bf16_t *)logits + r * V;
-    float x[TOPK_EPT];
+    float x[EPT];
 #pragma unroll
-    for (int i = 0; i < TOPK_EPT; ++i) {
+    for (int i = 0; i < EPT; ++i) {
         const int v = v0 + t + 256 * i;
         x[i] = v < v1 ? (is_bf16 ? bf2f(rb[v]) : rf[v]) : -INFINITY;
     }
     // the slice's log-sum-exp pieces
     float m = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < TOPK_EPT; ++i) m = fmaxf(m, x[i]);
+    for (int i = 0; i < EPT; ++i) m = fmaxf(m, x[i]);
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
     if (lane == 0) wm[wave] = m;
@@ -175,7 +210,7 @@ __global__ __launch_bounds__(256) void k_topk_slices(int is_bf16, const void *__
     float sum = 0.f;
     if (m > -INFINITY) {
 #pragma unroll
-        for (int i = 0; i < TOPK_EPT; ++i) sum += __expf(x[i] - m);      // exp(-inf) = 0 for the padding
+        for (int i = 0; i < EPT; ++i) sum += __expf(x[i] - m);      // exp(-inf) = 0 for the padding
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
@@ -183,24 +218,40 @@ __global__ __launch_bounds__(256) void k_topk_slices(int is_bf16, const void *__
     __syncthreads();
     const int64_t slot = r * S + s;
     if (t == 0) { smax[slot] = m; ssum[slot] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]); }
-    // Bw rounds of selection
-    float lastv = INFINITY;
-    int lasti = -1;
+    // Each thread sorts its own values once (a bitonic network on registers: no lane does anything another does not),
+    // best first; a round then only compares the heads of the 256 lists, and the one thread that wins moves its list up.
+    int id[EPT];
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+        const int v = v0 + t + 256 * i;
+        id[i] = v < v1 ? v : 0x7fffffff;
+    }
+#pragma unroll
+    for (int k = 2; k <= EPT; k <<= 1)
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1)
+#pragma unroll
+            for (int i = 0; i < EPT; ++i) {
+                const int l = i ^ j;
+                if (l > i) {
+                    const bool up = (i & k) == 0;              // this pair ends with the better element first
+                    const bool swap = up ? ranks_before(x[l], id[l], x[i], id[i]) : ranks_before(x[i], id[i], x[l], id[l]);
+                    const float xi = x[i], xl = x[l];
+                    const int ii = id[i], il = id[l];
+                    x[i] = swap ? xl : xi;
+                    x[l] = swap ? xi : xl;
+                    id[i] = swap ? il : ii;
+                    id[l] = swap ? ii : il;
+                }
+            }
     for (int round = 0; round < Bw; ++round) {
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-#pragma unroll
-        for (int i = 0; i < TOPK_EPT; ++i) {
-            const int v = v0 + t + 256 * i;
-            const bool after = v < v1 && ranks_before(lastv, lasti, x[i], v);
-            if (after && ranks_before(x[i], v, bv, bi)) { bv = x[i]; bi = v; }
-        }
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) {
-            const float ov = __shfl_xor(bv, o);
-            const int oi = __shfl_xor(bi, o);
-            if (ranks_before(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-        }
+        float bv = x[0];
+        int bi = id[0];
+        // the wavefront's best: the largest value, then the smallest id among the lanes that hold it
+        const uint32_t key = orderable(bv + 0.0f);         // -0 and +0 are the same value, as in every comparison here
+        const uint32_t kmax = wave_reduce_u32<true>(key);
+        bi = (int)wave_reduce_u32<false>(key == kmax ? (uint32_t)bi : 0x7fffffffu);
+        bv = from_orderable(kmax);
         __syncthreads();
         if (lane == 0) { wv[wave] = bv; wi[wave] = bi; }
         __syncthreads();
@@ -210,8 +261,12 @@ __global__ __launch_bounds__(256) void k_topk_slices(int is_bf16, const void *__
         for (int w = 1; w < 4; ++w)
             if (ranks_before(wv[w], wi[w], bv, bi)) { bv = wv[w]; bi = wi[w]; }
         if (t == 0) { sval[slot * Bw + round] = bv; sid[slot * Bw + round] = bi; }   // (-inf, INT_MAX) when the slice ran out
-        lastv = bv;
-        lasti = bi;
+        if (id[0] == bi && bi != 0x7fffffff) {             // the winner's list moves up
+#pragma unroll
+            for (int i = 0; i + 1 < EPT; ++i) { x[i] = x[i + 1]; id[i] = id[i + 1]; }
+            x[EPT - 1] = -INFINITY;
+            id[EPT - 1] = 0x7fffffff;
+        }
     }
 }
 
@@ -339,7 +394,10 @@ int32_t moa_topk_logprob(int32_t dtype, const void *logits, int32_t F, int32_t V
     hipStream_t st = (hipStream_t)stream;
     prof_set_site(S_TOPK_LOGPROB);
     prof_begin(K_TOPK_LOGPROB, st);
-    MOA_KLAUNCH(k_topk_slices, dim3((unsigned)n), dim3(256), 0, st, dtype == MOA_BF16 ? 1 : 0, logits, V, Bw, S, sval, sid, smax, ssum);
+    if ((V + S - 1) / S <= 256 * 16)         // half-filled slices (few rows, many slices): half the registers to walk per round
+        MOA_KLAUNCH(k_topk_slices<16>, dim3((unsigned)n), dim3(256), 0, st, dtype == MOA_BF16 ? 1 : 0, logits, V, Bw, S, sval, sid, smax, ssum);
+    else
+        MOA_KLAUNCH(k_topk_slices<TOPK_EPT>, dim3((unsigned)n), dim3(256), 0, st, dtype == MOA_BF16 ? 1 : 0, logits, V, Bw, S, sval, sid, smax, ssum);
     prof_end(st);
     if (hipGetLastError() != hipSuccess) return tree_fail(MOA_ERR_HIP, "topk_logprob: launch failed");
     const size_t lds = (size_t)S * Bw * 8 + (size_t)S * 8;

@@ -116,12 +116,15 @@ def test_tree_entry_points_reject_bad_shapes(G, moa):
 
 
 @pytest.mark.parametrize("dtype,F,V,Bw", [("f32", 8, 128256, 8), ("bf16", 8, 128256, 8), ("bf16", 3, 1000, 16), ("f32", 1, 37, 5),
-                                          ("f32", 2, 16, 16)])
+                                          ("f32", 2, 16, 16), ("bf16", 2, 200000, 8), ("f32", 1, 300000, 4)])
 def test_topk_logprob_parity(G, moa, oracle, dtype, F, V, Bw):
     rng = np.random.default_rng(V + Bw)
     logits = mi.quantize((rng.standard_normal((F, V)) * 3.0).astype(np.float32), dtype)
     logits[0, V // 3] = logits[0, V // 2] = logits[0].max() + (1.0 if dtype == "f32" else 1.0)       # tie for the first place
     logits = mi.quantize(logits, dtype)
+    if V >= 1000:                                            # zeros of both signs are one value: the lower id goes first
+        logits[-1] = np.minimum(logits[-1], 0.0)
+        logits[-1, [5, 70, V - 9]] = [-0.0, 0.0, -0.0]
     print(f"[case] topk_logprob {dtype} F={F} V={V} breadth={Bw}", flush=True)
     tok = torch.zeros((F, Bw), dtype=torch.int32, device="cuda")
     logp = torch.zeros((F, Bw), dtype=torch.float32, device="cuda")
