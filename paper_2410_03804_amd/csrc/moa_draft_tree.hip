@@ -14,18 +14,39 @@ constexpr int TREE_MAX_CAND = 4096;       // candidates ranked in LDS by moa_tre
 
 __device__ __forceinline__ bool ranks_before(float a, int ia, float b, int ib) { return a > b || (a == b && ia < ib); }
 
-// how many of the entries (lp[u], u), u < n, rank before (v, c); lp is a 16-byte aligned LDS array, read four
-// entries at a time (every lane reads the same address: one broadcast read instead of four)
-__device__ __forceinline__ int rank_among(const float *lp, int n, float v, int c)
+// a float as an unsigned integer of the same order (-inf lowest)
+__device__ __forceinline__ uint32_t orderable(float v)
+{
+    const uint32_t u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float from_orderable(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// (value, index) as one 64-bit key whose unsigned order is "ranks before": larger value first, then smaller index.
+// -0 and +0 are one value.  NaN never gets here (callers map it to -inf first).
+__device__ __forceinline__ uint64_t rank_key(float v, int idx)
+{
+    return ((uint64_t)orderable(v + 0.0f) << 32) | (uint64_t)(0xffffffffu - (uint32_t)idx);
+}
+__device__ __forceinline__ float key_value(uint64_t k) { return from_orderable((uint32_t)(k >> 32)); }
+__device__ __forceinline__ int key_index(uint64_t k) { return (int)(0xffffffffu - (uint32_t)k); }
+
+// how many of keys[0..n) rank before `mine`; keys is a 16-byte aligned LDS array, read two keys at a time (every
+// lane reads the same address: a broadcast)
+typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
+__device__ __forceinline__ int rank_among(const uint64_t *keys, int n, uint64_t mine)
 {
     int rank = 0;
-    const int n4 = n & ~3;
-    for (int u = 0; u < n4; u += 4) {
-        const f32x4 a = *(const f32x4 *)&lp[u];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) rank += ranks_before(a[e], u + e, v, c) ? 1 : 0;
+    const int n2 = n & ~1;
+#pragma unroll 4
+    for (int u = 0; u < n2; u += 2) {
+        const u64x2 a = *(const u64x2 *)&keys[u];
+        rank += (a[0] > mine ? 1 : 0) + (a[1] > mine ? 1 : 0);
     }
-    for (int u = n4; u < n; ++u) rank += ranks_before(lp[u], u, v, c) ? 1 : 0;
+    if (n2 < n) rank += keys[n2] > mine ? 1 : 0;
     return rank;
 }
 
@@ -34,13 +55,13 @@ __global__ __launch_bounds__(256) void k_tree_expand(int level, int Bw, int n_ma
                                                      int32_t *__restrict__ cand_tok, int32_t *__restrict__ cand_parent,
                                                      int32_t *__restrict__ frontier)
 {
-    __shared__ __attribute__((aligned(16))) float lp[256];
+    __shared__ __attribute__((aligned(16))) uint64_t lp[256];
     const int b = blockIdx.x, t = threadIdx.x;
     const int F = level == 1 ? 1 : Bw, n = F * Bw;
     const int base = level == 1 ? 0 : Bw + (level - 2) * Bw * Bw;
     float *clp = cand_logp + (int64_t)b * n_max;
     int32_t *ctk = cand_tok + (int64_t)b * n_max, *cpr = cand_parent + (int64_t)b * n_max, *fr = frontier + (int64_t)b * Bw;
-    float mine = 0.f;
+    uint64_t mine = 0;
     if (t < n) {
         const int f = t / Bw;
         float v = child_logp[(int64_t)b * n + t];
@@ -54,12 +75,12 @@ __global__ __launch_bounds__(256) void k_tree_expand(int level, int Bw, int n_ma
         clp[base + t] = v;
         ctk[base + t] = child_tok[(int64_t)b * n + t];
         cpr[base + t] = par;
-        lp[t] = v;
-        mine = v;
+        mine = rank_key(v, t);
+        lp[t] = mine;
     }
     __syncthreads();                                       // every read of the old frontier is done
     if (t < n) {
-        const int rank = rank_among(lp, n, mine, t);
+        const int rank = rank_among(lp, n, mine);
         if (rank < Bw) fr[rank] = base + t;
     }
 }
@@ -70,7 +91,7 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
                                                        int32_t *__restrict__ tok, int32_t *__restrict__ node_cand,
                                                        int32_t *dev_status)
 {
-    __shared__ __attribute__((aligned(16))) float lp[TREE_MAX_CAND];
+    __shared__ __attribute__((aligned(16))) uint64_t lp[TREE_MAX_CAND];
     __shared__ int32_t node_of[TREE_MAX_CAND];
     __shared__ int32_t cnt[256];
     const int b = blockIdx.x, t = threadIdx.x;
@@ -79,15 +100,14 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
     int32_t *po = parent + (int64_t)b * ld_out, *to = tok + (int64_t)b * ld_out, *no = node_cand + (int64_t)b * ld_out;
     for (int c = t; c < n; c += 256) {
         const float v = clp[c];
-        lp[c] = v == v ? v : -INFINITY;
+        lp[c] = rank_key(v == v ? v : -INFINITY, c);
     }
     __syncthreads();
     // each thread owns a run of consecutive candidates, so that node numbers follow candidate order
     const int per = (n + 255) / 256, c0 = t * per, c1 = min(c0 + per, n);
     int kept = 0;
     for (int c = c0; c < c1; ++c) {
-        const float v = lp[c];
-        const bool k = rank_among(lp, n, v, c) < keep;
+        const bool k = rank_among(lp, n, lp[c]) < keep;
         node_of[c] = k ? 1 : 0;
         kept += k ? 1 : 0;
     }
@@ -134,7 +154,6 @@ __global__ __launch_bounds__(256) void k_tree_finalize(int n, int n_max, int kee
 // ascending: a total order, so ties need no care); the slice's Bw best are then found by Bw rounds that compare only
 // the heads of the 256 lists (one workgroup-wide reduction per round).  A second kernel ranks the S*Bw survivors of
 // a row and merges the slices' (max, sum of exponentials).
-typedef __attribute__((ext_vector_type(4))) int32_t i32x4;
 
 // Wavefront-wide maximum / minimum of an unsigned value by data-parallel-primitive moves inside the vector ALU (four
 // shifts within the rows of 16 lanes, then two row broadcasts), read from lane 63: a dozen ALU instructions where
@@ -156,17 +175,6 @@ __device__ __forceinline__ uint32_t wave_reduce_u32(uint32_t x)
     MOA_DPP_STEP(0x143)   // row_bcast:31 -> lane 63: all four rows
 #undef MOA_DPP_STEP
     return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
-}
-
-// a float as an unsigned integer of the same order (-inf lowest)
-__device__ __forceinline__ uint32_t orderable(float v)
-{
-    const uint32_t u = __float_as_uint(v);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float from_orderable(uint32_t k)
-{
-    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
 constexpr int TOPK_EPT = 32;              // values a thread keeps
@@ -275,16 +283,15 @@ __global__ __launch_bounds__(256) void k_topk_merge(int Bw, int S, const float *
                                                     const float *__restrict__ smax, const float *__restrict__ ssum,
                                                     int32_t *__restrict__ tok, float *__restrict__ logp)
 {
-    extern __shared__ __attribute__((aligned(16))) float cv[];   // [n] values, [n] ids, [S] slice maxima, [S] slice sums
+    extern __shared__ __attribute__((aligned(16))) uint64_t ck[];   // [n] order keys, then [S] slice maxima, [S] slice sums
     __shared__ float red[4];
     __shared__ float lse_s;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int64_t r = blockIdx.x;
     const int n = S * Bw;
-    int32_t *ci = (int32_t *)(cv + n);
-    float *sm = cv + 2 * n, *ss = sm + S;
+    float *sm = (float *)(ck + n), *ss = sm + S;
     // everything the row needs is requested at once: one trip to memory instead of three
-    for (int c = t; c < n; c += 256) { cv[c] = sval[r * n + c]; ci[c] = sid[r * n + c]; }
+    for (int c = t; c < n; c += 256) ck[c] = rank_key(sval[r * n + c], sid[r * n + c]);
     for (int k = t; k < S; k += 256) { sm[k] = smax[r * S + k]; ss[k] = ssum[r * S + k]; }
     __syncthreads();
     float m = -INFINITY;
@@ -308,22 +315,11 @@ __global__ __launch_bounds__(256) void k_topk_merge(int Bw, int S, const float *
     __syncthreads();
     const float lse = lse_s;
     for (int c = t; c < n; c += 256) {
-        const float v = cv[c];
-        const int id = ci[c];
+        const uint64_t mine = ck[c];
+        const int id = key_index(mine);
         if (id == 0x7fffffff) continue;                    // an exhausted slice's filler
-        int rank = 0;
-        if ((n & 3) == 0) {                                // four survivors per LDS read
-            for (int u = 0; u < n; u += 4) {
-                const f32x4 a = *(const f32x4 *)&cv[u];
-                const i32x4 b = *(const i32x4 *)&ci[u];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) rank += ranks_before(a[e], b[e], v, id) ? 1 : 0;
-            }
-        } else {
-#pragma unroll 8
-            for (int u = 0; u < n; ++u) rank += ranks_before(cv[u], ci[u], v, id) ? 1 : 0;
-        }
-        if (rank < Bw) { tok[r * Bw + rank] = id; logp[r * Bw + rank] = v - lse; }
+        const int rank = rank_among(ck, n, mine);
+        if (rank < Bw) { tok[r * Bw + rank] = id; logp[r * Bw + rank] = key_value(mine) - lse; }
     }
 }
 
