@@ -30,9 +30,9 @@ VEC_F32_PEAK_TFLOPS = 157.3
 # plain 512 MiB device copy (fetch x2.000, write x1.000): profiles/c1_draft_step_hbm_traffic_pmc.md.  They hold for
 # the default workload only (C1, 2*E_kv-wide LSA input, one verify layer).
 PMC_TRAFFIC_MIB_C1 = {
-    "k_linear_splitk_bf16<4>": 89.99,     # mean of the two grouped launches of the default schedule
-    "k_linear_splitk_bf16<2>": 23.83,
-    "k_linear_tiled_bf16<2, 2>": 111.51,
+    "k_linear_splitk_chunked_bf16<4>": 82.54,     # mean of the two grouped launches of the default schedule
+    "k_linear_splitk_bf16<2>": 23.82,
+    "k_linear_tiled_bf16<2, 2>": 101.94,          # with the summing pass that rides in its launch
     "k_attn_fused<128, 8>": 10.28,
 }
 

@@ -259,6 +259,88 @@ __global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
     }
 }
 
+// The same for at most 64 rows with a workgroup walking CH consecutive 256-wide K chunks: the weights of the next
+// chunk are requested before this one's MFMAs (two register sets), the activation slice of a chunk goes through a
+// 33 KB LDS buffer (three workgroups per CU instead of two), and the partial sums are CH/2 times fewer.  The barriers
+// are bare s_barriers behind an LDS-only wait: __syncthreads() would wait for every outstanding global load, the
+// next chunk's weights included.
+template <int CH>
+__global__ __launch_bounds__(256, 3) void k_linear_splitk_chunked_bf16(SplitKArgs sa)
+{
+    constexpr int NQ = 2, KS = 128 * NQ, LDK = KS + 8, CPR = KS / 8, XL = (64 * CPR) / 256, RSTEP = 256 / CPR;
+    extern __shared__ __attribute__((aligned(16))) bf16_t Xs[];   // [64][LDK]
+    const LinArgs &a = sa.a;
+    if ((int)blockIdx.x < sa.lead_blocks) {        // the first workgroups of the grid carry the integer work
+        if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
+            step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)Xs, (int32_t *)Xs + MOA_MAX_TREE);
+        return;
+    }
+    const int bx = (int)blockIdx.x - sa.lead_blocks;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, kg = lane >> 4;
+    const int tile = bx / sa.splits, split = bx - tile * sa.splits;
+    int s = 0;
+    while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
+    const int n0 = (tile - sa.tile_begin[s]) * 64 + wave * 16;   // feature inside the segment
+    const int k0 = split * KS * CH;
+    const bf16_t *X = (const bf16_t *)(a.seg[s].X ? a.seg[s].X : a.X);
+    const int64_t ldx = a.seg[s].X ? a.seg[s].ldx : a.ldx;
+    const bf16_t *wp = (const bf16_t *)a.seg[s].W + (int64_t)(n0 + li) * a.K + k0 + 32 * kg;
+
+    // piece c = tid + 256 i of a slice is row c / CPR, 16-byte column c % CPR: one 32-bit lane offset serves all i
+    const uint32_t xoff = (uint32_t)(((tid / CPR) * ldx + 8 * (tid % CPR)) * (int64_t)sizeof(bf16_t));
+    u32x4 xr[XL];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) xr[i] = u32x4{0u, 0u, 0u, 0u};   // rows past the end stay zero; never stored
+    auto load_x = [&](int c) {
+        const char *xb = (const char *)(X + k0 + c * KS);
+#pragma unroll
+        for (int i = 0; i < XL; ++i)
+            if (tid / CPR + RSTEP * i < a.R)
+                xr[i] = *(const u32x4 *)(xb + (int64_t)i * RSTEP * ldx * (int64_t)sizeof(bf16_t) + xoff);
+    };
+    bf16x8 wf[2][NQ][4];
+    auto load_w = [&](int set, int c) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wf[set][q][j] = *(const bf16x8 *)(wp + c * KS + 128 * q + 8 * j);
+    };
+    load_x(0);
+    load_w(0, 0);
+    f32x4 acc[4];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int set = c & 1;
+        if (c + 1 < CH) load_w(set ^ 1, c + 1);
+        if (c > 0) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // every wave is done reading the previous slice
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int cc = tid + 256 * i;
+            *(u32x4 *)&Xs[(cc / CPR) * LDK + 8 * (cc % CPR)] = xr[i];
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (c + 1 < CH) load_x(c + 1);
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bf16x8 xf[4];
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) xf[rb] = *(const bf16x8 *)&Xs[(16 * rb + li) * LDK + 128 * q + 32 * kg + 8 * j];
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[set][q][j], xf[rb], acc[rb], 0, 0, 0);
+            }
+    }
+    // lane holds features 4 kg .. 4 kg + 3 of its wave's 16, for row 16 rb + li
+    float *p = sa.part + (int64_t)split * 64 * sa.ntot + tile * 64 + wave * 16 + 4 * kg;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+        if (16 * rb + li < a.R) *(f32x4 *)(p + (int64_t)(16 * rb + li) * sa.ntot) = acc[rb];
+}
+
 // one thread per (row, 8 consecutive features): sum the K slices in order, round once, store
 __device__ __forceinline__ void splitk_sum8(const SumArgs &sa, const float *p, f32x4 &lo, f32x4 &hi)
 {
@@ -652,10 +734,19 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
         ka.part = (float *)a.ws;
         ka.lead_blocks = (a.rider_units + 7) & ~7;
         *rode = a.rider_units > 0;
+        // At most 64 rows and a grid that still gives every CU a workgroup: K is cut into 1024-wide slices walked in
+        // four chunks (half the partial sums of the 512-wide single-shot form, three workgroups per CU); measured
+        // -4 us per step at C1.  MOA_SPLITK_PLAIN keeps the single-shot kernel (tuning).
+        static const bool plain = getenv("MOA_SPLITK_PLAIN") != nullptr;
+        constexpr int CH = 4;
+        const bool use_chunked = !plain && a.R <= 64 && a.K % (256 * CH) == 0 && (int64_t)t * (a.K / (256 * CH)) >= 256;
+        if (use_chunked) ka.splits = a.K / (256 * CH);
         const dim3 grid((unsigned)(ka.lead_blocks + t * ka.splits));
-        const size_t lds = (size_t)64 * (128 * nq + 8) * sizeof(bf16_t);
+        const size_t lds = (size_t)64 * (128 * (use_chunked ? 2 : nq) + 8) * sizeof(bf16_t);
         hipError_t e = hipSuccess;
-        prof_begin(K_LIN_SPLITK + 64 * nq, stream);
+        prof_begin(use_chunked ? K_LIN_SPLITK_CHUNKED + 64 * CH : K_LIN_SPLITK + 64 * nq, stream);
+        if (use_chunked) MOA_KLAUNCH(k_linear_splitk_chunked_bf16<CH>, grid, dim3(256), lds, stream, ka);
+        else
         switch (nq) {
         case 1: MOA_KLAUNCH(k_linear_splitk_bf16<1>, grid, dim3(256), lds, stream, ka); break;
         case 2: MOA_KLAUNCH(k_linear_splitk_bf16<2>, grid, dim3(256), lds, stream, ka); break;
