@@ -738,14 +738,18 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
         // four chunks (half the partial sums of the 512-wide single-shot form, three workgroups per CU); measured
         // -4 us per step at C1.  MOA_SPLITK_PLAIN keeps the single-shot kernel (tuning).
         static const bool plain = getenv("MOA_SPLITK_PLAIN") != nullptr;
-        constexpr int CH = 4;
-        const bool use_chunked = !plain && a.R <= 64 && a.K % (256 * CH) == 0 && (int64_t)t * (a.K / (256 * CH)) >= 256;
-        if (use_chunked) ka.splits = a.K / (256 * CH);
+        int ch = 0;                                  // chunks per workgroup; 0 = the single-shot kernel
+        if (!plain && a.R <= 64) {
+            if (a.K % 1024 == 0 && (int64_t)t * (a.K / 1024) >= 256) ch = 4;
+            else if (a.K % 512 == 0 && (int64_t)t * (a.K / 512) >= 256) ch = 2;
+        }
+        if (ch) ka.splits = a.K / (256 * ch);
         const dim3 grid((unsigned)(ka.lead_blocks + t * ka.splits));
-        const size_t lds = (size_t)64 * (128 * (use_chunked ? 2 : nq) + 8) * sizeof(bf16_t);
+        const size_t lds = (size_t)64 * (128 * (ch ? 2 : nq) + 8) * sizeof(bf16_t);
         hipError_t e = hipSuccess;
-        prof_begin(use_chunked ? K_LIN_SPLITK_CHUNKED + 64 * CH : K_LIN_SPLITK + 64 * nq, stream);
-        if (use_chunked) MOA_KLAUNCH(k_linear_splitk_chunked_bf16<CH>, grid, dim3(256), lds, stream, ka);
+        prof_begin(ch ? K_LIN_SPLITK_CHUNKED + 64 * ch : K_LIN_SPLITK + 64 * nq, stream);
+        if (ch == 4) MOA_KLAUNCH(k_linear_splitk_chunked_bf16<4>, grid, dim3(256), lds, stream, ka);
+        else if (ch == 2) MOA_KLAUNCH(k_linear_splitk_chunked_bf16<2>, grid, dim3(256), lds, stream, ka);
         else
         switch (nq) {
         case 1: MOA_KLAUNCH(k_linear_splitk_bf16<1>, grid, dim3(256), lds, stream, ka); break;

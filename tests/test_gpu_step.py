@@ -137,7 +137,7 @@ def test_schedules_agree(G, case):
 @pytest.mark.parametrize("case", ["small_bf16", "C1_bf16", "C0_f32"])
 def test_folded_memory_projection_agrees_with_the_two_projections(G, case):
     """With ca_wk lsa_wo and ca_wv lsa_wo folded once, the memory's new rows come straight from LSA's mean-folded heads
-    ((a Wo^T) Wk^T = a (Wk Wo)^T): same rows to rounding, everything else bit for bit."""
+    ((a Wo^T) Wk^T = a (Wk Wo)^T): same rows to rounding, the integer results bit for bit."""
     from paper_2410_03804_amd.workload import DeviceStep
     cfg, nlayers, lsa_tokens, with_sa = _case(case)
     work = mi.step_workload(cfg, n_verify_layers=nlayers)
@@ -149,8 +149,11 @@ def test_folded_memory_projection_agrees_with_the_two_projections(G, case):
         assert step.dev_status.item() == 0
         res.append(step)
     a, b = res
-    for name in ("lsa_out", "mask", "path", "n_path", "bonus"):
+    for name in ("mask", "path", "n_path", "bonus"):
         assert torch.equal(getattr(a, name), getattr(b, name)), name
+    # the LSA output comes from a launch twice as wide when the folded projections share it, which may take another
+    # slicing of K: the same sums in another order
+    assert torch.allclose(a.lsa_out.float(), b.lsa_out.float(), atol=G.ABS_TOL[cfg.dtype] / 4, rtol=G.REL_TOL[cfg.dtype] / 4)
     assert torch.equal(a.ca_len[0], b.ca_len[0])
     for x, y in ((a.ca_k, b.ca_k), (a.ca_v, b.ca_v), (a.ca_out, b.ca_out)):
         assert torch.allclose(x.float(), y.float(), atol=G.ABS_TOL[cfg.dtype], rtol=G.REL_TOL[cfg.dtype])
