@@ -226,14 +226,16 @@ __global__ __launch_bounds__(256) void k_linear_splitk_bf16(SplitKArgs sa)
 
     // The weights stay in registers while the workgroup walks the row tiles (one at decode sizes): W is
     // streamed once however many rows there are; the next tile's X slice is requested before this one is used.
+    // Bare barriers behind an LDS-only wait: __syncthreads() also waits for every outstanding global load, which
+    // would hold a row tile's MFMAs until the next tile's activations, requested just before, have arrived.
     for (int rt = 0; rt < rowtiles; ++rt) {
-        if (rt > 0) __syncthreads();           // every wave is done reading the previous slice
+        if (rt > 0) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // every wave is done reading the previous slice
 #pragma unroll
         for (int i = 0; i < XL; ++i) {
             const int c = tid + 256 * i;
             *(u32x4 *)&Xs[(c / CPR) * LDK + 8 * (c % CPR)] = xr[i];
         }
-        __syncthreads();
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         if (rt + 1 < rowtiles) load_x(rt + 1);
 
         f32x4 acc[4];
