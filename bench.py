@@ -31,7 +31,7 @@ VEC_F32_PEAK_TFLOPS = 157.3
 # the default workload only (C1, 2*E_kv-wide LSA input, one verify layer).
 PMC_TRAFFIC_MIB_C1 = {
     "k_linear_splitk_chunked_bf16<4>": 82.54,     # mean of the two grouped launches of the default schedule
-    "k_linear_splitk_bf16<2>": 23.82,
+    "k_linear_splitk_chunked_bf16<2>": 20.32,
     "k_linear_tiled_bf16<2, 2>": 101.94,          # with the summing pass that rides in its launch
     "k_attn_fused<128, 8>": 10.28,
 }
