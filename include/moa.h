@@ -386,6 +386,18 @@ int32_t moa_profile_collect(moa_profile_row_t *rows_host, int32_t max_rows, int3
 const char *moa_profile_kernel_name(int32_t kernel);
 const char *moa_profile_site_name(int32_t site);
 
+/* Testing aid (not part of the method).  The attention core of moa_cross_attn_draft, moa_tree_verify_attn,
+ * moa_self_attn_draft, moa_tli_decoder_layer and moa_draft_step has two matrix-core forms for bf16 with head_dim 64
+ * or 128 and picks one from the call's shape: one workgroup per 32 query rows walking the whole key range (short key
+ * ranges, few workgroups) or the key range split over workgroups with a merging pass (everything else).  Both compute
+ * the attention of Sec. 2.2 / 3.1.2; they differ in the order partial sums are merged.  This call forces one of them
+ * for every later call of the process (MOA_ATTN_KERNEL_AUTO restores the choice by shape) so that a parity test can
+ * run each case through both.  A forced form that a call cannot take (fp32, other head_dim, workspace too small for
+ * the split form) falls back as the automatic choice would.  Host only, launches nothing; MOA_ERR_SHAPE for another
+ * value.  Not thread-safe against calls in flight on other host threads (they see either value). */
+enum { MOA_ATTN_KERNEL_AUTO = 0, MOA_ATTN_KERNEL_WHOLE = 1, MOA_ATTN_KERNEL_SPLIT = 2 };
+int32_t moa_debug_force_attn_kernel(int32_t form);
+
 /* Two probes of what the device delivers in practice, timed like any other kernel through the aid
  * above (kernels "k_probe_read", "k_probe_mfma"); a benchmark prints them beside the published
  * peaks.  moa_probe_read streams `bytes` (multiple of 16, 16-byte aligned device buffer) once with

@@ -40,6 +40,22 @@ def build(force: bool = False) -> Path:
     return _LIB
 
 
+SANITIZE_FLAGS = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                  "-fno-omit-frame-pointer", "-static-libasan"]
+
+
+def build_sanitize_driver(out_dir=None) -> Path:
+    """Compile moa_ref.c together with sanitize_driver.c under AddressSanitizer + UndefinedBehaviorSanitizer into
+    an executable (host code only; a CPU test runs it).  The sanitizer runtime is linked statically so that the
+    program does not depend on the order of preloaded libraries."""
+    exe = Path(out_dir or _HERE) / "moa_ref_sanitize"
+    tmp = exe.with_suffix(f".tmp{os.getpid()}")
+    subprocess.check_call(["gcc", *SANITIZE_FLAGS, "-fopenmp", "-Wall", "-Wextra", "-o", str(tmp), str(_SRC),
+                           str(_HERE / "sanitize_driver.c"), "-lm"])
+    os.replace(tmp, exe)
+    return exe
+
+
 _lib = None
 
 

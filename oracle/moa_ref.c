@@ -151,6 +151,7 @@ int moa_ref_lsa(const double *hs, int64_t T, int L, int d_in, int Hq, int Hkv, i
         double *vg = (double *)malloc(sizeof(double) * (size_t)L * dh);
         double *oh = (double *)malloc(sizeof(double) * (size_t)dh);
         if (!Q || !K || !V || !A || !Y || !s || !vg || !oh) {
+#pragma omp atomic write
             bad = 1;
         } else {
             moa_ref_linear(X, L, d_in, wq, Eq, Q);

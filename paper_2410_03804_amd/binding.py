@@ -70,7 +70,8 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
             "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
-            "moa_msg_unpack_accept", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma"]
+            "moa_msg_unpack_accept", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma",
+            "moa_debug_force_attn_kernel"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -130,6 +131,7 @@ _lib.moa_profile_kernel_name.restype = C.c_char_p
 _lib.moa_profile_kernel_name.argtypes = [_i32]
 _lib.moa_profile_site_name.restype = C.c_char_p
 _lib.moa_profile_site_name.argtypes = [_i32]
+_lib.moa_debug_force_attn_kernel.argtypes = [_i32]
 _lib.moa_probe_read.argtypes = [_vp, _sz, _vp, _vp]
 _lib.moa_probe_mfma.argtypes = [_i32, _vp, C.POINTER(_i64), _vp]
 
@@ -596,6 +598,15 @@ def profile_enable(on: bool, only_kernel: str | None = None, every: int = 1):
     """Events around every `every`-th launch (of `only_kernel` only, when given)."""
     _check(_lib.moa_profile_sample_every(every))
     _check(_lib.moa_profile_enable(1 if on else 0, -1 if only_kernel is None else profile_kernel_id(only_kernel)))
+
+
+ATTN_KERNEL = {"auto": 0, "whole": 1, "split": 2}
+
+
+def debug_force_attn_kernel(form: str = "auto"):
+    """Force one of the two matrix-core forms of the attention core for every later call ("auto" restores the
+    choice by shape); a testing aid."""
+    _check(_lib.moa_debug_force_attn_kernel(ATTN_KERNEL[form]))
 
 
 def probe_read(buf, scratch4, stream=None):

@@ -20,9 +20,14 @@
 #include "../../include/moa.h"
 
 #include <math.h>
-#include <stdlib.h>
+
+#include <atomic>
 
 namespace moa {
+
+// which MFMA form the attention core takes: 0 = chosen from the call's shape, 1 = whole key range per workgroup,
+// 2 = split-KV + merge (moa_debug_force_attn_kernel; process-wide, read once per launch)
+static std::atomic<int> g_attn_form{0};
 
 __device__ __forceinline__ float wave_max(float v)
 {
@@ -712,24 +717,17 @@ static bool mfma_ok(int dtype, int dh, const AttnArgs *a)
     return al(a->q) && al(a->kcache) && al(a->vcache) && al(a->ktree) && al(a->vtree) && al(a->out);
 }
 
-// 32-row blocks per wave of the split-KV kernel
-static int attn_nblk(int RG)
-{
-    // one block per wave keeps two workgroups per CU, which measured 25 % faster than two blocks per wave at
-    // RG = 512 even though K/V are then read by twice as many row tiles (MOA_NBLK=2 selects the other for tuning)
-    const char *e = getenv("MOA_NBLK");
-    (void)RG;
-    return (e && e[0] == '2') ? 2 : 1;
-}
+// 32-row blocks per wave of the split-KV kernel: one block per wave keeps two workgroups per CU, which measured
+// 25 % faster than two blocks per wave at RG = 512 even though K/V are then read by twice as many row tiles
+constexpr int ATTN_NBLK = 1;
 
 static SplitGeom split_geometry(int B, int Mq, int H, int Hkv, int dh, int P_cap, bool tree)
 {
     const int RG = (H / Hkv) * Mq;
     const int tiles_cap = (P_cap + KT - 1) / KT;
     SplitGeom g;
-    const int nblk = attn_nblk(RG);
-    g.rowtiles = (RG + 128 * nblk - 1) / (128 * nblk);
-    g.rows_pad = g.rowtiles * 128 * nblk;
+    g.rowtiles = (RG + 128 * ATTN_NBLK - 1) / (128 * ATTN_NBLK);
+    g.rows_pad = g.rowtiles * 128 * ATTN_NBLK;
     int want = 512 / (B * Hkv * g.rowtiles);        // about two workgroups per compute unit
     int most = tiles_cap / 2;                        // at least two tiles per slice
     if (want > most) want = most;
@@ -766,15 +764,15 @@ static bool attn_split_ok(const AttnArgs &a, int P_cap_geo)
 // fixed part, but re-reads K/V once per 32 query rows and runs one workgroup per CU: it wins while the call is
 // latency-bound, i.e. while its workgroups fit the chip in one round and the key range is short (C1: 14.5 us
 // against 17.8 + 6.8 us).  With more work the split form (128 rows per workgroup, two workgroups per CU, then the
-// merge) is ahead (B = 16, prefixes up to 2048: 122 against 166 us).  MOA_ATTN=split / fused overrides the
-// choice (tuning and tests).
+// merge) is ahead (B = 16, prefixes up to 2048: 122 against 166 us).  moa_debug_force_attn_kernel overrides the
+// choice (the parity tests run every case through both forms).
 constexpr int FUSED_MAX_KEYS = 8192;
 constexpr int FUSED_MAX_WORKGROUPS = 256;
 static bool want_fused(const AttnArgs &a)
 {
-    const char *e = getenv("MOA_ATTN");
-    if (e && e[0] == 's') return false;
-    if (e && e[0] == 'f') return true;
+    const int form = g_attn_form.load(std::memory_order_relaxed);
+    if (form == MOA_ATTN_KERNEL_SPLIT) return false;
+    if (form == MOA_ATTN_KERNEL_WHOLE) return true;
     const int64_t wgs = (int64_t)a.B * a.Hkv * (((a.H / a.Hkv) * a.Mq + 31) / 32);
     return a.P_cap + a.Mt <= FUSED_MAX_KEYS && wgs <= FUSED_MAX_WORKGROUPS;
 }
@@ -785,14 +783,8 @@ static hipError_t launch_fused_as(const AttnGroup &grp, int nrb, unsigned grid, 
 {
     constexpr size_t lds = FusedLds<DH, NW>::bytes;
     static bool raised[16] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    hipError_t e = raise_lds_limit_once(raised, (const void *)k_attn_fused<DH, NW>, lds);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 16 || !raised[dev]) {
-        e = hipFuncSetAttribute((const void *)k_attn_fused<DH, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < 16) raised[dev] = true;
-    }
     prof_begin(K_ATTN_FUSED + 64 * (DH * 8 + NW / 4), stream);
     MOA_KLAUNCH((k_attn_fused<DH, NW>), dim3(grid), dim3(64 * NW), lds, stream, grp, nrb);
     prof_end(stream);
@@ -827,16 +819,9 @@ static hipError_t launch_attn_split(const AttnArgs *calls, int n, hipStream_t st
     grp.ncalls = n;
     const dim3 grid(g.nsplit, g.rowtiles, n * grp.nbg);
     const int nblocks = n * a.B * a.Mq * a.H;
-    const bool two = attn_nblk((a.H / a.Hkv) * a.Mq) == 2;
-    const int var = a.dh * 8 + (two ? 2 : 1);
-    prof_begin(K_ATTN_MFMA + 64 * var, stream);
-    if (a.dh == 128) {
-        if (two) MOA_KLAUNCH((k_attn_mfma<128, 2>), grid, dim3(256), 0, stream, grp, g);
-        else MOA_KLAUNCH((k_attn_mfma<128, 1>), grid, dim3(256), 0, stream, grp, g);
-    } else {
-        if (two) MOA_KLAUNCH((k_attn_mfma<64, 2>), grid, dim3(256), 0, stream, grp, g);
-        else MOA_KLAUNCH((k_attn_mfma<64, 1>), grid, dim3(256), 0, stream, grp, g);
-    }
+    prof_begin(K_ATTN_MFMA + 64 * (a.dh * 8 + ATTN_NBLK), stream);
+    if (a.dh == 128) MOA_KLAUNCH((k_attn_mfma<128, ATTN_NBLK>), grid, dim3(256), 0, stream, grp, g);
+    else MOA_KLAUNCH((k_attn_mfma<64, ATTN_NBLK>), grid, dim3(256), 0, stream, grp, g);
     prof_end(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -884,3 +869,11 @@ hipError_t launch_attn_pair(const AttnArgs &a0_in, const AttnArgs &a1_in, hipStr
 }
 
 }  // namespace moa
+
+extern "C" int32_t moa_debug_force_attn_kernel(int32_t form)
+{
+    if (form < MOA_ATTN_KERNEL_AUTO || form > MOA_ATTN_KERNEL_SPLIT)
+        return moa::api_fail(MOA_ERR_SHAPE, "debug_force_attn_kernel: form must be MOA_ATTN_KERNEL_AUTO / _WHOLE / _SPLIT");
+    moa::g_attn_form.store(form, std::memory_order_relaxed);
+    return MOA_OK;
+}

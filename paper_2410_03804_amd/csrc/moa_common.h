@@ -119,6 +119,19 @@ hipEvent_t prof_stop_event();
         else hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                                 \
     } while (0)
 
+// Raises a kernel's dynamic-LDS limit the first time it is launched on a device (done[] belongs to that kernel).
+// Two threads racing here set the same value twice.
+inline hipError_t raise_lds_limit_once(bool (&done)[16], const void *kernel, size_t bytes)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 16 && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 16) done[dev] = true;
+    return e;
+}
+
 // the integer work of a step (tree masks, accept walk, memory lengths): 2 B + 1 units of one wavefront each
 struct StepSmallArgs {
     const int32_t *parent, *tok, *tgt, *tok_off;

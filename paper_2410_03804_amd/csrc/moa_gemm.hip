@@ -12,8 +12,6 @@
 #include "moa_common.h"
 #include "moa_tree_device.h"
 
-#include <stdlib.h>
-
 namespace moa {
 
 // ------------------------------------------------------------------ generic
@@ -638,7 +636,8 @@ static hipError_t launch_tiled(const LinArgs &a, hipStream_t stream)
     ta.lead_blocks = ta.small_lead + ((ta.red_blocks + 7) & ~7);
     const dim3 grid((unsigned)(ta.lead_blocks + 8 * ta.tiles_per_xcd * (int)((a.R + BM - 1) / BM)));
     const size_t lds = (size_t)2 * (BN + BM) * 64 * sizeof(bf16_t);
-    hipError_t e = hipFuncSetAttribute((const void *)k_linear_tiled_bf16<WF, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static bool raised[16] = {};
+    hipError_t e = raise_lds_limit_once(raised, (const void *)k_linear_tiled_bf16<WF, WR>, lds);
     if (e != hipSuccess) return e;
     prof_begin(K_LIN_TILED + 64 * (WF * 8 + WR), stream);
     MOA_KLAUNCH((k_linear_tiled_bf16<WF, WR>), grid, dim3(256), lds, stream, ta);
@@ -716,13 +715,9 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
     int nq = 0;
     const LinPath path = linear_path(dtype, a, &nq);
     if (path == P_TILED) {
-        bool all256 = true;
-        for (int s = 0; s < a.nseg; ++s) all256 = all256 && a.seg[s].N % 256 == 0;
-        // 2x2 blocks per wave keeps two workgroups per CU; the 4x2 variant halves the LDS traffic per MFMA
-        // but drops to one workgroup per CU and measured slower (MOA_TILE=42 selects it for tuning).
-        const char *force = getenv("MOA_TILE");
+        // 2x2 blocks per wave keeps two workgroups per CU; a 4x2 variant halves the LDS traffic per MFMA but drops
+        // to one workgroup per CU and measured slower
         *rode = a.rider_units > 0;
-        if (all256 && force && force[0] == '4') return launch_tiled<4, 2>(a, stream);
         return launch_tiled<2, 2>(a, stream);
     }
     if (path == P_SPLITK) {
@@ -738,10 +733,9 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
         *rode = a.rider_units > 0;
         // At most 64 rows and a grid that still gives every CU a workgroup: K is cut into 1024-wide slices walked in
         // four chunks (half the partial sums of the 512-wide single-shot form, three workgroups per CU); measured
-        // -4 us per step at C1.  MOA_SPLITK_PLAIN keeps the single-shot kernel (tuning).
-        static const bool plain = getenv("MOA_SPLITK_PLAIN") != nullptr;
+        // -4 us per step at C1.
         int ch = 0;                                  // chunks per workgroup; 0 = the single-shot kernel
-        if (!plain && a.R <= 64) {
+        if (a.R <= 64) {
             if (a.K % 1024 == 0 && (int64_t)t * (a.K / 1024) >= 256) ch = 4;
             else if (a.K % 512 == 0 && (int64_t)t * (a.K / 512) >= 256) ch = 2;
         }
@@ -758,7 +752,8 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
         case 2: MOA_KLAUNCH(k_linear_splitk_bf16<2>, grid, dim3(256), lds, stream, ka); break;
         case 4: MOA_KLAUNCH(k_linear_splitk_bf16<4>, grid, dim3(256), lds, stream, ka); break;
         default:
-            e = hipFuncSetAttribute((const void *)k_linear_splitk_bf16<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            static bool raised8[16] = {};
+            e = raise_lds_limit_once(raised8, (const void *)k_linear_splitk_bf16<8>, lds);
             if (e == hipSuccess) MOA_KLAUNCH(k_linear_splitk_bf16<8>, grid, dim3(256), lds, stream, ka);
             break;
         }

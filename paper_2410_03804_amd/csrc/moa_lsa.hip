@@ -214,6 +214,8 @@ __global__ __launch_bounds__(256) void k_lsa_attn_mfma(LsaAttnArgs a)
     }
 }
 
+constexpr size_t LSA_MAX_LDS = 150 * 1024;   // what the host-side argument check admits
+
 size_t lsa_attn_lds_bytes(int /*dtype*/, int L, int dh)
 {
     return sizeof(float) * ((size_t)2 * L * (dh + 1) + (size_t)L * (L + 1) + L);
@@ -241,14 +243,16 @@ hipError_t launch_lsa_attn(const LsaAttnArgs &a, hipStream_t stream)
         return hipGetLastError();
     }
     const size_t lds = lsa_attn_lds_bytes(a.dtype, a.L, a.dh);
+    if (lds > LSA_MAX_LDS) return hipErrorInvalidValue;
     const dim3 grid((unsigned)(a.T * a.Hq));
     hipError_t e;
+    static bool raised[2][16] = {};          // the limit is raised once, to the most any accepted call needs
     if (a.dtype == DT_BF16) {
-        e = hipFuncSetAttribute((const void *)k_lsa_attn<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = raise_lds_limit_once(raised[0], (const void *)k_lsa_attn<bf16_t>, LSA_MAX_LDS);
         if (e != hipSuccess) return e;
         { prof_begin(K_LSA_ATTN, stream); MOA_KLAUNCH(k_lsa_attn<bf16_t>, grid, dim3(256), lds, stream, a); prof_end(stream); }
     } else {
-        e = hipFuncSetAttribute((const void *)k_lsa_attn<float>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = raise_lds_limit_once(raised[1], (const void *)k_lsa_attn<float>, LSA_MAX_LDS);
         if (e != hipSuccess) return e;
         { prof_begin(K_LSA_ATTN, stream); MOA_KLAUNCH(k_lsa_attn<float>, grid, dim3(256), lds, stream, a); prof_end(stream); }
     }

@@ -74,3 +74,37 @@ def check_close(got, want, dtype, what, residual_stream=False, stages=1):
         assert err <= ABS_TOL[dtype], f"{what}: max-abs {err:.3e} > {ABS_TOL[dtype]}"
     assert rel <= stages * REL_TOL[dtype], f"{what}: max-abs/rms {rel:.3e} > {stages} * {REL_TOL[dtype]}"
     return err, rel
+
+
+def sample_sequences(plen, n):
+    """Indices of n sequences that include the shortest and the longest prefix."""
+    order = np.argsort(plen, kind="stable")
+    pick = {int(order[0]), int(order[-1])}
+    for b in order[len(order) // 2:]:
+        if len(pick) >= n:
+            break
+        pick.add(int(b))
+    return sorted(pick)
+
+
+def slice_step_work(work, seqs):
+    """The step workload restricted to the sequences `seqs` (indexing only): every sequence of a step is independent
+    of the others, so the oracle's result on the slice is exact for the rows it covers.  Returns the sliced workload
+    and the rows of the full LSA input / output that belong to it."""
+    cfg = work["cfg"]
+    seqs = list(seqs)
+    off = work["tok_off"]
+    rows = np.concatenate([np.arange(off[b], off[b + 1]) for b in seqs]).astype(np.int64)
+    counts = [int(off[b + 1] - off[b]) for b in seqs]
+    sub = dict(work)
+    sub["cfg"] = mi.scaled(cfg, B=len(seqs))
+    for k in ("parent", "tok", "tgt", "prefix_len", "ca_xq", "ca_k", "ca_v", "ca_len0"):
+        sub[k] = work[k][seqs]
+    sub["lsa_hs"] = work["lsa_hs"][rows]
+    sub["tok_off"] = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    sub["layers"] = [dict(w=lay["w"], x=lay["x"][seqs], kcache=lay["kcache"][seqs], vcache=lay["vcache"][seqs])
+                     for lay in work["layers"]]
+    if work.get("sa") is not None:
+        sa = work["sa"]
+        sub["sa"] = dict(w=sa["w"], emb=sa["emb"][seqs], kcache=sa["kcache"][seqs], vcache=sa["vcache"][seqs])
+    return sub, rows

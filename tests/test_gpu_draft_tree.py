@@ -154,16 +154,18 @@ def test_lm_head_argmax_parity(G, moa, oracle, R, d, V):
     moa.lm_head_argmax(G.dev(x, "bf16"), G.dev(w, "bf16"), tgt, ws, best)
     torch.cuda.synchronize()
     got = tgt.cpu().numpy()
-    logits = x.astype(np.float64) @ w.astype(np.float64).T                      # what the oracle maximises, all of it
-    wt, wb = oracle.lm_head_argmax(x, w) if V <= 5000 else (np.argmax(logits, axis=1).astype(np.int32), logits.max(axis=1))
-    assert np.array_equal(wt, np.argmax(logits, axis=1))
+    # the oracle on every row of the small heads, on the first rows of the full vocabulary (rows are independent)
+    rows = np.arange(R if V <= 5000 else min(R, 6))
+    wt, wb = oracle.lm_head_argmax(x[rows], w)
+    logits = oracle.linear(x[rows], w)                          # what the oracle maximises, to see how close the runner-up is
+    assert np.array_equal(wt, np.argmax(logits, axis=1)) and np.allclose(wb, logits.max(axis=1), rtol=0, atol=1e-12)
     tol = 1e-5 * np.sqrt(d)
     assert np.all(got >= 0) and np.all(got < V)
-    chosen = logits[np.arange(R), got]
+    chosen = logits[np.arange(len(rows)), got[rows]]
     assert np.all(wb - chosen <= tol), "a token whose logit is not the maximum"
     srt = np.sort(logits, axis=1)
     clear = (srt[:, -1] - srt[:, -2]) > tol
-    assert np.array_equal(got[clear], wt[clear])
+    assert np.array_equal(got[rows][clear], wt[clear])
     if V > 100:
         assert got[0] == 11
-    assert np.max(np.abs(best.cpu().numpy() - chosen)) <= 2e-4 * np.sqrt(d)
+    assert np.max(np.abs(best.cpu().numpy()[rows] - chosen)) <= 2e-4 * np.sqrt(d)

@@ -24,16 +24,6 @@ def moa(G):
     return m
 
 
-def sample_sequences(plen, n):
-    order = np.argsort(plen)
-    pick = {int(order[0]), int(order[-1])}
-    for b in order[len(order) // 2:]:
-        if len(pick) >= n:
-            break
-        pick.add(int(b))
-    return sorted(pick)
-
-
 @pytest.mark.parametrize("name,nseq", [("C2", 3), ("C3", 2), ("C4", 2)])
 def test_tree_verify_full_size(G, moa, oracle, name, nseq):
     cfg = mi.CONFIGS[name]
@@ -63,7 +53,7 @@ def test_tree_verify_full_size(G, moa, oracle, name, nseq):
     assert st.item() == 0
     assert np.array_equal(G.mask_u64(mask), mask_np)
     got, gkt = G.host(out), G.host(kt)
-    for b in sample_sequences(plen, nseq):
+    for b in G.sample_sequences(plen, nseq):
         want, wkt, _ = oracle.tree_verify_attn(x[b:b + 1], w["wq"], w["wk"], w["wv"], w["wo"], kc[b:b + 1], vc[b:b + 1],
                                                plen[b:b + 1], mask_np[b:b + 1], cfg.H, cfg.Hkv, cfg.dh)
         G.check_close(gkt[b:b + 1], wkt, cfg.dtype, f"tree_verify.k_tree[{name},b={b},P={plen[b]}]")
@@ -90,7 +80,7 @@ def test_cross_attn_full_size(G, moa, oracle, name, nseq):
     print("[step] cross_attn_draft done", flush=True)
     assert st.item() == 0
     got = G.host(out)
-    for b in sample_sequences(ca_len, nseq):
+    for b in G.sample_sequences(ca_len, nseq):
         want = oracle.cross_attn(xq[b:b + 1], w["wq"], w["wo"], kc[b:b + 1], vc[b:b + 1], ca_len[b:b + 1],
                                  cfg.H, cfg.Hkv, cfg.dh)
         G.check_close(got[b:b + 1], want, cfg.dtype, f"cross_attn[{name},b={b},P={ca_len[b]}]")

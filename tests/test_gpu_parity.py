@@ -170,12 +170,13 @@ def ca_setup(cfg, Mq):
     return w, xq, kc, vc, ca_len, P_cap
 
 
-@pytest.fixture(params=["split", "fused"])
-def attn_kernel(request, monkeypatch):
+@pytest.fixture(params=["split", "whole"])
+def attn_kernel(request, moa):
     """Both MFMA forms of the attention core (split-KV + merge, whole key range per workgroup) on every case;
     without the override the library picks by key-range length.  No effect on the generic (fp32, odd head_dim) path."""
-    monkeypatch.setenv("MOA_ATTN", request.param)
-    return request.param
+    moa.debug_force_attn_kernel(request.param)
+    yield request.param
+    moa.debug_force_attn_kernel("auto")
 
 
 @pytest.mark.parametrize("case", list(CASES))

@@ -24,10 +24,11 @@ def moa(G):
     return m
 
 
-@pytest.fixture(params=["split", "fused"])
-def attn_kernel(request, monkeypatch):
-    monkeypatch.setenv("MOA_ATTN", request.param)
-    return request.param
+@pytest.fixture(params=["split", "whole"])
+def attn_kernel(request, moa):
+    moa.debug_force_attn_kernel(request.param)
+    yield request.param
+    moa.debug_force_attn_kernel("auto")
 
 
 def small_cfg(dtype, **kw):

@@ -77,6 +77,7 @@ def test_draft_step_parity(G, oracle, case, schedule):
     for l in range(nlayers):
         G.check_close(G.host(step.v_out[l]), want["v_out"][l], dt, f"step.verify{l}[{case}]")
         G.check_close(G.host(step.v_ktree[l]), want["v_ktree"][l], dt, f"step.k_tree{l}[{case}]")
+        G.check_close(G.host(step.v_vtree[l]), want["v_vtree"][l], dt, f"step.v_tree{l}[{case}]")
     assert np.array_equal(step.path.cpu().numpy(), want["path"])
     assert np.array_equal(step.n_path.cpu().numpy(), want["n_path"])
     assert np.array_equal(step.bonus.cpu().numpy(), want["bonus"])
