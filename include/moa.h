@@ -278,7 +278,7 @@ int32_t moa_lm_head_argmax(int32_t dtype, const void *x, int32_t R, int32_t d, c
  * bytes in front of the vector's codes.  Layout of a token: [3 B id][n_vec x ([4 B scale][n codes])];
  * msg holds moa_msg_accept_bytes(A, n_vec, n) bytes.  x [A, n_vec, n] in `dtype`;
  * moa_msg_unpack_accept returns fp32 values code * scale.  The gzip pass over the first message of a
- * conversation is host work and not part of this library. */
+ * conversation is moa_msg_gzip below. */
 int32_t moa_msg_pack_tree(const int32_t *tok, const int32_t *parent, int32_t B, int32_t M, void *msg,
                           int32_t *dev_status, void *stream);
 int32_t moa_msg_unpack_tree(const void *msg, int32_t B, int32_t M, int32_t *tok, int32_t *parent,
@@ -288,6 +288,19 @@ int32_t moa_msg_pack_accept(int32_t dtype, const int32_t *tok, const void *x, in
                             int32_t n, void *msg, int32_t *dev_status, void *stream);
 int32_t moa_msg_unpack_accept(const void *msg, int32_t A, int32_t n_vec, int32_t n, int32_t *tok,
                               float *x, void *stream);
+
+/* The server's first message of a conversation carries the activations of the whole prompt and is gzip-compressed
+ * after quantisation (Sec. 4.2).  Host-side byte work: msg_host is the message moa_msg_pack_accept wrote, copied to
+ * the host on its way to the network.  The gzip container (RFC 1952) around a DEFLATE stream (RFC 1951), header
+ * fields empty, so the output depends on the message bytes alone.  All pointers are HOST pointers.
+ *   moa_msg_gzip_bound : an output size that always suffices for an n-byte message.
+ *   moa_msg_gzip       : out_host[0 .. *out_bytes_host) = the compressed message.  MOA_ERR_RANGE if cap is too small.
+ *   moa_msg_gunzip     : the inverse; checks the stream's CRC-32 and length.  MOA_ERR_SHAPE for a truncated or
+ *                        corrupt stream, MOA_ERR_RANGE if the message does not fit cap.
+ * Messages are limited to 2 GiB. */
+int32_t moa_msg_gzip_bound(size_t n, size_t *bytes_host);
+int32_t moa_msg_gzip(const void *msg_host, size_t n, void *out_host, size_t cap, size_t *out_bytes_host);
+int32_t moa_msg_gunzip(const void *gz_host, size_t n, void *out_host, size_t cap, size_t *out_bytes_host);
 
 /* y = x w^T, the projection every layer of the path is made of, for the ones the path leaves to the
  * caller (the drafter's LM head when the logits themselves are wanted, Sec. 2.1 LM_head(o); an MLP).

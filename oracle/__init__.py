@@ -337,6 +337,18 @@ def msg_unpack_accept(msg, n_vec, n):
     return tok, x
 
 
+def msg_gzip(msg: bytes) -> bytes:
+    """The gzip pass over the server's first message (Sec. 4.2): the standard library's gzip, no file name, no time
+    stamp.  Any valid gzip stream of the message is a correct result; what is unique is what it decompresses to."""
+    import gzip
+    return gzip.compress(bytes(msg), mtime=0)
+
+
+def msg_gunzip(gz: bytes) -> bytes:
+    import gzip
+    return gzip.decompress(bytes(gz))
+
+
 def tree_accept(parent, tok, tgt):
     parent, tok, tgt = _i32(parent), _i32(tok), _i32(tgt)
     B, M = parent.shape

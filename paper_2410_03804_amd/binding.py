@@ -70,7 +70,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
             "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
-            "moa_msg_unpack_accept", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma",
+            "moa_msg_unpack_accept", "moa_msg_gzip_bound", "moa_msg_gzip", "moa_msg_gunzip", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma",
             "moa_debug_force_attn_kernel"]
 
 _lib.moa_status_str.restype = C.c_char_p
@@ -110,6 +110,9 @@ _lib.moa_msg_unpack_tree.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
 _lib.moa_msg_accept_bytes.argtypes = [_i32, _i32, _i32, C.POINTER(_sz)]
 _lib.moa_msg_pack_accept.argtypes = [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.moa_msg_unpack_accept.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
+_lib.moa_msg_gzip_bound.argtypes = [_sz, C.POINTER(_sz)]
+_lib.moa_msg_gzip.argtypes = [C.c_char_p, _sz, _vp, _sz, C.POINTER(_sz)]
+_lib.moa_msg_gunzip.argtypes = [C.c_char_p, _sz, _vp, _sz, C.POINTER(_sz)]
 _lib.moa_linear_workspace_bytes.argtypes = [_i32, _i64, _i32, _i32, C.POINTER(_sz)]
 _lib.moa_linear.argtypes = [_i32, _vp, _i64, _i32, _vp, _i32, _vp, _vp, _sz, _vp]
 _lib.moa_fold_projection.argtypes = [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp]
@@ -435,6 +438,24 @@ def msg_unpack_accept(msg, tok, x, stream=None):
     A, n_vec, n = x.shape
     _check(_lib.moa_msg_unpack_accept(_dev(msg, torch.uint8, msg_accept_bytes(A, n_vec, n), "msg"), A, n_vec, n,
                                       _dev(tok, torch.int32, A, "tok"), _dev(x, torch.float32, A * n_vec * n, "x"), _stream(stream)))
+
+
+def msg_gzip(msg: bytes) -> bytes:
+    """gzip-compress a (host) message, as the server does with the first message of a conversation."""
+    bound = _sz(0)
+    _check(_lib.moa_msg_gzip_bound(len(msg), C.byref(bound)))
+    out = C.create_string_buffer(max(bound.value, 1))
+    n = _sz(0)
+    _check(_lib.moa_msg_gzip(msg, len(msg), out, bound.value, C.byref(n)))
+    return out.raw[: n.value]
+
+
+def msg_gunzip(gz: bytes, max_bytes: int) -> bytes:
+    """The inverse of msg_gzip; max_bytes bounds the size of the message."""
+    out = C.create_string_buffer(max(int(max_bytes), 1))
+    n = _sz(0)
+    _check(_lib.moa_msg_gunzip(gz, len(gz), out, int(max_bytes), C.byref(n)))
+    return out.raw[: n.value]
 
 
 def linear_workspace_bytes(dtype: int, R: int, K: int, N: int) -> int:

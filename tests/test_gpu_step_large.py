@@ -37,8 +37,8 @@ LARGE_CASES = {
     # both cores of the step in one split-KV launch + one merge, at a size that would otherwise take the other form
     "split_pair_forced": (_cfg("SP", 23, B=3, M=37, P_min=80, P_max=300), 2, 3, "split"),
     # two-word masks (M = 128) through the whole-key-range form and through the split form
-    "two_word_masks_whole": (_cfg("M128w", 24, B=2, M=128, D=10, P_min=60, P_max=400), 1, 2, "whole"),
-    "two_word_masks_split": (_cfg("M128s", 25, B=2, M=128, D=10, P_min=60, P_max=400), 1, 2, "split"),
+    "two_word_masks_whole": (_cfg("M128w", 24, B=2, M=128, D=10, P_min=140, P_max=400), 1, 2, "whole"),
+    "two_word_masks_split": (_cfg("M128s", 25, B=2, M=128, D=10, P_min=140, P_max=400), 1, 2, "split"),
     # the batched and long-context workloads themselves
     "C2": (mi.CONFIGS["C2"], 1, 3, "auto"),
     "C3": (mi.CONFIGS["C3"], 1, 2, "auto"),
