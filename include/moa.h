@@ -146,6 +146,22 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
                              const uint64_t *mask, void *out, void *k_tree, void *v_tree,
                              int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
 
+/* moa_tree_verify_attn for callers that cannot allocate device memory and so cannot bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without ws / ws_bytes, same
+ * kernels, same results bit for bit.  The scratch (projected queries, heads, partial sums, partial attention results)
+ * is a fixed 32 MiB array in the library's own device memory, one copy per GPU, held until the process ends; the call
+ * itself allocates and frees nothing.  MOA_ERR_WORKSPACE when the call would need more than that (what
+ * moa_workspace_bytes(shape, B, P_cap, M, 0) reports; the Llama-3-8B shape with one sequence, a tree of 64 and 4096
+ * cached tokens needs about 12 MiB) -- use moa_tree_verify_attn then.  Every call on a GPU shares that GPU's array:
+ * calls that overlap in time on one GPU (different streams, different host threads) race; calls on one stream do not.
+ * The array keeps the previous call's contents and nothing in it has to start at zero. */
+int32_t moa_tree_verify_attn_noalloc(const moa_shape_t *shape, const void *x, int32_t B, int32_t M,
+                                     const void *wq, const void *wk, const void *wv, const void *wo,
+                                     const void *kcache, const void *vcache,
+                                     const int32_t *prefix_len /*[B]*/, int32_t P_cap,
+                                     const uint64_t *mask, void *out, void *k_tree, void *v_tree,
+                                     int32_t *dev_status, void *stream);
+
 /* Self-Attention layer of the draft model on draft-token embeddings, tree form (Sec. 3.1,
  * "Self-Attention": a causal self-attention on the queries of the Cross-Attention, so that a
  * drafted token is aware of the tokens drafted before it; Alg. 1, q <- SA_layer(token_embed(y));

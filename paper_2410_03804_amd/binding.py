@@ -71,7 +71,7 @@ _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
             "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
             "moa_msg_unpack_accept", "moa_msg_gzip_bound", "moa_msg_gzip", "moa_msg_gunzip", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma",
-            "moa_debug_force_attn_kernel"]
+            "moa_debug_force_attn_kernel", "moa_tree_verify_attn_noalloc"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -86,6 +86,8 @@ _lib.moa_ca_kv_append.argtypes = [C.POINTER(Shape), _vp, _i64, _i32, _vp, _i32, 
 _lib.moa_cross_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
 _lib.moa_tree_verify_attn.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
                                       _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moa_tree_verify_attn_noalloc.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
+                                              _vp, _vp, _vp, _vp, _vp]
 _lib.moa_draft_step.argtypes = [C.POINTER(_StepArgs)]
 _lib.moa_self_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
                                      _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -269,6 +271,26 @@ def tree_verify_attn(shape: Shape, x, wq, wk, wv, wo, kcache, vcache, prefix_len
                                      _dev(mask, torch.int64, B * M * W, "mask"), _dev(out, dt, B * M * d, "out"),
                                      _dev(k_tree, dt, B * ekv * M, "k_tree"), _dev(v_tree, dt, B * ekv * M, "v_tree"),
                                      _dev(dev_status, torch.int32, 1, "dev_status"), wsp, wsb, _stream(stream)))
+
+
+def tree_verify_attn_noalloc(shape: Shape, x, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask, out, k_tree, v_tree,
+                             dev_status=None, stream=None):
+    """moa_tree_verify_attn without a workspace: the scratch is the library's own fixed device array."""
+    dt = _TORCH_DTYPE[shape.dtype]
+    B, M, d = x.shape
+    if d != shape.d_model:
+        raise ValueError("x: last dimension must be d_model")
+    e, ekv = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    cache = B * ekv * P_cap
+    W = (M + 63) // 64
+    _check(_lib.moa_tree_verify_attn_noalloc(
+        C.byref(shape), _dev(x, dt, B * M * d, "x"), B, M,
+        _dev(wq, dt, e * d, "wq"), _dev(wk, dt, ekv * d, "wk"), _dev(wv, dt, ekv * d, "wv"), _dev(wo, dt, d * e, "wo"),
+        _dev(kcache, dt, cache, "kcache"), _dev(vcache, dt, cache, "vcache"),
+        _dev(prefix_len, torch.int32, B, "prefix_len"), P_cap,
+        _dev(mask, torch.int64, B * M * W, "mask"), _dev(out, dt, B * M * d, "out"),
+        _dev(k_tree, dt, B * ekv * M, "k_tree"), _dev(v_tree, dt, B * ekv * M, "v_tree"),
+        _dev(dev_status, torch.int32, 1, "dev_status"), _stream(stream)))
 
 
 def self_attn_draft(shape: Shape, emb, node_begin, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap, mask, out, k_draft, v_draft,

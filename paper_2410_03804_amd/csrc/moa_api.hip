@@ -637,6 +637,59 @@ int32_t moa_tree_verify_attn(const moa_shape_t *shape, const void *x, int32_t B,
                            out, k_tree, v_tree, dev_status, ws, ws_bytes, (hipStream_t)stream);
 }
 
+// ---- the same layer for callers that cannot bring a workspace: its scratch is a fixed array in device memory that
+// belongs to the library's code object (every GPU that loads the library holds its own copy until the process ends).
+// In host code the array's name is only a handle for hipGetSymbolAddress; the address a kernel can use is looked up
+// once per device, with that device current, and kept.
+#define MOA_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+static __device__ __align__(256) unsigned char scratch[MOA_NOALLOC_SCRATCH_BYTES];
+
+static int32_t noalloc_scratch_for_current_device(void **out)
+{
+    static std::mutex mu;
+    static void *addr[16] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "tree_verify_attn_noalloc: hipGetDevice");
+    if (dev < 0 || dev >= 16) return fail(MOA_ERR_HIP, "tree_verify_attn_noalloc: device %d outside the 16 supported", dev);
+    std::lock_guard<std::mutex> lk(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "tree_verify_attn_noalloc: hipGetSymbolAddress(scratch)");
+        addr[dev] = p;
+    }
+    *out = addr[dev];
+    return MOA_OK;
+}
+
+int32_t moa_tree_verify_attn_noalloc(const moa_shape_t *shape, const void *x, int32_t B, int32_t M, const void *wq,
+                                     const void *wk, const void *wv, const void *wo, const void *kcache,
+                                     const void *vcache, const int32_t *prefix_len, int32_t P_cap,
+                                     const uint64_t *mask, void *out, void *k_tree, void *v_tree,
+                                     int32_t *dev_status, void *stream)
+{
+    int32_t rc = check_shape(shape, false);
+    if (rc) return rc;
+    if (!x || !prefix_len || !mask || !out || !k_tree || !v_tree) return fail(MOA_ERR_NULL, "tree_verify_attn_noalloc: NULL pointer");
+    if (P_cap > 0 && (!kcache || !vcache)) return fail(MOA_ERR_NULL, "tree_verify_attn_noalloc: cache is NULL with P_cap > 0");
+    if (B < 1 || M < 1 || M > MOA_MAX_TREE || P_cap < 0)
+        return fail(MOA_ERR_SHAPE, "tree_verify_attn_noalloc: B=%d M=%d P_cap=%d (M <= %d)", B, M, P_cap, MOA_MAX_TREE);
+    if (!wo && shape->n_q_heads * shape->head_dim != shape->d_model)
+        return fail(MOA_ERR_SHAPE, "tree_verify_attn_noalloc: NULL wo needs d == H*dh");
+    const size_t need = attn_ws_bytes(shape, B, M, P_cap);
+    if (need > MOA_NOALLOC_SCRATCH_BYTES)
+        return fail(MOA_ERR_WORKSPACE, "tree_verify_attn_noalloc: this call needs %zu bytes of scratch, the built-in array holds %zu; "
+                                       "use moa_tree_verify_attn with a workspace", need, MOA_NOALLOC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    rc = noalloc_scratch_for_current_device(&ws);
+    if (rc) return rc;
+    // Nothing in the scratch has to start at zero: the projected queries, the heads and every partial sum or partial
+    // attention result a later kernel reads are written by an earlier kernel of this same call.
+    return attention_layer("tree_verify_attn_noalloc", shape, x, B, M, wq, wk, wv, wo, kcache, vcache, prefix_len, P_cap,
+                           mask, out, k_tree, v_tree, dev_status, ws, MOA_NOALLOC_SCRATCH_BYTES, (hipStream_t)stream);
+}
+
 int32_t moa_self_attn_draft(const moa_shape_t *shape, const void *emb, int32_t B, int32_t M, int32_t node_begin,
                             int32_t Mn, const void *wq, const void *wk, const void *wv, const void *wo,
                             const void *kcache, const void *vcache, const int32_t *prefix_len, int32_t P_cap,
