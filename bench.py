@@ -26,15 +26,28 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 VEC_F32_PEAK_TFLOPS = 157.3
 
-# HBM bytes per launch (MiB) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the counters read for a
-# plain 512 MiB device copy (fetch x2.000, write x1.000): profiles/c1_draft_step_hbm_traffic_pmc.md.  They hold for
-# the default workload only (C1, 2*E_kv-wide LSA input, one verify layer).
-PMC_TRAFFIC_MIB_C1 = {
-    "k_linear_splitk_chunked_bf16<4>": 82.54,     # mean of the two grouped launches of the default schedule
-    "k_linear_splitk_chunked_bf16<2>": 20.32,
-    "k_linear_tiled_bf16<2, 2>": 101.94,          # with the summing pass that rides in its launch
-    "k_attn_fused<128, 8>": 10.28,
-}
+# HBM bytes per launch as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the counters read for a
+# plain device copy of known size) are kept in a tracked summary that names the commit it was measured at and the
+# kernels the step launched then; the figure is reported only while the step still launches exactly those kernels.
+PMC_TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "c1_draft_step_hbm_traffic.json")
+
+
+def recorded_traffic(kernel, kernels_seen, default_workload):
+    """HBM bytes per launch of `kernel` from the tracked counter summary, or None when the summary does not describe
+    this run (another workload, a kernel set that has changed since, no summary)."""
+    if not default_workload:
+        return None, "not the workload the counters were collected on"
+    try:
+        with open(PMC_TRAFFIC_FILE) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None, "no tracked counter summary"
+    if sorted(rec.get("kernel_set", [])) != sorted(kernels_seen):
+        return None, f"kernel set changed since the counters were collected at {rec.get('commit')}"
+    mib = rec.get("traffic_MiB_per_launch", {}).get(kernel)
+    if mib is None:
+        return None, "kernel not in the tracked counter summary"
+    return int(mib * 2 ** 20), f"rocprofv3 FETCH_SIZE/WRITE_SIZE at {rec.get('commit')}"
 
 
 def parse():
@@ -105,9 +118,14 @@ def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree", with_sa=Fal
 
     c = {}
     c["tree_build"] = dict(bytes=B * M * 4 + B * M * ((M + 63) // 64) * 8 + B * M * 4, flops=0.0)
-    c["lsa.qkv_proj"] = lin(Tl * L, d_in, eq + 2 * ekv)
-    c["lsa.layer_attn"] = dict(bytes=(Tl * L * (eq + 2 * ekv) + Tl * eq) * es,
-                               flops=2.0 * Tl * cfg.lsa_heads * L * L * dh + 2.0 * Tl * cfg.lsa_heads * L * dh)
+    attn_flops = 2.0 * Tl * cfg.lsa_heads * L * L * dh + 2.0 * Tl * cfg.lsa_heads * L * dh
+    # three-kernel form: the projected rows the first kernel writes and the second reads back are traffic the method
+    # does not need (Sec. 3.1.1: a token's layer rows are self-contained), so they are not algorithmic bytes of either
+    c["lsa.qkv_proj"] = dict(bytes=(Tl * L * d_in + (eq + 2 * ekv) * d_in) * es, flops=2.0 * Tl * L * d_in * (eq + 2 * ekv))
+    c["lsa.layer_attn"] = dict(bytes=Tl * eq * es, flops=attn_flops)
+    # one-kernel form: layer rows and weights in, mean-folded heads out
+    c["lsa.fused"] = dict(bytes=(Tl * L * d_in + (eq + 2 * ekv) * d_in + Tl * eq) * es,
+                          flops=2.0 * Tl * L * d_in * (eq + 2 * ekv) + attn_flops)
     folded = fold and schedule != "sequential" and Tl <= 4096       # one launch: LSA output + the memory's new K/V rows
     c["lsa.o_proj"] = lin(Tl, eq, eq + 2 * ekv) if folded else lin(Tl, eq, eq)
     c["ca_append.kv_proj"] = lin(Tl, eq, 2 * ekv)
@@ -139,6 +157,19 @@ def site_costs(cfg, n_layers, schedule="grouped", lsa_tokens="tree", with_sa=Fal
     for k, v in one.items():
         alone = n_layers - 1 if k in paired else n_layers
         c[k] = {kk: vv * alone for kk, vv in v.items()}
+    # what one whole step must move once: LSA rows, every weight matrix, the two caches, inputs and outputs -- no
+    # intermediate (projected queries, heads, partial sums) counts
+    w_lsa = ((eq + 2 * ekv) * d_in + eq * eq + 2 * ekv * eq) * es
+    lsa_io = (Tl * L * d_in + Tl * eq + 2 * Tl * ekv) * es
+    ca_b = (2 * E * d) * es + cache_ca + 2 * T * d * es
+    ver_b = ((2 * E + 2 * ekv) * d) * es + cache_v + 2 * T * d * es + 2 * T * ekv * es
+    sa_b = 0.0
+    if with_sa:
+        ekv_s2 = mi.sa_kv_heads(cfg) * dh
+        sa_b = ((2 * E + 2 * ekv_s2) * d) * es + c["sa.core"]["bytes"] - 2 * T * E * es + 2 * T * d * es
+    c["__step__"] = dict(bytes=w_lsa + lsa_io + ca_b + n_layers * ver_b + sa_b + c["tree_build"]["bytes"] + c["tree_accept"]["bytes"],
+                         flops=c["lsa.fused"]["flops"] + c["lsa.o_proj"]["flops"] + c["ca.q_proj"]["flops"] + core_flops_ca +
+                         c["ca.o_proj"]["flops"] + n_layers * sum(v["flops"] for v in one.values()))
     if paired:
         c["tree_build+accept+lengths"] = add(c["tree_build"], c["tree_accept"], c["ca_append.lengths"])
         c["ca.q_proj+verify.qkv_proj"] = add(c["ca.q_proj"], one["verify.qkv_proj"])
@@ -428,15 +459,23 @@ def main():
             ach = flo / (avg_us * 1e-6) / 1e12
             roofline = dict(bound="mfma", achieved=round(ach, 2), peak=peak_mm, unit="TFLOP/s",
                             frac=round(ach / peak_mm, 4), traffic=None)
-        if (cfg.name == "C1" and not args.d_lsa_in and NL == 1 and args.schedule == "grouped"
-                and dominant in PMC_TRAFFIC_MIB_C1):
-            roofline["traffic"] = int(PMC_TRAFFIC_MIB_C1[dominant] * 2 ** 20)
+        default_workload = (cfg.name == "C1" and not args.d_lsa_in and NL == 1 and args.schedule == "grouped"
+                            and lsa_tokens == "tree" and not args.with_sa and not args.no_fold)
+        roofline["traffic"], roofline["traffic_source"] = recorded_traffic(dominant, list(per_kernel), default_workload)
         if ceilings:
             ceil = ceilings["hbm_read_gbs"] if roofline["bound"] == "hbm" else ceilings["mfma_bf16_tflops"]
             roofline["frac_of_measured_ceiling"] = round(roofline["achieved"] / ceil, 4)
         roofline.update(kernel=dominant, sites=sites, avg_launch_us=round(avg_us, 3),
                         launches_per_step=per_step_launches, alg_bytes_per_launch=int(byt),
                         flops_per_launch=int(flo), sampled_launches=launches, share_of_kernel_time=round(per_kernel[dominant] / sum(per_kernel.values()), 4))
+
+    # the whole step against the HBM roofline: the bytes the method must move once per step over the step time
+    sb, sf = costs["__step__"]["bytes"], costs["__step__"]["flops"]
+    step_gbs = sb / (ms_per_step * 1e-3) / 1e9
+    step_roofline = dict(bound="hbm", alg_bytes_per_step=int(sb), achieved=round(step_gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                         frac=round(step_gbs / HBM_PEAK_GBS, 4), gflop_per_step=round(sf / 1e9, 2),
+                         mfma_frac=round(sf / (ms_per_step * 1e-3) / 1e12 / peak_mm, 4),
+                         note="algorithmic bytes of one whole step / step time / 8 TB/s: the '% HBM peak' of the metric")
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -478,7 +517,7 @@ def main():
                                f"LSA on T={lsa_token_count(cfg, lsa_tokens)} tokens ({lsa_tokens}), {NL} tree-verify layer(s)"
                                + ("; Self-Attention layer in front of the CA" if args.with_sa else ""),
                    "verify_layers": NL, "buffer_sets": nsets, "profile_steps": P},
-        "roofline": roofline, "cpu_baseline": cpu, "ceilings": ceilings,
+        "roofline": roofline, "step_roofline": step_roofline, "cpu_baseline": cpu, "ceilings": ceilings,
         "tli": tli, "drafter_blocks": drafter_blocks,
         "hot_cache": {"ms_per_step": round(hot_ms, 5), "steps": hot_steps,
                       "note": "one buffer set reused: operands stay in the Infinity Cache; not the headline"},

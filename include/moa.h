@@ -427,6 +427,14 @@ const char *moa_profile_site_name(int32_t site);
 enum { MOA_ATTN_KERNEL_AUTO = 0, MOA_ATTN_KERNEL_WHOLE = 1, MOA_ATTN_KERNEL_SPLIT = 2 };
 int32_t moa_debug_force_attn_kernel(int32_t form);
 
+/* The same for the Layer Self-Attention (moa_lsa, moa_draft_step): for bf16 with head_dim 128, at most 96 layers, an
+ * input width in 64s and an even number of query heads per KV head, projection, attention over the layers and mean
+ * run as ONE kernel that keeps the projected rows on the compute unit; other shapes take three kernels with the
+ * projected rows in the workspace.  Both give the same bits.  MOA_LSA_KERNEL_SEPARATE forces the three-kernel form;
+ * MOA_LSA_KERNEL_FUSED and _AUTO pick the one-kernel form wherever it applies. */
+enum { MOA_LSA_KERNEL_AUTO = 0, MOA_LSA_KERNEL_FUSED = 1, MOA_LSA_KERNEL_SEPARATE = 2 };
+int32_t moa_debug_force_lsa_kernel(int32_t form);
+
 /* Two probes of what the device delivers in practice, timed like any other kernel through the aid
  * above (kernels "k_probe_read", "k_probe_mfma"); a benchmark prints them beside the published
  * peaks.  moa_probe_read streams `bytes` (multiple of 16, 16-byte aligned device buffer) once with

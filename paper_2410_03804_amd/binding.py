@@ -71,7 +71,7 @@ _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
             "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
             "moa_msg_unpack_accept", "moa_msg_gzip_bound", "moa_msg_gzip", "moa_msg_gunzip", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma",
-            "moa_debug_force_attn_kernel", "moa_tree_verify_attn_noalloc"]
+            "moa_debug_force_attn_kernel", "moa_debug_force_lsa_kernel", "moa_tree_verify_attn_noalloc"]
 
 _lib.moa_status_str.restype = C.c_char_p
 _lib.moa_status_str.argtypes = [C.c_int32]
@@ -137,6 +137,7 @@ _lib.moa_profile_kernel_name.argtypes = [_i32]
 _lib.moa_profile_site_name.restype = C.c_char_p
 _lib.moa_profile_site_name.argtypes = [_i32]
 _lib.moa_debug_force_attn_kernel.argtypes = [_i32]
+_lib.moa_debug_force_lsa_kernel.argtypes = [_i32]
 _lib.moa_probe_read.argtypes = [_vp, _sz, _vp, _vp]
 _lib.moa_probe_mfma.argtypes = [_i32, _vp, C.POINTER(_i64), _vp]
 
@@ -650,6 +651,14 @@ def debug_force_attn_kernel(form: str = "auto"):
     """Force one of the two matrix-core forms of the attention core for every later call ("auto" restores the
     choice by shape); a testing aid."""
     _check(_lib.moa_debug_force_attn_kernel(ATTN_KERNEL[form]))
+
+
+LSA_KERNEL = {"auto": 0, "fused": 1, "separate": 2}
+
+
+def debug_force_lsa_kernel(form: str = "auto"):
+    """Force the three-kernel form of the Layer Self-Attention ("separate") or restore the choice by shape; a testing aid."""
+    _check(_lib.moa_debug_force_lsa_kernel(LSA_KERNEL[form]))
 
 
 def probe_read(buf, scratch4, stream=None):

@@ -10,7 +10,7 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libmoa.so"
-SOURCES = ["moa_api.hip", "moa_tree.hip", "moa_gemm.hip", "moa_attn.hip", "moa_lsa.hip", "moa_block.hip", "moa_draft_tree.hip", "moa_lm_head.hip", "moa_msg.hip", "moa_gzip.hip", "moa_prof.hip"]
+SOURCES = ["moa_api.hip", "moa_tree.hip", "moa_gemm.hip", "moa_attn.hip", "moa_lsa.hip", "moa_lsa_fused.hip", "moa_block.hip", "moa_draft_tree.hip", "moa_lm_head.hip", "moa_msg.hip", "moa_gzip.hip", "moa_prof.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -7,6 +7,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <atomic>
 #include <mutex>
 
 using namespace moa;
@@ -247,6 +248,38 @@ static thread_local const LinSeg *t_lsa_extra = nullptr;
 static thread_local int t_lsa_nextra = 0;
 static thread_local bool t_lsa_extra_taken = false;
 
+// which form the Layer Self-Attention takes: 0 = the one-kernel form wherever its shapes allow, 1 = the same (a call
+// it cannot take still falls back), 2 = always projection, attention and mean as separate kernels
+static std::atomic<int> g_lsa_form{0};
+
+static bool lsa_takes_fused(const moa_shape_t *shape, const void *hs, const void *wq, const void *wk, const void *wv,
+                            const void *abar)
+{
+    if (g_lsa_form.load(std::memory_order_relaxed) == MOA_LSA_KERNEL_SEPARATE) return false;
+    return wq && wk && wv &&
+           lsa_fused_ok(shape->dtype, shape->n_layers, shape->d_lsa_in, shape->lsa_q_heads, shape->lsa_kv_heads,
+                        shape->head_dim, hs, wq, wk, wv, abar);
+}
+
+static LsaFusedCall lsa_fused_call(const moa_shape_t *shape, const void *hs, int64_t t0, int64_t tc, const void *wq,
+                                   const void *wk, const void *wv, void *abar)
+{
+    LsaFusedCall c = {};
+    c.dtype = shape->dtype;
+    c.hs = (const char *)hs + (size_t)t0 * shape->n_layers * shape->d_lsa_in * esize(shape->dtype);
+    c.wq = wq;
+    c.wk = wk;
+    c.wv = wv;
+    c.abar = abar;
+    c.T = tc;
+    c.L = shape->n_layers;
+    c.d_in = shape->d_lsa_in;
+    c.Hq = shape->lsa_q_heads;
+    c.Hkv = shape->lsa_kv_heads;
+    c.dh = shape->head_dim;
+    return c;
+}
+
 // ---- the LSA stage in pieces: moa_lsa runs them in order; the grouped draft step puts other launches between them
 static int32_t lsa_check(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk,
                          const void *wv, const void *out, const void *ws, size_t ws_bytes)
@@ -359,17 +392,27 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
     const size_t es = esize(dt);
     const LsaBufs b = lsa_carve(shape, T, ws, ws_bytes);
 
-    for (int64_t t0 = 0; t0 < T; t0 += LSA_CHUNK) {
-        const int64_t tc = (T - t0) < LSA_CHUNK ? (T - t0) : LSA_CHUNK;
+    // One kernel for projection, attention over the layers and mean where the shapes allow: no projected row ever
+    // reaches memory, so a pass covers a whole output-projection block of tokens; else chunks of LSA_CHUNK tokens
+    // whose Q/K/V rows go through the workspace.
+    const bool fused = lsa_takes_fused(shape, hs, wq, wk, wv, wo ? (const void *)b.abar0 : out);
+    const int64_t step = fused ? LSA_OBLOCK : LSA_CHUNK;
+    for (int64_t t0 = 0; t0 < T; t0 += step) {
+        const int64_t tc = (T - t0) < step ? (T - t0) : step;
         const int64_t b0 = (t0 / LSA_OBLOCK) * LSA_OBLOCK;            // first token of this output-projection block
         char *abar = wo ? b.abar0 + (size_t)(t0 - b0) * eq * es : (char *)out + (size_t)t0 * eq * es;
-        LinArgs la;
-        LsaAttnArgs aa;
-        lsa_chunk_args(shape, hs, t0, tc, wq, wk, wv, abar, b, &la, &aa);
-        prof_set_site(S_LSA_QKV);
-        if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "lsa: projection");
-        prof_set_site(S_LSA_ATTN);
-        MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
+        if (fused) {
+            prof_set_site(S_LSA_FUSED);
+            MOA_TRY_HIP(launch_lsa_fused(lsa_fused_call(shape, hs, t0, tc, wq, wk, wv, abar), st), "lsa: fused kernel");
+        } else {
+            LinArgs la;
+            LsaAttnArgs aa;
+            lsa_chunk_args(shape, hs, t0, tc, wq, wk, wv, abar, b, &la, &aa);
+            prof_set_site(S_LSA_QKV);
+            if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), "lsa: projection");
+            prof_set_site(S_LSA_ATTN);
+            MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
+        }
         const bool block_done = t0 + tc >= T || (t0 + tc) % LSA_OBLOCK == 0;
         if (wo && block_done) {                                      // W_o once per block, on one row per token
             const bool extras = t_lsa_nextra > 0 && T <= LSA_OBLOCK;
@@ -379,6 +422,14 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
             MOA_TRY_HIP(launch_linear(dt, lo, st), "lsa: output projection");
         }
     }
+    return MOA_OK;
+}
+
+int32_t moa_debug_force_lsa_kernel(int32_t form)
+{
+    if (form < MOA_LSA_KERNEL_AUTO || form > MOA_LSA_KERNEL_SEPARATE)
+        return fail(MOA_ERR_SHAPE, "debug_force_lsa_kernel: form must be MOA_LSA_KERNEL_AUTO / _FUSED / _SEPARATE");
+    g_lsa_form.store(form, std::memory_order_relaxed);
     return MOA_OK;
 }
 
@@ -1192,12 +1243,12 @@ static int32_t piece_lsa_append(const moa_step_args_t *a, const StepBufs &bf, vo
     return piece_append(a, bf, scr, scr_bytes, st);
 }
 
-// The step's first projections and the LSA chain of at most LSA_CHUNK tokens, with the small kernels riding in
-// launches that do not depend on them:
+// The step's first projections and an LSA chain that is one pass (at most LSA_CHUNK tokens, or an output-projection
+// block of them in the one-kernel form), with the small kernels riding in launches that do not depend on them:
 //   1. CA query + verification Q/K/V projections  + the step's integer work
-//   2. LSA Q/K/V projection                        + the pass that adds up launch 1's K slices (tiled kernel; else that
-//                                                    pass is a launch of its own)
-//   3. attention over the layers    4. LSA W_o (+ the memory's folded K/V)
+//   2. LSA in one kernel (or its Q/K/V projection) + the pass that adds up launch 1's K slices (the one-kernel form and
+//                                                    the tiled kernel carry it; else that pass is a launch of its own)
+//   3. (attention over the layers, when apart)     4. LSA W_o (+ the memory's folded K/V)
 // scr2 is the second scratch region: launch 1's partial sums live there while the LSA chain uses the first.
 static int32_t piece_lsa_interleaved(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes, char *scr2,
                                      hipStream_t st)
@@ -1211,19 +1262,27 @@ static int32_t piece_lsa_interleaved(const moa_step_args_t *a, const StepBufs &b
     rc = piece_projections(a, bf, scr2, scr_bytes, st, true, &sum_pair);
     if (rc) return rc;
     const LsaBufs b = lsa_carve(sh, T, scr, scr_bytes);
-    LinArgs la;
-    LsaAttnArgs aa;
-    lsa_chunk_args(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo ? (void *)b.abar0 : a->lsa_out, b, &la, &aa);
-    if (la.nseg) {
-        la.carry_sum = &sum_pair;
-        prof_set_site(S_LSA_QKV);
-        MOA_TRY_HIP(launch_linear(dt, la, st), "lsa: projection");
+    void *abar = a->lsa_wo ? (void *)b.abar0 : a->lsa_out;
+    if (lsa_takes_fused(sh, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar)) {
+        LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
+        fc.carry_sum = &sum_pair;
+        prof_set_site(S_LSA_FUSED);
+        MOA_TRY_HIP(launch_lsa_fused(fc, st), "lsa: fused kernel");
     } else {
-        prof_set_site(S_PAIR_QKV);
-        MOA_TRY_HIP(launch_splitk_sum(sum_pair, st), "draft_step: projections");
+        LinArgs la;
+        LsaAttnArgs aa;
+        lsa_chunk_args(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar, b, &la, &aa);
+        if (la.nseg) {
+            la.carry_sum = &sum_pair;
+            prof_set_site(S_LSA_QKV);
+            MOA_TRY_HIP(launch_linear(dt, la, st), "lsa: projection");
+        } else {
+            prof_set_site(S_PAIR_QKV);
+            MOA_TRY_HIP(launch_splitk_sum(sum_pair, st), "draft_step: projections");
+        }
+        prof_set_site(S_LSA_ATTN);
+        MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
     }
-    prof_set_site(S_LSA_ATTN);
-    MOA_TRY_HIP(launch_lsa_attn(aa, st), "lsa: attention over layers");
     LinSeg folded[2];
     const bool fold = a->lsa_wo && folded_segments(a, bf, folded);
     if (a->lsa_wo) {
@@ -1306,7 +1365,9 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
     // With room for a second scratch region (the first projections keep their partial sums there while the LSA chain
     // uses the first) and all LSA tokens in one chunk, the two are interleaved; else one after the other.
     int32_t rc;
-    if (a->T_lsa > 0 && a->T_lsa <= LSA_CHUNK && a->ws_bytes >= L.total() + L.scratch) {
+    const bool one_pass = a->T_lsa <= LSA_CHUNK ||
+                          (a->T_lsa <= LSA_OBLOCK && lsa_takes_fused(a->shape, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->ws));
+    if (a->T_lsa > 0 && one_pass && a->ws_bytes >= L.total() + L.scratch) {
         rc = piece_lsa_interleaved(a, bf, scr, L.scratch, scr + L.scratch, st);
         if (rc) return rc;
     } else {

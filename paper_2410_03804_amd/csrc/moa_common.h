@@ -95,13 +95,13 @@ enum KernelId {
     K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_SPLITK, K_LIN_REDUCE, K_LIN_TILED, K_SCATTER,
     K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_LSA_ATTN_MFMA, K_STEP_SMALL, K_ATTN_FUSED, K_PROBE_READ, K_PROBE_MFMA,
     K_RMSNORM, K_ROPE, K_SWIGLU, K_ADD_OUT, K_TREE_EXPAND, K_TREE_FINALIZE, K_TOPK_LOGPROB,
-    K_LM_HEAD, K_LM_HEAD_REDUCE, K_TOPK_MERGE, K_MSG_TREE, K_MSG_ACCEPT, K_LIN_SPLITK_CHUNKED, K_COUNT
+    K_LM_HEAD, K_LM_HEAD_REDUCE, K_TOPK_MERGE, K_MSG_TREE, K_MSG_ACCEPT, K_LIN_SPLITK_CHUNKED, K_LSA_FUSED, K_COUNT
 };
 enum SiteId {
     S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,
     S_CA_OPROJ, S_VERIFY_QKV, S_VERIFY_CORE, S_VERIFY_OPROJ, S_TREE_ACCEPT, S_STEP_SMALL, S_PAIR_QKV, S_PAIR_CORE,
     S_PAIR_OPROJ, S_PROBE, S_SA_QKV, S_SA_CORE, S_SA_OPROJ, S_TLI_QKV, S_TLI_CORE, S_TLI_OPROJ, S_TLI_NORM, S_TLI_ROPE,
-    S_TLI_GATE_UP, S_TLI_ACT, S_TLI_DOWN, S_TLI_ADD, S_TREE_EXPAND, S_TREE_FINALIZE, S_TOPK_LOGPROB, S_LM_HEAD, S_MSG, S_LINEAR, S_MLP_NORM, S_MLP_GATE_UP, S_MLP_DOWN, S_COUNT
+    S_TLI_GATE_UP, S_TLI_ACT, S_TLI_DOWN, S_TLI_ADD, S_TREE_EXPAND, S_TREE_FINALIZE, S_TOPK_LOGPROB, S_LM_HEAD, S_MSG, S_LINEAR, S_MLP_NORM, S_MLP_GATE_UP, S_MLP_DOWN, S_LSA_FUSED, S_COUNT
 };
 // records the message moa_last_error returns and hands the code back (entry points outside moa_api.hip)
 int32_t api_fail(int32_t code, const char *msg);
@@ -263,6 +263,24 @@ hipError_t launch_rope(int dtype, void *q, void *k_draft, const int32_t *prefix_
 hipError_t launch_fold_weights(int dtype, const void *a, const void *b, int N, int J, int K, void *out, hipStream_t stream);
 hipError_t launch_swiglu(int dtype, const void *gu, int64_t R, int d_ff, void *act, hipStream_t stream);
 hipError_t launch_add_out(int dtype, const float *h, const void *t, int64_t n, void *out, hipStream_t stream);
+
+// ---- LSA in one kernel: projection of a token's layer rows, attention over the layers, mean; writes the mean-folded
+// heads abar [T, Hq*dh] (the output projection is a launch of its own, on one row per token).  rider / carry_sum as in
+// LinArgs: work of other calls carried in spare workgroups at the front of the grid.
+struct LsaFusedCall {
+    int dtype;
+    const void *hs, *wq, *wk, *wv;
+    void *abar;
+    int64_t T;
+    int L, d_in, Hq, Hkv, dh;
+    StepSmallArgs rider;
+    int rider_units;
+    const SumArgs *carry_sum;
+};
+// shapes and alignments the kernel takes (bf16, head_dim 128, L <= 96, d_in in 64s, an even number of query heads per KV head)
+bool lsa_fused_ok(int dtype, int L, int d_in, int Hq, int Hkv, int dh, const void *hs, const void *wq, const void *wk,
+                  const void *wv, const void *abar);
+hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream);
 
 // ---- LSA attention over the layer axis (LsaAttnArgs is declared above, beside the projections that can carry it)
 size_t lsa_attn_lds_bytes(int dtype, int L, int dh);

@@ -1,0 +1,424 @@
+// Layer Self-Attention with mean aggregation in ONE kernel (paper Sec. 3.1.1; Alg. 1, LSA_layer_with_mean):
+// Q/K/V projection of a token's L layer rows, attention over the layer axis, and the mean over the layers, with the
+// projected Q, K, V never leaving the compute unit.  Every token is independent of the others (Sec. 3.1.1), so a
+// workgroup that owns whole tokens needs nothing from any other workgroup.
+//
+// A workgroup of eight wavefronts owns TT tokens (all their layer rows: RB = 32 NB TT rows, NB = ceil(L/32)) and the
+// features of one KV head's group that one attention needs: two query heads, the key head and the value head, 4 dh
+// features.  (A group of more than two query heads is cut into parts of two; each part recomputes K and V.)
+//
+//  projection  [RB x d_in] x [4 dh x d_in]^T on MFMA 32x32x16, walked along d_in in tiles of 64.  Wavefront w owns
+//              the features w dh/2 .. and ALL rows, so its slice of the weight tile is its own: it fetches it itself
+//              (global memory straight into LDS, 128-byte rows, XOR-swizzled against bank conflicts) into a private
+//              two-stage ring and needs no barrier for it, only its own load counter.  As soon as a wavefront has
+//              read its fragments of tile kt it requests tile kt+2 into the same place, so one whole tile and most of
+//              another are in flight per compute unit while a tile is being multiplied.  The activation tile (RB rows,
+//              shared by all wavefronts, an eighth of the weight tile) goes through a small ring of its own with one
+//              barrier per tile.
+//              Three things cost about the same per tile -- the weight tile's way from the L2 into LDS (64 KB per
+//              64 of d_in, all workgroups of an XCD asking for the same lines at once), the operand reads from LDS
+//              and the matrix work -- and they overlap only in part; the lever that is left is rows per workgroup
+//              (2, 3 or 4 tokens at one 32-layer block each), chosen from the token count on the host.
+//  attention   the accumulators are rounded to the storage type and parked in LDS as a [RB x 4 dh] tile (the ring
+//              memory is reused); one wavefront per (token, query head): S^T = K Q^T by MFMA, fp32 softmax in
+//              registers, column means of P by a 32-lane butterfly, then abar = sum_j pbar_j V_j
+//              (mean_i(P V) = (1^T P / L) V, exact in real arithmetic).  The output projection follows in another
+//              launch on one row per token.
+//
+// Arithmetic is that of the three-kernel form (same MFMA order along d_in, Q/K/V rounded once to the storage type),
+// so both give the same bits.
+#include "moa_common.h"
+#include "moa_sum_device.h"
+#include "moa_tree_device.h"
+
+#include <math.h>
+
+namespace moa {
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
+
+struct LsaFusedArgs {
+    const bf16_t *hs;              // [T, L, d_in]
+    const bf16_t *wq, *wk, *wv;    // [Hq*dh, d_in], [Hkv*dh, d_in] x 2
+    bf16_t *abar;                  // [T, Hq*dh]
+    int64_t T;
+    int L, d_in, Hq, Hkv;
+    int parts;                     // Hq / Hkv / 2: workgroups per KV head
+    int units;                     // Hkv * parts
+    int units_per_xcd;
+    int lead_blocks, small_lead, red_blocks;   // workgroups in front of the kernel's own: integer work of a step, a carried summing pass
+    int rider_units;
+    StepSmallArgs rider;
+    SumArgs red;
+};
+
+template <int DH, int NB, int TT>
+struct LsaFusedGeom {
+    static constexpr int NF = 4 * DH;            // features per workgroup
+    static constexpr int FW = NF / 8;            // per wavefront
+    static constexpr int RB = 32 * NB * TT;      // rows per workgroup
+    static constexpr int BK = 64;
+    static constexpr int XS = RB <= 64 ? 3 : 2;  // stages of the activation ring
+    static constexpr size_t w_bytes = (size_t)8 * 2 * FW * BK * sizeof(bf16_t);
+    static constexpr size_t x_bytes = (size_t)XS * RB * BK * sizeof(bf16_t);
+    static constexpr int TLD = NF + 8;           // row of the parked Q/K/V tile: 16-byte reads of 8 rows hit all banks
+    static constexpr size_t tile_bytes = (size_t)RB * TLD * sizeof(bf16_t);
+    static constexpr size_t pbar_bytes = (size_t)8 * 32 * NB * sizeof(float);
+    static constexpr size_t loop_bytes = w_bytes + x_bytes;
+    static constexpr size_t epi_bytes = tile_bytes + pbar_bytes;
+    static constexpr size_t bytes = loop_bytes > epi_bytes ? loop_bytes : epi_bytes;
+};
+
+template <int DH, int NB, int TT>
+__global__ __launch_bounds__(512) void k_lsa_fused(LsaFusedArgs a)
+{
+    using Gm = LsaFusedGeom<DH, NB, TT>;
+    constexpr int FW = Gm::FW, RB = Gm::RB, BK = Gm::BK, XS = Gm::XS, TLD = Gm::TLD;
+    constexpr int WFB = FW / 32;                 // 32-feature blocks per wavefront
+    constexpr int NRB = RB / 32;                 // 32-row blocks
+    constexpr int NWI = FW / 8;                  // weight-tile load instructions per wavefront (8 rows of 128 B each)
+    constexpr int NXI = (RB / 8 + 7) / 8;        // activation-tile load instructions per wavefront
+    constexpr int XD = XS - 1;                   // activation tiles requested ahead
+    extern __shared__ __attribute__((aligned(16))) bf16_t sm[];
+
+    if ((int)blockIdx.x < a.lead_blocks) {       // the first workgroups of the grid carry work of other calls
+        if ((int)blockIdx.x < a.small_lead) {
+            if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
+                step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)sm, (int32_t *)sm + MOA_MAX_TREE);
+        } else {
+            const int blk = 2 * ((int)blockIdx.x - a.small_lead) + (int)(threadIdx.x >> 8);
+            if (blk < a.red_blocks) splitk_reduce_block(a.red, blk, (int)(threadIdx.x & 255));
+        }
+        return;
+    }
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: an XCD keeps the weight slices of its
+    // units (2 MB each at the Llama-3-8B shape) and every token tile's activations pass through it once.
+    const int bx = (int)blockIdx.x - a.lead_blocks;
+    const int xcd = bx & 7, slot = bx >> 3;
+    const int unit = xcd * a.units_per_xcd + slot % a.units_per_xcd;
+    const int64_t tile = slot / a.units_per_xcd;
+    if (unit >= a.units) return;                 // the whole workgroup leaves before any barrier
+    const int g = unit / a.parts, part = unit - g * a.parts;
+    const int G = a.Hq / a.Hkv, L = a.L, K = a.d_in;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int lrow = lane >> 3, lpos = lane & 7;
+
+    f32x16 acc[WFB][NRB];
+#pragma unroll
+    for (int i = 0; i < WFB; ++i)
+#pragma unroll
+        for (int j = 0; j < NRB; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    const int nk = K / BK;                       // >= 2 (checked on the host)
+
+    // this wavefront's FW feature rows of the weight tile: inside one of Wq (two heads), Wk, Wv
+    const int which = wave * FW / DH;
+    const bf16_t *wm = which < 2 ? a.wq + (int64_t)((g * G + 2 * part + which) * DH + wave * FW % DH) * K
+                                 : (which == 2 ? a.wk : a.wv) + (int64_t)(g * DH + wave * FW % DH) * K;
+    const bf16_t *wsrc[NWI];
+#pragma unroll
+    for (int i = 0; i < NWI; ++i) {
+        const int row = 8 * i + lrow;
+        wsrc[i] = wm + (int64_t)row * K + 8 * (lpos ^ ((row >> 1) & 7));
+    }
+    // its share of the activation tile: instruction xi covers tile rows 8 xi .. 8 xi + 7 (a row past the tokens or the
+    // layers repeats a valid one; such rows are masked as keys and dropped as queries)
+    const bf16_t *xsrc[NXI];
+    int xrow0[NXI];
+#pragma unroll
+    for (int n = 0; n < NXI; ++n) {
+        int xi = wave + 8 * n;
+        if (xi > RB / 8 - 1) xi = RB / 8 - 1;    // a spare instruction repeats the last one (same bytes to the same place)
+        xrow0[n] = 8 * xi;
+        const int s = 8 * xi + lrow;
+        int64_t tok = tile * TT + s / (32 * NB);
+        int lay = s % (32 * NB);
+        if (tok > a.T - 1) tok = a.T - 1;
+        if (lay > L - 1) lay = L - 1;
+        xsrc[n] = a.hs + (tok * L + lay) * (int64_t)K + 8 * (lpos ^ ((s >> 1) & 7));
+    }
+    bf16_t *wl = sm + (size_t)wave * 2 * FW * BK;                 // this wavefront's ring: [2][FW][BK]
+    bf16_t *xl = sm + (size_t)8 * 2 * FW * BK;                    // [XS][RB][BK]
+    auto issue_w = [&](int kt) {
+        bf16_t *dst = wl + (kt & 1) * FW * BK;
+#pragma unroll
+        for (int i = 0; i < NWI; ++i)
+            __builtin_amdgcn_global_load_lds((global_void_t *)(wsrc[i] + (int64_t)kt * BK), (lds_void_t *)(dst + 8 * i * BK), 16, 0, 0);
+    };
+    auto issue_x = [&](int kt) {
+        bf16_t *dst = xl + (kt % XS) * RB * BK;
+#pragma unroll
+        for (int n = 0; n < NXI; ++n)
+            __builtin_amdgcn_global_load_lds((global_void_t *)(xsrc[n] + (int64_t)kt * BK), (lds_void_t *)(dst + xrow0[n] * BK), 16, 0, 0);
+    };
+
+    // Requests are issued in the order X(0) W(0) X(1) W(1) (W(0) X(0) W(1) with a two-stage activation ring), then per
+    // tile kt: X(kt+XD) W(kt+2), and complete in that order (all of them go straight to LDS).  At the top of tile kt,
+    // X(kt) and W(kt) must have landed; what was requested after the later of the two is X(kt+1) W(kt+1) (only
+    // W(kt+1) with the two-stage ring), and nothing in the last round.
+    if (XD >= 2) issue_x(0);
+    issue_w(0);
+    issue_x(XD >= 2 ? 1 : 0);
+    issue_w(1);
+    constexpr int PENDING = XD >= 2 ? NXI + NWI : NWI;
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        const bf16_t *wb = wl + (kt & 1) * FW * BK;
+        const bf16_t *xb = xl + (kt % XS) * RB * BK;
+        // The four k-steps of a tile are software-pipelined: the fragments of step ks+1 are requested from LDS before
+        // the MFMAs of step ks are issued, so LDS reads and matrix work of one wavefront overlap.  Once the last
+        // step's fragments have been read, the ring places this tile occupied are free and are refilled.
+        auto read_frags = [&](int ks, bf16x8 (&fa)[WFB], bf16x8 (&fb)[NRB]) {
+#pragma unroll
+            for (int i = 0; i < WFB; ++i) {
+                const int row = 32 * i + l32;
+                fa[i] = *(const bf16x8 *)&wb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
+            }
+#pragma unroll
+            for (int j = 0; j < NRB; ++j) {
+                const int row = 32 * j + l32;
+                fb[j] = *(const bf16x8 *)&xb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
+            }
+        };
+        bf16x8 af[2][WFB], bfr[2][NRB];
+        read_frags(0, af[0], bfr[0]);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks + 1 < BK / 16) read_frags(ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
+            if (ks == BK / 16 - 1) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if (kt + XD < nk) issue_x(kt + XD);
+                if (kt + 2 < nk) issue_w(kt + 2);
+            }
+#pragma unroll
+            for (int i = 0; i < WFB; ++i)
+#pragma unroll
+                for (int j = 0; j < NRB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // park Q | Q' | K | V of the RB rows in LDS, rounded to the storage type
+    __syncthreads();                             // every wavefront is done with the rings
+    bf16_t *tile_s = sm;
+    float *pbar_s = (float *)((char *)sm + Gm::tile_bytes) + wave * 32 * NB;
+    // acc[i][j][v]: feature = f0 + 32 i + 8 (v / 4) + 4 half + v % 4, row = 32 j + l32
+    const int f0 = wave * FW;
+    {
+#pragma unroll
+        for (int i = 0; i < WFB; ++i)
+#pragma unroll
+            for (int j = 0; j < NRB; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    u32x2 pk;
+                    pk[0] = (uint32_t)f2bf(acc[i][j][4 * q + 0]) | ((uint32_t)f2bf(acc[i][j][4 * q + 1]) << 16);
+                    pk[1] = (uint32_t)f2bf(acc[i][j][4 * q + 2]) | ((uint32_t)f2bf(acc[i][j][4 * q + 3]) << 16);
+                    *(u32x2 *)&tile_s[(32 * j + l32) * TLD + f0 + 32 * i + 8 * q + 4 * half] = pk;
+                }
+    }
+    __syncthreads();
+
+    // attention over the layer axis: one wavefront per (token of the tile, query head); spare wavefronts redo a
+    // unit and store nothing, so that the barriers below are reached by all
+    constexpr int NU = 2 * TT;
+    constexpr int NKS = DH / 16;
+    const bool live_wave = wave < NU;
+    const int u = wave % NU, tt = u >> 1, hq = u & 1;
+    const int64_t tok = tile * TT + tt;
+    const bf16_t *trow = tile_s + (size_t)tt * 32 * NB * TLD;
+    const float sc = 1.4426950408889634f / sqrtf((float)DH);      // log2 domain
+
+    // column sums of P in the S^T register layout: csum[jb][v] belongs to key 32 jb + 8 (v/4) + 4 half + v%4
+    float csum[NB][16];
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) csum[jb][e] = 0.f;
+#pragma unroll
+    for (int ib = 0; ib < NB; ++ib) {
+        const bool qvalid = 32 * ib + l32 < L;
+        bf16x8 qf[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const bf16x8 *)&trow[(32 * ib + l32) * TLD + hq * DH + 16 * ks + 8 * half];
+        f32x16 s[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[jb][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {        // key fragments straight from the parked tile: nothing to keep across blocks
+                const bf16x8 kf = *(const bf16x8 *)&trow[(32 * jb + l32) * TLD + 2 * DH + 16 * ks + 8 * half];
+                s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[jb], 0, 0, 0);
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = 32 * jb + 8 * (e >> 2) + 4 * half + (e & 3);
+                const float x = key < L ? s[jb][e] * sc : -INFINITY;
+                s[jb][e] = x;
+                mx = fmaxf(mx, x);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float sum = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { const float p = exp2f(s[jb][e] - mx); s[jb][e] = p; sum += p; }
+        sum += __shfl_xor(sum, 32);
+        const float inv = qvalid ? 1.0f / sum : 0.f;              // padded query columns contribute nothing
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) csum[jb][e] += s[jb][e] * inv;
+    }
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float x = csum[jb][e];
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) x += __shfl_xor(x, o);
+            csum[jb][e] = x;
+        }
+    if (l32 == 0) {
+        const float invL = 1.0f / (float)L;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) pbar_s[32 * jb + 8 * (e >> 2) + 4 * half + (e & 3)] = csum[jb][e] * invL;
+    }
+    __syncthreads();
+
+    // abar[c] = sum_j pbar[j] V[j][c]: a lane weights 8 components of its rows, then the row groups are added up
+    constexpr int CPR = DH / 8;                  // 16-byte pieces per V row
+    constexpr int RPI = 64 / CPR;                // rows per instruction
+    constexpr int NVI = 32 / RPI;
+    const int vrow0 = lane / CPR, vpiece = lane % CPR;
+    float o[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[c] = 0.f;
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int i = 0; i < NVI; ++i) {
+            const int row = 32 * jb + RPI * i + vrow0;
+            const float pj = row < L ? pbar_s[row] : 0.f;
+            const u32x4 vv = *(const u32x4 *)&trow[row * TLD + 3 * DH + 8 * vpiece];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                o[2 * w] = fmaf(pj, __uint_as_float(vv[w] << 16), o[2 * w]);
+                o[2 * w + 1] = fmaf(pj, __uint_as_float(vv[w] & 0xffff0000u), o[2 * w + 1]);
+            }
+        }
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int off = CPR; off < 64; off <<= 1) o[c] += __shfl_xor(o[c], off);
+    if (live_wave && tok < a.T && lane < CPR) {
+        u32x4 pk;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) pk[w] = (uint32_t)f2bf(o[2 * w]) | ((uint32_t)f2bf(o[2 * w + 1]) << 16);
+        *(u32x4 *)(a.abar + tok * (int64_t)a.Hq * DH + (int64_t)(g * G + 2 * part + hq) * DH + 8 * lane) = pk;
+    }
+}
+
+// ------------------------------------------------------------------ host side
+bool lsa_fused_ok(int dtype, int L, int d_in, int Hq, int Hkv, int dh, const void *hs, const void *wq, const void *wk,
+                  const void *wv, const void *abar)
+{
+    auto al = [](const void *p) { return p && (((uintptr_t)p) & 15) == 0; };
+    if (dtype != DT_BF16 || dh != 128) return false;
+    if (L < 1 || L > 96 || d_in < 128 || d_in % 64) return false;
+    if (Hq % Hkv || (Hq / Hkv) % 2) return false;
+    return al(hs) && al(wq) && al(wk) && al(wv) && al(abar);
+}
+
+// LDS a workgroup may ask for on the current device (looked up once per device; 0 if the query fails)
+static size_t lds_limit()
+{
+    static size_t limit[16] = {};
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return 0;
+    if (!limit[dev]) {
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || v <= 0) return 0;
+        limit[dev] = (size_t)v;
+    }
+    return limit[dev];
+}
+
+template <int NB, int TT>
+static hipError_t launch_lsa_fused_as(LsaFusedArgs &fa, hipStream_t stream)
+{
+    using Gm = LsaFusedGeom<128, NB, TT>;
+    static bool raised[16] = {};
+    hipError_t e = raise_lds_limit_once(raised, (const void *)k_lsa_fused<128, NB, TT>, Gm::bytes);
+    if (e != hipSuccess) return e;
+    const int64_t tiles = (fa.T + TT - 1) / TT;
+    const int64_t grid = fa.lead_blocks + 8 * (int64_t)fa.units_per_xcd * tiles;
+    if (grid > 0x7fffffff) return hipErrorInvalidValue;
+    prof_begin(K_LSA_FUSED + 64 * (NB * 8 + TT), stream);
+    MOA_KLAUNCH((k_lsa_fused<128, NB, TT>), dim3((unsigned)grid), dim3(512), Gm::bytes, stream, fa);
+    prof_end(stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream)
+{
+    if (c.T <= 0) return hipSuccess;
+    LsaFusedArgs fa = {};
+    fa.hs = (const bf16_t *)c.hs;
+    fa.wq = (const bf16_t *)c.wq;
+    fa.wk = (const bf16_t *)c.wk;
+    fa.wv = (const bf16_t *)c.wv;
+    fa.abar = (bf16_t *)c.abar;
+    fa.T = c.T;
+    fa.L = c.L;
+    fa.d_in = c.d_in;
+    fa.Hq = c.Hq;
+    fa.Hkv = c.Hkv;
+    fa.parts = c.Hq / c.Hkv / 2;
+    fa.units = c.Hkv * fa.parts;
+    fa.units_per_xcd = (fa.units + 7) / 8;
+    fa.rider_units = c.rider_units;
+    if (c.rider_units > 0) fa.rider = c.rider;
+    fa.small_lead = (c.rider_units + 7) & ~7;    // multiples of the XCD count: the unit mapping keeps its phase
+    fa.red_blocks = 0;
+    if (c.carry_sum && c.carry_sum->blocks > 0) {
+        fa.red = *c.carry_sum;
+        fa.red_blocks = c.carry_sum->blocks;
+    }
+    fa.lead_blocks = fa.small_lead + ((((fa.red_blocks + 1) / 2) + 7) & ~7);   // a lead workgroup of 512 threads does two blocks of the pass
+    // Rows per workgroup.  Measured at the Llama-3-8B shape (d_in 2048), a workgroup takes about 31 + 9 (rows / 32)
+    // microseconds whatever else runs (it is bound by its own chain of tile fetches from the L2 and its matrix work),
+    // and the chip runs 256 of them at a time: few tokens want small tiles (every compute unit busy), many tokens
+    // large ones (fewer passes over the weights).  Pick the tile that minimises rounds x time per round.
+    const int nb = (c.L + 31) / 32;
+    const bool big_ok = lds_limit() >= LsaFusedGeom<128, 1, 4>::bytes;      // the 128-row tiles fill the LDS to the last byte
+    auto cost = [&](int tt) {
+        const double wgs = (double)fa.units * (double)((c.T + tt - 1) / tt);
+        return (wgs > 256.0 ? wgs / 256.0 : 1.0) * (31.0 + 9.0 * nb * tt);
+    };
+    if (nb == 1) {
+        int best = 2;
+        if (cost(3) < cost(best)) best = 3;
+        if (big_ok && cost(4) < cost(best)) best = 4;
+        if (best == 4) return launch_lsa_fused_as<1, 4>(fa, stream);
+        if (best == 3) return launch_lsa_fused_as<1, 3>(fa, stream);
+        return launch_lsa_fused_as<1, 2>(fa, stream);
+    }
+    if (nb == 2) {
+        if (big_ok && cost(2) < cost(1)) return launch_lsa_fused_as<2, 2>(fa, stream);
+        return launch_lsa_fused_as<2, 1>(fa, stream);
+    }
+    return launch_lsa_fused_as<3, 1>(fa, stream);
+}
+
+}  // namespace moa

@@ -134,8 +134,18 @@ def run_lsa(G, moa, oracle, cfg, T):
     return G.host(out), want
 
 
+@pytest.fixture(params=["fused", "separate"])
+def lsa_kernel(request, moa):
+    """Both forms of the Layer Self-Attention on every case: projection, attention over the layers and mean in one
+    kernel (taken wherever the shapes allow: bf16, head_dim 128), or as three kernels with the projected rows in the
+    workspace (forced)."""
+    moa.debug_force_lsa_kernel(request.param)
+    yield request.param
+    moa.debug_force_lsa_kernel("auto")
+
+
 @pytest.mark.parametrize("case", list(CASES))
-def test_lsa_parity(G, moa, oracle, case):
+def test_lsa_parity(G, moa, oracle, case, lsa_kernel):
     cfg = CASES[case]
     T = 60 if case == "C1_bf16" else 7
     print(f"[case] lsa {case} T={T} L={cfg.L} d_in={cfg.d_lsa_in} heads={cfg.lsa_heads}/{cfg.Hkv} dh={cfg.dh}", flush=True)
@@ -143,7 +153,7 @@ def test_lsa_parity(G, moa, oracle, case):
     G.check_close(got, want, cfg.dtype, f"lsa[{case}]")
 
 
-def test_lsa_many_tokens_tiled_projection(G, moa, oracle):
+def test_lsa_many_tokens_tiled_projection(G, moa, oracle, lsa_kernel):
     """More than 128 projected rows takes the LDS-tiled MFMA GEMM; more than 256 tokens takes two chunks."""
     cfg = small_cfg("bf16", L=3, d_lsa_in=256, dh=128, Hkv=1)       # LSA heads 2/1, N = 256 + 128 + 128
     T = 300
@@ -153,12 +163,41 @@ def test_lsa_many_tokens_tiled_projection(G, moa, oracle):
 
 
 @pytest.mark.parametrize("L,dh", [(80, 128), (40, 64), (33, 128), (96, 64)])
-def test_lsa_layer_counts_beyond_one_block(G, moa, oracle, L, dh):
+def test_lsa_layer_counts_beyond_one_block(G, moa, oracle, L, dh, lsa_kernel):
     """Llama-2-70B stacks 80 layers: more than one 32-layer block on the layer axis, ragged last block."""
     cfg = small_cfg("bf16", L=L, d_lsa_in=2 * dh, dh=dh, Hkv=1)
     print(f"[case] lsa L={L} dh={dh}", flush=True)
     got, want = run_lsa(G, moa, oracle, cfg, 5)
     G.check_close(got, want, cfg.dtype, f"lsa[L={L},dh={dh}]")
+
+
+@pytest.mark.parametrize("L,d_in,Hkv,T", [(32, 512, 2, 9), (64, 1024, 2, 5), (17, 256, 1, 6), (96, 512, 4, 3), (2, 128, 1, 4),
+                                           (32, 1024, 4, 600), (32, 512, 2, 401), (64, 512, 2, 201)])
+def test_lsa_one_kernel_form_shapes(G, moa, oracle, L, d_in, Hkv, T):
+    """The one-kernel form across its template variants (one, two and three blocks of 32 layers), groups of two and of
+    four query heads per KV head (a group of four is cut into two parts that recompute K and V), odd token counts (a
+    half-filled token tile), the shortest input width it takes, and enough tokens for the tiles of three and four tokens
+    (two at two blocks of layers) with a ragged last tile; it must also give the bits of the three-kernel form."""
+    cfg = small_cfg("bf16", L=L, d_lsa_in=d_in, dh=128, Hkv=Hkv)
+    print(f"[case] lsa one-kernel L={L} d_in={d_in} heads={cfg.lsa_heads}/{Hkv} T={T}", flush=True)
+    shape = G.shape_of(cfg)
+    w = mi.lsa_weights(cfg)
+    hs = mi.lsa_inputs(cfg, T)
+    ws = G.workspace(shape, cfg.B, cfg.P_cap, cfg.M, T)
+    dw = [G.dev(w[k], cfg.dtype) for k in ("wq", "wk", "wv", "wo")]
+    outs = {}
+    for form in ("fused", "separate"):
+        moa.debug_force_lsa_kernel(form)
+        try:
+            out = torch.full((T, cfg.d_lsa), float("nan"), dtype=G.TDT[cfg.dtype], device="cuda")
+            moa.lsa(shape, G.dev(hs, cfg.dtype), *dw, out, ws)
+            torch.cuda.synchronize()
+        finally:
+            moa.debug_force_lsa_kernel("auto")
+        outs[form] = out
+    want = oracle.lsa(hs, w["wq"], w["wk"], w["wv"], w["wo"], cfg.lsa_heads, cfg.Hkv, cfg.dh)
+    G.check_close(G.host(outs["fused"]), want, cfg.dtype, f"lsa one-kernel[L={L},d_in={d_in},Hkv={Hkv}]")
+    assert torch.equal(outs["fused"], outs["separate"]), "same products in the same order, same roundings"
 
 
 def ca_setup(cfg, Mq):
