@@ -1386,16 +1386,25 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
 }
 
 // ---- the same pieces on two streams.
-// Dependencies inside one step: the LSA chain (projection -> layer attention -> W_o -> memory append) feeds
-// only the cross-attention core; the projections of the cross-attention queries and every verification layer
-// depend on none of it.  The LSA chain is bound by the matrix cores and by launch latency, the projections by
-// HBM, so running them side by side hides most of the weight streaming.  The side branch runs on a
-// library-owned stream that is forked from and joined back into the caller's stream with events, so the
-// caller still sees one stream's worth of ordering (and a stream capture records both branches).
+// Dependencies inside one step: the LSA chain (LSA -> W_o -> memory append) feeds only the cross-attention core; the
+// projections of the cross-attention queries and every verification layer depend on none of it.  The LSA kernel is
+// bound by the matrix cores and the L2, the projections by HBM, so the two halves want different parts of the chip.
+// They cannot share a compute unit (the LSA kernel fills its LDS), so they share the chip side by side: the LSA runs
+// with its largest token tile, which at decode sizes leaves half of the compute units without a workgroup of it, and
+// the weight-streaming launches of the side branch take those.  The side branch runs on a library-owned stream that
+// is forked from and joined back into the caller's stream with events, so the caller still sees one stream's worth of
+// ordering (and a stream capture records both branches).
+//   side: [CA query + verification Q/K/V projections + the step's integer work] -> E_small -> [sum of its K slices]
+//         -> E_q -> verification core -> W_o -> further layers -> E_join
+//   main: E_fork -> LSA -> wait E_small (old memory lengths) -> LSA W_o + memory append -> wait E_q (CA queries)
+//         -> cross-attention core -> W_o -> wait E_join
+// One side stream and one set of events exist per device; a mutex is held while a step is being enqueued, so steps of
+// several host threads on one device are enqueued one after the other.
 struct SideStream {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, caq = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, small = nullptr, q = nullptr, join = nullptr;
     bool ok = false;
+    std::mutex enqueue;
 };
 
 static SideStream *side_stream_for_current_device()
@@ -1409,7 +1418,8 @@ static SideStream *side_stream_for_current_device()
     if (!s.stream) {
         s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
                hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&s.caq, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&s.small, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&s.q, hipEventDisableTiming) == hipSuccess &&
                hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
     }
     return s.ok ? &s : nullptr;
@@ -1422,6 +1432,63 @@ static size_t two_stream_bytes(const moa_step_args_t *a)
     return L.total() + L.scratch;
 }
 
+// side branch; *forked_small / *forked_q report which events have been recorded when it fails half way
+static int32_t two_stream_side(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes, SideStream *ss)
+{
+    hipStream_t side = ss->stream;
+    SumArgs sum_pair = {};
+    int32_t rc = piece_projections(a, bf, scr, scr_bytes, side, true, &sum_pair);
+    if (rc) return rc;
+    MOA_TRY_HIP(hipEventRecord(ss->small, side), "draft_step: event");
+    prof_set_site(S_PAIR_QKV);
+    MOA_TRY_HIP(launch_splitk_sum(sum_pair, side), "draft_step: projections");
+    MOA_TRY_HIP(hipEventRecord(ss->q, side), "draft_step: event");
+    // the partial sums have been added up: the scratch is free for the core and the output projection
+    prof_set_site(S_VERIFY_CORE);
+    MOA_TRY_HIP(launch_attn(piece_verify_core_args(a, bf, scr, scr_bytes), side), "draft_step: verification core");
+    rc = piece_oproj(a, bf, 2, scr, scr_bytes, side);
+    if (rc) return rc;
+    return piece_more_verify_layers(a, scr, scr_bytes, side);
+}
+
+static int32_t two_stream_main(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes, SideStream *ss)
+{
+    hipStream_t main = (hipStream_t)a->stream;
+    const moa_shape_t *sh = a->shape;
+    const int64_t T = a->T_lsa;
+    int32_t rc = lsa_check(sh, a->lsa_hs, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_out, scr, scr_bytes);
+    if (rc) return rc;
+    const LsaBufs b = lsa_carve(sh, T, scr, scr_bytes);
+    void *abar = a->lsa_wo ? (void *)b.abar0 : a->lsa_out;
+    const bool fused = T > 0 && T <= LSA_OBLOCK && lsa_takes_fused(sh, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
+    if (fused) {
+        LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
+        fc.leave_room = 1;                   // the largest token tile: fewest workgroups, compute units left to the side branch
+        prof_set_site(S_LSA_FUSED);
+        MOA_TRY_HIP(launch_lsa_fused(fc, main), "lsa: fused kernel");
+        MOA_TRY_HIP(hipStreamWaitEvent(main, ss->small, 0), "draft_step: wait");     // the append needs the old lengths
+        LinSeg folded[2];
+        const bool fold = a->lsa_wo && folded_segments(a, bf, folded);
+        if (a->lsa_wo) {
+            const LinArgs lo = lsa_oproj_args(sh, 0, T, a->lsa_wo, a->lsa_out, b, folded, fold ? 2 : 0);
+            prof_set_site(S_LSA_OPROJ);
+            MOA_TRY_HIP(launch_linear(sh->dtype, lo, main), "lsa: output projection");
+        }
+        if (!fold) {
+            rc = piece_append(a, bf, scr, scr_bytes, main);
+            if (rc) return rc;
+        }
+    } else {
+        MOA_TRY_HIP(hipStreamWaitEvent(main, ss->small, 0), "draft_step: wait");
+        rc = piece_lsa_append(a, bf, scr, scr_bytes, main);
+        if (rc) return rc;
+    }
+    MOA_TRY_HIP(hipStreamWaitEvent(main, ss->q, 0), "draft_step: wait");             // the cross-attention's queries
+    prof_set_site(S_CA_CORE);
+    MOA_TRY_HIP(launch_attn(piece_ca_core_args(a, bf, scr, scr_bytes), main), "draft_step: cross-attention core");
+    return piece_oproj(a, bf, 1, scr, scr_bytes, main);
+}
+
 static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
 {
     hipStream_t main = (hipStream_t)a->stream, side = ss->stream;
@@ -1429,34 +1496,23 @@ static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
     char *scr_main = nullptr;
     const StepBufs bf = carve_step_bufs(a, L, &scr_main);
     char *scr_side = scr_main + L.scratch;
+    std::lock_guard<std::mutex> lk(ss->enqueue);
 
-    int32_t rc = piece_small(a, bf, main);                    // the mask is needed by the side branch
-    if (rc) return rc;
     MOA_TRY_HIP(hipEventRecord(ss->fork, main), "draft_step: fork");
     MOA_TRY_HIP(hipStreamWaitEvent(side, ss->fork, 0), "draft_step: fork");
-
-    // side branch: projections, then verification layer 0's core and W_o, then the other layers
-    rc = piece_projections(a, bf, scr_side, L.scratch, side, false);
-    if (rc) return rc;
-    MOA_TRY_HIP(hipEventRecord(ss->caq, side), "draft_step: event");
-    prof_set_site(S_VERIFY_CORE);
-    MOA_TRY_HIP(launch_attn(piece_verify_core_args(a, bf, scr_side, L.scratch), side), "draft_step: verification core");
-    rc = piece_oproj(a, bf, 2, scr_side, L.scratch, side);
-    if (rc) return rc;
-    rc = piece_more_verify_layers(a, scr_side, L.scratch, side);
-    if (rc) return rc;
-    MOA_TRY_HIP(hipEventRecord(ss->join, side), "draft_step: event");
-
-    // main branch: LSA chain, then the cross-attention core + W_o once its queries are there, join
-    rc = piece_lsa_append(a, bf, scr_main, L.scratch, main);
-    if (rc) return rc;
-    MOA_TRY_HIP(hipStreamWaitEvent(main, ss->caq, 0), "draft_step: wait");
-    prof_set_site(S_CA_CORE);
-    MOA_TRY_HIP(launch_attn(piece_ca_core_args(a, bf, scr_main, L.scratch), main), "draft_step: cross-attention core");
-    rc = piece_oproj(a, bf, 1, scr_main, L.scratch, main);
-    if (rc) return rc;
-    MOA_TRY_HIP(hipStreamWaitEvent(main, ss->join, 0), "draft_step: join");
-    return MOA_OK;
+    // Whatever happens from here on, the side stream is joined back into the caller's (a stream capture must not be
+    // left with an unjoined branch).  Events a failed branch did not get to record are recorded here, so that no
+    // wait of this or a later step refers to an older step's event.
+    int32_t rc = two_stream_side(a, bf, scr_side, L.scratch, ss);
+    if (rc) {
+        hipEventRecord(ss->small, side);
+        hipEventRecord(ss->q, side);
+    }
+    const hipError_t ej = hipEventRecord(ss->join, side);
+    if (rc == MOA_OK) rc = two_stream_main(a, bf, scr_main, L.scratch, ss);
+    const hipError_t ew = ej == hipSuccess ? hipStreamWaitEvent(main, ss->join, 0) : ej;
+    if (rc == MOA_OK && ew != hipSuccess) rc = hip_fail(ew, "draft_step: join");
+    return rc;
 }
 
 int32_t moa_draft_step(const moa_step_args_t *args)

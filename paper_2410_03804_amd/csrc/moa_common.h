@@ -276,6 +276,7 @@ struct LsaFusedCall {
     StepSmallArgs rider;
     int rider_units;
     const SumArgs *carry_sum;
+    int leave_room;      // take the largest token tile: fewest workgroups, so that another stream's kernels find free compute units
 };
 // shapes and alignments the kernel takes (bf16, head_dim 128, L <= 96, d_in in 64s, an even number of query heads per KV head)
 bool lsa_fused_ok(int dtype, int L, int d_in, int Hq, int Hkv, int dh, const void *hs, const void *wq, const void *wk,

@@ -409,13 +409,13 @@ hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream)
     if (nb == 1) {
         int best = 2;
         if (cost(3) < cost(best)) best = 3;
-        if (big_ok && cost(4) < cost(best)) best = 4;
+        if (big_ok && (cost(4) < cost(best) || c.leave_room)) best = 4;
         if (best == 4) return launch_lsa_fused_as<1, 4>(fa, stream);
         if (best == 3) return launch_lsa_fused_as<1, 3>(fa, stream);
         return launch_lsa_fused_as<1, 2>(fa, stream);
     }
     if (nb == 2) {
-        if (big_ok && cost(2) < cost(1)) return launch_lsa_fused_as<2, 2>(fa, stream);
+        if (big_ok && (cost(2) < cost(1) || c.leave_room)) return launch_lsa_fused_as<2, 2>(fa, stream);
         return launch_lsa_fused_as<2, 1>(fa, stream);
     }
     return launch_lsa_fused_as<3, 1>(fa, stream);
