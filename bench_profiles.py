@@ -8,6 +8,8 @@ databases are produced on the MI355X machine by commands like the ones each summary 
   python bench_profiles.py traffic  --fetch F.db --write W.db --cmd "<commands>" --title "..." --workload "..." \
                                     --out profiles/x            (writes x.md and x.json; bench.py reads the .json)
   python bench_profiles.py counters --db A.db B.db ... --cmd "<commands>" --title "..." --out profiles/x.md
+  python bench_profiles.py regimes  --line "label=bench_output.json" ... --cmd "<commands>" --title "..." --out profiles/x.md
+                                    (one table row per bench.py JSON line: step time, dominant kernel, rooflines)
 
 Counter rows of one dispatch (one per shader engine / XCD instance) are summed; a kernel's figure is the mean over
 its dispatches.
@@ -43,7 +45,13 @@ def short_name(n: str) -> str:
     return n[:cut].replace("moa::", "").strip()
 
 
+COMMIT_OVERRIDE = ""
+
+
 def head_commit() -> str:
+    """The commit the summarised run was made from: --commit if given, else the current HEAD."""
+    if COMMIT_OVERRIDE:
+        return COMMIT_OVERRIDE
     try:
         return subprocess.check_output(["git", "-C", str(ROOT), "rev-parse", "--short=12", "HEAD"], text=True).strip()
     except (OSError, subprocess.CalledProcessError):
@@ -188,11 +196,36 @@ def cmd_counters(a):
     print("\n".join(lines))
 
 
+def cmd_regimes(a):
+    lines = [f"# {a.title}", "", "Commands (from the repository root on the MI355X box; `bench.py` prints one JSON line each):", "", "```", a.cmd, "```", "",
+             f"Library commit: `{head_commit()}`. `frac` is the dominant kernel's achieved rate over the published peak of its bound "
+             "(HBM 8 TB/s, dense bf16 MFMA 2.5 PFLOP/s); `step frac` is the whole step's algorithmic bytes (or flops) over the "
+             "step time against the same peaks.", "",
+             "| workload | ms / step | tokens / s | dominant kernel | us / launch | bound | achieved | frac | step bound | step frac |",
+             "|---|---|---|---|---|---|---|---|---|---|"]
+    for item in a.line:
+        label, path = item.split("=", 1)
+        j = None
+        for text in Path(path).read_text().splitlines():
+            if text.startswith("{"):
+                j = json.loads(text)
+        if j is None:
+            raise SystemExit(f"no JSON line in {path}")
+        r, sr = j["roofline"], j.get("step_roofline") or {}
+        lines.append(f"| {label} | {j['ms_per_step']:.4f} | {j['value']:.0f} | `{r.get('kernel', '')}` | {r.get('avg_launch_us', 0):.1f} | "
+                     f"{r['bound']} | {r['achieved']:.0f} {r['unit']} | {r['frac']:.3f} | {sr.get('bound', '')} | {sr.get('frac', 0):.3f} |")
+    if a.note:
+        lines += ["", a.note]
+    Path(a.out).write_text("\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="what", required=True)
-    for name in ("trace", "traffic", "counters"):
+    for name in ("trace", "traffic", "counters", "regimes"):
         p = sub.add_parser(name)
+        p.add_argument("--commit", default="", help="commit the run was made from (default: the current HEAD)")
         p.add_argument("--title", required=True)
         p.add_argument("--cmd", required=True, help="the full command(s) that produced the databases")
         p.add_argument("--out", required=True)
@@ -203,12 +236,16 @@ def main():
             p.add_argument("--workload", required=True)
             p.add_argument("--copy-mib", type=int, default=512)
             p.add_argument("--alg", default="", help="JSON {kernel: algorithmic MiB per launch}")
+        elif name == "regimes":
+            p.add_argument("--line", nargs="+", required=True, help="label=path of a file holding bench.py's JSON line")
         else:
             p.add_argument("--db", nargs="+", required=True)
         if name == "counters":
             p.add_argument("--kernels", default="", help="semicolon-separated short kernel names to keep (default: all of ours)")
     a = ap.parse_args()
-    {"trace": cmd_trace, "traffic": cmd_traffic, "counters": cmd_counters}[a.what](a)
+    global COMMIT_OVERRIDE
+    COMMIT_OVERRIDE = a.commit
+    {"trace": cmd_trace, "traffic": cmd_traffic, "counters": cmd_counters, "regimes": cmd_regimes}[a.what](a)
 
 
 if __name__ == "__main__":

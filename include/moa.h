@@ -435,8 +435,10 @@ int32_t moa_debug_force_attn_kernel(int32_t form);
 /* The same for the Layer Self-Attention (moa_lsa, moa_draft_step): for bf16 with head_dim 128, at most 96 layers, an
  * input width in 64s and an even number of query heads per KV head, projection, attention over the layers and mean
  * run as ONE kernel that keeps the projected rows on the compute unit; other shapes take three kernels with the
- * projected rows in the workspace.  Both give the same bits.  MOA_LSA_KERNEL_SEPARATE forces the three-kernel form;
- * MOA_LSA_KERNEL_FUSED and _AUTO pick the one-kernel form wherever it applies. */
+ * projected rows in the workspace.  Both give the same bits.  MOA_LSA_KERNEL_SEPARATE forces the three-kernel form,
+ * MOA_LSA_KERNEL_FUSED the one-kernel form wherever it applies; left to itself (_AUTO) the library takes the
+ * one-kernel form except for at most 192 rows (T * n_layers) and for more than 1024 workgroups' worth of tokens whose
+ * layer count leaves over a tenth of its last 32-row block empty, where the three kernels measured faster. */
 enum { MOA_LSA_KERNEL_AUTO = 0, MOA_LSA_KERNEL_FUSED = 1, MOA_LSA_KERNEL_SEPARATE = 2 };
 int32_t moa_debug_force_lsa_kernel(int32_t form);
 

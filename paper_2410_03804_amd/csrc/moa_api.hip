@@ -252,13 +252,25 @@ static thread_local bool t_lsa_extra_taken = false;
 // it cannot take still falls back), 2 = always projection, attention and mean as separate kernels
 static std::atomic<int> g_lsa_form{0};
 
-static bool lsa_takes_fused(const moa_shape_t *shape, const void *hs, const void *wq, const void *wk, const void *wv,
-                            const void *abar)
+// Whether a Layer Self-Attention pass over T tokens runs as the one kernel.  Left to itself the library keeps the
+// separate kernels in two corners where they measured faster: a handful of rows (T L <= 192: the weight-streaming
+// projection spreads the weights over every compute unit, the one-kernel form over T x 8 workgroups only -- 28 against
+// 48 us for 5 tokens at the Llama-3-8B shape), and many tokens whose layer count fills its last 32-row block badly
+// (L = 80 in 96 rows: 535 against 492 us for 256 tokens at the Llama-2-70B shape).
+static bool lsa_takes_fused(const moa_shape_t *shape, int64_t T, const void *hs, const void *wq, const void *wk,
+                            const void *wv, const void *abar)
 {
-    if (g_lsa_form.load(std::memory_order_relaxed) == MOA_LSA_KERNEL_SEPARATE) return false;
-    return wq && wk && wv &&
-           lsa_fused_ok(shape->dtype, shape->n_layers, shape->d_lsa_in, shape->lsa_q_heads, shape->lsa_kv_heads,
-                        shape->head_dim, hs, wq, wk, wv, abar);
+    const int form = g_lsa_form.load(std::memory_order_relaxed);
+    if (form == MOA_LSA_KERNEL_SEPARATE) return false;
+    if (!(wq && wk && wv &&
+          lsa_fused_ok(shape->dtype, shape->n_layers, shape->d_lsa_in, shape->lsa_q_heads, shape->lsa_kv_heads,
+                       shape->head_dim, hs, wq, wk, wv, abar)))
+        return false;
+    if (form == MOA_LSA_KERNEL_FUSED) return true;
+    const int64_t L = shape->n_layers, padded = (L + 31) / 32 * 32;
+    if (T * L <= 192) return false;
+    if (10 * padded > 11 * L && T * (shape->lsa_q_heads / 2) > 1024) return false;
+    return true;
 }
 
 static LsaFusedCall lsa_fused_call(const moa_shape_t *shape, const void *hs, int64_t t0, int64_t tc, const void *wq,
@@ -395,7 +407,7 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
     // One kernel for projection, attention over the layers and mean where the shapes allow: no projected row ever
     // reaches memory, so a pass covers a whole output-projection block of tokens; else chunks of LSA_CHUNK tokens
     // whose Q/K/V rows go through the workspace.
-    const bool fused = lsa_takes_fused(shape, hs, wq, wk, wv, wo ? (const void *)b.abar0 : out);
+    const bool fused = lsa_takes_fused(shape, T, hs, wq, wk, wv, wo ? (const void *)b.abar0 : out);
     const int64_t step = fused ? LSA_OBLOCK : LSA_CHUNK;
     for (int64_t t0 = 0; t0 < T; t0 += step) {
         const int64_t tc = (T - t0) < step ? (T - t0) : step;
@@ -1263,7 +1275,7 @@ static int32_t piece_lsa_interleaved(const moa_step_args_t *a, const StepBufs &b
     if (rc) return rc;
     const LsaBufs b = lsa_carve(sh, T, scr, scr_bytes);
     void *abar = a->lsa_wo ? (void *)b.abar0 : a->lsa_out;
-    if (lsa_takes_fused(sh, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar)) {
+    if (lsa_takes_fused(sh, T, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar)) {
         LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
         fc.carry_sum = &sum_pair;
         prof_set_site(S_LSA_FUSED);
@@ -1366,7 +1378,7 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
     // uses the first) and all LSA tokens in one chunk, the two are interleaved; else one after the other.
     int32_t rc;
     const bool one_pass = a->T_lsa <= LSA_CHUNK ||
-                          (a->T_lsa <= LSA_OBLOCK && lsa_takes_fused(a->shape, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->ws));
+                          (a->T_lsa <= LSA_OBLOCK && lsa_takes_fused(a->shape, a->T_lsa, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->ws));
     if (a->T_lsa > 0 && one_pass && a->ws_bytes >= L.total() + L.scratch) {
         rc = piece_lsa_interleaved(a, bf, scr, L.scratch, scr + L.scratch, st);
         if (rc) return rc;
@@ -1460,7 +1472,7 @@ static int32_t two_stream_main(const moa_step_args_t *a, const StepBufs &bf, cha
     if (rc) return rc;
     const LsaBufs b = lsa_carve(sh, T, scr, scr_bytes);
     void *abar = a->lsa_wo ? (void *)b.abar0 : a->lsa_out;
-    const bool fused = T > 0 && T <= LSA_OBLOCK && lsa_takes_fused(sh, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
+    const bool fused = T > 0 && T <= LSA_OBLOCK && lsa_takes_fused(sh, T, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
     if (fused) {
         LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
         fc.leave_room = 1;                   // the largest token tile: fewest workgroups, compute units left to the side branch
@@ -1505,8 +1517,8 @@ static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
     // wait of this or a later step refers to an older step's event.
     int32_t rc = two_stream_side(a, bf, scr_side, L.scratch, ss);
     if (rc) {
-        hipEventRecord(ss->small, side);
-        hipEventRecord(ss->q, side);
+        (void)hipEventRecord(ss->small, side);   // the step already failed with rc; these only keep later waits fresh
+        (void)hipEventRecord(ss->q, side);
     }
     const hipError_t ej = hipEventRecord(ss->join, side);
     if (rc == MOA_OK) rc = two_stream_main(a, bf, scr_main, L.scratch, ss);
