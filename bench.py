@@ -75,6 +75,8 @@ def parse():
     ap.add_argument("--with-sa", action="store_true",
                     help="run the drafter's Self-Attention layer in front of the cross-attention (its output becomes "
                          "the CA queries); not part of the headline step")
+    ap.add_argument("--no-pack", action="store_true",
+                    help="feed the LSA kernel the plain Wq / Wk / Wv instead of the copy packed once into MFMA-operand order")
     ap.add_argument("--no-fold", action="store_true",
                     help="keep the memory's K/V projection a launch of its own instead of folding ca_wk/ca_wv with lsa_wo")
     ap.add_argument("--drafter-blocks", action="store_true",
@@ -315,7 +317,7 @@ def main():
     sets = []
     ws = None
     for w in works:
-        s = DeviceStep(w, n_len_slots=slots, ws=ws, fold=not args.no_fold)
+        s = DeviceStep(w, n_len_slots=slots, ws=ws, fold=not args.no_fold, pack=not args.no_pack)
         ws = s.ws
         sets.append(s)
     torch.cuda.synchronize()

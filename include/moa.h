@@ -111,6 +111,25 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T,
                 const void *wq, const void *wk, const void *wv, const void *wo,
                 void *out, void *ws, size_t ws_bytes, void *stream);
 
+/* The same Layer Self-Attention (Sec. 3.1.1; Alg. 1, LSA_layer_with_mean) with Wq, Wk, Wv rearranged once, at load
+ * time, into the order in which the matrix cores consume them, so that the one-kernel form (see
+ * moa_debug_force_lsa_kernel) reads every weight straight into the register it is used from instead of staging it
+ * in LDS.  Shapes: those that form takes -- bf16, head_dim 128, n_layers <= 96, d_lsa_in >= 128 and a multiple of
+ * 64, an even number of LSA query heads per KV head; others are refused with MOA_ERR_SHAPE.  Results are the bits
+ * moa_lsa gives for the same weights.
+ *   moa_lsa_packed_weight_bytes: size of the packed buffer (host only, launches nothing).
+ *   moa_lsa_pack_weights: wq [H_l*dh, d_in], wk, wv [Hkv_l*dh, d_in] -> packed (device, caller-owned, 16-byte
+ *     aligned, at least that many bytes, else MOA_ERR_WORKSPACE); one launch; layout: per unit of two query heads
+ *     with their key and value head, per wavefront (64 of the unit's 512 rows), per 64 columns, the 16-byte operand
+ *     pieces in lane order.  The plain matrices are not needed afterwards by moa_lsa_packed.
+ *   moa_lsa_packed: moa_lsa with w_packed in place of wq / wk / wv (all other arguments, workspace size and errors
+ *     as there; hs, w_packed and out 16-byte aligned). */
+int32_t moa_lsa_packed_weight_bytes(const moa_shape_t *shape, size_t *bytes_host);
+int32_t moa_lsa_pack_weights(const moa_shape_t *shape, const void *wq, const void *wk, const void *wv,
+                             void *packed, size_t packed_bytes, void *stream);
+int32_t moa_lsa_packed(const moa_shape_t *shape, const void *hs, int64_t T, const void *w_packed,
+                       const void *wo, void *out, void *ws, size_t ws_bytes, void *stream);
+
 /* Cross-attention memory append (Sec. 3.1.2: CA keys and values come from the output of
  * LSA; Alg. 1, kv <- (kv, kv')).  Rows tok_off[b] .. tok_off[b+1]-1 of mem_new belong to
  * sequence b (tok_off is a device array, tok_off[0] = 0, non-decreasing, tok_off[B] <= T;
@@ -400,6 +419,10 @@ typedef struct {
      * keys / values straight from LSA's mean-folded heads in the launch that also applies lsa_wo
      * ((a Wo^T) Wk^T = a (Wk Wo)^T, exact in real arithmetic); lsa_out is still written.            */
     const void *ca_wk_lsa_wo, *ca_wv_lsa_wo;
+    /* optional: lsa_wq / lsa_wk / lsa_wv packed by moa_lsa_pack_weights.  The step then runs the LSA's one-kernel
+     * form from the packed copy wherever it runs that form at all; lsa_wq / lsa_wk / lsa_wv are still required
+     * (the other form reads them).  Ignored for shapes that cannot be packed.                        */
+    const void *lsa_w_packed;
 } moa_step_args_t;
 
 int32_t moa_draft_step(const moa_step_args_t *args);
@@ -435,7 +458,8 @@ int32_t moa_debug_force_attn_kernel(int32_t form);
 /* The same for the Layer Self-Attention (moa_lsa, moa_draft_step): for bf16 with head_dim 128, at most 96 layers, an
  * input width in 64s and an even number of query heads per KV head, projection, attention over the layers and mean
  * run as ONE kernel that keeps the projected rows on the compute unit; other shapes take three kernels with the
- * projected rows in the workspace.  Both give the same bits.  MOA_LSA_KERNEL_SEPARATE forces the three-kernel form,
+ * projected rows in the workspace.  Both give the same bits where the three-kernel form also projects on the matrix
+ * cores (d_lsa_in a multiple of 128), and agree within rounding otherwise.  MOA_LSA_KERNEL_SEPARATE forces the three-kernel form,
  * MOA_LSA_KERNEL_FUSED the one-kernel form wherever it applies; left to itself (_AUTO) the library takes the
  * one-kernel form except for at most 192 rows (T * n_layers) and for more than 1024 workgroups' worth of tokens whose
  * layer count leaves over a tenth of its last 32-row block empty, where the three kernels measured faster. */

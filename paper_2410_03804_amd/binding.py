@@ -62,6 +62,7 @@ class _StepArgs(C.Structure):
         ("sa_kcache", C.c_void_p), ("sa_vcache", C.c_void_p), ("sa_P_cap", C.c_int32),
         ("sa_k_draft", C.c_void_p), ("sa_v_draft", C.c_void_p), ("sa_out", C.c_void_p),
         ("ca_wk_lsa_wo", C.c_void_p), ("ca_wv_lsa_wo", C.c_void_p),
+        ("lsa_w_packed", C.c_void_p),
     ]
 
 
@@ -70,7 +71,7 @@ SCHED_GROUPED, SCHED_TWO_STREAM, SCHED_SEQUENTIAL = 0, 1, 2
 _SYMBOLS = ["moa_status_str", "moa_last_error", "moa_workspace_bytes", "moa_tree_build", "moa_tree_accept",
             "moa_lsa", "moa_ca_kv_append", "moa_cross_attn_draft", "moa_tree_verify_attn", "moa_draft_step",
             "moa_self_attn_draft", "moa_tli_workspace_bytes", "moa_tli_decoder_layer", "moa_tree_expand_level", "moa_tree_finalize", "moa_topk_logprob", "moa_topk_workspace_bytes", "moa_lm_head_workspace_bytes", "moa_lm_head_argmax", "moa_msg_pack_tree", "moa_msg_unpack_tree", "moa_msg_accept_bytes", "moa_msg_pack_accept",
-            "moa_msg_unpack_accept", "moa_msg_gzip_bound", "moa_msg_gzip", "moa_msg_gunzip", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma",
+            "moa_msg_unpack_accept", "moa_msg_gzip_bound", "moa_msg_gzip", "moa_msg_gunzip", "moa_linear_workspace_bytes", "moa_linear", "moa_fold_projection", "moa_lsa_packed_weight_bytes", "moa_lsa_pack_weights", "moa_lsa_packed", "moa_mlp_block_workspace_bytes", "moa_mlp_block", "moa_rmsnorm", "moa_profile_enable", "moa_profile_sample_every", "moa_profile_collect", "moa_profile_kernel_name", "moa_profile_site_name", "moa_probe_read", "moa_probe_mfma",
             "moa_debug_force_attn_kernel", "moa_debug_force_lsa_kernel", "moa_tree_verify_attn_noalloc"]
 
 _lib.moa_status_str.restype = C.c_char_p
@@ -82,6 +83,9 @@ _lib.moa_workspace_bytes.argtypes = [C.POINTER(Shape), _i32, _i32, _i32, _i64, C
 _lib.moa_tree_build.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.moa_tree_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.moa_lsa.argtypes = [C.POINTER(Shape), _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moa_lsa_packed_weight_bytes.argtypes = [C.POINTER(Shape), C.POINTER(_sz)]
+_lib.moa_lsa_pack_weights.argtypes = [C.POINTER(Shape), _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moa_lsa_packed.argtypes = [C.POINTER(Shape), _vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moa_ca_kv_append.argtypes = [C.POINTER(Shape), _vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
 _lib.moa_cross_attn_draft.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
 _lib.moa_tree_verify_attn.argtypes = [C.POINTER(Shape), _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp,
@@ -222,6 +226,36 @@ def lsa(shape: Shape, hs, wq, wk, wv, wo, out, ws, stream=None):
     _check(_lib.moa_lsa(C.byref(shape), _dev(hs, dt, T * L * d_in, "hs"), T,
                         _dev(wq, dt, eq * d_in, "wq"), _dev(wk, dt, ekv * d_in, "wk"), _dev(wv, dt, ekv * d_in, "wv"),
                         _dev(wo, dt, eq * eq, "wo"), _dev(out, dt, T * eq, "out"), wsp, wsb, _stream(stream)))
+
+
+def lsa_packed_weight_bytes(shape: Shape) -> int:
+    n = _sz(0)
+    _check(_lib.moa_lsa_packed_weight_bytes(C.byref(shape), C.byref(n)))
+    return int(n.value)
+
+
+def lsa_pack_weights(shape: Shape, wq, wk, wv, stream=None):
+    """Wq / Wk / Wv in the order the one-kernel LSA consumes them (done once, at load time); returns the packed tensor."""
+    dt = _TORCH_DTYPE[shape.dtype]
+    d_in, dh = shape.d_lsa_in, shape.head_dim
+    eq, ekv = shape.lsa_q_heads * dh, shape.lsa_kv_heads * dh
+    nbytes = lsa_packed_weight_bytes(shape)
+    packed = torch.empty(nbytes // 2, dtype=dt, device=wq.device)
+    _check(_lib.moa_lsa_pack_weights(C.byref(shape), _dev(wq, dt, eq * d_in, "wq"), _dev(wk, dt, ekv * d_in, "wk"),
+                                     _dev(wv, dt, ekv * d_in, "wv"), _dev(packed, dt, nbytes // 2, "packed"), nbytes,
+                                     _stream(stream)))
+    return packed
+
+
+def lsa_packed(shape: Shape, hs, w_packed, wo, out, ws, stream=None):
+    dt = _TORCH_DTYPE[shape.dtype]
+    T = hs.shape[0]
+    L, d_in, dh = shape.n_layers, shape.d_lsa_in, shape.head_dim
+    eq = shape.lsa_q_heads * dh
+    wsp, wsb = _ws(ws)
+    _check(_lib.moa_lsa_packed(C.byref(shape), _dev(hs, dt, T * L * d_in, "hs"), T,
+                               _dev(w_packed, dt, lsa_packed_weight_bytes(shape) // 2, "w_packed"),
+                               _dev(wo, dt, eq * eq, "wo"), _dev(out, dt, T * eq, "out"), wsp, wsb, _stream(stream)))
 
 
 def ca_kv_append(shape: Shape, mem_new, tok_off, wk, wv, kc, vc, ca_len, P_cap, dev_status=None, ws=None, stream=None):
@@ -519,14 +553,15 @@ def _ptr_array(tensors, dtype, numel, name):
 
 def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len,
                ca_P_cap, ca_xq, ca_out, v_x, v_w, v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, P_cap,
-               tok, tgt, path, n_path, bonus, ws, dev_status=None, schedule=0, sa=None, folded=None):
+               tok, tgt, path, n_path, bonus, ws, dev_status=None, schedule=0, sa=None, folded=None, lsa_w_packed=None):
     """Marshal (and size-check) the arguments of moa_draft_step once; the returned plan can be run many times.
     lsa_w = dict(wq, wk, wv, wo); ca_w = dict(wq, wo, wk, wv); v_w = list (one per verified layer) of
     dict(wq, wk, wv, wo); v_* = lists of per-layer tensors.  The plan keeps the tensors alive.
     sa (optional) = dict(shape, emb, w=dict(wq, wk, wv, wo), kcache, vcache, P_cap, k_draft, v_draft, out): the
     Self-Attention layer in front of the cross-attention (ca_xq may then be None).
     folded (optional) = (ca_wk @ lsa_wo, ca_wv @ lsa_wo) from fold_projection: the memory append then shares the LSA
-    output projection's launch."""
+    output projection's launch.
+    lsa_w_packed (optional) = lsa_pack_weights(shape, wq, wk, wv) of the same LSA weights."""
     dt, i32 = _TORCH_DTYPE[shape.dtype], torch.int32
     B, M = parent.shape
     Mq = ca_xq.shape[1]
@@ -586,6 +621,8 @@ def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out
     if folded is not None:
         a.ca_wk_lsa_wo = _dev(folded[0], dt, ekv * eq, "ca_wk lsa_wo")
         a.ca_wv_lsa_wo = _dev(folded[1], dt, ekv * eq, "ca_wv lsa_wo")
+    if lsa_w_packed is not None:
+        a.lsa_w_packed = _dev(lsa_w_packed, dt, lsa_packed_weight_bytes(shape) // 2, "lsa_w_packed")
     if sa is not None:
         ssh = sa["shape"]
         ekv_s = ssh.n_kv_heads * dh
@@ -602,7 +639,7 @@ def draft_step_plan(shape: Shape, *, parent, mask, depth, lsa_hs, lsa_w, lsa_out
         a.sa_v_draft = _dev(sa["v_draft"], dt, B * ekv_s * M, "sa v_draft")
         a.sa_out = _dev(sa["out"], dt, B * M * d, "sa out")
         keep = keep + [ssh]
-    tensors = [sa, folded, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
+    tensors = [sa, folded, lsa_w_packed, parent, mask, depth, lsa_hs, lsa_w, lsa_out, tok_off, ca_w, ca_k, ca_v, ca_len, ca_xq, ca_out, v_x, v_w,
                v_kcache, v_vcache, v_out, v_ktree, v_vtree, prefix_len, tok, tgt, path, n_path, bonus, ws, dev_status]
     return StepPlan(a, shape, keep, tensors)
 

@@ -274,9 +274,10 @@ static bool lsa_takes_fused(const moa_shape_t *shape, int64_t T, const void *hs,
 }
 
 static LsaFusedCall lsa_fused_call(const moa_shape_t *shape, const void *hs, int64_t t0, int64_t tc, const void *wq,
-                                   const void *wk, const void *wv, void *abar)
+                                   const void *wk, const void *wv, void *abar, const void *w_packed = nullptr)
 {
     LsaFusedCall c = {};
+    c.w_packed = w_packed;
     c.dtype = shape->dtype;
     c.hs = (const char *)hs + (size_t)t0 * shape->n_layers * shape->d_lsa_in * esize(shape->dtype);
     c.wq = wq;
@@ -394,11 +395,11 @@ static LinArgs lsa_oproj_args(const moa_shape_t *shape, int64_t b0, int64_t rows
 
 extern "C" {
 
-int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk,
-                const void *wv, const void *wo, void *out, void *ws, size_t ws_bytes, void *stream)
+// the LSA pass behind moa_lsa and moa_lsa_packed (arguments checked by the caller); with w_packed the one-kernel
+// form runs whatever the token count, since the other form reads the plain matrices
+static int32_t lsa_run(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk, const void *wv,
+                       const void *w_packed, const void *wo, void *out, void *ws, size_t ws_bytes, void *stream)
 {
-    int32_t rc = lsa_check(shape, hs, T, wq, wk, wv, out, ws, ws_bytes);
-    if (rc || T == 0) return rc;
     const int dt = shape->dtype, eq = shape->lsa_q_heads * shape->head_dim;
     hipStream_t st = (hipStream_t)stream;
     const size_t es = esize(dt);
@@ -407,7 +408,7 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
     // One kernel for projection, attention over the layers and mean where the shapes allow: no projected row ever
     // reaches memory, so a pass covers a whole output-projection block of tokens; else chunks of LSA_CHUNK tokens
     // whose Q/K/V rows go through the workspace.
-    const bool fused = lsa_takes_fused(shape, T, hs, wq, wk, wv, wo ? (const void *)b.abar0 : out);
+    const bool fused = w_packed || lsa_takes_fused(shape, T, hs, wq, wk, wv, wo ? (const void *)b.abar0 : out);
     const int64_t step = fused ? LSA_OBLOCK : LSA_CHUNK;
     for (int64_t t0 = 0; t0 < T; t0 += step) {
         const int64_t tc = (T - t0) < step ? (T - t0) : step;
@@ -415,7 +416,7 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
         char *abar = wo ? b.abar0 + (size_t)(t0 - b0) * eq * es : (char *)out + (size_t)t0 * eq * es;
         if (fused) {
             prof_set_site(S_LSA_FUSED);
-            MOA_TRY_HIP(launch_lsa_fused(lsa_fused_call(shape, hs, t0, tc, wq, wk, wv, abar), st), "lsa: fused kernel");
+            MOA_TRY_HIP(launch_lsa_fused(lsa_fused_call(shape, hs, t0, tc, wq, wk, wv, abar, w_packed), st), "lsa: fused kernel");
         } else {
             LinArgs la;
             LsaAttnArgs aa;
@@ -435,6 +436,65 @@ int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void 
         }
     }
     return MOA_OK;
+}
+
+int32_t moa_lsa(const moa_shape_t *shape, const void *hs, int64_t T, const void *wq, const void *wk,
+                const void *wv, const void *wo, void *out, void *ws, size_t ws_bytes, void *stream)
+{
+    int32_t rc = lsa_check(shape, hs, T, wq, wk, wv, out, ws, ws_bytes);
+    if (rc || T == 0) return rc;
+    return lsa_run(shape, hs, T, wq, wk, wv, nullptr, wo, out, ws, ws_bytes, stream);
+}
+
+// shapes whose LSA weights can be packed: exactly those the one-kernel form takes
+static int32_t lsa_pack_check(const moa_shape_t *shape, const char *who)
+{
+    int32_t rc = check_shape(shape, true);
+    if (rc) return rc;
+    if (!lsa_fused_shape_ok(shape->dtype, shape->n_layers, shape->d_lsa_in, shape->lsa_q_heads, shape->lsa_kv_heads, shape->head_dim))
+        return fail(MOA_ERR_SHAPE, "%s: packed LSA weights need bf16, head_dim 128, n_layers <= 96, d_lsa_in >= 128 in 64s and "
+                                   "an even number of query heads per KV head", who);
+    return MOA_OK;
+}
+
+int32_t moa_lsa_packed_weight_bytes(const moa_shape_t *shape, size_t *bytes_host)
+{
+    if (!bytes_host) return fail(MOA_ERR_NULL, "lsa_packed_weight_bytes: bytes_host is NULL");
+    int32_t rc = lsa_pack_check(shape, "lsa_packed_weight_bytes");
+    if (rc) return rc;
+    *bytes_host = lsa_packed_weight_bytes(shape->d_lsa_in, shape->lsa_q_heads, shape->lsa_kv_heads, shape->head_dim);
+    return MOA_OK;
+}
+
+int32_t moa_lsa_pack_weights(const moa_shape_t *shape, const void *wq, const void *wk, const void *wv, void *packed,
+                             size_t packed_bytes, void *stream)
+{
+    int32_t rc = lsa_pack_check(shape, "lsa_pack_weights");
+    if (rc) return rc;
+    if (!wq || !wk || !wv || !packed) return fail(MOA_ERR_NULL, "lsa_pack_weights: NULL pointer");
+    if ((((uintptr_t)wq) | ((uintptr_t)wk) | ((uintptr_t)wv) | ((uintptr_t)packed)) & 15)
+        return fail(MOA_ERR_SHAPE, "lsa_pack_weights: pointers must be 16-byte aligned");
+    const size_t need = lsa_packed_weight_bytes(shape->d_lsa_in, shape->lsa_q_heads, shape->lsa_kv_heads, shape->head_dim);
+    if (packed_bytes < need) return fail(MOA_ERR_WORKSPACE, "lsa_pack_weights: packed buffer has %zu bytes, %zu needed", packed_bytes, need);
+    prof_set_site(S_LSA_FUSED);
+    MOA_TRY_HIP(launch_lsa_pack_weights(wq, wk, wv, packed, shape->d_lsa_in, shape->lsa_q_heads, shape->lsa_kv_heads, (hipStream_t)stream),
+                "lsa_pack_weights");
+    return MOA_OK;
+}
+
+int32_t moa_lsa_packed(const moa_shape_t *shape, const void *hs, int64_t T, const void *w_packed, const void *wo,
+                       void *out, void *ws, size_t ws_bytes, void *stream)
+{
+    int32_t rc = lsa_pack_check(shape, "lsa_packed");
+    if (rc) return rc;
+    if (!hs || !out || !w_packed) return fail(MOA_ERR_NULL, "lsa_packed: hs / w_packed / out is NULL");
+    if (T < 0) return fail(MOA_ERR_SHAPE, "lsa_packed: T=%lld", (long long)T);
+    if ((((uintptr_t)hs) | ((uintptr_t)w_packed) | ((uintptr_t)out)) & 15)
+        return fail(MOA_ERR_SHAPE, "lsa_packed: pointers must be 16-byte aligned");
+    if (T == 0) return MOA_OK;
+    rc = check_ws(ws, ws_bytes, lsa_ws_bytes(shape, T));
+    if (rc) return rc;
+    return lsa_run(shape, hs, T, nullptr, nullptr, nullptr, w_packed, wo, out, ws, ws_bytes, stream);
 }
 
 int32_t moa_debug_force_lsa_kernel(int32_t form)
@@ -1061,12 +1121,28 @@ int32_t moa_linear(int32_t dtype, const void *x, int64_t R, int32_t K, const voi
     return MOA_OK;
 }
 
+// The packed copy of the LSA weights a step may use: only where the one-kernel form runs anyway (the other form
+// reads the plain matrices), and only if it is aligned like every other operand of that kernel.
+static const void *step_lsa_packed(const moa_step_args_t *a)
+{
+    if (!a->lsa_w_packed || (((uintptr_t)a->lsa_w_packed) & 15)) return nullptr;
+    return lsa_takes_fused(a->shape, a->T_lsa, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->ws) ? a->lsa_w_packed : nullptr;
+}
+
+// moa_lsa for a step: the same checks, and the packed weights where they apply
+static int32_t step_lsa(const moa_step_args_t *a, void *ws, size_t ws_bytes, void *stream)
+{
+    int32_t rc = lsa_check(a->shape, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_out, ws, ws_bytes);
+    if (rc || a->T_lsa == 0) return rc;
+    return lsa_run(a->shape, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, step_lsa_packed(a), a->lsa_wo, a->lsa_out,
+                   ws, ws_bytes, stream);
+}
+
 static int32_t draft_step_stages(const moa_step_args_t *a)
 {
     int32_t rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, a->stream);
     if (rc) return rc;
-    rc = moa_lsa(a->shape, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, a->ws,
-                 a->ws_bytes, a->stream);
+    rc = step_lsa(a, a->ws, a->ws_bytes, a->stream);
     if (rc) return rc;
     const int d_mem = a->shape->lsa_q_heads * a->shape->head_dim;
     rc = moa_ca_kv_append(a->shape, a->lsa_out, a->T_lsa, d_mem, a->tok_off, a->B, a->ca_wk, a->ca_wv, a->ca_k,
@@ -1248,7 +1324,7 @@ static int32_t piece_lsa_append(const moa_step_args_t *a, const StepBufs &bf, vo
         t_lsa_nextra = 2;
     }
     t_lsa_extra_taken = false;
-    int32_t rc = moa_lsa(a->shape, a->lsa_hs, a->T_lsa, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_wo, a->lsa_out, scr, scr_bytes, st);
+    int32_t rc = step_lsa(a, scr, scr_bytes, st);
     t_lsa_extra = nullptr;
     t_lsa_nextra = 0;
     if (rc || a->T_lsa <= 0 || (t_lsa_extra_taken && !g_dry)) return rc;
@@ -1276,7 +1352,7 @@ static int32_t piece_lsa_interleaved(const moa_step_args_t *a, const StepBufs &b
     const LsaBufs b = lsa_carve(sh, T, scr, scr_bytes);
     void *abar = a->lsa_wo ? (void *)b.abar0 : a->lsa_out;
     if (lsa_takes_fused(sh, T, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar)) {
-        LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
+        LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar, step_lsa_packed(a));
         fc.carry_sum = &sum_pair;
         prof_set_site(S_LSA_FUSED);
         MOA_TRY_HIP(launch_lsa_fused(fc, st), "lsa: fused kernel");
@@ -1474,7 +1550,7 @@ static int32_t two_stream_main(const moa_step_args_t *a, const StepBufs &bf, cha
     void *abar = a->lsa_wo ? (void *)b.abar0 : a->lsa_out;
     const bool fused = T > 0 && T <= LSA_OBLOCK && lsa_takes_fused(sh, T, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
     if (fused) {
-        LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
+        LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar, step_lsa_packed(a));
         fc.leave_room = 1;                   // the largest token tile: fewest workgroups, compute units left to the side branch
         prof_set_site(S_LSA_FUSED);
         MOA_TRY_HIP(launch_lsa_fused(fc, main), "lsa: fused kernel");

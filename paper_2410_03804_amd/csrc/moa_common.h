@@ -95,7 +95,7 @@ enum KernelId {
     K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_SPLITK, K_LIN_REDUCE, K_LIN_TILED, K_SCATTER,
     K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_LSA_ATTN_MFMA, K_STEP_SMALL, K_ATTN_FUSED, K_PROBE_READ, K_PROBE_MFMA,
     K_RMSNORM, K_ROPE, K_SWIGLU, K_ADD_OUT, K_TREE_EXPAND, K_TREE_FINALIZE, K_TOPK_LOGPROB,
-    K_LM_HEAD, K_LM_HEAD_REDUCE, K_TOPK_MERGE, K_MSG_TREE, K_MSG_ACCEPT, K_LIN_SPLITK_CHUNKED, K_LSA_FUSED, K_COUNT
+    K_LM_HEAD, K_LM_HEAD_REDUCE, K_TOPK_MERGE, K_MSG_TREE, K_MSG_ACCEPT, K_LIN_SPLITK_CHUNKED, K_LSA_FUSED, K_LSA_FUSED_PK, K_LSA_PACK, K_COUNT
 };
 enum SiteId {
     S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,
@@ -270,6 +270,7 @@ hipError_t launch_add_out(int dtype, const float *h, const void *t, int64_t n, v
 struct LsaFusedCall {
     int dtype;
     const void *hs, *wq, *wk, *wv;
+    const void *w_packed;    // wq / wk / wv in the order launch_lsa_pack_weights writes, or NULL; when given, wq / wk / wv are not read
     void *abar;
     int64_t T;
     int L, d_in, Hq, Hkv, dh;
@@ -281,7 +282,12 @@ struct LsaFusedCall {
 // shapes and alignments the kernel takes (bf16, head_dim 128, L <= 96, d_in in 64s, an even number of query heads per KV head)
 bool lsa_fused_ok(int dtype, int L, int d_in, int Hq, int Hkv, int dh, const void *hs, const void *wq, const void *wk,
                   const void *wv, const void *abar);
+bool lsa_fused_shape_ok(int dtype, int L, int d_in, int Hq, int Hkv, int dh);
 hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream);
+// the weights of those shapes rearranged once into MFMA-operand order, for the form of the kernel that keeps them in registers
+size_t lsa_packed_weight_bytes(int d_in, int Hq, int Hkv, int dh);
+hipError_t launch_lsa_pack_weights(const void *wq, const void *wk, const void *wv, void *out, int d_in, int Hq, int Hkv,
+                                   hipStream_t stream);
 
 // ---- LSA attention over the layer axis (LsaAttnArgs is declared above, beside the projections that can carry it)
 size_t lsa_attn_lds_bytes(int dtype, int L, int dh);

@@ -41,6 +41,7 @@ typedef __attribute__((address_space(1))) const void global_void_t;
 struct LsaFusedArgs {
     const bf16_t *hs;              // [T, L, d_in]
     const bf16_t *wq, *wk, *wv;    // [Hq*dh, d_in], [Hkv*dh, d_in] x 2
+    const bf16_t *wpk;             // the same weights in MFMA-operand order (k_lsa_pack_weights), or NULL
     bf16_t *abar;                  // [T, Hq*dh]
     int64_t T;
     int L, d_in, Hq, Hkv;
@@ -68,139 +69,25 @@ struct LsaFusedGeom {
     static constexpr size_t loop_bytes = w_bytes + x_bytes;
     static constexpr size_t epi_bytes = tile_bytes + pbar_bytes;
     static constexpr size_t bytes = loop_bytes > epi_bytes ? loop_bytes : epi_bytes;
+    // the form that takes packed weights keeps them in registers: only a two-stage activation ring is left in LDS
+    static constexpr int WS = RB <= 64 ? 4 : 2;  // weight tiles held in registers per wavefront (what the registers left by the accumulators hold)
+    static constexpr int UN = 8;                 // tile steps per trip of the tile loop (a multiple of WS)
+    static constexpr size_t pk_loop_bytes = (size_t)2 * RB * BK * sizeof(bf16_t);
+    static constexpr size_t pk_bytes = pk_loop_bytes > epi_bytes ? pk_loop_bytes : epi_bytes;
 };
 
-template <int DH, int NB, int TT>
-__global__ __launch_bounds__(512) void k_lsa_fused(LsaFusedArgs a)
+// Second half of both kernels below: the accumulators of a workgroup's [RB x 4 dh] projection tile (acc[i][j][v]:
+// feature wave FW + 32 i + 8 (v / 4) + 4 half + v % 4, row 32 j + lane % 32) are rounded to the storage type and
+// parked in LDS, then one wavefront per (token of the tile, query head) runs the attention over the layer axis and the
+// mean.  Called by all 512 threads; `sm` is the workgroup's whole LDS, free to reuse after the barrier in here.
+template <int DH, int NB, int TT, typename Acc>
+__device__ __forceinline__ void lsa_fused_epilogue(Acc &acc, const LsaFusedArgs &a, bf16_t *sm, int64_t tile, int g, int part)
 {
     using Gm = LsaFusedGeom<DH, NB, TT>;
-    constexpr int FW = Gm::FW, RB = Gm::RB, BK = Gm::BK, XS = Gm::XS, TLD = Gm::TLD;
-    constexpr int WFB = FW / 32;                 // 32-feature blocks per wavefront
-    constexpr int NRB = RB / 32;                 // 32-row blocks
-    constexpr int NWI = FW / 8;                  // weight-tile load instructions per wavefront (8 rows of 128 B each)
-    constexpr int NXI = (RB / 8 + 7) / 8;        // activation-tile load instructions per wavefront
-    constexpr int XD = XS - 1;                   // activation tiles requested ahead
-    extern __shared__ __attribute__((aligned(16))) bf16_t sm[];
-
-    if ((int)blockIdx.x < a.lead_blocks) {       // the first workgroups of the grid carry work of other calls
-        if ((int)blockIdx.x < a.small_lead) {
-            if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
-                step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)sm, (int32_t *)sm + MOA_MAX_TREE);
-        } else {
-            const int blk = 2 * ((int)blockIdx.x - a.small_lead) + (int)(threadIdx.x >> 8);
-            if (blk < a.red_blocks) splitk_reduce_block(a.red, blk, (int)(threadIdx.x & 255));
-        }
-        return;
-    }
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: an XCD keeps the weight slices of its
-    // units (2 MB each at the Llama-3-8B shape) and every token tile's activations pass through it once.
-    const int bx = (int)blockIdx.x - a.lead_blocks;
-    const int xcd = bx & 7, slot = bx >> 3;
-    const int unit = xcd * a.units_per_xcd + slot % a.units_per_xcd;
-    const int64_t tile = slot / a.units_per_xcd;
-    if (unit >= a.units) return;                 // the whole workgroup leaves before any barrier
-    const int g = unit / a.parts, part = unit - g * a.parts;
-    const int G = a.Hq / a.Hkv, L = a.L, K = a.d_in;
-
+    constexpr int FW = Gm::FW, RB = Gm::RB, TLD = Gm::TLD;
+    constexpr int WFB = FW / 32, NRB = RB / 32;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-    const int lrow = lane >> 3, lpos = lane & 7;
-
-    f32x16 acc[WFB][NRB];
-#pragma unroll
-    for (int i = 0; i < WFB; ++i)
-#pragma unroll
-        for (int j = 0; j < NRB; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-    const int nk = K / BK;                       // >= 2 (checked on the host)
-
-    // this wavefront's FW feature rows of the weight tile: inside one of Wq (two heads), Wk, Wv
-    const int which = wave * FW / DH;
-    const bf16_t *wm = which < 2 ? a.wq + (int64_t)((g * G + 2 * part + which) * DH + wave * FW % DH) * K
-                                 : (which == 2 ? a.wk : a.wv) + (int64_t)(g * DH + wave * FW % DH) * K;
-    const bf16_t *wsrc[NWI];
-#pragma unroll
-    for (int i = 0; i < NWI; ++i) {
-        const int row = 8 * i + lrow;
-        wsrc[i] = wm + (int64_t)row * K + 8 * (lpos ^ ((row >> 1) & 7));
-    }
-    // its share of the activation tile: instruction xi covers tile rows 8 xi .. 8 xi + 7 (a row past the tokens or the
-    // layers repeats a valid one; such rows are masked as keys and dropped as queries)
-    const bf16_t *xsrc[NXI];
-    int xrow0[NXI];
-#pragma unroll
-    for (int n = 0; n < NXI; ++n) {
-        int xi = wave + 8 * n;
-        if (xi > RB / 8 - 1) xi = RB / 8 - 1;    // a spare instruction repeats the last one (same bytes to the same place)
-        xrow0[n] = 8 * xi;
-        const int s = 8 * xi + lrow;
-        int64_t tok = tile * TT + s / (32 * NB);
-        int lay = s % (32 * NB);
-        if (tok > a.T - 1) tok = a.T - 1;
-        if (lay > L - 1) lay = L - 1;
-        xsrc[n] = a.hs + (tok * L + lay) * (int64_t)K + 8 * (lpos ^ ((s >> 1) & 7));
-    }
-    bf16_t *wl = sm + (size_t)wave * 2 * FW * BK;                 // this wavefront's ring: [2][FW][BK]
-    bf16_t *xl = sm + (size_t)8 * 2 * FW * BK;                    // [XS][RB][BK]
-    auto issue_w = [&](int kt) {
-        bf16_t *dst = wl + (kt & 1) * FW * BK;
-#pragma unroll
-        for (int i = 0; i < NWI; ++i)
-            __builtin_amdgcn_global_load_lds((global_void_t *)(wsrc[i] + (int64_t)kt * BK), (lds_void_t *)(dst + 8 * i * BK), 16, 0, 0);
-    };
-    auto issue_x = [&](int kt) {
-        bf16_t *dst = xl + (kt % XS) * RB * BK;
-#pragma unroll
-        for (int n = 0; n < NXI; ++n)
-            __builtin_amdgcn_global_load_lds((global_void_t *)(xsrc[n] + (int64_t)kt * BK), (lds_void_t *)(dst + xrow0[n] * BK), 16, 0, 0);
-    };
-
-    // Requests are issued in the order X(0) W(0) X(1) W(1) (W(0) X(0) W(1) with a two-stage activation ring), then per
-    // tile kt: X(kt+XD) W(kt+2), and complete in that order (all of them go straight to LDS).  At the top of tile kt,
-    // X(kt) and W(kt) must have landed; what was requested after the later of the two is X(kt+1) W(kt+1) (only
-    // W(kt+1) with the two-stage ring), and nothing in the last round.
-    if (XD >= 2) issue_x(0);
-    issue_w(0);
-    issue_x(XD >= 2 ? 1 : 0);
-    issue_w(1);
-    constexpr int PENDING = XD >= 2 ? NXI + NWI : NWI;
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-        const bf16_t *wb = wl + (kt & 1) * FW * BK;
-        const bf16_t *xb = xl + (kt % XS) * RB * BK;
-        // The four k-steps of a tile are software-pipelined: the fragments of step ks+1 are requested from LDS before
-        // the MFMAs of step ks are issued, so LDS reads and matrix work of one wavefront overlap.  Once the last
-        // step's fragments have been read, the ring places this tile occupied are free and are refilled.
-        auto read_frags = [&](int ks, bf16x8 (&fa)[WFB], bf16x8 (&fb)[NRB]) {
-#pragma unroll
-            for (int i = 0; i < WFB; ++i) {
-                const int row = 32 * i + l32;
-                fa[i] = *(const bf16x8 *)&wb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
-            }
-#pragma unroll
-            for (int j = 0; j < NRB; ++j) {
-                const int row = 32 * j + l32;
-                fb[j] = *(const bf16x8 *)&xb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
-            }
-        };
-        bf16x8 af[2][WFB], bfr[2][NRB];
-        read_frags(0, af[0], bfr[0]);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks + 1 < BK / 16) read_frags(ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
-            if (ks == BK / 16 - 1) {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                if (kt + XD < nk) issue_x(kt + XD);
-                if (kt + 2 < nk) issue_w(kt + 2);
-            }
-#pragma unroll
-            for (int i = 0; i < WFB; ++i)
-#pragma unroll
-                for (int j = 0; j < NRB; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-        }
-    }
+    const int G = a.Hq / a.Hkv, L = a.L;
 
     // park Q | Q' | K | V of the RB rows in LDS, rounded to the storage type
     __syncthreads();                             // every wavefront is done with the rings
@@ -330,15 +217,316 @@ __global__ __launch_bounds__(512) void k_lsa_fused(LsaFusedArgs a)
     }
 }
 
+template <int DH, int NB, int TT>
+__global__ __launch_bounds__(512) void k_lsa_fused(LsaFusedArgs a)
+{
+    using Gm = LsaFusedGeom<DH, NB, TT>;
+    constexpr int FW = Gm::FW, RB = Gm::RB, BK = Gm::BK, XS = Gm::XS;
+    constexpr int WFB = FW / 32;                 // 32-feature blocks per wavefront
+    constexpr int NRB = RB / 32;                 // 32-row blocks
+    constexpr int NWI = FW / 8;                  // weight-tile load instructions per wavefront (8 rows of 128 B each)
+    constexpr int NXI = (RB / 8 + 7) / 8;        // activation-tile load instructions per wavefront
+    constexpr int XD = XS - 1;                   // activation tiles requested ahead
+    extern __shared__ __attribute__((aligned(16))) bf16_t sm[];
+
+    if ((int)blockIdx.x < a.lead_blocks) {       // the first workgroups of the grid carry work of other calls
+        if ((int)blockIdx.x < a.small_lead) {
+            if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
+                step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)sm, (int32_t *)sm + MOA_MAX_TREE);
+        } else {
+            const int blk = 2 * ((int)blockIdx.x - a.small_lead) + (int)(threadIdx.x >> 8);
+            if (blk < a.red_blocks) splitk_reduce_block(a.red, blk, (int)(threadIdx.x & 255));
+        }
+        return;
+    }
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: an XCD keeps the weight slices of its
+    // units (2 MB each at the Llama-3-8B shape) and every token tile's activations pass through it once.
+    const int bx = (int)blockIdx.x - a.lead_blocks;
+    const int xcd = bx & 7, slot = bx >> 3;
+    const int unit = xcd * a.units_per_xcd + slot % a.units_per_xcd;
+    const int64_t tile = slot / a.units_per_xcd;
+    if (unit >= a.units) return;                 // the whole workgroup leaves before any barrier
+    const int g = unit / a.parts, part = unit - g * a.parts;
+    const int G = a.Hq / a.Hkv, L = a.L, K = a.d_in;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int lrow = lane >> 3, lpos = lane & 7;
+
+    f32x16 acc[WFB][NRB];
+#pragma unroll
+    for (int i = 0; i < WFB; ++i)
+#pragma unroll
+        for (int j = 0; j < NRB; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    const int nk = K / BK;                       // >= 2 (checked on the host)
+
+    // this wavefront's FW feature rows of the weight tile: inside one of Wq (two heads), Wk, Wv
+    const int which = wave * FW / DH;
+    const bf16_t *wm = which < 2 ? a.wq + (int64_t)((g * G + 2 * part + which) * DH + wave * FW % DH) * K
+                                 : (which == 2 ? a.wk : a.wv) + (int64_t)(g * DH + wave * FW % DH) * K;
+    const bf16_t *wsrc[NWI];
+#pragma unroll
+    for (int i = 0; i < NWI; ++i) {
+        const int row = 8 * i + lrow;
+        wsrc[i] = wm + (int64_t)row * K + 8 * (lpos ^ ((row >> 1) & 7));
+    }
+    // its share of the activation tile: instruction xi covers tile rows 8 xi .. 8 xi + 7 (a row past the tokens or the
+    // layers repeats a valid one; such rows are masked as keys and dropped as queries)
+    const bf16_t *xsrc[NXI];
+    int xrow0[NXI];
+#pragma unroll
+    for (int n = 0; n < NXI; ++n) {
+        int xi = wave + 8 * n;
+        if (xi > RB / 8 - 1) xi = RB / 8 - 1;    // a spare instruction repeats the last one (same bytes to the same place)
+        xrow0[n] = 8 * xi;
+        const int s = 8 * xi + lrow;
+        int64_t tok = tile * TT + s / (32 * NB);
+        int lay = s % (32 * NB);
+        if (tok > a.T - 1) tok = a.T - 1;
+        if (lay > L - 1) lay = L - 1;
+        xsrc[n] = a.hs + (tok * L + lay) * (int64_t)K + 8 * (lpos ^ ((s >> 1) & 7));
+    }
+    bf16_t *wl = sm + (size_t)wave * 2 * FW * BK;                 // this wavefront's ring: [2][FW][BK]
+    bf16_t *xl = sm + (size_t)8 * 2 * FW * BK;                    // [XS][RB][BK]
+    auto issue_w = [&](int kt) {
+        bf16_t *dst = wl + (kt & 1) * FW * BK;
+#pragma unroll
+        for (int i = 0; i < NWI; ++i)
+            __builtin_amdgcn_global_load_lds((global_void_t *)(wsrc[i] + (int64_t)kt * BK), (lds_void_t *)(dst + 8 * i * BK), 16, 0, 0);
+    };
+    auto issue_x = [&](int kt) {
+        bf16_t *dst = xl + (kt % XS) * RB * BK;
+#pragma unroll
+        for (int n = 0; n < NXI; ++n)
+            __builtin_amdgcn_global_load_lds((global_void_t *)(xsrc[n] + (int64_t)kt * BK), (lds_void_t *)(dst + xrow0[n] * BK), 16, 0, 0);
+    };
+
+    // Requests are issued in the order X(0) W(0) X(1) W(1) (W(0) X(0) W(1) with a two-stage activation ring), then per
+    // tile kt: X(kt+XD) W(kt+2), and complete in that order (all of them go straight to LDS).  At the top of tile kt,
+    // X(kt) and W(kt) must have landed; what was requested after the later of the two is X(kt+1) W(kt+1) (only
+    // W(kt+1) with the two-stage ring), and nothing in the last round.
+    if (XD >= 2) issue_x(0);
+    issue_w(0);
+    issue_x(XD >= 2 ? 1 : 0);
+    issue_w(1);
+    constexpr int PENDING = XD >= 2 ? NXI + NWI : NWI;
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        const bf16_t *wb = wl + (kt & 1) * FW * BK;
+        const bf16_t *xb = xl + (kt % XS) * RB * BK;
+        // The four k-steps of a tile are software-pipelined: the fragments of step ks+1 are requested from LDS before
+        // the MFMAs of step ks are issued, so LDS reads and matrix work of one wavefront overlap.  Once the last
+        // step's fragments have been read, the ring places this tile occupied are free and are refilled.
+        auto read_frags = [&](int ks, bf16x8 (&fa)[WFB], bf16x8 (&fb)[NRB]) {
+#pragma unroll
+            for (int i = 0; i < WFB; ++i) {
+                const int row = 32 * i + l32;
+                fa[i] = *(const bf16x8 *)&wb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
+            }
+#pragma unroll
+            for (int j = 0; j < NRB; ++j) {
+                const int row = 32 * j + l32;
+                fb[j] = *(const bf16x8 *)&xb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
+            }
+        };
+        bf16x8 af[2][WFB], bfr[2][NRB];
+        read_frags(0, af[0], bfr[0]);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            if (ks + 1 < BK / 16) read_frags(ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
+            if (ks == BK / 16 - 1) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if (kt + XD < nk) issue_x(kt + XD);
+                if (kt + 2 < nk) issue_w(kt + 2);
+            }
+#pragma unroll
+            for (int i = 0; i < WFB; ++i)
+#pragma unroll
+                for (int j = 0; j < NRB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    lsa_fused_epilogue<DH, NB, TT>(acc, a, sm, tile, g, part);
+}
+
+// The same kernel for weights that the caller has packed once into MFMA-operand order (k_lsa_pack_weights).  A
+// wavefront's slice of the weight tile is used by that wavefront alone, so with the operands already in lane order it
+// has no business in LDS: every 16-byte operand piece is loaded straight into the register that the MFMA reads, 1 KB
+// contiguous per instruction.  That takes the weight tile (8/9 of the bytes) out of the LDS traffic -- reads and
+// writes of the unpacked form add up to the LDS bandwidth of the whole tile time -- and lets WS - 1 whole tiles be in
+// flight per wavefront in registers, which the 160 KB of LDS could not hold.  The activation tile goes through
+// registers into a two-stage LDS ring (one bare barrier per tile); all loads are ordinary loads, so the waits are the
+// compiler's.  Same MFMA order along d_in as the unpacked form: same bits.
+template <int DH, int NB, int TT>
+__global__ __launch_bounds__(512) void k_lsa_fused_pk(LsaFusedArgs a)
+{
+    using Gm = LsaFusedGeom<DH, NB, TT>;
+    constexpr int FW = Gm::FW, RB = Gm::RB, BK = Gm::BK, WS = Gm::WS;
+    constexpr int WFB = FW / 32;                 // 32-feature blocks per wavefront
+    constexpr int NRB = RB / 32;                 // 32-row blocks
+    constexpr int NWP = 4 * WFB;                 // operand pieces per lane and weight tile
+    constexpr int NXI = (RB / 8 + 7) / 8;        // activation-tile load instructions per wavefront
+    extern __shared__ __attribute__((aligned(16))) bf16_t sm[];
+
+    if ((int)blockIdx.x < a.lead_blocks) {       // the first workgroups of the grid carry work of other calls
+        if ((int)blockIdx.x < a.small_lead) {
+            if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
+                step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)sm, (int32_t *)sm + MOA_MAX_TREE);
+        } else {
+            const int blk = 2 * ((int)blockIdx.x - a.small_lead) + (int)(threadIdx.x >> 8);
+            if (blk < a.red_blocks) splitk_reduce_block(a.red, blk, (int)(threadIdx.x & 255));
+        }
+        return;
+    }
+    const int bx = (int)blockIdx.x - a.lead_blocks;
+    const int xcd = bx & 7, slot = bx >> 3;
+    const int unit = xcd * a.units_per_xcd + slot % a.units_per_xcd;
+    const int64_t tile = slot / a.units_per_xcd;
+    if (unit >= a.units) return;                 // the whole workgroup leaves before any barrier
+    const int g = unit / a.parts, part = unit - g * a.parts;
+    const int L = a.L, K = a.d_in;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int lrow = lane >> 3, lpos = lane & 7;
+
+    f32x16 acc[WFB][NRB];
+#pragma unroll
+    for (int i = 0; i < WFB; ++i)
+#pragma unroll
+        for (int j = 0; j < NRB; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    const int nk = K / BK;
+
+    // packed weights: [unit][wavefront][k tile][k step][feature block][lane] pieces of 8 elements
+    const bf16x8 *wp = (const bf16x8 *)a.wpk + ((int64_t)(unit * 8 + wave) * nk) * (NWP * 64) + lane;
+    // activation rows as in the unpacked form: instruction n covers tile rows xrow0[n] .. + 7, the piece a lane fetches
+    // is the one whose swizzled place in LDS is the lane's own
+    const bf16_t *xsrc[NXI];
+    int xrow0[NXI];
+#pragma unroll
+    for (int n = 0; n < NXI; ++n) {
+        int xi = wave + 8 * n;
+        if (xi > RB / 8 - 1) xi = RB / 8 - 1;
+        xrow0[n] = 8 * xi;
+        const int s = 8 * xi + lrow;
+        int64_t tok = tile * TT + s / (32 * NB);
+        int lay = s % (32 * NB);
+        if (tok > a.T - 1) tok = a.T - 1;
+        if (lay > L - 1) lay = L - 1;
+        xsrc[n] = a.hs + (tok * L + lay) * (int64_t)K + 8 * (lpos ^ ((s >> 1) & 7));
+    }
+    bf16_t *xl = sm;                             // [2][RB][BK]
+
+    // both operands are requested WS - 1 tiles ahead into register rings (a weight stage is refilled as soon as its
+    // tile has been multiplied, an activation stage as soon as it has been copied to LDS)
+    bf16x8 wr[WS][NWP];
+    bf16x8 xr[WS][NXI];
+    auto load_w = [&](int kt, bf16x8 (&dst)[NWP]) {
+#pragma unroll
+        for (int b = 0; b < NWP; ++b) dst[b] = wp[((int64_t)kt * NWP + b) * 64];
+    };
+    auto load_x = [&](int kt, bf16x8 (&dst)[NXI]) {
+#pragma unroll
+        for (int n = 0; n < NXI; ++n) dst[n] = *(const bf16x8 *)(xsrc[n] + (int64_t)kt * BK);
+    };
+#pragma unroll
+    for (int s = 0; s < WS; ++s) {               // a tile past the last repeats the last (nk >= 2)
+        if (s < WS - 1) load_x(s < nk ? s : nk - 1, xr[s]);
+        load_w(s < nk ? s : nk - 1, wr[s]);
+    }
+
+    // The loop body carries no branch around a load: the compiler's load counter then stays exact inside a trip
+    // (partial waits), where a conditional request makes it wait for everything in flight.  Requests past the last
+    // tile repeat the last tile; a trip covers UN tile steps (at the top of a trip the compiler's wait is a
+    // conservative one, so trips are made long), and the surplus steps of the last trip skip only their arithmetic.
+    constexpr int UN = Gm::UN;
+    const int nkr = (nk + UN - 1) / UN * UN;
+#pragma unroll 1
+    for (int kt0 = 0; kt0 < nkr; kt0 += UN) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int s = u % WS;
+            const int kt = kt0 + u;
+            bf16_t *xb = xl + (kt & 1) * RB * BK;
+            // the activation tile of this step goes to LDS (the place was last read two tiles ago, before the
+            // previous barrier); the tiles WS - 1 ahead are requested into the registers this step's tiles leave
+#pragma unroll
+            for (int n = 0; n < NXI; ++n) *(bf16x8 *)&xb[xrow0[n] * BK + 8 * lane] = xr[s][n];
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            const int ka = kt + WS - 1 < nk ? kt + WS - 1 : nk - 1;
+            load_x(ka, xr[(s + WS - 1) % WS]);
+            if (kt < nk) {
+                auto read_frags = [&](int ks, bf16x8 (&fb)[NRB]) {
+#pragma unroll
+                    for (int j = 0; j < NRB; ++j) {
+                        const int row = 32 * j + l32;
+                        fb[j] = *(const bf16x8 *)&xb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
+                    }
+                };
+                bf16x8 bfr[2][NRB];
+                read_frags(0, bfr[0]);
+#pragma unroll
+                for (int ks = 0; ks < BK / 16; ++ks) {
+                    if (ks + 1 < BK / 16) read_frags(ks + 1, bfr[(ks + 1) & 1]);
+#pragma unroll
+                    for (int i = 0; i < WFB; ++i)
+#pragma unroll
+                        for (int j = 0; j < NRB; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[s][ks * WFB + i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                }
+            }
+            // this step's weight registers are free now: the tile WS steps ahead goes there
+            load_w(kt + WS < nk ? kt + WS : nk - 1, wr[s]);
+        }
+    }
+    lsa_fused_epilogue<DH, NB, TT>(acc, a, sm, tile, g, part);
+}
+
+// Packs Wq / Wk / Wv for k_lsa_fused_pk: piece (unit, wavefront, k tile, k step, feature block, lane) holds the 8
+// elements that lane supplies as the A operand of that MFMA, i.e. row  f(unit, wavefront) + 32 block + lane % 32  of
+// the wavefront's matrix at columns  64 tile + 16 step + 8 (lane / 32) ..  One thread per piece.
+template <int DH>
+__global__ __launch_bounds__(256) void k_lsa_pack_weights(const bf16_t *wq, const bf16_t *wk, const bf16_t *wv, bf16_t *out,
+                                                          int d_in, int Hq, int Hkv, int64_t pieces)
+{
+    constexpr int FW = 4 * DH / 8, WFB = FW / 32;
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= pieces) return;
+    const int nk = d_in / 64, G = Hq / Hkv, parts = G / 2;
+    int64_t r = p;
+    const int lane = (int)(r % 64); r /= 64;
+    const int i = (int)(r % WFB); r /= WFB;
+    const int ks = (int)(r % 4); r /= 4;
+    const int kt = (int)(r % nk); r /= nk;
+    const int wave = (int)(r % 8); r /= 8;
+    const int unit = (int)r;
+    const int g = unit / parts, part = unit - g * parts;
+    const int which = wave * FW / DH;
+    const int frow = wave * FW % DH + 32 * i + (lane & 31);
+    const bf16_t *src = which < 2 ? wq + (int64_t)((g * G + 2 * part + which) * DH + frow) * d_in
+                                  : (which == 2 ? wk : wv) + (int64_t)(g * DH + frow) * d_in;
+    *(u32x4 *)(out + p * 8) = *(const u32x4 *)(src + 64 * kt + 16 * ks + 8 * (lane >> 5));
+}
+
 // ------------------------------------------------------------------ host side
 bool lsa_fused_ok(int dtype, int L, int d_in, int Hq, int Hkv, int dh, const void *hs, const void *wq, const void *wk,
                   const void *wv, const void *abar)
 {
     auto al = [](const void *p) { return p && (((uintptr_t)p) & 15) == 0; };
+    if (!lsa_fused_shape_ok(dtype, L, d_in, Hq, Hkv, dh)) return false;
+    return al(hs) && al(wq) && al(wk) && al(wv) && al(abar);
+}
+
+bool lsa_fused_shape_ok(int dtype, int L, int d_in, int Hq, int Hkv, int dh)
+{
     if (dtype != DT_BF16 || dh != 128) return false;
     if (L < 1 || L > 96 || d_in < 128 || d_in % 64) return false;
-    if (Hq % Hkv || (Hq / Hkv) % 2) return false;
-    return al(hs) && al(wq) && al(wk) && al(wv) && al(abar);
+    if (Hkv < 1 || Hq % Hkv || (Hq / Hkv) % 2) return false;
+    return true;
 }
 
 // LDS a workgroup may ask for on the current device (looked up once per device; 0 if the query fails)
@@ -358,14 +546,42 @@ template <int NB, int TT>
 static hipError_t launch_lsa_fused_as(LsaFusedArgs &fa, hipStream_t stream)
 {
     using Gm = LsaFusedGeom<128, NB, TT>;
-    static bool raised[16] = {};
-    hipError_t e = raise_lds_limit_once(raised, (const void *)k_lsa_fused<128, NB, TT>, Gm::bytes);
-    if (e != hipSuccess) return e;
     const int64_t tiles = (fa.T + TT - 1) / TT;
     const int64_t grid = fa.lead_blocks + 8 * (int64_t)fa.units_per_xcd * tiles;
     if (grid > 0x7fffffff) return hipErrorInvalidValue;
-    prof_begin(K_LSA_FUSED + 64 * (NB * 8 + TT), stream);
-    MOA_KLAUNCH((k_lsa_fused<128, NB, TT>), dim3((unsigned)grid), dim3(512), Gm::bytes, stream, fa);
+    if (fa.wpk) {
+        static bool raised[16] = {};
+        hipError_t e = raise_lds_limit_once(raised, (const void *)k_lsa_fused_pk<128, NB, TT>, Gm::pk_bytes);
+        if (e != hipSuccess) return e;
+        prof_begin(K_LSA_FUSED_PK + 64 * (NB * 8 + TT), stream);
+        MOA_KLAUNCH((k_lsa_fused_pk<128, NB, TT>), dim3((unsigned)grid), dim3(512), Gm::pk_bytes, stream, fa);
+    } else {
+        static bool raised[16] = {};
+        hipError_t e = raise_lds_limit_once(raised, (const void *)k_lsa_fused<128, NB, TT>, Gm::bytes);
+        if (e != hipSuccess) return e;
+        prof_begin(K_LSA_FUSED + 64 * (NB * 8 + TT), stream);
+        MOA_KLAUNCH((k_lsa_fused<128, NB, TT>), dim3((unsigned)grid), dim3(512), Gm::bytes, stream, fa);
+    }
+    prof_end(stream);
+    return hipGetLastError();
+}
+
+size_t lsa_packed_weight_bytes(int d_in, int Hq, int Hkv, int dh)
+{
+    // a workgroup's unit is two query heads with their key and value head: 4 dh rows; a group of more than two query
+    // heads repeats its K and V rows in each of its units
+    return (size_t)(Hq / 2) * 4 * dh * d_in * sizeof(bf16_t);
+}
+
+hipError_t launch_lsa_pack_weights(const void *wq, const void *wk, const void *wv, void *out, int d_in, int Hq, int Hkv,
+                                   hipStream_t stream)
+{
+    const int64_t pieces = (int64_t)(Hq / 2) * 4 * 128 * d_in / 8;
+    const int64_t grid = (pieces + 255) / 256;
+    if (grid > 0x7fffffff) return hipErrorInvalidValue;
+    prof_begin(K_LSA_PACK, stream);
+    MOA_KLAUNCH((k_lsa_pack_weights<128>), dim3((unsigned)grid), dim3(256), 0, stream, (const bf16_t *)wq, (const bf16_t *)wk,
+                (const bf16_t *)wv, (bf16_t *)out, d_in, Hq, Hkv, pieces);
     prof_end(stream);
     return hipGetLastError();
 }
@@ -378,6 +594,7 @@ hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream)
     fa.wq = (const bf16_t *)c.wq;
     fa.wk = (const bf16_t *)c.wk;
     fa.wv = (const bf16_t *)c.wv;
+    fa.wpk = (const bf16_t *)c.w_packed;
     fa.abar = (bf16_t *)c.abar;
     fa.T = c.T;
     fa.L = c.L;

@@ -28,7 +28,7 @@ class DeviceStep:
     """All tensors of one step on the GPU.  `n_len_slots` independent copies of the (tiny) cross-attention
     length array let a benchmark run that many steps back to back without resetting anything."""
 
-    def __init__(self, work, n_len_slots: int = 1, ws: torch.Tensor | None = None, fold: bool = True):
+    def __init__(self, work, n_len_slots: int = 1, ws: torch.Tensor | None = None, fold: bool = True, pack: bool = True):
         cfg = work["cfg"]
         dt = cfg.dtype
         self.cfg, self.shape = cfg, shape_of(cfg)
@@ -48,6 +48,14 @@ class DeviceStep:
         # one-time fold of the two projections between LSA's heads and the memory's keys / values
         self.folded = (moa.fold_projection(self.ca_w["wk"], self.lsa_w["wo"]),
                        moa.fold_projection(self.ca_w["wv"], self.lsa_w["wo"])) if fold else None
+        # one-time rearrangement of the LSA's Wq / Wk / Wv into MFMA-operand order, for shapes that have one
+        self.lsa_w_packed = None
+        if pack:
+            try:
+                self.lsa_w_packed = moa.lsa_pack_weights(self.shape, self.lsa_w["wq"], self.lsa_w["wk"], self.lsa_w["wv"])
+            except moa.MoaError as e:
+                if e.status != -2:              # MOA_ERR_SHAPE: no packed form for this shape; anything else is a failure
+                    raise
         self.ca_xq = _dev(work["ca_xq"], dt)
         self.ca_k, self.ca_v = _dev(work["ca_k"], dt), _dev(work["ca_v"], dt)
         self.ca_len0 = _dev(work["ca_len0"])
@@ -91,7 +99,7 @@ class DeviceStep:
                 v_w=self.v_w, v_kcache=self.v_kcache, v_vcache=self.v_vcache, v_out=self.v_out, v_ktree=self.v_ktree,
                 v_vtree=self.v_vtree, prefix_len=self.prefix_len, P_cap=self.P_cap, tok=self.tok, tgt=self.tgt,
                 path=self.path, n_path=self.n_path, bonus=self.bonus, ws=self.ws, dev_status=self.dev_status,
-                schedule=schedule, sa=self.sa, folded=self.folded)
+                schedule=schedule, sa=self.sa, folded=self.folded, lsa_w_packed=self.lsa_w_packed)
         return self._plans[key]
 
     def run(self, len_slot: int = 0, stream=None, schedule: int = 0):

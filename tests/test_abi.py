@@ -77,6 +77,38 @@ def test_null_and_range_errors_launch_nothing(moa):
     assert lib.moa_draft_step(None) == -1
 
 
+def test_packed_lsa_weights_sizes_and_refusals(moa):
+    """The packed copy of the LSA weights: its size is that of the rows the one-kernel form reads (two query heads, a key
+    head and a value head per unit: a group of four query heads stores its K and V rows twice); shapes that form does not
+    take have no packed form; bad pointers and short buffers are refused before anything is launched."""
+    s = moa.Shape(32, 4096, 32, 8, 128, 2048, 16, 8, moa.BF16)                 # Llama-3-8B: 16 LSA heads over 8 KV heads
+    assert moa.lsa_packed_weight_bytes(s) == (16 + 8 + 8) * 128 * 2048 * 2
+    s4 = moa.Shape(32, 4096, 32, 8, 128, 4096, 32, 8, moa.BF16)                # d_in = d: groups of four query heads
+    assert moa.lsa_packed_weight_bytes(s4) == (32 + 16 + 16) * 128 * 4096 * 2
+    for bad in (moa.Shape(32, 4096, 32, 8, 128, 2048, 16, 8, moa.F32),         # fp32
+                moa.Shape(32, 4096, 32, 8, 64, 2048, 32, 16, moa.BF16),        # head_dim 64
+                moa.Shape(32, 4096, 32, 8, 128, 2048, 16, 16, moa.BF16),       # one query head per KV head
+                moa.Shape(128, 4096, 32, 8, 128, 2048, 16, 8, moa.BF16),       # more than 96 layers
+                moa.Shape(32, 4096, 32, 8, 128, 2080, 16, 8, moa.BF16)):       # d_lsa_in not in 64s
+        with pytest.raises(moa.MoaError) as e:
+            moa.lsa_packed_weight_bytes(bad)
+        assert e.value.status == -2
+    lib = C.CDLL(moa.library_path())
+    fake = C.c_void_p(256)
+    need = moa.lsa_packed_weight_bytes(s)
+    lib.moa_lsa_pack_weights.restype = C.c_int32
+    lib.moa_lsa_pack_weights.argtypes = [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p]
+    assert lib.moa_lsa_pack_weights(C.byref(s), fake, fake, None, fake, need, None) == -1
+    assert lib.moa_lsa_pack_weights(C.byref(s), fake, fake, fake, fake, need - 1, None) == -6
+    assert lib.moa_lsa_pack_weights(C.byref(s), fake, fake, fake, C.c_void_p(264), need, None) == -2     # misaligned
+    lib.moa_lsa_packed.restype = C.c_int32
+    lib.moa_lsa_packed.argtypes = [C.c_void_p, C.c_void_p, C.c_int64] + [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
+    assert lib.moa_lsa_packed(C.byref(s), fake, 4, None, fake, fake, fake, 1 << 30, None) == -1
+    assert lib.moa_lsa_packed(C.byref(s), fake, -1, fake, fake, fake, fake, 1 << 30, None) == -2
+    assert lib.moa_lsa_packed(C.byref(s), fake, 4, fake, fake, fake, fake, 16, None) == -6
+    assert lib.moa_lsa_packed(C.byref(s), fake, 0, fake, fake, fake, None, 0, None) == 0                 # nothing to do
+
+
 def test_bench_refuses_more_than_one_gpu():
     """One GPU only: `bench.py --gpus N` with N above 1 must exit with a message that says so (before any GPU use)."""
     import subprocess

@@ -172,12 +172,15 @@ def test_lsa_layer_counts_beyond_one_block(G, moa, oracle, L, dh, lsa_kernel):
 
 
 @pytest.mark.parametrize("L,d_in,Hkv,T", [(32, 512, 2, 9), (64, 1024, 2, 5), (17, 256, 1, 6), (96, 512, 4, 3), (2, 128, 1, 4),
-                                           (32, 1024, 4, 600), (32, 512, 2, 401), (64, 512, 2, 201)])
+                                           (32, 1024, 4, 600), (32, 512, 2, 401), (64, 512, 2, 201), (32, 320, 1, 7),
+                                           (64, 576, 1, 600), (96, 1024, 4, 3)])
 def test_lsa_one_kernel_form_shapes(G, moa, oracle, L, d_in, Hkv, T):
     """The one-kernel form across its template variants (one, two and three blocks of 32 layers), groups of two and of
     four query heads per KV head (a group of four is cut into two parts that recompute K and V), odd token counts (a
     half-filled token tile), the shortest input width it takes, and enough tokens for the tiles of three and four tokens
-    (two at two blocks of layers) with a ragged last tile; it must also give the bits of the three-kernel form."""
+    (two at two blocks of layers) with a ragged last tile, and input widths whose tile count is not a multiple of the
+    packed form's register stages (5 and 9 tiles of 64); it must also give the bits of the three-kernel form, from
+    plain and from packed weights."""
     cfg = small_cfg("bf16", L=L, d_lsa_in=d_in, dh=128, Hkv=Hkv)
     print(f"[case] lsa one-kernel L={L} d_in={d_in} heads={cfg.lsa_heads}/{Hkv} T={T}", flush=True)
     shape = G.shape_of(cfg)
@@ -197,7 +200,21 @@ def test_lsa_one_kernel_form_shapes(G, moa, oracle, L, d_in, Hkv, T):
         outs[form] = out
     want = oracle.lsa(hs, w["wq"], w["wk"], w["wv"], w["wo"], cfg.lsa_heads, cfg.Hkv, cfg.dh)
     G.check_close(G.host(outs["fused"]), want, cfg.dtype, f"lsa one-kernel[L={L},d_in={d_in},Hkv={Hkv}]")
-    assert torch.equal(outs["fused"], outs["separate"]), "same products in the same order, same roundings"
+    if d_in % 128 == 0:     # then the three-kernel form projects on the matrix cores too, in the same order along d_in
+        assert torch.equal(outs["fused"], outs["separate"]), "same products in the same order, same roundings"
+    else:
+        G.check_close(G.host(outs["separate"]), want, cfg.dtype, f"lsa three kernels[L={L},d_in={d_in},Hkv={Hkv}]")
+    # the same kernel fed from weights packed into MFMA-operand order: registers instead of LDS for the weight tile
+    if (cfg.lsa_heads // Hkv) % 2:
+        with pytest.raises(moa.MoaError):       # a shape the one-kernel form does not take has no packed form
+            moa.lsa_pack_weights(shape, *dw[:3])
+        return
+    packed = moa.lsa_pack_weights(shape, *dw[:3])
+    out = torch.full((T, cfg.d_lsa), float("nan"), dtype=G.TDT[cfg.dtype], device="cuda")
+    moa.lsa_packed(shape, G.dev(hs, cfg.dtype), packed, dw[3], out, ws)
+    torch.cuda.synchronize()
+    G.check_close(G.host(out), want, cfg.dtype, f"lsa one-kernel, packed weights[L={L},d_in={d_in},Hkv={Hkv}]")
+    assert torch.equal(outs["fused"], out), "packing changes where a weight is read from, not the arithmetic"
 
 
 def ca_setup(cfg, Mq):

@@ -220,6 +220,27 @@ def test_step_captured_in_a_hip_graph_replays_like_eager(G, schedule):
     assert step.dev_status.item() == 0
 
 
+@pytest.mark.parametrize("schedule", ["grouped", "two_stream", "sequential"])
+def test_step_from_packed_and_plain_lsa_weights_gives_the_same_bits(G, schedule):
+    """The LSA weights packed once into MFMA-operand order change where the kernel reads a weight from, not the
+    arithmetic: a step fed the packed copy and one fed the plain matrices agree bit for bit in every output.  (The other
+    step cases run with the packed copy, as the benchmark does; this one also runs the plain path through a step.)"""
+    from paper_2410_03804_amd.workload import DeviceStep
+    cfg, nlayers = STEP_CASES["C1_bf16"]
+    work = mi.step_workload(cfg, n_verify_layers=nlayers)
+    outs = {}
+    for pack in (True, False):
+        step = DeviceStep(work, pack=pack)
+        assert (step.lsa_w_packed is not None) == pack
+        step.run(schedule=SCHEDULES[schedule])
+        torch.cuda.synchronize()
+        assert step.dev_status.item() == 0
+        exact, merged = _step_outputs(step)
+        outs[pack] = exact + merged
+    for a, b in zip(outs[True], outs[False]):
+        assert torch.equal(a, b)
+
+
 def test_measurement_aid_times_kernels_and_samples(G):
     """The profiling aid attributes device time to kernels; sampling every n-th launch keeps a share of them;
     the two ceiling probes run and report plausible rates for this device."""
