@@ -9,7 +9,7 @@
  *    every buffer (inputs, outputs, caches, workspace); the library allocates no
  *    device memory and never frees.  What it keeps per device for the life of the
  *    process: the fixed scratch array of moa_tree_verify_attn_noalloc, and, once
- *    MOA_SCHED_TWO_STREAM has been used, one stream and four events.
+ *    MOA_SCHED_TWO_STREAM has been used, one stream and two events.
  *  - All work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
  *    default stream).  No host synchronisation happens inside.  Argument checks
  *    that need only host values run before anything is launched; a failed check
@@ -365,17 +365,18 @@ int32_t moa_fold_projection(int32_t dtype, const void *w_outer, const void *w_in
  *    Needs Mq == M, n_verify_layers >= 1, non-NULL CA and first-layer weights and the workspace
  *    moa_workspace_bytes asks for; otherwise the step runs as MOA_SCHED_SEQUENTIAL.  tok[], tgt[]
  *    and ca_len[] are read by the first launch of the step, so nothing in the step may produce them.
- *  MOA_SCHED_TWO_STREAM (1): the LSA chain feeds only the CA core, so the projections (grouped as
- *    above, with the integer work) and the verification layers run on a second, library-owned stream
- *    that is forked from and joined back into `stream` with events, beside the LSA chain and the CA
- *    core on `stream`; the LSA takes its largest token tile so that compute units are left for the
- *    other branch.  Same requirements as MOA_SCHED_GROUPED.  One side stream exists per device: steps
- *    of several host threads on one device are enqueued one after the other (a mutex), and the branch
- *    is joined back even when a launch fails half way.
+ *  MOA_SCHED_TWO_STREAM (1): the grouped launches, with the first of them (the CA query and first-layer
+ *    Q/K/V projections, which depend on nothing else in the step) and the pass that adds up its slices on a
+ *    second, library-owned stream that is forked from and joined back into `stream` with one event each,
+ *    beside the LSA kernel on `stream`.  With lsa_w_packed the LSA kernel runs in a lean form that shares
+ *    its compute units with the projection kernel; without, with its largest token tile, so that compute
+ *    units are left over.  Same requirements as MOA_SCHED_GROUPED.  One side stream exists per device:
+ *    steps of several host threads on one device are enqueued one after the other (a mutex), and the
+ *    branch is joined back even when a launch fails half way.
  *  MOA_SCHED_SEQUENTIAL (2): every stage enqueued on `stream` in the order above, one launch
  *    per stage, exactly as the single entry points would.
- * Integer results are identical under all three; floating-point results of 1 and 2 are
- * bit-identical, those of 0 differ from them only where the two attention cores end up with a
+ * Integer results are identical under all three; floating-point results of 0 and 1 are
+ * bit-identical, those of 2 differ from them only where the two attention cores end up with a
  * different number of key slices (partials merged in another order). */
 enum { MOA_SCHED_GROUPED = 0, MOA_SCHED_TWO_STREAM = 1, MOA_SCHED_SEQUENTIAL = 2 };
 

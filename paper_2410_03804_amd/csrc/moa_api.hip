@@ -1474,26 +1474,33 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
 }
 
 // ---- the same pieces on two streams.
-// Dependencies inside one step: the LSA chain (LSA -> W_o -> memory append) feeds only the cross-attention core; the
-// projections of the cross-attention queries and every verification layer depend on none of it.  The LSA kernel is
-// bound by the matrix cores and the L2, the projections by HBM, so the two halves want different parts of the chip.
-// They cannot share a compute unit (the LSA kernel fills its LDS), so they share the chip side by side: the LSA runs
-// with its largest token tile, which at decode sizes leaves half of the compute units without a workgroup of it, and
-// the weight-streaming launches of the side branch take those.  The side branch runs on a library-owned stream that
-// is forked from and joined back into the caller's stream with events, so the caller still sees one stream's worth of
-// ordering (and a stream capture records both branches).
-//   side: [CA query + verification Q/K/V projections + the step's integer work] -> E_small -> [sum of its K slices]
-//         -> E_q -> verification core -> W_o -> further layers -> E_join
-//   main: E_fork -> LSA -> wait E_small (old memory lengths) -> LSA W_o + memory append -> wait E_q (CA queries)
-//         -> cross-attention core -> W_o -> wait E_join
-// One side stream and one set of events exist per device; a mutex is held while a step is being enqueued, so steps of
+// Dependencies inside one step: the LSA kernel depends on nothing else in the step, and neither do the projections of
+// the cross-attention queries and the first verification layer.  The LSA kernel is bound by the matrix cores and the
+// L2, those projections by HBM, so the two want different parts of the chip.  From packed weights the LSA kernel has a
+// lean form (a third of a SIMD's registers per wavefront, 67 KB of LDS) beside which a compute unit still holds a
+// workgroup of the weight-streaming kernel, so the two launches run on the same compute units at the same time; from
+// plain weights the LSA kernel fills the LDS and runs with its largest token tile instead, which at decode sizes leaves
+// half of the compute units to the other launch.  The projections run on a library-owned stream that is forked from
+// and joined back into the caller's stream with one event each (an edge between two hardware queues costs several
+// microseconds, so there are only these two), and the caller still sees one stream's worth of ordering (a stream
+// capture records both branches).
+//   side: E_fork -> [CA query + verification Q/K/V projections] -> [sum of its K slices] -> E_join
+//   main: E_fork -> [LSA + the step's integer work] -> LSA W_o + memory append -> wait E_join -> both attention cores
+//         -> both output projections -> further verification layers
+// (When the LSA cannot run as the one kernel, the integer work rides with the projections and the main branch waits
+// for E_join before the memory append.)
+// One side stream and one pair of events exist per device; a mutex is held while a step is being enqueued, so steps of
 // several host threads on one device are enqueued one after the other.
 struct SideStream {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, small = nullptr, q = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
     bool ok = false;
     std::mutex enqueue;
 };
+
+// The two events order work of one device against work of the same device: no system-scope fence (which writes the
+// caches back for the host and other devices to see) is needed for that, and none is asked for.
+static constexpr unsigned kEdgeFlags = hipEventDisableTiming | hipEventDisableSystemFence;
 
 static SideStream *side_stream_for_current_device()
 {
@@ -1505,10 +1512,8 @@ static SideStream *side_stream_for_current_device()
     SideStream &s = pool[dev];
     if (!s.stream) {
         s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
-               hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&s.small, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&s.q, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
+               hipEventCreateWithFlags(&s.fork, kEdgeFlags) == hipSuccess &&
+               hipEventCreateWithFlags(&s.join, kEdgeFlags) == hipSuccess;
     }
     return s.ok ? &s : nullptr;
 }
@@ -1520,41 +1525,44 @@ static size_t two_stream_bytes(const moa_step_args_t *a)
     return L.total() + L.scratch;
 }
 
-// side branch; *forked_small / *forked_q report which events have been recorded when it fails half way
-static int32_t two_stream_side(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes, SideStream *ss)
+// side branch
+static int32_t two_stream_side(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes, SideStream *ss,
+                               bool with_small)
 {
     hipStream_t side = ss->stream;
     SumArgs sum_pair = {};
-    int32_t rc = piece_projections(a, bf, scr, scr_bytes, side, true, &sum_pair);
+    int32_t rc = piece_projections(a, bf, scr, scr_bytes, side, with_small, &sum_pair);
     if (rc) return rc;
-    MOA_TRY_HIP(hipEventRecord(ss->small, side), "draft_step: event");
     prof_set_site(S_PAIR_QKV);
     MOA_TRY_HIP(launch_splitk_sum(sum_pair, side), "draft_step: projections");
-    MOA_TRY_HIP(hipEventRecord(ss->q, side), "draft_step: event");
-    // the partial sums have been added up: the scratch is free for the core and the output projection
-    prof_set_site(S_VERIFY_CORE);
-    MOA_TRY_HIP(launch_attn(piece_verify_core_args(a, bf, scr, scr_bytes), side), "draft_step: verification core");
-    rc = piece_oproj(a, bf, 2, scr, scr_bytes, side);
-    if (rc) return rc;
-    return piece_more_verify_layers(a, scr, scr_bytes, side);
+    return MOA_OK;
 }
 
-static int32_t two_stream_main(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes, SideStream *ss)
+// whether the main branch of a two-stream step runs the LSA as the one kernel (which then also carries the step's
+// integer work, so that nothing in the LSA chain has to wait for the other branch)
+static bool two_stream_lsa_fused(const moa_step_args_t *a)
+{
+    return a->T_lsa > 0 && a->T_lsa <= LSA_OBLOCK &&
+           lsa_takes_fused(a->shape, a->T_lsa, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->ws);
+}
+
+static int32_t two_stream_main(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes, size_t attn_each,
+                               SideStream *ss, bool fused)
 {
     hipStream_t main = (hipStream_t)a->stream;
     const moa_shape_t *sh = a->shape;
     const int64_t T = a->T_lsa;
     int32_t rc = lsa_check(sh, a->lsa_hs, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_out, scr, scr_bytes);
     if (rc) return rc;
-    const LsaBufs b = lsa_carve(sh, T, scr, scr_bytes);
-    void *abar = a->lsa_wo ? (void *)b.abar0 : a->lsa_out;
-    const bool fused = T > 0 && T <= LSA_OBLOCK && lsa_takes_fused(sh, T, a->lsa_hs, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar);
     if (fused) {
+        const LsaBufs b = lsa_carve(sh, T, scr, scr_bytes);
+        void *abar = a->lsa_wo ? (void *)b.abar0 : a->lsa_out;
         LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar, step_lsa_packed(a));
-        fc.leave_room = 1;                   // the largest token tile: fewest workgroups, compute units left to the side branch
+        fc.leave_room = 1;                   // the form that shares the chip with the other branch
+        fc.rider = small_args(a, bf);        // tree masks, accept walk, old memory lengths
+        fc.rider_units = 2 * a->B + 1;
         prof_set_site(S_LSA_FUSED);
         MOA_TRY_HIP(launch_lsa_fused(fc, main), "lsa: fused kernel");
-        MOA_TRY_HIP(hipStreamWaitEvent(main, ss->small, 0), "draft_step: wait");     // the append needs the old lengths
         LinSeg folded[2];
         const bool fold = a->lsa_wo && folded_segments(a, bf, folded);
         if (a->lsa_wo) {
@@ -1566,15 +1574,20 @@ static int32_t two_stream_main(const moa_step_args_t *a, const StepBufs &bf, cha
             rc = piece_append(a, bf, scr, scr_bytes, main);
             if (rc) return rc;
         }
+        // the cores need the other branch's queries; by now it has usually finished, so the wait costs nothing
+        MOA_TRY_HIP(hipStreamWaitEvent(main, ss->join, 0), "draft_step: join");
     } else {
-        MOA_TRY_HIP(hipStreamWaitEvent(main, ss->small, 0), "draft_step: wait");
+        MOA_TRY_HIP(hipStreamWaitEvent(main, ss->join, 0), "draft_step: join");      // the append needs the old lengths
         rc = piece_lsa_append(a, bf, scr, scr_bytes, main);
         if (rc) return rc;
     }
-    MOA_TRY_HIP(hipStreamWaitEvent(main, ss->q, 0), "draft_step: wait");             // the cross-attention's queries
-    prof_set_site(S_CA_CORE);
-    MOA_TRY_HIP(launch_attn(piece_ca_core_args(a, bf, scr, scr_bytes), main), "draft_step: cross-attention core");
-    return piece_oproj(a, bf, 1, scr, scr_bytes, main);
+    const AttnArgs ca = piece_ca_core_args(a, bf, scr, attn_each);
+    const AttnArgs ve = piece_verify_core_args(a, bf, scr + attn_each, attn_each);
+    prof_set_site(S_PAIR_CORE);
+    MOA_TRY_HIP(launch_attn_pair(ca, ve, main), "draft_step: attention cores");
+    rc = piece_oproj(a, bf, 3, scr, scr_bytes, main);
+    if (rc) return rc;
+    return piece_more_verify_layers(a, scr, scr_bytes, main);
 }
 
 static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
@@ -1589,17 +1602,17 @@ static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
     MOA_TRY_HIP(hipEventRecord(ss->fork, main), "draft_step: fork");
     MOA_TRY_HIP(hipStreamWaitEvent(side, ss->fork, 0), "draft_step: fork");
     // Whatever happens from here on, the side stream is joined back into the caller's (a stream capture must not be
-    // left with an unjoined branch).  Events a failed branch did not get to record are recorded here, so that no
-    // wait of this or a later step refers to an older step's event.
-    int32_t rc = two_stream_side(a, bf, scr_side, L.scratch, ss);
-    if (rc) {
-        (void)hipEventRecord(ss->small, side);   // the step already failed with rc; these only keep later waits fresh
-        (void)hipEventRecord(ss->q, side);
-    }
+    // left with an unjoined branch): the main branch waits for the join event on its way; when either branch fails,
+    // the wait is enqueued here (a second wait for the same event is harmless).
+    const bool fused = two_stream_lsa_fused(a);
+    int32_t rc = two_stream_side(a, bf, scr_side, L.scratch, ss, !fused);
     const hipError_t ej = hipEventRecord(ss->join, side);
-    if (rc == MOA_OK) rc = two_stream_main(a, bf, scr_main, L.scratch, ss);
-    const hipError_t ew = ej == hipSuccess ? hipStreamWaitEvent(main, ss->join, 0) : ej;
-    if (rc == MOA_OK && ew != hipSuccess) rc = hip_fail(ew, "draft_step: join");
+    if (rc == MOA_OK && ej != hipSuccess) rc = hip_fail(ej, "draft_step: join");
+    if (rc == MOA_OK) {
+        rc = two_stream_main(a, bf, scr_main, L.scratch, L.attn_each, ss, fused);
+        if (rc == MOA_OK) return rc;
+    }
+    if (ej == hipSuccess) (void)hipStreamWaitEvent(main, ss->join, 0);
     return rc;
 }
 

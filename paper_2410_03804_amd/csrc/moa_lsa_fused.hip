@@ -360,11 +360,11 @@ __global__ __launch_bounds__(512) void k_lsa_fused(LsaFusedArgs a)
 // flight per wavefront in registers, which the 160 KB of LDS could not hold.  The activation tile goes through
 // registers into a two-stage LDS ring (one bare barrier per tile); all loads are ordinary loads, so the waits are the
 // compiler's.  Same MFMA order along d_in as the unpacked form: same bits.
-template <int DH, int NB, int TT>
-__global__ __launch_bounds__(512) void k_lsa_fused_pk(LsaFusedArgs a)
+template <int DH, int NB, int TT, int WS>
+__device__ __forceinline__ void lsa_fused_pk_body(const LsaFusedArgs &a)
 {
     using Gm = LsaFusedGeom<DH, NB, TT>;
-    constexpr int FW = Gm::FW, RB = Gm::RB, BK = Gm::BK, WS = Gm::WS;
+    constexpr int FW = Gm::FW, RB = Gm::RB, BK = Gm::BK;
     constexpr int WFB = FW / 32;                 // 32-feature blocks per wavefront
     constexpr int NRB = RB / 32;                 // 32-row blocks
     constexpr int NWP = 4 * WFB;                 // operand pieces per lane and weight tile
@@ -444,6 +444,7 @@ __global__ __launch_bounds__(512) void k_lsa_fused_pk(LsaFusedArgs a)
     // tile repeat the last tile; a trip covers UN tile steps (at the top of a trip the compiler's wait is a
     // conservative one, so trips are made long), and the surplus steps of the last trip skip only their arithmetic.
     constexpr int UN = Gm::UN;
+    static_assert(UN % WS == 0, "a trip of the tile loop is a whole number of register-ring rounds");
     const int nkr = (nk + UN - 1) / UN * UN;
 #pragma unroll 1
     for (int kt0 = 0; kt0 < nkr; kt0 += UN) {
@@ -484,6 +485,22 @@ __global__ __launch_bounds__(512) void k_lsa_fused_pk(LsaFusedArgs a)
         }
     }
     lsa_fused_epilogue<DH, NB, TT>(acc, a, sm, tile, g, part);
+}
+
+template <int DH, int NB, int TT>
+__global__ __launch_bounds__(512) void k_lsa_fused_pk(LsaFusedArgs a)
+{
+    lsa_fused_pk_body<DH, NB, TT, LsaFusedGeom<DH, NB, TT>::WS>(a);
+}
+
+// The same with two register stages and the compiler held to a third of a SIMD's registers per wavefront (168): beside
+// a workgroup of this kernel a compute unit still has registers and LDS for a workgroup of the weight-streaming
+// projection kernel, so a step that runs its two independent branches on two streams gets them side by side on the same
+// compute units.  (64-row tiles only: larger tiles need the registers for their accumulators.)
+template <int DH, int NB, int TT>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_lsa_fused_pk_lean(LsaFusedArgs a)
+{
+    lsa_fused_pk_body<DH, NB, TT, 2>(a);
 }
 
 // Packs Wq / Wk / Wv for k_lsa_fused_pk: piece (unit, wavefront, k tile, k step, feature block, lane) holds the 8
@@ -543,12 +560,23 @@ static size_t lds_limit()
 }
 
 template <int NB, int TT>
-static hipError_t launch_lsa_fused_as(LsaFusedArgs &fa, hipStream_t stream)
+static hipError_t launch_lsa_fused_as(LsaFusedArgs &fa, hipStream_t stream, bool lean = false)
 {
     using Gm = LsaFusedGeom<128, NB, TT>;
     const int64_t tiles = (fa.T + TT - 1) / TT;
     const int64_t grid = fa.lead_blocks + 8 * (int64_t)fa.units_per_xcd * tiles;
     if (grid > 0x7fffffff) return hipErrorInvalidValue;
+    if constexpr (Gm::RB <= 64) {
+        if (fa.wpk && lean) {
+            static bool raised[16] = {};
+            hipError_t e = raise_lds_limit_once(raised, (const void *)k_lsa_fused_pk_lean<128, NB, TT>, Gm::pk_bytes);
+            if (e != hipSuccess) return e;
+            prof_begin(K_LSA_FUSED_PK_LEAN + 64 * (NB * 8 + TT), stream);
+            MOA_KLAUNCH((k_lsa_fused_pk_lean<128, NB, TT>), dim3((unsigned)grid), dim3(512), Gm::pk_bytes, stream, fa);
+            prof_end(stream);
+            return hipGetLastError();
+        }
+    }
     if (fa.wpk) {
         static bool raised[16] = {};
         hipError_t e = raise_lds_limit_once(raised, (const void *)k_lsa_fused_pk<128, NB, TT>, Gm::pk_bytes);
@@ -614,26 +642,34 @@ hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream)
     }
     fa.lead_blocks = fa.small_lead + ((((fa.red_blocks + 1) / 2) + 7) & ~7);   // a lead workgroup of 512 threads does two blocks of the pass
     // Rows per workgroup.  Measured at the Llama-3-8B shape (d_in 2048), a workgroup takes about 31 + 9 (rows / 32)
-    // microseconds whatever else runs (it is bound by its own chain of tile fetches from the L2 and its matrix work),
-    // and the chip runs 256 of them at a time: few tokens want small tiles (every compute unit busy), many tokens
-    // large ones (fewer passes over the weights).  Pick the tile that minimises rounds x time per round.
+    // microseconds from plain weights and 22 + 10.5 (rows / 32) from packed ones, whatever else runs (it is bound by
+    // its own chain of tile fetches from the L2 and its matrix work), and the chip runs 256 of them at a time: few
+    // tokens want small tiles (every compute unit busy), many tokens large ones (fewer passes over the weights).  Pick
+    // the tile that minimises rounds x time per round.
     const int nb = (c.L + 31) / 32;
     const bool big_ok = lds_limit() >= LsaFusedGeom<128, 1, 4>::bytes;      // the 128-row tiles fill the LDS to the last byte
+    const double fixed = fa.wpk ? 22.0 : 31.0, per_block = fa.wpk ? 10.5 : 9.0;
     auto cost = [&](int tt) {
         const double wgs = (double)fa.units * (double)((c.T + tt - 1) / tt);
-        return (wgs > 256.0 ? wgs / 256.0 : 1.0) * (31.0 + 9.0 * nb * tt);
+        return (wgs > 256.0 ? wgs / 256.0 : 1.0) * (fixed + per_block * nb * tt);
     };
+    // leave_room: another stream's kernels are meant to run beside this launch.  From packed weights that is the
+    // 64-row tile in its lean form, which shares a compute unit with them; from plain weights (LDS full either way) the
+    // largest tile, which leaves whole compute units empty.
+    const bool lean = c.leave_room && fa.wpk;
     if (nb == 1) {
         int best = 2;
-        if (cost(3) < cost(best)) best = 3;
-        if (big_ok && (cost(4) < cost(best) || c.leave_room)) best = 4;
+        if (!lean) {
+            if (cost(3) < cost(best)) best = 3;
+            if (big_ok && (cost(4) < cost(best) || c.leave_room)) best = 4;
+        }
         if (best == 4) return launch_lsa_fused_as<1, 4>(fa, stream);
         if (best == 3) return launch_lsa_fused_as<1, 3>(fa, stream);
-        return launch_lsa_fused_as<1, 2>(fa, stream);
+        return launch_lsa_fused_as<1, 2>(fa, stream, lean);
     }
     if (nb == 2) {
-        if (big_ok && (cost(2) < cost(1) || c.leave_room)) return launch_lsa_fused_as<2, 2>(fa, stream);
-        return launch_lsa_fused_as<2, 1>(fa, stream);
+        if (!lean && big_ok && (cost(2) < cost(1) || c.leave_room)) return launch_lsa_fused_as<2, 2>(fa, stream);
+        return launch_lsa_fused_as<2, 1>(fa, stream, lean);
     }
     return launch_lsa_fused_as<3, 1>(fa, stream);
 }

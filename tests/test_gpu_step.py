@@ -107,9 +107,10 @@ def _step_outputs(step):
 
 @pytest.mark.parametrize("case", ["small_bf16", "C1_bf16", "small_bf16_with_sa"])
 def test_schedules_agree(G, case):
-    """The step's result must not depend on how its independent pieces are launched: the two-stream schedule is
-    bit-identical to the sequential one; the grouped one too, except that the two attention cores may get another
-    number of key slices (their merged outputs then agree to rounding)."""
+    """The step's result must not depend on how its independent pieces are launched: what does not pass through a merge
+    of key slices is bit-identical under all three schedules; the grouped and the two-stream schedule launch the two
+    attention cores as one pair and agree bit for bit in everything; the sequential one may give the cores another
+    number of key slices (its merged outputs then agree with theirs to rounding)."""
     from paper_2410_03804_amd.workload import DeviceStep
     cfg, nlayers, lsa_tokens, with_sa = _case(case)
     work = mi.step_workload(cfg, n_verify_layers=nlayers, lsa_tokens=lsa_tokens, with_sa=with_sa)
@@ -127,12 +128,12 @@ def test_schedules_agree(G, case):
             for a, b in zip(ref_exact, exact):
                 assert torch.equal(a, b), name
             for a, b in zip(ref_merged, merged):
-                if name == "grouped":
-                    assert torch.allclose(a.float(), b.float(), atol=G.ABS_TOL[cfg.dtype], rtol=G.REL_TOL[cfg.dtype]), name
-                else:
-                    assert torch.equal(a, b), name
-    for a, b in zip(outs["grouped"][0][1], outs["grouped"][1][1]):
-        assert torch.equal(a, b)                 # and each schedule is deterministic
+                assert torch.allclose(a.float(), b.float(), atol=G.ABS_TOL[cfg.dtype], rtol=G.REL_TOL[cfg.dtype]), name
+    pair_ref = outs["grouped"][0][1]
+    for name in ("grouped", "two_stream"):       # the pair schedules agree with each other, and each is deterministic
+        for _, merged in outs[name]:
+            for a, b in zip(pair_ref, merged):
+                assert torch.equal(a, b), name
 
 
 @pytest.mark.parametrize("case", ["small_bf16", "C1_bf16", "C0_f32"])
