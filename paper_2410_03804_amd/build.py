@@ -49,5 +49,43 @@ def build(verbose: bool = False) -> Path:
     return LIB
 
 
+HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address,undefined", "-Xarch_host", "-fno-sanitize-recover=undefined"]
+
+
+def build_host_check_driver(out_dir=None) -> Path:
+    """The library's HOST code under AddressSanitizer + UndefinedBehaviorSanitizer, linked with csrc/host_check_driver.cpp
+    into an executable that a CPU test runs (no GPU: argument checks, workspace carving, the checks-only pass of a whole
+    step, the gzip pass).  Only the host side of every source is compiled; the device code objects the host stubs refer to
+    are replaced by empty ones, which is all a run without a device ever looks at."""
+    out = Path(out_dir or (HERE / "_build_host_check"))
+    out.mkdir(parents=True, exist_ok=True)
+    common = [_hipcc(), "--offload-arch=gfx950", "--cuda-host-only", "-O1", "-g", "-std=c++17", *HOST_SANITIZE]
+
+    def host_obj(src: str) -> Path:
+        obj = out / (Path(src).stem + ".o")
+        r = subprocess.run([*common, "-c", str(CSRC / src), "-o", str(obj)], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"host-only compile failed for {src}:\n{r.stderr}")
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+        objs = list(ex.map(host_obj, SOURCES))
+    drv = out / "host_check_driver.o"
+    subprocess.check_call([*common, "-x", "c++", "-c", str(CSRC / "host_check_driver.cpp"), "-o", str(drv)])
+    # the device code objects the kernels' host stubs point at: one empty, page-aligned object per source
+    syms = subprocess.check_output(["nm", *map(str, objs)], text=True)
+    names = sorted({l.split()[-1] for l in syms.splitlines() if " U __hip_fatbin_" in l})
+    stubs = out / "fatbin_stubs.cpp"
+    stubs.write_text("".join(
+        f'extern "C" __attribute__((section(".hip_fatbin"), aligned(4096), visibility("default"))) const unsigned char {n}[4096];\n'
+        f"const unsigned char {n}[4096] = {{0}};\n" for n in names))
+    stub_obj = out / "fatbin_stubs.o"
+    subprocess.check_call(["g++", "-c", str(stubs), "-o", str(stub_obj)])
+    exe = out / "moa_host_check"
+    subprocess.check_call([_hipcc(), "-fsanitize=address,undefined", "-fno-gpu-sanitize", "-o", str(exe), *map(str, objs), str(drv),
+                           str(stub_obj), "-lz"])
+    return exe
+
+
 if __name__ == "__main__":
     build(verbose=True)

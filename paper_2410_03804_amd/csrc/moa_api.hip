@@ -923,7 +923,8 @@ static TliBufs tli_carve(const moa_shape_t *s, int32_t d_ff, int32_t B, int32_t 
     const size_t es = esize(s->dtype), d = (size_t)s->d_model;
     TliBufs t;
     size_t off = 0;
-    auto take = [&](size_t bytes) { char *p = (char *)ws + off; off += align256(bytes); return p; };
+    // (sizes are measured with ws == NULL: no pointer arithmetic on a null base)
+    auto take = [&](size_t bytes) { char *p = ws ? (char *)ws + off : nullptr; off += align256(bytes); return p; };
     t.attn_bytes = align256(attn_ws_bytes(s, B, Mn, P_cap));
     t.attn = take(t.attn_bytes);
     t.lin_bytes = align256(max2(linear_workspace_bytes(s->dtype, R, s->d_model, 2 * d_ff),
@@ -1019,7 +1020,7 @@ static MlpBufs mlp_carve(int dtype, int64_t R, int d, int d_ff, void *ws, size_t
     const size_t es = esize(dtype);
     MlpBufs b;
     size_t off = 0;
-    auto take = [&](size_t bytes) { char *p = (char *)ws + off; off += align256(bytes); return p; };
+    auto take = [&](size_t bytes) { char *p = ws ? (char *)ws + off : nullptr; off += align256(bytes); return p; };
     b.lin_bytes = align256(max2(linear_workspace_bytes(dtype, R, d, 2 * d_ff), linear_workspace_bytes(dtype, R, d_ff, d)));
     b.lin = take(b.lin_bytes);
     b.n = take((size_t)R * d * es);
