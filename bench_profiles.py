@@ -78,6 +78,10 @@ def kernel_durations(db: str):
     return out
 
 
+# kernels a benchmark run launches outside its steps: ceiling probes, the one-time weight fold and weight packing
+SETUP_KERNELS = ("k_probe", "k_fold", "k_lsa_pack")
+
+
 def ours(name: str) -> bool:
     return name.startswith("k_")
 
@@ -138,7 +142,7 @@ def cmd_traffic(a):
     out.with_suffix(".md").write_text("\n".join(lines) + "\n")
     out.with_suffix(".json").write_text(json.dumps(dict(
         commit=head_commit(), workload=a.workload, fetch_scale=round(sf, 4), write_scale=round(sw, 4),
-        kernel_set=sorted(k for k in table if not k.startswith("k_probe") and not k.startswith("k_fold")),
+        kernel_set=sorted(k for k in table if not k.startswith(SETUP_KERNELS)),
         traffic_MiB_per_launch=table), indent=1) + "\n")
     print("\n".join(lines))
 
@@ -166,7 +170,7 @@ def cmd_counters(a):
     launches = {}
     for db in a.db:
         for k, cs in per_kernel_counters(db).items():
-            if not ours(k) or k.startswith("k_probe") or k.startswith("k_fold"):
+            if not ours(k) or k.startswith(SETUP_KERNELS):
                 continue
             for c, (n, v) in cs.items():
                 merged[k][c] = v
