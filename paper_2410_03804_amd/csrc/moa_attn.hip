@@ -633,8 +633,8 @@ __global__ __launch_bounds__(64 * NW) void k_attn_fused(AttnGroup grp, int nrb)
         const int dcol = 32 * (v0 >> 4) + 8 * ((v0 & 15) >> 2) + 4 * half;
         if (row_ok) {
             u32x2 pk;
-            pk[0] = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
-            pk[1] = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
+            pk[0] = pack_bf16x2(o[0], o[1]);
+            pk[1] = pack_bf16x2(o[2], o[3]);
             *(u32x2 *)(orow + dcol) = pk;
         }
     }
@@ -703,7 +703,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(AttnGroup grp, SplitGeom geo
     const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
     u32x4 pk;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) pk[w] = (uint32_t)f2bf(o[2 * w] * inv) | ((uint32_t)f2bf(o[2 * w + 1] * inv) << 16);
+    for (int w = 0; w < 4; ++w) pk[w] = pack_bf16x2(o[2 * w] * inv, o[2 * w + 1] * inv);
     *(u32x4 *)((bf16_t *)a.out + (((int64_t)b * a.Mq + m) * a.H + h) * DH + 8 * piece) = pk;
     if (lsum == 0.f && a.empty_is_error && piece == 0 && a.dev_status) atomicOr(a.dev_status, MOA_DEV_EMPTY_KEYS);
 }

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bf16v(const bf16_t *__restrict_
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const float glo = __uint_as_float(gv[i][e] << 16), ghi = __uint_as_float(gv[i][e] & 0xffff0000u);
-            o[e] = (uint32_t)f2bf(v[i][2 * e] * inv * glo) | ((uint32_t)f2bf(v[i][2 * e + 1] * inv * ghi) << 16);
+            o[e] = pack_bf16x2(v[i][2 * e] * inv * glo, v[i][2 * e + 1] * inv * ghi);
         }
         *(u32x4 *)(n_out + r * d + 8 * c) = o;
         if (h_out) {

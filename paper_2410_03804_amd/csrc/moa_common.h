@@ -20,13 +20,21 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 
 __device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round to nearest even; NaN stays NaN
+// round to nearest even; NaN stays NaN.  The hardware's own conversion (v_cvt_pk_bf16_f32 on this target): one
+// instruction per pair of values, where the integer formulation costs a dozen and a branch for the NaN case.
+typedef __attribute__((ext_vector_type(2))) float f32x2_cvt;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_cvt;
 __device__ __forceinline__ bf16_t f2bf(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+    const __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(bf16_t, h);
+}
+// two values rounded and packed: `lo` in bits 0..15, `hi` in bits 16..31
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    const f32x2_cvt v = {lo, hi};
+    const bf16x2_cvt h = __builtin_convertvector(v, bf16x2_cvt);
+    return __builtin_bit_cast(uint32_t, h);
 }
 
 template <typename T> __device__ __forceinline__ float ld(const T *p);

@@ -156,10 +156,10 @@ __global__ __launch_bounds__(256) void k_linear_skinny_bf16(SkinnyArgs sa)
         const int64_t off = store_offset(a.seg[s].st, r, n0 + 8 * fc);
         if (off < 0) continue;
         u32x4 pk;
-        pk[0] = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
-        pk[1] = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
-        pk[2] = (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
-        pk[3] = (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
+        pk[0] = pack_bf16x2(v[0], v[1]);
+        pk[1] = pack_bf16x2(v[2], v[3]);
+        pk[2] = pack_bf16x2(v[4], v[5]);
+        pk[3] = pack_bf16x2(v[6], v[7]);
         *(u32x4 *)(dst + off) = pk;
     }
 }
@@ -535,8 +535,8 @@ __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
                 const int n = n0 + wf0 + 32 * i + 8 * q + 4 * half;
                 const int64_t off = rp + store_feat_part(a.seg[s].st, n);
                 u32x2 pk;
-                pk[0] = (uint32_t)f2bf(acc[i][jj][4 * q + 0]) | ((uint32_t)f2bf(acc[i][jj][4 * q + 1]) << 16);
-                pk[1] = (uint32_t)f2bf(acc[i][jj][4 * q + 2]) | ((uint32_t)f2bf(acc[i][jj][4 * q + 3]) << 16);
+                pk[0] = pack_bf16x2(acc[i][jj][4 * q + 0], acc[i][jj][4 * q + 1]);
+                pk[1] = pack_bf16x2(acc[i][jj][4 * q + 2], acc[i][jj][4 * q + 3]);
                 *(u32x2 *)(dst + off) = pk;
             }
     }

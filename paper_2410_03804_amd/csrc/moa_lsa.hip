@@ -209,7 +209,7 @@ __global__ __launch_bounds__(256) void k_lsa_attn_mfma(LsaAttnArgs a)
     if (live && lane < CPR) {
         u32x4 pk;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) pk[w] = (uint32_t)f2bf(o[2 * w]) | ((uint32_t)f2bf(o[2 * w + 1]) << 16);
+        for (int w = 0; w < 4; ++w) pk[w] = pack_bf16x2(o[2 * w], o[2 * w + 1]);
         *(u32x4 *)((bf16_t *)a.abar + t * (int64_t)a.Hq * DH + (int64_t)h * DH + 8 * lane) = pk;
     }
 }

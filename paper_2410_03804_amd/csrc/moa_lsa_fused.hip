@@ -103,8 +103,8 @@ __device__ __forceinline__ void lsa_fused_epilogue(Acc &acc, const LsaFusedArgs 
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     u32x2 pk;
-                    pk[0] = (uint32_t)f2bf(acc[i][j][4 * q + 0]) | ((uint32_t)f2bf(acc[i][j][4 * q + 1]) << 16);
-                    pk[1] = (uint32_t)f2bf(acc[i][j][4 * q + 2]) | ((uint32_t)f2bf(acc[i][j][4 * q + 3]) << 16);
+                    pk[0] = pack_bf16x2(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1]);
+                    pk[1] = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
                     *(u32x2 *)&tile_s[(32 * j + l32) * TLD + f0 + 32 * i + 8 * q + 4 * half] = pk;
                 }
     }
@@ -212,7 +212,7 @@ __device__ __forceinline__ void lsa_fused_epilogue(Acc &acc, const LsaFusedArgs 
     if (live_wave && tok < a.T && lane < CPR) {
         u32x4 pk;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) pk[w] = (uint32_t)f2bf(o[2 * w]) | ((uint32_t)f2bf(o[2 * w + 1]) << 16);
+        for (int w = 0; w < 4; ++w) pk[w] = pack_bf16x2(o[2 * w], o[2 * w + 1]);
         *(u32x4 *)(a.abar + tok * (int64_t)a.Hq * DH + (int64_t)(g * G + 2 * part + hq) * DH + 8 * lane) = pk;
     }
 }

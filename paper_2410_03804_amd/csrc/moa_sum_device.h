@@ -29,10 +29,10 @@ __device__ __forceinline__ void splitk_sum8(const SumArgs &sa, const float *p, f
 __device__ __forceinline__ u32x4 pack8(const f32x4 &lo, const f32x4 &hi)
 {
     u32x4 pk;
-    pk[0] = (uint32_t)f2bf(lo[0]) | ((uint32_t)f2bf(lo[1]) << 16);
-    pk[1] = (uint32_t)f2bf(lo[2]) | ((uint32_t)f2bf(lo[3]) << 16);
-    pk[2] = (uint32_t)f2bf(hi[0]) | ((uint32_t)f2bf(hi[1]) << 16);
-    pk[3] = (uint32_t)f2bf(hi[2]) | ((uint32_t)f2bf(hi[3]) << 16);
+    pk[0] = pack_bf16x2(lo[0], lo[1]);
+    pk[1] = pack_bf16x2(lo[2], lo[3]);
+    pk[2] = pack_bf16x2(hi[0], hi[1]);
+    pk[3] = pack_bf16x2(hi[2], hi[3]);
     return pk;
 }
 
