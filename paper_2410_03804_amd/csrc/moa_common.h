@@ -37,6 +37,25 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, h);
 }
 
+// x summed over the 32 lanes that share lane / 32 (every one of them gets the sum).  Four of the five levels are
+// DPP moves inside the vector ALU -- neighbours in a quad, the other pair of the quad, then the mirror images within 8
+// and within 16 lanes, which after the levels before them hold exactly what the lanes 4 and 8 away hold -- and only the
+// last one (16 lanes away) goes through the LDS crossbar.  A butterfly of five shuffles costs five crossbar round trips.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move_f32(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float sum_over_lanes32(float x)
+{
+    x += dpp_move_f32<0xB1>(x);     // quad_perm [1, 0, 3, 2]
+    x += dpp_move_f32<0x4E>(x);     // quad_perm [2, 3, 0, 1]
+    x += dpp_move_f32<0x141>(x);    // row_half_mirror
+    x += dpp_move_f32<0x140>(x);    // row_mirror
+    x += __shfl_xor(x, 16);
+    return x;
+}
+
 template <typename T> __device__ __forceinline__ float ld(const T *p);
 template <> __device__ __forceinline__ float ld<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t *p) { return bf2f(*p); }

@@ -170,10 +170,7 @@ __global__ __launch_bounds__(256) void k_lsa_attn_mfma(LsaAttnArgs a)
     for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            float x = csum[jb][e];
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) x += __shfl_xor(x, o);
-            csum[jb][e] = x;
+            csum[jb][e] = sum_over_lanes32(csum[jb][e]);
         }
     if (l32 == 0) {
         const float invL = 1.0f / (float)L;
