@@ -32,6 +32,8 @@
 #include "moa_tree_device.h"
 
 #include <math.h>
+#include <type_traits>
+#include <utility>
 
 namespace moa {
 
@@ -70,7 +72,7 @@ struct LsaFusedGeom {
     static constexpr size_t epi_bytes = tile_bytes + pbar_bytes;
     static constexpr size_t bytes = loop_bytes > epi_bytes ? loop_bytes : epi_bytes;
     // the form that takes packed weights keeps them in registers: only a two-stage activation ring is left in LDS
-    static constexpr int WS = RB <= 64 ? 4 : 2;  // weight tiles held in registers per wavefront (what the registers left by the accumulators hold)
+    static constexpr int WS = 2;                 // weight tiles held in registers per wavefront: with the requests spread between the MFMAs two do as well as four
     static constexpr int UN = 8;                 // tile steps per trip of the tile loop (a multiple of WS)
     static constexpr size_t pk_loop_bytes = (size_t)2 * RB * BK * sizeof(bf16_t);
     static constexpr size_t pk_bytes = pk_loop_bytes > epi_bytes ? pk_loop_bytes : epi_bytes;
@@ -349,6 +351,19 @@ __global__ __launch_bounds__(512) void k_lsa_fused(LsaFusedArgs a)
     lsa_fused_epilogue<DH, NB, TT>(acc, a, sm, tile, g, part);
 }
 
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}): a loop whose index is a constant
+// expression in the body (register arrays indexed by it stay in registers)
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
 // The same kernel for weights that the caller has packed once into MFMA-operand order (k_lsa_pack_weights).  A
 // wavefront's slice of the weight tile is used by that wavefront alone, so with the operands already in lane order it
 // has no business in LDS: every 16-byte operand piece is loaded straight into the register that the MFMA reads, 1 KB
@@ -357,7 +372,7 @@ __global__ __launch_bounds__(512) void k_lsa_fused(LsaFusedArgs a)
 // flight per wavefront in registers, which the 160 KB of LDS could not hold.  The activation tile goes through
 // registers into a two-stage LDS ring (one bare barrier per tile); all loads are ordinary loads, so the waits are the
 // compiler's.  Same MFMA order along d_in as the unpacked form: same bits.
-template <int DH, int NB, int TT, int WS>
+template <int DH, int NB, int TT, int WS, bool SPREAD>
 __device__ __forceinline__ void lsa_fused_pk_body(const LsaFusedArgs &a)
 {
     using Gm = LsaFusedGeom<DH, NB, TT>;
@@ -436,35 +451,39 @@ __device__ __forceinline__ void lsa_fused_pk_body(const LsaFusedArgs &a)
         load_w(s < nk ? s : nk - 1, wr[s]);
     }
 
-    // The loop body carries no branch around a load: the compiler's load counter then stays exact inside a trip
-    // (partial waits), where a conditional request makes it wait for everything in flight.  Requests past the last
-    // tile repeat the last tile; a trip covers UN tile steps (at the top of a trip the compiler's wait is a
-    // conservative one, so trips are made long), and the surplus steps of the last trip skip only their arithmetic.
-    constexpr int UN = Gm::UN;
-    static_assert(UN % WS == 0, "a trip of the tile loop is a whole number of register-ring rounds");
-    const int nkr = (nk + UN - 1) / UN * UN;
-#pragma unroll 1
-    for (int kt0 = 0; kt0 < nkr; kt0 += UN) {
+    // One tile step on register stage S.  The activation tile of this step goes to LDS (the place was last read two
+    // tiles ago, before the previous barrier) and the one WS - 1 ahead is requested into the registers it leaves.
+    // Inside the step the weight requests are spread between the MFMAs: as soon as a k-step's MFMAs have been issued
+    // its weight registers are refilled with the same k-step of the tile WS ahead.  Issued in one burst at the top of
+    // a step, the requests of all eight wavefronts queue up at the compute unit's one address unit while the matrix
+    // cores wait (measured on a cut-down loop: 0.99 us per tile in a burst, 0.78 us spread out).  The scheduling
+    // barriers keep the compiler from regrouping them.  No branch surrounds a load: the compiler's load counter then
+    // stays exact (partial waits), where a conditional request makes it wait for everything in flight; requests past
+    // the last tile repeat the last tile.  GUARDED steps (the few behind the last whole trip) may lie past the last
+    // tile and then skip their arithmetic; they refill in one go behind it, and so do the forms without SPREAD (128-row
+    // tiles and the lean form: the spread-out order costs registers they do not have).
+    auto tile_step = [&](auto stage_c, auto guarded_c, int kt) {
+        constexpr int S = decltype(stage_c)::value;
+        constexpr bool GUARDED = decltype(guarded_c)::value;
+        const bf16_t *xb = xl + (kt & 1) * RB * BK;
+        {
+            bf16_t *xw = xl + (kt & 1) * RB * BK;
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int s = u % WS;
-            const int kt = kt0 + u;
-            bf16_t *xb = xl + (kt & 1) * RB * BK;
-            // the activation tile of this step goes to LDS (the place was last read two tiles ago, before the
-            // previous barrier); the tiles WS - 1 ahead are requested into the registers this step's tiles leave
+            for (int n = 0; n < NXI; ++n) *(bf16x8 *)&xw[xrow0[n] * BK + 8 * lane] = xr[S][n];
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        load_x(kt + WS - 1 < nk ? kt + WS - 1 : nk - 1, xr[(S + WS - 1) % WS]);
+        const int kw = kt + WS < nk ? kt + WS : nk - 1;
+        const bf16x8 *wnext = wp + (int64_t)kw * NWP * 64;
+        auto read_frags = [&](int ks, bf16x8 (&fb)[NRB]) {
 #pragma unroll
-            for (int n = 0; n < NXI; ++n) *(bf16x8 *)&xb[xrow0[n] * BK + 8 * lane] = xr[s][n];
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            const int ka = kt + WS - 1 < nk ? kt + WS - 1 : nk - 1;
-            load_x(ka, xr[(s + WS - 1) % WS]);
-            if (kt < nk) {
-                auto read_frags = [&](int ks, bf16x8 (&fb)[NRB]) {
-#pragma unroll
-                    for (int j = 0; j < NRB; ++j) {
-                        const int row = 32 * j + l32;
-                        fb[j] = *(const bf16x8 *)&xb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
-                    }
-                };
+            for (int j = 0; j < NRB; ++j) {
+                const int row = 32 * j + l32;
+                fb[j] = *(const bf16x8 *)&xb[row * BK + 8 * ((2 * ks + half) ^ ((row >> 1) & 7))];
+            }
+        };
+        if constexpr (GUARDED || !SPREAD) {
+            if (!GUARDED || kt < nk) {
                 bf16x8 bfr[2][NRB];
                 read_frags(0, bfr[0]);
 #pragma unroll
@@ -474,20 +493,47 @@ __device__ __forceinline__ void lsa_fused_pk_body(const LsaFusedArgs &a)
                     for (int i = 0; i < WFB; ++i)
 #pragma unroll
                         for (int j = 0; j < NRB; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[s][ks * WFB + i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[S][ks * WFB + i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
                 }
             }
-            // this step's weight registers are free now: the tile WS steps ahead goes there
-            load_w(kt + WS < nk ? kt + WS : nk - 1, wr[s]);
+            load_w(kw, wr[S]);
+        } else {
+            bf16x8 bfr[2][NRB];
+            read_frags(0, bfr[0]);
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                if (ks + 1 < BK / 16) read_frags(ks + 1, bfr[(ks + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < WFB; ++i)
+#pragma unroll
+                    for (int j = 0; j < NRB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[S][ks * WFB + i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < WFB; ++i) wr[S][ks * WFB + i] = wnext[(ks * WFB + i) * 64];
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-    }
+    };
+    // whole trips of UN steps (at the top of a trip the compiler's wait is a conservative one, so trips are long), then
+    // the remaining steps in rounds of WS
+    constexpr int UN = Gm::UN;
+    static_assert(UN % WS == 0, "a trip of the tile loop is a whole number of register-ring rounds");
+    const int nk_main = nk / UN * UN;
+#pragma unroll 1
+    for (int kt0 = 0; kt0 < nk_main; kt0 += UN)
+        static_for<UN>([&](auto u) { tile_step(std::integral_constant<int, decltype(u)::value % WS>{}, std::false_type{}, kt0 + decltype(u)::value); });
+    const int nk_end = nk_main + (nk - nk_main + WS - 1) / WS * WS;
+#pragma unroll 1
+    for (int kt0 = nk_main; kt0 < nk_end; kt0 += WS)
+        static_for<WS>([&](auto u) { tile_step(u, std::true_type{}, kt0 + decltype(u)::value); });
     lsa_fused_epilogue<DH, NB, TT>(acc, a, sm, tile, g, part);
 }
 
 template <int DH, int NB, int TT>
 __global__ __launch_bounds__(512) void k_lsa_fused_pk(LsaFusedArgs a)
 {
-    lsa_fused_pk_body<DH, NB, TT, LsaFusedGeom<DH, NB, TT>::WS>(a);
+    lsa_fused_pk_body<DH, NB, TT, LsaFusedGeom<DH, NB, TT>::WS, (LsaFusedGeom<DH, NB, TT>::RB <= 96)>(a);
 }
 
 // The same with two register stages and the compiler held to a third of a SIMD's registers per wavefront (168): beside
@@ -497,7 +543,7 @@ __global__ __launch_bounds__(512) void k_lsa_fused_pk(LsaFusedArgs a)
 template <int DH, int NB, int TT>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_lsa_fused_pk_lean(LsaFusedArgs a)
 {
-    lsa_fused_pk_body<DH, NB, TT, 2>(a);
+    lsa_fused_pk_body<DH, NB, TT, 2, false>(a);
 }
 
 // Packs Wq / Wk / Wv for k_lsa_fused_pk: piece (unit, wavefront, k tile, k step, feature block, lane) holds the 8
