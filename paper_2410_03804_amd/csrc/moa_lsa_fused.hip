@@ -498,17 +498,20 @@ __device__ __forceinline__ void lsa_fused_pk_body(const LsaFusedArgs &a)
             }
             load_w(kw, wr[S]);
         } else {
-            bf16x8 bfr[2][NRB];
+            // operand fragments of the next k-step are read ahead where the registers allow (64-row tiles)
+            constexpr int NBUF = NRB <= 2 ? 2 : 1;
+            bf16x8 bfr[NBUF][NRB];
             read_frags(0, bfr[0]);
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
-                if (ks + 1 < BK / 16) read_frags(ks + 1, bfr[(ks + 1) & 1]);
+                if (NBUF == 2 && ks + 1 < BK / 16) read_frags(ks + 1, bfr[(ks + 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < WFB; ++i)
 #pragma unroll
                     for (int j = 0; j < NRB; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[S][ks * WFB + i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[S][ks * WFB + i], bfr[ks % NBUF][j], acc[i][j], 0, 0, 0);
+                if (NBUF == 1 && ks + 1 < BK / 16) read_frags(ks + 1, bfr[0]);
 #pragma unroll
                 for (int i = 0; i < WFB; ++i) wr[S][ks * WFB + i] = wnext[(ks * WFB + i) * 64];
                 __builtin_amdgcn_sched_barrier(0);
@@ -533,7 +536,7 @@ __device__ __forceinline__ void lsa_fused_pk_body(const LsaFusedArgs &a)
 template <int DH, int NB, int TT>
 __global__ __launch_bounds__(512) void k_lsa_fused_pk(LsaFusedArgs a)
 {
-    lsa_fused_pk_body<DH, NB, TT, LsaFusedGeom<DH, NB, TT>::WS, (LsaFusedGeom<DH, NB, TT>::RB <= 96)>(a);
+    lsa_fused_pk_body<DH, NB, TT, LsaFusedGeom<DH, NB, TT>::WS, true>(a);
 }
 
 // The same with two register stages and the compiler held to a third of a SIMD's registers per wavefront (168): beside
@@ -685,13 +688,13 @@ hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream)
     }
     fa.lead_blocks = fa.small_lead + ((((fa.red_blocks + 1) / 2) + 7) & ~7);   // a lead workgroup of 512 threads does two blocks of the pass
     // Rows per workgroup.  Measured at the Llama-3-8B shape (d_in 2048), a workgroup takes about 31 + 9 (rows / 32)
-    // microseconds from plain weights and 22 + 10.5 (rows / 32) from packed ones, whatever else runs (it is bound by
+    // microseconds from plain weights and 10 + 11.7 (rows / 32) from packed ones, whatever else runs (it is bound by
     // its own chain of tile fetches from the L2 and its matrix work), and the chip runs 256 of them at a time: few
     // tokens want small tiles (every compute unit busy), many tokens large ones (fewer passes over the weights).  Pick
     // the tile that minimises rounds x time per round.
     const int nb = (c.L + 31) / 32;
     const bool big_ok = lds_limit() >= LsaFusedGeom<128, 1, 4>::bytes;      // the 128-row tiles fill the LDS to the last byte
-    const double fixed = fa.wpk ? 22.0 : 31.0, per_block = fa.wpk ? 10.5 : 9.0;
+    const double fixed = fa.wpk ? 10.0 : 31.0, per_block = fa.wpk ? 11.7 : 9.0;
     auto cost = [&](int tt) {
         const double wgs = (double)fa.units * (double)((c.T + tt - 1) / tt);
         return (wgs > 256.0 ? wgs / 256.0 : 1.0) * (fixed + per_block * nb * tt);
