@@ -697,7 +697,7 @@ hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream)
     const double fixed = fa.wpk ? 10.0 : 31.0, per_block = fa.wpk ? 11.7 : 9.0;
     auto cost = [&](int tt) {
         const double wgs = (double)fa.units * (double)((c.T + tt - 1) / tt);
-        return (wgs > 256.0 ? wgs / 256.0 : 1.0) * (fixed + per_block * nb * tt);
+        return ceil(wgs / 256.0) * (fixed + per_block * nb * tt);    // one workgroup per compute unit, all equally long: whole rounds
     };
     // leave_room: another stream's kernels are meant to run beside this launch.  From packed weights that is the
     // 64-row tile in its lean form, which shares a compute unit with them; from plain weights (LDS full either way) the
