@@ -21,12 +21,16 @@
 //              (2, 3 or 4 tokens at one 32-layer block each), chosen from the token count on the host.
 //  attention   the accumulators are rounded to the storage type and parked in LDS as a [RB x 4 dh] tile (the ring
 //              memory is reused); one wavefront per (token, query head): S^T = K Q^T by MFMA, fp32 softmax in
-//              registers, column means of P by a 32-lane butterfly, then abar = sum_j pbar_j V_j
-//              (mean_i(P V) = (1^T P / L) V, exact in real arithmetic).  The output projection follows in another
-//              launch on one row per token.
+//              registers, column means of P summed over the 32 query lanes (DPP moves, one shuffle), then
+//              abar = sum_j pbar_j V_j  (mean_i(P V) = (1^T P / L) V, exact in real arithmetic).  The output
+//              projection follows in another launch on one row per token.
 //
-// Arithmetic is that of the three-kernel form (same MFMA order along d_in, Q/K/V rounded once to the storage type),
-// so both give the same bits.
+// Three kernels share that second half: k_lsa_fused (plain weights, as above), k_lsa_fused_pk (weights packed once
+// into MFMA-operand order and read straight into registers; the form a step runs when it is given the packed copy)
+// and k_lsa_fused_pk_lean (the same held to a third of a SIMD's registers, for the two-stream schedule).
+//
+// Arithmetic is that of the three-kernel form (same MFMA order along d_in, Q/K/V rounded once to the storage type,
+// the same order of additions in the column sums), so all give the same bits.
 #include "moa_common.h"
 #include "moa_sum_device.h"
 #include "moa_tree_device.h"
