@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256, 2) void k_lm_head_argmax(LmHeadArgs a)
     const int n0 = tile * 64 + wave * 16;
     int wrow = n0 + li;
     if (wrow > a.V - 1) wrow = a.V - 1;                     // tokens past the end repeat the last one; masked below
-    const bf16_t *wp = a.W + (int64_t)wrow * a.K + 32 * kg;
+    const bf16_t *wp = a.W + (int64_t)wrow * a.K + 8 * kg;   // k slot (q, j, kg) is k = 128 q + 32 j + 8 kg
     const int nchunk = a.K / KS;
 
     // Piece c = tid + 256 i of the slice is row c / CPR, 16-byte column c % CPR: the column and the row's remainder
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256, 2) void k_lm_head_argmax(LmHeadArgs a)
 #pragma unroll
         for (int q = 0; q < NQ; ++q)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wf[set][q][j] = *(const bf16x8 *)(wp + (int64_t)kc * KS + 128 * q + 8 * j);
+            for (int j = 0; j < 4; ++j) wf[set][q][j] = *(const bf16x8 *)(wp + (int64_t)kc * KS + 128 * q + 32 * j);
     };
     load_x(0);
     load_w(0, 0);
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256, 2) void k_lm_head_argmax(LmHeadArgs a)
             for (int j = 0; j < 4; ++j) {
                 bf16x8 xf[4];
 #pragma unroll
-                for (int rb = 0; rb < 4; ++rb) xf[rb] = *(const bf16x8 *)&Xs[(16 * rb + li) * LDK + 128 * q + 32 * kg + 8 * j];
+                for (int rb = 0; rb < 4; ++rb) xf[rb] = *(const bf16x8 *)&Xs[(16 * rb + li) * LDK + 128 * q + 32 * j + 8 * kg];
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
                     acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[set][q][j], xf[rb], acc[rb], 0, 0, 0);
