@@ -9,7 +9,7 @@
  *    every buffer (inputs, outputs, caches, workspace); the library allocates no
  *    device memory and never frees.  What it keeps per device for the life of the
  *    process: the fixed scratch array of moa_tree_verify_attn_noalloc, and, once
- *    MOA_SCHED_TWO_STREAM has been used, one stream and two events.
+ *    MOA_SCHED_TWO_STREAM has been used, one stream and three events.
  *  - All work is enqueued on the caller's hipStream_t (passed as void*, NULL = the
  *    default stream).  No host synchronisation happens inside.  Argument checks
  *    that need only host values run before anything is launched; a failed check
@@ -373,11 +373,17 @@ int32_t moa_fold_projection(int32_t dtype, const void *w_outer, const void *w_in
  *    units are left over.  Same requirements as MOA_SCHED_GROUPED.  One side stream exists per device:
  *    steps of several host threads on one device are enqueued one after the other (a mutex), and the
  *    branch is joined back even when a launch fails half way.
+ *    With the Self-Attention layer (sa_emb != NULL) and the LSA as one kernel, the branches are cut differently:
+ *    `stream` carries the step's one long chain (tree masks, the Self-Attention layer, the CA query projection,
+ *    the CA core and its output projection), the library's stream the LSA with the memory append and then the
+ *    verification layers; a third event tells the CA core that the memory is complete.  The two attention
+ *    cores are then launches of their own.
  *  MOA_SCHED_SEQUENTIAL (2): every stage enqueued on `stream` in the order above, one launch
  *    per stage, exactly as the single entry points would.
  * Integer results are identical under all three; floating-point results of 0 and 1 are
- * bit-identical, those of 2 differ from them only where the two attention cores end up with a
- * different number of key slices (partials merged in another order). */
+ * bit-identical (without the Self-Attention layer), those of 2, and of 1 with that layer, differ from
+ * them only where the two attention cores end up with a different number of key slices (partials
+ * merged in another order). */
 enum { MOA_SCHED_GROUPED = 0, MOA_SCHED_TWO_STREAM = 1, MOA_SCHED_SEQUENTIAL = 2 };
 
 typedef struct {

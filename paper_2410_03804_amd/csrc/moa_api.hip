@@ -838,17 +838,29 @@ int32_t moa_self_attn_draft(const moa_shape_t *shape, const void *emb, int32_t B
 }
 
 // the optional Self-Attention layer in front of the cross-attention: tree mask, then the layer on the whole tree
-static int32_t step_self_attn(const moa_step_args_t *a)
+static int32_t step_self_attn_check(const moa_step_args_t *a)
 {
     if (!a->sa_shape || !a->sa_out) return fail(MOA_ERR_NULL, "draft_step: sa_shape / sa_out is NULL");
     if (a->Mq != a->M) return fail(MOA_ERR_SHAPE, "draft_step: the Self-Attention layer needs Mq == M");
     if (a->sa_shape->d_model != a->shape->d_model || a->sa_shape->dtype != a->shape->dtype)
         return fail(MOA_ERR_SHAPE, "draft_step: sa_shape must have the step's d_model and dtype");
-    int32_t rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, a->stream);
-    if (rc) return rc;
+    return MOA_OK;
+}
+
+static int32_t step_self_attn_layer(const moa_step_args_t *a, void *ws, size_t ws_bytes, void *stream)
+{
     return moa_self_attn_draft(a->sa_shape, a->sa_emb, a->B, a->M, 0, a->M, a->sa_wq, a->sa_wk, a->sa_wv, a->sa_wo,
                                a->sa_kcache, a->sa_vcache, a->prefix_len, a->sa_P_cap, a->mask, a->sa_out,
-                               a->sa_k_draft, a->sa_v_draft, a->dev_status, a->ws, a->ws_bytes, a->stream);
+                               a->sa_k_draft, a->sa_v_draft, a->dev_status, ws, ws_bytes, stream);
+}
+
+static int32_t step_self_attn(const moa_step_args_t *a)
+{
+    int32_t rc = step_self_attn_check(a);
+    if (rc) return rc;
+    rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, a->stream);
+    if (rc) return rc;
+    return step_self_attn_layer(a, a->ws, a->ws_bytes, a->stream);
 }
 
 // ---- a reused LLM decoder layer (Target Layer Inference)
@@ -1210,44 +1222,53 @@ static int32_t piece_small(const moa_step_args_t *a, const StepBufs &bf, hipStre
     return MOA_OK;
 }
 
-// cross-attention queries + first verification layer's Q/K/V in one launch
+// cross-attention queries + first verification layer's Q/K/V in one launch (which = 3), or the queries (1) or the
+// verification layer's three (2) alone
 // with_small: the integer work rides in spare workgroups of this launch's grid instead of being a launch of its
 // own (nothing before the LSA chain's append and the attention cores needs its results).  sum_out: the pass that
 // adds up this projection's K slices is left to the caller (scr is then a region nobody else writes until that pass
 // has run).
 static int32_t piece_projections(const moa_step_args_t *a, const StepBufs &bf, void *scr, size_t scr_bytes, hipStream_t st,
-                                 bool with_small, SumArgs *sum_out = nullptr)
+                                 bool with_small, SumArgs *sum_out = nullptr, int which = 3)
 {
     const moa_shape_t *sh = a->shape;
     const int dh = sh->head_dim, Hkv = sh->n_kv_heads, d = sh->d_model, M = a->M;
     const int e = sh->n_q_heads * dh, ekv = Hkv * dh;
     LinArgs la = {};
-    la.X = a->ca_xq;
     la.R = (int64_t)a->B * M;
     la.K = d;
     la.ldx = d;
     la.ws = scr;
     la.ws_bytes = scr_bytes;
-    la.nseg = 4;
-    la.seg[0].W = a->ca_wq;
-    la.seg[0].N = e;
-    la.seg[0].st = row_store(bf.q_ca, e);
-    la.seg[1].W = a->v_wq_host[0];
-    la.seg[1].N = e;
-    la.seg[1].st = row_store(bf.q_v, e);
-    la.seg[2].W = a->v_wk_host[0];
-    la.seg[2].N = ekv;
-    la.seg[2].st = heads_store(a->v_ktree_host[0], Hkv, dh, M, M);
-    la.seg[3].W = a->v_wv_host[0];
-    la.seg[3].N = ekv;
-    la.seg[3].st = heads_store(a->v_vtree_host[0], Hkv, dh, M, M);
-    for (int i = 1; i < 4; ++i) { la.seg[i].X = a->v_x_host[0]; la.seg[i].ldx = d; }
+    if (which & 1) {
+        LinSeg &q = la.seg[la.nseg++];
+        q.W = a->ca_wq;
+        q.N = e;
+        q.st = row_store(bf.q_ca, e);
+        q.X = a->ca_xq;
+        q.ldx = d;
+    }
+    if (which & 2) {
+        const void *w[3] = {a->v_wq_host[0], a->v_wk_host[0], a->v_wv_host[0]};
+        const StoreSpec st3[3] = {row_store(bf.q_v, e), heads_store(a->v_ktree_host[0], Hkv, dh, M, M),
+                                  heads_store(a->v_vtree_host[0], Hkv, dh, M, M)};
+        for (int i = 0; i < 3; ++i) {
+            LinSeg &g = la.seg[la.nseg++];
+            g.W = w[i];
+            g.N = i == 0 ? e : ekv;
+            g.st = st3[i];
+            g.X = a->v_x_host[0];
+            g.ldx = d;
+        }
+    }
+    la.X = la.seg[0].X;
+    la.seg[0].X = nullptr;               // the first segment reads the launch's own rows
     if (with_small) {
         la.rider = small_args(a, bf);
         la.rider_units = 2 * a->B + 1;
     }
     la.sum_out = sum_out;
-    prof_set_site(S_PAIR_QKV);
+    prof_set_site(which == 3 ? S_PAIR_QKV : which == 1 ? S_CA_QPROJ : S_VERIFY_QKV);
     MOA_TRY_HIP(launch_linear(sh->dtype, la, st), "draft_step: projections");
     return MOA_OK;
 }
@@ -1490,11 +1511,11 @@ static int32_t draft_step_grouped(const moa_step_args_t *a)
 //         -> both output projections -> further verification layers
 // (When the LSA cannot run as the one kernel, the integer work rides with the projections and the main branch waits
 // for E_join before the memory append.)
-// One side stream and one pair of events exist per device; a mutex is held while a step is being enqueued, so steps of
+// One side stream and its events (fork, join, and one more for the schedule with the Self-Attention layer) exist per device; a mutex is held while a step is being enqueued, so steps of
 // several host threads on one device are enqueued one after the other.
 struct SideStream {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, mid = nullptr;
     bool ok = false;
     std::mutex enqueue;
 };
@@ -1514,7 +1535,8 @@ static SideStream *side_stream_for_current_device()
     if (!s.stream) {
         s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
                hipEventCreateWithFlags(&s.fork, kEdgeFlags) == hipSuccess &&
-               hipEventCreateWithFlags(&s.join, kEdgeFlags) == hipSuccess;
+               hipEventCreateWithFlags(&s.join, kEdgeFlags) == hipSuccess &&
+               hipEventCreateWithFlags(&s.mid, kEdgeFlags) == hipSuccess;
     }
     return s.ok ? &s : nullptr;
 }
@@ -1617,6 +1639,122 @@ static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
     return rc;
 }
 
+// ---- two streams with the Self-Attention layer.
+// With that layer the step has one long chain -- tree masks -> SA projections -> SA core -> SA output projection ->
+// cross-attention query projection -> cross-attention core -> its output projection -- of launches that each leave
+// most of the chip idle, and two shorter chains nothing in front of the cross-attention core depends on: the LSA with
+// the memory append (needed by that core only) and the first verification layer.  The long chain stays on the
+// caller's stream; the other two run one after the other on the library's:
+//   main: tree masks -> E_fork -> SA layer -> CA query projection -> wait E_mid -> CA core -> CA output projection
+//         -> wait E_join
+//   side: wait E_fork -> [LSA + the step's other integer work] -> LSA W_o + memory append -> E_mid
+//         -> verification Q/K/V -> verification core -> its output projection -> further layers -> E_join
+// The masks are built once, in front of the fork, for both branches to read.
+static bool two_stream_takes_sa(const moa_step_args_t *args, const moa_step_args_t *a)
+{
+    if (!two_stream_lsa_fused(a) || a->n_verify_layers < 1) return false;
+    const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
+    return attn_ws_bytes(args->sa_shape, args->B, args->M, args->sa_P_cap) <= L.scratch;
+}
+
+// The side branch in the three parts the enqueue order below needs.
+struct SaSideState {
+    LsaBufs b;
+    bool fold;
+    LinSeg folded[2];
+};
+
+static int32_t two_stream_sa_side_lsa(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes,
+                                      hipStream_t side, SaSideState *st)
+{
+    const moa_shape_t *sh = a->shape;
+    const int64_t T = a->T_lsa;
+    int32_t rc = lsa_check(sh, a->lsa_hs, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, a->lsa_out, scr, scr_bytes);
+    if (rc) return rc;
+    st->b = lsa_carve(sh, T, scr, scr_bytes);
+    void *abar = a->lsa_wo ? (void *)st->b.abar0 : a->lsa_out;
+    LsaFusedCall fc = lsa_fused_call(sh, a->lsa_hs, 0, T, a->lsa_wq, a->lsa_wk, a->lsa_wv, abar, step_lsa_packed(a));
+    fc.leave_room = 1;
+    fc.rider = small_args(a, bf);        // accept walk, old memory lengths
+    fc.rider.skip_masks = 1;             // built in front of the fork
+    fc.rider_units = 2 * a->B + 1;
+    prof_set_site(S_LSA_FUSED);
+    MOA_TRY_HIP(launch_lsa_fused(fc, side), "lsa: fused kernel");
+    return MOA_OK;
+}
+
+static int32_t two_stream_sa_side_memory(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes,
+                                         hipStream_t side, SaSideState *st)
+{
+    const moa_shape_t *sh = a->shape;
+    st->fold = a->lsa_wo && folded_segments(a, bf, st->folded);
+    if (a->lsa_wo) {
+        const LinArgs lo = lsa_oproj_args(sh, 0, a->T_lsa, a->lsa_wo, a->lsa_out, st->b, st->folded, st->fold ? 2 : 0);
+        prof_set_site(S_LSA_OPROJ);
+        MOA_TRY_HIP(launch_linear(sh->dtype, lo, side), "lsa: output projection");
+    }
+    return st->fold ? MOA_OK : piece_append(a, bf, scr, scr_bytes, side);
+}
+
+static int32_t two_stream_sa_side_verify(const moa_step_args_t *a, const StepBufs &bf, char *scr, size_t scr_bytes,
+                                         size_t attn_each, hipStream_t side)
+{
+    int32_t rc = piece_projections(a, bf, scr, scr_bytes, side, false, nullptr, 2);
+    if (rc) return rc;
+    const AttnArgs ve = piece_verify_core_args(a, bf, scr, attn_each);
+    prof_set_site(S_VERIFY_CORE);
+    MOA_TRY_HIP(launch_attn(ve, side), "draft_step: verification core");
+    rc = piece_oproj(a, bf, 2, scr, scr_bytes, side);
+    if (rc) return rc;
+    return piece_more_verify_layers(a, scr, scr_bytes, side);
+}
+
+// Enqueue order matters beyond the order inside each stream: the runtime settles where in the producing stream a
+// cross-stream wait takes hold when the waiting stream's next launch is submitted, and takes that stream's tail at that
+// moment.  So each wait is followed at once by the launch that needs it, before the producing stream is given
+// anything further (measured: with the whole main chain enqueued ahead of the side branch's first launch, that
+// launch started only after the chain, 59 us late).
+static int32_t draft_step_concurrent_sa(const moa_step_args_t *args, const moa_step_args_t *a, SideStream *ss)
+{
+    hipStream_t main = (hipStream_t)a->stream, side = ss->stream;
+    const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
+    char *scr_main = nullptr;
+    const StepBufs bf = carve_step_bufs(a, L, &scr_main);
+    char *scr_side = scr_main + L.scratch;
+    std::lock_guard<std::mutex> lk(ss->enqueue);
+
+    int32_t rc = moa_tree_build(a->parent, a->B, a->M, a->mask, a->depth, a->dev_status, main);
+    if (rc) return rc;
+    MOA_TRY_HIP(hipEventRecord(ss->fork, main), "draft_step: fork");
+    MOA_TRY_HIP(hipStreamWaitEvent(side, ss->fork, 0), "draft_step: fork");
+    // From here on the side stream is joined back into the caller's whatever happens (see draft_step_concurrent).
+    SaSideState st;
+    rc = two_stream_sa_side_lsa(a, bf, scr_side, L.scratch, side, &st);
+    if (rc == MOA_OK) rc = step_self_attn_layer(args, scr_main, L.scratch, main);
+    if (rc == MOA_OK) rc = piece_projections(a, bf, scr_main, L.scratch, main, false, nullptr, 1);
+    if (rc == MOA_OK) rc = two_stream_sa_side_memory(a, bf, scr_side, L.scratch, side, &st);
+    if (rc == MOA_OK) {
+        hipError_t e = hipEventRecord(ss->mid, side);
+        if (e == hipSuccess) e = hipStreamWaitEvent(main, ss->mid, 0);
+        if (e != hipSuccess) rc = hip_fail(e, "draft_step: memory ready");
+    }
+    if (rc == MOA_OK) {
+        const AttnArgs ca = piece_ca_core_args(a, bf, scr_main, L.attn_each);
+        prof_set_site(S_CA_CORE);
+        const hipError_t e = launch_attn(ca, main);
+        if (e != hipSuccess) rc = hip_fail(e, "draft_step: cross-attention core");
+    }
+    if (rc == MOA_OK) rc = two_stream_sa_side_verify(a, bf, scr_side, L.scratch, L.attn_each, side);
+    const hipError_t ej = hipEventRecord(ss->join, side);
+    if (rc == MOA_OK && ej != hipSuccess) rc = hip_fail(ej, "draft_step: join");
+    if (rc == MOA_OK) rc = piece_oproj(a, bf, 1, scr_main, L.scratch, main);
+    if (ej == hipSuccess) {
+        const hipError_t e = hipStreamWaitEvent(main, ss->join, 0);
+        if (rc == MOA_OK && e != hipSuccess) rc = hip_fail(e, "draft_step: join");
+    }
+    return rc;
+}
+
 int32_t moa_draft_step(const moa_step_args_t *args)
 {
     if (!args) return fail(MOA_ERR_NULL, "draft_step: args is NULL");
@@ -1641,17 +1779,18 @@ int32_t moa_draft_step(const moa_step_args_t *args)
     if (rc == MOA_OK) rc = draft_step_stages(a);
     g_dry = false;
     if (rc) return rc;
-    // The layer runs in front of whichever schedule follows (whose first launch writes the same masks again).
+    // grouped launches by default; two streams on request when the workspace has room for both branches'
+    // scratch; otherwise one stage after another
+    const bool two = a->schedule == MOA_SCHED_TWO_STREAM && pieces_ok(a) && a->ws_bytes >= two_stream_bytes(a);
+    SideStream *ss = two ? side_stream_for_current_device() : nullptr;
+    // On two streams the layer is one branch's first piece; otherwise it runs in front of whichever schedule follows
+    // (whose first launch writes the same masks again).
+    if (sa && ss && two_stream_takes_sa(args, a)) return draft_step_concurrent_sa(args, a, ss);
     if (sa) {
         rc = step_self_attn(args);
         if (rc) return rc;
     }
-    // grouped launches by default; two streams on request when the workspace has room for both branches'
-    // scratch; otherwise one stage after another
-    if (a->schedule == MOA_SCHED_TWO_STREAM && pieces_ok(a) && a->ws_bytes >= two_stream_bytes(a)) {
-        SideStream *ss = side_stream_for_current_device();
-        if (ss) return draft_step_concurrent(a, ss);
-    }
+    if (ss) return draft_step_concurrent(a, ss);
     if (a->schedule != MOA_SCHED_SEQUENTIAL && can_group(a)) return draft_step_grouped(a);
     return draft_step_stages(a);
 }

@@ -165,6 +165,7 @@ struct StepSmallArgs {
     uint64_t *mask;
     int32_t *depth, *path, *n_path, *bonus, *ca_len, *old_len, *dev_status;
     int B, M, cap;
+    int skip_masks;          // the tree masks are built elsewhere in the step: units [0, B) do nothing
 };
 hipError_t launch_step_small(const StepSmallArgs &a, hipStream_t stream);
 

@@ -108,7 +108,7 @@ __device__ __forceinline__ void append_length_one(int b, const int32_t *__restri
 __device__ __forceinline__ void step_small_unit(const StepSmallArgs &a, int unit, int32_t *par, int32_t *tk)
 {
     if (unit < a.B) {
-        tree_build_block(unit, a.parent, a.M, a.mask, a.depth, a.dev_status, par);
+        if (!a.skip_masks) tree_build_block(unit, a.parent, a.M, a.mask, a.depth, a.dev_status, par);
     } else if (unit < 2 * a.B) {
         tree_accept_block(unit - a.B, a.parent, a.tok, a.tgt, a.M, a.path, a.n_path, a.bonus, par, tk);
     } else {
