@@ -122,7 +122,7 @@ enum KernelId {
     K_TREE_BUILD = 0, K_TREE_ACCEPT, K_APPEND_LEN, K_LIN_GENERIC, K_LIN_SKINNY, K_LIN_SPLITK, K_LIN_REDUCE, K_LIN_TILED, K_SCATTER,
     K_ATTN_GENERIC, K_ATTN_MFMA, K_ATTN_MERGE, K_LSA_ATTN, K_LSA_ATTN_MFMA, K_STEP_SMALL, K_ATTN_FUSED, K_PROBE_READ, K_PROBE_MFMA,
     K_RMSNORM, K_ROPE, K_SWIGLU, K_ADD_OUT, K_TREE_EXPAND, K_TREE_FINALIZE, K_TOPK_LOGPROB,
-    K_LM_HEAD, K_LM_HEAD_REDUCE, K_TOPK_MERGE, K_MSG_TREE, K_MSG_ACCEPT, K_LIN_SPLITK_CHUNKED, K_LSA_FUSED, K_LSA_FUSED_PK, K_LSA_PACK, K_LSA_FUSED_PK_LEAN, K_COUNT
+    K_LM_HEAD, K_LM_HEAD_REDUCE, K_TOPK_MERGE, K_MSG_TREE, K_MSG_ACCEPT, K_LIN_SPLITK_CHUNKED, K_LSA_FUSED, K_LSA_FUSED_PK, K_LSA_PACK, K_LSA_FUSED_PK_LEAN, K_LIN_SPLITK_XRES, K_COUNT
 };
 enum SiteId {
     S_NONE = 0, S_TREE_BUILD, S_LSA_QKV, S_LSA_ATTN, S_LSA_OPROJ, S_APPEND_KV, S_APPEND_LEN, S_CA_QPROJ, S_CA_CORE,

@@ -344,6 +344,124 @@ __global__ __launch_bounds__(256, 3) void k_linear_splitk_chunked_bf16(SplitKArg
         if (16 * rb + li < a.R) *(f32x4 *)(p + (int64_t)(16 * rb + li) * sa.ntot) = acc[rb];
 }
 
+// The same sums with the activation slice resident: a workgroup owns one 1024-wide K slice of one activation matrix for
+// its whole life -- the slice [64 rows x 1024] is parked in LDS once (132 KB, so one workgroup per compute unit) -- and
+// its wavefronts each stream the weight rows of 16-feature groups through registers, 256 columns at a time with the
+// next 256 in flight.  After the one barrier behind the staging nothing in the loop waits for another wavefront: no
+// barrier per chunk, no activation re-reads (the chunked form above pulls as many activation bytes from the L2 as
+// weight bytes from HBM), every wavefront keeps two chunks of loads in flight from its first instruction to its last.
+// The grid is planned on the host so that every compute unit gets one workgroup and every wavefront the same number of
+// groups: segments that read different activations are classes of their own, each with its share of the workgroups.
+// Partial sums go where the chunked form puts them (same K slices, same order of MFMAs along K: same bits), and the
+// same pass adds them up.
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
+
+struct XresArgs {
+    SplitKArgs k;
+    int ncls;
+    int wg0[5];          // first workgroup of each class behind the lead blocks; [ncls] = all
+    int g0[5];           // first 16-feature group of each class; [ncls] = all groups
+    int gpw[4];          // groups per workgroup
+    const void *X[4];    // the class's activations
+    int64_t ldx[4];
+};
+
+__global__ __launch_bounds__(1024) void k_linear_splitk_xres_bf16(XresArgs xa)
+{
+    constexpr int KS = 1024, LDK = KS + 8, CW = 256, NCH = KS / CW;
+    extern __shared__ __attribute__((aligned(16))) bf16_t Xs[];   // [64][LDK]
+    const SplitKArgs &sa = xa.k;
+    const LinArgs &a = sa.a;
+    if ((int)blockIdx.x < sa.lead_blocks) {        // the first workgroups of the grid carry the integer work
+        if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
+            step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)Xs, (int32_t *)Xs + MOA_MAX_TREE);
+        return;
+    }
+    const int bx = (int)blockIdx.x - sa.lead_blocks;
+    int cls = 0;
+    while (cls + 1 < xa.ncls && bx >= xa.wg0[cls + 1]) ++cls;
+    const int rel = bx - xa.wg0[cls];
+    const int split = rel % sa.splits, fr = rel / sa.splits;
+    const int nthreads = (int)blockDim.x, nw = nthreads >> 6;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, kg = lane >> 4;
+    const int k0 = split * KS;
+    const int gbeg = xa.g0[cls] + fr * xa.gpw[cls];
+    int gend = gbeg + xa.gpw[cls];
+    if (gend > xa.g0[cls + 1]) gend = xa.g0[cls + 1];
+    if (gbeg >= gend) return;                       // (the host plans no such workgroup) leaves before the barrier, whole
+
+    // weight rows of group g for this lane: k slot (q, j, kg) of chunk c is k = 256 c + 128 q + 32 j + 8 kg
+    auto wrow = [&](int g) {
+        if (g > gend - 1) g = gend - 1;             // a request past the wavefront's last group repeats a valid one
+        const int tile = g >> 2;
+        int s = 0;
+        while (s + 1 < a.nseg && tile >= sa.tile_begin[s + 1]) ++s;
+        const int n = (tile - sa.tile_begin[s]) * 64 + (g & 3) * 16 + li;
+        return (const bf16_t *)a.seg[s].W + (int64_t)n * a.K + k0 + 8 * kg;
+    };
+    bf16x8 wf[2][8];
+    auto load_w = [&](int set, const bf16_t *wp, int c) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wf[set][q * 4 + j] = *(const bf16x8 *)(wp + CW * c + 128 * q + 32 * j);
+    };
+    int g = gbeg + wave;
+    const bf16_t *wp = wrow(g);
+    load_w(0, wp, 0);                               // on their way while the activations are staged
+
+    // the activation slice, once, from global memory straight into LDS: instruction t fills the 1 KB half t % 2 of row
+    // t / 2; rows past the end repeat the last row (their sums are never stored).  Nothing waits inside the loop.
+    {
+        const bf16_t *X = (const bf16_t *)xa.X[cls] + k0 + 8 * lane;
+        const int64_t ldx = xa.ldx[cls];
+        for (int t = wave; t < 128; t += nw) {
+            const int row = t >> 1, h = t & 1;
+            const int rsrc = row < a.R ? row : (int)a.R - 1;
+            __builtin_amdgcn_global_load_lds((global_void_t *)(X + (int64_t)rsrc * ldx + 512 * h),
+                                             (lds_void_t *)(Xs + row * LDK + 512 * h), 16, 0, 0);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+
+    // A wavefront's groups one after the other; the chunk after the one being multiplied is always in flight, across
+    // the end of a group too.
+    for (; g < gend; g += nw) {
+        // (the slice in LDS does not change any more, and the compiler knows: without this it reads all of a group's
+        // operand fragments ahead of the loop, into five hundred registers it does not have)
+        asm volatile("" ::: "memory");
+        const bf16_t *wnext = wrow(g + nw);
+        f32x4 acc[4];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int set = c & 1;
+            if (c + 1 < NCH) load_w(set ^ 1, wp, c + 1);
+            else load_w(set ^ 1, wnext, 0);
+            __builtin_amdgcn_sched_barrier(0);      // the requests stay up here, a whole chunk ahead of their use
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    bf16x8 xf[4];
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb) xf[rb] = *(const bf16x8 *)&Xs[(16 * rb + li) * LDK + CW * c + 128 * q + 32 * j + 8 * kg];
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb)
+                        acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[set][q * 4 + j], xf[rb], acc[rb], 0, 0, 0);
+                }
+        }
+        // lane holds features 4 kg .. 4 kg + 3 of the group for row 16 rb + li
+        float *pp = sa.part + (int64_t)split * 64 * sa.ntot + g * 16 + 4 * kg;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+            if (16 * rb + li < a.R) *(f32x4 *)(pp + (int64_t)(16 * rb + li) * sa.ntot) = acc[rb];
+        wp = wnext;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_linear_splitk_reduce(SumArgs sa) { splitk_reduce_block(sa, (int)blockIdx.x, (int)threadIdx.x); }
 
 hipError_t launch_splitk_sum(const SumArgs &sa, hipStream_t stream)
@@ -414,8 +532,6 @@ struct TiledArgs {
 // row r lives at position c ^ ((r >> 1) & 7), applied to the global address each lane fetches (the eight
 // lanes of a row still cover the same 128 bytes).  The loads of tile kt+1 are issued before the MFMAs of tile
 // kt and complete behind them; one barrier per k tile publishes the new tile and retires the old one.
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_void_t;
 
 template <int WF, int WR>
 __global__ __launch_bounds__(256) void k_linear_tiled_bf16(TiledArgs ta)
@@ -613,6 +729,94 @@ static LinPath linear_path(int dtype, const LinArgs &a, int *nq_out)
 
 static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode, bool *fused);
 
+// the pass that adds up the K slices a weight-streaming kernel has left in ka.part: launched, or handed to the caller
+static hipError_t finish_splitk(const LinArgs &a, const SplitKArgs &ka, int ntot, hipStream_t stream, bool *fused)
+{
+    *fused = a.epi != LinArgs::EPI_NONE;
+    SumArgs sum = {};
+    const int64_t items = a.R * ((a.epi == LinArgs::EPI_SWIGLU ? ntot / 2 : ntot) / 8);
+    sum.blocks = (int)((items + 255) / 256);
+    sum.R = a.R;
+    sum.nseg = a.nseg;
+    for (int s = 0; s < a.nseg; ++s) sum.st[s] = a.seg[s].st;
+    for (int s = 0; s <= a.nseg; ++s) sum.tile_begin[s] = ka.tile_begin[s];
+    sum.splits = ka.splits;
+    sum.ntot = ntot;
+    sum.part = ka.part;
+    sum.epi = a.epi;
+    sum.epi_res = a.epi_res;
+    sum.epi_out = a.epi_out;
+    if (a.sum_out) {                         // the caller has it carried by a later launch, or launches it
+        *a.sum_out = sum;
+        return hipSuccess;
+    }
+    return launch_splitk_sum(sum, stream);
+}
+
+// Grid of the resident-activation kernel for a projection whose K slices are 1024 wide (ka.splits of them): one
+// workgroup per compute unit, classes = runs of segments that read the same activations, each class with a share of
+// the workgroups in proportion to its features, every wavefront of a workgroup one 16-feature group (or the same
+// small number of them).  False when the shape does not fill the chip that way.
+static bool plan_xres(const SplitKArgs &ka, XresArgs *xa, int *nw_out)
+{
+    const LinArgs &a = ka.a;
+    const int S = ka.splits;
+    if (a.R > 64 || a.K % 1024 || S < 1 || S * 1024 != a.K) return false;
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cus = n;
+    }
+    const int per_split = cus / S;               // workgroups per K slice
+    if (per_split < 1) return false;
+    xa->k = ka;
+    xa->ncls = 0;
+    int groups[4] = {0, 0, 0, 0}, g = 0;
+    for (int s = 0; s < a.nseg; ++s) {
+        const void *X = a.seg[s].X ? a.seg[s].X : a.X;
+        const int64_t ldx = a.seg[s].X ? a.seg[s].ldx : a.ldx;
+        if (xa->ncls == 0 || X != xa->X[xa->ncls - 1] || ldx != xa->ldx[xa->ncls - 1]) {
+            xa->X[xa->ncls] = X;
+            xa->ldx[xa->ncls] = ldx;
+            xa->g0[xa->ncls] = g;
+            ++xa->ncls;
+        }
+        groups[xa->ncls - 1] += a.seg[s].N / 16;
+        g += a.seg[s].N / 16;
+    }
+    xa->g0[xa->ncls] = g;
+    if (xa->ncls > per_split) return false;
+    // workgroups per class and K slice: in proportion to the groups, the remainder to whoever has most groups per workgroup
+    int wg[4], left = per_split;
+    for (int c = 0; c < xa->ncls; ++c) {
+        wg[c] = (int)((int64_t)per_split * groups[c] / g);
+        if (wg[c] < 1) wg[c] = 1;
+        left -= wg[c];
+    }
+    if (left < 0) return false;
+    for (; left > 0; --left) {
+        int best = 0;
+        for (int c = 1; c < xa->ncls; ++c)
+            if ((int64_t)groups[c] * wg[best] > (int64_t)groups[best] * wg[c]) best = c;
+        ++wg[best];
+    }
+    int most = 0, w0 = 0;
+    for (int c = 0; c < xa->ncls; ++c) {
+        xa->gpw[c] = (groups[c] + wg[c] - 1) / wg[c];
+        wg[c] = (groups[c] + xa->gpw[c] - 1) / xa->gpw[c];      // no workgroup without a group
+        xa->wg0[c] = w0;
+        w0 += wg[c] * S;
+        if (xa->gpw[c] > most) most = xa->gpw[c];
+    }
+    xa->wg0[xa->ncls] = w0;
+    const int per_wave = (most + 15) / 16;
+    const int nw = (most + per_wave - 1) / per_wave;
+    if (nw < 6) return false;                    // too few wavefronts per compute unit to keep the memory busy
+    *nw_out = nw;
+    return true;
+}
+
 // kernels without per-segment activation support get one call per segment
 static hipError_t launch_linear_each(int dtype, const LinArgs &a, hipStream_t stream)
 {
@@ -668,6 +872,22 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
             else if (a.K % 512 == 0 && (int64_t)t * (a.K / 512) >= 256) ch = 2;
         }
         if (ch) ka.splits = a.K / (256 * ch);
+        if (ch == 4) {
+            XresArgs xa;
+            int nw = 0;
+            if (plan_xres(ka, &xa, &nw)) {
+                const size_t xl = (size_t)64 * (1024 + 8) * sizeof(bf16_t);
+                static bool raised_x[16] = {};
+                hipError_t ex = raise_lds_limit_once(raised_x, (const void *)k_linear_splitk_xres_bf16, xl);
+                if (ex != hipSuccess) return ex;
+                prof_begin(K_LIN_SPLITK_XRES, stream);
+                MOA_KLAUNCH(k_linear_splitk_xres_bf16, dim3((unsigned)(ka.lead_blocks + xa.wg0[xa.ncls])), dim3(64 * nw), xl, stream, xa);
+                prof_end(stream);
+                ex = hipGetLastError();
+                if (ex != hipSuccess) return ex;
+                return finish_splitk(a, ka, ntot, stream, fused);
+            }
+        }
         const dim3 grid((unsigned)(ka.lead_blocks + t * ka.splits));
         const size_t lds = (size_t)64 * (128 * (ch ? 2 : nq) + 8) * sizeof(bf16_t);
         hipError_t e = hipSuccess;
@@ -689,25 +909,7 @@ static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t st
         if (e != hipSuccess) return e;
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        *fused = a.epi != LinArgs::EPI_NONE;
-        SumArgs sum = {};
-        const int64_t items = a.R * ((a.epi == LinArgs::EPI_SWIGLU ? ntot / 2 : ntot) / 8);
-        sum.blocks = (int)((items + 255) / 256);
-        sum.R = a.R;
-        sum.nseg = a.nseg;
-        for (int s = 0; s < a.nseg; ++s) sum.st[s] = a.seg[s].st;
-        for (int s = 0; s <= a.nseg; ++s) sum.tile_begin[s] = ka.tile_begin[s];
-        sum.splits = ka.splits;
-        sum.ntot = ntot;
-        sum.part = ka.part;
-        sum.epi = a.epi;
-        sum.epi_res = a.epi_res;
-        sum.epi_out = a.epi_out;
-        if (a.sum_out) {                         // the caller has it carried by a later launch, or launches it
-            *a.sum_out = sum;
-            return hipSuccess;
-        }
-        return launch_splitk_sum(sum, stream);
+        return finish_splitk(a, ka, ntot, stream, fused);
     }
     if (path == P_EACH) return launch_linear_each(dtype, a, stream);
     if (path == P_SKINNY) {

@@ -35,7 +35,7 @@ hipEvent_t take_event()
 const char *const kKernelNames[K_COUNT] = {
     "k_tree_build", "k_tree_accept", "k_append_lengths", "k_linear_generic", "k_linear_skinny_bf16", "k_linear_splitk_bf16",
     "k_linear_splitk_reduce", "k_linear_tiled_bf16", "k_scatter_copy", "k_attn_generic", "k_attn_mfma", "k_attn_merge", "k_lsa_attn", "k_lsa_attn_mfma", "k_step_small", "k_attn_fused", "k_probe_read", "k_probe_mfma",
-    "k_rmsnorm", "k_rope", "k_swiglu", "k_add_out", "k_tree_expand", "k_tree_finalize", "k_topk_slices", "k_lm_head_argmax", "k_lm_head_reduce", "k_topk_merge", "k_msg_tree", "k_msg_accept", "k_linear_splitk_chunked_bf16", "k_lsa_fused", "k_lsa_fused_pk", "k_lsa_pack_weights", "k_lsa_fused_pk_lean"};
+    "k_rmsnorm", "k_rope", "k_swiglu", "k_add_out", "k_tree_expand", "k_tree_finalize", "k_topk_slices", "k_lm_head_argmax", "k_lm_head_reduce", "k_topk_merge", "k_msg_tree", "k_msg_accept", "k_linear_splitk_chunked_bf16", "k_lsa_fused", "k_lsa_fused_pk", "k_lsa_pack_weights", "k_lsa_fused_pk_lean", "k_linear_splitk_xres_bf16"};
 const char *const kSiteNames[S_COUNT] = {
     "none", "tree_build", "lsa.qkv_proj", "lsa.layer_attn", "lsa.o_proj", "ca_append.kv_proj", "ca_append.lengths",
     "ca.q_proj", "ca.core", "ca.o_proj", "verify.qkv_proj", "verify.core", "verify.o_proj", "tree_accept",

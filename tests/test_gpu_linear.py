@@ -1,5 +1,6 @@
-"""GPU parity of the bare projection (moa_linear) across the kernels it dispatches to -- weight streaming in chunks
-(at most 64 rows, K in 1024s or 512s), weight streaming in one shot (up to 192 rows), the tiled GEMM, the narrow and
+"""GPU parity of the bare projection (moa_linear) across the kernels it dispatches to -- weight streaming with the
+activation slice resident in LDS or re-read in chunks (at most 64 rows, K in 1024s or 512s), weight streaming in one
+shot (up to 192 rows), the tiled GEMM, the narrow and
 the generic forms -- against the oracle's projection, with ragged row counts and the smallest and largest row count of each
 form."""
 import numpy as np
@@ -31,7 +32,11 @@ CASES = [
     ("bf16", 33, 4096, 8192),     # the same, ragged rows
     ("bf16", 64, 1024, 16384),    # a single slice: nothing to add up but the chunks
     ("bf16", 60, 2048, 4096),     # 512-wide slices in two chunks (64 tiles x 4)
-    ("bf16", 60, 14336, 4096),    # 14 slices
+    ("bf16", 60, 14336, 4096),    # 14 slices (activation slice resident: 18 workgroups per slice, 15 wavefronts each)
+    ("bf16", 60, 4096, 10240),    # activation slice resident, one group of 16 features per wavefront, ten wavefronts
+    ("bf16", 64, 4096, 28672),    # the same with two groups per wavefront
+    ("bf16", 5, 2048, 14336),     # two slices, seven wavefronts
+    ("bf16", 47, 4096, 6208),     # groups do not divide: the last workgroup of a slice has idle wavefronts
     ("bf16", 65, 4096, 4096),     # one row more: two row tiles, one shot per 512-wide slice
     ("bf16", 128, 2048, 2048),
     ("bf16", 160, 2048, 6144),    # three row tiles, wide slices
