@@ -1615,6 +1615,7 @@ static int32_t two_stream_main(const moa_step_args_t *a, const StepBufs &bf, cha
 
 static int32_t draft_step_concurrent(const moa_step_args_t *a, SideStream *ss)
 {
+    const LinearLeaveRoom share_the_compute_units;
     hipStream_t main = (hipStream_t)a->stream, side = ss->stream;
     const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
     char *scr_main = nullptr;
@@ -1716,6 +1717,7 @@ static int32_t two_stream_sa_side_verify(const moa_step_args_t *a, const StepBuf
 // launch started only after the chain, 59 us late).
 static int32_t draft_step_concurrent_sa(const moa_step_args_t *args, const moa_step_args_t *a, SideStream *ss)
 {
+    const LinearLeaveRoom share_the_compute_units;
     hipStream_t main = (hipStream_t)a->stream, side = ss->stream;
     const GroupLayout L = group_layout(a->shape, a->B, a->M, a->P_cap, a->ca_P_cap, a->T_lsa);
     char *scr_main = nullptr;

@@ -238,6 +238,13 @@ struct LinArgs {
 
 // Y_s = X_s W_s^T for up to four weight matrices (one launch on the fast paths; segments usually share X).
 hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream);
+// While an object of this type lives, this thread's projections keep to kernels that leave LDS and registers for a
+// second kernel on the same compute units (the two-stream schedule runs its branches side by side).
+struct LinearLeaveRoom {
+    LinearLeaveRoom();
+    ~LinearLeaveRoom();
+    bool before;
+};
 // scratch the fast weight-streaming path wants for R rows and ntot output features in total (0 = not used)
 size_t linear_workspace_bytes(int dtype, int64_t R, int K, int ntot);
 

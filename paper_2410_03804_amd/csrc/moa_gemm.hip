@@ -729,6 +729,10 @@ static LinPath linear_path(int dtype, const LinArgs &a, int *nq_out)
 
 static hipError_t launch_linear_impl(int dtype, const LinArgs &a, hipStream_t stream, bool *rode, bool *fused);
 
+static thread_local bool t_leave_room = false;
+LinearLeaveRoom::LinearLeaveRoom() : before(t_leave_room) { t_leave_room = true; }
+LinearLeaveRoom::~LinearLeaveRoom() { t_leave_room = before; }
+
 // the pass that adds up the K slices a weight-streaming kernel has left in ka.part: launched, or handed to the caller
 static hipError_t finish_splitk(const LinArgs &a, const SplitKArgs &ka, int ntot, hipStream_t stream, bool *fused)
 {
@@ -761,6 +765,7 @@ static bool plan_xres(const SplitKArgs &ka, XresArgs *xa, int *nw_out)
 {
     const LinArgs &a = ka.a;
     const int S = ka.splits;
+    if (t_leave_room) return false;              // 132 KB of LDS: nothing else fits beside it
     if (a.R > 64 || a.K % 1024 || S < 1 || S * 1024 != a.K) return false;
     static int cus = 0;
     if (!cus) {
