@@ -585,7 +585,7 @@ static int32_t attn_check(const char *who, const moa_shape_t *shape, const void 
 static int32_t attn_stage_project(const char *who, const moa_shape_t *shape, const void *x, int32_t B, int32_t M,
                                   const void *wq, const void *wk, const void *wv, bool tree, void *k_tree,
                                   void *v_tree, const AttnBufs &bf, hipStream_t st, const void **q_out,
-                                  int32_t M_total = 0, int32_t node0 = 0)
+                                  int32_t M_total = 0, int32_t node0 = 0, const RopeArgs *rope = nullptr)
 {
     const int dh = shape->head_dim, H = shape->n_q_heads, Hkv = shape->n_kv_heads, d = shape->d_model;
     const int e = H * dh, ekv = Hkv * dh, dt = shape->dtype;
@@ -622,7 +622,17 @@ static int32_t attn_stage_project(const char *who, const moa_shape_t *shape, con
             }
         }
     }
+    // rotary positions (a reused decoder layer): on the way out of the projection where all three are projected here
+    if (rope && la.nseg == 3) {
+        la.epi = LinArgs::EPI_ROPE;
+        la.rope = *rope;
+    }
     if (la.nseg) MOA_TRY_HIP(launch_linear(dt, la, st), who);
+    if (rope && la.nseg != 3 && !g_dry) {
+        prof_set_site(S_TLI_ROPE);
+        MOA_TRY_HIP(launch_rope(dt, rope->q, rope->k_draft, rope->prefix_len, rope->depth, rope->B, rope->Mn, rope->M, rope->node0,
+                                rope->H, rope->Hkv, rope->dh, rope->theta, rope->P_cap, st), who);
+    }
     return MOA_OK;
 }
 
@@ -998,15 +1008,21 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     t_sites = sites;
     const AttnBufs bf = attn_carve(shape, B, Mn, t.attn, t.attn_bytes);
     const void *q = nullptr;
-    rc = attn_stage_project(who, shape, t.n, B, Mn, wq, wk, wv, true, k_draft, v_draft, bf, st, &q, M, node_begin);
-    if (rc == MOA_OK) {
-        prof_set_site(S_TLI_ROPE);
-        if (!g_dry) {
-            const hipError_t e = launch_rope(dt, bf.qbuf, k_draft, prefix_len, depth, B, Mn, M, node_begin, shape->n_q_heads,
-                                             shape->n_kv_heads, shape->head_dim, (double)cfg->rope_theta, P_cap, st);
-            if (e != hipSuccess) rc = hip_fail(e, who);
-        }
-    }
+    RopeArgs rope = {};
+    rope.q = bf.qbuf;
+    rope.k_draft = k_draft;
+    rope.prefix_len = prefix_len;
+    rope.depth = depth;
+    rope.B = B;
+    rope.Mn = Mn;
+    rope.M = M;
+    rope.node0 = node_begin;
+    rope.H = shape->n_q_heads;
+    rope.Hkv = shape->n_kv_heads;
+    rope.dh = shape->head_dim;
+    rope.P_cap = P_cap;
+    rope.theta = (double)cfg->rope_theta;
+    rc = attn_stage_project(who, shape, t.n, B, Mn, wq, wk, wv, true, k_draft, v_draft, bf, st, &q, M, node_begin, &rope);
     if (rc == MOA_OK)
         rc = attn_stage_core(who, shape, q, B, Mn, wo, kcache, vcache, prefix_len, P_cap, mask, t.tmp, k_draft, v_draft,
                              dev_status, bf, st, M, node_begin);

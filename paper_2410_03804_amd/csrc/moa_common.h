@@ -183,6 +183,17 @@ struct LsaAttnArgs {
 // The pass that adds up the K slices of a weight-streaming projection, as data: what launch_linear leaves behind
 // when asked not to launch it (LinArgs::sum_out), what another launch can carry (LinArgs::carry_sum) and what
 // launch_splitk_sum runs.
+// Rotary position embedding of a decoder layer's queries and draft keys (position = clamped prefix length + depth of
+// the node; the pair (c, c + dh/2) of every head is rotated by position * theta^(-2c/dh), the angle in double
+// precision): everything launch_rope needs, so that a projection can apply it on the way out.
+struct RopeArgs {
+    void *q;                     // [B*Mn, H*dh]
+    void *k_draft;               // [B, Hkv, M, dh] slabs; rows node0 .. node0 + Mn - 1 are this call's
+    const int32_t *prefix_len, *depth;
+    int B, Mn, M, node0, H, Hkv, dh, P_cap;
+    double theta;
+};
+
 struct SumArgs {
     int blocks;          // workgroups of 256 threads; 0 = nothing to do
     int64_t R;
@@ -194,6 +205,8 @@ struct SumArgs {
     int epi;             // LinArgs::EPI_*
     const float *epi_res;
     void *epi_out;
+    RopeArgs rope;       // EPI_ROPE
+    double rope_log_theta;
 };
 hipError_t launch_splitk_sum(const SumArgs &s, hipStream_t stream);
 
@@ -221,10 +234,13 @@ struct LinArgs {
     // stored as its segments say and a small kernel follows.
     //  EPI_ADD_F32: one segment; epi_out[r, n] = epi_res[r, n] + y[r, n]   (row length N)
     //  EPI_SWIGLU : two segments of equal N stored side by side in one row of 2N; epi_out[r, j] = silu(y0[r, j]) * y1[r, j]
-    enum { EPI_NONE = 0, EPI_ADD_F32 = 1, EPI_SWIGLU = 2 };
+    //  EPI_ROPE   : three segments -- queries (row store), draft keys (head slabs), draft values; the first two get
+    //               their rotary position embedding (`rope`), exactly as launch_rope would apply it to the stored result
+    enum { EPI_NONE = 0, EPI_ADD_F32 = 1, EPI_SWIGLU = 2, EPI_ROPE = 3 };
     int epi;
     const float *epi_res;
     void *epi_out;
+    RopeArgs rope;
     // The summing pass of an earlier weight-streaming projection, carried in spare workgroups at the front of this
     // launch's grid: it is done when this launch has finished, and must neither feed this projection nor depend on
     // it.  Only the tiled kernel carries; on the other paths the pass is launched apart, first.  A host pointer, read

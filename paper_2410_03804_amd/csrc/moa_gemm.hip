@@ -750,6 +750,10 @@ static hipError_t finish_splitk(const LinArgs &a, const SplitKArgs &ka, int ntot
     sum.epi = a.epi;
     sum.epi_res = a.epi_res;
     sum.epi_out = a.epi_out;
+    if (a.epi == LinArgs::EPI_ROPE) {
+        sum.rope = a.rope;
+        sum.rope_log_theta = log(a.rope.theta);
+    }
     if (a.sum_out) {                         // the caller has it carried by a later launch, or launches it
         *a.sum_out = sum;
         return hipSuccess;
@@ -946,6 +950,8 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
     if (a.sum_out) *a.sum_out = SumArgs{};
     if (a.epi == LinArgs::EPI_ADD_F32 && a.nseg != 1) return hipErrorInvalidValue;
     if (a.epi == LinArgs::EPI_SWIGLU && (a.nseg != 2 || a.seg[0].N != a.seg[1].N)) return hipErrorInvalidValue;
+    if (a.epi == LinArgs::EPI_ROPE && (a.nseg != 3 || a.rope.dh % 16 || a.seg[0].N != a.rope.H * a.rope.dh || a.seg[1].N != a.rope.Hkv * a.rope.dh))
+        return hipErrorInvalidValue;
     // A carried pass rides in the tiled kernel only: that one keeps several workgroups per CU busy with matrix work,
     // so a few hundred short workgroups in front cost it nothing.  In the weight-streaming kernel (two workgroups per
     // CU, bound by the same memory path the pass uses) riding measured slower than a launch of its own.
@@ -960,7 +966,11 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
     hipError_t e = launch_linear_impl(dtype, b, stream, &rode, &fused);
     if (e != hipSuccess) return e;
     if (a.epi != LinArgs::EPI_NONE && !fused) {     // the projection was stored as its segments say: finish row-wise
+        const RopeArgs &ro = a.rope;
         if (a.epi == LinArgs::EPI_SWIGLU) e = launch_swiglu(dtype, a.seg[0].st.dst, a.R, a.seg[0].N, a.epi_out, stream);
+        else if (a.epi == LinArgs::EPI_ROPE)
+            e = launch_rope(dtype, ro.q, ro.k_draft, ro.prefix_len, ro.depth, ro.B, ro.Mn, ro.M, ro.node0, ro.H, ro.Hkv, ro.dh, ro.theta,
+                            ro.P_cap, stream);
         else e = launch_add_out(dtype, a.epi_res, a.seg[0].st.dst, a.R * a.seg[0].N, a.epi_out, stream);
         if (e != hipSuccess) return e;
     }

@@ -77,6 +77,33 @@ __device__ __forceinline__ void splitk_reduce_block(const SumArgs &sa, int block
     int s = 0;
     while (s + 1 < sa.nseg && tile >= sa.tile_begin[s + 1]) ++s;
     const int n = nt - sa.tile_begin[s] * 64;
+    if (sa.epi == LinArgs::EPI_ROPE && s < 2) {       // queries and keys: this thread's 8 features and their partners
+        const RopeArgs &ro = sa.rope;
+        const int half = ro.dh >> 1, c = n % ro.dh;
+        if (c >= half) return;                        // written by the thread that owns the lower half of the pair
+        f32x4 plo, phi;
+        splitk_sum8(sa, p + half, plo, phi);
+        const int b = (int)(r / ro.Mn), i = ro.node0 + (int)(r - (int64_t)b * ro.Mn);
+        int plen = ro.prefix_len[b];
+        plen = plen < 0 ? 0 : (plen > ro.P_cap ? ro.P_cap : plen);
+        const double pos = (double)plen + (double)ro.depth[(int64_t)b * ro.M + i];
+        f32x4 olo, ohi, qlo, qhi;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            // through the storage type first, as when the projection is stored and rotated in place afterwards
+            const float a = bf2f(f2bf(e < 4 ? lo[e] : hi[e - 4])), bb = bf2f(f2bf(e < 4 ? plo[e] : phi[e - 4]));
+            const double ang = pos * exp(-2.0 * (double)(c + e) / (double)ro.dh * sa.rope_log_theta);
+            double sn, cs;
+            sincos(ang, &sn, &cs);
+            const float x0 = (float)((double)a * cs - (double)bb * sn), x1 = (float)((double)bb * cs + (double)a * sn);
+            if (e < 4) { olo[e] = x0; qlo[e] = x1; } else { ohi[e - 4] = x0; qhi[e - 4] = x1; }
+        }
+        const int64_t off = store_offset(sa.st[s], r, n);
+        if (off < 0) return;
+        *(u32x4 *)((bf16_t *)sa.st[s].dst + off) = pack8(olo, ohi);
+        *(u32x4 *)((bf16_t *)sa.st[s].dst + off + half) = pack8(qlo, qhi);
+        return;
+    }
     const int64_t off = store_offset(sa.st[s], r, n);
     if (off < 0) return;
     *(u32x4 *)((bf16_t *)sa.st[s].dst + off) = pack8(lo, hi);
