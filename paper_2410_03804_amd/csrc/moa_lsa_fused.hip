@@ -55,6 +55,7 @@ struct LsaFusedArgs {
     int units;                     // Hkv * parts
     int units_per_xcd;
     int lead_blocks, small_lead, red_blocks;   // workgroups in front of the kernel's own: integer work of a step, a carried summing pass
+    int pf_lead;                               // the last of them (a multiple of the XCD count) only read ahead: see lsa_warm_block
     int rider_units;
     StepSmallArgs rider;
     SumArgs red;
@@ -368,6 +369,42 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
+// Helper workgroup `h` of `a.pf_lead` (packed form).  A cold weight tile is first touched by all of an XCD's
+// workgroups at once (they walk the k tiles in step), so all of them wait for HBM together, tile after tile; from the
+// L2 they do not.  At decode sizes the kernel's own workgroups leave sixteen compute units idle: two helpers per XCD
+// read that XCD's units' packed weights once, tile by tile and in turn, ahead of the workgroups that multiply them,
+// and throw them away.  (One compute unit pulls about 50 GB/s of misses however many requests it keeps in flight, so
+// sixteen helpers move 0.8 TB/s: the 16 MiB of weights in the kernel's first half.  Reading further operands of the
+// step's later launches ahead in the same way -- caches, output-projection weights, here or from the compute units
+// the attention cores leave idle -- was measured too: what the later launches gained, the carrying launch lost.)
+template <int DH, int NB, int TT>
+__device__ __forceinline__ void lsa_warm_block(const LsaFusedArgs &a, int h, bf16_t *sm)
+{
+    constexpr int NWP = 4 * (LsaFusedGeom<DH, NB, TT>::FW / 32);
+    static_assert(NWP * 64 == 512, "one piece per thread and (wavefront, k tile) block");
+    const int tid = threadIdx.x, nk = a.d_in / 64;
+    const int xcd = h & 7, turn = h >> 3, turns = a.pf_lead >> 3;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (int uu = 0; uu < a.units_per_xcd; ++uu) {
+        const int unit = xcd * a.units_per_xcd + uu;
+        if (unit >= a.units) break;
+        // [unit][wavefront][k tile] blocks of NWP * 64 pieces: one piece per thread and block
+        const u32x4 *base = (const u32x4 *)a.wpk + (int64_t)unit * 8 * nk * (NWP * 64) + tid;
+        for (int kt = 2 * turn; kt < nk; kt += 2 * turns) {          // two tiles per round: sixteen requests in flight
+            const int kt1 = kt + 1 < nk ? kt + 1 : kt;
+            u32x4 v[16];
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+                v[w] = base[(int64_t)(w * nk + kt) * (NWP * 64)];
+                v[8 + w] = base[(int64_t)(w * nk + kt1) * (NWP * 64)];
+            }
+#pragma unroll
+            for (int w = 0; w < 16; ++w) acc ^= v[w];
+        }
+    }
+    ((u32x4 *)sm)[tid] = acc;                    // into LDS nobody reads: what keeps the loads from being dropped
+}
+
 // The same kernel for weights that the caller has packed once into MFMA-operand order (k_lsa_pack_weights).  A
 // wavefront's slice of the weight tile is used by that wavefront alone, so with the operands already in lane order it
 // has no business in LDS: every 16-byte operand piece is loaded straight into the register that the MFMA reads, 1 KB
@@ -388,6 +425,10 @@ __device__ __forceinline__ void lsa_fused_pk_body(const LsaFusedArgs &a)
     extern __shared__ __attribute__((aligned(16))) bf16_t sm[];
 
     if ((int)blockIdx.x < a.lead_blocks) {       // the first workgroups of the grid carry work of other calls
+        if ((int)blockIdx.x >= a.lead_blocks - a.pf_lead) {
+            lsa_warm_block<DH, NB, TT>(a, (int)blockIdx.x - (a.lead_blocks - a.pf_lead), sm);
+            return;
+        }
         if ((int)blockIdx.x < a.small_lead) {
             if ((int)blockIdx.x < a.rider_units && threadIdx.x < 64)
                 step_small_unit(a.rider, (int)blockIdx.x, (int32_t *)sm, (int32_t *)sm + MOA_MAX_TREE);
@@ -614,6 +655,22 @@ static hipError_t launch_lsa_fused_as(LsaFusedArgs &fa, hipStream_t stream, bool
 {
     using Gm = LsaFusedGeom<128, NB, TT>;
     const int64_t tiles = (fa.T + TT - 1) / TT;
+    // Two helper workgroups per XCD (lsa_warm_block), where they cost nothing and can do their job: the kernel's own
+    // workgroups leave that many compute units idle (decode sizes), and an XCD's share of the weights fits its L2
+    // beside the activations streaming through.  Otherwise they take compute units and L2 from the workgroups they
+    // are meant to help (measured: first cycle 536 -> 559 us, d_in 4096 191 -> 197 us with helpers everywhere).
+    if (fa.pf_lead) {
+        static int cus = 0;
+        if (!cus) {
+            int dev = 0, n = 0;
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+            cus = n;
+        }
+        const int64_t own = 8 * (int64_t)fa.units_per_xcd * tiles;
+        const size_t w_per_xcd = (size_t)fa.units_per_xcd * (size_t)(fa.d_in / 64) * 65536;
+        if (lean || own + fa.pf_lead > cus || w_per_xcd > ((size_t)3 << 20)) fa.pf_lead = 0;
+        fa.lead_blocks += fa.pf_lead;
+    }
     const int64_t grid = fa.lead_blocks + 8 * (int64_t)fa.units_per_xcd * tiles;
     if (grid > 0x7fffffff) return hipErrorInvalidValue;
     if constexpr (Gm::RB <= 64) {
@@ -691,6 +748,7 @@ hipError_t launch_lsa_fused(const LsaFusedCall &c, hipStream_t stream)
         fa.red_blocks = c.carry_sum->blocks;
     }
     fa.lead_blocks = fa.small_lead + ((((fa.red_blocks + 1) / 2) + 7) & ~7);   // a lead workgroup of 512 threads does two blocks of the pass
+    fa.pf_lead = (c.w_packed && !c.leave_room) ? 16 : 0;     // wanted; launch_lsa_fused_as decides when it knows the grid
     // Rows per workgroup.  Measured at the Llama-3-8B shape (d_in 2048), a workgroup takes about 31 + 9 (rows / 32)
     // microseconds from plain weights and 10 + 11.7 (rows / 32) from packed ones, whatever else runs (it is bound by
     // its own chain of tile fetches from the L2 and its matrix work), and the chip runs 256 of them at a time: few
