@@ -20,17 +20,24 @@ struct LmHeadArgs {
 
 __device__ __forceinline__ bool better(float a, int ia, float b, int ib) { return a > b || (a == b && ia < ib); }
 
-template <int NQ>
+// TG groups of 16 tokens per wavefront: a workgroup's tile is 64 TG tokens, and the activation chunk it stages per K
+// chunk serves that many -- with TG = 1 the workgroups pull as many activation bytes out of the L2 as weight bytes out
+// of HBM (one 480 KB pass over X per 64 tokens).
+template <int NQ, int TG>
 __global__ __launch_bounds__(256, 2) void k_lm_head_argmax(LmHeadArgs a)
 {
     constexpr int KS = 128 * NQ, LDK = KS + 8, CPR = KS / 8, XL = (64 * CPR) / 256;
     extern __shared__ __attribute__((aligned(16))) bf16_t Xs[];   // [64][LDK]; reused for the per-wave bests at the end
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, kg = lane >> 4;
     const int tile = blockIdx.x;
-    const int n0 = tile * 64 + wave * 16;
-    int wrow = n0 + li;
-    if (wrow > a.V - 1) wrow = a.V - 1;                     // tokens past the end repeat the last one; masked below
-    const bf16_t *wp = a.W + (int64_t)wrow * a.K + 8 * kg;   // k slot (q, j, kg) is k = 128 q + 32 j + 8 kg
+    const int n0 = tile * 64 * TG + wave * 16 * TG;
+    const bf16_t *wp[TG];
+#pragma unroll
+    for (int t = 0; t < TG; ++t) {
+        int wrow = n0 + 16 * t + li;
+        if (wrow > a.V - 1) wrow = a.V - 1;                 // tokens past the end repeat the last one; masked below
+        wp[t] = a.W + (int64_t)wrow * a.K + 8 * kg;         // k slot (q, j, kg) is k = 128 q + 32 j + 8 kg
+    }
     const int nchunk = a.K / KS;
 
     // Piece c = tid + 256 i of the slice is row c / CPR, 16-byte column c % CPR: the column and the row's remainder
@@ -50,18 +57,22 @@ __global__ __launch_bounds__(256, 2) void k_lm_head_argmax(LmHeadArgs a)
             if (tid / CPR + RSTEP * i < a.R)
                 xr[i] = *(const u32x4 *)(xb + (int64_t)i * RSTEP * a.K * (int64_t)sizeof(bf16_t) + xoff);
     };
-    bf16x8 wf[2][NQ][4];
+    bf16x8 wf[2][TG][NQ][4];
     auto load_w = [&](int set, int kc) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q)
+        for (int t = 0; t < TG; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wf[set][q][j] = *(const bf16x8 *)(wp + (int64_t)kc * KS + 128 * q + 32 * j);
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) wf[set][t][q][j] = *(const bf16x8 *)(wp[t] + (int64_t)kc * KS + 128 * q + 32 * j);
     };
     load_x(0);
     load_w(0, 0);
-    f32x4 acc[4];
+    f32x4 acc[TG][4];
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < TG; ++t)
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) acc[t][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     auto chunk = [&](int set, int kc) {
         if (kc + 1 < nchunk) load_w(set ^ 1, kc + 1);       // the next chunk's weights are on their way
@@ -83,8 +94,10 @@ __global__ __launch_bounds__(256, 2) void k_lm_head_argmax(LmHeadArgs a)
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb) xf[rb] = *(const bf16x8 *)&Xs[(16 * rb + li) * LDK + 128 * q + 32 * j + 8 * kg];
 #pragma unroll
-                for (int rb = 0; rb < 4; ++rb)
-                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[set][q][j], xf[rb], acc[rb], 0, 0, 0);
+                for (int t = 0; t < TG; ++t)
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb)
+                        acc[t][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[set][t][q][j], xf[rb], acc[t][rb], 0, 0, 0);
             }
     };
     for (int kc = 0; kc < nchunk; kc += 2) {                // two chunks per trip: the register sets alternate statically
@@ -92,7 +105,7 @@ __global__ __launch_bounds__(256, 2) void k_lm_head_argmax(LmHeadArgs a)
         if (kc + 1 < nchunk) chunk(1, kc + 1);
     }
 
-    // lane holds tokens n0 + 4 kg .. + 3 for row 16 rb + li: best of the workgroup's 64 tokens per row
+    // lane holds tokens n0 + 16 t + 4 kg .. + 3 for row 16 rb + li: best of the workgroup's tokens per row
     __syncthreads();
     float *wv = (float *)Xs;                                 // [4 waves][64 rows]
     int32_t *wi = (int32_t *)(wv + 256);
@@ -101,11 +114,13 @@ __global__ __launch_bounds__(256, 2) void k_lm_head_argmax(LmHeadArgs a)
         float bv = -INFINITY;
         int bi = 0x7fffffff;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int id = n0 + 4 * kg + e;
-            const float v = acc[rb][e];
-            if (id < a.V && better(v, id, bv, bi)) { bv = v; bi = id; }
-        }
+        for (int t = 0; t < TG; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int id = n0 + 16 * t + 4 * kg + e;
+                const float v = acc[t][rb][e];
+                if (id < a.V && better(v, id, bv, bi)) { bv = v; bi = id; }
+            }
 #pragma unroll
         for (int o = 16; o <= 32; o <<= 1) {
             const float ov = __shfl_xor(bv, o);
@@ -178,7 +193,8 @@ int32_t moa_lm_head_argmax(int32_t dtype, const void *x, int32_t R, int32_t d, c
     if (dtype != MOA_BF16) return api_fail(MOA_ERR_DTYPE, "lm_head_argmax: bf16 only");
     if (R < 1 || V < 1 || d < 128 || d % 128) return api_fail(MOA_ERR_SHAPE, "lm_head_argmax: R >= 1, V >= 1, d a multiple of 128");
     if ((((uintptr_t)x) | ((uintptr_t)w)) & 15) return api_fail(MOA_ERR_SHAPE, "lm_head_argmax: x and w must be 16-byte aligned");
-    const int tiles = (V + 63) / 64;
+    constexpr int TG = 2;                       // 128 tokens per workgroup
+    const int tiles = (V + 64 * TG - 1) / (64 * TG);
     const size_t need = (size_t)tiles * 64 * (sizeof(float) + sizeof(int32_t));
     if (!ws || (((uintptr_t)ws) & 255) || ws_bytes < need) return api_fail(MOA_ERR_WORKSPACE, "lm_head_argmax: workspace NULL, misaligned or smaller than moa_lm_head_workspace_bytes");
     hipStream_t st = (hipStream_t)stream;
@@ -199,8 +215,8 @@ int32_t moa_lm_head_argmax(int32_t dtype, const void *x, int32_t R, int32_t d, c
         a.pid = (int32_t *)((float *)ws + (size_t)tiles * 64);
         prof_set_site(S_LM_HEAD);
         prof_begin(K_LM_HEAD, st);
-        if (nq == 2) MOA_KLAUNCH(k_lm_head_argmax<2>, dim3(tiles), dim3(256), lds, st, a);
-        else MOA_KLAUNCH(k_lm_head_argmax<1>, dim3(tiles), dim3(256), lds, st, a);
+        if (nq == 2) MOA_KLAUNCH((k_lm_head_argmax<2, TG>), dim3(tiles), dim3(256), lds, st, a);
+        else MOA_KLAUNCH((k_lm_head_argmax<1, TG>), dim3(tiles), dim3(256), lds, st, a);
         prof_end(st);
         if (hipGetLastError() != hipSuccess) return api_fail(MOA_ERR_HIP, "lm_head_argmax: launch failed");
         prof_begin(K_LM_HEAD_REDUCE, st);
