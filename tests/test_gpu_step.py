@@ -21,6 +21,10 @@ STEP_CASES = {
     "small_bf16": (mi.Config(name="S", index=8, dtype="bf16", B=3, P_min=80, P_max=300, M=37, D=5, max_branch=4, L=6,
                              d=512, H=8, Hkv=2, dh=128, d_lsa_in=512, rms_norm=True), 2),
     "C1_bf16": (mi.CONFIGS["C1"], 1),
+    # the 8B widths on few rows: the grouped projections run with the activation slice resident (two classes of
+    # segments, 18 of a workgroup's 64 rows in use), two sequences
+    "wide_few_rows_bf16": (mi.Config(name="W18", index=16, dtype="bf16", B=2, P_min=100, P_max=260, M=9, D=3, max_branch=3,
+                                     L=8, d=4096, H=32, Hkv=8, dh=128, d_lsa_in=2048, rms_norm=True), 2),
     # degenerate trees: the root alone (M = 1: nothing drafted, the bonus token is the only result) and a prefix
     # shorter than one key tile
     "single_node_bf16": (mi.Config(name="M1", index=9, dtype="bf16", B=2, P_min=5, P_max=40, M=1, D=0, max_branch=4, L=3,
