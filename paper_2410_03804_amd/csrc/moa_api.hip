@@ -685,7 +685,7 @@ static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const 
                                const void *wo, const void *kcache, const void *vcache, const int32_t *len,
                                int32_t P_cap, const uint64_t *mask, void *out, void *k_tree, void *v_tree,
                                int32_t *dev_status, const AttnBufs &bf, hipStream_t st, int32_t M_total = 0,
-                               int32_t node0 = 0)
+                               int32_t node0 = 0, const NormArgs *norm = nullptr)
 {
     const int e = shape->n_q_heads * shape->head_dim, dt = shape->dtype;
     const AttnArgs aa = attn_core_args(shape, q, B, M, kcache, vcache, len, P_cap, mask, wo ? (void *)bf.abuf : out,
@@ -703,6 +703,10 @@ static int32_t attn_stage_core(const char *who, const moa_shape_t *shape, const 
         lo.seg[0].ldx = 0;
         lo.ws = bf.scratch_c;
         lo.ws_bytes = bf.scratch_c_bytes;
+        if (norm) {                          // the block's residual and next norm on the way out (a reused decoder layer)
+            lo.epi = LinArgs::EPI_ADD_NORM;
+            lo.norm = *norm;
+        }
         prof_set_site(t_sites ? t_sites[2] : (mask ? S_VERIFY_OPROJ : S_CA_OPROJ));
         MOA_TRY_HIP(launch_linear(dt, lo, st), who);
     }
@@ -891,11 +895,13 @@ struct MlpBufs {
 // sites = launch sites of {norm, gate/up projection, down projection}
 static int32_t mlp_block_run(const char *who, int dt, const void *x, const void *res, int64_t R, int d, int d_ff,
                              const void *g, const void *w_gate, const void *w_up, const void *w_down, float eps, void *out,
-                             const MlpBufs &b, const int *sites, hipStream_t st)
+                             const MlpBufs &b, const int *sites, hipStream_t st, bool normed = false)
 {
     const size_t es = esize(dt);
-    prof_set_site(sites[0]);
-    MOA_TRY_HIP(launch_rmsnorm(dt, x, res, R, d, g, eps, b.h, b.n, st), who);
+    if (!normed) {                           // else b.h and b.n are there already (the projection in front made them)
+        prof_set_site(sites[0]);
+        MOA_TRY_HIP(launch_rmsnorm(dt, x, res, R, d, g, eps, b.h, b.n, st), who);
+    }
     LinArgs lg = {};
     lg.X = b.n;
     lg.R = R;
@@ -1023,9 +1029,16 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     rope.P_cap = P_cap;
     rope.theta = (double)cfg->rope_theta;
     rc = attn_stage_project(who, shape, t.n, B, Mn, wq, wk, wv, true, k_draft, v_draft, bf, st, &q, M, node_begin, &rope);
+    // W_o, then the residual and the MLP's norm: h1 = x + attention output, n = rmsnorm(h1) g_mlp
+    NormArgs nm = {};
+    nm.x = x;
+    nm.g = g_mlp;
+    nm.eps = cfg->rms_eps;
+    nm.h = t.h1;
+    nm.n = t.n;
     if (rc == MOA_OK)
         rc = attn_stage_core(who, shape, q, B, Mn, wo, kcache, vcache, prefix_len, P_cap, mask, t.tmp, k_draft, v_draft,
-                             dev_status, bf, st, M, node_begin);
+                             dev_status, bf, st, M, node_begin, &nm);
     t_sites = nullptr;
     if (rc) return rc;
 
@@ -1039,7 +1052,7 @@ int32_t moa_tli_decoder_layer(const moa_shape_t *shape, const moa_decoder_cfg_t 
     mb.gu = t.gu;
     mb.act = t.act;
     static const int mlp_sites[3] = {S_TLI_NORM, S_TLI_GATE_UP, S_TLI_DOWN};
-    return mlp_block_run(who, dt, x, t.tmp, R, d, d_ff, g_mlp, w_gate, w_up, w_down, cfg->rms_eps, out, mb, mlp_sites, st);
+    return mlp_block_run(who, dt, x, t.tmp, R, d, d_ff, g_mlp, w_gate, w_up, w_down, cfg->rms_eps, out, mb, mlp_sites, st, true);
 }
 
 // ---- the drafter's own layers: pre-norm in front of an attention sub-layer, MLP sub-block behind it

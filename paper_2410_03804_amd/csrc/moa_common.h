@@ -194,6 +194,16 @@ struct RopeArgs {
     double theta;
 };
 
+// Residual + RMS norm behind a projection (a pre-norm block's second half begins with it): h = x + y in single
+// precision, n = h / sqrt(mean(h^2) + eps) * g in the storage type -- what launch_rmsnorm makes of x and the stored y.
+struct NormArgs {
+    const void *x;       // [R, N] the block's input (storage type)
+    const void *g;       // [N]
+    float eps;
+    float *h;            // [R, N] out
+    void *n;             // [R, N] out
+};
+
 struct SumArgs {
     int blocks;          // workgroups of 256 threads; 0 = nothing to do
     int64_t R;
@@ -207,6 +217,7 @@ struct SumArgs {
     void *epi_out;
     RopeArgs rope;       // EPI_ROPE
     double rope_log_theta;
+    NormArgs norm;       // EPI_ADD_NORM: one workgroup per row (blocks = R)
 };
 hipError_t launch_splitk_sum(const SumArgs &s, hipStream_t stream);
 
@@ -236,11 +247,14 @@ struct LinArgs {
     //  EPI_SWIGLU : two segments of equal N stored side by side in one row of 2N; epi_out[r, j] = silu(y0[r, j]) * y1[r, j]
     //  EPI_ROPE   : three segments -- queries (row store), draft keys (head slabs), draft values; the first two get
     //               their rotary position embedding (`rope`), exactly as launch_rope would apply it to the stored result
-    enum { EPI_NONE = 0, EPI_ADD_F32 = 1, EPI_SWIGLU = 2, EPI_ROPE = 3 };
+    //  EPI_ADD_NORM: one segment of N <= 8192 features; `norm`: h = x + y, n = rmsnorm(h) g; y itself is stored (where the
+    //               segment says) only on the paths that finish with a kernel of their own
+    enum { EPI_NONE = 0, EPI_ADD_F32 = 1, EPI_SWIGLU = 2, EPI_ROPE = 3, EPI_ADD_NORM = 4 };
     int epi;
     const float *epi_res;
     void *epi_out;
     RopeArgs rope;
+    NormArgs norm;
     // The summing pass of an earlier weight-streaming projection, carried in spare workgroups at the front of this
     // launch's grid: it is done when this launch has finished, and must neither feed this projection nor depend on
     // it.  Only the tiled kernel carries; on the other paths the pass is launched apart, first.  A host pointer, read

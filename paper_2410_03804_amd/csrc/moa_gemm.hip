@@ -464,10 +464,71 @@ __global__ __launch_bounds__(1024) void k_linear_splitk_xres_bf16(XresArgs xa)
 
 __global__ __launch_bounds__(256) void k_linear_splitk_reduce(SumArgs sa) { splitk_reduce_block(sa, (int)blockIdx.x, (int)threadIdx.x); }
 
+// The pass with the residual and the RMS norm behind it (LinArgs::EPI_ADD_NORM): one workgroup per row, every lane
+// its 16-byte pieces of the row in registers for both halves (the sum of squares, then the scaled row).  The arithmetic
+// is launch_rmsnorm's on x and the projection rounded to the storage type: the same bits as the two launches.
+template <int NCH>
+__global__ __launch_bounds__(256) void k_linear_splitk_reduce_norm(SumArgs sa)
+{
+    __shared__ float part[4];
+    const int64_t r = blockIdx.x;
+    const int d = sa.ntot, nch = d >> 3;
+    const float *prow = sa.part + (((r >> 6) * sa.splits) * 64 + (r & 63)) * (int64_t)sa.ntot;
+    const bf16_t *x = (const bf16_t *)sa.norm.x + r * d, *g = (const bf16_t *)sa.norm.g;
+    float v[NCH][8];
+    u32x4 gv[NCH];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        const bool live = c < nch;
+        const int cc = live ? c : 0;
+        f32x4 lo, hi;
+        splitk_sum8(sa, prow + 8 * cc, lo, hi);
+        const u32x4 yv = pack8(lo, hi);                      // the projection as it would be stored
+        const u32x4 xv = *(const u32x4 *)(x + 8 * cc);
+        gv[i] = *(const u32x4 *)(g + 8 * cc);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float l = __uint_as_float(xv[e] << 16) + __uint_as_float(yv[e] << 16);
+            const float h = __uint_as_float(xv[e] & 0xffff0000u) + __uint_as_float(yv[e] & 0xffff0000u);
+            v[i][2 * e] = l;
+            v[i][2 * e + 1] = h;
+            if (live) ss += l * l + h * h;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+    const float inv = 1.0f / sqrtf(tot / (float)d + sa.norm.eps);
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        if (c >= nch) continue;
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float glo = __uint_as_float(gv[i][e] << 16), ghi = __uint_as_float(gv[i][e] & 0xffff0000u);
+            o[e] = pack_bf16x2(v[i][2 * e] * inv * glo, v[i][2 * e + 1] * inv * ghi);
+        }
+        *(u32x4 *)((bf16_t *)sa.norm.n + r * d + 8 * c) = o;
+        *(f32x4 *)(sa.norm.h + r * d + 8 * c) = f32x4{v[i][0], v[i][1], v[i][2], v[i][3]};
+        *(f32x4 *)(sa.norm.h + r * d + 8 * c + 4) = f32x4{v[i][4], v[i][5], v[i][6], v[i][7]};
+    }
+}
+
 hipError_t launch_splitk_sum(const SumArgs &sa, hipStream_t stream)
 {
     if (sa.blocks <= 0) return hipSuccess;
     prof_begin(K_LIN_REDUCE, stream);
+    if (sa.epi == LinArgs::EPI_ADD_NORM) {
+        if (sa.ntot <= 256 * 8 * 2) MOA_KLAUNCH(k_linear_splitk_reduce_norm<2>, dim3((unsigned)sa.R), dim3(256), 0, stream, sa);
+        else MOA_KLAUNCH(k_linear_splitk_reduce_norm<4>, dim3((unsigned)sa.R), dim3(256), 0, stream, sa);
+        prof_end(stream);
+        return hipGetLastError();
+    }
     MOA_KLAUNCH(k_linear_splitk_reduce, dim3((unsigned)sa.blocks), dim3(256), 0, stream, sa);
     prof_end(stream);
     return hipGetLastError();
@@ -736,7 +797,11 @@ LinearLeaveRoom::~LinearLeaveRoom() { t_leave_room = before; }
 // the pass that adds up the K slices a weight-streaming kernel has left in ka.part: launched, or handed to the caller
 static hipError_t finish_splitk(const LinArgs &a, const SplitKArgs &ka, int ntot, hipStream_t stream, bool *fused)
 {
-    *fused = a.epi != LinArgs::EPI_NONE;
+    // the residual + norm pass takes rows of at most 8192 values with 16-byte aligned operands, and is never carried
+    const bool norm_ok = a.epi != LinArgs::EPI_ADD_NORM ||
+                         (ntot <= 256 * 8 * 4 && !a.sum_out && a.norm.x && a.norm.g && a.norm.h && a.norm.n &&
+                          ((((uintptr_t)a.norm.x) | ((uintptr_t)a.norm.g) | ((uintptr_t)a.norm.h) | ((uintptr_t)a.norm.n)) & 15) == 0);
+    *fused = a.epi != LinArgs::EPI_NONE && norm_ok;
     SumArgs sum = {};
     const int64_t items = a.R * ((a.epi == LinArgs::EPI_SWIGLU ? ntot / 2 : ntot) / 8);
     sum.blocks = (int)((items + 255) / 256);
@@ -747,9 +812,10 @@ static hipError_t finish_splitk(const LinArgs &a, const SplitKArgs &ka, int ntot
     sum.splits = ka.splits;
     sum.ntot = ntot;
     sum.part = ka.part;
-    sum.epi = a.epi;
+    sum.epi = norm_ok ? a.epi : (int)LinArgs::EPI_NONE;
     sum.epi_res = a.epi_res;
     sum.epi_out = a.epi_out;
+    sum.norm = a.norm;
     if (a.epi == LinArgs::EPI_ROPE) {
         sum.rope = a.rope;
         sum.rope_log_theta = log(a.rope.theta);
@@ -950,6 +1016,7 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
     if (a.sum_out) *a.sum_out = SumArgs{};
     if (a.epi == LinArgs::EPI_ADD_F32 && a.nseg != 1) return hipErrorInvalidValue;
     if (a.epi == LinArgs::EPI_SWIGLU && (a.nseg != 2 || a.seg[0].N != a.seg[1].N)) return hipErrorInvalidValue;
+    if (a.epi == LinArgs::EPI_ADD_NORM && a.nseg != 1) return hipErrorInvalidValue;
     if (a.epi == LinArgs::EPI_ROPE && (a.nseg != 3 || a.rope.dh % 16 || a.seg[0].N != a.rope.H * a.rope.dh || a.seg[1].N != a.rope.Hkv * a.rope.dh))
         return hipErrorInvalidValue;
     // A carried pass rides in the tiled kernel only: that one keeps several workgroups per CU busy with matrix work,
@@ -971,6 +1038,8 @@ hipError_t launch_linear(int dtype, const LinArgs &a, hipStream_t stream)
         else if (a.epi == LinArgs::EPI_ROPE)
             e = launch_rope(dtype, ro.q, ro.k_draft, ro.prefix_len, ro.depth, ro.B, ro.Mn, ro.M, ro.node0, ro.H, ro.Hkv, ro.dh, ro.theta,
                             ro.P_cap, stream);
+        else if (a.epi == LinArgs::EPI_ADD_NORM)
+            e = launch_rmsnorm(dtype, a.norm.x, a.seg[0].st.dst, a.R, a.seg[0].N, a.norm.g, a.norm.eps, a.norm.h, a.norm.n, stream);
         else e = launch_add_out(dtype, a.epi_res, a.seg[0].st.dst, a.R * a.seg[0].N, a.epi_out, stream);
         if (e != hipSuccess) return e;
     }
